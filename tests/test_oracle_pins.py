@@ -1,0 +1,414 @@
+"""Pins of the CPU oracle to what the paper and the mathematics fix.
+
+None of these tests compares the oracle with itself: each checks it against a
+hand-derived fixture, an invariant of the definition (Section 3 Eq. 1,
+Section 4.1 Eq. 2-4), exact rational brute force, or a library routine for a
+special case.  The comments say which plausible mistake each one would catch.
+"""
+from fractions import Fraction
+from pathlib import Path
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_14363_amd import workloads as wl
+
+GOLDEN = Path(__file__).resolve().parent / "golden"
+
+
+def bits_of(values) -> np.ndarray:
+    t = torch.tensor(np.asarray(values, np.float64), dtype=torch.float64).to(torch.bfloat16)
+    assert torch.equal(t.to(torch.float64), torch.tensor(np.asarray(values, np.float64))), \
+        "fixture value is not exactly representable in bf16"
+    return wl.bf16_bits(t)
+
+
+def rand_bits(seed, shape, kind="normal", scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    x = torch.randn(*shape, generator=g)
+    if kind == "t3":
+        c = torch.randn(*shape, 3, generator=g).square().sum(-1)
+        x = x / torch.sqrt(c / 3)
+    return wl.bf16_bits((x * scale).to(torch.bfloat16))
+
+
+def quant_group(oracle, bits, nbits):
+    """Quantize every row of ``bits`` as ONE group of the given width."""
+    K = bits.shape[1]
+    if nbits == 8:
+        q, _, s, _ = oracle.quantize_act(bits, K)
+    else:
+        _, q, _, s = oracle.quantize_act(bits, 0)
+    return q, s
+
+
+def round_half_even(fr: Fraction) -> int:
+    fl = fr.numerator // fr.denominator
+    rem = fr - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        return fl + 1
+    return fl
+
+
+# --------------------------------------------------------------------------
+# quantizer, Eq. 1
+# --------------------------------------------------------------------------
+
+def _golden_rows(name):
+    for line in (GOLDEN / name).read_text().splitlines():
+        line = line.strip()
+        if line and not line.startswith("#"):
+            yield [f.split() for f in line.split("|")]
+
+
+def test_quantizer_hand_derived_ties(oracle):
+    # catches: round-half-away / floor / truncation, qmax = 2^(N-1) instead of
+    # 2^(N-1)-1, scale from max instead of max|.|, zero-group scale
+    n = 0
+    for nb, xs, sc, qs in _golden_rows("quantizer_ties.txt"):
+        nbits = int(nb[0])
+        x = [float(v) for v in xs]
+        q, s = quant_group(oracle, bits_of([x]), nbits)
+        assert s[0] == np.float32(float(sc[0])), (x, s)
+        assert q[0].tolist() == [int(v) for v in qs], (x, q[0].tolist())
+        n += 1
+    assert n >= 10
+
+
+@pytest.mark.parametrize("nbits,qmax", [(8, 127), (4, 7)])
+@pytest.mark.parametrize("kind,scale", [("normal", 1.0), ("t3", 1.0), ("normal", 3e-3),
+                                        ("normal", 4e4)])
+def test_quantizer_error_bound_range_and_scale(oracle, nbits, qmax, kind, scale):
+    bits = rand_bits(11, (64, 96), kind, scale)
+    x = wl.bits_to_f64(bits)
+    q, s = quant_group(oracle, bits, nbits)
+    s64 = s.astype(np.float64)
+    # the scale is the correctly rounded fp32 value of max|x| / qmax (exact check)
+    for m in range(x.shape[0]):
+        exact = Fraction(float(np.abs(x[m]).max())) / qmax
+        got = Fraction(float(s[m]))
+        ulp = Fraction(float(np.spacing(s[m])))
+        assert abs(got - exact) <= ulp / 2
+    # codes stay inside the symmetric range and the largest element hits it
+    assert np.abs(q.astype(np.int32)).max() <= qmax
+    am = np.abs(x).argmax(axis=1)
+    assert np.all(np.abs(q[np.arange(len(am)), am].astype(np.int32)) == qmax)
+    # |x - Q(x)| <= s/2, up to the rounding of the fp32 quotient
+    err = np.abs(x - q.astype(np.float64) * s64[:, None])
+    assert np.all(err <= s64[:, None] / 2 + np.abs(x) * 2.0 ** -23)
+    # the bound is attained closely somewhere, i.e. s is not needlessly large
+    assert (err / s64[:, None]).max() > 0.45
+
+
+@pytest.mark.parametrize("nbits", [8, 4])
+def test_quantizer_exact_rational_brute_force(oracle, nbits):
+    # codes equal round-half-even of the exact quotient x / s unless the exact
+    # quotient is within fp32 rounding of a tie
+    bits = rand_bits(5, (6, 40), "t3")
+    x = wl.bits_to_f64(bits)
+    q, s = quant_group(oracle, bits, nbits)
+    checked = 0
+    for m in range(x.shape[0]):
+        sf = Fraction(float(s[m]))
+        for k in range(x.shape[1]):
+            t = Fraction(float(x[m, k])) / sf
+            frac = t - (t.numerator // t.denominator)
+            if abs(frac - Fraction(1, 2)) <= abs(t) * Fraction(1, 2 ** 22):
+                continue
+            assert int(q[m, k]) == round_half_even(t)
+            checked += 1
+    assert checked > 200
+
+
+def test_quantizer_symmetries(oracle):
+    bits = rand_bits(3, (8, 64))
+    neg = bits ^ np.uint16(0x8000)
+    for nbits in (8, 4):
+        q, s = quant_group(oracle, bits, nbits)
+        qn, sn = quant_group(oracle, neg, nbits)
+        assert np.array_equal(qn, -q) and np.array_equal(sn, s)          # Q(-x) = -Q(x)
+        for k in (-5, 3):                                                # Q(2^k x): same codes
+            sc = wl.bf16_bits(wl.bits_to_bf16(bits).to(torch.float32).mul(2.0 ** k)
+                              .to(torch.bfloat16))
+            q2, s2 = quant_group(oracle, sc, nbits)
+            assert np.array_equal(q2, q) and np.array_equal(s2, s * np.float32(2.0 ** k))
+
+
+def test_quantizer_idempotent_on_power_of_two_scale(oracle):
+    # a row whose max is qmax * 2^k quantizes to a grid that is a fixed point
+    rng = np.random.default_rng(0)
+    for nbits, qmax in ((8, 127), (4, 7)):
+        codes = rng.integers(-qmax, qmax + 1, size=(4, 32))
+        codes[:, 0] = qmax
+        x = codes * 0.25
+        q, s = quant_group(oracle, bits_of(x), nbits)
+        assert np.all(s == np.float32(0.25)) and np.array_equal(q, codes)
+
+
+# --------------------------------------------------------------------------
+# the split into a high and a low group, Eq. 2 / Eq. 3
+# --------------------------------------------------------------------------
+
+def np_uniform(x64, qmax):
+    """Per-row symmetric quantizer with numpy's IEEE fp32 ops (special-case comparator)."""
+    x = x64.astype(np.float32)
+    amax = np.abs(x).max(axis=1)
+    s = np.where(amax == 0, np.float32(1), amax / np.float32(qmax)).astype(np.float32)
+    q = np.clip(np.rint(x / s[:, None]), -qmax, qmax).astype(np.int8)
+    return q, s
+
+
+def test_split_degenerates_to_uniform(oracle):
+    bits = rand_bits(7, (16, 128), "t3")
+    x = wl.bits_to_f64(bits)
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(bits, 0)           # r = 0: uniform INT4
+    q, s = np_uniform(x, 7)
+    assert q_hi.shape == (16, 0) and np.array_equal(q_lo, q) and np.array_equal(s_lo, s)
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(bits, 128)         # r = K: uniform INT8
+    q, s = np_uniform(x, 127)
+    assert q_lo.shape == (16, 0) and np.array_equal(q_hi, q) and np.array_equal(s_hi, s)
+
+
+def test_split_groups_are_independent_and_placed(oracle):
+    # catches: scale taken over the whole row, groups swapped, off-by-one at r
+    bits = rand_bits(9, (8, 96))
+    r = 24
+    x = wl.bits_to_f64(bits)
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(bits, r)
+    qh, sh = np_uniform(x[:, :r], 127)
+    ql, sl = np_uniform(x[:, r:], 7)
+    assert np.array_equal(q_hi, qh) and np.array_equal(s_hi, sh)
+    assert np.array_equal(q_lo, ql) and np.array_equal(s_lo, sl)
+    other = bits.copy()
+    other[:, r:] = rand_bits(10, (8, 96 - r), scale=50.0)
+    q_hi2, _, s_hi2, s_lo2 = oracle.quantize_act(other, r)
+    assert np.array_equal(q_hi2, q_hi) and np.array_equal(s_hi2, s_hi)
+    assert not np.array_equal(s_lo2, s_lo)
+    # a single huge element at column r-1 moves only the high scale, at r only the low one
+    for col, moved in ((r - 1, "hi"), (r, "lo")):
+        spike = bits.copy()
+        spike[:, col] = bits_of([1024.0])[0]
+        _, _, sh2, sl2 = oracle.quantize_act(spike, r)
+        assert np.all((sh2 != s_hi) == (moved == "hi")) and np.all((sl2 != s_lo) == (moved == "lo"))
+
+
+def test_weight_scales_are_fp16_rounded_up(oracle):
+    bits = rand_bits(21, (48, 160), "normal", 0.02)
+    w = wl.bits_to_f64(bits)
+    r = 32
+    w_hi, w_lo, sw_hi, sw_lo = oracle.quantize_weights(bits, r)
+    for codes, sw, grp, qmax in ((w_hi, sw_hi, w[:, :r], 127), (w_lo, sw_lo, w[:, r:], 7)):
+        s16 = sw.view(np.float16)
+        s32 = (np.abs(grp).max(axis=1).astype(np.float32) / np.float32(qmax)).astype(np.float32)
+        assert np.all(s16.astype(np.float32) >= s32)                    # rounded up ...
+        below = np.nextafter(s16, np.float16(0))
+        assert np.all(below.astype(np.float32) < s32)                   # ... to the nearest one
+        assert np.any(s16.astype(np.float32) > s32)                     # (rounding did happen)
+        s = s16.astype(np.float64)[:, None]
+        assert np.abs(codes.astype(np.int32)).max() <= qmax
+        err = np.abs(grp - codes.astype(np.float64) * s)
+        assert np.all(err <= s / 2 + np.abs(grp) * 2.0 ** -23)          # Eq. 1 with stored scale
+        q = np.clip(np.rint(grp.astype(np.float32) / s16.astype(np.float32)[:, None]),
+                    -qmax, qmax)
+        assert np.array_equal(codes, q.astype(np.int8))
+
+
+def test_weight_quantizer_is_per_output_channel(oracle):
+    # rows of W [N, K] are output channels: with fp16-exact scales the weight
+    # quantizer must agree with the per-row activation quantizer on the same matrix
+    rng = np.random.default_rng(1)
+    hi = rng.integers(-127, 128, size=(6, 16)); hi[:, 3] = 127
+    lo = rng.integers(-7, 8, size=(6, 32)); lo[:, 5] = -7
+    scale = 2.0 ** -np.arange(6)[:, None]
+    bits = bits_of(np.concatenate([hi * scale, lo * (2 * scale)], axis=1))
+    w_hi, w_lo, sw_hi, sw_lo = oracle.quantize_weights(bits, 16)
+    assert np.array_equal(w_hi, hi) and np.array_equal(w_lo, lo)
+    assert np.array_equal(sw_hi.view(np.float16).astype(np.float64), scale[:, 0])
+    assert np.array_equal(sw_lo.view(np.float16).astype(np.float64), 2 * scale[:, 0])
+    # all-zero channel and scales outside the fp16 normal range are clamped
+    z = bits_of(np.zeros((1, 48)))
+    _, _, a, b = oracle.quantize_weights(z, 16)
+    assert a.view(np.float16)[0] == 1 and b.view(np.float16)[0] == 1
+    tiny = bits_of(np.full((1, 48), 2.0 ** -30))
+    th, tl, a, b = oracle.quantize_weights(tiny, 16)
+    assert a.view(np.float16)[0] == np.float16(2.0 ** -14) and not th.any() and not tl.any()
+
+
+def test_nibble_packing_fixture_and_roundtrip(oracle):
+    for codes, hexes in _golden_rows("nibble_packing.txt"):
+        c = np.array([[int(v) for v in codes]], np.int8)
+        assert oracle.pack_nibbles(c)[0].tolist() == [int(h, 16) for h in hexes]
+    rng = np.random.default_rng(2)
+    c = rng.integers(-7, 8, size=(5, 26)).astype(np.int8)
+    p = oracle.pack_nibbles(c, ld_out=16)
+    assert p.shape == (5, 16) and not p[:, 13:].any()
+    lo = (p[:, :13] & 0xF).astype(np.int8); lo = np.where(lo > 7, lo - 16, lo)
+    hi = (p[:, :13] >> 4).astype(np.int8); hi = np.where(hi > 7, hi - 16, hi)
+    assert np.array_equal(lo, c[:, 0::2]) and np.array_equal(hi, c[:, 1::2])
+
+
+# --------------------------------------------------------------------------
+# integer GEMM and dequantization, Eq. 4
+# --------------------------------------------------------------------------
+
+def test_gemm_brute_force_and_library(oracle):
+    rng = np.random.default_rng(3)
+    a = rng.integers(-127, 128, size=(5, 7)).astype(np.int8)
+    b = rng.integers(-127, 128, size=(3, 7)).astype(np.int8)
+    got = oracle.gemm_i64(a, b)
+    assert got.shape == (5, 3)
+    for m in range(5):
+        for n in range(3):
+            assert got[m, n] == sum(int(a[m, k]) * int(b[n, k]) for k in range(7))
+    a = rng.integers(-127, 128, size=(33, 300)).astype(np.int8)
+    b = rng.integers(-127, 128, size=(17, 300)).astype(np.int8)
+    assert np.array_equal(oracle.gemm_i64(a, b), a.astype(np.int64) @ b.astype(np.int64).T)
+    # additivity over a split of the reduction axis (what Eq. 4's two-term sum relies on)
+    assert np.array_equal(oracle.gemm_i64(a, b),
+                          oracle.gemm_i64(a[:, :100], b[:, :100]) + oracle.gemm_i64(a[:, 100:], b[:, 100:]))
+
+
+def test_gemm_closed_forms(oracle):
+    rng = np.random.default_rng(4)
+    b = rng.integers(-127, 128, size=(9, 20)).astype(np.int8)
+    ones = np.ones((4, 20), np.int8)
+    assert np.array_equal(oracle.gemm_i64(ones, b), np.tile(b.astype(np.int64).sum(1), (4, 1)))
+    onehot = np.zeros((20, 20), np.int8); onehot[np.arange(20), np.arange(20)] = 3
+    assert np.array_equal(oracle.gemm_i64(onehot, b), 3 * b.astype(np.int64).T)
+    full = np.full((2, 4096), -127, np.int8)
+    assert np.all(oracle.gemm_i64(full, full) == 127 * 127 * 4096)
+    assert oracle.gemm_i64(np.zeros((2, 0), np.int8), np.zeros((3, 0), np.int8)).tolist() == [[0] * 3] * 2
+
+
+def test_dequant_exact_cases(oracle):
+    rng = np.random.default_rng(5)
+    M, N = 4, 6
+    ah = rng.integers(-10 ** 6, 10 ** 6, size=(M, N))
+    al = rng.integers(-10 ** 5, 10 ** 5, size=(M, N))
+    sh = rng.uniform(0.01, 1, M).astype(np.float32)
+    sl = rng.uniform(0.01, 1, M).astype(np.float32)
+    wh = rng.uniform(1e-3, 1e-2, N).astype(np.float16)
+    wlo = rng.uniform(1e-3, 1e-2, N).astype(np.float16)
+    y = oracle.dequant(ah, al, sh, sl, wh.view(np.uint16), wlo.view(np.uint16))
+    for m in range(M):
+        for n in range(N):
+            exact = (int(ah[m, n]) * Fraction(float(sh[m])) * Fraction(float(wh[n]))
+                     + int(al[m, n]) * Fraction(float(sl[m])) * Fraction(float(wlo[n])))
+            assert abs(Fraction(float(y[m, n])) - exact) <= abs(exact) * Fraction(1, 2 ** 48) + Fraction(1, 10 ** 30)
+    # an empty group contributes nothing; scales of the wrong axis would break these
+    y_hi = oracle.dequant(ah, None, sh, sl, wh.view(np.uint16), wlo.view(np.uint16))
+    assert np.allclose(y_hi, ah * sh.astype(np.float64)[:, None] * wh.astype(np.float64)[None, :], rtol=1e-14)
+    y_lo = oracle.dequant(None, al, sh, sl, wh.view(np.uint16), wlo.view(np.uint16))
+    assert np.allclose(y_hi + y_lo, y, rtol=1e-14)
+
+
+def test_layer_is_exact_on_grid_inputs(oracle):
+    # inputs already on the quantization grid with power-of-two scales: the layer
+    # must return X W^T exactly (both Eq. 4 terms, right scales on right axes)
+    rng = np.random.default_rng(6)
+    M, N, r, kl = 5, 7, 8, 12
+    xh = rng.integers(-127, 128, size=(M, r)); xh[:, 0] = 127
+    xl = rng.integers(-7, 8, size=(M, kl)); xl[:, 1] = 7
+    wh = rng.integers(-127, 128, size=(N, r)); wh[:, 2] = -127
+    wlo = rng.integers(-7, 8, size=(N, kl)); wlo[:, 3] = 7
+    sx = 2.0 ** rng.integers(-3, 3, size=(M, 1)); sxl = 2.0 ** rng.integers(-3, 3, size=(M, 1))
+    sw = 2.0 ** rng.integers(-9, -5, size=(N, 1)); swl = 2.0 ** rng.integers(-9, -5, size=(N, 1))
+    X = np.concatenate([xh * sx, xl * sxl], axis=1)
+    W = np.concatenate([wh * sw, wlo * swl], axis=1)
+    res = oracle.linear(bits_of(X), bits_of(W), r)
+    assert np.array_equal(res.acc_hi, xh @ wh.T) and np.array_equal(res.acc_lo, xl @ wlo.T)
+    assert np.array_equal(res.y, X @ W.T)
+
+
+# --------------------------------------------------------------------------
+# Hadamard, Section 4.3 (U_D)
+# --------------------------------------------------------------------------
+
+def test_hadamard_equals_library_matrix(oracle):
+    from scipy.linalg import hadamard as sylvester
+    rng = np.random.default_rng(7)
+    for b in (1, 2, 8, 64):
+        # small integers: products and sums are exact, so is the comparison after /sqrt(b)
+        x = rng.integers(-8, 9, size=(3, 16 + 2 * b + 8)).astype(np.float64)
+        c0, c1 = 16, 16 + 2 * b
+        y = wl.bits_to_f64(oracle.hadamard(bits_of(x), c0, c1, b))
+        assert np.array_equal(y[:, :c0], x[:, :c0]) and np.array_equal(y[:, c1:], x[:, c1:])
+        H = sylvester(b).astype(np.float64) if b > 1 else np.ones((1, 1))
+        for g in range(2):
+            blk = x[:, c0 + g * b:c0 + (g + 1) * b] @ H / np.sqrt(b)
+            want = wl.bits_to_f64(wl.bf16_bits(torch.tensor(blk.astype(np.float32)).to(torch.bfloat16)))
+            got = y[:, c0 + g * b:c0 + (g + 1) * b]
+            # fp32->bf16 of an fp64 value can differ from direct rounding by one bf16 ulp at most
+            assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -7)
+            assert np.mean(got == want) > 0.98
+            assert np.allclose(got[:, 0], x[:, c0 + g * b:c0 + (g + 1) * b].sum(1) / np.sqrt(b), rtol=2.0 ** -8)
+
+
+def test_hadamard_is_orthogonal_involution(oracle):
+    bits = rand_bits(8, (4, 512))
+    x = wl.bits_to_f64(bits)
+    y_bits = oracle.hadamard(bits, 0, 512, 256)
+    y = wl.bits_to_f64(y_bits)
+    assert np.allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=2e-3)
+    back = wl.bits_to_f64(oracle.hadamard(y_bits, 0, 512, 256))
+    assert np.abs(back - x).max() <= 2.0 ** -7 * np.abs(x).max() * 2
+    # a unit impulse at position p of a block becomes row p of H / sqrt(b): +-1/16 everywhere
+    imp = np.zeros((1, 512)); imp[0, 256 + 5] = 16.0
+    out = wl.bits_to_f64(oracle.hadamard(bits_of(imp), 0, 512, 256))
+    assert not out[0, :256].any()
+    signs = np.array([(-1) ** bin(5 & j).count("1") for j in range(256)], np.float64)
+    assert np.array_equal(out[0, 256:], signs)
+
+
+def test_round_bf16_matches_torch_on_fp32_inputs(oracle):
+    g = torch.Generator().manual_seed(12)
+    v = torch.randn(4096, generator=g) * torch.logspace(-20, 20, 4096)
+    v = torch.cat([v, torch.tensor([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3e38, 1e-40])])
+    want = wl.bf16_bits(v.to(torch.bfloat16))
+    assert np.array_equal(oracle.round_bf16(v.to(torch.float64).numpy()), want)
+
+
+# --------------------------------------------------------------------------
+# statements of the paper about the whole scheme
+# --------------------------------------------------------------------------
+
+def test_rotation_inputs_are_orthogonal():
+    # Section 4.1: U U^T = I, so projecting leaves norms and products unchanged
+    R = wl.random_orthogonal(96, 3).to(torch.float64)
+    assert torch.allclose(R @ R.T, torch.eye(96, dtype=torch.float64), atol=1e-5)
+    x = torch.randn(8, 96, dtype=torch.float64)
+    assert torch.allclose((x @ R).norm(dim=1), x.norm(dim=1), rtol=1e-5)
+
+
+def test_snr_grows_with_rank_and_bits(oracle):
+    # Section 5.4 (rank ablation): a wider 8-bit group lowers the error; 4 extra
+    # bits are worth about 24 dB on Gaussian data (6.02 dB per bit)
+    shape = wl.LayerShape("snr", M=48, K=512, N=64, r=0, seed=4)
+    xb, wb = wl.bf16_bits(wl.make_activations(shape)), wl.bf16_bits(wl.make_weights(shape))
+    ref = wl.bits_to_f64(xb) @ wl.bits_to_f64(wb).T
+    snr = [oracle.snr_db(ref, oracle.linear(xb, wb, r).y) for r in (0, 64, 128, 256, 512)]
+    assert all(b > a for a, b in zip(snr, snr[1:]))
+    assert 20.0 < snr[-1] - snr[0] < 28.0
+    # uniform-noise model: activation error power is s^2/12 per element
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(xb, 0)
+    x = wl.bits_to_f64(xb)
+    err = x - q_lo * s_lo.astype(np.float64)[:, None]
+    model = np.sum(s_lo.astype(np.float64) ** 2 / 12) * x.shape[1]
+    assert 0.75 < np.sum(err ** 2) / model < 1.25
+
+
+def test_theorem_4_2_bound_holds_loosely(oracle):
+    # Theorem 4.2 (Gaussian data): E||X - X_q||_F <= c_L E||X||_F - (c_L - c_H) E||X P_h||_F
+    K, r = 1024, 128
+    shape = wl.LayerShape("thm", M=64, K=K, N=8, r=r, seed=9)
+    xb = wl.bf16_bits(wl.make_activations(shape))
+    x = wl.bits_to_f64(xb)
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(xb, r)
+    xq = np.concatenate([q_hi * s_hi.astype(np.float64)[:, None],
+                         q_lo * s_lo.astype(np.float64)[:, None]], axis=1)
+    c_l = np.sqrt(np.pi * np.log(K - r)) / 7
+    c_h = np.sqrt(np.pi * np.log(r)) / 127
+    lhs = np.linalg.norm(x - xq)
+    rhs = c_l * np.linalg.norm(x) - (c_l - c_h) * np.linalg.norm(x[:, :r])
+    assert lhs <= rhs
