@@ -1,0 +1,164 @@
+/*
+ * resq.h - C ABI of the MI355X (gfx950) ResQ mixed-precision linear layer.
+ *
+ * ResQ (arXiv 2412.14363) keeps r of the K input coefficients of a linear
+ * layer in 8 bits and the other K - r in 4 bits, for activations and weights
+ * alike, and evaluates the layer as two integer GEMMs between operands of the
+ * same precision whose dequantized results are added (Section 4.1, Eq. 2-4).
+ * This library is that inference path: per-token activation quantization,
+ * offline weight quantization and packing, the fused two-GEMM kernel with its
+ * dequantizing epilogue, and the online Hadamard transform of the down_proj
+ * input (Section 4.3).
+ *
+ * Conventions common to every call
+ *   - Columns [0, r) of the K axis are the high-precision (INT8) group, columns
+ *     [r, K) the low-precision (INT4) group.  r = 0 and r = K are legal; the
+ *     pointers of an empty group may be null.  K - r must be even.
+ *   - The quantizer is the symmetric one of Section 3, Eq. 1: zero-point 0,
+ *     scale = max|x| / (2^(N-1) - 1) over the group (127 for N = 8, 7 for
+ *     N = 4), code = clip(round_half_even(x / scale)), fp32 IEEE division.
+ *     A group that is all zero has scale 1.
+ *   - Every pointer is a DEVICE pointer owned by the caller unless marked
+ *     "host".  The library allocates nothing and never synchronizes: work is
+ *     enqueued on `stream` (a hipStream_t passed as void*; null = the default
+ *     stream) and results are ready when that stream reaches them.
+ *   - Every function returns a resq_status.  Arguments are checked on the host
+ *     before anything is launched; on any status other than RESQ_OK nothing
+ *     was enqueued (RESQ_ERR_HIP excepted: the runtime refused a launch).
+ *   - bf16 tensors are row-major with a leading dimension given in ELEMENTS.
+ *   - Inputs are expected to be finite; NaN or infinity give unspecified codes.
+ */
+#ifndef RESQ_H
+#define RESQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum resq_status {
+    RESQ_OK = 0,
+    RESQ_ERR_NULL = 1,   /* a required pointer is null                               */
+    RESQ_ERR_SHAPE = 2,  /* M, N, K < 1, r outside [0, K], K - r odd, ld too small,
+                            bad Hadamard block, size beyond a documented limit        */
+    RESQ_ERR_ALIGN = 3,  /* a pointer or leading dimension breaks a stated alignment  */
+    RESQ_ERR_BUFFER = 4, /* packed-weight buffer smaller than resq_packed_weight_bytes */
+    RESQ_ERR_HIP = 5     /* the HIP runtime reported an error at launch               */
+} resq_status;
+
+/* Static, human-readable name of a status code (host pointer, never null). */
+const char* resq_status_string(int status);
+
+/* ---- layout queries (pure host functions) ------------------------------- */
+
+/*
+ * Bytes per token row of the two activation code arrays written by
+ * resq_quantize_act and read by resq_gemm_mixed.  High codes are int8, one per
+ * byte, the row padded with zero codes to a multiple of 128 codes; low codes
+ * are two's-complement nibbles, two per byte (column r + 2j in bits 0..3 and
+ * column r + 2j + 1 in bits 4..7 of byte j), the row padded with zero codes to
+ * a multiple of 256 codes.  Zero codes add nothing to Eq. 4's sums.  Both
+ * return 0 for an empty group and -1 for an invalid (K, r).
+ */
+int64_t resq_act_hi_ld(int64_t K, int64_t r);
+int64_t resq_act_lo_ld(int64_t K, int64_t r);
+
+/*
+ * Size in bytes of the packed weight buffer of an [N, K] layer with a high
+ * group of width r; 0 for invalid arguments.  The layout is private to the
+ * library (tiled for the matrix cores; read it back with resq_unpack_weights):
+ * N is padded to a multiple of 256 rows, the high group to a multiple of 128
+ * and the low group to a multiple of 256 codes, all with zero codes, followed
+ * by two fp16 scale vectors.
+ */
+size_t resq_packed_weight_bytes(int64_t N, int64_t K, int64_t r);
+
+/*
+ * Default block size of the online Hadamard transform over `width` columns:
+ * the largest power of two that divides width, at most 8192 (Sylvester
+ * Hadamard matrices exist only for powers of two, so a width such as
+ * 12544 = 49 * 256 is covered by a block-diagonal transform, which is still
+ * orthogonal).  Returns 0 for width < 1.
+ */
+int64_t resq_hadamard_block(int64_t width);
+
+/* ---- the hot path -------------------------------------------------------- */
+
+/*
+ * Per-token mixed-precision activation quantization (Section 4.1 Eq. 2 with
+ * the quantizer of Section 3 Eq. 1, per token as in Section 5.1).
+ *   x      bf16 [M, ldx], ldx >= K                      (read)
+ *   q_hi   int8  [M, resq_act_hi_ld(K, r)]              (written, padding zeroed)
+ *   q_lo   uint8 [M, resq_act_lo_ld(K, r)]              (written, padding zeroed)
+ *   s_hi, s_lo   fp32 [M] scales of the two groups      (written)
+ * One read of x; the absmax, the division, the rounding and the packing are
+ * fused.  Alignment: none required; x 16-byte aligned with ldx, K and r
+ * multiples of 8 selects the vectorized path.  q_hi and q_lo must be 16-byte
+ * aligned.  Limits: K <= 2^20.
+ */
+int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                      int8_t* q_hi, uint8_t* q_lo, float* s_hi, float* s_lo, void* stream);
+
+/*
+ * Offline weight quantization and packing (Section 4.1 Eq. 3; per output
+ * channel, symmetric, round-to-nearest, Section 5.1).
+ *   w       bf16 [N, ldw], ldw >= K: (out_features, in_features)   (read)
+ *   packed  resq_packed_weight_bytes(N, K, r) bytes, 256-byte aligned (written)
+ * The per-channel scale of each group is stored as fp16, rounded toward +inf
+ * from max|w| / qmax and clamped to [2^-14, 65504]; the codes are computed
+ * with the stored value, so |w - code * scale| <= scale / 2 holds for it.
+ * packed_bytes is the capacity of `packed`.
+ */
+int resq_pack_weights(const void* w, int64_t ldw, int64_t N, int64_t K, int64_t r,
+                      void* packed, size_t packed_bytes, void* stream);
+
+/*
+ * Inverse of the packing, for inspection and parity checks: plain row-major
+ * codes (one per byte) and the stored fp16 scale bit patterns.
+ *   w_hi int8 [N, r]   w_lo int8 [N, K - r]   sw_hi, sw_lo uint16 [N]   (written)
+ */
+int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int8_t* w_hi,
+                        int8_t* w_lo, uint16_t* sw_hi, uint16_t* sw_lo, void* stream);
+
+/*
+ * The layer (Section 4.1 Eq. 4): for every token m and output channel n
+ *   A_hi[m, n] = sum_{k <  r} q_hi[m, k] * w_hi[n, k]       (int8 x int8 -> int32)
+ *   A_lo[m, n] = sum_{k >= r} q_lo[m, k] * w_lo[n, k]       (int4 x int4 -> int32)
+ *   y[m, n]    = bf16( A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n] )
+ * Both sums run on the int8 matrix cores (nibbles are widened in registers)
+ * inside one kernel; y is written once.  The integer sums are exact as long as
+ * 127^2 * r and 49 * (K - r) * 256 stay below 2^31 (K - r <= 171196).
+ *   q_hi, q_lo, s_hi, s_lo   as written by resq_quantize_act for the same K, r
+ *   packed                   as written by resq_pack_weights for the same N, K, r
+ *   y        bf16 [M, ldy], ldy >= N                         (written)
+ *   dbg_acc_hi, dbg_acc_lo   int32 [M, N] each, or null: when given, the two
+ *                            integer accumulators are written as well
+ * Shapes with M <= 16 take a weight-streaming kernel bound by HBM bandwidth,
+ * larger M the tiled matrix-core kernel; the results are identical.
+ * Alignment: q_hi, q_lo 16 bytes; packed 256 bytes; y 2 bytes.
+ */
+int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
+                    const float* s_lo, int64_t M, const void* packed, int64_t N, int64_t K,
+                    int64_t r, void* y, int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo,
+                    void* stream);
+
+/*
+ * Online Hadamard projection of the down_proj input (Section 4.3, U_D):
+ *   y[m, c0 + g*b + j] = (1/sqrt(b)) * sum_i x[m, c0 + g*b + i] * H_b[i, j]
+ * for each block g of b columns in [col_begin, col_end), H_b the Sylvester
+ * (natural-order) Hadamard matrix; other columns are copied.  fp32 butterflies,
+ * bf16 in and out; y may alias x (in place).
+ *   x, y   bf16 [M, ld], ld >= K
+ *   block  power of two dividing col_end - col_begin, <= 8192;
+ *          0 selects resq_hadamard_block(col_end - col_begin)
+ * col_begin must be even.
+ */
+int resq_online_hadamard(const void* x, void* y, int64_t ld, int64_t M, int64_t K,
+                         int64_t col_begin, int64_t col_end, int64_t block, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RESQ_H */

@@ -1,0 +1,202 @@
+"""Python binding of the C ABI in ``include/resq.h``.
+
+Argument marshalling only: every function here has the name of the C entry
+point it calls, takes torch tensors (device memory and streams are the only
+things torch is used for), checks their dtype/device, and passes raw pointers.
+All arithmetic runs in the HIP kernels.  There is no CPU fallback: if the
+library cannot be loaded, importing the symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Optional
+
+import torch
+
+from . import build as _build
+
+RESQ_OK = 0
+STATUS_NAMES = {0: "RESQ_OK", 1: "RESQ_ERR_NULL", 2: "RESQ_ERR_SHAPE", 3: "RESQ_ERR_ALIGN",
+                4: "RESQ_ERR_BUFFER", 5: "RESQ_ERR_HIP"}
+
+# every symbol include/resq.h declares: name -> (restype, argtypes)
+_i64, _p, _sz = C.c_int64, C.c_void_p, C.c_size_t
+SYMBOLS = {
+    "resq_status_string": (C.c_char_p, [C.c_int]),
+    "resq_act_hi_ld": (_i64, [_i64, _i64]),
+    "resq_act_lo_ld": (_i64, [_i64, _i64]),
+    "resq_packed_weight_bytes": (_sz, [_i64, _i64, _i64]),
+    "resq_hadamard_block": (_i64, [_i64]),
+    "resq_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
+    "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
+    "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
+    "resq_gemm_mixed": (C.c_int, [_p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
+    "resq_online_hadamard": (C.c_int, [_p, _p, _i64, _i64, _i64, _i64, _i64, _i64, _p]),
+}
+
+_lib = None
+
+
+class ResqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().resq_status_string(status).decode()
+        super().__init__(f"{where}: {msg}")
+
+
+def lib() -> C.CDLL:
+    """The loaded HIP library (built on first use if no library is there)."""
+    global _lib
+    if _lib is None:
+        path = _build.ensure_built()
+        handle = C.CDLL(str(path))
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(handle, name)  # AttributeError if the symbol is missing
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != RESQ_OK:
+        raise ResqError(status, where)
+
+
+def _dev(t: Optional[torch.Tensor], dtype, name: str):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+# ---- layout queries ---------------------------------------------------------
+
+def resq_act_hi_ld(K: int, r: int) -> int:
+    return int(lib().resq_act_hi_ld(K, r))
+
+
+def resq_act_lo_ld(K: int, r: int) -> int:
+    return int(lib().resq_act_lo_ld(K, r))
+
+
+def resq_packed_weight_bytes(N: int, K: int, r: int) -> int:
+    return int(lib().resq_packed_weight_bytes(N, K, r))
+
+
+def resq_hadamard_block(width: int) -> int:
+    return int(lib().resq_hadamard_block(width))
+
+
+# ---- buffers ----------------------------------------------------------------
+
+class ActCodes:
+    """Device buffers resq_quantize_act writes and resq_gemm_mixed reads."""
+
+    def __init__(self, M: int, K: int, r: int, device="cuda"):
+        self.M, self.K, self.r = M, K, r
+        self.ld_hi, self.ld_lo = resq_act_hi_ld(K, r), resq_act_lo_ld(K, r)
+        if self.ld_hi < 0:
+            raise ValueError("invalid (K, r)")
+        self.q_hi = torch.empty((M, self.ld_hi), dtype=torch.int8, device=device)
+        self.q_lo = torch.empty((M, self.ld_lo), dtype=torch.uint8, device=device)
+        self.s_hi = torch.empty(M, dtype=torch.float32, device=device)
+        self.s_lo = torch.empty(M, dtype=torch.float32, device=device)
+
+
+def alloc_packed(N: int, K: int, r: int, device="cuda") -> torch.Tensor:
+    nbytes = resq_packed_weight_bytes(N, K, r)
+    if nbytes == 0:
+        raise ValueError("invalid (N, K, r)")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+# ---- the entry points -------------------------------------------------------
+
+def resq_quantize_act(x: torch.Tensor, r: int, out: Optional[ActCodes] = None,
+                      stream=None) -> ActCodes:
+    M, K = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    if out is None:
+        out = ActCodes(M, K, r, x.device)
+    st = lib().resq_quantize_act(_dev(x, torch.bfloat16, "x"), x.stride(0), M, K, r,
+                                 out.q_hi.data_ptr() if r > 0 else None,
+                                 out.q_lo.data_ptr() if K - r > 0 else None,
+                                 out.s_hi.data_ptr() if r > 0 else None,
+                                 out.s_lo.data_ptr() if K - r > 0 else None, _stream(stream))
+    _check(st, "resq_quantize_act")
+    return out
+
+
+def resq_pack_weights(w: torch.Tensor, r: int, packed: Optional[torch.Tensor] = None,
+                      stream=None) -> torch.Tensor:
+    N, K = w.shape
+    if w.stride(1) != 1:
+        raise ValueError("w must be row-major [N, K]")
+    if packed is None:
+        packed = alloc_packed(N, K, r, w.device)
+    st = lib().resq_pack_weights(_dev(w, torch.bfloat16, "w"), w.stride(0), N, K, r,
+                                 _dev(packed, torch.uint8, "packed"), packed.numel(),
+                                 _stream(stream))
+    _check(st, "resq_pack_weights")
+    return packed
+
+
+def resq_unpack_weights(packed: torch.Tensor, N: int, K: int, r: int, stream=None):
+    dev = packed.device
+    w_hi = torch.empty((N, r), dtype=torch.int8, device=dev)
+    w_lo = torch.empty((N, K - r), dtype=torch.int8, device=dev)
+    sw_hi = torch.empty(N, dtype=torch.int16, device=dev)
+    sw_lo = torch.empty(N, dtype=torch.int16, device=dev)
+    st = lib().resq_unpack_weights(_dev(packed, torch.uint8, "packed"), N, K, r,
+                                   w_hi.data_ptr() if r > 0 else None,
+                                   w_lo.data_ptr() if K - r > 0 else None,
+                                   sw_hi.data_ptr() if r > 0 else None,
+                                   sw_lo.data_ptr() if K - r > 0 else None, _stream(stream))
+    _check(st, "resq_unpack_weights")
+    return w_hi, w_lo, sw_hi, sw_lo
+
+
+def resq_gemm_mixed(act: ActCodes, packed: torch.Tensor, N: int, y: Optional[torch.Tensor] = None,
+                    dbg_acc_hi: Optional[torch.Tensor] = None,
+                    dbg_acc_lo: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K, r = act.M, act.K, act.r
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=packed.device)
+    if y.stride(1) != 1:
+        raise ValueError("y must be row-major")
+    st = lib().resq_gemm_mixed(act.q_hi.data_ptr() if r > 0 else None,
+                               act.q_lo.data_ptr() if K - r > 0 else None,
+                               act.s_hi.data_ptr() if r > 0 else None,
+                               act.s_lo.data_ptr() if K - r > 0 else None, M,
+                               _dev(packed, torch.uint8, "packed"), N, K, r,
+                               _dev(y, torch.bfloat16, "y"), y.stride(0),
+                               _dev(dbg_acc_hi, torch.int32, "dbg_acc_hi"),
+                               _dev(dbg_acc_lo, torch.int32, "dbg_acc_lo"), _stream(stream))
+    _check(st, "resq_gemm_mixed")
+    return y
+
+
+def resq_online_hadamard(x: torch.Tensor, col_begin: int, col_end: int, block: int = 0,
+                         out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    if out is None:
+        out = torch.empty_like(x)
+    if out.stride() != x.stride():
+        raise ValueError("out must have x's layout")
+    st = lib().resq_online_hadamard(_dev(x, torch.bfloat16, "x"), _dev(out, torch.bfloat16, "out"),
+                                    x.stride(0), M, K, col_begin, col_end, block, _stream(stream))
+    _check(st, "resq_online_hadamard")
+    return out

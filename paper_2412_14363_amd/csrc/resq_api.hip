@@ -1,0 +1,219 @@
+// C ABI of the library: argument checks on the host, then kernel launches on
+// the caller's stream.  See include/resq.h for the contract of every entry.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "resq.h"
+#include "resq_gemm.hip.h"
+#include "resq_hadamard.hip.h"
+#include "resq_layout.h"
+#include "resq_quantize.hip.h"
+
+using namespace resq;
+
+namespace {
+
+constexpr int64_t kMaxK = 1 << 20;
+constexpr int64_t kMaxLoWidth = 171196;  // 256 * 49 * (K - r) < 2^31
+constexpr int64_t kMaxHiWidth = 133143;  // 127^2 * r < 2^31
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline int shape_ok(int64_t rows, int64_t K, int64_t r) {
+    if (rows < 1 || K < 1 || K > kMaxK || r < 0 || r > K) return 0;
+    if ((K - r) % 2 != 0) return 0;
+    if (rows > 0x7FFFFFFF) return 0;
+    return 1;
+}
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? RESQ_OK : RESQ_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* resq_status_string(int status) {
+    switch (status) {
+        case RESQ_OK: return "RESQ_OK";
+        case RESQ_ERR_NULL: return "RESQ_ERR_NULL: a required pointer is null";
+        case RESQ_ERR_SHAPE: return "RESQ_ERR_SHAPE: invalid sizes, group width or leading dimension";
+        case RESQ_ERR_ALIGN: return "RESQ_ERR_ALIGN: pointer or leading dimension misaligned";
+        case RESQ_ERR_BUFFER: return "RESQ_ERR_BUFFER: packed weight buffer too small";
+        case RESQ_ERR_HIP: return "RESQ_ERR_HIP: the HIP runtime refused the launch";
+        default: return "unknown resq status";
+    }
+}
+
+int64_t resq_act_hi_ld(int64_t K, int64_t r) {
+    if (K < 1 || r < 0 || r > K || (K - r) % 2 != 0) return -1;
+    return round_up(r, kHiPad);
+}
+
+int64_t resq_act_lo_ld(int64_t K, int64_t r) {
+    if (K < 1 || r < 0 || r > K || (K - r) % 2 != 0) return -1;
+    return round_up(K - r, kLoPad) / 2;
+}
+
+size_t resq_packed_weight_bytes(int64_t N, int64_t K, int64_t r) {
+    if (!shape_ok(N, K, r)) return 0;
+    return (size_t)make_weight_layout(N, K, r).total_bytes;
+}
+
+int64_t resq_hadamard_block(int64_t width) {
+    if (width < 1) return 0;
+    int64_t b = width & (-width);
+    return b > 8192 ? 8192 : b;
+}
+
+int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r, int8_t* q_hi,
+                      uint8_t* q_lo, float* s_hi, float* s_lo, void* stream) {
+    if (!shape_ok(M, K, r) || ldx < K) return RESQ_ERR_SHAPE;
+    if (!x) return RESQ_ERR_NULL;
+    if (r > 0 && (!q_hi || !s_hi)) return RESQ_ERR_NULL;
+    if (K - r > 0 && (!q_lo || !s_lo)) return RESQ_ERR_NULL;
+    if (!aligned(x, 2) || !aligned(q_hi, 16) || !aligned(q_lo, 16) || !aligned(s_hi, 4) ||
+        !aligned(s_lo, 4))
+        return RESQ_ERR_ALIGN;
+    const int64_t ld_hi = round_up(r, kHiPad), ld_lo = round_up(K - r, kLoPad) / 2;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    const dim3 grid((unsigned)M), block(kQuantThreads);
+    const bool vec = aligned(x, 16) && ldx % 8 == 0 && K % 8 == 0 && r % 8 == 0 && K <= 16384;
+#define RESQ_LAUNCH_QA(ITERS)                                                                   \
+    hipLaunchKernelGGL(quantize_act_vec_kernel<ITERS>, grid, block, 0, st, xp, ldx, (int)K,     \
+                       (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo)
+    if (vec) {
+        if (K <= 2048) RESQ_LAUNCH_QA(1);
+        else if (K <= 4096) RESQ_LAUNCH_QA(2);
+        else if (K <= 8192) RESQ_LAUNCH_QA(4);
+        else RESQ_LAUNCH_QA(8);
+    } else {
+        hipLaunchKernelGGL(quantize_act_generic_kernel, grid, block, 0, st, xp, ldx, (int)K,
+                           (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo);
+    }
+#undef RESQ_LAUNCH_QA
+    return launch_status();
+}
+
+int resq_pack_weights(const void* w, int64_t ldw, int64_t N, int64_t K, int64_t r, void* packed,
+                      size_t packed_bytes, void* stream) {
+    if (!shape_ok(N, K, r) || ldw < K) return RESQ_ERR_SHAPE;
+    if (K - r > kMaxLoWidth || r > kMaxHiWidth) return RESQ_ERR_SHAPE;
+    if (!w || !packed) return RESQ_ERR_NULL;
+    if (!aligned(w, 2) || !aligned(packed, 256)) return RESQ_ERR_ALIGN;
+    const WeightLayout L = make_weight_layout(N, K, r);
+    if (packed_bytes < (size_t)L.total_bytes) return RESQ_ERR_BUFFER;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)L.n_pad), dim3(kQuantThreads), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(w), ldw, L,
+                       static_cast<uint8_t*>(packed));
+    return launch_status();
+}
+
+int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int8_t* w_hi,
+                        int8_t* w_lo, uint16_t* sw_hi, uint16_t* sw_lo, void* stream) {
+    if (!shape_ok(N, K, r)) return RESQ_ERR_SHAPE;
+    if (!packed) return RESQ_ERR_NULL;
+    if (r > 0 && (!w_hi || !sw_hi)) return RESQ_ERR_NULL;
+    if (K - r > 0 && (!w_lo || !sw_lo)) return RESQ_ERR_NULL;
+    if (!aligned(packed, 256) || !aligned(sw_hi, 2) || !aligned(sw_lo, 2)) return RESQ_ERR_ALIGN;
+    const WeightLayout L = make_weight_layout(N, K, r);
+    hipLaunchKernelGGL(unpack_weights_kernel, dim3((unsigned)N), dim3(kQuantThreads), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint8_t*>(packed), L,
+                       w_hi, w_lo, sw_hi, sw_lo);
+    return launch_status();
+}
+
+int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, const float* s_lo,
+                    int64_t M, const void* packed, int64_t N, int64_t K, int64_t r, void* y,
+                    int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo, void* stream) {
+    if (!shape_ok(N, K, r) || M < 1 || M > 0x7FFFFFFF || ldy < N) return RESQ_ERR_SHAPE;
+    if (K - r > kMaxLoWidth || r > kMaxHiWidth) return RESQ_ERR_SHAPE;
+    if (!packed || !y) return RESQ_ERR_NULL;
+    if (r > 0 && (!q_hi || !s_hi)) return RESQ_ERR_NULL;
+    if (K - r > 0 && (!q_lo || !s_lo)) return RESQ_ERR_NULL;
+    if (!aligned(q_hi, 16) || !aligned(q_lo, 16) || !aligned(packed, 256) || !aligned(y, 2) ||
+        !aligned(s_hi, 4) || !aligned(s_lo, 4) || !aligned(dbg_acc_hi, 4) ||
+        !aligned(dbg_acc_lo, 4))
+        return RESQ_ERR_ALIGN;
+
+    GemmArgs a;
+    a.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
+    a.q_lo = q_lo;
+    a.L = make_weight_layout(N, K, r);
+    a.ld_hi = a.L.kh_pad;
+    a.ld_lo = a.L.kl_pad / 2;
+    a.s_hi = s_hi;
+    a.s_lo = s_lo;
+    a.packed = static_cast<const uint8_t*>(packed);
+    a.M = M;
+    a.y = static_cast<uint16_t*>(y);
+    a.ldy = ldy;
+    a.dbg_hi = dbg_acc_hi;
+    a.dbg_lo = dbg_acc_lo;
+    a.stages_hi = (int)(a.L.kh_pad / kHiPad);
+    a.stages_lo = (int)(a.L.kl_pad / kLoPad);
+    a.tiles_m = (int)((M + kBM - 1) / kBM);
+    a.tiles_n = (int)(a.L.n_pad / kBN);
+    const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
+    if (tiles > 0x7FFFFFFF) return RESQ_ERR_SHAPE;
+
+    const int lds_bytes = 2 * kStageBytes;
+    static bool attr_set = false;  // benign if raced: the call is idempotent
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mixed_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds_bytes) != hipSuccess)
+            return RESQ_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_mixed_kernel, dim3((unsigned)tiles), dim3(kGemmThreads), lds_bytes,
+                       static_cast<hipStream_t>(stream), a);
+    return launch_status();
+}
+
+int resq_online_hadamard(const void* x, void* y, int64_t ld, int64_t M, int64_t K,
+                         int64_t col_begin, int64_t col_end, int64_t block, void* stream) {
+    if (M < 1 || K < 1 || K > kMaxK || ld < K || col_begin < 0 || col_end > K ||
+        col_begin >= col_end)
+        return RESQ_ERR_SHAPE;
+    if (!x || !y) return RESQ_ERR_NULL;
+    const int64_t width = col_end - col_begin;
+    if (block == 0) block = resq_hadamard_block(width);
+    if (block < 1 || block > 8192 || (block & (block - 1)) != 0 || width % block != 0)
+        return RESQ_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(y, 16) || ld % 8 != 0 || col_begin % 8 != 0 || width % 8 != 0)
+        return RESQ_ERR_ALIGN;
+
+    HadArgs a;
+    a.x = static_cast<const uint16_t*>(x);
+    a.y = static_cast<uint16_t*>(y);
+    a.ld = ld;
+    a.M = M;
+    a.K = (int)K;
+    a.c0 = (int)col_begin;
+    a.c1 = (int)col_end;
+    int lg = 0;
+    while ((int64_t(1) << lg) < block) ++lg;
+    a.log2b = lg;
+    a.scale = 1.0f / sqrtf((float)block);
+    const int I = block <= 512 ? 1 : (int)(block / 512);
+    const int64_t span = 512 * (int64_t)I;
+    a.spans_per_row = (int)((width + span - 1) / span);
+    const int64_t items = M * a.spans_per_row;
+    const int64_t blocks = (items + kHadThreads / 64 - 1) / (kHadThreads / 64);
+    if (blocks > 0x7FFFFFFF || M > 0x7FFFFFFF) return RESQ_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (x != y && (col_begin > 0 || col_end < K))
+        hipLaunchKernelGGL(hadamard_copy_rest_kernel, dim3((unsigned)M), dim3(kHadThreads), 0, st, a);
+    const dim3 grid((unsigned)blocks), blk(kHadThreads);
+    switch (I) {
+        case 1: hipLaunchKernelGGL(hadamard_kernel<1>, grid, blk, 0, st, a); break;
+        case 2: hipLaunchKernelGGL(hadamard_kernel<2>, grid, blk, 0, st, a); break;
+        case 4: hipLaunchKernelGGL(hadamard_kernel<4>, grid, blk, 0, st, a); break;
+        case 8: hipLaunchKernelGGL(hadamard_kernel<8>, grid, blk, 0, st, a); break;
+        default: hipLaunchKernelGGL(hadamard_kernel<16>, grid, blk, 0, st, a); break;
+    }
+    return launch_status();
+}
+
+}  // extern "C"

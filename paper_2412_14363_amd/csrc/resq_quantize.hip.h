@@ -1,0 +1,270 @@
+// Quantizer kernels: per-token activation quantization (Section 4.1 Eq. 2) and
+// offline per-output-channel weight quantization + packing (Eq. 3), both with
+// the symmetric quantizer of Section 3 Eq. 1.
+//
+// Arithmetic contract (what makes the integer codes reproducible bit for bit):
+//   amax  = max |x| over the group                (exact: bf16 -> fp32 is exact)
+//   scale = amax / qmax                           (fp32 IEEE division; 1 if amax == 0)
+//   code  = clip(rint(x / scale), -qmax, qmax)    (fp32 IEEE division, ties to even)
+// Do not build this file with fast-math or replace a division by a reciprocal.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "resq_layout.h"
+
+namespace resq {
+
+constexpr int kQuantThreads = 256;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ int quant_code(float x, float scale, int qmax) {
+    float q = rintf(x / scale);
+    q = fminf(fmaxf(q, -(float)qmax), (float)qmax);
+    return (int)q;
+}
+
+// max over the 256 threads of a block of two non-negative floats at once
+__device__ __forceinline__ void block_max2(float& a, float& b, float* red /* [8] in LDS */) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        a = fmaxf(a, __shfl_xor(a, off));
+        b = fmaxf(b, __shfl_xor(b, off));
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        red[wave] = a;
+        red[4 + wave] = b;
+    }
+    __syncthreads();
+    a = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    b = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
+}
+
+__device__ __forceinline__ float group_scale(float amax, int qmax) {
+    return amax == 0.0f ? 1.0f : amax / (float)qmax;
+}
+
+// largest |.| of the eight bf16 values in a 16-byte vector, as a float
+__device__ __forceinline__ float absmax8(const uint4& v) {
+    // non-negative bf16 patterns order like unsigned integers
+    uint32_t a = v.x & 0x7FFF7FFFu, b = v.y & 0x7FFF7FFFu, c = v.z & 0x7FFF7FFFu,
+             d = v.w & 0x7FFF7FFFu;
+    uint32_t lo = max(max(a & 0xFFFFu, b & 0xFFFFu), max(c & 0xFFFFu, d & 0xFFFFu));
+    uint32_t hi = max(max(a >> 16, b >> 16), max(c >> 16, d >> 16));
+    return bf16_bits_to_f32(max(lo, hi));
+}
+
+// ---------------------------------------------------------------------------
+// Activations, vectorized: one block per token, the row is read once (16 bytes
+// per lane, coalesced), kept in registers across the absmax reduction, then
+// quantized and stored.  Requires K, r, ldx multiples of 8 and x 16-byte
+// aligned; ITERS * 2048 >= K.
+// ---------------------------------------------------------------------------
+template <int ITERS>
+__global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
+    int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
+    float* __restrict__ s_lo) {
+    __shared__ float red[8];
+    const int64_t m = blockIdx.x;
+    const int t = threadIdx.x;
+    const int nunits = K >> 3;
+    const int hi_units = r >> 3;
+    const uint4* row = reinterpret_cast<const uint4*>(x + m * ldx);
+
+    uint4 v[ITERS];
+    float amax_h = 0.0f, amax_l = 0.0f;
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+        const int u = t + i * kQuantThreads;
+        if (u < nunits) {
+            v[i] = row[u];
+            const float a = absmax8(v[i]);
+            if (u < hi_units) amax_h = fmaxf(amax_h, a);
+            else amax_l = fmaxf(amax_l, a);
+        }
+    }
+    block_max2(amax_h, amax_l, red);
+    const float sh = group_scale(amax_h, kQmaxHi);
+    const float sl = group_scale(amax_l, kQmaxLo);
+    if (t == 0) {
+        if (r > 0) s_hi[m] = sh;
+        if (K - r > 0) s_lo[m] = sl;
+    }
+
+    int8_t* qh = q_hi + m * ld_hi;
+    uint8_t* ql = q_lo + m * ld_lo;
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+        const int u = t + i * kQuantThreads;
+        if (u < nunits) {
+            const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+            if (u < hi_units) {
+                uint32_t out[2] = {0u, 0u};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu);
+                    const int c = quant_code(bf16_bits_to_f32(bits), sh, kQmaxHi);
+                    out[j >> 2] |= (uint32_t)(c & 0xFF) << (8 * (j & 3));
+                }
+                *reinterpret_cast<uint2*>(qh + (int64_t)u * 8) = make_uint2(out[0], out[1]);
+            } else {
+                uint32_t out = 0u;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu);
+                    const int c = quant_code(bf16_bits_to_f32(bits), sl, kQmaxLo);
+                    out |= (uint32_t)(c & 0xF) << (4 * j);
+                }
+                *reinterpret_cast<uint32_t*>(ql + (int64_t)(u - hi_units) * 4) = out;
+            }
+        }
+    }
+    // zero codes in the padding of both rows
+    for (int64_t b = (int64_t)r + 8 * t; b < ld_hi; b += 8 * kQuantThreads)
+        *reinterpret_cast<uint2*>(qh + b) = make_uint2(0u, 0u);
+    for (int64_t b = (int64_t)(K - r) / 2 + 4 * t; b < ld_lo; b += 4 * kQuantThreads)
+        *reinterpret_cast<uint32_t*>(ql + b) = 0u;
+}
+
+// ---------------------------------------------------------------------------
+// Activations, any K, r (K - r even) and alignment: two passes over the row
+// with 2-byte loads.  Correct everywhere, fast nowhere.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kQuantThreads) void quantize_act_generic_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
+    int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
+    float* __restrict__ s_lo) {
+    __shared__ float red[8];
+    const int64_t m = blockIdx.x;
+    const int t = threadIdx.x;
+    const uint16_t* row = x + m * ldx;
+    float amax_h = 0.0f, amax_l = 0.0f;
+    for (int k = t; k < K; k += kQuantThreads) {
+        const float a = bf16_bits_to_f32(row[k] & 0x7FFFu);
+        if (k < r) amax_h = fmaxf(amax_h, a);
+        else amax_l = fmaxf(amax_l, a);
+    }
+    block_max2(amax_h, amax_l, red);
+    const float sh = group_scale(amax_h, kQmaxHi);
+    const float sl = group_scale(amax_l, kQmaxLo);
+    if (t == 0) {
+        if (r > 0) s_hi[m] = sh;
+        if (K - r > 0) s_lo[m] = sl;
+    }
+    int8_t* qh = q_hi + m * ld_hi;
+    uint8_t* ql = q_lo + m * ld_lo;
+    for (int64_t k = t; k < ld_hi; k += kQuantThreads)
+        qh[k] = k < r ? (int8_t)quant_code(bf16_bits_to_f32(row[k]), sh, kQmaxHi) : (int8_t)0;
+    const int pairs = (K - r) / 2;
+    for (int64_t j = t; j < ld_lo; j += kQuantThreads) {
+        uint32_t byte = 0u;
+        if (j < pairs) {
+            const int c0 = quant_code(bf16_bits_to_f32(row[r + 2 * j]), sl, kQmaxLo);
+            const int c1 = quant_code(bf16_bits_to_f32(row[r + 2 * j + 1]), sl, kQmaxLo);
+            byte = (uint32_t)(c0 & 0xF) | ((uint32_t)(c1 & 0xF) << 4);
+        }
+        ql[j] = (uint8_t)byte;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Weights (offline): one block per padded output channel.
+// ---------------------------------------------------------------------------
+
+// smallest positive normal fp16 >= s after clamping s to [2^-14, 65504]
+__device__ __forceinline__ uint16_t fp16_round_up(float s) {
+    s = fminf(fmaxf(s, 6.103515625e-05f), 65504.0f);
+    const uint32_t u = __float_as_uint(s);
+    uint32_t h = (((u >> 23) - 112u) << 10) | ((u & 0x7FFFFFu) >> 13);
+    if (u & 0x1FFFu) h += 1u;
+    return (uint16_t)h;
+}
+__device__ __forceinline__ float fp16_normal_to_f32(uint32_t h) {
+    return __uint_as_float((((h >> 10) & 0x1Fu) + 112u) << 23 | (h & 0x3FFu) << 13);
+}
+
+__global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
+    const uint16_t* __restrict__ w, int64_t ldw, WeightLayout L, uint8_t* __restrict__ packed) {
+    __shared__ float red[8];
+    const int64_t n = blockIdx.x;  // 0 .. n_pad - 1
+    const int t = threadIdx.x;
+    const int K = (int)L.K, r = (int)L.r;
+    uint16_t* sw_hi = reinterpret_cast<uint16_t*>(packed + L.scale_off);
+    uint16_t* sw_lo = sw_hi + L.n_pad;
+    const bool live = n < L.N;
+    const uint16_t* row = w + (live ? n : 0) * ldw;
+
+    float amax_h = 0.0f, amax_l = 0.0f;
+    if (live) {
+        for (int k = t; k < K; k += kQuantThreads) {
+            const float a = bf16_bits_to_f32(row[k] & 0x7FFFu);
+            if (k < r) amax_h = fmaxf(amax_h, a);
+            else amax_l = fmaxf(amax_l, a);
+        }
+    }
+    block_max2(amax_h, amax_l, red);
+    const uint16_t hh = fp16_round_up(group_scale(amax_h, kQmaxHi));
+    const uint16_t hl = fp16_round_up(group_scale(amax_l, kQmaxLo));
+    const float sh = fp16_normal_to_f32(hh), sl = fp16_normal_to_f32(hl);
+    if (t == 0) {
+        sw_hi[n] = (live && r > 0) ? hh : (uint16_t)0x3C00u;      // 1.0
+        sw_lo[n] = (live && K - r > 0) ? hl : (uint16_t)0x3C00u;
+    }
+    // high group: units of 16 codes
+    for (int u = t; u < (int)(L.kh_pad / 16); u += kQuantThreads) {
+        uint32_t out[4] = {0u, 0u, 0u, 0u};
+        if (live) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int k = u * 16 + j;
+                if (k < r) {
+                    const int c = quant_code(bf16_bits_to_f32(row[k]), sh, kQmaxHi);
+                    out[j >> 2] |= (uint32_t)(c & 0xFF) << (8 * (j & 3));
+                }
+            }
+        }
+        *reinterpret_cast<uint4*>(packed + hi_unit_offset(L, n, u)) =
+            make_uint4(out[0], out[1], out[2], out[3]);
+    }
+    // low group: units of 32 codes = 16 bytes
+    for (int u = t; u < (int)(L.kl_pad / 32); u += kQuantThreads) {
+        uint32_t out[4] = {0u, 0u, 0u, 0u};
+        if (live) {
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const int k = r + u * 32 + j;
+                if (k < K) {
+                    const int c = quant_code(bf16_bits_to_f32(row[k]), sl, kQmaxLo);
+                    out[j >> 3] |= (uint32_t)(c & 0xF) << (4 * (j & 7));
+                }
+            }
+        }
+        *reinterpret_cast<uint4*>(packed + lo_unit_offset(L, n, u)) =
+            make_uint4(out[0], out[1], out[2], out[3]);
+    }
+}
+
+__global__ __launch_bounds__(kQuantThreads) void unpack_weights_kernel(
+    const uint8_t* __restrict__ packed, WeightLayout L, int8_t* __restrict__ w_hi,
+    int8_t* __restrict__ w_lo, uint16_t* __restrict__ sw_hi, uint16_t* __restrict__ sw_lo) {
+    const int64_t n = blockIdx.x;  // 0 .. N - 1
+    const int t = threadIdx.x;
+    const int r = (int)L.r, kl = (int)(L.K - L.r);
+    const uint16_t* s = reinterpret_cast<const uint16_t*>(packed + L.scale_off);
+    if (t == 0) {
+        if (r > 0) sw_hi[n] = s[n];
+        if (kl > 0) sw_lo[n] = s[L.n_pad + n];
+    }
+    for (int k = t; k < r; k += kQuantThreads)
+        w_hi[n * r + k] = (int8_t)packed[hi_unit_offset(L, n, k / 16) + (k % 16)];
+    for (int k = t; k < kl; k += kQuantThreads) {
+        const uint32_t byte = packed[lo_unit_offset(L, n, k / 32) + (k % 32) / 2];
+        const int nib = (k & 1) ? (byte >> 4) : (byte & 0xFu);
+        w_lo[n * (int64_t)kl + k] = (int8_t)((nib ^ 8) - 8);  // sign-extend 4 bits
+    }
+}
+
+}  // namespace resq

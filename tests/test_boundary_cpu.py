@@ -1,0 +1,105 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, answers the layout queries, and turns bad
+arguments into status codes before anything is launched."""
+import ctypes as C
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2412_14363_amd import binding
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def declared_symbols():
+    text = (ROOT / "include" / "resq.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(resq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 10
+    handle = C.CDLL(str(binding._build.ensure_built()))
+    for n in names:
+        assert hasattr(handle, n), f"{n} declared in resq.h but not exported"
+    assert sorted(binding.SYMBOLS) == names
+
+
+def test_layout_queries():
+    assert binding.resq_act_hi_ld(256, 32) == 128
+    assert binding.resq_act_lo_ld(256, 32) == 128          # 224 codes -> 256 -> 128 bytes
+    assert binding.resq_act_hi_ld(4096, 512) == 512
+    assert binding.resq_act_lo_ld(4096, 512) == 1792
+    assert binding.resq_act_hi_ld(4096, 0) == 0 and binding.resq_act_lo_ld(4096, 4096) == 0
+    assert binding.resq_act_hi_ld(10, 3) == -1             # K - r odd
+    assert binding.resq_act_lo_ld(8, 9) == -1
+    # 8192 x 28672, r = 1024: 4.5 bits per weight plus two fp16 scales per channel
+    assert binding.resq_packed_weight_bytes(28672, 8192, 1024) == 28672 * (1024 + 3584) + 4 * 28672
+    # N is padded to 256 rows
+    assert binding.resq_packed_weight_bytes(29568, 8192, 1024) == 29696 * (1024 + 3584 + 4)
+    assert binding.resq_packed_weight_bytes(0, 8, 0) == 0
+    assert binding.resq_hadamard_block(12544) == 256
+    assert binding.resq_hadamard_block(14336) == 2048
+    assert binding.resq_hadamard_block(1 << 20) == 8192
+    assert binding.resq_hadamard_block(7) == 1 and binding.resq_hadamard_block(0) == 0
+
+
+def test_status_strings():
+    L = binding.lib()
+    for code, name in binding.STATUS_NAMES.items():
+        assert L.resq_status_string(code).decode().startswith(name)
+    assert b"unknown" in L.resq_status_string(99)
+
+
+P = 0x10000   # a plausible, aligned, never dereferenced address
+
+
+def test_quantize_act_rejects_bad_arguments():
+    f = binding.lib().resq_quantize_act
+    assert f(P, 256, 0, 256, 32, P, P, P, P, None) == 2            # M < 1
+    assert f(P, 256, 4, 256, 257, P, P, P, P, None) == 2           # r > K
+    assert f(P, 256, 4, 256, 33, P, P, P, P, None) == 2            # K - r odd
+    assert f(P, 255, 4, 256, 32, P, P, P, P, None) == 2            # ldx < K
+    assert f(None, 256, 4, 256, 32, P, P, P, P, None) == 1
+    assert f(P, 256, 4, 256, 32, None, P, P, P, None) == 1
+    assert f(P, 256, 4, 256, 32, P, P, P, None, None) == 1
+    assert f(P, 256, 4, 256, 32, P + 8, P, P, P, None) == 3
+    assert f(P + 1, 256, 4, 256, 32, P, P, P, P, None) == 3
+
+
+def test_pack_and_gemm_reject_bad_arguments():
+    L = binding.lib()
+    need = binding.resq_packed_weight_bytes(256, 256, 32)
+    assert L.resq_pack_weights(P, 256, 256, 256, 32, P, need - 1, None) == 4
+    assert L.resq_pack_weights(P, 256, 256, 256, 32, P + 16, need, None) == 3
+    assert L.resq_pack_weights(None, 256, 256, 256, 32, P, need, None) == 1
+    assert L.resq_pack_weights(P, 100, 256, 256, 32, P, need, None) == 2
+    g = L.resq_gemm_mixed
+    assert g(P, P, P, P, 16, P, 256, 256, 32, P, 255, None, None, None) == 2   # ldy < N
+    assert g(P, P, P, P, 16, None, 256, 256, 32, P, 256, None, None, None) == 1
+    assert g(None, P, P, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 1
+    assert g(P, P + 4, P, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 3
+    assert g(P, P, P, P, 16, P, 256, 256, 31, P, 256, None, None, None) == 2
+    u = L.resq_unpack_weights
+    assert u(None, 256, 256, 32, P, P, P, P, None) == 1
+    assert u(P, 256, 256, 32, P, None, P, P, None) == 1
+
+
+def test_hadamard_rejects_bad_arguments():
+    h = binding.lib().resq_online_hadamard
+    assert h(P, P, 512, 4, 512, 0, 512, 3, None) == 2              # not a power of two
+    assert h(P, P, 512, 4, 512, 0, 512, 1024, None) == 2           # does not divide the width
+    assert h(P, P, 512, 4, 512, 0, 768, 0, None) == 2              # col_end > K
+    assert h(P, P, 512, 4, 512, 8, 8, 0, None) == 2                # empty range
+    assert h(None, P, 512, 4, 512, 0, 512, 0, None) == 1
+    assert h(P, P, 512, 4, 512, 4, 260, 0, None) == 3              # col_begin not a multiple of 8
+    assert h(P + 2, P, 512, 4, 512, 0, 512, 0, None) == 3
+
+
+def test_binding_fails_loudly_without_device_tensors():
+    import torch
+    x = torch.zeros(4, 256, dtype=torch.bfloat16)
+    with pytest.raises((ValueError, RuntimeError)):
+        binding.resq_quantize_act(x, 32)

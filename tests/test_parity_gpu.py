@@ -1,0 +1,224 @@
+"""GPU parity: every step of the HIP path against the CPU oracle, through the
+C ABI, on the same seeded inputs.  Integer codes, scales and int32
+accumulators must match bit for bit; bf16 outputs within 1e-2 relative."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_14363_amd import workloads as wl
+from parity_util import REL_TOL, y_within_tolerance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rq():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU fallback")
+    from paper_2412_14363_amd import binding
+    binding.lib()
+    return binding
+
+
+def check_act_codes(oracle, rq, x: torch.Tensor, r: int):
+    M, K = x.shape
+    act = rq.resq_quantize_act(x.cuda(), r)
+    torch.cuda.synchronize()
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(wl.bf16_bits(x), r)
+    if r > 0:
+        want = np.zeros((M, act.ld_hi), np.int8)
+        want[:, :r] = q_hi
+        assert np.array_equal(act.q_hi.cpu().numpy(), want), "INT8 codes differ"
+        assert np.array_equal(act.s_hi.cpu().numpy().view(np.uint32), s_hi.view(np.uint32))
+    if K - r > 0:
+        want = oracle.pack_nibbles(q_lo, act.ld_lo)
+        assert np.array_equal(act.q_lo.cpu().numpy(), want), "INT4 codes differ"
+        assert np.array_equal(act.s_lo.cpu().numpy().view(np.uint32), s_lo.view(np.uint32))
+    return act
+
+
+def check_weights(oracle, rq, w: torch.Tensor, r: int):
+    N, K = w.shape
+    packed = rq.resq_pack_weights(w.cuda(), r)
+    got = [t.cpu().numpy() for t in rq.resq_unpack_weights(packed, N, K, r)]
+    want = oracle.quantize_weights(wl.bf16_bits(w), r)
+    if r > 0:
+        assert np.array_equal(got[0], want[0]), "INT8 weight codes differ"
+        assert np.array_equal(got[2].view(np.uint16), want[2]), "high weight scales differ"
+    if K - r > 0:
+        assert np.array_equal(got[1], want[1]), "INT4 weight codes differ"
+        assert np.array_equal(got[3].view(np.uint16), want[3]), "low weight scales differ"
+    return packed, want
+
+
+def check_layer(oracle, rq, x: torch.Tensor, w: torch.Tensor, r: int, ldy_extra: int = 0):
+    M, K = x.shape
+    N = w.shape[0]
+    act = check_act_codes(oracle, rq, x, r)
+    packed, wq = check_weights(oracle, rq, w, r)
+    ref = oracle.linear(wl.bf16_bits(x), None, r, weights=wq)
+    dbg_hi = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    dbg_lo = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    ybuf = torch.zeros((M, N + ldy_extra), dtype=torch.bfloat16, device="cuda")
+    y = rq.resq_gemm_mixed(act, packed, N, y=ybuf[:, :N], dbg_acc_hi=dbg_hi, dbg_acc_lo=dbg_lo)
+    torch.cuda.synchronize()
+    if r > 0:
+        assert np.array_equal(dbg_hi.cpu().numpy().astype(np.int64), ref.acc_hi), "A_hi differs"
+    if K - r > 0:
+        assert np.array_equal(dbg_lo.cpu().numpy().astype(np.int64), ref.acc_lo), "A_lo differs"
+    rel = y_within_tolerance(y, ref.y)
+    assert rel <= REL_TOL, f"bf16 output off by {rel}"
+    if ldy_extra:
+        assert not ybuf[:, N:].any(), "wrote past N"
+    # without the debug outputs the result must be the same
+    y2 = rq.resq_gemm_mixed(act, packed, N)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y.contiguous())
+    return rel
+
+
+# ---- activations -----------------------------------------------------------
+
+def test_quantize_act_tiny_config(oracle, rq):
+    check_act_codes(oracle, rq, wl.make_activations(wl.TINY), wl.TINY.r)
+
+
+@pytest.mark.parametrize("M,K,r", [(3, 2048, 256), (5, 4096, 512), (2, 8192, 1024),
+                                   (2, 14336, 1792), (7, 4096, 0), (7, 4096, 4096),
+                                   (4, 264, 8), (4, 16384, 2048)])
+def test_quantize_act_vector_path(oracle, rq, M, K, r):
+    s = wl.LayerShape("qa", M=M, K=K, N=1, r=r, act="student_t3", seed=M + K)
+    check_act_codes(oracle, rq, wl.make_activations(s), r)
+
+
+@pytest.mark.parametrize("M,K,r", [(3, 250, 30), (2, 1000, 2), (5, 77, 77), (4, 90, 0),
+                                   (1, 2, 0), (3, 33, 1), (2, 20000, 4000)])
+def test_quantize_act_generic_path(oracle, rq, M, K, r):
+    s = wl.LayerShape("qg", M=M, K=K, N=1, r=r, outliers="first4" if K > 8 else "none", seed=K)
+    check_act_codes(oracle, rq, wl.make_activations(s), r)
+
+
+def test_quantize_act_strided_rows_zero_rows_and_ties(oracle, rq):
+    # rows taken from a wider buffer (ldx > K), an all-zero token, an all-zero group,
+    # and exact ties (values on half-integers of a power-of-two scale)
+    g = torch.Generator().manual_seed(5)
+    big = torch.randn(6, 640, generator=g).to(torch.bfloat16)
+    x = big[:, 64:576]                       # K = 512, ldx = 640, 16-byte aligned start
+    x[1] = 0
+    x[2, :64] = 0
+    x[3, 64:] = 0
+    x[4, :64] = torch.tensor([127.0] + [0.5 * k for k in range(63)]).to(torch.bfloat16)
+    x[4, 64:] = torch.tensor([7.0] + [0.5 * (k % 14) for k in range(447)]).to(torch.bfloat16)
+    xc = x.contiguous()
+    M, K, r = 6, 512, 64
+    dev = big.cuda()
+    act = rq.resq_quantize_act(dev[:, 64:576], r)
+    torch.cuda.synchronize()
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(wl.bf16_bits(xc), r)
+    assert np.array_equal(act.q_hi.cpu().numpy()[:, :r], q_hi)
+    assert np.array_equal(act.q_lo.cpu().numpy()[:, :(K - r) // 2], oracle.pack_nibbles(q_lo))
+    assert np.array_equal(act.s_hi.cpu().numpy(), s_hi) and np.array_equal(act.s_lo.cpu().numpy(), s_lo)
+    assert s_hi[1] == 1 and s_lo[1] == 1 and s_hi[2] == 1 and s_lo[3] == 1
+
+
+# ---- weights ---------------------------------------------------------------
+
+@pytest.mark.parametrize("N,K,r", [(256, 256, 32), (300, 520, 72), (17, 90, 30), (64, 512, 0),
+                                   (64, 512, 512), (513, 4096, 512)])
+def test_pack_weights_roundtrip(oracle, rq, N, K, r):
+    s = wl.LayerShape("w", M=1, K=K, N=N, r=r, seed=N)
+    w = wl.make_weights(s)
+    w[0] = 0                                 # an all-zero output channel
+    check_weights(oracle, rq, w, r)
+
+
+# ---- the layer -------------------------------------------------------------
+
+def test_layer_tiny_config(oracle, rq):
+    s = wl.TINY
+    check_layer(oracle, rq, wl.make_activations(s), wl.make_weights(s), s.r)
+
+
+@pytest.mark.parametrize("M,K,N,r", [
+    (16, 256, 256, 0), (16, 256, 256, 256),      # uniform INT4, uniform INT8
+    (130, 640, 300, 128),                        # ragged M and N, several tiles
+    (257, 1000, 515, 104),                       # K, r off the stage size; N % 4 != 0
+    (64, 4096, 512, 512),                        # Llama-8B K with d/8
+    (200, 90, 40, 30),                           # everything smaller than one stage
+    (1, 512, 256, 64), (4, 512, 256, 64),        # decode-sized M
+    (300, 2048, 768, 256),
+])
+def test_layer_shapes(oracle, rq, M, K, N, r):
+    x, w = wl.random_small_case(M * 7 + K, M, K, N, r, act="student_t3")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+def test_layer_saturated_codes(oracle, rq):
+    # every code at +-qmax: the largest accumulators the shapes allow
+    M, K, N, r = 32, 2048, 256, 256
+    x = torch.ones(M, K)
+    x[::2, ::3] = -1
+    w = torch.ones(N, K) * 0.5
+    w[:, ::5] = -0.5
+    check_layer(oracle, rq, x.to(torch.bfloat16), w.to(torch.bfloat16), r)
+
+
+def test_layer_oproj_prefill_sampled(oracle, rq):
+    # the benchmark's configuration at full size; the oracle checks all codes and
+    # a seeded sample of 48 token rows of the accumulators and outputs
+    s = wl.OPROJ_PREFILL
+    x, w = wl.make_activations(s), wl.make_weights(s)
+    act = check_act_codes(oracle, rq, x, s.r)
+    packed, wq = check_weights(oracle, rq, w, s.r)
+    dbg_hi = torch.empty((s.M, s.N), dtype=torch.int32, device="cuda")
+    dbg_lo = torch.empty((s.M, s.N), dtype=torch.int32, device="cuda")
+    y = rq.resq_gemm_mixed(act, packed, s.N, dbg_acc_hi=dbg_hi, dbg_acc_lo=dbg_lo)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(0).choice(s.M, 48, replace=False))
+    ref = oracle.linear(wl.bf16_bits(x[rows]), None, s.r, weights=wq)
+    assert np.array_equal(dbg_hi.cpu().numpy()[rows].astype(np.int64), ref.acc_hi)
+    assert np.array_equal(dbg_lo.cpu().numpy()[rows].astype(np.int64), ref.acc_lo)
+    assert y_within_tolerance(y[rows], ref.y) <= REL_TOL
+    y2 = rq.resq_gemm_mixed(act, packed, s.N)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+
+
+# ---- Hadamard --------------------------------------------------------------
+
+def check_hadamard(oracle, rq, x, c0, c1, block, inplace=False):
+    b = block or rq.resq_hadamard_block(c1 - c0)
+    xd = x.cuda()
+    yd = rq.resq_online_hadamard(xd, c0, c1, block, out=xd if inplace else None)
+    torch.cuda.synchronize()
+    got = wl.bf16_bits(yd.cpu())
+    want = oracle.hadamard(wl.bf16_bits(x), c0, c1, b)
+    # fp32 butterflies against the fp64 definition: the same bf16 value, or its neighbour
+    g64, w64 = wl.bits_to_f64(got), wl.bits_to_f64(want)
+    assert np.array_equal(got[:, :c0], want[:, :c0]) and np.array_equal(got[:, c1:], want[:, c1:])
+    scale = np.abs(w64).max()
+    assert np.all(np.abs(g64 - w64) <= np.maximum(np.abs(w64), 2.0 ** -8 * scale) * 2.0 ** -7)
+    assert np.mean(got == want) > 0.99
+    return yd
+
+
+@pytest.mark.parametrize("M,K,c0,c1,block", [
+    (5, 512, 0, 512, 0), (3, 1024, 256, 1024, 256), (3, 1024, 256, 1024, 16),
+    (2, 2048, 0, 2048, 0), (2, 8192, 0, 8192, 0), (4, 1792 + 12544, 1792, 1792 + 12544, 0),
+    (3, 520, 8, 520, 8), (3, 64, 0, 64, 1), (2, 4096, 0, 4096, 1024), (2, 48, 8, 40, 0),
+])
+def test_hadamard(oracle, rq, M, K, c0, c1, block):
+    g = torch.Generator().manual_seed(K + c0)
+    x = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    check_hadamard(oracle, rq, x, c0, c1, block)
+    check_hadamard(oracle, rq, x, c0, c1, block, inplace=True)
+
+
+def test_down_proj_path_hadamard_then_quantize(oracle, rq):
+    # the down_proj input: Hadamard on the low group, then the quantizer.  The
+    # quantizer is checked bit-exactly on the GPU's own transformed activations.
+    s = wl.LayerShape("down_small", M=24, K=1792 + 12544, N=256, r=1792, act="student_t3",
+                      hadamard=True, seed=3)
+    x, w = wl.make_activations(s), wl.make_weights(s)
+    xt = check_hadamard(oracle, rq, x, s.r, s.K, 0)
+    check_layer(oracle, rq, xt.cpu(), w, s.r)
