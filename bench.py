@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the ResQ mixed INT8/INT4 linear layer on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic, seeded
+activations that are already resident in HBM: the per-token quantize+pack
+kernel, then the mixed GEMM with its dequantizing epilogue (for the down_proj
+workload the online Hadamard runs first).  Weights are quantized and packed
+once, before the timed region, as they are offline in the method.
+
+Prints ONE JSON line.  ``value`` is 2*M*N*K operations per second of the whole
+step for prefill workloads (TOPS) and algorithmic bytes per second for decode
+workloads (GB/s).  ``roofline`` prices the GEMM kernel alone, its duration
+measured with HIP events around every launch in a second pass over the same
+steps; ``cpu_baseline`` is the CPU oracle timed on a bounded sample of the same
+workload on this host's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 matrix-core peak, TOP/s
+PEAK_HBM_GBS = 8000.0     # MI355X HBM3E peak, GB/s
+
+# HBM traffic per GEMM launch in bytes from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None where no such run has been made for the workload.
+MEASURED_TRAFFIC = {}
+
+
+def workload_shape(name: str):
+    from paper_2412_14363_amd import workloads as wl
+    table = {
+        "tiny": wl.TINY,
+        "oproj_prefill": wl.OPROJ_PREFILL,
+        "gate_up_prefill": wl.MLP_GATE_UP,
+        "down_prefill": wl.MLP_DOWN,
+        "decode_m1": wl.decode_shape(1),
+        "decode_m4": wl.decode_shape(4),
+        "decode_m16": wl.decode_shape(16),
+        "qwen_r0": wl.qwen_mlp_shape(0),
+        "qwen_r1024": wl.qwen_mlp_shape(1024),
+        "qwen_r2048": wl.qwen_mlp_shape(2048),
+    }
+    if name not in table:
+        raise SystemExit(f"unknown workload {name!r}; choose from {sorted(table)}")
+    return table[name]
+
+
+def algorithmic_bytes_gemm(s) -> int:
+    """Bytes one GEMM launch must move: codes and scales of the activations, the
+    packed weights with their scales, and the bf16 output."""
+    per_tok = s.r + (s.K - s.r) // 2 + 8
+    return s.M * per_tok + s.N * (s.r + (s.K - s.r) // 2 + 4) + 2 * s.M * s.N
+
+
+def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 0):
+    """Time the oracle (activation quantizer, two int GEMMs, dequantization) on a
+    row sample sized for roughly ``budget_s`` seconds."""
+    import numpy as np
+    from oracle import resq_oracle as oracle
+    from paper_2412_14363_amd import workloads as wl
+
+    xb = wl.bf16_bits(x)
+    probe = min(shape.M, 2)
+    t0 = time.perf_counter()
+    oracle.linear(xb[:probe], None, shape.r, weights=wq_np)
+    t_probe = max(time.perf_counter() - t0, 1e-4)
+    rows = int(max(1, min(shape.M, probe * budget_s / t_probe)))
+    idx = np.sort(np.random.default_rng(0).choice(shape.M, rows, replace=False))
+    sample = np.ascontiguousarray(xb[idx])
+    t0 = time.perf_counter()
+    if shape.hadamard:
+        sample = oracle.hadamard(sample, shape.r, shape.K, hadamard_block)
+    oracle.linear(sample, None, shape.r, weights=wq_np)
+    dt = time.perf_counter() - t0
+    ops = 2.0 * rows * shape.N * shape.K
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{rows} of {shape.M} token rows x all {shape.N} channels, seed 0, "
+                      f"{dt:.1f} s; weights pre-quantized as on the GPU side",
+            "seconds": dt, "rows": rows}
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="oproj_prefill")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU; --gpus must be 1 "
+                         "(the layer has no multi-GPU path, see DESIGN.md)")
+
+    import torch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU: the library has no CPU path")
+    torch.cuda.set_device(0)
+    from paper_2412_14363_amd import binding as rq
+    from paper_2412_14363_amd import workloads as wl
+
+    s = workload_shape(args.workload)
+    decode = s.M <= 16
+    x = wl.make_activations(s)
+    w = wl.make_weights(s)
+    xd = x.cuda()
+    # decode: rotate over enough weight copies that the 256 MB last-level cache
+    # cannot hold them, so that HBM is what is measured
+    n_copies = 1
+    packed0 = rq.resq_pack_weights(w.cuda(), s.r)
+    if decode:
+        n_copies = max(1, int(-(-768e6 // packed0.numel())))
+    packed = [packed0] + [packed0.clone() for _ in range(n_copies - 1)]
+    act = rq.ActCodes(s.M, s.K, s.r)
+    y = torch.empty((s.M, s.N), dtype=torch.bfloat16, device="cuda")
+    xh = torch.empty_like(xd) if s.hadamard else None
+    L = rq.lib()
+    st = torch.cuda.current_stream().cuda_stream
+
+    def ptr(t, live=True):
+        return t.data_ptr() if live else None
+
+    hi, lo = s.r > 0, s.K - s.r > 0
+    had_args = (xd.data_ptr(), xh.data_ptr() if xh is not None else None, s.K, s.M, s.K, s.r,
+                s.K, 0, st)
+    xq = xh if s.hadamard else xd
+    qa_args = (xq.data_ptr(), s.K, s.M, s.K, s.r, ptr(act.q_hi, hi), ptr(act.q_lo, lo),
+               ptr(act.s_hi, hi), ptr(act.s_lo, lo), st)
+    gemm_args = [(ptr(act.q_hi, hi), ptr(act.q_lo, lo), ptr(act.s_hi, hi), ptr(act.s_lo, lo),
+                  s.M, p.data_ptr(), s.N, s.K, s.r, y.data_ptr(), s.N, None, None, st)
+                 for p in packed]
+
+    def step(i: int, events=None):
+        if s.hadamard:
+            rc = L.resq_online_hadamard(*had_args)
+            assert rc == 0, rc
+        if events is not None:
+            events[0].record()
+        rc = L.resq_quantize_act(*qa_args)
+        assert rc == 0, rc
+        if events is not None:
+            events[1].record()
+        rc = L.resq_gemm_mixed(*gemm_args[i % n_copies])
+        assert rc == 0, rc
+        if events is not None:
+            events[2].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # second pass over the same steps with HIP events around each kernel
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    quant_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    gemm_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+
+    ops = 2.0 * s.M * s.N * s.K
+    abytes = algorithmic_bytes_gemm(s)
+    traffic = MEASURED_TRAFFIC.get(args.workload)
+    if decode:
+        metric, unit = "decode GB/s (% HBM peak)", "GB/s"
+        value = (abytes + 2 * s.M * s.K) / (ms_per_step * 1e-3) / 1e9
+        achieved = abytes / (gemm_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": achieved / PEAK_HBM_GBS, "traffic": traffic}
+    else:
+        metric, unit = "mixed INT8/INT4 linear TOPS (% int8 MFMA peak)", "TOPS"
+        value = ops / (ms_per_step * 1e-3) / 1e12
+        achieved = ops / (gemm_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": achieved / PEAK_INT8_TOPS, "traffic": traffic}
+    roof["kernel"] = "resq gemm_mixed"
+    roof["kernel_ms"] = gemm_ms
+
+    out = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{s.name}: M={s.M} K={s.K} N={s.N} r={s.r}",
+                   "step": ("hadamard + " if s.hadamard else "") + "quantize_act + gemm_mixed",
+                   "weight_copies_rotated": n_copies},
+        "tokens_per_s": s.M / (ms_per_step * 1e-3),
+        "quantize_ms": quant_ms, "gemm_ms": gemm_ms,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import resq_oracle as oracle
+        wq_np = oracle.quantize_weights(wl.bf16_bits(w), s.r)
+        cb = cpu_baseline(s, x, wq_np, args.cpu_budget,
+                          rq.resq_hadamard_block(s.K - s.r) if s.hadamard else 0)
+        if decode:
+            # same unit as the metric: algorithmic bytes of the sampled rows per second
+            frac = cb["rows"] / s.M
+            cb["value"] = abytes * frac / cb["seconds"] / 1e9
+            cb["unit"] = "GB/s"
+        out["cpu_baseline"] = {k: cb[k] for k in ("value", "unit", "cores", "kind", "sample")}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -157,17 +157,13 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
     const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
     if (tiles > 0x7FFFFFFF) return RESQ_ERR_SHAPE;
 
-    const int lds_bytes = 2 * kStageBytes;
-    static bool attr_set = false;  // benign if raced: the call is idempotent
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mixed_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lds_bytes) != hipSuccess)
-            return RESQ_ERR_HIP;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(gemm_mixed_kernel, dim3((unsigned)tiles), dim3(kGemmThreads), lds_bytes,
-                       static_cast<hipStream_t>(stream), a);
+    // static LDS (three stage buffers, 144 KiB): one workgroup per compute unit
+    if (dbg_acc_hi || dbg_acc_lo)
+        hipLaunchKernelGGL(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0,
+                           static_cast<hipStream_t>(stream), a);
+    else
+        hipLaunchKernelGGL(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0,
+                           static_cast<hipStream_t>(stream), a);
     return launch_status();
 }
 
