@@ -39,17 +39,16 @@
 namespace resq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kGemmThreads = 256;
 constexpr int kBM = 128;
 constexpr int kBN = 256;
-constexpr int kStageABytes = kBM * 128;  // 16 KiB
-constexpr int kStageBBytes = kBN * 128;  // 32 KiB
+constexpr int kStageABytes = kBM * kRowBytes;  // 16 KiB = 8 blocks
+constexpr int kStageBBytes = kBN * kRowBytes;  // 32 KiB = 16 blocks
 constexpr int kStageBytes = kStageABytes + kStageBBytes;
-constexpr int kAChunksPerWave = kStageABytes / kChunkBytes / 4;  // 4
-constexpr int kBChunksPerWave = kStageBBytes / kChunkBytes / 4;  // 8
-constexpr int kLoadsPerStage = kAChunksPerWave + kBChunksPerWave;  // per lane
+constexpr int kLoadsPerStage = (kBM + kBN) / kRowsPerBlock * 2 / 4;  // per lane: 12
 
 struct GemmArgs {
     const uint8_t* q_hi;
@@ -93,6 +92,29 @@ __device__ __forceinline__ void load_to_lds_16B(const uint8_t* g, uint8_t* lds_w
         (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
+// 16-byte LDS read whose completion the compiler does not track: the caller
+// pairs it with lds_wait_all() on the same registers before using the values.
+// (Reads the compiler can see would each be preceded by a wait for every
+// direct-to-LDS load in flight, which would serialize the pipeline.)
+template <int OFF>
+__device__ __forceinline__ void lds_read16(v4i& dst, uint32_t addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
+}
+
+// fragments of one reduction step: 2 activation tiles, 4 weight tiles (32 rows x 32 bytes each)
+struct Frags {
+    v4i fa[2];
+    v4i fb[4];
+};
+
+// Wait until every LDS read has returned.  The registers are tied to the wait
+// as in/out operands so that no use of them can be scheduled above it.
+__device__ __forceinline__ void lds_wait_all(Frags& f) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f.fa[0]), "+v"(f.fa[1]), "+v"(f.fb[0]), "+v"(f.fb[1]), "+v"(f.fb[2]),
+                   "+v"(f.fb[3]));
+}
+
 // blockIdx -> (tile_m, tile_n).  Consecutive workgroup ids land on different
 // XCDs (8 of them, each with its own L2), so ids are first regrouped per XCD
 // and each XCD then walks a compact band of the tile grid.
@@ -102,24 +124,6 @@ __device__ __forceinline__ void tile_of_block(const GemmArgs& a, int& tm, int& t
     if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
     tn = id / a.tiles_m;
     tm = id % a.tiles_m;
-}
-
-// 16-byte LDS read whose completion the compiler does not track: the caller
-// pairs it with lds_wait<N>() on the same register before using the value.
-// (Reads the compiler can see would each be preceded by a wait for every
-// direct-to-LDS load in flight, which would serialize the pipeline.)
-template <int OFF>
-__device__ __forceinline__ void lds_read16(v4i& dst, uint32_t addr) {
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
-}
-// Wait until every LDS read has returned.  The twelve registers are tied to
-// the wait as in/out operands so that no use of them can be scheduled above it.
-__device__ __forceinline__ void lds_wait_all(v4i& a0, v4i& a1, v4i& a2, v4i& a3, v4i& b0, v4i& b1,
-                                             v4i& b2, v4i& b3, v4i& b4, v4i& b5, v4i& b6,
-                                             v4i& b7) {
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(b0), "+v"(b1), "+v"(b2), "+v"(b3),
-                   "+v"(b4), "+v"(b5), "+v"(b6), "+v"(b7));
 }
 
 template <bool DBG>
@@ -136,107 +140,109 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     const int64_t m0 = (int64_t)tile_m * kBM;
     const int64_t n0 = (int64_t)tile_n * kBN;
 
-    // ---- what this lane copies per stage ---------------------------------------
-    // Wave w fills chunks 4w..4w+3 of the A image and 8w..8w+7 of the B image.
-    // A chunk q (= 16-token block q/2, 64-byte half q%2): lane l fetches token row
-    // (l % 16), 16-byte piece (l / 16); rows past M are clamped to the last row
-    // (their results are never stored).  A B chunk is 1 KiB contiguous in HBM.
-    const uint8_t* a_src[kAChunksPerWave];
-    const uint8_t* b_src[kBChunksPerWave];
-    auto set_sources = [&](const uint8_t* q, int64_t ld, int64_t b_chunk0) __attribute__((always_inline)) {
+    // ---- global -> LDS copy --------------------------------------------------
+    // One load instruction fills half a block (1 KiB): LDS unit q = lane + 64 h
+    // receives row r(q), 16-byte piece kc(q) of the block, so eight consecutive
+    // lanes fetch one whole 128-byte line of a row.  Wave w copies A blocks
+    // 2w, 2w+1 and B blocks 4w..4w+3 of each stage.  Token rows past M are
+    // clamped to the last row (their results are never stored).
+    const int r_lo = (lane >> 4) * 2 + ((lane >> 3) & 1);                 // row for h = 0; + 8 for h = 1
+    const int kc_h0 = (lane & 7) ^ (lane >> 4);                           // piece for h = 0
+    const int kc_h1 = (lane & 7) ^ ((lane >> 4) + 4);                     // piece for h = 1
+    const uint8_t* a_src[4];
+    const uint8_t* b_src[8];
+    auto set_sources = [&](const uint8_t* q, int64_t ld, int64_t first_block) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < kAChunksPerWave; ++i) {
-            const int chunk = wave * kAChunksPerWave + i;
-            int64_t row = m0 + (chunk >> 1) * 16 + (lane & 15);
+        for (int i = 0; i < 4; ++i) {
+            const int blk = wave * 2 + (i >> 1), h = i & 1;
+            int64_t row = m0 + blk * 16 + r_lo + 8 * h;
             row = row < a.M ? row : a.M - 1;
-            a_src[i] = q + row * ld + (chunk & 1) * 64 + (lane >> 4) * 16;
+            a_src[i] = q + row * ld + (h ? kc_h1 : kc_h0) * 16;
         }
 #pragma unroll
-        for (int i = 0; i < kBChunksPerWave; ++i) {
-            const int chunk = wave * kBChunksPerWave + i;
-            b_src[i] = a.packed + (n0 / 16 + (chunk >> 1)) * a.L.block_bytes +
-                       (b_chunk0 + (chunk & 1)) * kChunkBytes + lane * 16;
+        for (int i = 0; i < 8; ++i) {
+            const int blk = wave * 4 + (i >> 1), h = i & 1;
+            b_src[i] = a.packed + (n0 / 16 + blk) * a.L.group_bytes + first_block * kBlockBytes +
+                       (r_lo + 8 * h) * kRowBytes + (h ? kc_h1 : kc_h0) * 16;
         }
     };
     auto issue_stage = [&](int s, int buf) __attribute__((always_inline)) {
         uint8_t* dst = lds + buf * kStageBytes;
 #pragma unroll
-        for (int i = 0; i < kAChunksPerWave; ++i)
-            load_to_lds_16B(a_src[i] + (int64_t)s * 128,
-                            dst + (wave * kAChunksPerWave + i) * kChunkBytes);
+        for (int i = 0; i < 4; ++i)
+            load_to_lds_16B(a_src[i] + (int64_t)s * kRowBytes, dst + (wave * 4 + i) * 1024);
 #pragma unroll
-        for (int i = 0; i < kBChunksPerWave; ++i)
-            load_to_lds_16B(b_src[i] + (int64_t)s * 2 * kChunkBytes,
-                            dst + kStageABytes + (wave * kBChunksPerWave + i) * kChunkBytes);
+        for (int i = 0; i < 8; ++i)
+            load_to_lds_16B(b_src[i] + (int64_t)s * kBlockBytes,
+                            dst + kStageABytes + (wave * 8 + i) * 1024);
     };
 
-    // ---- accumulators: acc[j][i] is channels 16 j.., tokens 16 i.. of the wave tile;
-    // lane l holds token (l % 16) and channels 4 (l / 16) + {0,1,2,3}
-    v4i acc[8][4];
-    v4f part[8][4];
+    // ---- accumulators ----------------------------------------------------------
+    // acc[j][i]: channels 32 j.., tokens 32 i.. of the wave tile.  Lane l holds
+    // token (l % 32) and, in element v, channel 8 (v / 4) + 4 (l / 32) + v % 4.
+    v16i acc[4][2];
+    v16f part[4][2];
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            acc[j][i] = (v4i){0, 0, 0, 0};
-            part[j][i] = (v4f){0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                acc[j][i][v] = 0;
+                part[j][i][v] = 0.f;
+            }
+
+    // ---- LDS -> register reads ---------------------------------------------------
+    // An operand tile is 32 rows x 128 bytes (two blocks).  In reduction step s4
+    // lane l supplies row (l % 32), piece 2 s4 + l / 32.  off[s4] is the byte
+    // offset of that piece inside the tile.
+    uint32_t a_off[4], b_off[4];
+    {
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+        const int R = lane & 31, r = R & 15, g = lane >> 5;
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const int kc = 2 * s4 + g;
+            const uint32_t off = (R >> 4) * kBlockBytes + ((r >> 1) * 16 + (r & 1) * 8 + (kc ^ (r >> 1))) * 16;
+            a_off[s4] = lds0 + wm * (4 * kBlockBytes) + off;
+            b_off[s4] = lds0 + kStageABytes + wn * (8 * kBlockBytes) + off;
         }
-
-    // LDS byte addresses of this lane's operand pieces in buffer 0
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
-    const uint32_t a_addr0 = lds0 + wm * 4 * 2 * kChunkBytes + lane * 16;
-    const uint32_t b_addr0 = lds0 + kStageABytes + wn * 8 * 2 * kChunkBytes + lane * 16;
-
-    // fragments of one 64-byte chunk: 4 activation pieces, 8 weight pieces
-    struct Frags {
-        v4i fa[4];
-        v4i fb[8];
+    }
+    auto read_step = [&](auto step, Frags& f, int buf) __attribute__((always_inline)) {
+        constexpr int S4 = decltype(step)::value;
+        const uint32_t aa = a_off[S4] + buf * kStageBytes, bb = b_off[S4] + buf * kStageBytes;
+        lds_read16<0 * 2 * kBlockBytes>(f.fa[0], aa);
+        lds_read16<1 * 2 * kBlockBytes>(f.fa[1], aa);
+        lds_read16<0 * 2 * kBlockBytes>(f.fb[0], bb);
+        lds_read16<1 * 2 * kBlockBytes>(f.fb[1], bb);
+        lds_read16<2 * 2 * kBlockBytes>(f.fb[2], bb);
+        lds_read16<3 * 2 * kBlockBytes>(f.fb[3], bb);
     };
-    // issue the 12 reads of chunk C of the stage in buffer `buf`
-    auto read_chunk = [&](auto chunk, Frags& f, int buf) __attribute__((always_inline)) {
-        constexpr int C = decltype(chunk)::value;
-        const uint32_t aa = a_addr0 + buf * kStageBytes, bb = b_addr0 + buf * kStageBytes;
-        lds_read16<(0 * 2 + C) * kChunkBytes>(f.fa[0], aa);
-        lds_read16<(1 * 2 + C) * kChunkBytes>(f.fa[1], aa);
-        lds_read16<(2 * 2 + C) * kChunkBytes>(f.fa[2], aa);
-        lds_read16<(3 * 2 + C) * kChunkBytes>(f.fa[3], aa);
-        lds_read16<(0 * 2 + C) * kChunkBytes>(f.fb[0], bb);
-        lds_read16<(1 * 2 + C) * kChunkBytes>(f.fb[1], bb);
-        lds_read16<(2 * 2 + C) * kChunkBytes>(f.fb[2], bb);
-        lds_read16<(3 * 2 + C) * kChunkBytes>(f.fb[3], bb);
-        lds_read16<(4 * 2 + C) * kChunkBytes>(f.fb[4], bb);
-        lds_read16<(5 * 2 + C) * kChunkBytes>(f.fb[5], bb);
-        lds_read16<(6 * 2 + C) * kChunkBytes>(f.fb[6], bb);
-        lds_read16<(7 * 2 + C) * kChunkBytes>(f.fb[7], bb);
-    };
-    auto wait_chunk = [&](Frags& f) __attribute__((always_inline)) {
-        lds_wait_all(f.fa[0], f.fa[1], f.fa[2], f.fa[3], f.fb[0], f.fb[1], f.fb[2], f.fb[3],
-                     f.fb[4], f.fb[5], f.fb[6], f.fb[7]);
-    };
-    auto mma_chunk = [&](auto is_lo, Frags& f) __attribute__((always_inline)) {
+    auto mma_step = [&](auto is_lo, Frags& f) __attribute__((always_inline)) {
         if constexpr (decltype(is_lo)::value) {
-            v4i fe[4], fo[4];
+            v4i ae[2], ao[2];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                fe[i] = (f.fa[i] << 4) & (int)0xF0F0F0F0;
-                fo[i] = f.fa[i] & (int)0xF0F0F0F0;
+            for (int i = 0; i < 2; ++i) {
+                ae[i] = (f.fa[i] << 4) & (int)0xF0F0F0F0;
+                ao[i] = f.fa[i] & (int)0xF0F0F0F0;
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < 4; ++j) {
                 const v4i be = (f.fb[j] << 4) & (int)0xF0F0F0F0;
                 const v4i bo = f.fb[j] & (int)0xF0F0F0F0;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[j][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(be, fe[i], acc[j][i], 0, 0, 0);
-                    acc[j][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bo, fo[i], acc[j][i], 0, 0, 0);
-                }
+                for (int i = 0; i < 2; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(be, ae[i], acc[j][i], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bo, ao[i], acc[j][i], 0, 0, 0);
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(f.fb[j], f.fa[i], acc[j][i], 0, 0, 0);
+                for (int i = 0; i < 2; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.fb[j], f.fa[i], acc[j][i], 0, 0, 0);
         }
     };
 
@@ -245,11 +251,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     // every wave waits for its own loads of stage s (those of stage s + 1 may
     // stay in flight) and joins the barrier: stage s is then visible to all,
     // and every wave is done with stage s - 1, whose buffer the loads of stage
-    // s + 2 then overwrite.  Each stage is two chunks; the reads of the second
-    // are issued before the matrix instructions of the first, which hide them.
+    // s + 2 then overwrite.  A stage is four reduction steps; the reads of a
+    // step are issued before the matrix instructions of the previous one.
     auto run_group = [&](auto is_lo, int stages) __attribute__((always_inline)) {
-        using C0 = std::integral_constant<int, 0>;
-        using C1 = std::integral_constant<int, 1>;
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        using S2 = std::integral_constant<int, 2>;
+        using S3 = std::integral_constant<int, 3>;
         wait_loads_and_barrier<0>();  // the previous group's buffers are no longer read
         issue_stage(0, 0);
         if (stages > 1) issue_stage(1, 1);
@@ -260,53 +268,70 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             else wait_loads_and_barrier<0>();
             if (s + 2 < stages) issue_stage(s + 2, prv);
             Frags x, y;
-            read_chunk(C0{}, x, buf);
-            wait_chunk(x);
-            read_chunk(C1{}, y, buf);
-            mma_chunk(is_lo, x);
-            wait_chunk(y);
-            mma_chunk(is_lo, y);
+            read_step(S0{}, x, buf);
+            lds_wait_all(x);
+            read_step(S1{}, y, buf);
+            mma_step(is_lo, x);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_wait_all(y);
+            read_step(S2{}, x, buf);
+            mma_step(is_lo, y);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_wait_all(x);
+            read_step(S3{}, y, buf);
+            mma_step(is_lo, x);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_wait_all(y);
+            mma_step(is_lo, y);
+            __builtin_amdgcn_sched_barrier(0);
             buf = buf == 2 ? 0 : buf + 1;
         }
     };
 
     // per-lane coordinates of the epilogue
-    const int64_t tok0 = m0 + wm * 64 + (lane & 15);
-    const int64_t ch0 = n0 + wn * 128 + (lane >> 4) * 4;
+    const int64_t tok0 = m0 + wm * 64 + (lane & 31);
+    const int64_t ch0 = n0 + wn * 128 + (lane >> 5) * 4;
     const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
     const uint16_t* sw_lo = sw_hi + a.L.n_pad;
 
     // part += (acc >> shift) * s_tok[m] * s_ch[n]; acc = 0
     auto fold = [&](const float* s_tok, const uint16_t* s_ch, int32_t* dbg, int shift) __attribute__((always_inline)) {
-        float st[4];
+        float st[2];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t m = tok0 + 16 * i;
+        for (int i = 0; i < 2; ++i) {
+            const int64_t m = tok0 + 32 * i;
             st[i] = m < a.M ? s_tok[m] : 0.0f;
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int64_t n = ch0 + 16 * j;  // < n_pad always
-            const uint2 sc = *reinterpret_cast<const uint2*>(s_ch + n);
-            const float sn[4] = {fp16_bits_to_f32(sc.x & 0xFFFFu), fp16_bits_to_f32(sc.x >> 16),
-                                 fp16_bits_to_f32(sc.y & 0xFFFFu), fp16_bits_to_f32(sc.y >> 16)};
+        for (int j = 0; j < 4; ++j) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int64_t m = tok0 + 16 * i;
+            for (int vq = 0; vq < 4; ++vq) {
+                const int64_t n = ch0 + 32 * j + 8 * vq;  // < n_pad always
+                const uint2 sc = *reinterpret_cast<const uint2*>(s_ch + n);
+                const float sn[4] = {fp16_bits_to_f32(sc.x & 0xFFFFu), fp16_bits_to_f32(sc.x >> 16),
+                                     fp16_bits_to_f32(sc.y & 0xFFFFu), fp16_bits_to_f32(sc.y >> 16)};
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int iv = acc[j][i][v] >> shift;
-                    part[j][i][v] += (float)iv * (st[i] * sn[v]);
-                    if constexpr (DBG) {
-                        if (dbg && m < a.M && n + v < a.L.N) dbg[m * a.L.N + n + v] = iv;
+                for (int i = 0; i < 2; ++i) {
+                    const int64_t m = tok0 + 32 * i;
+#pragma unroll
+                    for (int vr = 0; vr < 4; ++vr) {
+                        const int v = vq * 4 + vr;
+                        const int iv = acc[j][i][v] >> shift;
+                        part[j][i][v] += (float)iv * (st[i] * sn[vr]);
+                        if constexpr (DBG) {
+                            if (dbg && m < a.M && n + vr < a.L.N) dbg[m * a.L.N + n + vr] = iv;
+                        }
+                        acc[j][i][v] = 0;
                     }
-                    acc[j][i][v] = 0;
                 }
-                // keep the fp32 tile in accumulation registers while the other
-                // group's loop needs the ordinary ones for operands
-                asm volatile("" : "+a"(part[j][i]));
             }
         }
+        // keep the fp32 tile in accumulation registers while the other group's
+        // loop needs the ordinary ones for operands
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(part[j][i]));
     };
 
     if (a.stages_hi > 0) {
@@ -315,7 +340,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         fold(a.s_hi, sw_hi, a.dbg_hi, 0);
     }
     if (a.stages_lo > 0) {
-        set_sources(a.q_lo, a.ld_lo, a.L.hi_chunks);
+        set_sources(a.q_lo, a.ld_lo, a.L.hi_blocks);
         run_group(std::true_type{}, a.stages_lo);
         fold(a.s_lo, sw_lo, a.dbg_lo, 8);
     }
@@ -323,23 +348,26 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     // ---- write y once --------------------------------------------------------
     const bool vec_ok = ((reinterpret_cast<uintptr_t>(a.y) & 7) == 0) && (a.ldy % 4 == 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t m = tok0 + 16 * i;
+    for (int i = 0; i < 2; ++i) {
+        const int64_t m = tok0 + 32 * i;
         if (m >= a.M) continue;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int64_t n = ch0 + 16 * j;
-            uint16_t o[4];
+        for (int j = 0; j < 4; ++j) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) o[v] = f32_to_bf16_rne(part[j][i][v]);
-            uint16_t* dst = a.y + m * a.ldy + n;
-            if (vec_ok && n + 3 < a.L.N) {
-                *reinterpret_cast<uint2*>(dst) =
-                    make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
-            } else {
+            for (int vq = 0; vq < 4; ++vq) {
+                const int64_t n = ch0 + 32 * j + 8 * vq;
+                uint16_t o[4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (n + v < a.L.N) dst[v] = o[v];
+                for (int vr = 0; vr < 4; ++vr) o[vr] = f32_to_bf16_rne(part[j][i][vq * 4 + vr]);
+                uint16_t* dst = a.y + m * a.ldy + n;
+                if (vec_ok && n + 3 < a.L.N) {
+                    *reinterpret_cast<uint2*>(dst) =
+                        make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+                } else {
+#pragma unroll
+                    for (int vr = 0; vr < 4; ++vr)
+                        if (n + vr < a.L.N) dst[vr] = o[vr];
+                }
             }
         }
     }

@@ -8,22 +8,17 @@
 //                                byte, even column in bits 0..3
 // Padding codes are zero.
 //
-// Packed weights are tiled for the 16x16x64 int8 matrix-core instruction.  Its
-// operand register holds, in lane l, 16 consecutive bytes of the reduction axis
-// for row (l % 16), sub-chunk (l / 16).  A "chunk" is the 1 KiB image of one
-// such operand: 16 weight rows x 64 bytes, stored sub-chunk-major,
-//   byte offset = ((kc * 16) + row) * 16 + byte,   kc in 0..3, row in 0..15,
-// so that a wavefront reads it with one fully coalesced 16-byte-per-lane load
-// (lane l reads offset 16 * l) straight into operand registers or into LDS.
-// A chunk of the high group covers 64 int8 codes per row, a chunk of the low
-// group 128 nibble codes per row (byte j of a row's 64 holds codes 2j, 2j+1,
-// as in the activation rows).
-//
-// The buffer is
-//   for each block of 16 output channels (n_pad / 16 of them):
-//       kh_pad / 64 high chunks, then kl_pad / 128 low chunks
+// Packed weights use the same two row formats, cut into blocks that a GEMM
+// stage consumes whole: a "block" is 16 output channels x 128 bytes of one
+// group's row (128 int8 codes of the high group, or 256 nibble codes of the low
+// group), row-major, 2 KiB, contiguous in HBM.  The buffer is
+//   for each group of 16 output channels (n_pad / 16 of them):
+//       kh_pad / 128 high blocks, then kl_pad / 256 low blocks
 //   fp16 sw_hi[n_pad], fp16 sw_lo[n_pad]
 // with n_pad = round_up(N, 256); padding rows hold zero codes and scale 1.
+// So channel n, byte b of its padded high row lives at
+//   (n / 16) * group_bytes + (b / 128) * 2048 + (n % 16) * 128 + b % 128
+// and byte b of its packed low row at the same place past the high blocks.
 #pragma once
 #include <stdint.h>
 
@@ -36,15 +31,16 @@ constexpr int kHiPad = 128;     // codes; one LDS stage of the tiled GEMM = 128 
 constexpr int kLoPad = 256;     // codes (= 128 bytes per row)
 constexpr int kNPad = 256;      // output channels; the widest GEMM tile
 constexpr int kRowsPerBlock = 16;
-constexpr int kChunkBytes = 1024;
+constexpr int kRowBytes = 128;  // bytes of one row inside a block
+constexpr int kBlockBytes = kRowsPerBlock * kRowBytes;  // 2048
 
 __host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
 struct WeightLayout {
     int64_t N, K, r;
     int64_t kh_pad, kl_pad, n_pad;
-    int64_t hi_chunks, lo_chunks;  // per 16-row block
-    int64_t block_bytes;           // bytes of one 16-row block
+    int64_t hi_blocks, lo_blocks;  // per group of 16 channels
+    int64_t group_bytes;           // bytes of one group of 16 channels
     int64_t scale_off;             // byte offset of sw_hi; sw_lo follows at + 2 * n_pad
     int64_t total_bytes;
 };
@@ -55,24 +51,22 @@ __host__ __device__ inline WeightLayout make_weight_layout(int64_t N, int64_t K,
     L.kh_pad = round_up(r, kHiPad);
     L.kl_pad = round_up(K - r, kLoPad);
     L.n_pad = round_up(N, kNPad);
-    L.hi_chunks = L.kh_pad / 64;
-    L.lo_chunks = L.kl_pad / 128;
-    L.block_bytes = (L.hi_chunks + L.lo_chunks) * kChunkBytes;
-    L.scale_off = (L.n_pad / kRowsPerBlock) * L.block_bytes;
+    L.hi_blocks = L.kh_pad / kHiPad;
+    L.lo_blocks = L.kl_pad / kLoPad;
+    L.group_bytes = (L.hi_blocks + L.lo_blocks) * kBlockBytes;
+    L.scale_off = (L.n_pad / kRowsPerBlock) * L.group_bytes;
     L.total_bytes = L.scale_off + 4 * L.n_pad;
     return L;
 }
 
-// byte offset of the 16-byte unit holding, for output channel n, bytes
-// [16 * u, 16 * u + 16) of its padded high row (u counts 16-byte units)
-__host__ __device__ inline int64_t hi_unit_offset(const WeightLayout& L, int64_t n, int64_t u) {
-    return (n / kRowsPerBlock) * L.block_bytes + (u / 4) * kChunkBytes +
-           ((u % 4) * 16 + (n % kRowsPerBlock)) * 16;
+// byte offset of byte b of channel n's padded high row / packed low row
+__host__ __device__ inline int64_t hi_byte_offset(const WeightLayout& L, int64_t n, int64_t b) {
+    return (n / kRowsPerBlock) * L.group_bytes + (b / kRowBytes) * kBlockBytes +
+           (n % kRowsPerBlock) * kRowBytes + b % kRowBytes;
 }
-// same for the packed low row (unit u = bytes [16u, 16u+16) = codes [32u, 32u+32))
-__host__ __device__ inline int64_t lo_unit_offset(const WeightLayout& L, int64_t n, int64_t u) {
-    return (n / kRowsPerBlock) * L.block_bytes + (L.hi_chunks + u / 4) * kChunkBytes +
-           ((u % 4) * 16 + (n % kRowsPerBlock)) * 16;
+__host__ __device__ inline int64_t lo_byte_offset(const WeightLayout& L, int64_t n, int64_t b) {
+    return (n / kRowsPerBlock) * L.group_bytes + (L.hi_blocks + b / kRowBytes) * kBlockBytes +
+           (n % kRowsPerBlock) * kRowBytes + b % kRowBytes;
 }
 
 }  // namespace resq

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
                 }
             }
         }
-        *reinterpret_cast<uint4*>(packed + hi_unit_offset(L, n, u)) =
+        *reinterpret_cast<uint4*>(packed + hi_byte_offset(L, n, (int64_t)u * 16)) =
             make_uint4(out[0], out[1], out[2], out[3]);
     }
     // low group: units of 32 codes = 16 bytes
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
                 }
             }
         }
-        *reinterpret_cast<uint4*>(packed + lo_unit_offset(L, n, u)) =
+        *reinterpret_cast<uint4*>(packed + lo_byte_offset(L, n, (int64_t)u * 16)) =
             make_uint4(out[0], out[1], out[2], out[3]);
     }
 }
@@ -259,9 +259,9 @@ __global__ __launch_bounds__(kQuantThreads) void unpack_weights_kernel(
         if (kl > 0) sw_lo[n] = s[L.n_pad + n];
     }
     for (int k = t; k < r; k += kQuantThreads)
-        w_hi[n * r + k] = (int8_t)packed[hi_unit_offset(L, n, k / 16) + (k % 16)];
+        w_hi[n * r + k] = (int8_t)packed[hi_byte_offset(L, n, k)];
     for (int k = t; k < kl; k += kQuantThreads) {
-        const uint32_t byte = packed[lo_unit_offset(L, n, k / 32) + (k % 32) / 2];
+        const uint32_t byte = packed[lo_byte_offset(L, n, k / 2)];
         const int nib = (k & 1) ? (byte >> 4) : (byte & 0xFu);
         w_lo[n * (int64_t)kl + k] = (int8_t)((nib ^ 8) - 8);  // sign-extend 4 bits
     }
