@@ -150,14 +150,14 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
     a.ldy = ldy;
     a.dbg_hi = dbg_acc_hi;
     a.dbg_lo = dbg_acc_lo;
-    a.stages_hi = (int)(a.L.kh_pad / kHiPad);
-    a.stages_lo = (int)(a.L.kl_pad / kLoPad);
+    a.stages_hi = (int)a.L.hi_blocks;  // one stage = one 64-byte block per row
+    a.stages_lo = (int)a.L.lo_blocks;
     a.tiles_m = (int)((M + kBM - 1) / kBM);
     a.tiles_n = (int)(a.L.n_pad / kBN);
     const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
     if (tiles > 0x7FFFFFFF) return RESQ_ERR_SHAPE;
 
-    // static LDS (three stage buffers, 144 KiB): one workgroup per compute unit
+    // static LDS (six stage buffers, 144 KiB): one workgroup per compute unit
     if (dbg_acc_hi || dbg_acc_lo)
         hipLaunchKernelGGL(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0,
                            static_cast<hipStream_t>(stream), a);

@@ -2,32 +2,43 @@
 //   A_hi = q_hi * w_hi^T over the high group, A_lo = q_lo * w_lo^T over the low
 //   group, y = bf16(A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n]).
 //
-// One workgroup of 4 wavefronts owns a 128 (tokens) x 256 (channels) output
-// tile; each wavefront owns 64 x 128 of it as 4 x 8 tiles of the 16x16x64 int8
-// matrix-core instruction.  The reduction axis is walked in stages of 128 bytes
-// per row: a stage of the high group is 128 int8 codes, a stage of the low
-// group 256 nibble codes, so the global->LDS copy is the same for both.  LDS
-// holds operand images ("chunks", see resq_layout.h) that a wavefront reads
-// with one conflict-free 16-byte-per-lane load each.
+// Tiling.  One workgroup of 4 wavefronts owns a 128 (tokens) x 256 (channels)
+// output tile; each wavefront owns 64 x 128 of it as 2 x 4 tiles of the
+// 32x32x32 int8 matrix-core instruction, the weights as its first operand so
+// that a lane ends up with four consecutive channels of one token.
 //
-// Global -> LDS copies use the direct-to-LDS load (16 bytes per lane, the LDS
-// destination is a wave-uniform base plus 16 * lane), so no registers are spent
-// on staging; three LDS buffers keep two stages in flight behind the one being
-// multiplied, with one workgroup barrier per stage.  The three buffers are
-// separate __shared__ arrays and the stage loop is unrolled by three so that
-// every LDS access names its array statically: the compiler then only waits
-// for the loads that fill the buffer it is about to read.
+// Stages.  The reduction axis is walked in stages of 64 bytes per row: 64 int8
+// codes of the high group or 128 nibble codes of the low group, i.e. two
+// matrix-core steps of 32 bytes.  High and low stages form one sequence; the
+// global->LDS copy is the same for both.  Six LDS buffers of 24 KiB hold the
+// stage being multiplied, the next one, and up to four in flight.
 //
-// The low group: a lane's 16 packed bytes hold 32 codes.  (p << 4) & 0xF0F0F0F0
+// Global -> LDS.  The direct-to-LDS load moves 16 bytes per lane to a
+// wave-uniform LDS base plus 16 * lane, so the LDS image is fixed by which
+// global address each lane asks for.  A block (16 rows x 64 bytes) is stored
+// with piece kc (16 bytes) of row r at unit 4 r + (kc ^ (r >> 2)): four
+// consecutive lanes fetch one row's 64 contiguous bytes, and the 16 lanes that
+// later read the same piece of 16 different rows hit 16 different bank groups.
+//
+// LDS -> registers.  Operand reads are issued as untracked ds_read_b128 (inline
+// asm) and paired with an explicit wait: reads the compiler can see would each
+// be preceded by a wait for every direct-to-LDS load still in flight.
+//
+// Software pipeline, per reduction step k:  read(k+2) | transform(k+1) | multiply(k)
+// where transform widens nibbles for a low step (and is a register copy for a
+// high step), so that the matrix instructions of step k never wait for the
+// vector ALU work of their own operands.
+//
+// The low group.  A lane's 16 packed bytes hold 32 codes; (p << 4) & 0xF0F0F0F0
 // puts the even codes, p & 0xF0F0F0F0 the odd codes, into the high nibble of
-// each byte, i.e. 16 * code as int8, for activations and weights alike; the two
-// results feed two matrix-core instructions.  The accumulator therefore holds
-// 256 * A_lo, and an arithmetic shift by 8 recovers A_lo exactly.
+// each byte, i.e. 16 * code as int8, for activations and weights alike, and the
+// two results feed two matrix-core instructions.  The accumulator then holds
+// 256 * A_lo; an arithmetic shift by 8 recovers A_lo exactly.
 //
-// The two groups have different scale pairs, so they cannot share an integer
-// accumulator: after the high stages the int32 tile is scaled into an fp32
-// tile that stays in registers, the int32 tile is cleared for the low stages,
-// and the output is written once.
+// Two scale pairs, one output write.  After the last high step the int32 tile is
+// scaled into an fp32 tile that stays in (accumulation) registers, the int32
+// tile is cleared for the low steps, and y is written once, through LDS so that
+// every store instruction writes whole 256-byte row segments.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -45,10 +56,13 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int kGemmThreads = 256;
 constexpr int kBM = 128;
 constexpr int kBN = 256;
-constexpr int kStageABytes = kBM * kRowBytes;  // 16 KiB = 8 blocks
-constexpr int kStageBBytes = kBN * kRowBytes;  // 32 KiB = 16 blocks
+constexpr int kStageABytes = kBM * kRowBytes;  // 8 KiB = 8 blocks
+constexpr int kStageBBytes = kBN * kRowBytes;  // 16 KiB = 16 blocks
 constexpr int kStageBytes = kStageABytes + kStageBBytes;
-constexpr int kLoadsPerStage = (kBM + kBN) / kRowsPerBlock * 2 / 4;  // per lane: 12
+constexpr int kNumBuf = 6;
+constexpr int kPrefetch = kNumBuf - 1;  // stages requested ahead of the one being multiplied
+constexpr int kLoadsPerStage = (kBM + kBN) / kRowsPerBlock / 4;  // per lane: 6
+constexpr int kOutRowBytes = 128 * 2 + 16;  // one wave-tile row of bf16 in LDS, padded
 
 struct GemmArgs {
     const uint8_t* q_hi;
@@ -71,19 +85,27 @@ __device__ __forceinline__ float fp16_bits_to_f32(uint32_t h) {
     return __uint_as_float((((h >> 10) & 0x1Fu) + 112u) << 23 | (h & 0x3FFu) << 13);
 }
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return u >> 16;
 }
 
 // Wait until at most N of this wave's vector-memory loads are outstanding, then
-// join the workgroup barrier.  Written as one asm statement with a memory
-// clobber: the compiler may not move LDS accesses across it, and, unlike
-// __syncthreads(), it does not drain the loads of the stages still in flight.
+// join the workgroup barrier.  One asm statement with a memory clobber: the
+// compiler may not move LDS accesses across it, and, unlike __syncthreads(),
+// it does not drain the loads of the stages still in flight.
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+// the same with N = 6 * later, later = 0..3 stages allowed to stay in flight
+__device__ __forceinline__ void wait_stage_and_barrier(int later) {
+    if (later >= 4) wait_loads_and_barrier<4 * kLoadsPerStage>();
+    else if (later == 3) wait_loads_and_barrier<3 * kLoadsPerStage>();
+    else if (later == 2) wait_loads_and_barrier<2 * kLoadsPerStage>();
+    else if (later == 1) wait_loads_and_barrier<1 * kLoadsPerStage>();
+    else wait_loads_and_barrier<0>();
 }
 
 __device__ __forceinline__ void load_to_lds_16B(const uint8_t* g, uint8_t* lds_wave_base) {
@@ -92,24 +114,27 @@ __device__ __forceinline__ void load_to_lds_16B(const uint8_t* g, uint8_t* lds_w
         (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
-// 16-byte LDS read whose completion the compiler does not track: the caller
-// pairs it with lds_wait_all() on the same registers before using the values.
-// (Reads the compiler can see would each be preceded by a wait for every
-// direct-to-LDS load in flight, which would serialize the pipeline.)
 template <int OFF>
 __device__ __forceinline__ void lds_read16(v4i& dst, uint32_t addr) {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
 }
 
-// fragments of one reduction step: 2 activation tiles, 4 weight tiles (32 rows x 32 bytes each)
-struct Frags {
+// packed fragments of one reduction step as read from LDS:
+// 2 activation tiles and 4 weight tiles of 32 rows x 32 bytes
+struct Packed {
     v4i fa[2];
     v4i fb[4];
+};
+// matrix-core operands of one reduction step: for a low step the even-code and
+// odd-code halves of every fragment; for a high step only the e members are used
+struct Operands {
+    v4i ae[2], ao[2];
+    v4i be[4], bo[4];
 };
 
 // Wait until every LDS read has returned.  The registers are tied to the wait
 // as in/out operands so that no use of them can be scheduled above it.
-__device__ __forceinline__ void lds_wait_all(Frags& f) {
+__device__ __forceinline__ void lds_wait_all(Packed& f) {
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(f.fa[0]), "+v"(f.fa[1]), "+v"(f.fb[0]), "+v"(f.fb[1]), "+v"(f.fb[2]),
                    "+v"(f.fb[3]));
@@ -128,7 +153,7 @@ __device__ __forceinline__ void tile_of_block(const GemmArgs& a, int& tm, int& t
 
 template <bool DBG>
 __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs a) {
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[3 * kStageBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[kNumBuf * kStageBytes];
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -139,42 +164,42 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     tile_of_block(a, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * kBM;
     const int64_t n0 = (int64_t)tile_n * kBN;
+    const int S_hi = a.stages_hi, S = a.stages_hi + a.stages_lo;
 
     // ---- global -> LDS copy --------------------------------------------------
-    // One load instruction fills half a block (1 KiB): LDS unit q = lane + 64 h
-    // receives row r(q), 16-byte piece kc(q) of the block, so eight consecutive
-    // lanes fetch one whole 128-byte line of a row.  Wave w copies A blocks
-    // 2w, 2w+1 and B blocks 4w..4w+3 of each stage.  Token rows past M are
-    // clamped to the last row (their results are never stored).
-    const int r_lo = (lane >> 4) * 2 + ((lane >> 3) & 1);                 // row for h = 0; + 8 for h = 1
-    const int kc_h0 = (lane & 7) ^ (lane >> 4);                           // piece for h = 0
-    const int kc_h1 = (lane & 7) ^ ((lane >> 4) + 4);                     // piece for h = 1
-    const uint8_t* a_src[4];
-    const uint8_t* b_src[8];
-    auto set_sources = [&](const uint8_t* q, int64_t ld, int64_t first_block) __attribute__((always_inline)) {
+    // One load instruction fills one block: lane l fetches row l / 4, piece
+    // (l % 4) ^ (l / 16).  Wave w copies A blocks 2w, 2w+1 and B blocks 4w..4w+3
+    // of each stage.  Token rows past M are clamped to the last row (their
+    // results are never stored).  The weight blocks of one 16-channel group are
+    // contiguous over all stages, high ones first.
+    const uint8_t* a_src_hi[2];
+    const uint8_t* a_src_lo[2];
+    const uint8_t* b_src[4];
+    {
+        const int r = lane >> 2, kc = (lane & 3) ^ (lane >> 4);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int blk = wave * 2 + (i >> 1), h = i & 1;
-            int64_t row = m0 + blk * 16 + r_lo + 8 * h;
+        for (int i = 0; i < 2; ++i) {
+            int64_t row = m0 + (wave * 2 + i) * 16 + r;
             row = row < a.M ? row : a.M - 1;
-            a_src[i] = q + row * ld + (h ? kc_h1 : kc_h0) * 16;
+            a_src_hi[i] = a.q_hi + row * a.ld_hi + kc * 16;
+            a_src_lo[i] = a.q_lo + row * a.ld_lo + kc * 16 - (int64_t)S_hi * kRowBytes;
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int blk = wave * 4 + (i >> 1), h = i & 1;
-            b_src[i] = a.packed + (n0 / 16 + blk) * a.L.group_bytes + first_block * kBlockBytes +
-                       (r_lo + 8 * h) * kRowBytes + (h ? kc_h1 : kc_h0) * 16;
-        }
-    };
-    auto issue_stage = [&](int s, int buf) __attribute__((always_inline)) {
-        uint8_t* dst = lds + buf * kStageBytes;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            load_to_lds_16B(a_src[i] + (int64_t)s * kRowBytes, dst + (wave * 4 + i) * 1024);
+            b_src[i] = a.packed + (n0 / 16 + wave * 4 + i) * a.L.group_bytes + r * kRowBytes + kc * 16;
+    }
+    // request stage sg (0 .. S-1, high stages first) into buffer buf
+    auto issue_stage = [&](int sg, int buf) __attribute__((always_inline)) {
+        uint8_t* dst = lds + buf * kStageBytes;
+        const bool lo = sg >= S_hi;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            load_to_lds_16B(b_src[i] + (int64_t)s * kBlockBytes,
-                            dst + kStageABytes + (wave * 8 + i) * 1024);
+        for (int i = 0; i < 2; ++i)
+            load_to_lds_16B((lo ? a_src_lo[i] : a_src_hi[i]) + (int64_t)sg * kRowBytes,
+                            dst + (wave * 2 + i) * kBlockBytes);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            load_to_lds_16B(b_src[i] + (int64_t)sg * kBlockBytes,
+                            dst + kStageABytes + (wave * 4 + i) * kBlockBytes);
     };
 
     // ---- accumulators ----------------------------------------------------------
@@ -193,24 +218,23 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             }
 
     // ---- LDS -> register reads ---------------------------------------------------
-    // An operand tile is 32 rows x 128 bytes (two blocks).  In reduction step s4
-    // lane l supplies row (l % 32), piece 2 s4 + l / 32.  off[s4] is the byte
-    // offset of that piece inside the tile.
-    uint32_t a_off[4], b_off[4];
+    // An operand tile is 32 rows x 64 bytes (two blocks).  In step st (0, 1) of a
+    // stage lane l supplies row (l % 32), piece 2 st + l / 32.
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    uint32_t a_off[2], b_off[2];
     {
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
         const int R = lane & 31, r = R & 15, g = lane >> 5;
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-            const int kc = 2 * s4 + g;
-            const uint32_t off = (R >> 4) * kBlockBytes + ((r >> 1) * 16 + (r & 1) * 8 + (kc ^ (r >> 1))) * 16;
-            a_off[s4] = lds0 + wm * (4 * kBlockBytes) + off;
-            b_off[s4] = lds0 + kStageABytes + wn * (8 * kBlockBytes) + off;
+        for (int st = 0; st < 2; ++st) {
+            const int kc = 2 * st + g;
+            const uint32_t off = (R >> 4) * kBlockBytes + (4 * r + (kc ^ (r >> 2))) * 16;
+            a_off[st] = lds0 + wm * (4 * kBlockBytes) + off;
+            b_off[st] = lds0 + kStageABytes + wn * (8 * kBlockBytes) + off;
         }
     }
-    auto read_step = [&](auto step, Frags& f, int buf) __attribute__((always_inline)) {
-        constexpr int S4 = decltype(step)::value;
-        const uint32_t aa = a_off[S4] + buf * kStageBytes, bb = b_off[S4] + buf * kStageBytes;
+    auto read_step = [&](auto step, Packed& f, int buf) __attribute__((always_inline)) {
+        constexpr int ST = decltype(step)::value;
+        const uint32_t aa = a_off[ST] + buf * kStageBytes, bb = b_off[ST] + buf * kStageBytes;
         lds_read16<0 * 2 * kBlockBytes>(f.fa[0], aa);
         lds_read16<1 * 2 * kBlockBytes>(f.fa[1], aa);
         lds_read16<0 * 2 * kBlockBytes>(f.fb[0], bb);
@@ -218,74 +242,47 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         lds_read16<2 * 2 * kBlockBytes>(f.fb[2], bb);
         lds_read16<3 * 2 * kBlockBytes>(f.fb[3], bb);
     };
-    auto mma_step = [&](auto is_lo, Frags& f) __attribute__((always_inline)) {
+    auto transform = [&](auto is_lo, const Packed& p, Operands& u) __attribute__((always_inline)) {
         if constexpr (decltype(is_lo)::value) {
-            v4i ae[2], ao[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                ae[i] = (f.fa[i] << 4) & (int)0xF0F0F0F0;
-                ao[i] = f.fa[i] & (int)0xF0F0F0F0;
+                u.ae[i] = (p.fa[i] << 4) & (int)0xF0F0F0F0;
+                u.ao[i] = p.fa[i] & (int)0xF0F0F0F0;
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const v4i be = (f.fb[j] << 4) & (int)0xF0F0F0F0;
-                const v4i bo = f.fb[j] & (int)0xF0F0F0F0;
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(be, ae[i], acc[j][i], 0, 0, 0);
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bo, ao[i], acc[j][i], 0, 0, 0);
+                u.be[j] = (p.fb[j] << 4) & (int)0xF0F0F0F0;
+                u.bo[j] = p.fb[j] & (int)0xF0F0F0F0;
             }
         } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) u.ae[i] = p.fa[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) u.be[j] = p.fb[j];
+        }
+    };
+    auto multiply = [&](auto is_lo, const Operands& u) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.be[j], u.ae[i], acc[j][i], 0, 0, 0);
+        if constexpr (decltype(is_lo)::value) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.fb[j], f.fa[i], acc[j][i], 0, 0, 0);
+                    acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.bo[j], u.ao[i], acc[j][i], 0, 0, 0);
         }
     };
-
-    // One group's stages; the buffer of stage s is s % 3, and up to two stages
-    // are in flight behind the one being multiplied.  At the top of stage s
-    // every wave waits for its own loads of stage s (those of stage s + 1 may
-    // stay in flight) and joins the barrier: stage s is then visible to all,
-    // and every wave is done with stage s - 1, whose buffer the loads of stage
-    // s + 2 then overwrite.  A stage is four reduction steps; the reads of a
-    // step are issued before the matrix instructions of the previous one.
-    auto run_group = [&](auto is_lo, int stages) __attribute__((always_inline)) {
-        using S0 = std::integral_constant<int, 0>;
-        using S1 = std::integral_constant<int, 1>;
-        using S2 = std::integral_constant<int, 2>;
-        using S3 = std::integral_constant<int, 3>;
-        wait_loads_and_barrier<0>();  // the previous group's buffers are no longer read
-        issue_stage(0, 0);
-        if (stages > 1) issue_stage(1, 1);
-        int buf = 0;
-        for (int s = 0; s < stages; ++s) {
-            const int prv = buf == 0 ? 2 : buf - 1;
-            if (s + 1 < stages) wait_loads_and_barrier<kLoadsPerStage>();
-            else wait_loads_and_barrier<0>();
-            if (s + 2 < stages) issue_stage(s + 2, prv);
-            Frags x, y;
-            read_step(S0{}, x, buf);
-            lds_wait_all(x);
-            read_step(S1{}, y, buf);
-            mma_step(is_lo, x);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_wait_all(y);
-            read_step(S2{}, x, buf);
-            mma_step(is_lo, y);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_wait_all(x);
-            read_step(S3{}, y, buf);
-            mma_step(is_lo, x);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_wait_all(y);
-            mma_step(is_lo, y);
-            __builtin_amdgcn_sched_barrier(0);
-            buf = buf == 2 ? 0 : buf + 1;
-        }
+    // one pipeline slot: operands of the next step are produced while the
+    // matrix instructions of the current step run
+    auto slot = [&](auto next_lo, auto cur_lo, const Packed& p_next, Operands& u_next,
+                    const Operands& u_cur) __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        transform(next_lo, p_next, u_next);
+        multiply(cur_lo, u_cur);
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     // per-lane coordinates of the epilogue
@@ -326,49 +323,106 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                 }
             }
         }
-        // keep the fp32 tile in accumulation registers while the other group's
-        // loop needs the ordinary ones for operands
+        // keep the fp32 tile in accumulation registers while the low steps need
+        // the ordinary ones for operands
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(part[j][i]));
     };
 
-    if (a.stages_hi > 0) {
-        set_sources(a.q_hi, a.ld_hi, 0);
-        run_group(std::false_type{}, a.stages_hi);
-        fold(a.s_hi, sw_hi, a.dbg_hi, 0);
-    }
-    if (a.stages_lo > 0) {
-        set_sources(a.q_lo, a.ld_lo, a.L.hi_blocks);
-        run_group(std::true_type{}, a.stages_lo);
-        fold(a.s_lo, sw_lo, a.dbg_lo, 8);
+    // ---- main loop ---------------------------------------------------------------
+    using T0 = std::integral_constant<int, 0>;
+    using T1 = std::integral_constant<int, 1>;
+    using HI = std::false_type;
+    using LO = std::true_type;
+    {
+        Packed px, py;
+        Operands ux, uy;
+        const int ahead = S < kPrefetch ? S : kPrefetch;
+        for (int i = 0; i < ahead; ++i) issue_stage(i, i);
+        wait_stage_and_barrier(ahead - 1);  // stage 0 has landed everywhere
+        read_step(T0{}, px, 0);
+        lds_wait_all(px);
+        read_step(T1{}, py, 0);
+        if (S_hi > 0) transform(HI{}, px, ux);
+        else transform(LO{}, px, ux);
+
+        int buf = 0;
+        // one stage = two pipeline slots; `cur` is the kind of this stage's steps,
+        // `next` the kind of the next stage's first step
+        auto stage = [&](auto cur, auto next, int sg) __attribute__((always_inline)) {
+            const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
+            const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
+            // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
+            // stages sg + 2 .. sg + 4 may stay in flight
+            const int rem = S - 2 - sg;
+            wait_stage_and_barrier(rem > 3 ? 3 : rem);
+            if (sg + kPrefetch < S) issue_stage(sg + kPrefetch, prv);
+            // invariant: ux = operands of (sg, step 0); py = reads of (sg, step 1) in flight
+            lds_wait_all(py);
+            read_step(T0{}, px, nxt);  // past the last stage: a harmless read of stale LDS
+            slot(cur, cur, py, uy, ux);
+            lds_wait_all(px);
+            read_step(T1{}, py, nxt);
+            slot(next, cur, px, ux, uy);
+            buf = nxt;
+        };
+        if (S_hi > 0) {
+            for (int sg = 0; sg + 1 < S_hi; ++sg) stage(HI{}, HI{}, sg);
+            stage(HI{}, LO{}, S_hi - 1);
+            fold(a.s_hi, sw_hi, a.dbg_hi, 0);
+        }
+        for (int sg = S_hi; sg < S; ++sg) stage(LO{}, LO{}, sg);
+        if (a.stages_lo > 0) fold(a.s_lo, sw_lo, a.dbg_lo, 8);
     }
 
     // ---- write y once --------------------------------------------------------
-    const bool vec_ok = ((reinterpret_cast<uintptr_t>(a.y) & 7) == 0) && (a.ldy % 4 == 0);
+    wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
+    const bool fast = ((reinterpret_cast<uintptr_t>(a.y) & 15) == 0) && (a.ldy % 8 == 0) &&
+                      (n0 + kBN <= a.L.N);
+    if (fast) {
+        // wave tile (64 tokens x 128 channels, bf16) -> LDS, row-padded; then each
+        // store instruction writes four whole 256-byte row segments
+        uint8_t* mine = lds + wave * (64 * kOutRowBytes);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int64_t m = tok0 + 32 * i;
-        if (m >= a.M) continue;
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int64_t n = ch0 + 32 * j + 8 * vq;
-                uint16_t o[4];
+                for (int vq = 0; vq < 4; ++vq) {
+                    const uint32_t lo = f32_to_bf16_rne(part[j][i][vq * 4 + 0]) |
+                                        (f32_to_bf16_rne(part[j][i][vq * 4 + 1]) << 16);
+                    const uint32_t hi = f32_to_bf16_rne(part[j][i][vq * 4 + 2]) |
+                                        (f32_to_bf16_rne(part[j][i][vq * 4 + 3]) << 16);
+                    const int row = 32 * i + (lane & 31);
+                    const int col = 32 * j + 8 * vq + 4 * (lane >> 5);
+                    *reinterpret_cast<uint2*>(mine + row * kOutRowBytes + col * 2) = make_uint2(lo, hi);
+                }
+        __syncthreads();
 #pragma unroll
-                for (int vr = 0; vr < 4; ++vr) o[vr] = f32_to_bf16_rne(part[j][i][vq * 4 + vr]);
-                uint16_t* dst = a.y + m * a.ldy + n;
-                if (vec_ok && n + 3 < a.L.N) {
-                    *reinterpret_cast<uint2*>(dst) =
-                        make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
-                } else {
+        for (int it = 0; it < 16; ++it) {
+            const int row = it * 4 + (lane >> 4);
+            const int64_t m = m0 + wm * 64 + row;
+            const uint4 v = *reinterpret_cast<const uint4*>(mine + row * kOutRowBytes + (lane & 15) * 16);
+            if (m < a.M)
+                *reinterpret_cast<uint4*>(a.y + m * a.ldy + n0 + wn * 128 + (lane & 15) * 8) = v;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int64_t m = tok0 + 32 * i;
+            if (m >= a.M) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int64_t n = ch0 + 32 * j + 8 * vq;
 #pragma unroll
                     for (int vr = 0; vr < 4; ++vr)
-                        if (n + vr < a.L.N) dst[vr] = o[vr];
+                        if (n + vr < a.L.N)
+                            a.y[m * a.ldy + n + vr] = (uint16_t)f32_to_bf16_rne(part[j][i][vq * 4 + vr]);
                 }
-            }
         }
     }
 }

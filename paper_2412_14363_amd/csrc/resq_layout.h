@@ -9,15 +9,16 @@
 // Padding codes are zero.
 //
 // Packed weights use the same two row formats, cut into blocks that a GEMM
-// stage consumes whole: a "block" is 16 output channels x 128 bytes of one
-// group's row (128 int8 codes of the high group, or 256 nibble codes of the low
-// group), row-major, 2 KiB, contiguous in HBM.  The buffer is
+// stage consumes whole: a "block" is 16 output channels x 64 bytes of one
+// group's row (64 int8 codes of the high group, or 128 nibble codes of the low
+// group), row-major, 1 KiB, contiguous in HBM: exactly one operand of the
+// 16x16x64 matrix-core instruction, or half of a 32x32x32 one.  The buffer is
 //   for each group of 16 output channels (n_pad / 16 of them):
-//       kh_pad / 128 high blocks, then kl_pad / 256 low blocks
+//       kh_pad / 64 high blocks, then kl_pad / 128 low blocks
 //   fp16 sw_hi[n_pad], fp16 sw_lo[n_pad]
 // with n_pad = round_up(N, 256); padding rows hold zero codes and scale 1.
 // So channel n, byte b of its padded high row lives at
-//   (n / 16) * group_bytes + (b / 128) * 2048 + (n % 16) * 128 + b % 128
+//   (n / 16) * group_bytes + (b / 64) * 1024 + (n % 16) * 64 + b % 64
 // and byte b of its packed low row at the same place past the high blocks.
 #pragma once
 #include <stdint.h>
@@ -27,12 +28,12 @@ namespace resq {
 constexpr int kQmaxHi = 127;  // 2^(8-1) - 1  (Section 3, Eq. 1, N = 8)
 constexpr int kQmaxLo = 7;    // 2^(4-1) - 1  (Section 3, Eq. 1, N = 4)
 
-constexpr int kHiPad = 128;     // codes; one LDS stage of the tiled GEMM = 128 bytes per row
+constexpr int kHiPad = 128;     // codes
 constexpr int kLoPad = 256;     // codes (= 128 bytes per row)
 constexpr int kNPad = 256;      // output channels; the widest GEMM tile
 constexpr int kRowsPerBlock = 16;
-constexpr int kRowBytes = 128;  // bytes of one row inside a block
-constexpr int kBlockBytes = kRowsPerBlock * kRowBytes;  // 2048
+constexpr int kRowBytes = 64;   // bytes of one row inside a block
+constexpr int kBlockBytes = kRowsPerBlock * kRowBytes;  // 1024
 
 __host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
@@ -51,8 +52,8 @@ __host__ __device__ inline WeightLayout make_weight_layout(int64_t N, int64_t K,
     L.kh_pad = round_up(r, kHiPad);
     L.kl_pad = round_up(K - r, kLoPad);
     L.n_pad = round_up(N, kNPad);
-    L.hi_blocks = L.kh_pad / kHiPad;
-    L.lo_blocks = L.kl_pad / kLoPad;
+    L.hi_blocks = L.kh_pad / kRowBytes;
+    L.lo_blocks = L.kl_pad / (2 * kRowBytes);
     L.group_bytes = (L.hi_blocks + L.lo_blocks) * kBlockBytes;
     L.scale_off = (L.n_pad / kRowsPerBlock) * L.group_bytes;
     L.total_bytes = L.scale_off + 4 * L.n_pad;
