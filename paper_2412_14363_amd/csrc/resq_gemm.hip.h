@@ -141,14 +141,28 @@ __device__ __forceinline__ void lds_wait_all(Packed& f) {
 }
 
 // blockIdx -> (tile_m, tile_n).  Consecutive workgroup ids land on different
-// XCDs (8 of them, each with its own L2), so ids are first regrouped per XCD
-// and each XCD then walks a compact band of the tile grid.
+// XCDs (8 of them, 32 compute units and one L2 each), and an XCD runs its
+// workgroups in id order, 32 at a time.  When the grid allows it, the 32 tiles
+// an XCD works on together form an 8 x 4 patch (1024 tokens x 1024 channels),
+// so that each activation stage is fetched into that L2 once per 4 tiles and
+// each weight stage once per 8; the 8 XCDs take neighbouring patches.
 __device__ __forceinline__ void tile_of_block(const GemmArgs& a, int& tm, int& tn) {
     const int total = a.tiles_m * a.tiles_n;
-    int id = blockIdx.x;
-    if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
-    tn = id / a.tiles_m;
-    tm = id % a.tiles_m;
+    const int id = blockIdx.x;
+    if (total % 256 == 0 && a.tiles_m % 8 == 0 && a.tiles_n % 4 == 0) {
+        const int xcd = id & 7, k = id >> 3;
+        const int patch = (k >> 5) * 8 + xcd, within = k & 31;
+        const int patches_m = a.tiles_m >> 3;
+        tm = (patch % patches_m) * 8 + (within & 7);
+        tn = (patch / patches_m) * 4 + (within >> 3);
+    } else if (total % 8 == 0) {
+        const int lin = (id & 7) * (total >> 3) + (id >> 3);
+        tn = lin / a.tiles_m;
+        tm = lin % a.tiles_m;
+    } else {
+        tn = id / a.tiles_m;
+        tm = id % a.tiles_m;
+    }
 }
 
 template <bool DBG>
@@ -261,28 +275,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             for (int j = 0; j < 4; ++j) u.be[j] = p.fb[j];
         }
     };
-    auto multiply = [&](auto is_lo, const Operands& u) __attribute__((always_inline)) {
+    // matrix instructions FIRST .. LAST-1 of a step, in an order that keeps two
+    // instructions on the same accumulator eight apart
+    auto multiply = [&](auto is_lo, auto first, auto last, const Operands& u) __attribute__((always_inline)) {
+        constexpr int FIRST = decltype(first)::value, LAST = decltype(last)::value;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
+        for (int q = FIRST; q < LAST; ++q) {
+            const int j = (q & 7) >> 1, i = q & 1;
+            if (q < 8)
                 acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.be[j], u.ae[i], acc[j][i], 0, 0, 0);
-        if constexpr (decltype(is_lo)::value) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.bo[j], u.ao[i], acc[j][i], 0, 0, 0);
+            else
+                acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.bo[j], u.ao[i], acc[j][i], 0, 0, 0);
         }
-    };
-    // one pipeline slot: operands of the next step are produced while the
-    // matrix instructions of the current step run
-    auto slot = [&](auto next_lo, auto cur_lo, const Packed& p_next, Operands& u_next,
-                    const Operands& u_cur) __attribute__((always_inline)) {
-        __builtin_amdgcn_sched_barrier(0);
-        transform(next_lo, p_next, u_next);
-        multiply(cur_lo, u_cur);
-        __builtin_amdgcn_sched_barrier(0);
     };
 
     // per-lane coordinates of the epilogue
@@ -349,23 +353,39 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         else transform(LO{}, px, ux);
 
         int buf = 0;
-        // one stage = two pipeline slots; `cur` is the kind of this stage's steps,
-        // `next` the kind of the next stage's first step
+        // One stage = two pipeline slots; `cur` is the kind of this stage's steps,
+        // `next` the kind of the next stage's first step.  In each slot the first
+        // two matrix instructions are issued before anything else, so that the
+        // waits, the barrier and the issue of reads and loads run in their shadow.
+        using N0 = std::integral_constant<int, 0>;
+        using N2 = std::integral_constant<int, 2>;
         auto stage = [&](auto cur, auto next, int sg) __attribute__((always_inline)) {
+            using NM = std::integral_constant<int, decltype(cur)::value ? 16 : 8>;
             const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
             const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
+            // invariant: ux = operands of (sg, step 0); py = reads of (sg, step 1) in flight
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(cur, N0{}, N2{}, ux);
+            __builtin_amdgcn_sched_barrier(0);
             // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
             // stages sg + 2 .. sg + 4 may stay in flight
             const int rem = S - 2 - sg;
             wait_stage_and_barrier(rem > 3 ? 3 : rem);
-            if (sg + kPrefetch < S) issue_stage(sg + kPrefetch, prv);
-            // invariant: ux = operands of (sg, step 0); py = reads of (sg, step 1) in flight
             lds_wait_all(py);
             read_step(T0{}, px, nxt);  // past the last stage: a harmless read of stale LDS
-            slot(cur, cur, py, uy, ux);
+            __builtin_amdgcn_sched_barrier(0);
+            if (sg + kPrefetch < S) issue_stage(sg + kPrefetch, prv);
+            transform(cur, py, uy);
+            multiply(cur, N2{}, NM{}, ux);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(cur, N0{}, N2{}, uy);
+            __builtin_amdgcn_sched_barrier(0);
             lds_wait_all(px);
             read_step(T1{}, py, nxt);
-            slot(next, cur, px, ux, uy);
+            __builtin_amdgcn_sched_barrier(0);
+            transform(next, px, ux);
+            multiply(cur, N2{}, NM{}, uy);
+            __builtin_amdgcn_sched_barrier(0);
             buf = nxt;
         };
         if (S_hi > 0) {
