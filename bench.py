@@ -57,8 +57,8 @@ def workload_shape(name: str):
 def algorithmic_bytes_gemm(s) -> int:
     """Bytes one GEMM launch must move: codes and scales of the activations, the
     packed weights with their scales, and the bf16 output."""
-    per_tok = s.r + (s.K - s.r) // 2 + 8
-    return s.M * per_tok + s.N * (s.r + (s.K - s.r) // 2 + 4) + 2 * s.M * s.N
+    per_tok = s.r + (s.K - s.r) // 2 + 12
+    return s.M * per_tok + s.N * (s.r + (s.K - s.r) // 2 + 8) + 2 * s.M * s.N
 
 
 def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 0):
@@ -135,9 +135,10 @@ def main() -> None:
                 s.K, 0, st)
     xq = xh if s.hadamard else xd
     qa_args = (xq.data_ptr(), s.K, s.M, s.K, s.r, ptr(act.q_hi, hi), ptr(act.q_lo, lo),
-               ptr(act.s_hi, hi), ptr(act.s_lo, lo), st)
+               ptr(act.s_hi, hi), ptr(act.s_lo, lo), ptr(act.lo_sum, lo), st)
     gemm_args = [(ptr(act.q_hi, hi), ptr(act.q_lo, lo), ptr(act.s_hi, hi), ptr(act.s_lo, lo),
-                  s.M, p.data_ptr(), s.N, s.K, s.r, y.data_ptr(), s.N, None, None, st)
+                  ptr(act.lo_sum, lo), s.M, p.data_ptr(), s.N, s.K, s.r, y.data_ptr(), s.N, None,
+                  None, st)
                  for p in packed]
 
     def step(i: int, events=None):

@@ -56,11 +56,13 @@ const char* resq_status_string(int status);
 /*
  * Bytes per token row of the two activation code arrays written by
  * resq_quantize_act and read by resq_gemm_mixed.  High codes are int8, one per
- * byte, the row padded with zero codes to a multiple of 128 codes; low codes
- * are two's-complement nibbles, two per byte (column r + 2j in bits 0..3 and
- * column r + 2j + 1 in bits 4..7 of byte j), the row padded with zero codes to
- * a multiple of 256 codes.  Zero codes add nothing to Eq. 4's sums.  Both
- * return 0 for an empty group and -1 for an invalid (K, r).
+ * byte, the row padded with zero codes to a multiple of 128 codes.  Low codes
+ * are nibbles, two per byte: column r + 2j in bits 0..3 of byte j as code + 8
+ * (offset binary, 1..15) and column r + 2j + 1 in bits 4..7 in two's
+ * complement, so that each of the two can be widened for the int8 matrix cores
+ * with a single AND; the row is padded with zero codes (bytes 0x08) to a
+ * multiple of 256 codes.  Zero codes add nothing to Eq. 4's sums.  Both return
+ * 0 for an empty group and -1 for an invalid (K, r).
  */
 int64_t resq_act_hi_ld(int64_t K, int64_t r);
 int64_t resq_act_lo_ld(int64_t K, int64_t r);
@@ -71,7 +73,7 @@ int64_t resq_act_lo_ld(int64_t K, int64_t r);
  * library (tiled for the matrix cores; read it back with resq_unpack_weights):
  * N is padded to a multiple of 256 rows, the high group to a multiple of 128
  * and the low group to a multiple of 256 codes, all with zero codes, followed
- * by two fp16 scale vectors.
+ * by two fp16 scale vectors and one int32 correction per channel.
  */
 size_t resq_packed_weight_bytes(int64_t N, int64_t K, int64_t r);
 
@@ -91,15 +93,20 @@ int64_t resq_hadamard_block(int64_t width);
  * the quantizer of Section 3 Eq. 1, per token as in Section 5.1).
  *   x      bf16 [M, ldx], ldx >= K                      (read)
  *   q_hi   int8  [M, resq_act_hi_ld(K, r)]              (written, padding zeroed)
- *   q_lo   uint8 [M, resq_act_lo_ld(K, r)]              (written, padding zeroed)
+ *   q_lo   uint8 [M, resq_act_lo_ld(K, r)]              (written, padding = zero codes)
  *   s_hi, s_lo   fp32 [M] scales of the two groups      (written)
+ *   lo_sum int32 [M]: per token, the sum of the low codes of the odd columns
+ *          r + 1, r + 3, ...                            (written)
+ *          resq_gemm_mixed needs it to undo the offset of the nibbles that are
+ *          stored as code + 8 (see resq_act_lo_ld)
  * One read of x; the absmax, the division, the rounding and the packing are
  * fused.  Alignment: none required; x 16-byte aligned with ldx, K and r
  * multiples of 8 selects the vectorized path.  q_hi and q_lo must be 16-byte
  * aligned.  Limits: K <= 2^20.
  */
 int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
-                      int8_t* q_hi, uint8_t* q_lo, float* s_hi, float* s_lo, void* stream);
+                      int8_t* q_hi, uint8_t* q_lo, float* s_hi, float* s_lo, int32_t* lo_sum,
+                      void* stream);
 
 /*
  * Offline weight quantization and packing (Section 4.1 Eq. 3; per output
@@ -128,9 +135,10 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
  *   A_lo[m, n] = sum_{k >= r} q_lo[m, k] * w_lo[n, k]       (int4 x int4 -> int32)
  *   y[m, n]    = bf16( A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n] )
  * Both sums run on the int8 matrix cores (nibbles are widened in registers)
- * inside one kernel; y is written once.  The integer sums are exact as long as
- * 127^2 * r and 49 * (K - r) * 256 stay below 2^31 (K - r <= 171196).
- *   q_hi, q_lo, s_hi, s_lo   as written by resq_quantize_act for the same K, r
+ * inside one kernel; y is written once.  The integer sums are exact: with
+ * K <= 2^20 neither 127^2 * r nor the widened low sum 1680 * (K - r) can reach
+ * 2^31.
+ *   q_hi, q_lo, s_hi, s_lo, lo_sum   as written by resq_quantize_act for the same K, r
  *   packed                   as written by resq_pack_weights for the same N, K, r
  *   y        bf16 [M, ldy], ldy >= N                         (written)
  *   dbg_acc_hi, dbg_acc_lo   int32 [M, N] each, or null: when given, the two
@@ -140,7 +148,8 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
  * Alignment: q_hi, q_lo 16 bytes; packed 256 bytes; y 2 bytes.
  */
 int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
-                    const float* s_lo, int64_t M, const void* packed, int64_t N, int64_t K,
+                    const float* s_lo, const int32_t* lo_sum, int64_t M, const void* packed,
+                    int64_t N, int64_t K,
                     int64_t r, void* y, int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo,
                     void* stream);
 

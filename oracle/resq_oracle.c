@@ -23,7 +23,9 @@
  *   - weight scales are stored in fp16, rounded toward +inf from the fp32
  *     quotient (so that no code can exceed the clip) and clamped to the fp16
  *     normal range; weight codes are computed with the stored value
- *   - 4-bit codes are packed two per byte, even element in bits 0..3
+ *   - 4-bit codes are packed two per byte: the even element in bits 0..3 as
+ *     code + 8 (offset binary, 1..15), the odd element in bits 4..7 in two's
+ *     complement; a padding byte holds two zero codes, i.e. 0x08
  *
  * Pins: every function here is checked in tests/test_oracle_pins.py against
  * invariants, closed forms, library routines and exact brute force; none is
@@ -185,21 +187,33 @@ void oracle_quantize_weights(const uint16_t* w, int64_t ldw, int64_t N, int64_t 
 }
 
 /*
- * Pack 4-bit codes two per byte: element 2j in bits 0..3 and element 2j+1 in
- * bits 4..7 of byte j, two's complement.  Each output row has ld_out bytes;
- * bytes past cols/2 are zero (zero codes add nothing to a dot product).
- * cols must be even.
+ * Pack 4-bit codes two per byte: element 2j in bits 0..3 of byte j as code + 8
+ * (offset binary), element 2j+1 in bits 4..7 in two's complement.  Each output
+ * row has ld_out bytes; bytes past cols/2 hold two zero codes (0x08), which add
+ * nothing to a dot product.  cols must be even.
  */
 void oracle_pack_nibbles(const int8_t* codes, int64_t rows, int64_t cols, int64_t ld_out,
                          uint8_t* out) {
     for (int64_t i = 0; i < rows; ++i) {
         uint8_t* o = out + i * ld_out;
-        memset(o, 0, (size_t)ld_out);
+        memset(o, 0x08, (size_t)ld_out);
         for (int64_t j = 0; j < cols / 2; ++j) {
-            uint8_t a = (uint8_t)codes[i * cols + 2 * j] & 0xFu;
+            uint8_t a = (uint8_t)(codes[i * cols + 2 * j] + 8) & 0xFu;
             uint8_t b = (uint8_t)codes[i * cols + 2 * j + 1] & 0xFu;
             o[j] = (uint8_t)(a | (b << 4));
         }
+    }
+}
+
+/*
+ * Per row, the sum of the codes in odd positions (1, 3, 5, ...).  The GPU
+ * quantizer emits this number per token next to the packed low codes.
+ */
+void oracle_odd_code_sums(const int8_t* codes, int64_t rows, int64_t cols, int32_t* out) {
+    for (int64_t i = 0; i < rows; ++i) {
+        int32_t s = 0;
+        for (int64_t k = 1; k < cols; k += 2) s += codes[i * cols + k];
+        out[i] = s;
     }
 }
 

@@ -46,12 +46,14 @@ def _load():
         lib.oracle_quantize_act.argtypes = [p, i64, i64, i64, i64, p, p, p, p]
         lib.oracle_quantize_weights.argtypes = [p, i64, i64, i64, i64, p, p, p, p]
         lib.oracle_pack_nibbles.argtypes = [p, i64, i64, i64, p]
+        lib.oracle_odd_code_sums.argtypes = [p, i64, i64, p]
         lib.oracle_gemm_i64.argtypes = [p, i64, p, i64, i64, i64, i64, p]
         lib.oracle_gemm_i64.restype = i64
         lib.oracle_dequant.argtypes = [p, p, p, p, p, p, i64, i64, p]
         lib.oracle_hadamard.argtypes = [p, p, i64, i64, i64, i64, i64, i64]
         for f in ("oracle_round_bf16", "oracle_quantize_act", "oracle_quantize_weights",
-                  "oracle_pack_nibbles", "oracle_dequant", "oracle_hadamard"):
+                  "oracle_pack_nibbles", "oracle_odd_code_sums", "oracle_dequant",
+                  "oracle_hadamard"):
             getattr(lib, f).restype = None
         _lib = lib
     return _lib
@@ -107,7 +109,8 @@ def quantize_weights(w_bits: np.ndarray, r: int):
 
 
 def pack_nibbles(codes: np.ndarray, ld_out: Optional[int] = None) -> np.ndarray:
-    """4-bit codes, one per byte, -> two per byte (even element in bits 0..3)."""
+    """4-bit codes, one per byte, -> two per byte: even element in bits 0..3 as
+    code + 8, odd element in bits 4..7 in two's complement; padding bytes 0x08."""
     codes = _c(codes, np.int8)
     rows, cols = codes.shape
     assert cols % 2 == 0
@@ -115,6 +118,15 @@ def pack_nibbles(codes: np.ndarray, ld_out: Optional[int] = None) -> np.ndarray:
     assert ld >= cols // 2
     out = np.empty((rows, ld), np.uint8)
     _load().oracle_pack_nibbles(_ptr(codes), rows, cols, ld, _ptr(out))
+    return out
+
+
+def odd_code_sums(codes: np.ndarray) -> np.ndarray:
+    """Per row, the sum of the codes in odd positions, int32."""
+    codes = _c(codes, np.int8)
+    rows, cols = codes.shape
+    out = np.zeros(rows, np.int32)
+    _load().oracle_odd_code_sums(_ptr(codes), rows, cols, _ptr(out))
     return out
 
 

@@ -27,10 +27,10 @@ SYMBOLS = {
     "resq_act_lo_ld": (_i64, [_i64, _i64]),
     "resq_packed_weight_bytes": (_sz, [_i64, _i64, _i64]),
     "resq_hadamard_block": (_i64, [_i64]),
-    "resq_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
+    "resq_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
     "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
-    "resq_gemm_mixed": (C.c_int, [_p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
+    "resq_gemm_mixed": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
     "resq_online_hadamard": (C.c_int, [_p, _p, _i64, _i64, _i64, _i64, _i64, _i64, _p]),
 }
 
@@ -111,6 +111,7 @@ class ActCodes:
         self.q_lo = torch.empty((M, self.ld_lo), dtype=torch.uint8, device=device)
         self.s_hi = torch.empty(M, dtype=torch.float32, device=device)
         self.s_lo = torch.empty(M, dtype=torch.float32, device=device)
+        self.lo_sum = torch.empty(M, dtype=torch.int32, device=device)
 
 
 def alloc_packed(N: int, K: int, r: int, device="cuda") -> torch.Tensor:
@@ -133,7 +134,8 @@ def resq_quantize_act(x: torch.Tensor, r: int, out: Optional[ActCodes] = None,
                                  out.q_hi.data_ptr() if r > 0 else None,
                                  out.q_lo.data_ptr() if K - r > 0 else None,
                                  out.s_hi.data_ptr() if r > 0 else None,
-                                 out.s_lo.data_ptr() if K - r > 0 else None, _stream(stream))
+                                 out.s_lo.data_ptr() if K - r > 0 else None,
+                                 out.lo_sum.data_ptr() if K - r > 0 else None, _stream(stream))
     _check(st, "resq_quantize_act")
     return out
 
@@ -178,7 +180,8 @@ def resq_gemm_mixed(act: ActCodes, packed: torch.Tensor, N: int, y: Optional[tor
     st = lib().resq_gemm_mixed(act.q_hi.data_ptr() if r > 0 else None,
                                act.q_lo.data_ptr() if K - r > 0 else None,
                                act.s_hi.data_ptr() if r > 0 else None,
-                               act.s_lo.data_ptr() if K - r > 0 else None, M,
+                               act.s_lo.data_ptr() if K - r > 0 else None,
+                               act.lo_sum.data_ptr() if K - r > 0 else None, M,
                                _dev(packed, torch.uint8, "packed"), N, K, r,
                                _dev(y, torch.bfloat16, "y"), y.stride(0),
                                _dev(dbg_acc_hi, torch.int32, "dbg_acc_hi"),

@@ -14,7 +14,7 @@ using namespace resq;
 namespace {
 
 constexpr int64_t kMaxK = 1 << 20;
-constexpr int64_t kMaxLoWidth = 171196;  // 256 * 49 * (K - r) < 2^31
+constexpr int64_t kMaxLoWidth = 1 << 20;  // 1680 * (K - r) < 2^31 (widened low sums)
 constexpr int64_t kMaxHiWidth = 133143;  // 127^2 * r < 2^31
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -66,13 +66,13 @@ int64_t resq_hadamard_block(int64_t width) {
 }
 
 int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r, int8_t* q_hi,
-                      uint8_t* q_lo, float* s_hi, float* s_lo, void* stream) {
+                      uint8_t* q_lo, float* s_hi, float* s_lo, int32_t* lo_sum, void* stream) {
     if (!shape_ok(M, K, r) || ldx < K) return RESQ_ERR_SHAPE;
     if (!x) return RESQ_ERR_NULL;
     if (r > 0 && (!q_hi || !s_hi)) return RESQ_ERR_NULL;
-    if (K - r > 0 && (!q_lo || !s_lo)) return RESQ_ERR_NULL;
+    if (K - r > 0 && (!q_lo || !s_lo || !lo_sum)) return RESQ_ERR_NULL;
     if (!aligned(x, 2) || !aligned(q_hi, 16) || !aligned(q_lo, 16) || !aligned(s_hi, 4) ||
-        !aligned(s_lo, 4))
+        !aligned(s_lo, 4) || !aligned(lo_sum, 4))
         return RESQ_ERR_ALIGN;
     const int64_t ld_hi = round_up(r, kHiPad), ld_lo = round_up(K - r, kLoPad) / 2;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -81,7 +81,7 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
     const bool vec = aligned(x, 16) && ldx % 8 == 0 && K % 8 == 0 && r % 8 == 0 && K <= 16384;
 #define RESQ_LAUNCH_QA(ITERS)                                                                   \
     hipLaunchKernelGGL(quantize_act_vec_kernel<ITERS>, grid, block, 0, st, xp, ldx, (int)K,     \
-                       (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo)
+                       (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum)
     if (vec) {
         if (K <= 2048) RESQ_LAUNCH_QA(1);
         else if (K <= 4096) RESQ_LAUNCH_QA(2);
@@ -89,7 +89,7 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
         else RESQ_LAUNCH_QA(8);
     } else {
         hipLaunchKernelGGL(quantize_act_generic_kernel, grid, block, 0, st, xp, ldx, (int)K,
-                           (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo);
+                           (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum);
     }
 #undef RESQ_LAUNCH_QA
     return launch_status();
@@ -124,13 +124,15 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
 }
 
 int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, const float* s_lo,
-                    int64_t M, const void* packed, int64_t N, int64_t K, int64_t r, void* y,
+                    const int32_t* lo_sum, int64_t M, const void* packed, int64_t N, int64_t K,
+                    int64_t r, void* y,
                     int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo, void* stream) {
     if (!shape_ok(N, K, r) || M < 1 || M > 0x7FFFFFFF || ldy < N) return RESQ_ERR_SHAPE;
     if (K - r > kMaxLoWidth || r > kMaxHiWidth) return RESQ_ERR_SHAPE;
     if (!packed || !y) return RESQ_ERR_NULL;
     if (r > 0 && (!q_hi || !s_hi)) return RESQ_ERR_NULL;
-    if (K - r > 0 && (!q_lo || !s_lo)) return RESQ_ERR_NULL;
+    if (K - r > 0 && (!q_lo || !s_lo || !lo_sum)) return RESQ_ERR_NULL;
+    if (!aligned(lo_sum, 4)) return RESQ_ERR_ALIGN;
     if (!aligned(q_hi, 16) || !aligned(q_lo, 16) || !aligned(packed, 256) || !aligned(y, 2) ||
         !aligned(s_hi, 4) || !aligned(s_lo, 4) || !aligned(dbg_acc_hi, 4) ||
         !aligned(dbg_acc_lo, 4))
@@ -144,6 +146,7 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
     a.ld_lo = a.L.kl_pad / 2;
     a.s_hi = s_hi;
     a.s_lo = s_lo;
+    a.lo_sum = lo_sum;
     a.packed = static_cast<const uint8_t*>(packed);
     a.M = M;
     a.y = static_cast<uint16_t*>(y);

@@ -29,11 +29,17 @@
 // high step), so that the matrix instructions of step k never wait for the
 // vector ALU work of their own operands.
 //
-// The low group.  A lane's 16 packed bytes hold 32 codes; (p << 4) & 0xF0F0F0F0
-// puts the even codes, p & 0xF0F0F0F0 the odd codes, into the high nibble of
-// each byte, i.e. 16 * code as int8, for activations and weights alike, and the
-// two results feed two matrix-core instructions.  The accumulator then holds
-// 256 * A_lo; an arithmetic shift by 8 recovers A_lo exactly.
+// The low group.  A lane's 16 packed bytes hold 32 codes, and each nibble is
+// widened to an int8 operand with one AND (the vector ALU has room for about
+// four instructions per matrix instruction, so every one counts).  In an
+// activation byte the low nibble is c_even + 8 and the high nibble c_odd; in a
+// weight byte the high nibble is w_even and the low nibble w_odd + 8.  Then
+//   (pa & 0x0F) * (pw & 0xF0) = (c_even + 8) * 16 w_even
+//   (pa & 0xF0) * (pw & 0x0F) = 16 c_odd * (w_odd + 8)
+// feed two matrix-core instructions, and the accumulator ends as
+//   16 * A_lo + 128 * (sum_even w[n] + sum_odd c[m]);
+// the two sums are known per channel (packed with the weights) and per token
+// (written by the quantizer), so A_lo is recovered exactly.
 //
 // Two scale pairs, one output write.  After the last high step the int32 tile is
 // scaled into an fp32 tile that stays in (accumulation) registers, the int32
@@ -70,6 +76,7 @@ struct GemmArgs {
     int64_t ld_hi, ld_lo;
     const float* s_hi;
     const float* s_lo;
+    const int32_t* lo_sum;  // per token: sum of the low codes in odd columns
     const uint8_t* packed;
     WeightLayout L;
     int64_t M;
@@ -85,10 +92,12 @@ __device__ __forceinline__ float fp16_bits_to_f32(uint32_t h) {
     return __uint_as_float((((h >> 10) & 0x1Fu) + 112u) << 23 | (h & 0x3FFu) << 13);
 }
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+// two fp32 -> two bf16 (round to nearest even) in one dword, low half first
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const v2bf r = __builtin_convertvector((v2f){lo, hi}, v2bf);
+    return *reinterpret_cast<const uint32_t*>(&r);
 }
 
 // Wait until at most N of this wave's vector-memory loads are outstanding, then
@@ -260,13 +269,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         if constexpr (decltype(is_lo)::value) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                u.ae[i] = (p.fa[i] << 4) & (int)0xF0F0F0F0;
-                u.ao[i] = p.fa[i] & (int)0xF0F0F0F0;
+                u.ae[i] = p.fa[i] & (int)0x0F0F0F0F;  // even columns: code + 8
+                u.ao[i] = p.fa[i] & (int)0xF0F0F0F0;  // odd columns: 16 * code
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                u.be[j] = (p.fb[j] << 4) & (int)0xF0F0F0F0;
-                u.bo[j] = p.fb[j] & (int)0xF0F0F0F0;
+                u.be[j] = p.fb[j] & (int)0xF0F0F0F0;  // even columns: 16 * code
+                u.bo[j] = p.fb[j] & (int)0x0F0F0F0F;  // odd columns: code + 8
             }
         } else {
 #pragma unroll
@@ -295,13 +304,23 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
     const uint16_t* sw_lo = sw_hi + a.L.n_pad;
 
-    // part += (acc >> shift) * s_tok[m] * s_ch[n]; acc = 0
-    auto fold = [&](const float* s_tok, const uint16_t* s_ch, int32_t* dbg, int shift) __attribute__((always_inline)) {
+    // part += A * s_tok[m] * s_ch[n]; acc = 0, where A is the group's integer sum:
+    // the accumulator itself for the high group; for the low group
+    // (acc - 128 * (even_sum[n] + lo_sum[m])) / 16, an exact division whose 1/16
+    // is folded into the scale outside the debug kernel (same fp32 product).
+    const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
+    auto fold = [&](auto is_lo, const float* s_tok, const uint16_t* s_ch, int32_t* dbg) __attribute__((always_inline)) {
+        constexpr bool LOW = decltype(is_lo)::value;
         float st[2];
+        int ca[2] = {0, 0};
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int64_t m = tok0 + 32 * i;
             st[i] = m < a.M ? s_tok[m] : 0.0f;
+            if constexpr (LOW) {
+                ca[i] = m < a.M ? a.lo_sum[m] * 128 : 0;
+                if constexpr (!DBG) st[i] *= 0.0625f;
+            }
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -311,13 +330,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                 const uint2 sc = *reinterpret_cast<const uint2*>(s_ch + n);
                 const float sn[4] = {fp16_bits_to_f32(sc.x & 0xFFFFu), fp16_bits_to_f32(sc.x >> 16),
                                      fp16_bits_to_f32(sc.y & 0xFFFFu), fp16_bits_to_f32(sc.y >> 16)};
+                int cw[4] = {0, 0, 0, 0};
+                if constexpr (LOW) {
+                    const int4 e = *reinterpret_cast<const int4*>(even_sum + n);
+                    cw[0] = e.x * 128; cw[1] = e.y * 128; cw[2] = e.z * 128; cw[3] = e.w * 128;
+                }
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     const int64_t m = tok0 + 32 * i;
 #pragma unroll
                     for (int vr = 0; vr < 4; ++vr) {
                         const int v = vq * 4 + vr;
-                        const int iv = acc[j][i][v] >> shift;
+                        int iv = acc[j][i][v];
+                        if constexpr (LOW) {
+                            iv -= cw[vr] + ca[i];
+                            if constexpr (DBG) iv >>= 4;
+                        }
                         part[j][i][v] += (float)iv * (st[i] * sn[vr]);
                         if constexpr (DBG) {
                             if (dbg && m < a.M && n + vr < a.L.N) dbg[m * a.L.N + n + vr] = iv;
@@ -329,10 +357,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         }
         // keep the fp32 tile in accumulation registers while the low steps need
         // the ordinary ones for operands
+        if constexpr (!LOW) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(part[j][i]));
+                for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(part[j][i]));
+        }
     };
 
     // ---- main loop ---------------------------------------------------------------
@@ -359,6 +389,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         // waits, the barrier and the issue of reads and loads run in their shadow.
         using N0 = std::integral_constant<int, 0>;
         using N2 = std::integral_constant<int, 2>;
+        // Scheduling pattern of the second part of a slot: the vector ALU can
+        // issue about four instructions in the shadow of one matrix instruction,
+        // and only if they sit between two matrix instructions, so the widening
+        // of the next step's operands is spread evenly, four per matrix
+        // instruction, instead of being bunched at the front.
+        auto spread = [&](auto is_lo) __attribute__((always_inline)) {
+            constexpr int PAIRS = decltype(is_lo)::value ? 12 : 6;
+#pragma unroll
+            for (int q = 0; q < PAIRS; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // four vector ALU instructions
+            }
+        };
         auto stage = [&](auto cur, auto next, int sg) __attribute__((always_inline)) {
             using NM = std::integral_constant<int, decltype(cur)::value ? 16 : 8>;
             const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
@@ -377,6 +420,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             if (sg + kPrefetch < S) issue_stage(sg + kPrefetch, prv);
             transform(cur, py, uy);
             multiply(cur, N2{}, NM{}, ux);
+            spread(cur);
             __builtin_amdgcn_sched_barrier(0);
             multiply(cur, N0{}, N2{}, uy);
             __builtin_amdgcn_sched_barrier(0);
@@ -385,16 +429,17 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             __builtin_amdgcn_sched_barrier(0);
             transform(next, px, ux);
             multiply(cur, N2{}, NM{}, uy);
+            spread(cur);
             __builtin_amdgcn_sched_barrier(0);
             buf = nxt;
         };
         if (S_hi > 0) {
             for (int sg = 0; sg + 1 < S_hi; ++sg) stage(HI{}, HI{}, sg);
             stage(HI{}, LO{}, S_hi - 1);
-            fold(a.s_hi, sw_hi, a.dbg_hi, 0);
+            fold(HI{}, a.s_hi, sw_hi, a.dbg_hi);
         }
         for (int sg = S_hi; sg < S; ++sg) stage(LO{}, LO{}, sg);
-        if (a.stages_lo > 0) fold(a.s_lo, sw_lo, a.dbg_lo, 8);
+        if (a.stages_lo > 0) fold(LO{}, a.s_lo, sw_lo, a.dbg_lo);
     }
 
     // ---- write y once --------------------------------------------------------
@@ -411,10 +456,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
-                    const uint32_t lo = f32_to_bf16_rne(part[j][i][vq * 4 + 0]) |
-                                        (f32_to_bf16_rne(part[j][i][vq * 4 + 1]) << 16);
-                    const uint32_t hi = f32_to_bf16_rne(part[j][i][vq * 4 + 2]) |
-                                        (f32_to_bf16_rne(part[j][i][vq * 4 + 3]) << 16);
+                    const uint32_t lo = pack_bf16(part[j][i][vq * 4 + 0], part[j][i][vq * 4 + 1]);
+                    const uint32_t hi = pack_bf16(part[j][i][vq * 4 + 2], part[j][i][vq * 4 + 3]);
                     const int row = 32 * i + (lane & 31);
                     const int col = 32 * j + 8 * vq + 4 * (lane >> 5);
                     *reinterpret_cast<uint2*>(mine + row * kOutRowBytes + col * 2) = make_uint2(lo, hi);
@@ -441,7 +484,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
 #pragma unroll
                     for (int vr = 0; vr < 4; ++vr)
                         if (n + vr < a.L.N)
-                            a.y[m * a.ldy + n + vr] = (uint16_t)f32_to_bf16_rne(part[j][i][vq * 4 + vr]);
+                            a.y[m * a.ldy + n + vr] = (uint16_t)pack_bf16(part[j][i][vq * 4 + vr], 0.f);
                 }
         }
     }

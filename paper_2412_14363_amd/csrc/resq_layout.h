@@ -5,8 +5,10 @@
 // plain row-major per token:
 //   q_hi  int8  [M, kh_pad]      kh_pad = round_up(r, 128)
 //   q_lo  uint8 [M, kl_pad / 2]  kl_pad = round_up(K - r, 256), two nibbles per
-//                                byte, even column in bits 0..3
-// Padding codes are zero.
+//                                byte: bits 0..3 = code of the even column + 8,
+//                                bits 4..7 = code of the odd column (two's
+//                                complement)
+// Padding codes are zero (a padding byte of q_lo is 0x08).
 //
 // Packed weights use the same two row formats, cut into blocks that a GEMM
 // stage consumes whole: a "block" is 16 output channels x 64 bytes of one
@@ -15,8 +17,13 @@
 // 16x16x64 matrix-core instruction, or half of a 32x32x32 one.  The buffer is
 //   for each group of 16 output channels (n_pad / 16 of them):
 //       kh_pad / 64 high blocks, then kl_pad / 128 low blocks
-//   fp16 sw_hi[n_pad], fp16 sw_lo[n_pad]
+//   fp16 sw_hi[n_pad], fp16 sw_lo[n_pad], int32 even_sum[n_pad]
 // with n_pad = round_up(N, 256); padding rows hold zero codes and scale 1.
+// A weight byte of the low group pairs the other way round than an activation
+// byte: bits 4..7 = code of the even column (two's complement), bits 0..3 =
+// code of the odd column + 8, so that every product of the widened nibbles
+// pairs one offset operand with one signed operand (see resq_gemm.hip.h);
+// even_sum[n] is the sum of channel n's low codes in even columns.
 // So channel n, byte b of its padded high row lives at
 //   (n / 16) * group_bytes + (b / 64) * 1024 + (n % 16) * 64 + b % 64
 // and byte b of its packed low row at the same place past the high blocks.
@@ -42,7 +49,7 @@ struct WeightLayout {
     int64_t kh_pad, kl_pad, n_pad;
     int64_t hi_blocks, lo_blocks;  // per group of 16 channels
     int64_t group_bytes;           // bytes of one group of 16 channels
-    int64_t scale_off;             // byte offset of sw_hi; sw_lo follows at + 2 * n_pad
+    int64_t scale_off;             // byte offset of sw_hi; sw_lo at + 2 n_pad, even_sum at + 4 n_pad
     int64_t total_bytes;
 };
 
@@ -56,7 +63,7 @@ __host__ __device__ inline WeightLayout make_weight_layout(int64_t N, int64_t K,
     L.lo_blocks = L.kl_pad / (2 * kRowBytes);
     L.group_bytes = (L.hi_blocks + L.lo_blocks) * kBlockBytes;
     L.scale_off = (L.n_pad / kRowsPerBlock) * L.group_bytes;
-    L.total_bytes = L.scale_off + 4 * L.n_pad;
+    L.total_bytes = L.scale_off + 8 * L.n_pad;
     return L;
 }
 

@@ -42,6 +42,15 @@ __device__ __forceinline__ void block_max2(float& a, float& b, float* red /* [8]
     b = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
 }
 
+// sum over the 256 threads of a block
+__device__ __forceinline__ int block_sum(int v, int* red /* [4] in LDS */) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
 __device__ __forceinline__ float group_scale(float amax, int qmax) {
     return amax == 0.0f ? 1.0f : amax / (float)qmax;
 }
@@ -66,8 +75,9 @@ template <int ITERS>
 __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
     int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
-    float* __restrict__ s_lo) {
+    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum) {
     __shared__ float red[8];
+    __shared__ int red_sum[4];
     const int64_t m = blockIdx.x;
     const int t = threadIdx.x;
     const int nunits = K >> 3;
@@ -96,6 +106,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 
     int8_t* qh = q_hi + m * ld_hi;
     uint8_t* ql = q_lo + m * ld_lo;
+    int odd_sum = 0;  // low codes of odd columns
 #pragma unroll
     for (int i = 0; i < ITERS; ++i) {
         const int u = t + i * kQuantThreads;
@@ -116,7 +127,8 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu);
                     const int c = quant_code(bf16_bits_to_f32(bits), sl, kQmaxLo);
-                    out |= (uint32_t)(c & 0xF) << (4 * j);
+                    if (j & 1) odd_sum += c;
+                    out |= (uint32_t)(((j & 1) ? c : c + 8) & 0xF) << (4 * j);
                 }
                 *reinterpret_cast<uint32_t*>(ql + (int64_t)(u - hi_units) * 4) = out;
             }
@@ -126,7 +138,9 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
     for (int64_t b = (int64_t)r + 8 * t; b < ld_hi; b += 8 * kQuantThreads)
         *reinterpret_cast<uint2*>(qh + b) = make_uint2(0u, 0u);
     for (int64_t b = (int64_t)(K - r) / 2 + 4 * t; b < ld_lo; b += 4 * kQuantThreads)
-        *reinterpret_cast<uint32_t*>(ql + b) = 0u;
+        *reinterpret_cast<uint32_t*>(ql + b) = 0x08080808u;
+    odd_sum = block_sum(odd_sum, red_sum);
+    if (t == 0 && K - r > 0) lo_sum[m] = odd_sum;
 }
 
 // ---------------------------------------------------------------------------
@@ -136,8 +150,9 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 __global__ __launch_bounds__(kQuantThreads) void quantize_act_generic_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
     int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
-    float* __restrict__ s_lo) {
+    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum) {
     __shared__ float red[8];
+    __shared__ int red_sum[4];
     const int64_t m = blockIdx.x;
     const int t = threadIdx.x;
     const uint16_t* row = x + m * ldx;
@@ -159,15 +174,19 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_generic_kernel(
     for (int64_t k = t; k < ld_hi; k += kQuantThreads)
         qh[k] = k < r ? (int8_t)quant_code(bf16_bits_to_f32(row[k]), sh, kQmaxHi) : (int8_t)0;
     const int pairs = (K - r) / 2;
+    int odd_sum = 0;
     for (int64_t j = t; j < ld_lo; j += kQuantThreads) {
-        uint32_t byte = 0u;
+        uint32_t byte = 0x08u;
         if (j < pairs) {
             const int c0 = quant_code(bf16_bits_to_f32(row[r + 2 * j]), sl, kQmaxLo);
             const int c1 = quant_code(bf16_bits_to_f32(row[r + 2 * j + 1]), sl, kQmaxLo);
-            byte = (uint32_t)(c0 & 0xF) | ((uint32_t)(c1 & 0xF) << 4);
+            odd_sum += c1;
+            byte = (uint32_t)((c0 + 8) & 0xF) | ((uint32_t)(c1 & 0xF) << 4);
         }
         ql[j] = (uint8_t)byte;
     }
+    odd_sum = block_sum(odd_sum, red_sum);
+    if (t == 0 && K - r > 0) lo_sum[m] = odd_sum;
 }
 
 // ---------------------------------------------------------------------------
@@ -189,6 +208,7 @@ __device__ __forceinline__ float fp16_normal_to_f32(uint32_t h) {
 __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
     const uint16_t* __restrict__ w, int64_t ldw, WeightLayout L, uint8_t* __restrict__ packed) {
     __shared__ float red[8];
+    __shared__ int red_sum[4];
     const int64_t n = blockIdx.x;  // 0 .. n_pad - 1
     const int t = threadIdx.x;
     const int K = (int)L.K, r = (int)L.r;
@@ -229,22 +249,31 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
         *reinterpret_cast<uint4*>(packed + hi_byte_offset(L, n, (int64_t)u * 16)) =
             make_uint4(out[0], out[1], out[2], out[3]);
     }
-    // low group: units of 32 codes = 16 bytes
+    // low group: units of 32 codes = 16 bytes; byte = (even code) << 4 | (odd code + 8)
+    int even_sum = 0;
     for (int u = t; u < (int)(L.kl_pad / 32); u += kQuantThreads) {
-        uint32_t out[4] = {0u, 0u, 0u, 0u};
+        uint32_t out[4] = {0x08080808u, 0x08080808u, 0x08080808u, 0x08080808u};
         if (live) {
 #pragma unroll
             for (int j = 0; j < 32; ++j) {
                 const int k = r + u * 32 + j;
                 if (k < K) {
                     const int c = quant_code(bf16_bits_to_f32(row[k]), sl, kQmaxLo);
-                    out[j >> 3] |= (uint32_t)(c & 0xF) << (4 * (j & 7));
+                    if (j & 1) {
+                        out[j >> 3] = (out[j >> 3] & ~(0xFu << (4 * (j & 7) - 4))) |
+                                      ((uint32_t)((c + 8) & 0xF) << (4 * (j & 7) - 4));
+                    } else {
+                        even_sum += c;
+                        out[j >> 3] |= (uint32_t)(c & 0xF) << (4 * (j & 7) + 4);
+                    }
                 }
             }
         }
         *reinterpret_cast<uint4*>(packed + lo_byte_offset(L, n, (int64_t)u * 16)) =
             make_uint4(out[0], out[1], out[2], out[3]);
     }
+    even_sum = block_sum(even_sum, red_sum);
+    if (t == 0) reinterpret_cast<int32_t*>(packed + L.scale_off + 4 * L.n_pad)[n] = even_sum;
 }
 
 __global__ __launch_bounds__(kQuantThreads) void unpack_weights_kernel(
@@ -262,8 +291,9 @@ __global__ __launch_bounds__(kQuantThreads) void unpack_weights_kernel(
         w_hi[n * r + k] = (int8_t)packed[hi_byte_offset(L, n, k)];
     for (int k = t; k < kl; k += kQuantThreads) {
         const uint32_t byte = packed[lo_byte_offset(L, n, k / 2)];
-        const int nib = (k & 1) ? (byte >> 4) : (byte & 0xFu);
-        w_lo[n * (int64_t)kl + k] = (int8_t)((nib ^ 8) - 8);  // sign-extend 4 bits
+        // even column: bits 4..7, two's complement; odd column: bits 0..3, code + 8
+        w_lo[n * (int64_t)kl + k] = (k & 1) ? (int8_t)((int)(byte & 0xFu) - 8)
+                                            : (int8_t)((int)((byte >> 4) ^ 8u) - 8);
     }
 }
 

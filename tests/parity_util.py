@@ -24,6 +24,6 @@ def unpack_nibbles(p: np.ndarray, cols: int) -> np.ndarray:
     lo = (p & 0xF).astype(np.int8)
     hi = (p >> 4).astype(np.int8)
     out = np.empty((p.shape[0], p.shape[1] * 2), np.int8)
-    out[:, 0::2] = np.where(lo > 7, lo - 16, lo)
+    out[:, 0::2] = lo - 8
     out[:, 1::2] = np.where(hi > 7, hi - 16, hi)
     return out[:, :cols]

@@ -35,10 +35,10 @@ def test_layout_queries():
     assert binding.resq_act_hi_ld(4096, 0) == 0 and binding.resq_act_lo_ld(4096, 4096) == 0
     assert binding.resq_act_hi_ld(10, 3) == -1             # K - r odd
     assert binding.resq_act_lo_ld(8, 9) == -1
-    # 8192 x 28672, r = 1024: 4.5 bits per weight plus two fp16 scales per channel
-    assert binding.resq_packed_weight_bytes(28672, 8192, 1024) == 28672 * (1024 + 3584) + 4 * 28672
+    # 8192 x 28672, r = 1024: 4.5 bits per weight plus two fp16 scales and one int32 per channel
+    assert binding.resq_packed_weight_bytes(28672, 8192, 1024) == 28672 * (1024 + 3584) + 8 * 28672
     # N is padded to 256 rows
-    assert binding.resq_packed_weight_bytes(29568, 8192, 1024) == 29696 * (1024 + 3584 + 4)
+    assert binding.resq_packed_weight_bytes(29568, 8192, 1024) == 29696 * (1024 + 3584 + 8)
     assert binding.resq_packed_weight_bytes(0, 8, 0) == 0
     assert binding.resq_hadamard_block(12544) == 256
     assert binding.resq_hadamard_block(14336) == 2048
@@ -58,15 +58,17 @@ P = 0x10000   # a plausible, aligned, never dereferenced address
 
 def test_quantize_act_rejects_bad_arguments():
     f = binding.lib().resq_quantize_act
-    assert f(P, 256, 0, 256, 32, P, P, P, P, None) == 2            # M < 1
-    assert f(P, 256, 4, 256, 257, P, P, P, P, None) == 2           # r > K
-    assert f(P, 256, 4, 256, 33, P, P, P, P, None) == 2            # K - r odd
-    assert f(P, 255, 4, 256, 32, P, P, P, P, None) == 2            # ldx < K
-    assert f(None, 256, 4, 256, 32, P, P, P, P, None) == 1
-    assert f(P, 256, 4, 256, 32, None, P, P, P, None) == 1
-    assert f(P, 256, 4, 256, 32, P, P, P, None, None) == 1
-    assert f(P, 256, 4, 256, 32, P + 8, P, P, P, None) == 3
-    assert f(P + 1, 256, 4, 256, 32, P, P, P, P, None) == 3
+    assert f(P, 256, 0, 256, 32, P, P, P, P, P, None) == 2         # M < 1
+    assert f(P, 256, 4, 256, 257, P, P, P, P, P, None) == 2        # r > K
+    assert f(P, 256, 4, 256, 33, P, P, P, P, P, None) == 2         # K - r odd
+    assert f(P, 255, 4, 256, 32, P, P, P, P, P, None) == 2         # ldx < K
+    assert f(None, 256, 4, 256, 32, P, P, P, P, P, None) == 1
+    assert f(P, 256, 4, 256, 32, None, P, P, P, P, None) == 1
+    assert f(P, 256, 4, 256, 32, P, P, P, None, P, None) == 1
+    assert f(P, 256, 4, 256, 32, P, P, P, P, None, None) == 1      # lo_sum missing
+    assert f(P, 256, 4, 256, 256, P, None, P, None, None, None) != 1   # r = K: low pointers may be null
+    assert f(P, 256, 4, 256, 32, P + 8, P, P, P, P, None) == 3
+    assert f(P + 1, 256, 4, 256, 32, P, P, P, P, P, None) == 3
 
 
 def test_pack_and_gemm_reject_bad_arguments():
@@ -77,11 +79,12 @@ def test_pack_and_gemm_reject_bad_arguments():
     assert L.resq_pack_weights(None, 256, 256, 256, 32, P, need, None) == 1
     assert L.resq_pack_weights(P, 100, 256, 256, 32, P, need, None) == 2
     g = L.resq_gemm_mixed
-    assert g(P, P, P, P, 16, P, 256, 256, 32, P, 255, None, None, None) == 2   # ldy < N
-    assert g(P, P, P, P, 16, None, 256, 256, 32, P, 256, None, None, None) == 1
-    assert g(None, P, P, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 1
-    assert g(P, P + 4, P, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 3
-    assert g(P, P, P, P, 16, P, 256, 256, 31, P, 256, None, None, None) == 2
+    assert g(P, P, P, P, P, 16, P, 256, 256, 32, P, 255, None, None, None) == 2   # ldy < N
+    assert g(P, P, P, P, P, 16, None, 256, 256, 32, P, 256, None, None, None) == 1
+    assert g(None, P, P, P, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 1
+    assert g(P, P, P, P, None, 16, P, 256, 256, 32, P, 256, None, None, None) == 1
+    assert g(P, P + 4, P, P, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 3
+    assert g(P, P, P, P, P, 16, P, 256, 256, 31, P, 256, None, None, None) == 2
     u = L.resq_unpack_weights
     assert u(None, 256, 256, 32, P, P, P, P, None) == 1
     assert u(P, 256, 256, 32, P, None, P, P, None) == 1

@@ -242,10 +242,12 @@ def test_nibble_packing_fixture_and_roundtrip(oracle):
     rng = np.random.default_rng(2)
     c = rng.integers(-7, 8, size=(5, 26)).astype(np.int8)
     p = oracle.pack_nibbles(c, ld_out=16)
-    assert p.shape == (5, 16) and not p[:, 13:].any()
-    lo = (p[:, :13] & 0xF).astype(np.int8); lo = np.where(lo > 7, lo - 16, lo)
+    assert p.shape == (5, 16) and np.all(p[:, 13:] == 0x08)      # padding = two zero codes
+    lo = (p[:, :13] & 0xF).astype(np.int8) - 8                   # offset binary
     hi = (p[:, :13] >> 4).astype(np.int8); hi = np.where(hi > 7, hi - 16, hi)
     assert np.array_equal(lo, c[:, 0::2]) and np.array_equal(hi, c[:, 1::2])
+    assert np.array_equal(oracle.odd_code_sums(c), c[:, 1::2].astype(np.int64).sum(1))
+    assert oracle.odd_code_sums(np.array([[1, 2, 3, -4, 5, 6]], np.int8)).tolist() == [4]
 
 
 # --------------------------------------------------------------------------

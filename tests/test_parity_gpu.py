@@ -34,6 +34,7 @@ def check_act_codes(oracle, rq, x: torch.Tensor, r: int):
         want = oracle.pack_nibbles(q_lo, act.ld_lo)
         assert np.array_equal(act.q_lo.cpu().numpy(), want), "INT4 codes differ"
         assert np.array_equal(act.s_lo.cpu().numpy().view(np.uint32), s_lo.view(np.uint32))
+        assert np.array_equal(act.lo_sum.cpu().numpy(), oracle.odd_code_sums(q_lo)), "lo_sum differs"
     return act
 
 
