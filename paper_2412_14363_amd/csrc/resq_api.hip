@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "resq.h"
+#include "resq_decode.hip.h"
 #include "resq_gemm.hip.h"
 #include "resq_hadamard.hip.h"
 #include "resq_layout.h"
@@ -138,10 +139,46 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
         !aligned(dbg_acc_lo, 4))
         return RESQ_ERR_ALIGN;
 
+    const WeightLayout L = make_weight_layout(N, K, r);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool dbg = dbg_acc_hi || dbg_acc_lo;
+
+    // few tokens: stream the weights once (HBM-bound kernel), activations in LDS
+    const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
+    if (M <= kDecodeMaxM && M * lds_row <= 150 * 1024) {
+        DecodeArgs d;
+        d.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
+        d.q_lo = q_lo;
+        d.ld_hi = L.kh_pad;
+        d.ld_lo = L.kl_pad / 2;
+        d.s_hi = s_hi;
+        d.s_lo = s_lo;
+        d.lo_sum = lo_sum;
+        d.packed = static_cast<const uint8_t*>(packed);
+        d.L = L;
+        d.M = (int)M;
+        d.y = static_cast<uint16_t*>(y);
+        d.ldy = ldy;
+        d.dbg_hi = dbg_acc_hi;
+        d.dbg_lo = dbg_acc_lo;
+        d.groups = (int)((N + 15) / 16);
+        d.lds_row = (int)lds_row;
+        const int lds_bytes = (int)(M * lds_row);
+        auto kernel = dbg ? gemm_decode_kernel<true> : gemm_decode_kernel<false>;
+        if (lds_bytes > 64 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+            return RESQ_ERR_HIP;
+        // one workgroup per compute unit (256 of them), fewer when there is less work
+        const int wgs = d.groups < 256 ? d.groups : 256;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)wgs), dim3(kDecodeThreads), lds_bytes, st, d);
+        return launch_status();
+    }
+
     GemmArgs a;
     a.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
     a.q_lo = q_lo;
-    a.L = make_weight_layout(N, K, r);
+    a.L = L;
     a.ld_hi = a.L.kh_pad;
     a.ld_lo = a.L.kl_pad / 2;
     a.s_hi = s_hi;
@@ -161,12 +198,10 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
     if (tiles > 0x7FFFFFFF) return RESQ_ERR_SHAPE;
 
     // static LDS (six stage buffers, 144 KiB): one workgroup per compute unit
-    if (dbg_acc_hi || dbg_acc_lo)
-        hipLaunchKernelGGL(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0,
-                           static_cast<hipStream_t>(stream), a);
+    if (dbg)
+        hipLaunchKernelGGL(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
     else
-        hipLaunchKernelGGL(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0,
-                           static_cast<hipStream_t>(stream), a);
+        hipLaunchKernelGGL(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
     return launch_status();
 }
 

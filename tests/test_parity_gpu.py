@@ -154,6 +154,25 @@ def test_layer_shapes(oracle, rq, M, K, N, r):
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
+@pytest.mark.parametrize("M,K,N,r", [
+    (1, 8192, 4096, 1024), (4, 8192, 4096, 1024), (16, 8192, 4100, 1024),   # Llama-70B K, d/8
+    (16, 1000, 515, 104),                        # K, r off the block size; N % 4 != 0
+    (3, 256, 256, 0), (16, 256, 256, 256),       # uniform INT4, uniform INT8
+    (7, 14336, 272, 1792),                       # longest K of the workloads
+])
+def test_layer_decode_shapes(oracle, rq, M, K, N, r):
+    # M <= 16 takes the weight-streaming kernel
+    x, w = wl.random_small_case(M * 11 + K, M, K, N, r, outliers="first4")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+def test_layer_decode_full_size(oracle, rq):
+    # the decode workload at full size (Llama-3-70B up_proj, 16 tokens); the oracle
+    # checks all codes and every accumulator and output
+    s = wl.decode_shape(16)
+    check_layer(oracle, rq, wl.make_activations(s), wl.make_weights(s), s.r)
+
+
 def test_layer_saturated_codes(oracle, rq):
     # every code at +-qmax: the largest accumulators the shapes allow
     M, K, N, r = 32, 2048, 256, 256
