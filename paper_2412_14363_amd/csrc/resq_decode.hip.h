@@ -65,13 +65,15 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
     }
 
     // activation codes of every token -> LDS (row = high codes, then packed low codes);
-    // 16-byte unit u of token m, four loads in flight per thread
+    // 16-byte unit u of token m, up to twelve loads in flight per thread
+    constexpr int FILL = 12;
     const int units = a.M * row_units;
-    for (int u0 = t; u0 < units; u0 += 4 * kDecodeThreads) {
-        uint4 v[4];
+    for (int u0 = t; u0 < units; u0 += FILL * kDecodeThreads) {
+        uint4 v[FILL];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < FILL; ++q) {
             const int u = u0 + q * kDecodeThreads;
+            v[q] = make_uint4(0u, 0u, 0u, 0u);
             if (u < units) {
                 const int m = u / row_units, c = u - m * row_units;
                 v[q] = c < hi_units
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
             }
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < FILL; ++q) {
             const int u = u0 + q * kDecodeThreads;
             if (u < units) {
                 const int m = u / row_units, c = u - m * row_units;
