@@ -66,20 +66,51 @@ __device__ __forceinline__ float absmax8(const uint4& v) {
 }
 
 // ---------------------------------------------------------------------------
-// Activations, vectorized: one block per token, the row is read once (16 bytes
-// per lane, coalesced), kept in registers across the absmax reduction, then
-// quantized and stored.  Requires K, r, ldx multiples of 8 and x 16-byte
-// aligned; ITERS * 2048 >= K.
+// Activations, vectorized.  A token row is read once (16 bytes per lane,
+// coalesced), kept in registers across the absmax reduction, then quantized and
+// stored.  WAVES wavefronts share one row: WAVES = 1 needs no LDS and no
+// barrier (many tokens), WAVES = 4 spreads one row over a whole workgroup (few
+// tokens).  Requires K, r, ldx multiples of 8 and x 16-byte aligned;
+// ITERS * 512 * WAVES >= K.
+//
+// The division x / scale is what the quantizer is defined by, but a correctly
+// rounded fp32 division costs about ten instructions per element, as much time
+// as the memory traffic of this kernel.  So: t = x * (1 / scale) is within a
+// few ulp of the correctly rounded quotient, and rint(t) equals rint(x / scale)
+// whenever t is further than that from every half-integer.  Elements within
+// 2^-14 of a half-integer (|t| <= 127, so more than 8 ulp) are redone with the
+// true division, in a branch that is taken only by the wavefronts that hold
+// such an element.  The codes are therefore exactly those of the definition.
 // ---------------------------------------------------------------------------
-template <int ITERS>
+__device__ __forceinline__ void quant8(const uint4& v, float scale, float inv, int qmax, int (&c)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float xs[8];
+    bool near_tie = false;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        xs[j] = bf16_bits_to_f32((j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu));
+        const float t = xs[j] * inv;
+        near_tie |= fabsf(__builtin_amdgcn_fractf(t) - 0.5f) < 6.103515625e-05f;
+        c[j] = (int)fminf(fmaxf(rintf(t), -(float)qmax), (float)qmax);
+    }
+    if (__builtin_amdgcn_ballot_w64(near_tie) != 0) {  // wave-uniform: rarely taken
+#pragma unroll
+        for (int j = 0; j < 8; ++j) c[j] = quant_code(xs[j], scale, qmax);
+    }
+}
+
+template <int ITERS, int WAVES>
 __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
-    const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
+    const uint16_t* __restrict__ x, int64_t ldx, int64_t M, int K, int r, int8_t* __restrict__ q_hi,
     int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
     float* __restrict__ s_lo, int32_t* __restrict__ lo_sum) {
+    constexpr int ROWS = 4 / WAVES;       // token rows per block
+    constexpr int RT = 64 * WAVES;        // threads per row
     __shared__ float red[8];
     __shared__ int red_sum[4];
-    const int64_t m = blockIdx.x;
-    const int t = threadIdx.x;
+    const int t = threadIdx.x % RT;
+    const int64_t m = (int64_t)blockIdx.x * ROWS + threadIdx.x / RT;
+    if (WAVES == 1 && m >= M) return;     // whole wavefront
     const int nunits = K >> 3;
     const int hi_units = r >> 3;
     const uint4* row = reinterpret_cast<const uint4*>(x + m * ldx);
@@ -88,7 +119,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
     float amax_h = 0.0f, amax_l = 0.0f;
 #pragma unroll
     for (int i = 0; i < ITERS; ++i) {
-        const int u = t + i * kQuantThreads;
+        const int u = t + i * RT;
         if (u < nunits) {
             v[i] = row[u];
             const float a = absmax8(v[i]);
@@ -96,9 +127,18 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
             else amax_l = fmaxf(amax_l, a);
         }
     }
-    block_max2(amax_h, amax_l, red);
+    if (WAVES == 1) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            amax_h = fmaxf(amax_h, __shfl_xor(amax_h, off));
+            amax_l = fmaxf(amax_l, __shfl_xor(amax_l, off));
+        }
+    } else {
+        block_max2(amax_h, amax_l, red);
+    }
     const float sh = group_scale(amax_h, kQmaxHi);
     const float sl = group_scale(amax_l, kQmaxLo);
+    const float inv_h = 1.0f / sh, inv_l = 1.0f / sl;
     if (t == 0) {
         if (r > 0) s_hi[m] = sh;
         if (K - r > 0) s_lo[m] = sl;
@@ -109,37 +149,38 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
     int odd_sum = 0;  // low codes of odd columns
 #pragma unroll
     for (int i = 0; i < ITERS; ++i) {
-        const int u = t + i * kQuantThreads;
+        const int u = t + i * RT;
         if (u < nunits) {
-            const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+            int c[8];
             if (u < hi_units) {
+                quant8(v[i], sh, inv_h, kQmaxHi, c);
                 uint32_t out[2] = {0u, 0u};
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu);
-                    const int c = quant_code(bf16_bits_to_f32(bits), sh, kQmaxHi);
-                    out[j >> 2] |= (uint32_t)(c & 0xFF) << (8 * (j & 3));
-                }
+                for (int j = 0; j < 8; ++j) out[j >> 2] |= (uint32_t)(c[j] & 0xFF) << (8 * (j & 3));
                 *reinterpret_cast<uint2*>(qh + (int64_t)u * 8) = make_uint2(out[0], out[1]);
             } else {
+                quant8(v[i], sl, inv_l, kQmaxLo, c);
                 uint32_t out = 0u;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu);
-                    const int c = quant_code(bf16_bits_to_f32(bits), sl, kQmaxLo);
-                    if (j & 1) odd_sum += c;
-                    out |= (uint32_t)(((j & 1) ? c : c + 8) & 0xF) << (4 * j);
+                    if (j & 1) odd_sum += c[j];
+                    out |= (uint32_t)(((j & 1) ? c[j] : c[j] + 8) & 0xF) << (4 * j);
                 }
                 *reinterpret_cast<uint32_t*>(ql + (int64_t)(u - hi_units) * 4) = out;
             }
         }
     }
     // zero codes in the padding of both rows
-    for (int64_t b = (int64_t)r + 8 * t; b < ld_hi; b += 8 * kQuantThreads)
+    for (int64_t b = (int64_t)r + 8 * t; b < ld_hi; b += 8 * RT)
         *reinterpret_cast<uint2*>(qh + b) = make_uint2(0u, 0u);
-    for (int64_t b = (int64_t)(K - r) / 2 + 4 * t; b < ld_lo; b += 4 * kQuantThreads)
+    for (int64_t b = (int64_t)(K - r) / 2 + 4 * t; b < ld_lo; b += 4 * RT)
         *reinterpret_cast<uint32_t*>(ql + b) = 0x08080808u;
-    odd_sum = block_sum(odd_sum, red_sum);
+    if (WAVES == 1) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) odd_sum += __shfl_xor(odd_sum, off);
+    } else {
+        odd_sum = block_sum(odd_sum, red_sum);
+    }
     if (t == 0 && K - r > 0) lo_sum[m] = odd_sum;
 }
 
