@@ -10,8 +10,9 @@ once, before the timed region, as they are offline in the method.
 Prints ONE JSON line.  ``value`` is 2*M*N*K operations per second of the whole
 step for prefill workloads (TOPS) and algorithmic bytes per second for decode
 workloads (GB/s).  ``roofline`` prices the GEMM kernel alone, its duration
-measured with HIP events around every launch in a second pass over the same
-steps; ``cpu_baseline`` is the CPU oracle timed on a bounded sample of the same
+measured with HIP events that the library records at the kernel's own start and
+end (resq_time_next_kernel) in a second pass over the same steps;
+``cpu_baseline`` is the CPU oracle timed on a bounded sample of the same
 workload on this host's cores.
 """
 from __future__ import annotations
@@ -106,6 +107,18 @@ def main() -> None:
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU: the library has no CPU path")
     torch.cuda.set_device(0)
+    if args.workload == "copy_calib":
+        # Calibration for the FETCH_SIZE / WRITE_SIZE counters: a plain device copy of
+        # known size (1 GiB read, 1 GiB written per launch), to be run under rocprofv3 --pmc.
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": "copy_calib", "bytes_read_per_copy": n,
+                          "bytes_written_per_copy": n, "copies": args.steps}))
+        return
     from paper_2412_14363_amd import binding as rq
     from paper_2412_14363_amd import workloads as wl
 
@@ -142,19 +155,21 @@ def main() -> None:
                  for p in packed]
 
     def step(i: int, events=None):
+        # events: three (start, stop) pairs of hipEvent_t, recorded by the library at
+        # the start and end of the kernel each call launches
         if s.hadamard:
+            if events is not None:
+                L.resq_time_next_kernel(*events[0])
             rc = L.resq_online_hadamard(*had_args)
             assert rc == 0, rc
         if events is not None:
-            events[0].record()
+            L.resq_time_next_kernel(*events[1])
         rc = L.resq_quantize_act(*qa_args)
         assert rc == 0, rc
         if events is not None:
-            events[1].record()
+            L.resq_time_next_kernel(*events[2])
         rc = L.resq_gemm_mixed(*gemm_args[i % n_copies])
         assert rc == 0, rc
-        if events is not None:
-            events[2].record()
 
     for i in range(args.warmup):
         step(i)
@@ -166,13 +181,31 @@ def main() -> None:
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
 
-    # second pass over the same steps with HIP events around each kernel
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    # second pass over the same steps; HIP events at the start and end of each kernel
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+
+    def new_event():
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def elapsed_ms(pair):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), pair[0], pair[1]) == 0
+        return ms.value
+
+    evs = [[(new_event(), new_event()) for _ in range(3)] for _ in range(args.steps)]
     for i in range(args.steps):
         step(i, evs[i])
     torch.cuda.synchronize()
-    quant_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    gemm_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    had_ms = sum(elapsed_ms(e[0]) for e in evs) / args.steps if s.hadamard else 0.0
+    quant_ms = sum(elapsed_ms(e[1]) for e in evs) / args.steps
+    gemm_ms = sum(elapsed_ms(e[2]) for e in evs) / args.steps
+    for e in evs:
+        for pair in e:
+            hip.hipEventDestroy(pair[0])
+            hip.hipEventDestroy(pair[1])
 
     ops = 2.0 * s.M * s.N * s.K
     abytes = algorithmic_bytes_gemm(s)
@@ -200,7 +233,7 @@ def main() -> None:
                    "step": ("hadamard + " if s.hadamard else "") + "quantize_act + gemm_mixed",
                    "weight_copies_rotated": n_copies},
         "tokens_per_s": s.M / (ms_per_step * 1e-3),
-        "quantize_ms": quant_ms, "gemm_ms": gemm_ms,
+        "hadamard_ms": had_ms, "quantize_ms": quant_ms, "gemm_ms": gemm_ms,
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -51,6 +51,17 @@ typedef enum resq_status {
 /* Static, human-readable name of a status code (host pointer, never null). */
 const char* resq_status_string(int status);
 
+/*
+ * Measurement aid: the next quantize, GEMM or Hadamard kernel that THIS host
+ * thread launches through the library records the two events (hipEvent_t passed
+ * as void*, created by the caller) exactly at the kernel's start and end, so
+ * that hipEventElapsedTime(start, stop) is the kernel's own duration without
+ * the gaps that events recorded around a launch include.  One-shot: the request
+ * is consumed by that launch.  The helper kernels of resq_pack_weights and
+ * resq_unpack_weights are not timed.
+ */
+int resq_time_next_kernel(void* start_event, void* stop_event);
+
 /* ---- layout queries (pure host functions) ------------------------------- */
 
 /*

@@ -23,6 +23,7 @@ STATUS_NAMES = {0: "RESQ_OK", 1: "RESQ_ERR_NULL", 2: "RESQ_ERR_SHAPE", 3: "RESQ_
 _i64, _p, _sz = C.c_int64, C.c_void_p, C.c_size_t
 SYMBOLS = {
     "resq_status_string": (C.c_char_p, [C.c_int]),
+    "resq_time_next_kernel": (C.c_int, [_p, _p]),
     "resq_act_hi_ld": (_i64, [_i64, _i64]),
     "resq_act_lo_ld": (_i64, [_i64, _i64]),
     "resq_packed_weight_bytes": (_sz, [_i64, _i64, _i64]),

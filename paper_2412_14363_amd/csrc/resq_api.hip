@@ -1,6 +1,7 @@
 // C ABI of the library: argument checks on the host, then kernel launches on
 // the caller's stream.  See include/resq.h for the contract of every entry.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "resq.h"
@@ -29,6 +30,17 @@ inline int shape_ok(int64_t rows, int64_t K, int64_t r) {
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? RESQ_OK : RESQ_ERR_HIP; }
 
+// One-shot timing request of resq_time_next_kernel(): the next main kernel this
+// thread launches is bracketed by the two events (exact kernel start and end).
+thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+
+template <typename... KArgs, typename... Args>
+inline void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+    hipEvent_t e0 = g_time_start, e1 = g_time_stop;
+    g_time_start = g_time_stop = nullptr;
+    hipExtLaunchKernelGGL(kernel, grid, block, lds, st, e0, e1, 0, args...);
+}
+
 }  // namespace
 
 extern "C" {
@@ -43,6 +55,13 @@ const char* resq_status_string(int status) {
         case RESQ_ERR_HIP: return "RESQ_ERR_HIP: the HIP runtime refused the launch";
         default: return "unknown resq status";
     }
+}
+
+int resq_time_next_kernel(void* start_event, void* stop_event) {
+    if (!start_event || !stop_event) return RESQ_ERR_NULL;
+    g_time_start = static_cast<hipEvent_t>(start_event);
+    g_time_stop = static_cast<hipEvent_t>(stop_event);
+    return RESQ_OK;
 }
 
 int64_t resq_act_hi_ld(int64_t K, int64_t r) {
@@ -83,9 +102,9 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
     // many tokens: one wavefront per token (no barrier); few: one workgroup per token
     const bool wave_per_row = M >= 512;
 #define RESQ_LAUNCH_QA(ITERS, WAVES)                                                             \
-    hipLaunchKernelGGL((quantize_act_vec_kernel<ITERS, WAVES>),                                   \
-                       dim3((unsigned)((M + 4 / WAVES - 1) / (4 / WAVES))), block, 0, st, xp,    \
-                       ldx, M, (int)K, (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum)
+    launch(quantize_act_vec_kernel<ITERS, WAVES>,                                                \
+           dim3((unsigned)((M + 4 / WAVES - 1) / (4 / WAVES))), block, 0, st, xp, ldx, M, (int)K, \
+           (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum)
     if (vec && wave_per_row) {
         if (K <= 2048) RESQ_LAUNCH_QA(4, 1);
         else if (K <= 4096) RESQ_LAUNCH_QA(8, 1);
@@ -97,8 +116,8 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
         else if (K <= 8192) RESQ_LAUNCH_QA(4, 4);
         else RESQ_LAUNCH_QA(8, 4);
     } else {
-        hipLaunchKernelGGL(quantize_act_generic_kernel, dim3((unsigned)M), block, 0, st, xp, ldx,
-                           (int)K, (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum);
+        launch(quantize_act_generic_kernel, dim3((unsigned)M), block, 0, st, xp, ldx, (int)K, (int)r,
+               q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum);
     }
 #undef RESQ_LAUNCH_QA
     return launch_status();
@@ -179,7 +198,7 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
             return RESQ_ERR_HIP;
         // one workgroup per compute unit (256 of them), fewer when there is less work
         const int wgs = d.groups < 256 ? d.groups : 256;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)wgs), dim3(kDecodeThreads), lds_bytes, st, d);
+        launch(kernel, dim3((unsigned)wgs), dim3(kDecodeThreads), lds_bytes, st, d);
         return launch_status();
     }
 
@@ -207,9 +226,9 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
 
     // static LDS (six stage buffers, 144 KiB): one workgroup per compute unit
     if (dbg)
-        hipLaunchKernelGGL(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+        launch(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
     else
-        hipLaunchKernelGGL(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+        launch(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
     return launch_status();
 }
 
@@ -249,11 +268,11 @@ int resq_online_hadamard(const void* x, void* y, int64_t ld, int64_t M, int64_t 
         hipLaunchKernelGGL(hadamard_copy_rest_kernel, dim3((unsigned)M), dim3(kHadThreads), 0, st, a);
     const dim3 grid((unsigned)blocks), blk(kHadThreads);
     switch (I) {
-        case 1: hipLaunchKernelGGL(hadamard_kernel<1>, grid, blk, 0, st, a); break;
-        case 2: hipLaunchKernelGGL(hadamard_kernel<2>, grid, blk, 0, st, a); break;
-        case 4: hipLaunchKernelGGL(hadamard_kernel<4>, grid, blk, 0, st, a); break;
-        case 8: hipLaunchKernelGGL(hadamard_kernel<8>, grid, blk, 0, st, a); break;
-        default: hipLaunchKernelGGL(hadamard_kernel<16>, grid, blk, 0, st, a); break;
+        case 1: launch(hadamard_kernel<1>, grid, blk, 0, st, a); break;
+        case 2: launch(hadamard_kernel<2>, grid, blk, 0, st, a); break;
+        case 4: launch(hadamard_kernel<4>, grid, blk, 0, st, a); break;
+        case 8: launch(hadamard_kernel<8>, grid, blk, 0, st, a); break;
+        default: launch(hadamard_kernel<16>, grid, blk, 0, st, a); break;
     }
     return launch_status();
 }
