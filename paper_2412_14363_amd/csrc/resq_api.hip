@@ -99,22 +99,14 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     const dim3 block(kQuantThreads);
     const bool vec = aligned(x, 16) && ldx % 8 == 0 && K % 8 == 0 && r % 8 == 0 && K <= 16384;
-    // many tokens: one wavefront per token (no barrier); few: one workgroup per token
-    const bool wave_per_row = M >= 512;
-#define RESQ_LAUNCH_QA(ITERS, WAVES)                                                             \
-    launch(quantize_act_vec_kernel<ITERS, WAVES>,                                                \
-           dim3((unsigned)((M + 4 / WAVES - 1) / (4 / WAVES))), block, 0, st, xp, ldx, M, (int)K, \
+#define RESQ_LAUNCH_QA(ITERS)                                                                   \
+    launch(quantize_act_vec_kernel<ITERS>, dim3((unsigned)M), block, 0, st, xp, ldx, (int)K,    \
            (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum)
-    if (vec && wave_per_row) {
-        if (K <= 2048) RESQ_LAUNCH_QA(4, 1);
-        else if (K <= 4096) RESQ_LAUNCH_QA(8, 1);
-        else if (K <= 8192) RESQ_LAUNCH_QA(16, 1);
-        else RESQ_LAUNCH_QA(32, 1);
-    } else if (vec) {
-        if (K <= 2048) RESQ_LAUNCH_QA(1, 4);
-        else if (K <= 4096) RESQ_LAUNCH_QA(2, 4);
-        else if (K <= 8192) RESQ_LAUNCH_QA(4, 4);
-        else RESQ_LAUNCH_QA(8, 4);
+    if (vec) {
+        if (K <= 2048) RESQ_LAUNCH_QA(1);
+        else if (K <= 4096) RESQ_LAUNCH_QA(2);
+        else if (K <= 8192) RESQ_LAUNCH_QA(4);
+        else RESQ_LAUNCH_QA(8);
     } else {
         launch(quantize_act_generic_kernel, dim3((unsigned)M), block, 0, st, xp, ldx, (int)K, (int)r,
                q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum);

@@ -56,61 +56,82 @@ __device__ __forceinline__ float group_scale(float amax, int qmax) {
 }
 
 // largest |.| of the eight bf16 values in a 16-byte vector, as a float
+typedef unsigned short v2us __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float absmax8(const uint4& v) {
-    // non-negative bf16 patterns order like unsigned integers
-    uint32_t a = v.x & 0x7FFF7FFFu, b = v.y & 0x7FFF7FFFu, c = v.z & 0x7FFF7FFFu,
-             d = v.w & 0x7FFF7FFFu;
-    uint32_t lo = max(max(a & 0xFFFFu, b & 0xFFFFu), max(c & 0xFFFFu, d & 0xFFFFu));
-    uint32_t hi = max(max(a >> 16, b >> 16), max(c >> 16, d >> 16));
-    return bf16_bits_to_f32(max(lo, hi));
+    // non-negative bf16 patterns order like unsigned integers: packed 16-bit max
+    auto as2 = [](uint32_t w) { w &= 0x7FFF7FFFu; return *reinterpret_cast<v2us*>(&w); };
+    const v2us m = __builtin_elementwise_max(__builtin_elementwise_max(as2(v.x), as2(v.y)),
+                                             __builtin_elementwise_max(as2(v.z), as2(v.w)));
+    return bf16_bits_to_f32(max((uint32_t)m[0], (uint32_t)m[1]));
 }
 
 // ---------------------------------------------------------------------------
-// Activations, vectorized.  A token row is read once (16 bytes per lane,
-// coalesced), kept in registers across the absmax reduction, then quantized and
-// stored.  WAVES wavefronts share one row: WAVES = 1 needs no LDS and no
-// barrier (many tokens), WAVES = 4 spreads one row over a whole workgroup (few
-// tokens).  Requires K, r, ldx multiples of 8 and x 16-byte aligned;
-// ITERS * 512 * WAVES >= K.
+// Activations, vectorized: one workgroup per token.  The row is read once (16
+// bytes per lane, coalesced), kept in registers across the absmax reduction,
+// then quantized and stored.  (One wavefront per token, without LDS or barrier,
+// was measured slower at every size: fewer, fatter waves hide less latency.)
+// Requires K, r, ldx multiples of 8 and x 16-byte aligned; ITERS * 2048 >= K.
 //
 // The division x / scale is what the quantizer is defined by, but a correctly
 // rounded fp32 division costs about ten instructions per element, as much time
 // as the memory traffic of this kernel.  So: t = x * (1 / scale) is within a
 // few ulp of the correctly rounded quotient, and rint(t) equals rint(x / scale)
 // whenever t is further than that from every half-integer.  Elements within
-// 2^-14 of a half-integer (|t| <= 127, so more than 8 ulp) are redone with the
-// true division, in a branch that is taken only by the wavefronts that hold
-// such an element.  The codes are therefore exactly those of the definition.
+// qmax * 2^-20 of a half-integer (|t| <= qmax, so at least 8 ulp of t) are
+// redone with the true division, in a branch that is taken only by the
+// wavefronts that hold such an element.  The codes are therefore exactly those
+// of the definition.  (bf16 inputs make exact ties common, about 2 in 10^4
+// elements, so the branch is not rare, but it is cheap on average.)
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void quant8(const uint4& v, float scale, float inv, int qmax, int (&c)[8]) {
+// Eight elements at once.  On return the low bits of u[j] hold the two's
+// complement code of element j (plus 8 for even j when LOW, the offset-binary
+// storage of even columns) and odd_sum has gained the codes of the odd elements.
+// Adding 1.5 * 2^23 to t rounds it to an integer, ties to even, in the low
+// mantissa bits of the sum, so rounding, conversion and the offset cost one add.
+template <bool LOW>
+__device__ __forceinline__ void quant8(const uint4& v, float scale, float inv, uint32_t (&u)[8],
+                                       float& odd_sum) {
+    constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23, bit pattern 0x4B400000
+    constexpr int qmax = LOW ? kQmaxLo : kQmaxHi;
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    float xs[8];
+    float xs[8], rr[8];
     bool near_tie = false;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        xs[j] = bf16_bits_to_f32((j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xFFFFu));
+        xs[j] = __uint_as_float((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
+        const float magic = kMagic + ((LOW && !(j & 1)) ? 8.0f : 0.0f);
         const float t = xs[j] * inv;
-        near_tie |= fabsf(__builtin_amdgcn_fractf(t) - 0.5f) < 6.103515625e-05f;
-        c[j] = (int)fminf(fmaxf(rintf(t), -(float)qmax), (float)qmax);
+        const float uf = t + magic;
+        rr[j] = uf - kMagic;                    // rint(t) (+ 8), exact
+        near_tie |= fabsf(t - (uf - magic)) > 0.5f - (LOW ? 8.0f : 128.0f) * 9.5367431640625e-07f;
+        u[j] = __float_as_uint(uf);
     }
     if (__builtin_amdgcn_ballot_w64(near_tie) != 0) {  // wave-uniform: rarely taken
 #pragma unroll
-        for (int j = 0; j < 8; ++j) c[j] = quant_code(xs[j], scale, qmax);
+        for (int j = 0; j < 8; ++j) {
+            const int c = quant_code(xs[j], scale, qmax) + ((LOW && !(j & 1)) ? 8 : 0);
+            u[j] = (uint32_t)c;
+            rr[j] = (float)c;
+        }
     }
+    if (LOW) odd_sum += (rr[1] + rr[3]) + (rr[5] + rr[7]);
 }
 
-template <int ITERS, int WAVES>
+// low bytes of four registers -> one dword
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    return __builtin_amdgcn_perm(b, a, 0x0c0c0400u) | __builtin_amdgcn_perm(d, c, 0x04000c0cu);
+}
+
+template <int ITERS>
 __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
-    const uint16_t* __restrict__ x, int64_t ldx, int64_t M, int K, int r, int8_t* __restrict__ q_hi,
+    const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
     int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
     float* __restrict__ s_lo, int32_t* __restrict__ lo_sum) {
-    constexpr int ROWS = 4 / WAVES;       // token rows per block
-    constexpr int RT = 64 * WAVES;        // threads per row
+    constexpr int RT = kQuantThreads;     // threads per row
     __shared__ float red[8];
     __shared__ int red_sum[4];
-    const int t = threadIdx.x % RT;
-    const int64_t m = (int64_t)blockIdx.x * ROWS + threadIdx.x / RT;
-    if (WAVES == 1 && m >= M) return;     // whole wavefront
+    const int t = threadIdx.x;
+    const int64_t m = blockIdx.x;
     const int nunits = K >> 3;
     const int hi_units = r >> 3;
     const uint4* row = reinterpret_cast<const uint4*>(x + m * ldx);
@@ -127,15 +148,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
             else amax_l = fmaxf(amax_l, a);
         }
     }
-    if (WAVES == 1) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            amax_h = fmaxf(amax_h, __shfl_xor(amax_h, off));
-            amax_l = fmaxf(amax_l, __shfl_xor(amax_l, off));
-        }
-    } else {
-        block_max2(amax_h, amax_l, red);
-    }
+    block_max2(amax_h, amax_l, red);
     const float sh = group_scale(amax_h, kQmaxHi);
     const float sl = group_scale(amax_l, kQmaxLo);
     const float inv_h = 1.0f / sh, inv_l = 1.0f / sl;
@@ -146,41 +159,34 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 
     int8_t* qh = q_hi + m * ld_hi;
     uint8_t* ql = q_lo + m * ld_lo;
-    int odd_sum = 0;  // low codes of odd columns
+    float odd_f = 0.0f;  // low codes of odd columns (small integers, exact in fp32)
 #pragma unroll
     for (int i = 0; i < ITERS; ++i) {
         const int u = t + i * RT;
         if (u < nunits) {
-            int c[8];
+            uint32_t c[8];
             if (u < hi_units) {
-                quant8(v[i], sh, inv_h, kQmaxHi, c);
-                uint32_t out[2] = {0u, 0u};
-#pragma unroll
-                for (int j = 0; j < 8; ++j) out[j >> 2] |= (uint32_t)(c[j] & 0xFF) << (8 * (j & 3));
-                *reinterpret_cast<uint2*>(qh + (int64_t)u * 8) = make_uint2(out[0], out[1]);
+                quant8<false>(v[i], sh, inv_h, c, odd_f);
+                *reinterpret_cast<uint2*>(qh + (int64_t)u * 8) =
+                    make_uint2(pack_low_bytes(c[0], c[1], c[2], c[3]), pack_low_bytes(c[4], c[5], c[6], c[7]));
             } else {
-                quant8(v[i], sl, inv_l, kQmaxLo, c);
-                uint32_t out = 0u;
+                quant8<true>(v[i], sl, inv_l, c, odd_f);
+                // byte k = (even code + 8) | (odd code << 4)
+                uint32_t by[4];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if (j & 1) odd_sum += c[j];
-                    out |= (uint32_t)(((j & 1) ? c[j] : c[j] + 8) & 0xF) << (4 * j);
-                }
-                *reinterpret_cast<uint32_t*>(ql + (int64_t)(u - hi_units) * 4) = out;
+                for (int k = 0; k < 4; ++k) by[k] = (c[2 * k + 1] << 4) | (c[2 * k] & 0xFu);
+                *reinterpret_cast<uint32_t*>(ql + (int64_t)(u - hi_units) * 4) =
+                    pack_low_bytes(by[0], by[1], by[2], by[3]);
             }
         }
     }
+    int odd_sum = (int)odd_f;
     // zero codes in the padding of both rows
     for (int64_t b = (int64_t)r + 8 * t; b < ld_hi; b += 8 * RT)
         *reinterpret_cast<uint2*>(qh + b) = make_uint2(0u, 0u);
     for (int64_t b = (int64_t)(K - r) / 2 + 4 * t; b < ld_lo; b += 4 * RT)
         *reinterpret_cast<uint32_t*>(ql + b) = 0x08080808u;
-    if (WAVES == 1) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) odd_sum += __shfl_xor(odd_sum, off);
-    } else {
-        odd_sum = block_sum(odd_sum, red_sum);
-    }
+    odd_sum = block_sum(odd_sum, red_sum);
     if (t == 0 && K - r > 0) lo_sum[m] = odd_sum;
 }
 
