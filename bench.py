@@ -31,9 +31,13 @@ if str(ROOT) not in sys.path:
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 matrix-core peak, TOP/s
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E peak, GB/s
 
-# HBM traffic per GEMM launch in bytes from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None where no such run has been made for the workload.
-MEASURED_TRAFFIC = {}
+# HBM traffic of the GEMM kernel per launch, in bytes: FETCH_SIZE + WRITE_SIZE of two
+# rocprofv3 --pmc runs, each scaled by what the same counter reads for a 1 GiB device copy
+# (x2.000 and x1.000; the summaries are under profiles/).  Absent = not measured.
+MEASURED_TRAFFIC = {
+    "oproj_prefill": 38.39e6 + 16.78e6,
+    "decode_m16": 133.60e6 + 0.92e6,
+}
 
 
 def workload_shape(name: str):
@@ -100,8 +104,8 @@ def main() -> None:
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        raise SystemExit("bench.py: this build runs on ONE GPU; --gpus must be 1 "
-                         "(the layer has no multi-GPU path, see DESIGN.md)")
+        raise SystemExit("bench.py: this build runs on ONE GPU and has no multi-GPU path; "
+                         "--gpus must be 1")
 
     import torch
     if not torch.cuda.is_available():
@@ -229,7 +233,7 @@ def main() -> None:
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"{s.name}: M={s.M} K={s.K} N={s.N} r={s.r}",
+        "config": {"workload": f"{s.name}: M={s.M} K={s.K} N={s.N} r={s.r}", "tag": args.workload,
                    "step": ("hadamard + " if s.hadamard else "") + "quantize_act + gemm_mixed",
                    "weight_copies_rotated": n_copies},
         "tokens_per_s": s.M / (ms_per_step * 1e-3),
