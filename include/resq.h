@@ -146,9 +146,9 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
  *   A_lo[m, n] = sum_{k >= r} q_lo[m, k] * w_lo[n, k]       (int4 x int4 -> int32)
  *   y[m, n]    = bf16( A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n] )
  * Both sums run on the int8 matrix cores (nibbles are widened in registers)
- * inside one kernel; y is written once.  The integer sums are exact: with
- * K <= 2^20 neither 127^2 * r nor the widened low sum 1680 * (K - r) can reach
- * 2^31.
+ * inside one kernel; y is written once.  The integer sums are exact: the call
+ * accepts r <= 133143 and K - r <= 2^20, so neither 127^2 * r nor the widened
+ * low sum 1680 * (K - r) can reach 2^31 (larger groups: RESQ_ERR_SHAPE).
  *   q_hi, q_lo, s_hi, s_lo, lo_sum   as written by resq_quantize_act for the same K, r
  *   packed                   as written by resq_pack_weights for the same N, K, r
  *   y        bf16 [M, ldy], ldy >= N                         (written)
