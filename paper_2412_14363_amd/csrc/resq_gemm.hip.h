@@ -50,6 +50,7 @@
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "resq_layout.h"
 
@@ -69,6 +70,16 @@ constexpr int kNumBuf = 6;
 constexpr int kPrefetch = kNumBuf - 1;  // stages requested ahead of the one being multiplied
 constexpr int kLoadsPerStage = (kBM + kBN) / kRowsPerBlock / 4;  // per lane: 6
 constexpr int kOutRowBytes = 128 * 2 + 16;  // one wave-tile row of bf16 in LDS, padded
+// After the stage buffers: the tile's per-channel and per-token constants of the
+// epilogue, copied there by the first loads of the kernel.
+constexpr int kMetaOff = kNumBuf * kStageBytes;
+constexpr int kMetaSwHi = 0;       // fp16 [256] high-group weight scales
+constexpr int kMetaSwLo = 512;     // fp16 [256] low-group weight scales
+constexpr int kMetaEven = 1024;    // int32 [256] even-column code sums of the low group
+constexpr int kMetaSHi = 2048;     // fp32 [128] high-group token scales
+constexpr int kMetaSLo = 2560;     // fp32 [128] low-group token scales
+constexpr int kMetaLoSum = 3072;   // int32 [128] odd-column code sums of the low group
+constexpr int kMetaBytes = 3584;
 
 struct GemmArgs {
     const uint8_t* q_hi;
@@ -92,6 +103,9 @@ __device__ __forceinline__ float fp16_bits_to_f32(uint32_t h) {
     return __uint_as_float((((h >> 10) & 0x1Fu) + 112u) << 23 | (h & 0x3FFu) << 13);
 }
 
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+
 // two fp32 -> two bf16 (round to nearest even) in one dword, low half first
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
@@ -108,7 +122,7 @@ template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
-// the same with N = 6 * later, later = 0..3 stages allowed to stay in flight
+// the same with N = 6 * later, later = 0..4 stages allowed to stay in flight
 __device__ __forceinline__ void wait_stage_and_barrier(int later) {
     if (later >= 4) wait_loads_and_barrier<4 * kLoadsPerStage>();
     else if (later == 3) wait_loads_and_barrier<3 * kLoadsPerStage>();
@@ -117,15 +131,30 @@ __device__ __forceinline__ void wait_stage_and_barrier(int later) {
     else wait_loads_and_barrier<0>();
 }
 
-__device__ __forceinline__ void load_to_lds_16B(const uint8_t* g, uint8_t* lds_wave_base) {
+// direct-to-LDS loads: lane l's 16 (4) bytes land at lds_wave_base + 16 (4) * l
+__device__ __forceinline__ void load_to_lds_16B(const void* g, uint8_t* lds_wave_base) {
     __builtin_amdgcn_global_load_lds(
         (const __attribute__((address_space(1))) void*)g,
         (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
+__device__ __forceinline__ void load_to_lds_4B(const void* g, uint8_t* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)g,
+        (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
+}
 
+// untracked LDS reads (the compiler does not know these touch LDS)
 template <int OFF>
 __device__ __forceinline__ void lds_read16(v4i& dst, uint32_t addr) {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int OFF>
+__device__ __forceinline__ void lds_read8(v2i& dst, uint32_t addr) {
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int OFF>
+__device__ __forceinline__ void lds_read4(int& dst, uint32_t addr) {
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
 }
 
 // packed fragments of one reduction step as read from LDS:
@@ -174,9 +203,21 @@ __device__ __forceinline__ void tile_of_block(const GemmArgs& a, int& tm, int& t
     }
 }
 
+template <int N>
+using IC = std::integral_constant<int, N>;
+// f(IC<0>), f(IC<1>), ..., f(IC<N-1>)
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+    (f(IC<Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 template <bool DBG>
 __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs a) {
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[kNumBuf * kStageBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[kMetaOff + kMetaBytes];
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -187,42 +228,67 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     tile_of_block(a, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * kBM;
     const int64_t n0 = (int64_t)tile_n * kBN;
-    const int S_hi = a.stages_hi, S = a.stages_hi + a.stages_lo;
+    const int S_hi = a.stages_hi, S_lo = a.stages_lo, S = S_hi + S_lo;
+    const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
+    const uint16_t* sw_lo = sw_hi + a.L.n_pad;
+    const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
+
+    // ---- epilogue constants -> LDS ---------------------------------------------
+    // These are the oldest loads of every wave, so the first wait for a stage
+    // covers them.  Token rows past M repeat the last row (never stored).
+    if (wave == 0) {
+        load_to_lds_16B((lane < 32 ? sw_hi : sw_lo) + n0 + (lane & 31) * 8, lds + kMetaOff + kMetaSwHi);
+    } else if (wave == 1) {
+        load_to_lds_16B(even_sum + n0 + lane * 4, lds + kMetaOff + kMetaEven);
+    } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int64_t m = m0 + h * 64 + lane;
+            m = m < a.M ? m : a.M - 1;
+            if (wave == 2) {
+                if (S_hi > 0) load_to_lds_4B(a.s_hi + m, lds + kMetaOff + kMetaSHi + h * 256);
+                if (S_lo > 0) load_to_lds_4B(a.s_lo + m, lds + kMetaOff + kMetaSLo + h * 256);
+            } else if (S_lo > 0) {
+                load_to_lds_4B(a.lo_sum + m, lds + kMetaOff + kMetaLoSum + h * 256);
+            }
+        }
+    }
 
     // ---- global -> LDS copy --------------------------------------------------
     // One load instruction fills one block: lane l fetches row l / 4, piece
     // (l % 4) ^ (l / 16).  Wave w copies A blocks 2w, 2w+1 and B blocks 4w..4w+3
     // of each stage.  Token rows past M are clamped to the last row (their
     // results are never stored).  The weight blocks of one 16-channel group are
-    // contiguous over all stages, high ones first.
-    const uint8_t* a_src_hi[2];
-    const uint8_t* a_src_lo[2];
-    const uint8_t* b_src[4];
+    // contiguous over all stages, high ones first.  Every address is a
+    // wave-uniform base (scalar registers, advanced per stage) plus a 32-bit
+    // per-lane offset that never changes.
+    uint32_t a_voff_hi[2], a_voff_lo[2], b_voff;
+    const uint8_t* a_base_hi = a.q_hi + m0 * a.ld_hi;
+    const uint8_t* a_base_lo = a.q_lo + m0 * a.ld_lo - (int64_t)S_hi * kRowBytes;
+    const uint8_t* b_base = a.packed + (n0 / 16 + wave * 4) * a.L.group_bytes;
     {
         const int r = lane >> 2, kc = (lane & 3) ^ (lane >> 4);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            int64_t row = m0 + (wave * 2 + i) * 16 + r;
-            row = row < a.M ? row : a.M - 1;
-            a_src_hi[i] = a.q_hi + row * a.ld_hi + kc * 16;
-            a_src_lo[i] = a.q_lo + row * a.ld_lo + kc * 16 - (int64_t)S_hi * kRowBytes;
+            int64_t row = (wave * 2 + i) * 16 + r;
+            row = m0 + row < a.M ? row : a.M - 1 - m0;
+            a_voff_hi[i] = (uint32_t)(row * a.ld_hi + kc * 16);
+            a_voff_lo[i] = (uint32_t)(row * a.ld_lo + kc * 16);
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            b_src[i] = a.packed + (n0 / 16 + wave * 4 + i) * a.L.group_bytes + r * kRowBytes + kc * 16;
+        b_voff = r * kRowBytes + kc * 16;
     }
-    // request stage sg (0 .. S-1, high stages first) into buffer buf
-    auto issue_stage = [&](int sg, int buf) __attribute__((always_inline)) {
+    // load K of stage sg (0 .. S-1, high stages first) into buffer buf; K = 0, 1: A blocks, 2..5: B blocks
+    auto issue_load = [&](auto k, int sg, int buf) __attribute__((always_inline)) {
+        constexpr int K = decltype(k)::value;
         uint8_t* dst = lds + buf * kStageBytes;
-        const bool lo = sg >= S_hi;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            load_to_lds_16B((lo ? a_src_lo[i] : a_src_hi[i]) + (int64_t)sg * kRowBytes,
-                            dst + (wave * 2 + i) * kBlockBytes);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            load_to_lds_16B(b_src[i] + (int64_t)sg * kBlockBytes,
-                            dst + kStageABytes + (wave * 4 + i) * kBlockBytes);
+        if constexpr (K < 2) {
+            const bool lo = sg >= S_hi;
+            const uint8_t* base = (lo ? a_base_lo : a_base_hi) + (int64_t)sg * kRowBytes;
+            load_to_lds_16B(base + (lo ? a_voff_lo[K] : a_voff_hi[K]), dst + (wave * 2 + K) * kBlockBytes);
+        } else {
+            const uint8_t* base = b_base + (K - 2) * a.L.group_bytes + (int64_t)sg * kBlockBytes;
+            load_to_lds_16B(base + b_voff, dst + kStageABytes + (wave * 4 + K - 2) * kBlockBytes);
+        }
     };
 
     // ---- accumulators ----------------------------------------------------------
@@ -235,10 +301,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                acc[j][i][v] = 0;
-                part[j][i][v] = 0.f;
-            }
+            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
 
     // ---- LDS -> register reads ---------------------------------------------------
     // An operand tile is 32 rows x 64 bytes (two blocks).  In step st (0, 1) of a
@@ -255,237 +318,317 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             b_off[st] = lds0 + kStageABytes + wn * (8 * kBlockBytes) + off;
         }
     }
-    auto read_step = [&](auto step, Packed& f, int buf) __attribute__((always_inline)) {
-        constexpr int ST = decltype(step)::value;
-        const uint32_t aa = a_off[ST] + buf * kStageBytes, bb = b_off[ST] + buf * kStageBytes;
-        lds_read16<0 * 2 * kBlockBytes>(f.fa[0], aa);
-        lds_read16<1 * 2 * kBlockBytes>(f.fa[1], aa);
-        lds_read16<0 * 2 * kBlockBytes>(f.fb[0], bb);
-        lds_read16<1 * 2 * kBlockBytes>(f.fb[1], bb);
-        lds_read16<2 * 2 * kBlockBytes>(f.fb[2], bb);
-        lds_read16<3 * 2 * kBlockBytes>(f.fb[3], bb);
+    // read K of a step: K = 0, 1: activation fragments, 2..5: weight fragments
+    auto read_frag = [&](auto k, Packed& f, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
+        constexpr int K = decltype(k)::value;
+        if constexpr (K < 2) lds_read16<K * 2 * kBlockBytes>(f.fa[K], aa);
+        else lds_read16<(K - 2) * 2 * kBlockBytes>(f.fb[K - 2], bb);
     };
-    auto transform = [&](auto is_lo, const Packed& p, Operands& u) __attribute__((always_inline)) {
+    // piece P of the widening of one step's fragments: 12 pieces for a low step
+    // (one AND over a fragment each), 6 for a high step (a register copy each)
+    auto transform_piece = [&](auto is_lo, auto p, const Packed& f, Operands& u) __attribute__((always_inline)) {
+        constexpr int P = decltype(p)::value;
         if constexpr (decltype(is_lo)::value) {
+            if constexpr (P < 2) u.ae[P] = f.fa[P] & (int)0x0F0F0F0F;           // even columns: code + 8
+            else if constexpr (P < 4) u.ao[P - 2] = f.fa[P - 2] & (int)0xF0F0F0F0;  // odd columns: 16 * code
+            else if constexpr (P < 8) u.be[P - 4] = f.fb[P - 4] & (int)0xF0F0F0F0;  // even columns: 16 * code
+            else if constexpr (P < 12) u.bo[P - 8] = f.fb[P - 8] & (int)0x0F0F0F0F;  // odd columns: code + 8
+        } else {
+            if constexpr (P < 2) u.ae[P] = f.fa[P];
+            else if constexpr (P < 6) u.be[P - 2] = f.fb[P - 2];
+        }
+    };
+    // matrix instruction Q of a step (8 per high step, 16 per low step), in an
+    // order that keeps two instructions on the same accumulator eight apart
+    auto mfma = [&](auto q, const Operands& u) __attribute__((always_inline)) {
+        constexpr int Q = decltype(q)::value;
+        constexpr int j = (Q & 7) >> 1, i = Q & 1;
+        if constexpr (Q < 8)
+            acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.be[j], u.ae[i], acc[j][i], 0, 0, 0);
+        else
+            acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.bo[j], u.ao[i], acc[j][i], 0, 0, 0);
+    };
+
+    // ---- epilogue pieces -------------------------------------------------------------
+    // Lane coordinates inside the tile: token tl + 32 i, channel cl + 32 j + 8 vq + vr.
+    const int tl = wm * 64 + (lane & 31);
+    const int cl = wn * 128 + (lane >> 5) * 4;
+    uint8_t* const out_stage = lds + wave * (64 * kOutRowBytes);
+
+    // Fold the integer tile of one group into the result:
+    //   value = part + A * s_tok[m] * s_ch[n],
+    // where A is the group's integer sum: the accumulator itself for the high
+    // group; for the low group (acc - 128 * (even_sum[n] + lo_sum[m])) / 16, an
+    // exact division whose 1/16 is folded into the scale outside the debug kernel
+    // (same fp32 product).  Not FINAL: part = value, acc = 0 (part then stays in
+    // accumulation registers while the low steps need the ordinary ones for
+    // operands).  FINAL: value is rounded to bf16 and staged in LDS, row-padded,
+    // for the row-segment stores.
+    auto fold = [&](auto is_lo, auto is_final, int32_t* dbg) __attribute__((always_inline)) {
+        constexpr bool LOW = decltype(is_lo)::value, FINAL = decltype(is_final)::value;
+        // The constants come from LDS.  FINAL: no direct-to-LDS load is in flight
+        // any more, ordinary loads.  Otherwise: untracked reads, each batch fused
+        // with its wait in one asm statement so that the registers are valid
+        // wherever the compiler can see them.
+        constexpr int kTok = LOW ? kMetaSLo : kMetaSHi, kSc = LOW ? kMetaSwLo : kMetaSwHi;
+        int st_bits[2], ca[2] = {0, 0};
+        v2i sc[4][4];
+        v4i ev[4][4];
+        if constexpr (FINAL) {
+            const uint8_t* meta = lds + kMetaOff;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                u.ae[i] = p.fa[i] & (int)0x0F0F0F0F;  // even columns: code + 8
-                u.ao[i] = p.fa[i] & (int)0xF0F0F0F0;  // odd columns: 16 * code
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                u.be[j] = p.fb[j] & (int)0xF0F0F0F0;  // even columns: 16 * code
-                u.bo[j] = p.fb[j] & (int)0x0F0F0F0F;  // odd columns: code + 8
+                st_bits[i] = *reinterpret_cast<const int*>(meta + kTok + (tl + 32 * i) * 4);
+                if constexpr (LOW) ca[i] = *reinterpret_cast<const int*>(meta + kMetaLoSum + (tl + 32 * i) * 4);
             }
         } else {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) u.ae[i] = p.fa[i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) u.be[j] = p.fb[j];
+            static_assert(!LOW, "the low group is folded last");
+            asm volatile("ds_read_b32 %0, %2\n\tds_read_b32 %1, %2 offset:128\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(st_bits[0]), "=&v"(st_bits[1])
+                         : "v"(lds0 + kMetaOff + kTok + tl * 4));
         }
-    };
-    // matrix instructions FIRST .. LAST-1 of a step, in an order that keeps two
-    // instructions on the same accumulator eight apart
-    auto multiply = [&](auto is_lo, auto first, auto last, const Operands& u) __attribute__((always_inline)) {
-        constexpr int FIRST = decltype(first)::value, LAST = decltype(last)::value;
+        auto fetch = [&](auto jj) __attribute__((always_inline)) {
+            constexpr int j = decltype(jj)::value;
+            if constexpr (FINAL) {
+                const uint8_t* meta = lds + kMetaOff;
 #pragma unroll
-        for (int q = FIRST; q < LAST; ++q) {
-            const int j = (q & 7) >> 1, i = q & 1;
-            if (q < 8)
-                acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.be[j], u.ae[i], acc[j][i], 0, 0, 0);
-            else
-                acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.bo[j], u.ao[i], acc[j][i], 0, 0, 0);
-        }
-    };
-
-    // per-lane coordinates of the epilogue
-    const int64_t tok0 = m0 + wm * 64 + (lane & 31);
-    const int64_t ch0 = n0 + wn * 128 + (lane >> 5) * 4;
-    const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
-    const uint16_t* sw_lo = sw_hi + a.L.n_pad;
-
-    // part += A * s_tok[m] * s_ch[n]; acc = 0, where A is the group's integer sum:
-    // the accumulator itself for the high group; for the low group
-    // (acc - 128 * (even_sum[n] + lo_sum[m])) / 16, an exact division whose 1/16
-    // is folded into the scale outside the debug kernel (same fp32 product).
-    const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
-    auto fold = [&](auto is_lo, const float* s_tok, const uint16_t* s_ch, int32_t* dbg) __attribute__((always_inline)) {
-        constexpr bool LOW = decltype(is_lo)::value;
-        float st[2];
-        int ca[2] = {0, 0};
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int c = cl + 32 * j + 8 * vq;
+                    sc[j][vq] = *reinterpret_cast<const v2i*>(meta + kSc + c * 2);
+                    if constexpr (LOW) ev[j][vq] = *reinterpret_cast<const v4i*>(meta + kMetaEven + c * 4);
+                }
+            } else {
+                v2i r0, r1, r2, r3;
+                const uint32_t addr = lds0 + kMetaOff + kSc + cl * 2;
+                asm volatile("ds_read_b64 %0, %4 offset:%5\n\tds_read_b64 %1, %4 offset:%6\n\t"
+                             "ds_read_b64 %2, %4 offset:%7\n\tds_read_b64 %3, %4 offset:%8\n\t"
+                             "s_waitcnt lgkmcnt(0)"
+                             : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
+                             : "v"(addr), "n"((32 * j + 0) * 2), "n"((32 * j + 8) * 2),
+                               "n"((32 * j + 16) * 2), "n"((32 * j + 24) * 2));
+                sc[j][0] = r0;
+                sc[j][1] = r1;
+                sc[j][2] = r2;
+                sc[j][3] = r3;
+            }
+        };
+        // debug dump of the integer sums: row pointers and the number of valid columns from cl on
+        int32_t* dbg_row[2] = {nullptr, nullptr};
+        bool dbg_ok[2] = {false, false};
+        int dbg_cols = 0;
+        if constexpr (DBG) {
+            dbg_cols = (int)(a.L.N - n0 - cl);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int64_t m = tok0 + 32 * i;
-            st[i] = m < a.M ? s_tok[m] : 0.0f;
-            if constexpr (LOW) {
-                ca[i] = m < a.M ? a.lo_sum[m] * 128 : 0;
-                if constexpr (!DBG) st[i] *= 0.0625f;
+            for (int i = 0; i < 2; ++i) {
+                const int64_t m = m0 + tl + 32 * i;
+                dbg_ok[i] = dbg != nullptr && m < a.M;
+                dbg_row[i] = dbg + m * a.L.N + n0 + cl;
             }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int64_t n = ch0 + 32 * j + 8 * vq;  // < n_pad always
-                const uint2 sc = *reinterpret_cast<const uint2*>(s_ch + n);
-                const float sn[4] = {fp16_bits_to_f32(sc.x & 0xFFFFu), fp16_bits_to_f32(sc.x >> 16),
-                                     fp16_bits_to_f32(sc.y & 0xFFFFu), fp16_bits_to_f32(sc.y >> 16)};
-                int cw[4] = {0, 0, 0, 0};
-                if constexpr (LOW) {
-                    const int4 e = *reinterpret_cast<const int4*>(even_sum + n);
-                    cw[0] = e.x * 128; cw[1] = e.y * 128; cw[2] = e.z * 128; cw[3] = e.w * 128;
-                }
+        float st[2];
+        static_for<4>([&](auto jj) __attribute__((always_inline)) {
+            constexpr int j = decltype(jj)::value;
+            fetch(jj);
+            if constexpr (j == 0) {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const int64_t m = tok0 + 32 * i;
+                    st[i] = __int_as_float(st_bits[i]);
+                    if constexpr (LOW) {
+                        ca[i] *= 128;
+                        if constexpr (!DBG) st[i] *= 0.0625f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const v4h h = *reinterpret_cast<const v4h*>(&sc[j][vq]);
+                const float sn[4] = {(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    float val[4];
 #pragma unroll
                     for (int vr = 0; vr < 4; ++vr) {
                         const int v = vq * 4 + vr;
                         int iv = acc[j][i][v];
                         if constexpr (LOW) {
-                            iv -= cw[vr] + ca[i];
+                            iv -= ev[j][vq][vr] * 128 + ca[i];
                             if constexpr (DBG) iv >>= 4;
                         }
-                        part[j][i][v] += (float)iv * (st[i] * sn[vr]);
+                        val[vr] = (float)iv * (st[i] * sn[vr]);
+                        if constexpr (LOW) val[vr] += part[j][i][v];
                         if constexpr (DBG) {
-                            if (dbg && m < a.M && n + vr < a.L.N) dbg[m * a.L.N + n + vr] = iv;
+                            if (dbg_ok[i] && 32 * j + 8 * vq + vr < dbg_cols) dbg_row[i][32 * j + 8 * vq + vr] = iv;
                         }
-                        acc[j][i][v] = 0;
+                        if constexpr (!FINAL) {
+                            part[j][i][v] = val[vr];
+                            acc[j][i][v] = 0;
+                        }
+                    }
+                    if constexpr (FINAL) {
+                        const int row = 32 * i + (lane & 31);
+                        const int col = 32 * j + 8 * vq + 4 * (lane >> 5);
+                        *reinterpret_cast<uint2*>(out_stage + row * kOutRowBytes + col * 2) =
+                            make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
                     }
                 }
             }
-        }
-        // keep the fp32 tile in accumulation registers while the low steps need
-        // the ordinary ones for operands
-        if constexpr (!LOW) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
+            // the fp32 tile goes to accumulation registers at once: the ordinary
+            // ones are needed for the operands of the low steps
+            if constexpr (!FINAL) {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(part[j][i]));
-        }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
 
     // ---- main loop ---------------------------------------------------------------
-    using T0 = std::integral_constant<int, 0>;
-    using T1 = std::integral_constant<int, 1>;
     using HI = std::false_type;
     using LO = std::true_type;
     {
         Packed px, py;
         Operands ux, uy;
         const int ahead = S < kPrefetch ? S : kPrefetch;
-        for (int i = 0; i < ahead; ++i) issue_stage(i, i);
-        wait_stage_and_barrier(ahead - 1);  // stage 0 has landed everywhere
-        read_step(T0{}, px, 0);
+        for (int i = 0; i < ahead; ++i)
+            static_for<kLoadsPerStage>([&](auto k) __attribute__((always_inline)) { issue_load(k, i, i); });
+        wait_stage_and_barrier(ahead - 1);  // stage 0 (and the epilogue constants) have landed everywhere
+        static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, px, a_off[0], b_off[0]); });
         lds_wait_all(px);
-        read_step(T1{}, py, 0);
-        if (S_hi > 0) transform(HI{}, px, ux);
-        else transform(LO{}, px, ux);
+        static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, py, a_off[1], b_off[1]); });
+        if (S_hi > 0) static_for<6>([&](auto p) __attribute__((always_inline)) { transform_piece(HI{}, p, px, ux); });
+        else static_for<12>([&](auto p) __attribute__((always_inline)) { transform_piece(LO{}, p, px, ux); });
 
         int buf = 0;
-        // One stage = two pipeline slots; `cur` is the kind of this stage's steps,
-        // `next` the kind of the next stage's first step.  In each slot the first
-        // two matrix instructions are issued before anything else, so that the
-        // waits, the barrier and the issue of reads and loads run in their shadow.
-        using N0 = std::integral_constant<int, 0>;
-        using N2 = std::integral_constant<int, 2>;
-        // Scheduling pattern of the second part of a slot: the vector ALU can
-        // issue about four instructions in the shadow of one matrix instruction,
-        // and only if they sit between two matrix instructions, so the widening
-        // of the next step's operands is spread evenly, four per matrix
-        // instruction, instead of being bunched at the front.
-        auto spread = [&](auto is_lo) __attribute__((always_inline)) {
-            constexpr int PAIRS = decltype(is_lo)::value ? 12 : 6;
-#pragma unroll
-            for (int q = 0; q < PAIRS; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // four vector ALU instructions
-            }
-        };
-        auto stage = [&](auto cur, auto next, int sg) __attribute__((always_inline)) {
-            using NM = std::integral_constant<int, decltype(cur)::value ? 16 : 8>;
+        // One stage = two pipeline slots (reduction steps).  `cur` is the kind of
+        // this stage's steps, `next` the kind of the next stage's first step;
+        // ISSUE: this stage requests stage sg + kPrefetch (every stage but the
+        // last kPrefetch ones).  A slot is a fixed sequence of groups, one matrix
+        // instruction each, with the slot's other work dealt out among them so that
+        // it issues in the shadow of the matrix pipeline (about four vector ALU
+        // instructions, or a read and a load, fit behind one matrix instruction):
+        //   slot 0: multiply step 0 | wait + barrier after PRE groups | then per group one
+        //           LDS read of the next stage's step 0 and one piece of step 1's widening
+        //   slot 1: multiply step 1 | per group one LDS read of the next stage's step 1 and
+        //           one piece of the next step 0's widening
+        // and the stage's six global loads at even distances after the barrier: the
+        // four waves run in step, and loads issued in a burst back up the memory
+        // pipeline (19 clocks per load) until the waves stall on issue.
+        auto stage = [&](auto cur, auto next, auto issue, int sg) __attribute__((always_inline)) {
+            constexpr bool CUR_LO = decltype(cur)::value, ISSUE = decltype(issue)::value;
+            constexpr int NM = CUR_LO ? 16 : 8;   // matrix instructions per step
+            constexpr int PRE = CUR_LO ? 4 : 2;   // ... of which this many go first
+            constexpr int NT_CUR = CUR_LO ? 12 : 6, NT_NEXT = decltype(next)::value ? 12 : 6;
+            constexpr int LD_EVERY = (NM - PRE) / 3;  // a global load every so many groups, three per slot
             const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
             const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
+            const uint32_t shift = nxt * kStageBytes;
             // invariant: ux = operands of (sg, step 0); py = reads of (sg, step 1) in flight
             __builtin_amdgcn_sched_barrier(0);
-            multiply(cur, N0{}, N2{}, ux);
+            static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, ux); });
             __builtin_amdgcn_sched_barrier(0);
             // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
             // stages sg + 2 .. sg + 4 may stay in flight
-            const int rem = S - 2 - sg;
-            wait_stage_and_barrier(rem > 3 ? 3 : rem);
+            if constexpr (ISSUE) {
+                wait_loads_and_barrier<3 * kLoadsPerStage>();
+            } else {
+                const int rem = S - 2 - sg;
+                wait_stage_and_barrier(rem > 3 ? 3 : rem);
+            }
             lds_wait_all(py);
-            read_step(T0{}, px, nxt);  // past the last stage: a harmless read of stale LDS
             __builtin_amdgcn_sched_barrier(0);
-            if (sg + kPrefetch < S) issue_stage(sg + kPrefetch, prv);
-            transform(cur, py, uy);
-            multiply(cur, N2{}, NM{}, ux);
-            spread(cur);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(cur, N0{}, N2{}, uy);
+            static_for<NM - PRE>([&](auto g) __attribute__((always_inline)) {
+                constexpr int G = decltype(g)::value;
+                mfma(IC<PRE + G>{}, ux);
+                // past the last stage the reads fetch stale LDS: harmless
+                if constexpr (G < 6) read_frag(g, px, a_off[0] + shift, b_off[0] + shift);
+                if constexpr (G < NT_CUR) transform_piece(cur, g, py, uy);
+                if constexpr (NT_CUR > NM - PRE && G == NM - PRE - 1)
+                    static_for<NT_CUR - (NM - PRE)>([&](auto e) __attribute__((always_inline)) {
+                        transform_piece(cur, IC<NM - PRE + decltype(e)::value>{}, py, uy);
+                    });
+                if constexpr (ISSUE && G % LD_EVERY == LD_EVERY - 1 && G / LD_EVERY < 3)
+                    issue_load(IC<G / LD_EVERY>{}, sg + kPrefetch, prv);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, uy); });
             __builtin_amdgcn_sched_barrier(0);
             lds_wait_all(px);
-            read_step(T1{}, py, nxt);
             __builtin_amdgcn_sched_barrier(0);
-            transform(next, px, ux);
-            multiply(cur, N2{}, NM{}, uy);
-            spread(cur);
-            __builtin_amdgcn_sched_barrier(0);
+            static_for<NM - PRE>([&](auto g) __attribute__((always_inline)) {
+                constexpr int G = decltype(g)::value;
+                mfma(IC<PRE + G>{}, uy);
+                if constexpr (G < 6) read_frag(g, py, a_off[1] + shift, b_off[1] + shift);
+                if constexpr (G < NT_NEXT) transform_piece(next, g, px, ux);
+                if constexpr (NT_NEXT > NM - PRE && G == NM - PRE - 1)
+                    static_for<NT_NEXT - (NM - PRE)>([&](auto e) __attribute__((always_inline)) {
+                        transform_piece(next, IC<NM - PRE + decltype(e)::value>{}, px, ux);
+                    });
+                if constexpr (ISSUE && G % LD_EVERY == LD_EVERY - 1 && G / LD_EVERY < 3)
+                    issue_load(IC<3 + G / LD_EVERY>{}, sg + kPrefetch, prv);
+                __builtin_amdgcn_sched_barrier(0);
+            });
             buf = nxt;
         };
+        using YES = std::true_type;
+        using NO = std::false_type;
+        const int issue_end = S - kPrefetch;  // stages below this one request a later stage
+        int sg = 0;
         if (S_hi > 0) {
-            for (int sg = 0; sg + 1 < S_hi; ++sg) stage(HI{}, HI{}, sg);
-            stage(HI{}, LO{}, S_hi - 1);
-            fold(HI{}, a.s_hi, sw_hi, a.dbg_hi);
+            for (; sg < S_hi - 1 && sg < issue_end; ++sg) stage(HI{}, HI{}, YES{}, sg);
+            for (; sg < S_hi; ++sg) {
+                if (sg < S_hi - 1) stage(HI{}, HI{}, NO{}, sg);
+                else if (sg < issue_end) stage(HI{}, LO{}, YES{}, sg);
+                else stage(HI{}, LO{}, NO{}, sg);
+            }
+            if (S_lo > 0) {
+                lds_wait_all(py);  // the reads of the next step are in flight: let them land first
+                fold(HI{}, NO{}, a.dbg_hi);
+            } else {
+                lds_wait_all(py);             // reads past the last stage: let them land
+                wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
+                fold(HI{}, YES{}, a.dbg_hi);
+            }
         }
-        for (int sg = S_hi; sg < S; ++sg) stage(LO{}, LO{}, sg);
-        if (a.stages_lo > 0) fold(LO{}, a.s_lo, sw_lo, a.dbg_lo);
+        if (S_hi == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) part[j][i][v] = 0.f;
+                    asm volatile("" : "+a"(part[j][i]));
+                }
+        }
+        if (S_lo > 0) {
+            for (; sg < issue_end; ++sg) stage(LO{}, LO{}, YES{}, sg);
+            for (; sg < S; ++sg) stage(LO{}, LO{}, NO{}, sg);
+            lds_wait_all(py);
+            wait_loads_and_barrier<0>();
+            fold(LO{}, YES{}, a.dbg_lo);
+
+        }
     }
 
     // ---- write y once --------------------------------------------------------
-    wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
+    // The wave's 64 x 128 bf16 tile sits in LDS; each store instruction writes
+    // four whole 256-byte row segments.
+    __syncthreads();
     const bool fast = ((reinterpret_cast<uintptr_t>(a.y) & 15) == 0) && (a.ldy % 8 == 0) &&
                       (n0 + kBN <= a.L.N);
-    if (fast) {
-        // wave tile (64 tokens x 128 channels, bf16) -> LDS, row-padded; then each
-        // store instruction writes four whole 256-byte row segments
-        uint8_t* mine = lds + wave * (64 * kOutRowBytes);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+    for (int it = 0; it < 16; ++it) {
+        const int row = it * 4 + (lane >> 4);
+        const int64_t m = m0 + wm * 64 + row;
+        const int64_t n = n0 + wn * 128 + (lane & 15) * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(out_stage + row * kOutRowBytes + (lane & 15) * 16);
+        if (m >= a.M) continue;
+        if (fast) {
+            *reinterpret_cast<uint4*>(a.y + m * a.ldy + n) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const uint32_t lo = pack_bf16(part[j][i][vq * 4 + 0], part[j][i][vq * 4 + 1]);
-                    const uint32_t hi = pack_bf16(part[j][i][vq * 4 + 2], part[j][i][vq * 4 + 3]);
-                    const int row = 32 * i + (lane & 31);
-                    const int col = 32 * j + 8 * vq + 4 * (lane >> 5);
-                    *reinterpret_cast<uint2*>(mine + row * kOutRowBytes + col * 2) = make_uint2(lo, hi);
-                }
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < 16; ++it) {
-            const int row = it * 4 + (lane >> 4);
-            const int64_t m = m0 + wm * 64 + row;
-            const uint4 v = *reinterpret_cast<const uint4*>(mine + row * kOutRowBytes + (lane & 15) * 16);
-            if (m < a.M)
-                *reinterpret_cast<uint4*>(a.y + m * a.ldy + n0 + wn * 128 + (lane & 15) * 8) = v;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int64_t m = tok0 + 32 * i;
-            if (m >= a.M) continue;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const int64_t n = ch0 + 32 * j + 8 * vq;
-#pragma unroll
-                    for (int vr = 0; vr < 4; ++vr)
-                        if (n + vr < a.L.N)
-                            a.y[m * a.ldy + n + vr] = (uint16_t)pack_bf16(part[j][i][vq * 4 + vr], 0.f);
-                }
+            for (int e = 0; e < 8; ++e)
+                if (n + e < a.L.N) a.y[m * a.ldy + n + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
         }
     }
 }

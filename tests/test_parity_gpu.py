@@ -69,6 +69,12 @@ def check_layer(oracle, rq, x: torch.Tensor, w: torch.Tensor, r: int, ldy_extra:
         assert np.array_equal(dbg_lo.cpu().numpy().astype(np.int64), ref.acc_lo), "A_lo differs"
     rel = y_within_tolerance(y, ref.y)
     assert rel <= REL_TOL, f"bf16 output off by {rel}"
+    # the same call without the accumulator dump runs the kernel variant that ships
+    y2 = rq.resq_gemm_mixed(act, packed, N, y=torch.zeros_like(ybuf)[:, :N])
+    torch.cuda.synchronize()
+    rel2 = y_within_tolerance(y2, ref.y)
+    assert rel2 <= REL_TOL, f"bf16 output (no dump) off by {rel2}"
+    assert torch.equal(y2, y), "output differs with and without the accumulator dump"
     if ldy_extra:
         assert not ybuf[:, N:].any(), "wrote past N"
     # without the debug outputs the result must be the same
