@@ -574,13 +574,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         const int issue_end = S - kPrefetch;  // stages below this one request a later stage
         int sg = 0;
         if (S_hi > 0) {
-            for (; sg < S_hi - 1 && sg < issue_end; ++sg) stage(HI{}, HI{}, YES{}, sg);
-            for (; sg < S_hi; ++sg) {
-                if (sg < S_hi - 1) stage(HI{}, HI{}, NO{}, sg);
-                else if (sg < issue_end) stage(HI{}, LO{}, YES{}, sg);
-                else stage(HI{}, LO{}, NO{}, sg);
-            }
+            // The last high stage prepares the first low step as if it were a high
+            // one (a plain copy of the packed bytes), so that the loops need no
+            // stage of a mixed kind; the copy is widened in place afterwards.
+            for (; sg < S_hi && sg < issue_end; ++sg) stage(HI{}, HI{}, YES{}, sg);
+            for (; sg < S_hi; ++sg) stage(HI{}, HI{}, NO{}, sg);
             if (S_lo > 0) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    ux.ao[i] = ux.ae[i] & (int)0xF0F0F0F0;
+                    ux.ae[i] = ux.ae[i] & (int)0x0F0F0F0F;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    ux.bo[j] = ux.be[j] & (int)0x0F0F0F0F;
+                    ux.be[j] = ux.be[j] & (int)0xF0F0F0F0;
+                }
                 lds_wait_all(py);  // the reads of the next step are in flight: let them land first
                 fold(HI{}, NO{}, a.dbg_hi);
             } else {
@@ -605,7 +614,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             lds_wait_all(py);
             wait_loads_and_barrier<0>();
             fold(LO{}, YES{}, a.dbg_lo);
-
         }
     }
 
