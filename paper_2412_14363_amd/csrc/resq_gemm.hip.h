@@ -287,7 +287,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             load_to_lds_16B(base + (lo ? a_voff_lo[K] : a_voff_hi[K]), dst + (wave * 2 + K) * kBlockBytes);
         } else {
             const uint8_t* base = b_base + (K - 2) * a.L.group_bytes + (int64_t)sg * kBlockBytes;
-            load_to_lds_16B(base + b_voff, dst + kStageABytes + (wave * 4 + K - 2) * kBlockBytes);
+            // the lane offset is made opaque here so that it is not folded into a per-lane
+            // 64-bit pointer outside the loop: the load takes a scalar base plus a 32-bit offset
+            uint32_t voff = b_voff;
+            asm volatile("" : "+v"(voff));
+            load_to_lds_16B(base + voff, dst + kStageABytes + (wave * 4 + K - 2) * kBlockBytes);
         }
     };
 
