@@ -178,6 +178,15 @@ __device__ __forceinline__ void lds_wait_all(Packed& f) {
                    "+v"(f.fb[3]));
 }
 
+// Wait until at most N LDS reads are outstanding (they return in order); ties the
+// e members of an operand set, which high steps read into directly.
+template <int N>
+__device__ __forceinline__ void lds_wait_operands(Operands& u) {
+    asm volatile("s_waitcnt lgkmcnt(%6)"
+                 : "+v"(u.ae[0]), "+v"(u.ae[1]), "+v"(u.be[0]), "+v"(u.be[1]), "+v"(u.be[2]), "+v"(u.be[3])
+                 : "n"(N));
+}
+
 // blockIdx -> (tile_m, tile_n).  Consecutive workgroup ids land on different
 // XCDs (8 of them, 32 compute units and one L2 each), and an XCD runs its
 // workgroups in id order, 32 at a time.  When the grid allows it, the 32 tiles
@@ -327,6 +336,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         constexpr int K = decltype(k)::value;
         if constexpr (K < 2) lds_read16<K * 2 * kBlockBytes>(f.fa[K], aa);
         else lds_read16<(K - 2) * 2 * kBlockBytes>(f.fb[K - 2], bb);
+    };
+    // the same read into the e members of an operand set (high steps need no widening)
+    auto read_operand = [&](auto k, Operands& u, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
+        constexpr int K = decltype(k)::value;
+        if constexpr (K < 2) lds_read16<K * 2 * kBlockBytes>(u.ae[K], aa);
+        else lds_read16<(K - 2) * 2 * kBlockBytes>(u.be[K - 2], bb);
     };
     // piece P of the widening of one step's fragments: 12 pieces for a low step
     // (one AND over a fragment each), 6 for a high step (a register copy each)
@@ -496,11 +511,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         for (int i = 0; i < ahead; ++i)
             static_for<kLoadsPerStage>([&](auto k) __attribute__((always_inline)) { issue_load(k, i, i); });
         wait_stage_and_barrier(ahead - 1);  // stage 0 (and the epilogue constants) have landed everywhere
-        static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, px, a_off[0], b_off[0]); });
-        lds_wait_all(px);
-        static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, py, a_off[1], b_off[1]); });
-        if (S_hi > 0) static_for<6>([&](auto p) __attribute__((always_inline)) { transform_piece(HI{}, p, px, ux); });
-        else static_for<12>([&](auto p) __attribute__((always_inline)) { transform_piece(LO{}, p, px, ux); });
+        if (S_hi > 0) {
+            // high stages read straight into the operand registers
+            static_for<6>([&](auto k) __attribute__((always_inline)) { read_operand(k, ux, a_off[0], b_off[0]); });
+        } else {
+            static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, px, a_off[0], b_off[0]); });
+            lds_wait_all(px);
+            static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, py, a_off[1], b_off[1]); });
+            static_for<12>([&](auto p) __attribute__((always_inline)) { transform_piece(LO{}, p, px, ux); });
+        }
 
         int buf = 0;
         // One stage = two pipeline slots (reduction steps).  `cur` is the kind of
@@ -573,17 +592,84 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             });
             buf = nxt;
         };
+        // A high stage needs no widening, so its reads go straight into the operand
+        // registers of the step after the one being multiplied (ux and uy take
+        // turns) and the Packed sets are not used.  Invariant at entry: the reads
+        // of (sg, step 0) into ux have been issued.  Per slot, 8 matrix
+        // instructions M0..M7 with the 6 reads of the next step behind M0..M5 and
+        // the waits placed so that each instruction only waits for its own
+        // operands (activations first, then the weight fragments in order):
+        //   before M0: <= 3 reads of this step outstanding; before M2: <= 2, and so
+        //   on, each plus the reads of the next step issued by then.
+        auto stage_hi = [&](auto issue, int sg) __attribute__((always_inline)) {
+            constexpr bool ISSUE = decltype(issue)::value;
+            const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
+            const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
+            const uint32_t here = buf * kStageBytes, shift = nxt * kStageBytes;
+            auto slot = [&](auto second, Operands& use, Operands& fill, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
+                constexpr bool SECOND = decltype(second)::value;
+                __builtin_amdgcn_sched_barrier(0);
+                lds_wait_operands<3>(use);
+                mfma(IC<0>{}, use);
+                read_operand(IC<0>{}, fill, aa, bb);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma(IC<1>{}, use);
+                read_operand(IC<1>{}, fill, aa, bb);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (!SECOND) {
+                    // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
+                    // stages sg + 2 .. sg + 4 may stay in flight
+                    if constexpr (ISSUE) {
+                        wait_loads_and_barrier<3 * kLoadsPerStage>();
+                    } else {
+                        const int rem = S - 2 - sg;
+                        wait_stage_and_barrier(rem > 3 ? 3 : rem);
+                    }
+                }
+                lds_wait_operands<2 + 2>(use);
+                mfma(IC<2>{}, use);
+                read_operand(IC<2>{}, fill, aa, bb);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma(IC<3>{}, use);
+                read_operand(IC<3>{}, fill, aa, bb);
+                if constexpr (ISSUE) issue_load(IC<SECOND ? 3 : 0>{}, sg + kPrefetch, prv);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_wait_operands<1 + 4>(use);
+                mfma(IC<4>{}, use);
+                read_operand(IC<4>{}, fill, aa, bb);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma(IC<5>{}, use);
+                read_operand(IC<5>{}, fill, aa, bb);
+                if constexpr (ISSUE) issue_load(IC<SECOND ? 4 : 1>{}, sg + kPrefetch, prv);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_wait_operands<0 + 6>(use);
+                mfma(IC<6>{}, use);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma(IC<7>{}, use);
+                if constexpr (ISSUE) issue_load(IC<SECOND ? 5 : 2>{}, sg + kPrefetch, prv);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            // slot 0 multiplies (sg, step 0) and reads (sg, step 1); slot 1 multiplies that
+            // and reads (sg + 1, step 0) -- stale LDS past the last stage, harmless
+            slot(std::false_type{}, ux, uy, a_off[1] + here, b_off[1] + here);
+            slot(std::true_type{}, uy, ux, a_off[0] + shift, b_off[0] + shift);
+            buf = nxt;
+        };
         using YES = std::true_type;
         using NO = std::false_type;
         const int issue_end = S - kPrefetch;  // stages below this one request a later stage
         int sg = 0;
         if (S_hi > 0) {
-            // The last high stage prepares the first low step as if it were a high
-            // one (a plain copy of the packed bytes), so that the loops need no
-            // stage of a mixed kind; the copy is widened in place afterwards.
-            for (; sg < S_hi && sg < issue_end; ++sg) stage(HI{}, HI{}, YES{}, sg);
-            for (; sg < S_hi; ++sg) stage(HI{}, HI{}, NO{}, sg);
+            // The last high stage reads the first low step like a high one (its packed
+            // bytes land in ux), so that the loops need no stage of a mixed kind; they
+            // are widened in place afterwards.
+            for (; sg < S_hi && sg < issue_end; ++sg) stage_hi(YES{}, sg);
+            for (; sg < S_hi; ++sg) stage_hi(NO{}, sg);
+            lds_wait_operands<0>(ux);  // the packed bytes of the first low step (or stale ones)
             if (S_lo > 0) {
+                static_for<6>([&](auto k) __attribute__((always_inline)) {
+                    read_frag(k, py, a_off[1] + buf * kStageBytes, b_off[1] + buf * kStageBytes);
+                });
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     ux.ao[i] = ux.ae[i] & (int)0xF0F0F0F0;
@@ -597,7 +683,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                 lds_wait_all(py);  // the reads of the next step are in flight: let them land first
                 fold(HI{}, NO{}, a.dbg_hi);
             } else {
-                lds_wait_all(py);             // reads past the last stage: let them land
                 wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
                 fold(HI{}, YES{}, a.dbg_hi);
             }
