@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace resq {
 
 constexpr int kHadThreads = 256;
@@ -28,6 +30,22 @@ struct HadArgs {
     int spans_per_row;
     float scale;  // 1 / sqrt(b)
 };
+
+// value of lane (l ^ MASK): data-parallel-primitive moves inside a row of 16
+// lanes where the pattern has one (quad permutes for 1 and 2, a rotation by 8),
+// the swizzle unit inside 32 lanes, a general shuffle across the two halves
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float x) {
+    const int xi = __float_as_int(x);
+    int r;
+    if constexpr (MASK == 1) r = __builtin_amdgcn_update_dpp(xi, xi, 0xB1, 0xF, 0xF, false);       // quad_perm [1,0,3,2]
+    else if constexpr (MASK == 2) r = __builtin_amdgcn_update_dpp(xi, xi, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
+    else if constexpr (MASK == 8) r = __builtin_amdgcn_update_dpp(xi, xi, 0x128, 0xF, 0xF, false); // row_ror:8
+    else if constexpr (MASK == 4) r = __builtin_amdgcn_ds_swizzle(xi, 0x101F);                     // xor 4 within 32
+    else if constexpr (MASK == 16) r = __builtin_amdgcn_ds_swizzle(xi, 0x401F);                    // xor 16 within 32
+    else r = __float_as_int(__shfl_xor(x, MASK));
+    return __int_as_float(r);
+}
 
 template <int I>
 __global__ __launch_bounds__(kHadThreads) void hadamard_kernel(const HadArgs a) {
@@ -68,21 +86,22 @@ __global__ __launch_bounds__(kHadThreads) void hadamard_kernel(const HadArgs a) 
                     }
         }
     }
-    // stages across lanes (bits 3..8)
+    // stages across lanes (bits 3..8): new = partner + sign * own, sign = -1 in
+    // the upper lane of a pair
+    auto lane_stage = [&](auto m) __attribute__((always_inline)) {
+        constexpr int MASK = decltype(m)::value;
+        const float sign = (lane & MASK) ? -1.0f : 1.0f;
 #pragma unroll
-    for (int p = 3; p < 9; ++p) {
-        if (p < a.log2b) {
-            const int mask = 1 << (p - 3);
-            const bool upper = lane & mask;
+        for (int i = 0; i < I; ++i)
 #pragma unroll
-            for (int i = 0; i < I; ++i)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float other = __shfl_xor(v[i][j], mask);
-                    v[i][j] = upper ? other - v[i][j] : v[i][j] + other;
-                }
-        }
-    }
+            for (int j = 0; j < 8; ++j) v[i][j] = lane_xor<MASK>(v[i][j]) + sign * v[i][j];
+    };
+    if (a.log2b > 3) lane_stage(std::integral_constant<int, 1>{});
+    if (a.log2b > 4) lane_stage(std::integral_constant<int, 2>{});
+    if (a.log2b > 5) lane_stage(std::integral_constant<int, 4>{});
+    if (a.log2b > 6) lane_stage(std::integral_constant<int, 8>{});
+    if (a.log2b > 7) lane_stage(std::integral_constant<int, 16>{});
+    if (a.log2b > 8) lane_stage(std::integral_constant<int, 32>{});
     // stages across a lane's vectors (bits 9..)
 #pragma unroll
     for (int p = 9; (1 << (p - 9)) < I; ++p) {
