@@ -102,6 +102,8 @@ def main() -> None:
     ap.add_argument("--workload", default="oproj_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--unfused-hadamard", action="store_true",
+                    help="down_proj input: transform and quantize in two kernels instead of one")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU and has no multi-GPU path; "
@@ -140,7 +142,8 @@ def main() -> None:
     packed = [packed0] + [packed0.clone() for _ in range(n_copies - 1)]
     act = rq.ActCodes(s.M, s.K, s.r)
     y = torch.empty((s.M, s.N), dtype=torch.bfloat16, device="cuda")
-    xh = torch.empty_like(xd) if s.hadamard else None
+    fused = s.hadamard and not args.unfused_hadamard
+    xh = torch.empty_like(xd) if s.hadamard and not fused else None
     L = rq.lib()
     st = torch.cuda.current_stream().cuda_stream
 
@@ -150,7 +153,9 @@ def main() -> None:
     hi, lo = s.r > 0, s.K - s.r > 0
     had_args = (xd.data_ptr(), xh.data_ptr() if xh is not None else None, s.K, s.M, s.K, s.r,
                 s.K, 0, st)
-    xq = xh if s.hadamard else xd
+    xq = xh if xh is not None else xd
+    hq_args = (xd.data_ptr(), s.K, s.M, s.K, s.r, 0, ptr(act.q_hi, hi), ptr(act.q_lo, lo),
+               ptr(act.s_hi, hi), ptr(act.s_lo, lo), ptr(act.lo_sum, lo), None, 0, st)
     qa_args = (xq.data_ptr(), s.K, s.M, s.K, s.r, ptr(act.q_hi, hi), ptr(act.q_lo, lo),
                ptr(act.s_hi, hi), ptr(act.s_lo, lo), ptr(act.lo_sum, lo), st)
     gemm_args = [(ptr(act.q_hi, hi), ptr(act.q_lo, lo), ptr(act.s_hi, hi), ptr(act.s_lo, lo),
@@ -161,14 +166,14 @@ def main() -> None:
     def step(i: int, events=None):
         # events: three (start, stop) pairs of hipEvent_t, recorded by the library at
         # the start and end of the kernel each call launches
-        if s.hadamard:
+        if s.hadamard and not fused:
             if events is not None:
                 L.resq_time_next_kernel(*events[0])
             rc = L.resq_online_hadamard(*had_args)
             assert rc == 0, rc
         if events is not None:
             L.resq_time_next_kernel(*events[1])
-        rc = L.resq_quantize_act(*qa_args)
+        rc = L.resq_hadamard_quantize_act(*hq_args) if fused else L.resq_quantize_act(*qa_args)
         assert rc == 0, rc
         if events is not None:
             L.resq_time_next_kernel(*events[2])
@@ -203,7 +208,7 @@ def main() -> None:
     for i in range(args.steps):
         step(i, evs[i])
     torch.cuda.synchronize()
-    had_ms = sum(elapsed_ms(e[0]) for e in evs) / args.steps if s.hadamard else 0.0
+    had_ms = sum(elapsed_ms(e[0]) for e in evs) / args.steps if s.hadamard and not fused else 0.0
     quant_ms = sum(elapsed_ms(e[1]) for e in evs) / args.steps
     gemm_ms = sum(elapsed_ms(e[2]) for e in evs) / args.steps
     for e in evs:
@@ -234,7 +239,9 @@ def main() -> None:
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{s.name}: M={s.M} K={s.K} N={s.N} r={s.r}", "tag": args.workload,
-                   "step": ("hadamard + " if s.hadamard else "") + "quantize_act + gemm_mixed",
+                   "step": ("hadamard_quantize_act (one kernel) + " if fused else
+                            "online_hadamard + quantize_act + " if s.hadamard else
+                            "quantize_act + ") + "gemm_mixed",
                    "weight_copies_rotated": n_copies},
         "tokens_per_s": s.M / (ms_per_step * 1e-3),
         "hadamard_ms": had_ms, "quantize_ms": quant_ms, "gemm_ms": gemm_ms,

@@ -120,6 +120,29 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
                       void* stream);
 
 /*
+ * The online Hadamard projection of the low group (Section 4.3, U_D; see
+ * resq_online_hadamard) fused with resq_quantize_act: the codes, scales and
+ * lo_sum are exactly those of
+ *   resq_online_hadamard(x, t, ..., col_begin = r, col_end = K, block)
+ *   resq_quantize_act(t, ...)
+ * (same butterflies in the same order, same rounding of the rotated values to
+ * bf16 before they are quantized), but the rotated row is not written to memory
+ * and read back: one read of x in all.
+ *   block   power of two in [8, 512] dividing both r and K - r (a block is held
+ *           by one wavefront); 0 selects resq_hadamard_block(K - r).  Other
+ *           sizes: RESQ_ERR_SHAPE, use the two calls above.
+ *   x_rot   null, or bf16 [M, ld_rot] (ld_rot >= K, 16-byte aligned, ld_rot a
+ *           multiple of 8): receives columns [r, K) of the rotated rows, for
+ *           inspection and parity checks; columns [0, r) are not touched.
+ * Needs the vectorized path: x 16-byte aligned, ldx, K, r multiples of 8,
+ * K <= 16384 (else RESQ_ERR_ALIGN).  Other arguments as resq_quantize_act.
+ */
+int resq_hadamard_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                               int64_t block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
+                               float* s_lo, int32_t* lo_sum, void* x_rot, int64_t ld_rot,
+                               void* stream);
+
+/*
  * Offline weight quantization and packing (Section 4.1 Eq. 3; per output
  * channel, symmetric, round-to-nearest, Section 5.1).
  *   w       bf16 [N, ldw], ldw >= K: (out_features, in_features)   (read)

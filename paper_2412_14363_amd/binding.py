@@ -29,6 +29,7 @@ SYMBOLS = {
     "resq_packed_weight_bytes": (_sz, [_i64, _i64, _i64]),
     "resq_hadamard_block": (_i64, [_i64]),
     "resq_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p]),
+    "resq_hadamard_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _i64, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
     "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
     "resq_gemm_mixed": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
@@ -138,6 +139,26 @@ def resq_quantize_act(x: torch.Tensor, r: int, out: Optional[ActCodes] = None,
                                  out.s_lo.data_ptr() if K - r > 0 else None,
                                  out.lo_sum.data_ptr() if K - r > 0 else None, _stream(stream))
     _check(st, "resq_quantize_act")
+    return out
+
+
+def resq_hadamard_quantize_act(x: torch.Tensor, r: int, block: int = 0,
+                               out: Optional[ActCodes] = None,
+                               x_rot: Optional[torch.Tensor] = None, stream=None) -> ActCodes:
+    M, K = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    if x_rot is not None and x_rot.stride(1) != 1:
+        raise ValueError("x_rot must be row-major")
+    if out is None:
+        out = ActCodes(M, K, r, x.device)
+    st = lib().resq_hadamard_quantize_act(
+        _dev(x, torch.bfloat16, "x"), x.stride(0), M, K, r, block,
+        out.q_hi.data_ptr() if r > 0 else None, out.q_lo.data_ptr(),
+        out.s_hi.data_ptr() if r > 0 else None, out.s_lo.data_ptr(), out.lo_sum.data_ptr(),
+        _dev(x_rot, torch.bfloat16, "x_rot"), x_rot.stride(0) if x_rot is not None else 0,
+        _stream(stream))
+    _check(st, "resq_hadamard_quantize_act")
     return out
 
 

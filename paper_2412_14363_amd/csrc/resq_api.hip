@@ -85,8 +85,10 @@ int64_t resq_hadamard_block(int64_t width) {
     return b > 8192 ? 8192 : b;
 }
 
-int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r, int8_t* q_hi,
-                      uint8_t* q_lo, float* s_hi, float* s_lo, int32_t* lo_sum, void* stream) {
+// shared by resq_quantize_act (rot.log2b == 0) and resq_hadamard_quantize_act
+static int quantize_act_impl(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                             int8_t* q_hi, uint8_t* q_lo, float* s_hi, float* s_lo,
+                             int32_t* lo_sum, const RotateArgs& rot, void* stream) {
     if (!shape_ok(M, K, r) || ldx < K) return RESQ_ERR_SHAPE;
     if (!x) return RESQ_ERR_NULL;
     if (r > 0 && (!q_hi || !s_hi)) return RESQ_ERR_NULL;
@@ -99,9 +101,17 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     const dim3 block(kQuantThreads);
     const bool vec = aligned(x, 16) && ldx % 8 == 0 && K % 8 == 0 && r % 8 == 0 && K <= 16384;
-#define RESQ_LAUNCH_QA(ITERS)                                                                   \
-    launch(quantize_act_vec_kernel<ITERS>, dim3((unsigned)M), block, 0, st, xp, ldx, (int)K,    \
-           (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum)
+    const bool rotate = rot.log2b > 0;
+    if (rotate && !vec) return RESQ_ERR_ALIGN;
+#define RESQ_LAUNCH_QA(ITERS)                                                                     \
+    do {                                                                                          \
+        if (rotate)                                                                               \
+            launch(quantize_act_vec_kernel<ITERS, true>, dim3((unsigned)M), block, 0, st, xp, ldx, \
+                   (int)K, (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum, rot);            \
+        else                                                                                      \
+            launch(quantize_act_vec_kernel<ITERS, false>, dim3((unsigned)M), block, 0, st, xp,    \
+                   ldx, (int)K, (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum, rot);       \
+    } while (0)
     if (vec) {
         if (K <= 2048) RESQ_LAUNCH_QA(1);
         else if (K <= 4096) RESQ_LAUNCH_QA(2);
@@ -113,6 +123,32 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
     }
 #undef RESQ_LAUNCH_QA
     return launch_status();
+}
+
+int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r, int8_t* q_hi,
+                      uint8_t* q_lo, float* s_hi, float* s_lo, int32_t* lo_sum, void* stream) {
+    RotateArgs rot{0, 1.0f, nullptr, 0};
+    return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, stream);
+}
+
+int resq_hadamard_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                               int64_t block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
+                               float* s_lo, int32_t* lo_sum, void* x_rot, int64_t ld_rot,
+                               void* stream) {
+    if (!shape_ok(M, K, r) || K - r < 1) return RESQ_ERR_SHAPE;
+    const int64_t width = K - r;
+    if (block == 0) block = resq_hadamard_block(width);
+    if (block < 8 || block > 512 || (block & (block - 1)) != 0 || width % block != 0 || r % block != 0)
+        return RESQ_ERR_SHAPE;
+    if (x_rot && ld_rot < K) return RESQ_ERR_SHAPE;
+    if (x_rot && (!aligned(x_rot, 16) || ld_rot % 8 != 0)) return RESQ_ERR_ALIGN;
+    RotateArgs rot;
+    rot.log2b = 0;
+    while ((int64_t(1) << rot.log2b) < block) ++rot.log2b;
+    rot.scale = 1.0f / sqrtf((float)block);
+    rot.x_rot = static_cast<uint16_t*>(x_rot);
+    rot.ld_rot = ld_rot;
+    return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, stream);
 }
 
 int resq_pack_weights(const void* w, int64_t ldw, int64_t N, int64_t K, int64_t r, void* packed,

@@ -47,6 +47,66 @@ __device__ __forceinline__ float lane_xor(float x) {
     return __int_as_float(r);
 }
 
+// ---- pieces shared with the fused transform + quantize kernel ------------------
+// A lane holds 8 consecutive columns (16 bytes of bf16); column bits 0..2 select
+// the register, bits 3..8 the lane.
+
+__device__ __forceinline__ void unpack8_bf16(const uint4& w, float (&v)[8]) {
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        v[j] = __uint_as_float((j & 1) ? (ww[j >> 1] & 0xFFFF0000u) : (ww[j >> 1] << 16));
+}
+
+// butterfly stages of column bits 0..2 (those below log2b)
+__device__ __forceinline__ void wht_in_lane(float (&v)[8], int log2b) {
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+        if (p < log2b) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (!(j & (1 << p))) {
+                    const float lo = v[j], hi = v[j | (1 << p)];
+                    v[j] = lo + hi;
+                    v[j | (1 << p)] = lo - hi;
+                }
+        }
+    }
+}
+
+// one butterfly stage across lanes: new = partner + sign * own, sign = -1 in
+// the upper lane of a pair
+template <int MASK>
+__device__ __forceinline__ void wht_lane_stage(float (&v)[8], int lane) {
+    const float sign = (lane & MASK) ? -1.0f : 1.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = lane_xor<MASK>(v[j]) + sign * v[j];
+}
+
+// butterfly stages of column bits 3..8 (those below log2b); every lane of the
+// wavefront must call this
+__device__ __forceinline__ void wht_across_lanes(float (&v)[8], int log2b, int lane) {
+    if (log2b > 3) wht_lane_stage<1>(v, lane);
+    if (log2b > 4) wht_lane_stage<2>(v, lane);
+    if (log2b > 5) wht_lane_stage<4>(v, lane);
+    if (log2b > 6) wht_lane_stage<8>(v, lane);
+    if (log2b > 7) wht_lane_stage<16>(v, lane);
+    if (log2b > 8) wht_lane_stage<32>(v, lane);
+}
+
+// scale, round to bf16 (nearest even: the hardware conversion), pack
+typedef float v2f_had __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf_had __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 pack8_bf16(const float (&v)[8], float scale) {
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+        const v2bf_had r = __builtin_convertvector((v2f_had){v[j] * scale, v[j + 1] * scale}, v2bf_had);
+        o[j >> 1] = *reinterpret_cast<const uint32_t*>(&r);
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 template <int I>
 __global__ __launch_bounds__(kHadThreads) void hadamard_kernel(const HadArgs a) {
     const int lane = threadIdx.x & 63;
@@ -65,43 +125,12 @@ __global__ __launch_bounds__(kHadThreads) void hadamard_kernel(const HadArgs a) 
         const int col = base + i * 512 + lane * 8;
         uint4 w = make_uint4(0u, 0u, 0u, 0u);
         if (col < a.c1) w = *reinterpret_cast<const uint4*>(xr + col);
-        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-            v[i][j] = __uint_as_float((j & 1) ? (ww[j >> 1] & 0xFFFF0000u) : (ww[j >> 1] << 16));
+        unpack8_bf16(w, v[i]);
     }
-
-    // stages inside a lane's 8-vector (bits 0..2)
 #pragma unroll
-    for (int p = 0; p < 3; ++p) {
-        if (p < a.log2b) {
+    for (int i = 0; i < I; ++i) wht_in_lane(v[i], a.log2b);
 #pragma unroll
-            for (int i = 0; i < I; ++i)
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (!(j & (1 << p))) {
-                        const float lo = v[i][j], hi = v[i][j | (1 << p)];
-                        v[i][j] = lo + hi;
-                        v[i][j | (1 << p)] = lo - hi;
-                    }
-        }
-    }
-    // stages across lanes (bits 3..8): new = partner + sign * own, sign = -1 in
-    // the upper lane of a pair
-    auto lane_stage = [&](auto m) __attribute__((always_inline)) {
-        constexpr int MASK = decltype(m)::value;
-        const float sign = (lane & MASK) ? -1.0f : 1.0f;
-#pragma unroll
-        for (int i = 0; i < I; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[i][j] = lane_xor<MASK>(v[i][j]) + sign * v[i][j];
-    };
-    if (a.log2b > 3) lane_stage(std::integral_constant<int, 1>{});
-    if (a.log2b > 4) lane_stage(std::integral_constant<int, 2>{});
-    if (a.log2b > 5) lane_stage(std::integral_constant<int, 4>{});
-    if (a.log2b > 6) lane_stage(std::integral_constant<int, 8>{});
-    if (a.log2b > 7) lane_stage(std::integral_constant<int, 16>{});
-    if (a.log2b > 8) lane_stage(std::integral_constant<int, 32>{});
+    for (int i = 0; i < I; ++i) wht_across_lanes(v[i], a.log2b, lane);
     // stages across a lane's vectors (bits 9..)
 #pragma unroll
     for (int p = 9; (1 << (p - 9)) < I; ++p) {
@@ -123,18 +152,7 @@ __global__ __launch_bounds__(kHadThreads) void hadamard_kernel(const HadArgs a) 
 #pragma unroll
     for (int i = 0; i < I; ++i) {
         const int col = base + i * 512 + lane * 8;
-        if (col < a.c1) {
-            uint32_t o[4];
-#pragma unroll
-            for (int j = 0; j < 8; j += 2) {
-                uint32_t lo = __float_as_uint(v[i][j] * a.scale);
-                uint32_t hi = __float_as_uint(v[i][j + 1] * a.scale);
-                lo += 0x7FFFu + ((lo >> 16) & 1u);  // round to nearest even bf16
-                hi += 0x7FFFu + ((hi >> 16) & 1u);
-                o[j >> 1] = (lo >> 16) | (hi & 0xFFFF0000u);
-            }
-            *reinterpret_cast<uint4*>(yr + col) = make_uint4(o[0], o[1], o[2], o[3]);
-        }
+        if (col < a.c1) *reinterpret_cast<uint4*>(yr + col) = pack8_bf16(v[i], a.scale);
     }
 }
 

@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "resq_hadamard.hip.h"
 #include "resq_layout.h"
 
 namespace resq {
@@ -122,11 +123,21 @@ __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint3
     return __builtin_amdgcn_perm(b, a, 0x0c0c0400u) | __builtin_amdgcn_perm(d, c, 0x04000c0cu);
 }
 
-template <int ITERS>
+// Optional block Walsh-Hadamard transform of the low group in front of the
+// quantizer (the online projection of the down_proj input, Section 4.3): the
+// rotated row never goes to memory unless the caller asks for it.
+struct RotateArgs {
+    int log2b;          // 0: no transform; else log2 of the block size, 3..9
+    float scale;        // 1 / sqrt(block)
+    uint16_t* x_rot;    // null, or bf16 [M, ld_rot]: receives columns [r, K) of the rotated row
+    int64_t ld_rot;
+};
+
+template <int ITERS, bool ROTATE>
 __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
     int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
-    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum) {
+    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum, const RotateArgs rot) {
     constexpr int RT = kQuantThreads;     // threads per row
     __shared__ float red[8];
     __shared__ int red_sum[4];
@@ -137,12 +148,37 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
     const uint4* row = reinterpret_cast<const uint4*>(x + m * ldx);
 
     uint4 v[ITERS];
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+        const int u = t + i * RT;
+        v[i] = u < nunits ? row[u] : make_uint4(0u, 0u, 0u, 0u);
+    }
+    if constexpr (ROTATE) {
+        // The same butterflies, in the same order, as the stand-alone transform
+        // kernel, followed by its rounding to bf16: the codes are those of
+        // quantizing that kernel's output.  A block is block/8 consecutive lanes
+        // (r and K - r are multiples of the block), so a wavefront may hold lanes
+        // of the high group too: they take part in the exchanges and keep their
+        // own values.
+        const int lane = t & 63;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            const int u = t + i * RT;
+            float f[8];
+            unpack8_bf16(v[i], f);
+            wht_in_lane(f, rot.log2b);
+            wht_across_lanes(f, rot.log2b, lane);
+            if (u >= hi_units && u < nunits) {
+                v[i] = pack8_bf16(f, rot.scale);
+                if (rot.x_rot) *reinterpret_cast<uint4*>(rot.x_rot + m * rot.ld_rot + (int64_t)u * 8) = v[i];
+            }
+        }
+    }
     float amax_h = 0.0f, amax_l = 0.0f;
 #pragma unroll
     for (int i = 0; i < ITERS; ++i) {
         const int u = t + i * RT;
         if (u < nunits) {
-            v[i] = row[u];
             const float a = absmax8(v[i]);
             if (u < hi_units) amax_h = fmaxf(amax_h, a);
             else amax_l = fmaxf(amax_l, a);
@@ -171,10 +207,11 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
                     make_uint2(pack_low_bytes(c[0], c[1], c[2], c[3]), pack_low_bytes(c[4], c[5], c[6], c[7]));
             } else {
                 quant8<true>(v[i], sl, inv_l, c, odd_f);
-                // byte k = (even code + 8) | (odd code << 4)
+                // byte k = (even code + 8) | (odd code << 4); the even value is 1..15 in
+                // its low byte already, and only the low byte of by[k] is kept
                 uint32_t by[4];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) by[k] = (c[2 * k + 1] << 4) | (c[2 * k] & 0xFu);
+                for (int k = 0; k < 4; ++k) by[k] = (c[2 * k + 1] << 4) | c[2 * k];
                 *reinterpret_cast<uint32_t*>(ql + (int64_t)(u - hi_units) * 4) =
                     pack_low_bytes(by[0], by[1], by[2], by[3]);
             }

@@ -101,6 +101,22 @@ def test_hadamard_rejects_bad_arguments():
     assert h(P + 2, P, 512, 4, 512, 0, 512, 0, None) == 3
 
 
+def test_hadamard_quantize_rejects_bad_arguments():
+    f = binding.lib().resq_hadamard_quantize_act
+    ok = (P, 1024, 4, 1024, 256)
+    assert f(*ok, 3, P, P, P, P, P, None, 0, None) == 2            # block not a power of two
+    assert f(*ok, 1024, P, P, P, P, P, None, 0, None) == 2         # block > 512
+    assert f(*ok, 4, P, P, P, P, P, None, 0, None) == 2            # block < 8
+    assert f(P, 1024, 4, 1024, 128, 256, P, P, P, P, P, None, 0, None) == 2   # block does not divide r
+    assert f(P, 1024, 4, 1024, 1024, 0, P, P, P, P, P, None, 0, None) == 2    # empty low group
+    assert f(P, 16384, 4, 8192 + 2048, 2048, 0, P, P, P, P, P, None, 0, None) == 2   # default block 8192
+    assert f(*ok, 256, P, P, P, P, P, P, 1000, None) == 2          # ld_rot < K
+    assert f(*ok, 256, P, P, P, P, P, P + 8, 1024, None) == 3      # x_rot not 16-byte aligned
+    assert f(P + 2, 1024, 4, 1024, 256, 256, P, P, P, P, P, None, 0, None) == 3      # needs the vector path
+    assert f(None, 1024, 4, 1024, 256, 256, P, P, P, P, P, None, 0, None) == 1
+    assert f(*ok, 256, P, P, P, P, None, None, 0, None) == 1       # lo_sum missing
+
+
 def test_binding_fails_loudly_without_device_tensors():
     import torch
     x = torch.zeros(4, 256, dtype=torch.bfloat16)

@@ -38,6 +38,22 @@ def check_act_codes(oracle, rq, x: torch.Tensor, r: int):
     return act
 
 
+def compare_act_codes(oracle, act, x_bits: np.ndarray, r: int):
+    """Codes, scales and lo_sum in `act` against the oracle's quantizer on x_bits."""
+    M, K = x_bits.shape
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(x_bits, r)
+    if r > 0:
+        want = np.zeros((M, act.ld_hi), np.int8)
+        want[:, :r] = q_hi
+        assert np.array_equal(act.q_hi.cpu().numpy(), want), "INT8 codes differ"
+        assert np.array_equal(act.s_hi.cpu().numpy().view(np.uint32), s_hi.view(np.uint32))
+    if K - r > 0:
+        want = oracle.pack_nibbles(q_lo, act.ld_lo)
+        assert np.array_equal(act.q_lo.cpu().numpy(), want), "INT4 codes differ"
+        assert np.array_equal(act.s_lo.cpu().numpy().view(np.uint32), s_lo.view(np.uint32))
+        assert np.array_equal(act.lo_sum.cpu().numpy(), oracle.odd_code_sums(q_lo)), "lo_sum differs"
+
+
 def check_weights(oracle, rq, w: torch.Tensor, r: int):
     N, K = w.shape
     packed = rq.resq_pack_weights(w.cuda(), r)
@@ -248,3 +264,45 @@ def test_down_proj_path_hadamard_then_quantize(oracle, rq):
     x, w = wl.make_activations(s), wl.make_weights(s)
     xt = check_hadamard(oracle, rq, x, s.r, s.K, 0)
     check_layer(oracle, rq, xt.cpu(), w, s.r)
+
+
+@pytest.mark.parametrize("M,K,r,block", [
+    (5, 1792 + 12544, 1792, 0),      # the down_proj input: 49 blocks of 256
+    (3, 2048, 512, 512), (4, 1024, 256, 64), (3, 4096, 0, 512), (2, 528, 16, 16),
+    (130, 4096, 512, 256), (3, 1024, 512, 8),
+])
+def test_hadamard_quantize_fused(oracle, rq, M, K, r, block):
+    # one kernel: rotate the low group, round to bf16, quantize.  (1) the rotated
+    # values against the oracle's transform (fp32 butterflies vs the fp64
+    # definition); (2) codes, scales and lo_sum bit-exact against the oracle's
+    # quantizer fed the kernel's own rotated row; (3) everything identical to the
+    # two separate kernels.
+    s = wl.LayerShape("hq", M=M, K=K, N=1, r=r, act="student_t3", seed=K + r + M)
+    x = wl.make_activations(s)
+    xd = x.cuda()
+    b = block or rq.resq_hadamard_block(K - r)
+    x_rot = torch.zeros_like(xd)
+    act = rq.resq_hadamard_quantize_act(xd, r, block, x_rot=x_rot)
+    torch.cuda.synchronize()
+    got = wl.bf16_bits(x_rot.cpu())
+    want = oracle.hadamard(wl.bf16_bits(x), r, K, b)
+    assert not got[:, :r].any(), "columns of the high group must not be written"
+    g64, w64 = wl.bits_to_f64(got[:, r:]), wl.bits_to_f64(want[:, r:])
+    scale = np.abs(w64).max()
+    assert np.all(np.abs(g64 - w64) <= np.maximum(np.abs(w64), 2.0 ** -8 * scale) * 2.0 ** -7)
+    assert np.mean(got[:, r:] == want[:, r:]) > 0.99
+    rotated = wl.bf16_bits(x).copy()
+    rotated[:, r:] = got[:, r:]
+    compare_act_codes(oracle, act, rotated, r)
+    y = rq.resq_online_hadamard(xd, r, K, block)
+    act2 = rq.resq_quantize_act(y, r)
+    torch.cuda.synchronize()
+    assert torch.equal(y[:, r:], x_rot[:, r:])
+    for name in ("q_hi", "q_lo", "s_hi", "s_lo", "lo_sum"):
+        if name in ("q_hi", "s_hi") and r == 0:
+            continue
+        assert torch.equal(getattr(act, name), getattr(act2, name)), name
+    # and without the inspection output
+    act3 = rq.resq_hadamard_quantize_act(xd, r, block)
+    torch.cuda.synchronize()
+    assert torch.equal(act3.q_lo, act.q_lo) and torch.equal(act3.s_lo, act.s_lo)
