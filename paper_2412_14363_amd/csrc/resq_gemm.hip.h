@@ -41,10 +41,10 @@
 // the two sums are known per channel (packed with the weights) and per token
 // (written by the quantizer), so A_lo is recovered exactly.
 //
-// Two scale pairs, one output write.  After the last high step the int32 tile is
-// scaled into an fp32 tile that stays in (accumulation) registers, the int32
-// tile is cleared for the low steps, and y is written once, through LDS so that
-// every store instruction writes whole 256-byte row segments.
+// Two scale pairs, one output write.  Each group has its own int32 tile in
+// accumulation registers (2 x 128 per lane); both are folded into the output
+// at the end, and y is written once, through LDS so that every store
+// instruction writes whole 256-byte row segments.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -305,16 +305,30 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     };
 
     // ---- accumulators ----------------------------------------------------------
+    // One int32 tile per group, both in accumulation registers for the whole
+    // kernel (2 x 128), folded into the output together at the end.
     // acc[j][i]: channels 32 j.., tokens 32 i.. of the wave tile.  Lane l holds
     // token (l % 32) and, in element v, channel 8 (v / 4) + 4 (l / 32) + v % 4.
-    v16i acc[4][2];
-    v16f part[4][2];
+    v16i acc_hi[4][2], acc_lo[4][2];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
+            for (int v = 0; v < 16; ++v) {
+                acc_hi[j][i][v] = 0;
+                acc_lo[j][i][v] = 0;
+            }
+
+    // The tile that a loop does not touch stays where it is, in accumulation
+    // registers: stating so in every stage keeps the register allocator from
+    // moving it to ordinary registers and back around the loops (128 moves a time).
+    auto park = [&](v16i (&acc)[4][2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(acc[j][i]));
+    };
 
     // ---- LDS -> register reads ---------------------------------------------------
     // An operand tile is 32 rows x 64 bytes (two blocks).  In step st (0, 1) of a
@@ -359,7 +373,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     };
     // matrix instruction Q of a step (8 per high step, 16 per low step), in an
     // order that keeps two instructions on the same accumulator eight apart
-    auto mfma = [&](auto q, const Operands& u) __attribute__((always_inline)) {
+    auto mfma = [&](auto q, const Operands& u, v16i (&acc)[4][2]) __attribute__((always_inline)) {
         constexpr int Q = decltype(q)::value;
         constexpr int j = (Q & 7) >> 1, i = Q & 1;
         if constexpr (Q < 8)
@@ -374,65 +388,30 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     const int cl = wn * 128 + (lane >> 5) * 4;
     uint8_t* const out_stage = lds + wave * (64 * kOutRowBytes);
 
-    // Fold the integer tile of one group into the result:
-    //   value = part + A * s_tok[m] * s_ch[n],
-    // where A is the group's integer sum: the accumulator itself for the high
-    // group; for the low group (acc - 128 * (even_sum[n] + lo_sum[m])) / 16, an
-    // exact division whose 1/16 is folded into the scale outside the debug kernel
-    // (same fp32 product).  Not FINAL: part = value, acc = 0 (part then stays in
-    // accumulation registers while the low steps need the ordinary ones for
-    // operands).  FINAL: value is rounded to bf16 and staged in LDS, row-padded,
-    // for the row-segment stores.
-    auto fold = [&](auto is_lo, auto is_final, int32_t* dbg) __attribute__((always_inline)) {
-        constexpr bool LOW = decltype(is_lo)::value, FINAL = decltype(is_final)::value;
-        // The constants come from LDS.  FINAL: no direct-to-LDS load is in flight
-        // any more, ordinary loads.  Otherwise: untracked reads, each batch fused
-        // with its wait in one asm statement so that the registers are valid
-        // wherever the compiler can see them.
-        constexpr int kTok = LOW ? kMetaSLo : kMetaSHi, kSc = LOW ? kMetaSwLo : kMetaSwHi;
-        int st_bits[2], ca[2] = {0, 0};
-        v2i sc[4][4];
-        v4i ev[4][4];
-        if constexpr (FINAL) {
-            const uint8_t* meta = lds + kMetaOff;
+    // Fold both integer tiles into the output:
+    //   y = A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n]
+    // A_hi is its accumulator; A_lo = (acc_lo - 128 * (even_sum[n] + lo_sum[m])) / 16,
+    // an exact division whose 1/16 is folded into the scale outside the debug
+    // kernel (same fp32 product).  The result is rounded to bf16 and staged in
+    // LDS, row-padded, for the row-segment stores.  The constants come from LDS
+    // (no direct-to-LDS load is in flight any more: ordinary loads).
+    auto fold = [&](auto has_hi, auto has_lo) __attribute__((always_inline)) {
+        constexpr bool HI_ON = decltype(has_hi)::value, LO_ON = decltype(has_lo)::value;
+        const uint8_t* meta = lds + kMetaOff;
+        float st_hi[2] = {0.f, 0.f}, st_lo[2] = {0.f, 0.f};
+        int ca[2] = {0, 0};
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                st_bits[i] = *reinterpret_cast<const int*>(meta + kTok + (tl + 32 * i) * 4);
-                if constexpr (LOW) ca[i] = *reinterpret_cast<const int*>(meta + kMetaLoSum + (tl + 32 * i) * 4);
+        for (int i = 0; i < 2; ++i) {
+            if constexpr (HI_ON) st_hi[i] = *reinterpret_cast<const float*>(meta + kMetaSHi + (tl + 32 * i) * 4);
+            if constexpr (LO_ON) {
+                st_lo[i] = *reinterpret_cast<const float*>(meta + kMetaSLo + (tl + 32 * i) * 4);
+                if constexpr (!DBG) st_lo[i] *= 0.0625f;
+                ca[i] = 128 * *reinterpret_cast<const int*>(meta + kMetaLoSum + (tl + 32 * i) * 4);
             }
-        } else {
-            static_assert(!LOW, "the low group is folded last");
-            asm volatile("ds_read_b32 %0, %2\n\tds_read_b32 %1, %2 offset:128\n\ts_waitcnt lgkmcnt(0)"
-                         : "=&v"(st_bits[0]), "=&v"(st_bits[1])
-                         : "v"(lds0 + kMetaOff + kTok + tl * 4));
         }
-        auto fetch = [&](auto jj) __attribute__((always_inline)) {
-            constexpr int j = decltype(jj)::value;
-            if constexpr (FINAL) {
-                const uint8_t* meta = lds + kMetaOff;
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const int c = cl + 32 * j + 8 * vq;
-                    sc[j][vq] = *reinterpret_cast<const v2i*>(meta + kSc + c * 2);
-                    if constexpr (LOW) ev[j][vq] = *reinterpret_cast<const v4i*>(meta + kMetaEven + c * 4);
-                }
-            } else {
-                v2i r0, r1, r2, r3;
-                const uint32_t addr = lds0 + kMetaOff + kSc + cl * 2;
-                asm volatile("ds_read_b64 %0, %4 offset:%5\n\tds_read_b64 %1, %4 offset:%6\n\t"
-                             "ds_read_b64 %2, %4 offset:%7\n\tds_read_b64 %3, %4 offset:%8\n\t"
-                             "s_waitcnt lgkmcnt(0)"
-                             : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
-                             : "v"(addr), "n"((32 * j + 0) * 2), "n"((32 * j + 8) * 2),
-                               "n"((32 * j + 16) * 2), "n"((32 * j + 24) * 2));
-                sc[j][0] = r0;
-                sc[j][1] = r1;
-                sc[j][2] = r2;
-                sc[j][3] = r3;
-            }
-        };
         // debug dump of the integer sums: row pointers and the number of valid columns from cl on
-        int32_t* dbg_row[2] = {nullptr, nullptr};
+        int32_t* dbg_row_hi[2] = {nullptr, nullptr};
+        int32_t* dbg_row_lo[2] = {nullptr, nullptr};
         bool dbg_ok[2] = {false, false};
         int dbg_cols = 0;
         if constexpr (DBG) {
@@ -440,65 +419,62 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int64_t m = m0 + tl + 32 * i;
-                dbg_ok[i] = dbg != nullptr && m < a.M;
-                dbg_row[i] = dbg + m * a.L.N + n0 + cl;
+                dbg_ok[i] = m < a.M;
+                dbg_row_hi[i] = a.dbg_hi + m * a.L.N + n0 + cl;
+                dbg_row_lo[i] = a.dbg_lo + m * a.L.N + n0 + cl;
             }
         }
-        float st[2];
-        static_for<4>([&](auto jj) __attribute__((always_inline)) {
-            constexpr int j = decltype(jj)::value;
-            fetch(jj);
-            if constexpr (j == 0) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    st[i] = __int_as_float(st_bits[i]);
-                    if constexpr (LOW) {
-                        ca[i] *= 128;
-                        if constexpr (!DBG) st[i] *= 0.0625f;
-                    }
-                }
-            }
+        for (int j = 0; j < 4; ++j) {
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
-                const v4h h = *reinterpret_cast<const v4h*>(&sc[j][vq]);
-                const float sn[4] = {(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+                const int c = cl + 32 * j + 8 * vq;
+                float sn_hi[4] = {0.f, 0.f, 0.f, 0.f}, sn_lo[4] = {0.f, 0.f, 0.f, 0.f};
+                v4i ev = {0, 0, 0, 0};
+                if constexpr (HI_ON) {
+                    const v4h h = *reinterpret_cast<const v4h*>(meta + kMetaSwHi + c * 2);
+#pragma unroll
+                    for (int vr = 0; vr < 4; ++vr) sn_hi[vr] = (float)h[vr];
+                }
+                if constexpr (LO_ON) {
+                    const v4h h = *reinterpret_cast<const v4h*>(meta + kMetaSwLo + c * 2);
+#pragma unroll
+                    for (int vr = 0; vr < 4; ++vr) sn_lo[vr] = (float)h[vr];
+                    ev = *reinterpret_cast<const v4i*>(meta + kMetaEven + c * 4);
+                }
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     float val[4];
 #pragma unroll
                     for (int vr = 0; vr < 4; ++vr) {
                         const int v = vq * 4 + vr;
-                        int iv = acc[j][i][v];
-                        if constexpr (LOW) {
-                            iv -= ev[j][vq][vr] * 128 + ca[i];
-                            if constexpr (DBG) iv >>= 4;
+                        val[vr] = 0.f;
+                        if constexpr (HI_ON) {
+                            const int ih = acc_hi[j][i][v];
+                            val[vr] = (float)ih * (st_hi[i] * sn_hi[vr]);
+                            if constexpr (DBG) {
+                                if (a.dbg_hi && dbg_ok[i] && 32 * j + 8 * vq + vr < dbg_cols)
+                                    dbg_row_hi[i][32 * j + 8 * vq + vr] = ih;
+                            }
                         }
-                        val[vr] = (float)iv * (st[i] * sn[vr]);
-                        if constexpr (LOW) val[vr] += part[j][i][v];
-                        if constexpr (DBG) {
-                            if (dbg_ok[i] && 32 * j + 8 * vq + vr < dbg_cols) dbg_row[i][32 * j + 8 * vq + vr] = iv;
-                        }
-                        if constexpr (!FINAL) {
-                            part[j][i][v] = val[vr];
-                            acc[j][i][v] = 0;
+                        if constexpr (LO_ON) {
+                            int il = acc_lo[j][i][v] - (ev[vr] * 128 + ca[i]);
+                            if constexpr (DBG) il >>= 4;
+                            val[vr] += (float)il * (st_lo[i] * sn_lo[vr]);
+                            if constexpr (DBG) {
+                                if (a.dbg_lo && dbg_ok[i] && 32 * j + 8 * vq + vr < dbg_cols)
+                                    dbg_row_lo[i][32 * j + 8 * vq + vr] = il;
+                            }
                         }
                     }
-                    if constexpr (FINAL) {
-                        const int row = 32 * i + (lane & 31);
-                        const int col = 32 * j + 8 * vq + 4 * (lane >> 5);
-                        *reinterpret_cast<uint2*>(out_stage + row * kOutRowBytes + col * 2) =
-                            make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
-                    }
+                    const int row = 32 * i + (lane & 31);
+                    const int col = 32 * j + 8 * vq + 4 * (lane >> 5);
+                    *reinterpret_cast<uint2*>(out_stage + row * kOutRowBytes + col * 2) =
+                        make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
                 }
             }
-            // the fp32 tile goes to accumulation registers at once: the ordinary
-            // ones are needed for the operands of the low steps
-            if constexpr (!FINAL) {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(part[j][i]));
-            }
             __builtin_amdgcn_sched_barrier(0);
-        });
+        }
     };
 
     // ---- main loop ---------------------------------------------------------------
@@ -546,8 +522,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
             const uint32_t shift = nxt * kStageBytes;
             // invariant: ux = operands of (sg, step 0); py = reads of (sg, step 1) in flight
+            park(acc_hi);
             __builtin_amdgcn_sched_barrier(0);
-            static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, ux); });
+            static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, ux, acc_lo); });
             __builtin_amdgcn_sched_barrier(0);
             // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
             // stages sg + 2 .. sg + 4 may stay in flight
@@ -561,7 +538,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             __builtin_amdgcn_sched_barrier(0);
             static_for<NM - PRE>([&](auto g) __attribute__((always_inline)) {
                 constexpr int G = decltype(g)::value;
-                mfma(IC<PRE + G>{}, ux);
+                mfma(IC<PRE + G>{}, ux, acc_lo);
                 // past the last stage the reads fetch stale LDS: harmless
                 if constexpr (G < 6) read_frag(g, px, a_off[0] + shift, b_off[0] + shift);
                 if constexpr (G < NT_CUR) transform_piece(cur, g, py, uy);
@@ -573,13 +550,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                     issue_load(IC<G / LD_EVERY>{}, sg + kPrefetch, prv);
                 __builtin_amdgcn_sched_barrier(0);
             });
-            static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, uy); });
+            static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, uy, acc_lo); });
             __builtin_amdgcn_sched_barrier(0);
             lds_wait_all(px);
             __builtin_amdgcn_sched_barrier(0);
             static_for<NM - PRE>([&](auto g) __attribute__((always_inline)) {
                 constexpr int G = decltype(g)::value;
-                mfma(IC<PRE + G>{}, uy);
+                mfma(IC<PRE + G>{}, uy, acc_lo);
                 if constexpr (G < 6) read_frag(g, py, a_off[1] + shift, b_off[1] + shift);
                 if constexpr (G < NT_NEXT) transform_piece(next, g, px, ux);
                 if constexpr (NT_NEXT > NM - PRE && G == NM - PRE - 1)
@@ -606,14 +583,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
             const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
             const uint32_t here = buf * kStageBytes, shift = nxt * kStageBytes;
+            park(acc_lo);
             auto slot = [&](auto second, Operands& use, Operands& fill, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
                 constexpr bool SECOND = decltype(second)::value;
                 __builtin_amdgcn_sched_barrier(0);
                 lds_wait_operands<3>(use);
-                mfma(IC<0>{}, use);
+                mfma(IC<0>{}, use, acc_hi);
                 read_operand(IC<0>{}, fill, aa, bb);
                 __builtin_amdgcn_sched_barrier(0);
-                mfma(IC<1>{}, use);
+                mfma(IC<1>{}, use, acc_hi);
                 read_operand(IC<1>{}, fill, aa, bb);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (!SECOND) {
@@ -627,25 +605,25 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                     }
                 }
                 lds_wait_operands<2 + 2>(use);
-                mfma(IC<2>{}, use);
+                mfma(IC<2>{}, use, acc_hi);
                 read_operand(IC<2>{}, fill, aa, bb);
                 __builtin_amdgcn_sched_barrier(0);
-                mfma(IC<3>{}, use);
+                mfma(IC<3>{}, use, acc_hi);
                 read_operand(IC<3>{}, fill, aa, bb);
                 if constexpr (ISSUE) issue_load(IC<SECOND ? 3 : 0>{}, sg + kPrefetch, prv);
                 __builtin_amdgcn_sched_barrier(0);
                 lds_wait_operands<1 + 4>(use);
-                mfma(IC<4>{}, use);
+                mfma(IC<4>{}, use, acc_hi);
                 read_operand(IC<4>{}, fill, aa, bb);
                 __builtin_amdgcn_sched_barrier(0);
-                mfma(IC<5>{}, use);
+                mfma(IC<5>{}, use, acc_hi);
                 read_operand(IC<5>{}, fill, aa, bb);
                 if constexpr (ISSUE) issue_load(IC<SECOND ? 4 : 1>{}, sg + kPrefetch, prv);
                 __builtin_amdgcn_sched_barrier(0);
                 lds_wait_operands<0 + 6>(use);
-                mfma(IC<6>{}, use);
+                mfma(IC<6>{}, use, acc_hi);
                 __builtin_amdgcn_sched_barrier(0);
-                mfma(IC<7>{}, use);
+                mfma(IC<7>{}, use, acc_hi);
                 if constexpr (ISSUE) issue_load(IC<SECOND ? 5 : 2>{}, sg + kPrefetch, prv);
                 __builtin_amdgcn_sched_barrier(0);
             };
@@ -680,30 +658,17 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                     ux.bo[j] = ux.be[j] & (int)0x0F0F0F0F;
                     ux.be[j] = ux.be[j] & (int)0xF0F0F0F0;
                 }
-                lds_wait_all(py);  // the reads of the next step are in flight: let them land first
-                fold(HI{}, NO{}, a.dbg_hi);
-            } else {
-                wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
-                fold(HI{}, YES{}, a.dbg_hi);
             }
-        }
-        if (S_hi == 0) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) part[j][i][v] = 0.f;
-                    asm volatile("" : "+a"(part[j][i]));
-                }
         }
         if (S_lo > 0) {
             for (; sg < issue_end; ++sg) stage(LO{}, LO{}, YES{}, sg);
             for (; sg < S; ++sg) stage(LO{}, LO{}, NO{}, sg);
-            lds_wait_all(py);
-            wait_loads_and_barrier<0>();
-            fold(LO{}, YES{}, a.dbg_lo);
+            lds_wait_all(py);  // reads past the last stage: let them land
         }
+        wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
+        if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{});
+        else if (S_hi > 0) fold(YES{}, NO{});
+        else fold(NO{}, YES{});
     }
 
     // ---- write y once --------------------------------------------------------
