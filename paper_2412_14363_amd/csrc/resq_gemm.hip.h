@@ -24,10 +24,12 @@
 // asm) and paired with an explicit wait: reads the compiler can see would each
 // be preceded by a wait for every direct-to-LDS load still in flight.
 //
-// Software pipeline, per reduction step k:  read(k+2) | transform(k+1) | multiply(k)
-// where transform widens nibbles for a low step (and is a register copy for a
-// high step), so that the matrix instructions of step k never wait for the
-// vector ALU work of their own operands.
+// Software pipeline.  Low steps: read(k+2) | widen(k+1) | multiply(k), so that
+// the matrix instructions of step k never wait for the vector ALU work of
+// their own operands.  High steps need no widening: read(k+1) lands in the
+// operand registers themselves while step k is multiplied.  The epilogue's
+// per-channel and per-token constants (3.5 KiB) are fetched into LDS by the
+// first loads of the kernel.
 //
 // The low group.  A lane's 16 packed bytes hold 32 codes, and each nibble is
 // widened to an int8 operand with one AND (the vector ALU has room for about
@@ -357,19 +359,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         if constexpr (K < 2) lds_read16<K * 2 * kBlockBytes>(u.ae[K], aa);
         else lds_read16<(K - 2) * 2 * kBlockBytes>(u.be[K - 2], bb);
     };
-    // piece P of the widening of one step's fragments: 12 pieces for a low step
-    // (one AND over a fragment each), 6 for a high step (a register copy each)
-    auto transform_piece = [&](auto is_lo, auto p, const Packed& f, Operands& u) __attribute__((always_inline)) {
+    // piece P (0..11) of the widening of one low step's fragments: one AND over a fragment
+    auto widen_piece = [&](auto p, const Packed& f, Operands& u) __attribute__((always_inline)) {
         constexpr int P = decltype(p)::value;
-        if constexpr (decltype(is_lo)::value) {
-            if constexpr (P < 2) u.ae[P] = f.fa[P] & (int)0x0F0F0F0F;           // even columns: code + 8
-            else if constexpr (P < 4) u.ao[P - 2] = f.fa[P - 2] & (int)0xF0F0F0F0;  // odd columns: 16 * code
-            else if constexpr (P < 8) u.be[P - 4] = f.fb[P - 4] & (int)0xF0F0F0F0;  // even columns: 16 * code
-            else if constexpr (P < 12) u.bo[P - 8] = f.fb[P - 8] & (int)0x0F0F0F0F;  // odd columns: code + 8
-        } else {
-            if constexpr (P < 2) u.ae[P] = f.fa[P];
-            else if constexpr (P < 6) u.be[P - 2] = f.fb[P - 2];
-        }
+        if constexpr (P < 2) u.ae[P] = f.fa[P] & (int)0x0F0F0F0F;           // even columns: code + 8
+        else if constexpr (P < 4) u.ao[P - 2] = f.fa[P - 2] & (int)0xF0F0F0F0;  // odd columns: 16 * code
+        else if constexpr (P < 8) u.be[P - 4] = f.fb[P - 4] & (int)0xF0F0F0F0;  // even columns: 16 * code
+        else u.bo[P - 8] = f.fb[P - 8] & (int)0x0F0F0F0F;                        // odd columns: code + 8
     };
     // matrix instruction Q of a step (8 per high step, 16 per low step), in an
     // order that keeps two instructions on the same accumulator eight apart
@@ -478,8 +474,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     };
 
     // ---- main loop ---------------------------------------------------------------
-    using HI = std::false_type;
-    using LO = std::true_type;
     {
         Packed px, py;
         Operands ux, uy;
@@ -494,34 +488,32 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, px, a_off[0], b_off[0]); });
             lds_wait_all(px);
             static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, py, a_off[1], b_off[1]); });
-            static_for<12>([&](auto p) __attribute__((always_inline)) { transform_piece(LO{}, p, px, ux); });
+            static_for<12>([&](auto p) __attribute__((always_inline)) { widen_piece(p, px, ux); });
         }
 
         int buf = 0;
-        // One stage = two pipeline slots (reduction steps).  `cur` is the kind of
-        // this stage's steps, `next` the kind of the next stage's first step;
-        // ISSUE: this stage requests stage sg + kPrefetch (every stage but the
-        // last kPrefetch ones).  A slot is a fixed sequence of groups, one matrix
-        // instruction each, with the slot's other work dealt out among them so that
-        // it issues in the shadow of the matrix pipeline (about four vector ALU
-        // instructions, or a read and a load, fit behind one matrix instruction):
-        //   slot 0: multiply step 0 | wait + barrier after PRE groups | then per group one
+        // A low stage = two pipeline slots (reduction steps) of 16 matrix
+        // instructions.  ISSUE: this stage requests stage sg + kPrefetch (every
+        // stage but the last kPrefetch ones).  A slot is a fixed sequence of groups,
+        // one matrix instruction each, with the slot's other work dealt out among
+        // them so that it issues in the shadow of the matrix pipeline (about four
+        // vector ALU instructions, or a read and a load, fit behind one matrix
+        // instruction):
+        //   slot 0: multiply step 0 | wait + barrier after 4 groups | then per group one
         //           LDS read of the next stage's step 0 and one piece of step 1's widening
         //   slot 1: multiply step 1 | per group one LDS read of the next stage's step 1 and
         //           one piece of the next step 0's widening
-        // and the stage's six global loads at even distances after the barrier: the
-        // four waves run in step, and loads issued in a burst back up the memory
-        // pipeline (19 clocks per load) until the waves stall on issue.
-        auto stage = [&](auto cur, auto next, auto issue, int sg) __attribute__((always_inline)) {
-            constexpr bool CUR_LO = decltype(cur)::value, ISSUE = decltype(issue)::value;
-            constexpr int NM = CUR_LO ? 16 : 8;   // matrix instructions per step
-            constexpr int PRE = CUR_LO ? 4 : 2;   // ... of which this many go first
-            constexpr int NT_CUR = CUR_LO ? 12 : 6, NT_NEXT = decltype(next)::value ? 12 : 6;
+        // and the stage's six global loads at even distances after the barrier.
+        // Invariant at entry: ux = operands of (sg, step 0); the reads of (sg, step 1)
+        // into py are in flight.
+        auto stage_lo = [&](auto issue, int sg) __attribute__((always_inline)) {
+            constexpr bool ISSUE = decltype(issue)::value;
+            constexpr int NM = 16;               // matrix instructions per step
+            constexpr int PRE = 4;               // ... of which this many go before the barrier
             constexpr int LD_EVERY = (NM - PRE) / 3;  // a global load every so many groups, three per slot
             const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
             const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
             const uint32_t shift = nxt * kStageBytes;
-            // invariant: ux = operands of (sg, step 0); py = reads of (sg, step 1) in flight
             park(acc_hi);
             __builtin_amdgcn_sched_barrier(0);
             static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, ux, acc_lo); });
@@ -541,12 +533,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                 mfma(IC<PRE + G>{}, ux, acc_lo);
                 // past the last stage the reads fetch stale LDS: harmless
                 if constexpr (G < 6) read_frag(g, px, a_off[0] + shift, b_off[0] + shift);
-                if constexpr (G < NT_CUR) transform_piece(cur, g, py, uy);
-                if constexpr (NT_CUR > NM - PRE && G == NM - PRE - 1)
-                    static_for<NT_CUR - (NM - PRE)>([&](auto e) __attribute__((always_inline)) {
-                        transform_piece(cur, IC<NM - PRE + decltype(e)::value>{}, py, uy);
-                    });
-                if constexpr (ISSUE && G % LD_EVERY == LD_EVERY - 1 && G / LD_EVERY < 3)
+                widen_piece(g, py, uy);
+                if constexpr (ISSUE && G % LD_EVERY == LD_EVERY - 1)
                     issue_load(IC<G / LD_EVERY>{}, sg + kPrefetch, prv);
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -558,12 +546,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                 constexpr int G = decltype(g)::value;
                 mfma(IC<PRE + G>{}, uy, acc_lo);
                 if constexpr (G < 6) read_frag(g, py, a_off[1] + shift, b_off[1] + shift);
-                if constexpr (G < NT_NEXT) transform_piece(next, g, px, ux);
-                if constexpr (NT_NEXT > NM - PRE && G == NM - PRE - 1)
-                    static_for<NT_NEXT - (NM - PRE)>([&](auto e) __attribute__((always_inline)) {
-                        transform_piece(next, IC<NM - PRE + decltype(e)::value>{}, px, ux);
-                    });
-                if constexpr (ISSUE && G % LD_EVERY == LD_EVERY - 1 && G / LD_EVERY < 3)
+                widen_piece(g, px, ux);
+                if constexpr (ISSUE && G % LD_EVERY == LD_EVERY - 1)
                     issue_load(IC<3 + G / LD_EVERY>{}, sg + kPrefetch, prv);
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -661,8 +645,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             }
         }
         if (S_lo > 0) {
-            for (; sg < issue_end; ++sg) stage(LO{}, LO{}, YES{}, sg);
-            for (; sg < S; ++sg) stage(LO{}, LO{}, NO{}, sg);
+            for (; sg < issue_end; ++sg) stage_lo(YES{}, sg);
+            for (; sg < S; ++sg) stage_lo(NO{}, sg);
             lds_wait_all(py);  // reads past the last stage: let them land
         }
         wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
