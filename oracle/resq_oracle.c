@@ -20,6 +20,9 @@
  *   - the round in Eq. 1 is round-half-to-even of the fp32 quotient x / s;
  *     the clip is to [-(2^(N-1)-1), 2^(N-1)-1]
  *   - an all-zero group gets scale 1
+ *   - the asymmetric branch of Eq. 1 (activations only, the setting of Section
+ *     5.1): z = min, s = (max - min) / (2^N - 1), unsigned codes 0 .. 2^N - 1,
+ *     the difference x - z and the quotient both rounded to fp32
  *   - weight scales are stored in fp16, rounded toward +inf from the fp32
  *     quotient (so that no code can exceed the clip) and clamped to the fp16
  *     normal range; weight codes are computed with the stored value
@@ -153,6 +156,96 @@ void oracle_quantize_act(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, i
             s_lo[m] = s;
             for (int64_t k = 0; k < kl; ++k)
                 q_lo[m * kl + k] = (int8_t)quant_code(bf16_to_f32(row[r + k]), s, QMAX_L);
+        }
+    }
+}
+
+/*
+ * Asymmetric branch of Eq. 1 (Section 3), the setting of the paper's own
+ * experiments for activations (Section 5.1, per token), applied to each group
+ * of Eq. 2 separately:
+ *   z = min(x),  s = (max(x) - min(x)) / (2^N - 1),
+ *   code = clip(round((x - z) / s), 0, 2^N - 1),   x ~ code * s + z.
+ * The difference and the quotient are fp32 IEEE operations, the round is half
+ * to even, as for the symmetric branch; a constant group (max = min) gets s = 1
+ * and codes 0.  Codes are returned unsigned, one per byte.
+ */
+static void quantize_group_asym(const uint16_t* v, int64_t n, int levels, uint8_t* q, float* s_out,
+                                float* z_out) {
+    float mn = bf16_to_f32(v[0]), mx = mn;
+    for (int64_t k = 1; k < n; ++k) {
+        float a = bf16_to_f32(v[k]);
+        if (a < mn) mn = a;
+        if (a > mx) mx = a;
+    }
+    volatile float range = mx - mn;
+    float s = range == 0.0f ? 1.0f : range / (float)levels;
+    for (int64_t k = 0; k < n; ++k) {
+        volatile float d = bf16_to_f32(v[k]) - mn; /* volatile: rounded to fp32 */
+        volatile float t = d / s;
+        float c = nearbyintf(t);
+        if (c < 0.0f) c = 0.0f;
+        if (c > (float)levels) c = (float)levels;
+        q[k] = (uint8_t)c;
+    }
+    *s_out = s;
+    *z_out = mn;
+}
+
+void oracle_quantize_act_asym(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                              uint8_t* q_hi, uint8_t* q_lo, float* s_hi, float* s_lo,
+                              float* z_hi, float* z_lo) {
+    const int64_t kl = K - r;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t* row = x + m * ldx;
+        if (r > 0) quantize_group_asym(row, r, 255, q_hi + m * r, s_hi + m, z_hi + m);
+        if (kl > 0) quantize_group_asym(row + r, kl, 15, q_lo + m * kl, s_lo + m, z_lo + m);
+    }
+}
+
+/*
+ * Integer GEMM of unsigned activation codes with signed weight codes:
+ * acc[m, n] = sum_k a[m, k] * b[n, k], exact in int64 (Eq. 4 with the codes of
+ * the asymmetric quantizer).
+ */
+void oracle_gemm_u8i8_i64(const uint8_t* a, int64_t lda, const int8_t* b, int64_t ldb, int64_t M,
+                          int64_t N, int64_t Kc, int64_t* acc) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < Kc; ++k)
+                s += (int64_t)a[m * lda + k] * (int64_t)b[n * ldb + k];
+            acc[m * N + n] = s;
+        }
+    }
+}
+
+/*
+ * Dequantization with asymmetric activations: inserting x ~ q s + z (Eq. 1)
+ * and w ~ c sw into Eq. 4 gives, per group,
+ *   y[m, n] += sw[n] * ( s[m] * sum_k q[m, k] c[n, k]  +  z[m] * sum_k c[n, k] ),
+ * evaluated in fp64 from the fp32 scales and zero-points.  acc_* are the sums
+ * over the unsigned codes, wsum_* the per-channel sums of the weight codes.
+ */
+void oracle_dequant_asym(const int64_t* acc_hi, const int64_t* acc_lo, const float* s_hi,
+                         const float* s_lo, const float* z_hi, const float* z_lo,
+                         const int64_t* wsum_hi, const int64_t* wsum_lo, const uint16_t* sw_hi,
+                         const uint16_t* sw_lo, int64_t M, int64_t N, double* y) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double v = 0.0;
+            if (acc_hi)
+                v += (double)fp16_normal_to_f32(sw_hi[n]) *
+                     ((double)s_hi[m] * (double)acc_hi[m * N + n] +
+                      (double)z_hi[m] * (double)wsum_hi[n]);
+            if (acc_lo)
+                v += (double)fp16_normal_to_f32(sw_lo[n]) *
+                     ((double)s_lo[m] * (double)acc_lo[m * N + n] +
+                      (double)z_lo[m] * (double)wsum_lo[n]);
+            y[m * N + n] = v;
         }
     }
 }

@@ -51,6 +51,9 @@ def _load():
         lib.oracle_gemm_i64.restype = i64
         lib.oracle_dequant.argtypes = [p, p, p, p, p, p, i64, i64, p]
         lib.oracle_hadamard.argtypes = [p, p, i64, i64, i64, i64, i64, i64]
+        lib.oracle_quantize_act_asym.argtypes = [p, i64, i64, i64, i64, p, p, p, p, p, p]
+        lib.oracle_gemm_u8i8_i64.argtypes = [p, i64, p, i64, i64, i64, i64, p]
+        lib.oracle_dequant_asym.argtypes = [p, p, p, p, p, p, p, p, p, p, i64, i64, p]
         for f in ("oracle_round_bf16", "oracle_quantize_act", "oracle_quantize_weights",
                   "oracle_pack_nibbles", "oracle_odd_code_sums", "oracle_dequant",
                   "oracle_hadamard"):
@@ -195,6 +198,80 @@ def linear(x_bits: np.ndarray, w_bits: np.ndarray, r: int, weights=None) -> Laye
     y = dequant(acc_hi if r > 0 else None, acc_lo if K - r > 0 else None, s_hi, s_lo, sw_hi,
                 sw_lo)
     return LayerResult(q_hi, q_lo, s_hi, s_lo, w_hi, w_lo, sw_hi, sw_lo, acc_hi, acc_lo, y)
+
+
+# ---- asymmetric activations (the other branch of Eq. 1) ---------------------
+
+def quantize_act_asym(x_bits: np.ndarray, r: int):
+    """Eq. 2 per token with the asymmetric quantizer of Eq. 1.  Returns
+    (q_hi uint8 [M,r] in 0..255, q_lo uint8 [M,K-r] in 0..15, s_hi, s_lo, z_hi, z_lo f32 [M])."""
+    x_bits = _c(x_bits, np.uint16)
+    M, K = x_bits.shape
+    q_hi = np.zeros((M, r), np.uint8)
+    q_lo = np.zeros((M, K - r), np.uint8)
+    s_hi, s_lo = np.ones(M, np.float32), np.ones(M, np.float32)
+    z_hi, z_lo = np.zeros(M, np.float32), np.zeros(M, np.float32)
+    _load().oracle_quantize_act_asym(_ptr(x_bits), K, M, K, r, _ptr(q_hi), _ptr(q_lo), _ptr(s_hi),
+                                     _ptr(s_lo), _ptr(z_hi), _ptr(z_lo))
+    return q_hi, q_lo, s_hi, s_lo, z_hi, z_lo
+
+
+def gemm_u8i8_i64(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """acc[m,n] = sum_k a[m,k] b[n,k] for unsigned a and signed b, exact in int64."""
+    a = _c(a, np.uint8)
+    b = _c(b, np.int8)
+    M, Kc = a.shape
+    N, Kb = b.shape
+    assert Kc == Kb
+    acc = np.zeros((M, N), np.int64)
+    if Kc > 0:
+        _load().oracle_gemm_u8i8_i64(_ptr(a), Kc, _ptr(b), Kc, M, N, Kc, _ptr(acc))
+    return acc
+
+
+def dequant_asym(acc_hi, acc_lo, s_hi, s_lo, z_hi, z_lo, wsum_hi, wsum_lo, sw_hi, sw_lo):
+    """y = sum over groups of sw (s A + z wsum) in fp64; a None accumulator is an empty group."""
+    ref = acc_hi if acc_hi is not None else acc_lo
+    M, N = ref.shape
+    y = np.empty((M, N), np.float64)
+    ah = None if acc_hi is None else _c(acc_hi, np.int64)
+    al = None if acc_lo is None else _c(acc_lo, np.int64)
+    arrs = [_c(v, np.float32) for v in (s_hi, s_lo, z_hi, z_lo)]
+    wsh, wsl = _c(wsum_hi, np.int64), _c(wsum_lo, np.int64)
+    wh, wl = _c(sw_hi, np.uint16), _c(sw_lo, np.uint16)
+    _load().oracle_dequant_asym(_ptr(ah), _ptr(al), *[_ptr(v) for v in arrs], _ptr(wsh), _ptr(wsl),
+                                _ptr(wh), _ptr(wl), M, N, _ptr(y))
+    return y
+
+
+@dataclass
+class AsymLayerResult:
+    q_hi: np.ndarray      # uint8 [M, r], 0..255
+    q_lo: np.ndarray      # uint8 [M, K-r], 0..15
+    s_hi: np.ndarray
+    s_lo: np.ndarray
+    z_hi: np.ndarray      # f32 [M]: min of the group
+    z_lo: np.ndarray
+    wsum_hi: np.ndarray   # int64 [N]: sums of the weight codes
+    wsum_lo: np.ndarray
+    acc_hi: np.ndarray    # int64 [M, N], sums over the unsigned codes
+    acc_lo: np.ndarray
+    y: np.ndarray         # f64 [M, N]
+
+
+def linear_asym(x_bits: np.ndarray, w_bits: np.ndarray, r: int, weights=None) -> AsymLayerResult:
+    """The layer with per-token asymmetric activations (Section 5.1) and the same
+    symmetric per-channel weights."""
+    K = x_bits.shape[1]
+    q_hi, q_lo, s_hi, s_lo, z_hi, z_lo = quantize_act_asym(x_bits, r)
+    w_hi, w_lo, sw_hi, sw_lo = weights if weights is not None else quantize_weights(w_bits, r)
+    acc_hi = gemm_u8i8_i64(q_hi, w_hi)
+    acc_lo = gemm_u8i8_i64(q_lo, w_lo)
+    wsum_hi = w_hi.sum(axis=1, dtype=np.int64)
+    wsum_lo = w_lo.sum(axis=1, dtype=np.int64)
+    y = dequant_asym(acc_hi if r > 0 else None, acc_lo if K - r > 0 else None, s_hi, s_lo, z_hi,
+                     z_lo, wsum_hi, wsum_lo, sw_hi, sw_lo)
+    return AsymLayerResult(q_hi, q_lo, s_hi, s_lo, z_hi, z_lo, wsum_hi, wsum_lo, acc_hi, acc_lo, y)
 
 
 def snr_db(ref: np.ndarray, approx: np.ndarray) -> float:

@@ -414,3 +414,178 @@ def test_theorem_4_2_bound_holds_loosely(oracle):
     lhs = np.linalg.norm(x - xq)
     rhs = c_l * np.linalg.norm(x) - (c_l - c_h) * np.linalg.norm(x[:, :r])
     assert lhs <= rhs
+
+
+# --------------------------------------------------------------------------
+# asymmetric activations: the other branch of Eq. 1 (the setting of Section 5.1)
+# --------------------------------------------------------------------------
+
+def quant_group_asym(oracle, bits, nbits):
+    """Asymmetric quantization of every row of ``bits`` as ONE group."""
+    K = bits.shape[1]
+    if nbits == 8:
+        q, _, s, _, z, _ = oracle.quantize_act_asym(bits, K)
+    else:
+        _, q, _, s, _, z = oracle.quantize_act_asym(bits, 0)
+    return q, s, z
+
+
+def test_asym_quantizer_hand_derived_fixture(oracle):
+    # catches: 2^N levels instead of 2^N - 1, zero-point at max or at 0, round-half-away,
+    # floor, scale from max|x|, a constant group dividing by zero
+    n = 0
+    for nb, xs, sc, zp, qs in _golden_rows("quantizer_asym.txt"):
+        q, s, z = quant_group_asym(oracle, bits_of([[float(v) for v in xs]]), int(nb[0]))
+        assert s[0] == np.float32(float(sc[0])) and z[0] == np.float32(float(zp[0])), (xs, s, z)
+        assert q[0].tolist() == [int(v) for v in qs], (xs, q[0].tolist())
+        n += 1
+    assert n >= 9
+
+
+@pytest.mark.parametrize("nbits", [8, 4])
+@pytest.mark.parametrize("kind,scale,shift", [("normal", 1.0, 0.0), ("t3", 1.0, 0.0),
+                                             ("normal", 3e-3, 0.01), ("normal", 50.0, 300.0)])
+def test_asym_quantizer_error_bound_and_range(oracle, nbits, kind, scale, shift):
+    g = torch.Generator().manual_seed(17)
+    x = torch.randn(48, 80, generator=g) * scale + shift
+    if kind == "t3":
+        x = x / torch.sqrt(torch.randn(48, 80, 3, generator=g).square().sum(-1) / 3)
+    bits = wl.bf16_bits(x.to(torch.bfloat16))
+    x64 = wl.bits_to_f64(bits)
+    q, s, z = quant_group_asym(oracle, bits, nbits)
+    levels = 2 ** nbits - 1
+    for m in range(x64.shape[0]):
+        mn, mx = Fraction(float(x64[m].min())), Fraction(float(x64[m].max()))
+        assert Fraction(float(z[m])) == mn                      # zero-point = min, exactly
+        exact = (mx - mn) / levels                              # scale = correctly rounded (max-min)/levels
+        assert abs(Fraction(float(s[m])) - exact) <= Fraction(float(np.spacing(s[m]))) / 2
+    assert q.min() == 0 and q.max() == levels                   # min -> 0, max -> 2^N - 1
+    assert np.all(q[np.arange(48), x64.argmin(1)] == 0)
+    assert np.all(q[np.arange(48), x64.argmax(1)] == levels)
+    # reconstruction q s + z is within half a step of x (plus fp32 rounding of x - z and of s)
+    rec = q.astype(np.float64) * s.astype(np.float64)[:, None] + z.astype(np.float64)[:, None]
+    step = s.astype(np.float64)[:, None]
+    assert np.all(np.abs(x64 - rec) <= 0.5 * step * (1 + 2.0 ** -18) + np.abs(x64) * 2.0 ** -22)
+    # codes are monotone in x
+    for m in range(0, 48, 7):
+        order = np.argsort(x64[m], kind="stable")
+        assert np.all(np.diff(q[m][order].astype(np.int32)) >= 0)
+
+
+@pytest.mark.parametrize("nbits", [8, 4])
+def test_asym_quantizer_exact_rational_brute_force(oracle, nbits):
+    # values on a coarse dyadic grid: x - z is exact, s is one fp32 rounding of a
+    # rational, and the code is decided exactly unless (x - z) / s is within a few
+    # ulp of a half-integer, which is asserted not to happen for the cases kept
+    levels = 2 ** nbits - 1
+    g = torch.Generator().manual_seed(nbits)
+    x = (torch.randint(-127, 128, (40, 24), generator=g).double() / 8.0)
+    bits = bits_of(x.numpy())
+    q, s, z = quant_group_asym(oracle, bits, nbits)
+    checked = 0
+    for m in range(40):
+        row = [Fraction(float(v)) for v in x[m].tolist()]
+        sm = Fraction(float(s[m]))
+        for k, v in enumerate(row):
+            t = (v - min(row)) / sm
+            frac = t - (t.numerator // t.denominator)
+            if abs(frac - Fraction(1, 2)) < Fraction(1, 1000):
+                continue                                         # too close to a tie for an fp32 quotient
+            assert q[m, k] == min(max(round_half_even(t), 0), levels)
+            checked += 1
+    assert checked > 800
+
+
+def test_asym_quantizer_invariances(oracle):
+    # power-of-two rescaling leaves the codes alone and scales s, z; a shift by a constant
+    # that keeps every value exact shifts z only; negation mirrors the codes
+    g = torch.Generator().manual_seed(3)
+    x = torch.randint(-64, 64, (16, 32), generator=g).double() / 4.0
+    for nbits in (8, 4):
+        levels = 2 ** nbits - 1
+        q, s, z = quant_group_asym(oracle, bits_of(x.numpy()), nbits)
+        q2, s2, z2 = quant_group_asym(oracle, bits_of((x * 8).numpy()), nbits)
+        assert np.array_equal(q, q2) and np.array_equal(s * 8, s2) and np.array_equal(z * 8, z2)
+        q3, s3, z3 = quant_group_asym(oracle, bits_of((x + 16).numpy()), nbits)
+        assert np.array_equal(q, q3) and np.array_equal(s, s3) and np.array_equal(z + 16, z3)
+        q4, s4, z4 = quant_group_asym(oracle, bits_of((-x).numpy()), nbits)
+        # a tie at c + 1/2 goes to the even neighbour on both sides, so mirrored codes may differ by one there
+        assert np.array_equal(s, s4)
+        assert np.all(np.abs(q4.astype(np.int32) - (levels - q.astype(np.int32))) <= 1)
+        assert np.mean(q4 == levels - q) > 0.9
+
+
+def test_asym_groups_are_independent_and_placed(oracle):
+    bits = rand_bits(5, (6, 64), "t3")
+    qh, ql, sh, sl, zh, zl = oracle.quantize_act_asym(bits, 16)
+    q8, _, s8, _, z8, _ = oracle.quantize_act_asym(np.ascontiguousarray(bits[:, :16]), 16)
+    _, q4, _, s4, _, z4 = oracle.quantize_act_asym(np.ascontiguousarray(bits[:, 16:]), 0)
+    assert np.array_equal(qh, q8) and np.array_equal(sh, s8) and np.array_equal(zh, z8)
+    assert np.array_equal(ql, q4) and np.array_equal(sl, s4) and np.array_equal(zl, z4)
+
+
+def test_gemm_u8i8_against_python_loops_and_numpy(oracle):
+    rng = np.random.default_rng(0)
+    a = rng.integers(0, 256, (5, 9), dtype=np.uint8)
+    b = rng.integers(-127, 128, (4, 9)).astype(np.int8)
+    want = [[sum(int(a[m, k]) * int(b[n, k]) for k in range(9)) for n in range(4)] for m in range(5)]
+    assert oracle.gemm_u8i8_i64(a, b).tolist() == want           # catches a transposed index, sign extension of a
+    a = rng.integers(0, 256, (33, 300), dtype=np.uint8)
+    b = rng.integers(-127, 128, (17, 300)).astype(np.int8)
+    assert np.array_equal(oracle.gemm_u8i8_i64(a, b), a.astype(np.int64) @ b.astype(np.int64).T)
+
+
+def test_asym_dequant_equals_reconstruct_then_multiply(oracle):
+    # the factored form  sw (s A + z wsum)  against the definition it comes from:
+    # reconstruct every activation (q s + z) and weight (c sw) and multiply, in exact
+    # rational arithmetic.  catches: a dropped or mis-signed zero-point term, wsum of
+    # the wrong group, scales swapped between groups
+    rng = np.random.default_rng(1)
+    M, N, K, r = 3, 4, 12, 4
+    qh = rng.integers(0, 256, (M, r), dtype=np.uint8)
+    ql = rng.integers(0, 16, (M, K - r), dtype=np.uint8)
+    wh = rng.integers(-127, 128, (N, r)).astype(np.int8)
+    wl_ = rng.integers(-7, 8, (N, K - r)).astype(np.int8)
+    sh = rng.uniform(0.01, 2, M).astype(np.float32); sl = rng.uniform(0.01, 2, M).astype(np.float32)
+    zh = rng.uniform(-5, 5, M).astype(np.float32); zl = rng.uniform(-5, 5, M).astype(np.float32)
+    swh = np.float16(rng.uniform(0.001, 0.1, N)).view(np.uint16)
+    swl = np.float16(rng.uniform(0.001, 0.1, N)).view(np.uint16)
+    y = oracle.dequant_asym(oracle.gemm_u8i8_i64(qh, wh), oracle.gemm_u8i8_i64(ql, wl_), sh, sl, zh, zl,
+                            wh.sum(1, dtype=np.int64), wl_.sum(1, dtype=np.int64), swh, swl)
+    F = lambda v: Fraction(float(v))
+    for m in range(M):
+        for n in range(N):
+            tot = Fraction(0)
+            for k in range(r):
+                tot += (int(qh[m, k]) * F(sh[m]) + F(zh[m])) * (int(wh[n, k]) * F(swh.view(np.float16)[n]))
+            for k in range(K - r):
+                tot += (int(ql[m, k]) * F(sl[m]) + F(zl[m])) * (int(wl_[n, k]) * F(swl.view(np.float16)[n]))
+            assert abs(F(y[m, n]) - tot) <= abs(tot) * Fraction(1, 2 ** 45) + Fraction(1, 2 ** 60)
+
+
+def test_asym_layer_tracks_reference_and_beats_symmetric_on_one_sided_data(oracle):
+    # activations after a ReLU-like nonlinearity are one-sided: the asymmetric grid spends
+    # all its levels on the occupied half-line, worth about one bit (6 dB) of activation
+    # SNR over the symmetric grid; at the layer output the (unchanged) weight noise dilutes it
+    g = torch.Generator().manual_seed(9)
+    x = torch.randn(64, 256, generator=g).abs().to(torch.bfloat16)
+    w = (torch.randn(96, 256, generator=g) * 0.02).to(torch.bfloat16)
+    xb, wb = wl.bf16_bits(x), wl.bf16_bits(w)
+    x64 = wl.bits_to_f64(xb)
+    ref = x64 @ wl.bits_to_f64(wb).T
+    _, ql, _, sl, _, zl = oracle.quantize_act_asym(xb, 0)
+    _, qs, _, ss = oracle.quantize_act(xb, 0)
+    rec_a = ql.astype(np.float64) * sl[:, None].astype(np.float64) + zl[:, None].astype(np.float64)
+    rec_s = qs.astype(np.float64) * ss[:, None].astype(np.float64)
+    gain = oracle.snr_db(x64, rec_a) - oracle.snr_db(x64, rec_s)
+    assert 4.5 < gain < 8.0, gain
+    for r in (0, 32, 256):
+        asym = oracle.snr_db(ref, oracle.linear_asym(xb, wb, r).y)
+        sym = oracle.snr_db(ref, oracle.linear(xb, wb, r).y)
+        assert asym > sym + 1.0, (r, asym, sym)
+    # and on zero-mean data the two are within a couple of dB of each other
+    x = torch.randn(64, 256, generator=g).to(torch.bfloat16)
+    xb = wl.bf16_bits(x)
+    ref = wl.bits_to_f64(xb) @ wl.bits_to_f64(wb).T
+    a, s_ = oracle.snr_db(ref, oracle.linear_asym(xb, wb, 32).y), oracle.snr_db(ref, oracle.linear(xb, wb, 32).y)
+    assert abs(a - s_) < 3.0
