@@ -84,7 +84,8 @@ int64_t resq_act_lo_ld(int64_t K, int64_t r);
  * library (tiled for the matrix cores; read it back with resq_unpack_weights):
  * N is padded to a multiple of 256 rows, the high group to a multiple of 128
  * and the low group to a multiple of 256 codes, all with zero codes, followed
- * by two fp16 scale vectors and one int32 correction per channel.
+ * by two fp16 scale vectors and three int32 sums of codes per channel (16 bytes
+ * per channel in all).
  */
 size_t resq_packed_weight_bytes(int64_t N, int64_t K, int64_t r);
 
@@ -143,6 +144,31 @@ int resq_hadamard_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K,
                                void* stream);
 
 /*
+ * Per-token quantization with the ASYMMETRIC branch of Section 3 Eq. 1, the
+ * setting of the paper's own experiments for activations (Section 5.1), applied
+ * to each group separately:
+ *   z = min(x), s = (max(x) - min(x)) / (2^N - 1), code = clip(round((x - z) / s), 0, 2^N - 1)
+ * with x - z and the quotient in fp32 and the round half to even; a constant
+ * group has s = 1.  Codes are STORED minus 2^(N-1) in the layouts of
+ * resq_quantize_act (int8 for the high group; for the low group the plain code
+ * 0..15 in bits 0..3 for even columns, a two's-complement nibble of code - 8 in
+ * bits 4..7 for odd columns), so that the matrix cores see the operands they see
+ * for symmetric codes; padding is the stored code 0.
+ *   s_hi, s_lo   fp32 [M] scales                                     (written)
+ *   c_hi, c_lo   fp32 [M]: z + 2^(N-1) s, the real value that the stored code 0
+ *                stands for, i.e. x ~ stored * s + c                 (written)
+ *   lo_sum       as in resq_quantize_act, over the stored values     (written)
+ *   hadamard_block  0: none; > 0: the block Walsh-Hadamard transform of the low
+ *                group first, in the same kernel, under the conditions of
+ *                resq_hadamard_quantize_act; < 0: the same with the default block
+ * Other arguments, alignment and limits as resq_quantize_act.  Feed the result
+ * to resq_gemm_mixed_asym.
+ */
+int resq_quantize_act_asym(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                           int64_t hadamard_block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
+                           float* s_lo, float* c_hi, float* c_lo, int32_t* lo_sum, void* stream);
+
+/*
  * Offline weight quantization and packing (Section 4.1 Eq. 3; per output
  * channel, symmetric, round-to-nearest, Section 5.1).
  *   w       bf16 [N, ldw], ldw >= K: (out_features, in_features)   (read)
@@ -186,6 +212,22 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
                     int64_t N, int64_t K,
                     int64_t r, void* y, int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo,
                     void* stream);
+
+/*
+ * The layer for asymmetric activation codes (resq_quantize_act_asym): inserting
+ * x ~ stored * s + c (Section 3 Eq. 1) and w ~ code * sw into Section 4.1 Eq. 4
+ * gives, per group,
+ *   y[m, n] += sw[n] * ( s[m] * A[m, n] + c[m] * wsum[n] ),
+ * A the integer sum over the stored codes (what dbg_acc_* receive) and wsum[n]
+ * the sum of channel n's weight codes of that group, which resq_pack_weights
+ * keeps in the packed buffer.  Same kernels as resq_gemm_mixed plus one
+ * multiply-add per group in the epilogue; all other arguments as there.
+ */
+int resq_gemm_mixed_asym(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
+                         const float* s_lo, const float* c_hi, const float* c_lo,
+                         const int32_t* lo_sum, int64_t M, const void* packed, int64_t N, int64_t K,
+                         int64_t r, void* y, int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo,
+                         void* stream);
 
 /*
  * Online Hadamard projection of the down_proj input (Section 4.3, U_D):

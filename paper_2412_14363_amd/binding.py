@@ -30,6 +30,8 @@ SYMBOLS = {
     "resq_hadamard_block": (_i64, [_i64]),
     "resq_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p]),
     "resq_hadamard_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _i64, _p]),
+    "resq_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p]),
+    "resq_gemm_mixed_asym": (C.c_int, [_p, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
     "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
     "resq_gemm_mixed": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
@@ -114,6 +116,10 @@ class ActCodes:
         self.s_hi = torch.empty(M, dtype=torch.float32, device=device)
         self.s_lo = torch.empty(M, dtype=torch.float32, device=device)
         self.lo_sum = torch.empty(M, dtype=torch.int32, device=device)
+        # asymmetric codes only (resq_quantize_act_asym): real value of the stored code 0
+        self.c_hi = torch.empty(M, dtype=torch.float32, device=device)
+        self.c_lo = torch.empty(M, dtype=torch.float32, device=device)
+        self.asym = False
 
 
 def alloc_packed(N: int, K: int, r: int, device="cuda") -> torch.Tensor:
@@ -160,6 +166,46 @@ def resq_hadamard_quantize_act(x: torch.Tensor, r: int, block: int = 0,
         _stream(stream))
     _check(st, "resq_hadamard_quantize_act")
     return out
+
+
+def resq_quantize_act_asym(x: torch.Tensor, r: int, hadamard_block: int = 0,
+                           out: Optional[ActCodes] = None, stream=None) -> ActCodes:
+    M, K = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    if out is None:
+        out = ActCodes(M, K, r, x.device)
+    hi, lo = r > 0, K - r > 0
+    st = lib().resq_quantize_act_asym(
+        _dev(x, torch.bfloat16, "x"), x.stride(0), M, K, r, hadamard_block,
+        out.q_hi.data_ptr() if hi else None, out.q_lo.data_ptr() if lo else None,
+        out.s_hi.data_ptr() if hi else None, out.s_lo.data_ptr() if lo else None,
+        out.c_hi.data_ptr() if hi else None, out.c_lo.data_ptr() if lo else None,
+        out.lo_sum.data_ptr() if lo else None, _stream(stream))
+    _check(st, "resq_quantize_act_asym")
+    out.asym = True
+    return out
+
+
+def resq_gemm_mixed_asym(act: ActCodes, packed: torch.Tensor, N: int,
+                         y: Optional[torch.Tensor] = None,
+                         dbg_acc_hi: Optional[torch.Tensor] = None,
+                         dbg_acc_lo: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K, r = act.M, act.K, act.r
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=packed.device)
+    if y.stride(1) != 1:
+        raise ValueError("y must be row-major")
+    hi, lo = r > 0, K - r > 0
+    st = lib().resq_gemm_mixed_asym(
+        act.q_hi.data_ptr() if hi else None, act.q_lo.data_ptr() if lo else None,
+        act.s_hi.data_ptr() if hi else None, act.s_lo.data_ptr() if lo else None,
+        act.c_hi.data_ptr() if hi else None, act.c_lo.data_ptr() if lo else None,
+        act.lo_sum.data_ptr() if lo else None, M, _dev(packed, torch.uint8, "packed"), N, K, r,
+        _dev(y, torch.bfloat16, "y"), y.stride(0), _dev(dbg_acc_hi, torch.int32, "dbg_acc_hi"),
+        _dev(dbg_acc_lo, torch.int32, "dbg_acc_lo"), _stream(stream))
+    _check(st, "resq_gemm_mixed_asym")
+    return y
 
 
 def resq_pack_weights(w: torch.Tensor, r: int, packed: Optional[torch.Tensor] = None,

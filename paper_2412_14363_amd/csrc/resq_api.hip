@@ -85,70 +85,101 @@ int64_t resq_hadamard_block(int64_t width) {
     return b > 8192 ? 8192 : b;
 }
 
-// shared by resq_quantize_act (rot.log2b == 0) and resq_hadamard_quantize_act
+// shared by the four activation quantizer entry points: rot.log2b == 0 means no
+// rotation, c_hi == c_lo == null the symmetric quantizer
 static int quantize_act_impl(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
                              int8_t* q_hi, uint8_t* q_lo, float* s_hi, float* s_lo,
-                             int32_t* lo_sum, const RotateArgs& rot, void* stream) {
+                             int32_t* lo_sum, const RotateArgs& rot, bool asym, float* c_hi,
+                             float* c_lo, void* stream) {
     if (!shape_ok(M, K, r) || ldx < K) return RESQ_ERR_SHAPE;
     if (!x) return RESQ_ERR_NULL;
-    if (r > 0 && (!q_hi || !s_hi)) return RESQ_ERR_NULL;
-    if (K - r > 0 && (!q_lo || !s_lo || !lo_sum)) return RESQ_ERR_NULL;
+    if (r > 0 && (!q_hi || !s_hi || (asym && !c_hi))) return RESQ_ERR_NULL;
+    if (K - r > 0 && (!q_lo || !s_lo || !lo_sum || (asym && !c_lo))) return RESQ_ERR_NULL;
     if (!aligned(x, 2) || !aligned(q_hi, 16) || !aligned(q_lo, 16) || !aligned(s_hi, 4) ||
-        !aligned(s_lo, 4) || !aligned(lo_sum, 4))
+        !aligned(s_lo, 4) || !aligned(lo_sum, 4) || !aligned(c_hi, 4) || !aligned(c_lo, 4))
         return RESQ_ERR_ALIGN;
     const int64_t ld_hi = round_up(r, kHiPad), ld_lo = round_up(K - r, kLoPad) / 2;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint16_t* xp = static_cast<const uint16_t*>(x);
-    const dim3 block(kQuantThreads);
+    const dim3 block(kQuantThreads), grid((unsigned)M);
     const bool vec = aligned(x, 16) && ldx % 8 == 0 && K % 8 == 0 && r % 8 == 0 && K <= 16384;
     const bool rotate = rot.log2b > 0;
     if (rotate && !vec) return RESQ_ERR_ALIGN;
-#define RESQ_LAUNCH_QA(ITERS)                                                                     \
-    do {                                                                                          \
-        if (rotate)                                                                               \
-            launch(quantize_act_vec_kernel<ITERS, true>, dim3((unsigned)M), block, 0, st, xp, ldx, \
-                   (int)K, (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum, rot);            \
-        else                                                                                      \
-            launch(quantize_act_vec_kernel<ITERS, false>, dim3((unsigned)M), block, 0, st, xp,    \
-                   ldx, (int)K, (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum, rot);       \
+#define RESQ_QA_ARGS xp, ldx, (int)K, (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum
+#define RESQ_LAUNCH_QA(ITERS)                                                                       \
+    do {                                                                                            \
+        if (rotate && asym)                                                                         \
+            launch(quantize_act_vec_kernel<ITERS, true, true>, grid, block, 0, st, RESQ_QA_ARGS, rot, c_hi, c_lo);   \
+        else if (rotate)                                                                            \
+            launch(quantize_act_vec_kernel<ITERS, true, false>, grid, block, 0, st, RESQ_QA_ARGS, rot, c_hi, c_lo);  \
+        else if (asym)                                                                              \
+            launch(quantize_act_vec_kernel<ITERS, false, true>, grid, block, 0, st, RESQ_QA_ARGS, rot, c_hi, c_lo);  \
+        else                                                                                        \
+            launch(quantize_act_vec_kernel<ITERS, false, false>, grid, block, 0, st, RESQ_QA_ARGS, rot, c_hi, c_lo); \
     } while (0)
     if (vec) {
         if (K <= 2048) RESQ_LAUNCH_QA(1);
         else if (K <= 4096) RESQ_LAUNCH_QA(2);
         else if (K <= 8192) RESQ_LAUNCH_QA(4);
         else RESQ_LAUNCH_QA(8);
+    } else if (asym) {
+        launch(quantize_act_generic_kernel<true>, grid, block, 0, st, RESQ_QA_ARGS, c_hi, c_lo);
     } else {
-        launch(quantize_act_generic_kernel, dim3((unsigned)M), block, 0, st, xp, ldx, (int)K, (int)r,
-               q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum);
+        launch(quantize_act_generic_kernel<false>, grid, block, 0, st, RESQ_QA_ARGS, c_hi, c_lo);
     }
 #undef RESQ_LAUNCH_QA
+#undef RESQ_QA_ARGS
     return launch_status();
+}
+
+// checks the block of a fused rotation and fills rot; block == 0 selects the default
+static int make_rotate_args(int64_t K, int64_t r, int64_t block, void* x_rot, int64_t ld_rot,
+                            RotateArgs& rot) {
+    const int64_t width = K - r;
+    if (width < 1) return RESQ_ERR_SHAPE;
+    if (block == 0) block = resq_hadamard_block(width);
+    if (block < 8 || block > 512 || (block & (block - 1)) != 0 || width % block != 0 || r % block != 0)
+        return RESQ_ERR_SHAPE;
+    if (x_rot && ld_rot < K) return RESQ_ERR_SHAPE;
+    if (x_rot && (!aligned(x_rot, 16) || ld_rot % 8 != 0)) return RESQ_ERR_ALIGN;
+    rot.log2b = 0;
+    while ((int64_t(1) << rot.log2b) < block) ++rot.log2b;
+    rot.scale = 1.0f / sqrtf((float)block);
+    rot.x_rot = static_cast<uint16_t*>(x_rot);
+    rot.ld_rot = ld_rot;
+    return RESQ_OK;
 }
 
 int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r, int8_t* q_hi,
                       uint8_t* q_lo, float* s_hi, float* s_lo, int32_t* lo_sum, void* stream) {
     RotateArgs rot{0, 1.0f, nullptr, 0};
-    return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, stream);
+    return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, false, nullptr,
+                             nullptr, stream);
 }
 
 int resq_hadamard_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
                                int64_t block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
                                float* s_lo, int32_t* lo_sum, void* x_rot, int64_t ld_rot,
                                void* stream) {
-    if (!shape_ok(M, K, r) || K - r < 1) return RESQ_ERR_SHAPE;
-    const int64_t width = K - r;
-    if (block == 0) block = resq_hadamard_block(width);
-    if (block < 8 || block > 512 || (block & (block - 1)) != 0 || width % block != 0 || r % block != 0)
-        return RESQ_ERR_SHAPE;
-    if (x_rot && ld_rot < K) return RESQ_ERR_SHAPE;
-    if (x_rot && (!aligned(x_rot, 16) || ld_rot % 8 != 0)) return RESQ_ERR_ALIGN;
+    if (!shape_ok(M, K, r)) return RESQ_ERR_SHAPE;
     RotateArgs rot;
-    rot.log2b = 0;
-    while ((int64_t(1) << rot.log2b) < block) ++rot.log2b;
-    rot.scale = 1.0f / sqrtf((float)block);
-    rot.x_rot = static_cast<uint16_t*>(x_rot);
-    rot.ld_rot = ld_rot;
-    return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, stream);
+    const int rc = make_rotate_args(K, r, block, x_rot, ld_rot, rot);
+    if (rc != RESQ_OK) return rc;
+    return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, false, nullptr,
+                             nullptr, stream);
+}
+
+int resq_quantize_act_asym(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                           int64_t hadamard_block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
+                           float* s_lo, float* c_hi, float* c_lo, int32_t* lo_sum, void* stream) {
+    if (!shape_ok(M, K, r)) return RESQ_ERR_SHAPE;
+    RotateArgs rot{0, 1.0f, nullptr, 0};
+    if (hadamard_block != 0) {
+        const int rc = make_rotate_args(K, r, hadamard_block < 0 ? 0 : hadamard_block, nullptr, 0, rot);
+        if (rc != RESQ_OK) return rc;
+    }
+    return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, true, c_hi, c_lo,
+                             stream);
 }
 
 int resq_pack_weights(const void* w, int64_t ldw, int64_t N, int64_t K, int64_t r, void* packed,
@@ -179,16 +210,21 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
     return launch_status();
 }
 
-int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, const float* s_lo,
-                    const int32_t* lo_sum, int64_t M, const void* packed, int64_t N, int64_t K,
-                    int64_t r, void* y,
-                    int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo, void* stream) {
+// shared by resq_gemm_mixed (asym false, c_hi = c_lo = null) and resq_gemm_mixed_asym
+static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
+                           const float* s_lo, bool asym, const float* c_hi, const float* c_lo,
+                           const int32_t* lo_sum, int64_t M, const void* packed, int64_t N,
+                           int64_t K, int64_t r, void* y, int64_t ldy, int32_t* dbg_acc_hi,
+                           int32_t* dbg_acc_lo, void* stream) {
     if (!shape_ok(N, K, r) || M < 1 || M > 0x7FFFFFFF || ldy < N) return RESQ_ERR_SHAPE;
     if (K - r > kMaxLoWidth || r > kMaxHiWidth) return RESQ_ERR_SHAPE;
     if (!packed || !y) return RESQ_ERR_NULL;
-    if (r > 0 && (!q_hi || !s_hi)) return RESQ_ERR_NULL;
-    if (K - r > 0 && (!q_lo || !s_lo || !lo_sum)) return RESQ_ERR_NULL;
-    if (!aligned(lo_sum, 4)) return RESQ_ERR_ALIGN;
+    if (r > 0 && (!q_hi || !s_hi || (asym && !c_hi))) return RESQ_ERR_NULL;
+    if (K - r > 0 && (!q_lo || !s_lo || !lo_sum || (asym && !c_lo))) return RESQ_ERR_NULL;
+    if (!aligned(lo_sum, 4) || !aligned(c_hi, 4) || !aligned(c_lo, 4)) return RESQ_ERR_ALIGN;
+    // an empty group's pointer is never read; null both when the codes are symmetric
+    if (!asym || r == 0) c_hi = nullptr;
+    if (!asym || K - r == 0) c_lo = nullptr;
     if (!aligned(q_hi, 16) || !aligned(q_lo, 16) || !aligned(packed, 256) || !aligned(y, 2) ||
         !aligned(s_hi, 4) || !aligned(s_lo, 4) || !aligned(dbg_acc_hi, 4) ||
         !aligned(dbg_acc_lo, 4))
@@ -209,6 +245,8 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
         d.s_hi = s_hi;
         d.s_lo = s_lo;
         d.lo_sum = lo_sum;
+        d.c_hi = c_hi;
+        d.c_lo = c_lo;
         d.packed = static_cast<const uint8_t*>(packed);
         d.L = L;
         d.M = (int)M;
@@ -239,6 +277,8 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
     a.s_hi = s_hi;
     a.s_lo = s_lo;
     a.lo_sum = lo_sum;
+    a.c_hi = c_hi;
+    a.c_lo = c_lo;
     a.packed = static_cast<const uint8_t*>(packed);
     a.M = M;
     a.y = static_cast<uint16_t*>(y);
@@ -258,6 +298,23 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
     else
         launch(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
     return launch_status();
+}
+
+int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, const float* s_lo,
+                    const int32_t* lo_sum, int64_t M, const void* packed, int64_t N, int64_t K,
+                    int64_t r, void* y, int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo,
+                    void* stream) {
+    return gemm_mixed_impl(q_hi, q_lo, s_hi, s_lo, false, nullptr, nullptr, lo_sum, M, packed, N, K,
+                           r, y, ldy, dbg_acc_hi, dbg_acc_lo, stream);
+}
+
+int resq_gemm_mixed_asym(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
+                         const float* s_lo, const float* c_hi, const float* c_lo,
+                         const int32_t* lo_sum, int64_t M, const void* packed, int64_t N, int64_t K,
+                         int64_t r, void* y, int64_t ldy, int32_t* dbg_acc_hi, int32_t* dbg_acc_lo,
+                         void* stream) {
+    return gemm_mixed_impl(q_hi, q_lo, s_hi, s_lo, true, c_hi, c_lo, lo_sum, M, packed, N, K, r, y,
+                           ldy, dbg_acc_hi, dbg_acc_lo, stream);
 }
 
 int resq_online_hadamard(const void* x, void* y, int64_t ld, int64_t M, int64_t K,

@@ -34,6 +34,8 @@ struct DecodeArgs {
     const float* s_hi;
     const float* s_lo;
     const int32_t* lo_sum;
+    const float* c_hi;  // asymmetric activation codes only (else null): per token, the real
+    const float* c_lo;  // value that the stored code 0 of the group stands for
     const uint8_t* packed;
     WeightLayout L;
     int M;
@@ -104,6 +106,12 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
     const float sth = (has_hi && tok_live) ? a.s_hi[tok] : 0.f;
     const float stl = (has_lo && tok_live) ? a.s_lo[tok] : 0.f;
     const int ca = (has_lo && tok_live) ? a.lo_sum[tok] : 0;
+    // asymmetric activations: zero-point term c[m] * wsum[n] * sw[n] per group
+    const bool asym = a.c_hi != nullptr || a.c_lo != nullptr;
+    const float cth = (asym && has_hi && tok_live) ? a.c_hi[tok] : 0.f;
+    const float ctl = (asym && has_lo && tok_live) ? a.c_lo[tok] : 0.f;
+    const int32_t* wsum_hi = even_sum + a.L.n_pad;
+    const int32_t* wsum_lo = even_sum + 2 * a.L.n_pad;
 
     for (; group < a.groups; group += 8 * gridDim.x) {
         const uint4* wp = reinterpret_cast<const uint4*>(a.packed + (int64_t)group * a.L.group_bytes + lane_off);
@@ -156,6 +164,8 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
             const int a_hi = acc_hi[v];
             const int a_lo = (acc_lo[v] - 128 * (ev[v] + ca)) >> 4;  // exact
             out[v] = (float)a_hi * (sth * snh[v]) + (float)a_lo * (stl * snl[v]);
+            if (asym)
+                out[v] += cth * ((float)wsum_hi[n + v] * snh[v]) + ctl * ((float)wsum_lo[n + v] * snl[v]);
             if constexpr (DBG) {
                 if (n + v < a.L.N) {
                     if (a.dbg_hi) a.dbg_hi[(int64_t)tok * a.L.N + n + v] = a_hi;

@@ -81,7 +81,12 @@ constexpr int kMetaEven = 1024;    // int32 [256] even-column code sums of the l
 constexpr int kMetaSHi = 2048;     // fp32 [128] high-group token scales
 constexpr int kMetaSLo = 2560;     // fp32 [128] low-group token scales
 constexpr int kMetaLoSum = 3072;   // int32 [128] odd-column code sums of the low group
-constexpr int kMetaBytes = 3584;
+// only for asymmetric activation codes:
+constexpr int kMetaWsumHi = 3584;  // int32 [256] sums of the high weight codes
+constexpr int kMetaWsumLo = 4608;  // int32 [256] sums of the low weight codes
+constexpr int kMetaCHi = 5632;     // fp32 [128] real value of the stored high code 0, per token
+constexpr int kMetaCLo = 6144;     // fp32 [128] the same for the low group
+constexpr int kMetaBytes = 6656;
 
 struct GemmArgs {
     const uint8_t* q_hi;
@@ -90,6 +95,8 @@ struct GemmArgs {
     const float* s_hi;
     const float* s_lo;
     const int32_t* lo_sum;  // per token: sum of the low codes in odd columns
+    const float* c_hi;      // asymmetric activation codes only (else null): per token, the real
+    const float* c_lo;      // value that the stored code 0 of the group stands for
     const uint8_t* packed;
     WeightLayout L;
     int64_t M;
@@ -243,14 +250,17 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
     const uint16_t* sw_lo = sw_hi + a.L.n_pad;
     const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
+    const bool asym = a.c_hi != nullptr || a.c_lo != nullptr;
 
     // ---- epilogue constants -> LDS ---------------------------------------------
     // These are the oldest loads of every wave, so the first wait for a stage
     // covers them.  Token rows past M repeat the last row (never stored).
     if (wave == 0) {
         load_to_lds_16B((lane < 32 ? sw_hi : sw_lo) + n0 + (lane & 31) * 8, lds + kMetaOff + kMetaSwHi);
+        if (asym) load_to_lds_16B(even_sum + a.L.n_pad + n0 + lane * 4, lds + kMetaOff + kMetaWsumHi);
     } else if (wave == 1) {
         load_to_lds_16B(even_sum + n0 + lane * 4, lds + kMetaOff + kMetaEven);
+        if (asym) load_to_lds_16B(even_sum + 2 * a.L.n_pad + n0 + lane * 4, lds + kMetaOff + kMetaWsumLo);
     } else {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -259,8 +269,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             if (wave == 2) {
                 if (S_hi > 0) load_to_lds_4B(a.s_hi + m, lds + kMetaOff + kMetaSHi + h * 256);
                 if (S_lo > 0) load_to_lds_4B(a.s_lo + m, lds + kMetaOff + kMetaSLo + h * 256);
-            } else if (S_lo > 0) {
-                load_to_lds_4B(a.lo_sum + m, lds + kMetaOff + kMetaLoSum + h * 256);
+            } else {
+                if (S_lo > 0) load_to_lds_4B(a.lo_sum + m, lds + kMetaOff + kMetaLoSum + h * 256);
+                if (asym && S_hi > 0) load_to_lds_4B(a.c_hi + m, lds + kMetaOff + kMetaCHi + h * 256);
+                if (asym && S_lo > 0) load_to_lds_4B(a.c_lo + m, lds + kMetaOff + kMetaCLo + h * 256);
             }
         }
     }
@@ -391,14 +403,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     // kernel (same fp32 product).  The result is rounded to bf16 and staged in
     // LDS, row-padded, for the row-segment stores.  The constants come from LDS
     // (no direct-to-LDS load is in flight any more: ordinary loads).
-    auto fold = [&](auto has_hi, auto has_lo) __attribute__((always_inline)) {
+    // ASYM (asymmetric activation codes, stored minus 2^(N-1)): each group gains the
+    // zero-point term c[m] * wsum[n] * sw[n], c the real value of the stored code 0
+    // and wsum the sum of the channel's weight codes (Eq. 1 inserted into Eq. 4).
+    auto fold = [&](auto has_hi, auto has_lo, auto is_asym) __attribute__((always_inline)) {
         constexpr bool HI_ON = decltype(has_hi)::value, LO_ON = decltype(has_lo)::value;
+        constexpr bool ASYM = decltype(is_asym)::value;
         const uint8_t* meta = lds + kMetaOff;
-        float st_hi[2] = {0.f, 0.f}, st_lo[2] = {0.f, 0.f};
+        float st_hi[2] = {0.f, 0.f}, st_lo[2] = {0.f, 0.f}, ct_hi[2] = {0.f, 0.f}, ct_lo[2] = {0.f, 0.f};
         int ca[2] = {0, 0};
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             if constexpr (HI_ON) st_hi[i] = *reinterpret_cast<const float*>(meta + kMetaSHi + (tl + 32 * i) * 4);
+            if constexpr (ASYM && HI_ON) ct_hi[i] = *reinterpret_cast<const float*>(meta + kMetaCHi + (tl + 32 * i) * 4);
+            if constexpr (ASYM && LO_ON) ct_lo[i] = *reinterpret_cast<const float*>(meta + kMetaCLo + (tl + 32 * i) * 4);
             if constexpr (LO_ON) {
                 st_lo[i] = *reinterpret_cast<const float*>(meta + kMetaSLo + (tl + 32 * i) * 4);
                 if constexpr (!DBG) st_lo[i] *= 0.0625f;
@@ -426,17 +444,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             for (int vq = 0; vq < 4; ++vq) {
                 const int c = cl + 32 * j + 8 * vq;
                 float sn_hi[4] = {0.f, 0.f, 0.f, 0.f}, sn_lo[4] = {0.f, 0.f, 0.f, 0.f};
+                float zw_hi[4] = {0.f, 0.f, 0.f, 0.f}, zw_lo[4] = {0.f, 0.f, 0.f, 0.f};  // wsum[n] * sw[n]
                 v4i ev = {0, 0, 0, 0};
                 if constexpr (HI_ON) {
                     const v4h h = *reinterpret_cast<const v4h*>(meta + kMetaSwHi + c * 2);
 #pragma unroll
                     for (int vr = 0; vr < 4; ++vr) sn_hi[vr] = (float)h[vr];
+                    if constexpr (ASYM) {
+                        const v4i ws = *reinterpret_cast<const v4i*>(meta + kMetaWsumHi + c * 4);
+#pragma unroll
+                        for (int vr = 0; vr < 4; ++vr) zw_hi[vr] = (float)ws[vr] * sn_hi[vr];
+                    }
                 }
                 if constexpr (LO_ON) {
                     const v4h h = *reinterpret_cast<const v4h*>(meta + kMetaSwLo + c * 2);
 #pragma unroll
                     for (int vr = 0; vr < 4; ++vr) sn_lo[vr] = (float)h[vr];
                     ev = *reinterpret_cast<const v4i*>(meta + kMetaEven + c * 4);
+                    if constexpr (ASYM) {
+                        const v4i ws = *reinterpret_cast<const v4i*>(meta + kMetaWsumLo + c * 4);
+#pragma unroll
+                        for (int vr = 0; vr < 4; ++vr) zw_lo[vr] = (float)ws[vr] * sn_lo[vr];
+                    }
                 }
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
@@ -448,6 +477,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                         if constexpr (HI_ON) {
                             const int ih = acc_hi[j][i][v];
                             val[vr] = (float)ih * (st_hi[i] * sn_hi[vr]);
+                            if constexpr (ASYM) val[vr] += ct_hi[i] * zw_hi[vr];
                             if constexpr (DBG) {
                                 if (a.dbg_hi && dbg_ok[i] && 32 * j + 8 * vq + vr < dbg_cols)
                                     dbg_row_hi[i][32 * j + 8 * vq + vr] = ih;
@@ -457,6 +487,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                             int il = acc_lo[j][i][v] - (ev[vr] * 128 + ca[i]);
                             if constexpr (DBG) il >>= 4;
                             val[vr] += (float)il * (st_lo[i] * sn_lo[vr]);
+                            if constexpr (ASYM) val[vr] += ct_lo[i] * zw_lo[vr];
                             if constexpr (DBG) {
                                 if (a.dbg_lo && dbg_ok[i] && 32 * j + 8 * vq + vr < dbg_cols)
                                     dbg_row_lo[i][32 * j + 8 * vq + vr] = il;
@@ -650,9 +681,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             lds_wait_all(py);  // reads past the last stage: let them land
         }
         wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
-        if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{});
-        else if (S_hi > 0) fold(YES{}, NO{});
-        else fold(NO{}, YES{});
+        if (asym) {
+            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, YES{});
+            else if (S_hi > 0) fold(YES{}, NO{}, YES{});
+            else fold(NO{}, YES{}, YES{});
+        } else {
+            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, NO{});
+            else if (S_hi > 0) fold(YES{}, NO{}, NO{});
+            else fold(NO{}, YES{}, NO{});
+        }
     }
 
     // ---- write y once --------------------------------------------------------

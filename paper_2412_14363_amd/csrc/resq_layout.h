@@ -49,7 +49,12 @@ struct WeightLayout {
     int64_t kh_pad, kl_pad, n_pad;
     int64_t hi_blocks, lo_blocks;  // per group of 16 channels
     int64_t group_bytes;           // bytes of one group of 16 channels
-    int64_t scale_off;             // byte offset of sw_hi; sw_lo at + 2 n_pad, even_sum at + 4 n_pad
+    int64_t scale_off;             // byte offset of the per-channel constants, n_pad entries each:
+                                   //   fp16 sw_hi at + 0, fp16 sw_lo at + 2 n_pad,
+                                   //   int32 even_sum (low codes of even columns) at + 4 n_pad,
+                                   //   int32 wsum_hi at + 8 n_pad, int32 wsum_lo at + 12 n_pad
+                                   //   (sums of all codes of a group: the zero-point term of
+                                   //   asymmetric activations)
     int64_t total_bytes;
 };
 
@@ -63,7 +68,7 @@ __host__ __device__ inline WeightLayout make_weight_layout(int64_t N, int64_t K,
     L.lo_blocks = L.kl_pad / (2 * kRowBytes);
     L.group_bytes = (L.hi_blocks + L.lo_blocks) * kBlockBytes;
     L.scale_off = (L.n_pad / kRowsPerBlock) * L.group_bytes;
-    L.total_bytes = L.scale_off + 8 * L.n_pad;
+    L.total_bytes = L.scale_off + 16 * L.n_pad;
     return L;
 }
 

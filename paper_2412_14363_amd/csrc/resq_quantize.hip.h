@@ -43,6 +43,35 @@ __device__ __forceinline__ void block_max2(float& a, float& b, float* red /* [8]
     b = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
 }
 
+// max over the 256 threads of a block of four floats at once
+__device__ __forceinline__ void block_max4(float (&a)[4], float* red /* [16] in LDS */) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = fmaxf(a[i], __shfl_xor(a[i], off));
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[4 * i + wave] = a[i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        a[i] = fmaxf(fmaxf(red[4 * i], red[4 * i + 1]), fmaxf(red[4 * i + 2], red[4 * i + 3]));
+}
+
+// Asymmetric branch of Section 3 Eq. 1: z = min, s = (max - min) / (2^N - 1),
+// code = clip(rint((x - z) / s), 0, 2^N - 1), difference and quotient in fp32.
+// A constant group has s = 1.
+__device__ __forceinline__ float asym_scale(float mn, float mx, int levels) {
+    const float range = mx - mn;
+    return range == 0.0f ? 1.0f : range / (float)levels;
+}
+__device__ __forceinline__ int quant_code_asym(float x, float zero, float scale, int levels) {
+    float q = rintf((x - zero) / scale);
+    q = fminf(fmaxf(q, 0.0f), (float)levels);
+    return (int)q;
+}
+
 // sum over the 256 threads of a block
 __device__ __forceinline__ int block_sum(int v, int* red /* [4] in LDS */) {
 #pragma unroll
@@ -118,6 +147,43 @@ __device__ __forceinline__ void quant8(const uint4& v, float scale, float inv, u
     if (LOW) odd_sum += (rr[1] + rr[3]) + (rr[5] + rr[7]);
 }
 
+// The same for the asymmetric quantizer.  Codes are STORED minus 2^(N-1) (int8 for
+// the high group; for the low group a two's-complement nibble in odd columns and
+// the plain code 0..15, i.e. stored value + 8, in even columns), so that the GEMM
+// sees the operands it sees for symmetric codes.  On return the low bits of u[j]
+// hold that stored value and odd_sum has gained the stored values of the odd elements.
+template <bool LOW>
+__device__ __forceinline__ void quant8_asym(const uint4& v, float zero, float scale, float inv,
+                                            uint32_t (&u)[8], float& odd_sum) {
+    constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23
+    constexpr int levels = LOW ? 15 : 255;
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float ds[8], rr[8];
+    bool near_tie = false;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float x = __uint_as_float((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
+        const float off = LOW ? ((j & 1) ? 8.0f : 0.0f) : 128.0f;  // stored = code - off
+        ds[j] = x - zero;
+        const float t = ds[j] * inv;
+        const float uf = t + (kMagic - off);
+        rr[j] = uf - kMagic;                    // rint(t) - off, exact
+        near_tie |= fabsf(t - (uf - (kMagic - off))) > 0.5f - (LOW ? 16.0f : 256.0f) * 9.5367431640625e-07f;
+        u[j] = __float_as_uint(uf);
+    }
+    if (__builtin_amdgcn_ballot_w64(near_tie) != 0) {  // wave-uniform
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float q = rintf(ds[j] / scale);
+            q = fminf(fmaxf(q, 0.0f), (float)levels);
+            const int c = (int)q - (LOW ? ((j & 1) ? 8 : 0) : 128);
+            u[j] = (uint32_t)c;
+            rr[j] = (float)c;
+        }
+    }
+    if (LOW) odd_sum += (rr[1] + rr[3]) + (rr[5] + rr[7]);
+}
+
 // low bytes of four registers -> one dword
 __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     return __builtin_amdgcn_perm(b, a, 0x0c0c0400u) | __builtin_amdgcn_perm(d, c, 0x04000c0cu);
@@ -133,13 +199,16 @@ struct RotateArgs {
     int64_t ld_rot;
 };
 
-template <int ITERS, bool ROTATE>
+// ASYM: the asymmetric quantizer; c_hi / c_lo [M] receive z + 2^(N-1) s, the real
+// value that the stored code 0 stands for (what the GEMM's epilogue needs).
+template <int ITERS, bool ROTATE, bool ASYM>
 __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
     int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
-    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum, const RotateArgs rot) {
+    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum, const RotateArgs rot,
+    float* __restrict__ c_hi, float* __restrict__ c_lo) {
     constexpr int RT = kQuantThreads;     // threads per row
-    __shared__ float red[8];
+    __shared__ float red[16];
     __shared__ int red_sum[4];
     const int t = threadIdx.x;
     const int64_t m = blockIdx.x;
@@ -174,19 +243,50 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
             }
         }
     }
-    float amax_h = 0.0f, amax_l = 0.0f;
+    float sh, sl, zh = 0.0f, zl = 0.0f;
+    if constexpr (ASYM) {
+        // max and -min of both groups in one reduction
+        const float inf = __builtin_huge_valf();
+        float ext[4] = {-inf, -inf, -inf, -inf};  // max_h, -min_h, max_l, -min_l
 #pragma unroll
-    for (int i = 0; i < ITERS; ++i) {
-        const int u = t + i * RT;
-        if (u < nunits) {
-            const float a = absmax8(v[i]);
-            if (u < hi_units) amax_h = fmaxf(amax_h, a);
-            else amax_l = fmaxf(amax_l, a);
+        for (int i = 0; i < ITERS; ++i) {
+            const int u = t + i * RT;
+            if (u < nunits) {
+                float f[8];
+                unpack8_bf16(v[i], f);
+                const float mx = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])),
+                                       fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+                const float mn = fminf(fminf(fminf(f[0], f[1]), fminf(f[2], f[3])),
+                                       fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+                const int g = u < hi_units ? 0 : 2;
+                ext[g] = fmaxf(ext[g], mx);
+                ext[g + 1] = fmaxf(ext[g + 1], -mn);
+            }
         }
+        block_max4(ext, red);
+        zh = -ext[1];
+        zl = -ext[3];
+        sh = r > 0 ? asym_scale(zh, ext[0], 255) : 1.0f;
+        sl = K - r > 0 ? asym_scale(zl, ext[2], 15) : 1.0f;
+        if (t == 0) {
+            if (r > 0) c_hi[m] = zh + 128.0f * sh;
+            if (K - r > 0) c_lo[m] = zl + 8.0f * sl;
+        }
+    } else {
+        float amax_h = 0.0f, amax_l = 0.0f;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            const int u = t + i * RT;
+            if (u < nunits) {
+                const float a = absmax8(v[i]);
+                if (u < hi_units) amax_h = fmaxf(amax_h, a);
+                else amax_l = fmaxf(amax_l, a);
+            }
+        }
+        block_max2(amax_h, amax_l, red);
+        sh = group_scale(amax_h, kQmaxHi);
+        sl = group_scale(amax_l, kQmaxLo);
     }
-    block_max2(amax_h, amax_l, red);
-    const float sh = group_scale(amax_h, kQmaxHi);
-    const float sl = group_scale(amax_l, kQmaxLo);
     const float inv_h = 1.0f / sh, inv_l = 1.0f / sl;
     if (t == 0) {
         if (r > 0) s_hi[m] = sh;
@@ -202,11 +302,13 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
         if (u < nunits) {
             uint32_t c[8];
             if (u < hi_units) {
-                quant8<false>(v[i], sh, inv_h, c, odd_f);
+                if constexpr (ASYM) quant8_asym<false>(v[i], zh, sh, inv_h, c, odd_f);
+                else quant8<false>(v[i], sh, inv_h, c, odd_f);
                 *reinterpret_cast<uint2*>(qh + (int64_t)u * 8) =
                     make_uint2(pack_low_bytes(c[0], c[1], c[2], c[3]), pack_low_bytes(c[4], c[5], c[6], c[7]));
             } else {
-                quant8<true>(v[i], sl, inv_l, c, odd_f);
+                if constexpr (ASYM) quant8_asym<true>(v[i], zl, sl, inv_l, c, odd_f);
+                else quant8<true>(v[i], sl, inv_l, c, odd_f);
                 // byte k = (even code + 8) | (odd code << 4); the even value is 1..15 in
                 // its low byte already, and only the low byte of by[k] is kept
                 uint32_t by[4];
@@ -231,39 +333,71 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 // Activations, any K, r (K - r even) and alignment: two passes over the row
 // with 2-byte loads.  Correct everywhere, fast nowhere.
 // ---------------------------------------------------------------------------
+template <bool ASYM>
 __global__ __launch_bounds__(kQuantThreads) void quantize_act_generic_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
     int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
-    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum) {
-    __shared__ float red[8];
+    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum, float* __restrict__ c_hi,
+    float* __restrict__ c_lo) {
+    __shared__ float red[16];
     __shared__ int red_sum[4];
     const int64_t m = blockIdx.x;
     const int t = threadIdx.x;
     const uint16_t* row = x + m * ldx;
-    float amax_h = 0.0f, amax_l = 0.0f;
-    for (int k = t; k < K; k += kQuantThreads) {
-        const float a = bf16_bits_to_f32(row[k] & 0x7FFFu);
-        if (k < r) amax_h = fmaxf(amax_h, a);
-        else amax_l = fmaxf(amax_l, a);
+    float sh, sl, zh = 0.0f, zl = 0.0f;
+    if constexpr (ASYM) {
+        const float inf = __builtin_huge_valf();
+        float ext[4] = {-inf, -inf, -inf, -inf};  // max_h, -min_h, max_l, -min_l
+        for (int k = t; k < K; k += kQuantThreads) {
+            const float a = bf16_bits_to_f32(row[k]);
+            const int g = k < r ? 0 : 2;
+            ext[g] = fmaxf(ext[g], a);
+            ext[g + 1] = fmaxf(ext[g + 1], -a);
+        }
+        block_max4(ext, red);
+        zh = -ext[1];
+        zl = -ext[3];
+        sh = r > 0 ? asym_scale(zh, ext[0], 255) : 1.0f;
+        sl = K - r > 0 ? asym_scale(zl, ext[2], 15) : 1.0f;
+        if (t == 0) {
+            if (r > 0) c_hi[m] = zh + 128.0f * sh;
+            if (K - r > 0) c_lo[m] = zl + 8.0f * sl;
+        }
+    } else {
+        float amax_h = 0.0f, amax_l = 0.0f;
+        for (int k = t; k < K; k += kQuantThreads) {
+            const float a = bf16_bits_to_f32(row[k] & 0x7FFFu);
+            if (k < r) amax_h = fmaxf(amax_h, a);
+            else amax_l = fmaxf(amax_l, a);
+        }
+        block_max2(amax_h, amax_l, red);
+        sh = group_scale(amax_h, kQmaxHi);
+        sl = group_scale(amax_l, kQmaxLo);
     }
-    block_max2(amax_h, amax_l, red);
-    const float sh = group_scale(amax_h, kQmaxHi);
-    const float sl = group_scale(amax_l, kQmaxLo);
     if (t == 0) {
         if (r > 0) s_hi[m] = sh;
         if (K - r > 0) s_lo[m] = sl;
     }
+    // stored codes: symmetric codes as they are; asymmetric codes minus 2^(N-1)
+    auto code_hi = [&](float v) {
+        if constexpr (ASYM) return quant_code_asym(v, zh, sh, 255) - 128;
+        else return quant_code(v, sh, kQmaxHi);
+    };
+    auto code_lo = [&](float v) {
+        if constexpr (ASYM) return quant_code_asym(v, zl, sl, 15) - 8;
+        else return quant_code(v, sl, kQmaxLo);
+    };
     int8_t* qh = q_hi + m * ld_hi;
     uint8_t* ql = q_lo + m * ld_lo;
     for (int64_t k = t; k < ld_hi; k += kQuantThreads)
-        qh[k] = k < r ? (int8_t)quant_code(bf16_bits_to_f32(row[k]), sh, kQmaxHi) : (int8_t)0;
+        qh[k] = k < r ? (int8_t)code_hi(bf16_bits_to_f32(row[k])) : (int8_t)0;
     const int pairs = (K - r) / 2;
     int odd_sum = 0;
     for (int64_t j = t; j < ld_lo; j += kQuantThreads) {
         uint32_t byte = 0x08u;
         if (j < pairs) {
-            const int c0 = quant_code(bf16_bits_to_f32(row[r + 2 * j]), sl, kQmaxLo);
-            const int c1 = quant_code(bf16_bits_to_f32(row[r + 2 * j + 1]), sl, kQmaxLo);
+            const int c0 = code_lo(bf16_bits_to_f32(row[r + 2 * j]));
+            const int c1 = code_lo(bf16_bits_to_f32(row[r + 2 * j + 1]));
             odd_sum += c1;
             byte = (uint32_t)((c0 + 8) & 0xF) | ((uint32_t)(c1 & 0xF) << 4);
         }
@@ -318,6 +452,7 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
         sw_lo[n] = (live && K - r > 0) ? hl : (uint16_t)0x3C00u;
     }
     // high group: units of 16 codes
+    int sum_hi = 0, sum_lo_odd = 0;
     for (int u = t; u < (int)(L.kh_pad / 16); u += kQuantThreads) {
         uint32_t out[4] = {0u, 0u, 0u, 0u};
         if (live) {
@@ -326,6 +461,7 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
                 const int k = u * 16 + j;
                 if (k < r) {
                     const int c = quant_code(bf16_bits_to_f32(row[k]), sh, kQmaxHi);
+                    sum_hi += c;
                     out[j >> 2] |= (uint32_t)(c & 0xFF) << (8 * (j & 3));
                 }
             }
@@ -344,6 +480,7 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
                 if (k < K) {
                     const int c = quant_code(bf16_bits_to_f32(row[k]), sl, kQmaxLo);
                     if (j & 1) {
+                        sum_lo_odd += c;
                         out[j >> 3] = (out[j >> 3] & ~(0xFu << (4 * (j & 7) - 4))) |
                                       ((uint32_t)((c + 8) & 0xF) << (4 * (j & 7) - 4));
                     } else {
@@ -357,7 +494,16 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
             make_uint4(out[0], out[1], out[2], out[3]);
     }
     even_sum = block_sum(even_sum, red_sum);
-    if (t == 0) reinterpret_cast<int32_t*>(packed + L.scale_off + 4 * L.n_pad)[n] = even_sum;
+    __syncthreads();
+    sum_lo_odd = block_sum(sum_lo_odd, red_sum);
+    __syncthreads();
+    sum_hi = block_sum(sum_hi, red_sum);
+    if (t == 0) {
+        int32_t* sums = reinterpret_cast<int32_t*>(packed + L.scale_off + 4 * L.n_pad);
+        sums[n] = even_sum;
+        sums[L.n_pad + n] = sum_hi;
+        sums[2 * L.n_pad + n] = even_sum + sum_lo_odd;
+    }
 }
 
 __global__ __launch_bounds__(kQuantThreads) void unpack_weights_kernel(

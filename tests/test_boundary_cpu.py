@@ -35,10 +35,10 @@ def test_layout_queries():
     assert binding.resq_act_hi_ld(4096, 0) == 0 and binding.resq_act_lo_ld(4096, 4096) == 0
     assert binding.resq_act_hi_ld(10, 3) == -1             # K - r odd
     assert binding.resq_act_lo_ld(8, 9) == -1
-    # 8192 x 28672, r = 1024: 4.5 bits per weight plus two fp16 scales and one int32 per channel
-    assert binding.resq_packed_weight_bytes(28672, 8192, 1024) == 28672 * (1024 + 3584) + 8 * 28672
+    # 8192 x 28672, r = 1024: 4.5 bits per weight plus two fp16 scales and three int32 sums per channel
+    assert binding.resq_packed_weight_bytes(28672, 8192, 1024) == 28672 * (1024 + 3584) + 16 * 28672
     # N is padded to 256 rows
-    assert binding.resq_packed_weight_bytes(29568, 8192, 1024) == 29696 * (1024 + 3584 + 8)
+    assert binding.resq_packed_weight_bytes(29568, 8192, 1024) == 29696 * (1024 + 3584 + 16)
     assert binding.resq_packed_weight_bytes(0, 8, 0) == 0
     assert binding.resq_hadamard_block(12544) == 256
     assert binding.resq_hadamard_block(14336) == 2048
@@ -115,6 +115,21 @@ def test_hadamard_quantize_rejects_bad_arguments():
     assert f(P + 2, 1024, 4, 1024, 256, 256, P, P, P, P, P, None, 0, None) == 3      # needs the vector path
     assert f(None, 1024, 4, 1024, 256, 256, P, P, P, P, P, None, 0, None) == 1
     assert f(*ok, 256, P, P, P, P, None, None, 0, None) == 1       # lo_sum missing
+
+
+def test_asym_entry_points_reject_bad_arguments():
+    q = binding.lib().resq_quantize_act_asym
+    assert q(P, 256, 4, 256, 32, 0, P, P, P, P, P, P, P, None) != 1
+    assert q(P, 256, 4, 256, 32, 0, P, P, P, P, None, P, P, None) == 1     # c_hi missing
+    assert q(P, 256, 4, 256, 32, 0, P, P, P, P, P, None, P, None) == 1     # c_lo missing
+    assert q(P, 256, 4, 256, 256, 0, P, None, P, None, P, None, None, None) != 1   # r = K
+    assert q(P, 256, 4, 256, 32, 64, P, P, P, P, P, P, P, None) == 2       # block does not divide r
+    assert q(P, 256, 4, 256, 33, 0, P, P, P, P, P, P, P, None) == 2        # K - r odd
+    assert q(P, 256, 4, 256, 32, 0, P, P, P, P, P + 2, P, P, None) == 3
+    g = binding.lib().resq_gemm_mixed_asym
+    assert g(P, P, P, P, None, P, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 1
+    assert g(P, P, P, P, P, None, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 1
+    assert g(P, P, P, P, P, P, P, 16, P, 256, 256, 32, P, 255, None, None, None) == 2
 
 
 def test_binding_fails_loudly_without_device_tensors():

@@ -306,3 +306,116 @@ def test_hadamard_quantize_fused(oracle, rq, M, K, r, block):
     act3 = rq.resq_hadamard_quantize_act(xd, r, block)
     torch.cuda.synchronize()
     assert torch.equal(act3.q_lo, act.q_lo) and torch.equal(act3.s_lo, act.s_lo)
+
+
+# ---- asymmetric activations (the other branch of Eq. 1, the setting of Section 5.1) ----
+
+def stored_to_codes(act, r, K):
+    """GPU storage (code - 2^(N-1)) back to the oracle's unsigned codes."""
+    q_hi = (act.q_hi.cpu().numpy()[:, :r].astype(np.int32) + 128).astype(np.uint8)
+    from parity_util import unpack_nibbles
+    q_lo = (unpack_nibbles(act.q_lo.cpu().numpy(), K - r).astype(np.int32) + 8).astype(np.uint8)
+    return q_hi, q_lo
+
+
+def compare_asym_codes(oracle, act, x_bits, r):
+    M, K = x_bits.shape
+    q_hi, q_lo, s_hi, s_lo, z_hi, z_lo = oracle.quantize_act_asym(x_bits, r)
+    g_hi, g_lo = stored_to_codes(act, r, K)
+    if r > 0:
+        assert np.array_equal(g_hi, q_hi), "INT8 codes differ"
+        assert not act.q_hi.cpu().numpy()[:, r:].any(), "padding of the high codes must be the stored code 0"
+        assert np.array_equal(act.s_hi.cpu().numpy().view(np.uint32), s_hi.view(np.uint32))
+        want_c = (z_hi + np.float32(128) * s_hi).astype(np.float32)
+        assert np.array_equal(act.c_hi.cpu().numpy().view(np.uint32), want_c.view(np.uint32))
+    if K - r > 0:
+        assert np.array_equal(g_lo, q_lo), "INT4 codes differ"
+        stored = q_lo.astype(np.int8) - 8
+        assert np.array_equal(act.q_lo.cpu().numpy(), oracle.pack_nibbles(stored, act.ld_lo)), "packing differs"
+        assert np.array_equal(act.s_lo.cpu().numpy().view(np.uint32), s_lo.view(np.uint32))
+        want_c = (z_lo + np.float32(8) * s_lo).astype(np.float32)
+        assert np.array_equal(act.c_lo.cpu().numpy().view(np.uint32), want_c.view(np.uint32))
+        assert np.array_equal(act.lo_sum.cpu().numpy(), oracle.odd_code_sums(stored)), "lo_sum differs"
+
+
+def check_layer_asym(oracle, rq, x, w, r, ldy_extra=0):
+    M, K = x.shape
+    N = w.shape[0]
+    act = rq.resq_quantize_act_asym(x.cuda(), r)
+    torch.cuda.synchronize()
+    compare_asym_codes(oracle, act, wl.bf16_bits(x), r)
+    packed, wq = check_weights(oracle, rq, w, r)
+    ref = oracle.linear_asym(wl.bf16_bits(x), None, r, weights=wq)
+    dbg_hi = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    dbg_lo = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    ybuf = torch.zeros((M, N + ldy_extra), dtype=torch.bfloat16, device="cuda")
+    y = rq.resq_gemm_mixed_asym(act, packed, N, y=ybuf[:, :N], dbg_acc_hi=dbg_hi, dbg_acc_lo=dbg_lo)
+    torch.cuda.synchronize()
+    # the kernel's integer sums run over the stored codes: A_stored = A_unsigned - 2^(N-1) wsum
+    if r > 0:
+        want = ref.acc_hi - 128 * ref.wsum_hi[None, :]
+        assert np.array_equal(dbg_hi.cpu().numpy().astype(np.int64), want), "A_hi differs"
+    if K - r > 0:
+        want = ref.acc_lo - 8 * ref.wsum_lo[None, :]
+        assert np.array_equal(dbg_lo.cpu().numpy().astype(np.int64), want), "A_lo differs"
+    rel = y_within_tolerance(y, ref.y)
+    assert rel <= REL_TOL, f"bf16 output off by {rel}"
+    # the same call without the accumulator dump runs the kernel variant that ships (the
+    # compiler may contract its multiply-adds differently: same tolerance, not bit equality)
+    y2 = rq.resq_gemm_mixed_asym(act, packed, N, y=torch.zeros_like(ybuf)[:, :N])
+    torch.cuda.synchronize()
+    rel2 = y_within_tolerance(y2, ref.y)
+    assert rel2 <= REL_TOL, f"bf16 output (no dump) off by {rel2}"
+    assert (y2.float() - y.float()).abs().max() <= 2.0 ** -7 * y.float().abs().max()
+    if ldy_extra:
+        assert not ybuf[:, N:].any(), "wrote past N"
+
+
+@pytest.mark.parametrize("M,K,r", [(3, 2048, 256), (5, 4096, 512), (7, 4096, 0), (7, 4096, 4096),
+                                   (2, 14336, 1792), (4, 264, 8),               # vector path
+                                   (3, 250, 30), (5, 77, 77), (4, 90, 0), (3, 34, 2)])   # generic path
+def test_quantize_act_asym(oracle, rq, M, K, r):
+    s = wl.LayerShape("qa", M=M, K=K, N=1, r=r, act="student_t3", seed=M + K + 1)
+    x = wl.make_activations(s)
+    x[0] = x[0].abs()                        # a one-sided row
+    x[1, K // 2:] = 3.0                      # a constant stretch
+    act = rq.resq_quantize_act_asym(x.cuda(), r)
+    torch.cuda.synchronize()
+    compare_asym_codes(oracle, act, wl.bf16_bits(x), r)
+
+
+def test_quantize_act_asym_constant_rows_and_ties(oracle, rq):
+    x = torch.zeros(4, 512, dtype=torch.bfloat16)
+    x[1] = 2.5                               # constant row: s = 1, codes 0
+    x[2, :256] = torch.arange(256, dtype=torch.float32).to(torch.bfloat16) * 0.5   # ties on a power-of-two grid
+    x[2, 255] = 127.5
+    x[3, 256:] = torch.linspace(-3, 4.5, 256).to(torch.bfloat16)
+    for r in (0, 256, 512):
+        act = rq.resq_quantize_act_asym(x.cuda(), r)
+        torch.cuda.synchronize()
+        compare_asym_codes(oracle, act, wl.bf16_bits(x), r)
+
+
+@pytest.mark.parametrize("M,K,N,r", [
+    (130, 640, 300, 128), (257, 1000, 515, 104), (64, 4096, 512, 512), (200, 90, 40, 30),
+    (48, 512, 256, 0), (48, 512, 256, 512),          # tiled kernel
+    (1, 512, 256, 64), (16, 1000, 515, 104), (7, 2048, 272, 256), (3, 256, 256, 0),   # weight-streaming kernel
+])
+def test_layer_asym(oracle, rq, M, K, N, r):
+    x, w = wl.random_small_case(M * 5 + K, M, K, N, r, act="student_t3")
+    x = (x.float() + 1.5).to(torch.bfloat16)          # off-centre activations: a real zero-point
+    check_layer_asym(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+def test_hadamard_then_asym_quantize_fused(oracle, rq):
+    # rotation fused in front of the asymmetric quantizer = the two kernels in sequence
+    s = wl.LayerShape("hqa", M=6, K=2048, N=1, r=512, act="student_t3", seed=11)
+    x = (wl.make_activations(s).float().abs()).to(torch.bfloat16)
+    xd = x.cuda()
+    fused = rq.resq_quantize_act_asym(xd, s.r, hadamard_block=256)
+    y = rq.resq_online_hadamard(xd, s.r, s.K, 256)
+    two = rq.resq_quantize_act_asym(y, s.r)
+    torch.cuda.synchronize()
+    for name in ("q_hi", "q_lo", "s_hi", "s_lo", "c_hi", "c_lo", "lo_sum"):
+        assert torch.equal(getattr(fused, name), getattr(two, name)), name
+    compare_asym_codes(oracle, fused, wl.bf16_bits(y.cpu()), s.r)
