@@ -66,7 +66,8 @@ def algorithmic_bytes_gemm(s) -> int:
     return s.M * per_tok + s.N * (s.r + (s.K - s.r) // 2 + 8) + 2 * s.M * s.N
 
 
-def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 0):
+def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 0,
+                 asym: bool = False):
     """Time the oracle (activation quantizer, two int GEMMs, dequantization) on a
     row sample sized for roughly ``budget_s`` seconds."""
     import numpy as np
@@ -76,7 +77,8 @@ def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 
     xb = wl.bf16_bits(x)
     probe = min(shape.M, 2)
     t0 = time.perf_counter()
-    oracle.linear(xb[:probe], None, shape.r, weights=wq_np)
+    layer = oracle.linear_asym if asym else oracle.linear
+    layer(xb[:probe], None, shape.r, weights=wq_np)
     t_probe = max(time.perf_counter() - t0, 1e-4)
     rows = int(max(1, min(shape.M, probe * budget_s / t_probe)))
     idx = np.sort(np.random.default_rng(0).choice(shape.M, rows, replace=False))
@@ -84,7 +86,7 @@ def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 
     t0 = time.perf_counter()
     if shape.hadamard:
         sample = oracle.hadamard(sample, shape.r, shape.K, hadamard_block)
-    oracle.linear(sample, None, shape.r, weights=wq_np)
+    layer(sample, None, shape.r, weights=wq_np)
     dt = time.perf_counter() - t0
     ops = 2.0 * rows * shape.N * shape.K
     return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(),
@@ -102,6 +104,9 @@ def main() -> None:
     ap.add_argument("--workload", default="oproj_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--asym", action="store_true",
+                    help="asymmetric per-token activations (the paper's experimental setting) "
+                         "instead of the symmetric ones the headline metric is defined on")
     ap.add_argument("--unfused-hadamard", action="store_true",
                     help="down_proj input: transform and quantize in two kernels instead of one")
     args = ap.parse_args()
@@ -162,6 +167,14 @@ def main() -> None:
                   ptr(act.lo_sum, lo), s.M, p.data_ptr(), s.N, s.K, s.r, y.data_ptr(), s.N, None,
                   None, st)
                  for p in packed]
+    # asymmetric activations: same kernels, one more pair of per-token vectors
+    qa_asym_args = (xq.data_ptr(), s.K, s.M, s.K, s.r, -1 if fused else 0, ptr(act.q_hi, hi),
+                    ptr(act.q_lo, lo), ptr(act.s_hi, hi), ptr(act.s_lo, lo), ptr(act.c_hi, hi),
+                    ptr(act.c_lo, lo), ptr(act.lo_sum, lo), st)
+    gemm_asym_args = [(ptr(act.q_hi, hi), ptr(act.q_lo, lo), ptr(act.s_hi, hi), ptr(act.s_lo, lo),
+                       ptr(act.c_hi, hi), ptr(act.c_lo, lo), ptr(act.lo_sum, lo), s.M, p.data_ptr(),
+                       s.N, s.K, s.r, y.data_ptr(), s.N, None, None, st)
+                      for p in packed]
 
     def step(i: int, events=None):
         # events: three (start, stop) pairs of hipEvent_t, recorded by the library at
@@ -173,11 +186,17 @@ def main() -> None:
             assert rc == 0, rc
         if events is not None:
             L.resq_time_next_kernel(*events[1])
-        rc = L.resq_hadamard_quantize_act(*hq_args) if fused else L.resq_quantize_act(*qa_args)
+        if args.asym:
+            rc = L.resq_quantize_act_asym(*qa_asym_args)
+        else:
+            rc = L.resq_hadamard_quantize_act(*hq_args) if fused else L.resq_quantize_act(*qa_args)
         assert rc == 0, rc
         if events is not None:
             L.resq_time_next_kernel(*events[2])
-        rc = L.resq_gemm_mixed(*gemm_args[i % n_copies])
+        if args.asym:
+            rc = L.resq_gemm_mixed_asym(*gemm_asym_args[i % n_copies])
+        else:
+            rc = L.resq_gemm_mixed(*gemm_args[i % n_copies])
         assert rc == 0, rc
 
     for i in range(args.warmup):
@@ -242,6 +261,7 @@ def main() -> None:
                    "step": ("hadamard_quantize_act (one kernel) + " if fused else
                             "online_hadamard + quantize_act + " if s.hadamard else
                             "quantize_act + ") + "gemm_mixed",
+                   "activations": "asymmetric per token" if args.asym else "symmetric per token",
                    "weight_copies_rotated": n_copies},
         "tokens_per_s": s.M / (ms_per_step * 1e-3),
         "hadamard_ms": had_ms, "quantize_ms": quant_ms, "gemm_ms": gemm_ms,
@@ -251,7 +271,7 @@ def main() -> None:
         from oracle import resq_oracle as oracle
         wq_np = oracle.quantize_weights(wl.bf16_bits(w), s.r)
         cb = cpu_baseline(s, x, wq_np, args.cpu_budget,
-                          rq.resq_hadamard_block(s.K - s.r) if s.hadamard else 0)
+                          rq.resq_hadamard_block(s.K - s.r) if s.hadamard else 0, args.asym)
         if decode:
             # same unit as the metric: algorithmic bytes of the sampled rows per second
             frac = cb["rows"] / s.M
