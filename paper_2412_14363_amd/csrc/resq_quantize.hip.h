@@ -26,13 +26,29 @@ __device__ __forceinline__ int quant_code(float x, float scale, int qmax) {
     return (int)q;
 }
 
+// Butterfly reductions over the 64 lanes of a wavefront; the lane exchanges are
+// the cheap ones of the transform kernel (DPP moves, swizzles) where they exist.
+__device__ __forceinline__ float wave_max(float a) {
+    a = fmaxf(a, lane_xor<1>(a));
+    a = fmaxf(a, lane_xor<2>(a));
+    a = fmaxf(a, lane_xor<4>(a));
+    a = fmaxf(a, lane_xor<8>(a));
+    a = fmaxf(a, lane_xor<16>(a));
+    return fmaxf(a, lane_xor<32>(a));
+}
+__device__ __forceinline__ int wave_sum(int v) {
+    v += __float_as_int(lane_xor<1>(__int_as_float(v)));
+    v += __float_as_int(lane_xor<2>(__int_as_float(v)));
+    v += __float_as_int(lane_xor<4>(__int_as_float(v)));
+    v += __float_as_int(lane_xor<8>(__int_as_float(v)));
+    v += __float_as_int(lane_xor<16>(__int_as_float(v)));
+    return v + __float_as_int(lane_xor<32>(__int_as_float(v)));
+}
+
 // max over the 256 threads of a block of two non-negative floats at once
 __device__ __forceinline__ void block_max2(float& a, float& b, float* red /* [8] in LDS */) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        a = fmaxf(a, __shfl_xor(a, off));
-        b = fmaxf(b, __shfl_xor(b, off));
-    }
+    a = wave_max(a);
+    b = wave_max(b);
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) {
         red[wave] = a;
@@ -46,9 +62,7 @@ __device__ __forceinline__ void block_max2(float& a, float& b, float* red /* [8]
 // max over the 256 threads of a block of four floats at once
 __device__ __forceinline__ void block_max4(float (&a)[4], float* red /* [16] in LDS */) {
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = fmaxf(a[i], __shfl_xor(a[i], off));
+    for (int i = 0; i < 4; ++i) a[i] = wave_max(a[i]);
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0)
 #pragma unroll
@@ -74,8 +88,7 @@ __device__ __forceinline__ int quant_code_asym(float x, float zero, float scale,
 
 // sum over the 256 threads of a block
 __device__ __forceinline__ int block_sum(int v, int* red /* [4] in LDS */) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    v = wave_sum(v);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
     return red[0] + red[1] + red[2] + red[3];
