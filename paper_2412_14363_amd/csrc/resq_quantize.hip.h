@@ -343,6 +343,87 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Activations, short rows (K <= 512, e.g. one attention head of a K/V cache
+// entry, Section 4.3): one wavefront per row, four rows per workgroup, one
+// 8-element unit per lane, reductions inside the wavefront: no LDS, no barrier.
+// Same arithmetic and the same outputs as the kernel above.
+// ---------------------------------------------------------------------------
+template <bool ASYM>
+__global__ __launch_bounds__(kQuantThreads) void quantize_act_short_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int64_t M, int K, int r, int8_t* __restrict__ q_hi,
+    int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
+    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum, float* __restrict__ c_hi,
+    float* __restrict__ c_lo) {
+    const int lane = threadIdx.x & 63;
+    const int64_t m = (int64_t)blockIdx.x * (kQuantThreads / 64) + (threadIdx.x >> 6);
+    if (m >= M) return;  // whole wavefronts leave together
+    const int nunits = K >> 3, hi_units = r >> 3;
+    const bool live = lane < nunits, high = lane < hi_units;
+    const uint4 v = live ? reinterpret_cast<const uint4*>(x + m * ldx)[lane] : make_uint4(0u, 0u, 0u, 0u);
+
+    float sh, sl, zh = 0.0f, zl = 0.0f;
+    if constexpr (ASYM) {
+        const float inf = __builtin_huge_valf();
+        float mx = -inf, nmn = -inf;
+        if (live) {
+            float f[8];
+            unpack8_bf16(v, f);
+            mx = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])), fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+            nmn = -fminf(fminf(fminf(f[0], f[1]), fminf(f[2], f[3])), fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+        }
+        const float mx_h = wave_max(high ? mx : -inf), nmn_h = wave_max(high ? nmn : -inf);
+        const float mx_l = wave_max(live && !high ? mx : -inf), nmn_l = wave_max(live && !high ? nmn : -inf);
+        zh = -nmn_h;
+        zl = -nmn_l;
+        sh = r > 0 ? asym_scale(zh, mx_h, 255) : 1.0f;
+        sl = K - r > 0 ? asym_scale(zl, mx_l, 15) : 1.0f;
+        if (lane == 0) {
+            if (r > 0) c_hi[m] = zh + 128.0f * sh;
+            if (K - r > 0) c_lo[m] = zl + 8.0f * sl;
+        }
+    } else {
+        const float a = live ? absmax8(v) : 0.0f;
+        sh = group_scale(wave_max(high ? a : 0.0f), kQmaxHi);
+        sl = group_scale(wave_max(high ? 0.0f : a), kQmaxLo);
+    }
+    if (lane == 0) {
+        if (r > 0) s_hi[m] = sh;
+        if (K - r > 0) s_lo[m] = sl;
+    }
+    int8_t* qh = q_hi + m * ld_hi;
+    uint8_t* ql = q_lo + m * ld_lo;
+    float odd_f = 0.0f;
+    // the branch on `high` is not wave-uniform, and quant8 votes across the wavefront:
+    // run both kinds for every lane's vote, keep the own kind's result
+    uint32_t ch[8], cl8[8];
+    float odd_dummy = 0.0f;
+    if (hi_units > 0) {
+        if constexpr (ASYM) quant8_asym<false>(v, zh, sh, 1.0f / sh, ch, odd_dummy);
+        else quant8<false>(v, sh, 1.0f / sh, ch, odd_dummy);
+    }
+    if (nunits > hi_units) {
+        if constexpr (ASYM) quant8_asym<true>(v, zl, sl, 1.0f / sl, cl8, odd_f);
+        else quant8<true>(v, sl, 1.0f / sl, cl8, odd_f);
+    }
+    if (live && high) {
+        *reinterpret_cast<uint2*>(qh + (int64_t)lane * 8) =
+            make_uint2(pack_low_bytes(ch[0], ch[1], ch[2], ch[3]), pack_low_bytes(ch[4], ch[5], ch[6], ch[7]));
+    } else if (live) {
+        uint32_t by[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) by[k] = (cl8[2 * k + 1] << 4) | cl8[2 * k];
+        *reinterpret_cast<uint32_t*>(ql + (int64_t)(lane - hi_units) * 4) = pack_low_bytes(by[0], by[1], by[2], by[3]);
+    }
+    // zero codes in the padding of both rows
+    for (int64_t b = (int64_t)r + 8 * lane; b < ld_hi; b += 8 * 64)
+        *reinterpret_cast<uint2*>(qh + b) = make_uint2(0u, 0u);
+    for (int64_t b = (int64_t)(K - r) / 2 + 4 * lane; b < ld_lo; b += 4 * 64)
+        *reinterpret_cast<uint32_t*>(ql + b) = 0x08080808u;
+    const int odd_sum = wave_sum(live && !high ? (int)odd_f : 0);
+    if (lane == 0 && K - r > 0) lo_sum[m] = odd_sum;
+}
+
+// ---------------------------------------------------------------------------
 // Activations, any K, r (K - r even) and alignment: two passes over the row
 // with 2-byte loads.  Correct everywhere, fast nowhere.
 // ---------------------------------------------------------------------------

@@ -419,3 +419,29 @@ def test_hadamard_then_asym_quantize_fused(oracle, rq):
     for name in ("q_hi", "q_lo", "s_hi", "s_lo", "c_hi", "c_lo", "lo_sum"):
         assert torch.equal(getattr(fused, name), getattr(two, name)), name
     compare_asym_codes(oracle, fused, wl.bf16_bits(y.cpu()), s.r)
+
+
+# ---- short rows: per-head quantization of a K/V cache entry (Section 4.3) ----------
+
+@pytest.mark.parametrize("rows,d_head,r", [(8 * 37, 128, 16), (8 * 37 + 3, 128, 16), (50, 64, 8),
+                                           (21, 512, 64), (33, 128, 0), (33, 128, 128), (5, 8, 8)])
+def test_kv_cache_head_quantization(oracle, rq, rows, d_head, r):
+    # [tokens x heads, d_head] rows, each a group pair of its own: symmetric and asymmetric
+    # (the paper quantizes the cache per head, asymmetrically), one wavefront per row
+    s = wl.LayerShape("kv", M=rows, K=d_head, N=1, r=r, act="student_t3", seed=rows + d_head)
+    x = wl.make_activations(s)
+    x[0] = 0
+    check_act_codes(oracle, rq, x, r)
+    act = rq.resq_quantize_act_asym(x.cuda(), r)
+    torch.cuda.synchronize()
+    compare_asym_codes(oracle, act, wl.bf16_bits(x), r)
+
+
+def test_online_head_projection_as_uniform_int8_layer(oracle, rq):
+    # the 8-bit online projection of queries and keys (U_C, d_head x d_head, Section 4.3):
+    # rows = tokens x heads, K = N = d_head, every column in the high group
+    g = torch.Generator().manual_seed(4)
+    rows, d = 32 * 40, 128
+    x = torch.randn(rows, d, generator=g).to(torch.bfloat16)
+    u = torch.linalg.qr(torch.randn(d, d, generator=g))[0].contiguous().to(torch.bfloat16)   # an orthogonal U_C
+    check_layer(oracle, rq, x, u, d)
