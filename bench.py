@@ -53,6 +53,7 @@ def workload_shape(name: str):
         "qwen_r0": wl.qwen_mlp_shape(0),
         "qwen_r1024": wl.qwen_mlp_shape(1024),
         "qwen_r2048": wl.qwen_mlp_shape(2048),
+        "kv_quant": wl.KV_CACHE_QUANT,
     }
     if name not in table:
         raise SystemExit(f"unknown workload {name!r}; choose from {sorted(table)}")
@@ -96,6 +97,81 @@ def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 
             "seconds": dt, "rows": rows}
 
 
+def quant_only_bench(args, s) -> None:
+    """A workload that is the quantizer alone (per-head quantization of K/V cache entries,
+    asymmetric as in the paper): HBM-bound, reported in GB/s of algorithmic bytes."""
+    import ctypes
+    import numpy as np
+    import torch
+    from paper_2412_14363_amd import binding as rq
+    from paper_2412_14363_amd import workloads as wl
+
+    x = wl.make_activations(s)
+    xd = x.cuda()
+    act = rq.ActCodes(s.M, s.K, s.r)
+    L = rq.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    qa = (xd.data_ptr(), s.K, s.M, s.K, s.r, 0, act.q_hi.data_ptr(), act.q_lo.data_ptr(),
+          act.s_hi.data_ptr(), act.s_lo.data_ptr(), act.c_hi.data_ptr(), act.c_lo.data_ptr(),
+          act.lo_sum.data_ptr(), st)
+
+    def step(events=None):
+        if events is not None:
+            L.resq_time_next_kernel(*events)
+        rc = L.resq_quantize_act_asym(*qa)
+        assert rc == 0, rc
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    hip = ctypes.CDLL("libamdhip64.so")
+    evs = []
+    for _ in range(args.steps):
+        a, b = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+        evs.append((a, b))
+        step((a, b))
+    torch.cuda.synchronize()
+    tot = 0.0
+    for a, b in evs:
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        tot += ms.value
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(b)
+    kernel_ms = tot / args.steps
+    # per row: the bf16 row in; padded codes, two scales, two offsets and one sum out
+    abytes = s.M * (2 * s.K + act.ld_hi + act.ld_lo + 20)
+    out = {
+        "metric": "per-head K/V cache quantization GB/s (% HBM peak)",
+        "value": abytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"{s.name}: rows={s.M} d_head={s.K} r={s.r}", "tag": args.workload,
+                   "step": "quantize_act_asym", "activations": "asymmetric per head"},
+        "quantize_ms": kernel_ms,
+        "roofline": {"bound": "hbm", "achieved": abytes / (kernel_ms * 1e-3) / 1e9,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "resq quantize_act (short rows)", "kernel_ms": kernel_ms},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import resq_oracle as oracle
+        xb = wl.bf16_bits(x)
+        t0 = time.perf_counter()
+        oracle.quantize_act_asym(xb, s.r)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": abytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": f"all {s.M} rows, {dt:.2f} s"}
+    print(json.dumps(out))
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +210,9 @@ def main() -> None:
     from paper_2412_14363_amd import workloads as wl
 
     s = workload_shape(args.workload)
+    if s.N == 0:
+        quant_only_bench(args, s)
+        return
     decode = s.M <= 16
     x = wl.make_activations(s)
     w = wl.make_weights(s)

@@ -118,14 +118,21 @@ static int quantize_act_impl(const void* x, int64_t ldx, int64_t M, int64_t K, i
             launch(quantize_act_vec_kernel<ITERS, false, false>, grid, block, 0, st, RESQ_QA_ARGS, rot, c_hi, c_lo); \
     } while (0)
     if (vec && K <= 512 && !rotate) {
-        // short rows (an attention head of a K/V cache entry): one wavefront per row
-        const dim3 grid4((unsigned)((M + 3) / 4));
-        if (asym)
-            launch(quantize_act_short_kernel<true>, grid4, block, 0, st, xp, ldx, M, (int)K, (int)r,
-                   q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum, c_hi, c_lo);
-        else
-            launch(quantize_act_short_kernel<false>, grid4, block, 0, st, xp, ldx, M, (int)K, (int)r,
-                   q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum, c_hi, c_lo);
+        // short rows (an attention head of a K/V cache entry): 16, 32 or 64 lanes per row
+#define RESQ_LAUNCH_SHORT(G)                                                                       \
+    do {                                                                                           \
+        const dim3 grid_s((unsigned)((M + kQuantThreads / G - 1) / (kQuantThreads / G)));          \
+        if (asym)                                                                                  \
+            launch(quantize_act_short_kernel<true, G>, grid_s, block, 0, st, xp, ldx, M, (int)K,   \
+                   (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum, c_hi, c_lo);              \
+        else                                                                                       \
+            launch(quantize_act_short_kernel<false, G>, grid_s, block, 0, st, xp, ldx, M, (int)K,  \
+                   (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum, c_hi, c_lo);              \
+    } while (0)
+        if (K <= 128) RESQ_LAUNCH_SHORT(16);
+        else if (K <= 256) RESQ_LAUNCH_SHORT(32);
+        else RESQ_LAUNCH_SHORT(64);
+#undef RESQ_LAUNCH_SHORT
     } else if (vec) {
         if (K <= 2048) RESQ_LAUNCH_QA(1);
         else if (K <= 4096) RESQ_LAUNCH_QA(2);

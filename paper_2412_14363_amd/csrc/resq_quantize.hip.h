@@ -28,21 +28,26 @@ __device__ __forceinline__ int quant_code(float x, float scale, int qmax) {
 
 // Butterfly reductions over the 64 lanes of a wavefront; the lane exchanges are
 // the cheap ones of the transform kernel (DPP moves, swizzles) where they exist.
+// G = 16, 32 or 64: the reduction runs inside aligned groups of G lanes.
+template <int G = 64>
 __device__ __forceinline__ float wave_max(float a) {
     a = fmaxf(a, lane_xor<1>(a));
     a = fmaxf(a, lane_xor<2>(a));
     a = fmaxf(a, lane_xor<4>(a));
     a = fmaxf(a, lane_xor<8>(a));
-    a = fmaxf(a, lane_xor<16>(a));
-    return fmaxf(a, lane_xor<32>(a));
+    if constexpr (G > 16) a = fmaxf(a, lane_xor<16>(a));
+    if constexpr (G > 32) a = fmaxf(a, lane_xor<32>(a));
+    return a;
 }
+template <int G = 64>
 __device__ __forceinline__ int wave_sum(int v) {
     v += __float_as_int(lane_xor<1>(__int_as_float(v)));
     v += __float_as_int(lane_xor<2>(__int_as_float(v)));
     v += __float_as_int(lane_xor<4>(__int_as_float(v)));
     v += __float_as_int(lane_xor<8>(__int_as_float(v)));
-    v += __float_as_int(lane_xor<16>(__int_as_float(v)));
-    return v + __float_as_int(lane_xor<32>(__int_as_float(v)));
+    if constexpr (G > 16) v += __float_as_int(lane_xor<16>(__int_as_float(v)));
+    if constexpr (G > 32) v += __float_as_int(lane_xor<32>(__int_as_float(v)));
+    return v;
 }
 
 // max over the 256 threads of a block of two non-negative floats at once
@@ -344,22 +349,26 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 
 // ---------------------------------------------------------------------------
 // Activations, short rows (K <= 512, e.g. one attention head of a K/V cache
-// entry, Section 4.3): one wavefront per row, four rows per workgroup, one
-// 8-element unit per lane, reductions inside the wavefront: no LDS, no barrier.
-// Same arithmetic and the same outputs as the kernel above.
+// entry, Section 4.3): a group of G = 16, 32 or 64 lanes per row (G * 8 >= K),
+// so 256 / G rows per workgroup, one 8-element unit per lane, reductions inside
+// the group: no LDS, no barrier.  Same arithmetic and the same outputs as the
+// kernel above.
 // ---------------------------------------------------------------------------
-template <bool ASYM>
+template <bool ASYM, int G>
 __global__ __launch_bounds__(kQuantThreads) void quantize_act_short_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int64_t M, int K, int r, int8_t* __restrict__ q_hi,
     int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
     float* __restrict__ s_lo, int32_t* __restrict__ lo_sum, float* __restrict__ c_hi,
     float* __restrict__ c_lo) {
-    const int lane = threadIdx.x & 63;
-    const int64_t m = (int64_t)blockIdx.x * (kQuantThreads / 64) + (threadIdx.x >> 6);
-    if (m >= M) return;  // whole wavefronts leave together
+    const int gl = threadIdx.x & (G - 1);  // lane inside the group
+    const int64_t m_raw = (int64_t)blockIdx.x * (kQuantThreads / G) + threadIdx.x / G;
+    // every lane of a wavefront runs the exchanges and the votes below; groups past
+    // the last row work on the last row and store nothing
+    const bool row_live = m_raw < M;
+    const int64_t m = row_live ? m_raw : M - 1;
     const int nunits = K >> 3, hi_units = r >> 3;
-    const bool live = lane < nunits, high = lane < hi_units;
-    const uint4 v = live ? reinterpret_cast<const uint4*>(x + m * ldx)[lane] : make_uint4(0u, 0u, 0u, 0u);
+    const bool live = gl < nunits, high = gl < hi_units;
+    const uint4 v = live ? reinterpret_cast<const uint4*>(x + m * ldx)[gl] : make_uint4(0u, 0u, 0u, 0u);
 
     float sh, sl, zh = 0.0f, zl = 0.0f;
     if constexpr (ASYM) {
@@ -371,30 +380,31 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_short_kernel(
             mx = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])), fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
             nmn = -fminf(fminf(fminf(f[0], f[1]), fminf(f[2], f[3])), fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
         }
-        const float mx_h = wave_max(high ? mx : -inf), nmn_h = wave_max(high ? nmn : -inf);
-        const float mx_l = wave_max(live && !high ? mx : -inf), nmn_l = wave_max(live && !high ? nmn : -inf);
+        const float mx_h = wave_max<G>(high ? mx : -inf), nmn_h = wave_max<G>(high ? nmn : -inf);
+        const float mx_l = wave_max<G>(live && !high ? mx : -inf);
+        const float nmn_l = wave_max<G>(live && !high ? nmn : -inf);
         zh = -nmn_h;
         zl = -nmn_l;
         sh = r > 0 ? asym_scale(zh, mx_h, 255) : 1.0f;
         sl = K - r > 0 ? asym_scale(zl, mx_l, 15) : 1.0f;
-        if (lane == 0) {
+        if (gl == 0 && row_live) {
             if (r > 0) c_hi[m] = zh + 128.0f * sh;
             if (K - r > 0) c_lo[m] = zl + 8.0f * sl;
         }
     } else {
         const float a = live ? absmax8(v) : 0.0f;
-        sh = group_scale(wave_max(high ? a : 0.0f), kQmaxHi);
-        sl = group_scale(wave_max(high ? 0.0f : a), kQmaxLo);
+        sh = group_scale(wave_max<G>(high ? a : 0.0f), kQmaxHi);
+        sl = group_scale(wave_max<G>(high ? 0.0f : a), kQmaxLo);
     }
-    if (lane == 0) {
+    if (gl == 0 && row_live) {
         if (r > 0) s_hi[m] = sh;
         if (K - r > 0) s_lo[m] = sl;
     }
     int8_t* qh = q_hi + m * ld_hi;
     uint8_t* ql = q_lo + m * ld_lo;
     float odd_f = 0.0f;
-    // the branch on `high` is not wave-uniform, and quant8 votes across the wavefront:
-    // run both kinds for every lane's vote, keep the own kind's result
+    // the branch on `high` is not wave-uniform, and the quantizer votes across the
+    // wavefront: run both kinds for every lane's vote, keep the own kind's result
     uint32_t ch[8], cl8[8];
     float odd_dummy = 0.0f;
     if (hi_units > 0) {
@@ -405,22 +415,23 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_short_kernel(
         if constexpr (ASYM) quant8_asym<true>(v, zl, sl, 1.0f / sl, cl8, odd_f);
         else quant8<true>(v, sl, 1.0f / sl, cl8, odd_f);
     }
+    const int odd_sum = wave_sum<G>(live && !high ? (int)odd_f : 0);
+    if (!row_live) return;
     if (live && high) {
-        *reinterpret_cast<uint2*>(qh + (int64_t)lane * 8) =
+        *reinterpret_cast<uint2*>(qh + (int64_t)gl * 8) =
             make_uint2(pack_low_bytes(ch[0], ch[1], ch[2], ch[3]), pack_low_bytes(ch[4], ch[5], ch[6], ch[7]));
     } else if (live) {
         uint32_t by[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) by[k] = (cl8[2 * k + 1] << 4) | cl8[2 * k];
-        *reinterpret_cast<uint32_t*>(ql + (int64_t)(lane - hi_units) * 4) = pack_low_bytes(by[0], by[1], by[2], by[3]);
+        *reinterpret_cast<uint32_t*>(ql + (int64_t)(gl - hi_units) * 4) = pack_low_bytes(by[0], by[1], by[2], by[3]);
     }
     // zero codes in the padding of both rows
-    for (int64_t b = (int64_t)r + 8 * lane; b < ld_hi; b += 8 * 64)
+    for (int64_t b = (int64_t)r + 8 * gl; b < ld_hi; b += 8 * G)
         *reinterpret_cast<uint2*>(qh + b) = make_uint2(0u, 0u);
-    for (int64_t b = (int64_t)(K - r) / 2 + 4 * lane; b < ld_lo; b += 4 * 64)
+    for (int64_t b = (int64_t)(K - r) / 2 + 4 * gl; b < ld_lo; b += 4 * G)
         *reinterpret_cast<uint32_t*>(ql + b) = 0x08080808u;
-    const int odd_sum = wave_sum(live && !high ? (int)odd_f : 0);
-    if (lane == 0 && K - r > 0) lo_sum[m] = odd_sum;
+    if (gl == 0 && K - r > 0) lo_sum[m] = odd_sum;
 }
 
 // ---------------------------------------------------------------------------

@@ -51,6 +51,13 @@ MLP_DOWN = LayerShape("llama3_8b_down_prefill", M=4096, K=14336, N=4096, r=1792,
                       act="student_t3", hadamard=True)
 
 
+# Side paths of Section 4.3 on Llama-3-8B head shapes (2048 tokens, 8 K/V heads, d_head 128,
+# an eighth of each head in 8 bits): the K and the V entries of 2048 tokens, one row per head,
+# quantized asymmetrically per head; N = 0 marks a workload without a GEMM.
+KV_CACHE_QUANT = LayerShape("llama3_8b_kv_cache_quant", M=2048 * 8 * 2, K=128, N=0, r=16,
+                            act="student_t3", seed=7)
+
+
 def decode_shape(M: int) -> LayerShape:
     return LayerShape(f"llama3_70b_up_decode_m{M}", M=M, K=8192, N=28672, r=1024,
                       outliers="one_percent_hi")
