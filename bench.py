@@ -172,6 +172,97 @@ def quant_only_bench(args, s) -> None:
     print(json.dumps(out))
 
 
+def mlp_block_bench(args) -> None:
+    """The MLP block of Llama-3-8B on 4096 tokens as four kernels: quantize_act,
+    gate/up as one layer with the gated activation in its epilogue (N2 = 28672), the
+    fused Hadamard + quantizer on its output, and down_proj."""
+    import ctypes
+    import torch
+    from paper_2412_14363_amd import binding as rq
+    from paper_2412_14363_amd import workloads as wl
+
+    gu, dn = wl.MLP_GATE_UP, wl.MLP_DOWN
+    M, K, F = gu.M, gu.K, gu.N
+    x = wl.make_activations(gu).cuda()
+    w_gate, w_up = wl.make_weights(gu), wl.make_weights(wl.LayerShape("up", M=1, K=K, N=F, r=gu.r, seed=1))
+    w_gu = torch.stack([w_gate, w_up], dim=1).reshape(2 * F, K).contiguous()   # rows 2c, 2c+1 = gate, up
+    p_gu = rq.resq_pack_weights(w_gu.cuda(), gu.r)
+    p_dn = rq.resq_pack_weights(wl.make_weights(dn).cuda(), dn.r)
+    a1, a2 = rq.ActCodes(M, K, gu.r), rq.ActCodes(M, F, dn.r)
+    h = torch.empty((M, F), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((M, dn.N), dtype=torch.bfloat16, device="cuda")
+    L = rq.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    calls = [
+        ("quantize_ms", L.resq_quantize_act, (x.data_ptr(), K, M, K, gu.r, a1.q_hi.data_ptr(), a1.q_lo.data_ptr(),
+                                              a1.s_hi.data_ptr(), a1.s_lo.data_ptr(), a1.lo_sum.data_ptr(), st)),
+        ("gate_up_swiglu_ms", L.resq_gemm_mixed_swiglu,
+         (a1.q_hi.data_ptr(), a1.q_lo.data_ptr(), a1.s_hi.data_ptr(), a1.s_lo.data_ptr(), a1.lo_sum.data_ptr(),
+          M, p_gu.data_ptr(), 2 * F, K, gu.r, h.data_ptr(), F, st)),
+        ("hadamard_quantize_ms", L.resq_hadamard_quantize_act,
+         (h.data_ptr(), F, M, F, dn.r, 0, a2.q_hi.data_ptr(), a2.q_lo.data_ptr(), a2.s_hi.data_ptr(),
+          a2.s_lo.data_ptr(), a2.lo_sum.data_ptr(), None, 0, st)),
+        ("down_ms", L.resq_gemm_mixed,
+         (a2.q_hi.data_ptr(), a2.q_lo.data_ptr(), a2.s_hi.data_ptr(), a2.s_lo.data_ptr(), a2.lo_sum.data_ptr(),
+          M, p_dn.data_ptr(), dn.N, F, dn.r, y.data_ptr(), dn.N, None, None, st)),
+    ]
+
+    def step(events=None):
+        for i, (_, fn, fargs) in enumerate(calls):
+            if events is not None:
+                L.resq_time_next_kernel(*events[i])
+            rc = fn(*fargs)
+            assert rc == 0, rc
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    hip = ctypes.CDLL("libamdhip64.so")
+    evs = []
+    for _ in range(args.steps):
+        row = []
+        for _ in calls:
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+            row.append((a, b))
+        evs.append(row)
+        step(row)
+    torch.cuda.synchronize()
+    sums = [0.0] * len(calls)
+    for row in evs:
+        for i, (a, b) in enumerate(row):
+            ms = ctypes.c_float()
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+            sums[i] += ms.value
+            hip.hipEventDestroy(a)
+            hip.hipEventDestroy(b)
+    per = {name: sums[i] / args.steps for i, (name, _, _) in enumerate(calls)}
+    ops_gu, ops_dn = 2.0 * M * K * 2 * F, 2.0 * M * F * dn.N
+    achieved = ops_gu / (per["gate_up_swiglu_ms"] * 1e-3) / 1e12
+    out = {
+        "metric": "mixed INT8/INT4 MLP block TOPS (% int8 MFMA peak)",
+        "value": (ops_gu + ops_dn) / (ms_per_step * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"llama3_8b_mlp_block: M={M} d={K} d_ffn={F} r={gu.r}/{dn.r}",
+                   "tag": "mlp_block",
+                   "step": "quantize_act + gemm_mixed_swiglu (gate/up, N2=28672) + "
+                           "hadamard_quantize_act + gemm_mixed (down)"},
+        "tokens_per_s": M / (ms_per_step * 1e-3), **per,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                     "frac": achieved / PEAK_INT8_TOPS, "traffic": None,
+                     "kernel": "resq gemm_mixed (gate/up with gated epilogue)",
+                     "kernel_ms": per["gate_up_swiglu_ms"]},
+    }
+    print(json.dumps(out))
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -209,6 +300,9 @@ def main() -> None:
     from paper_2412_14363_amd import binding as rq
     from paper_2412_14363_amd import workloads as wl
 
+    if args.workload == "mlp_block":
+        mlp_block_bench(args)
+        return
     s = workload_shape(args.workload)
     if s.N == 0:
         quant_only_bench(args, s)

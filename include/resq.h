@@ -214,6 +214,23 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
                     void* stream);
 
 /*
+ * The gate and up projections of an MLP block as ONE layer with the gated
+ * activation in its epilogue, so that the down_proj input (which Section 4.3
+ * transforms and quantizes next) is written directly instead of two [M, F]
+ * tensors that another kernel would read back:
+ *   y[m, c] = bf16( silu(z[m, 2c]) * z[m, 2c + 1] ),  silu(x) = x / (1 + exp(-x)),
+ * z the dequantized output of resq_gemm_mixed (in fp32, not rounded to bf16 in
+ * between).  `packed` holds N2 = 2 F channels packed by resq_pack_weights from a
+ * weight matrix whose rows 2c and 2c + 1 are the gate row and the up row of
+ * feature c (the caller interleaves them); y is bf16 [M, ldy], ldy >= N2 / 2.
+ * Symmetric activation codes; no accumulator dump.  Other arguments, alignment
+ * and kernel choice as resq_gemm_mixed.
+ */
+int resq_gemm_mixed_swiglu(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
+                           const float* s_lo, const int32_t* lo_sum, int64_t M, const void* packed,
+                           int64_t N2, int64_t K, int64_t r, void* y, int64_t ldy, void* stream);
+
+/*
  * The layer for asymmetric activation codes (resq_quantize_act_asym): inserting
  * x ~ stored * s + c (Section 3 Eq. 1) and w ~ code * sw into Section 4.1 Eq. 4
  * gives, per group,

@@ -274,6 +274,15 @@ def linear_asym(x_bits: np.ndarray, w_bits: np.ndarray, r: int, weights=None) ->
     return AsymLayerResult(q_hi, q_lo, s_hi, s_lo, z_hi, z_lo, wsum_hi, wsum_lo, acc_hi, acc_lo, y)
 
 
+def swiglu(y: np.ndarray) -> np.ndarray:
+    """Gated pair epilogue of the MLP front (the activation function that precedes the
+    down_proj input, Section 4.3): columns 2c and 2c+1 of ``y`` are the gate and the up
+    output of feature c; returns silu(gate) * up, silu(x) = x / (1 + exp(-x)), in fp64."""
+    y = np.asarray(y, np.float64)
+    gate, up = y[:, 0::2], y[:, 1::2]
+    return gate / (1.0 + np.exp(-gate)) * up
+
+
 def snr_db(ref: np.ndarray, approx: np.ndarray) -> float:
     """10 log10( sum ref^2 / sum (ref - approx)^2 ), fp64."""
     ref = np.asarray(ref, np.float64)

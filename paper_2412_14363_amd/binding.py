@@ -32,6 +32,7 @@ SYMBOLS = {
     "resq_hadamard_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _i64, _p]),
     "resq_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p]),
     "resq_gemm_mixed_asym": (C.c_int, [_p, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
+    "resq_gemm_mixed_swiglu": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
     "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
     "resq_gemm_mixed": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
@@ -255,6 +256,24 @@ def resq_gemm_mixed(act: ActCodes, packed: torch.Tensor, N: int, y: Optional[tor
                                _dev(dbg_acc_hi, torch.int32, "dbg_acc_hi"),
                                _dev(dbg_acc_lo, torch.int32, "dbg_acc_lo"), _stream(stream))
     _check(st, "resq_gemm_mixed")
+    return y
+
+
+def resq_gemm_mixed_swiglu(act: ActCodes, packed: torch.Tensor, N2: int,
+                           y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """packed: 2F interleaved (gate, up) channels; returns y [M, F] = silu(gate) * up."""
+    M, K, r = act.M, act.K, act.r
+    if y is None:
+        y = torch.empty((M, N2 // 2), dtype=torch.bfloat16, device=packed.device)
+    if y.stride(1) != 1:
+        raise ValueError("y must be row-major")
+    hi, lo = r > 0, K - r > 0
+    st = lib().resq_gemm_mixed_swiglu(
+        act.q_hi.data_ptr() if hi else None, act.q_lo.data_ptr() if lo else None,
+        act.s_hi.data_ptr() if hi else None, act.s_lo.data_ptr() if lo else None,
+        act.lo_sum.data_ptr() if lo else None, M, _dev(packed, torch.uint8, "packed"), N2, K, r,
+        _dev(y, torch.bfloat16, "y"), y.stride(0), _stream(stream))
+    _check(st, "resq_gemm_mixed_swiglu")
     return y
 
 

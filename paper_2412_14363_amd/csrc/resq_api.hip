@@ -231,8 +231,9 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
                            const float* s_lo, bool asym, const float* c_hi, const float* c_lo,
                            const int32_t* lo_sum, int64_t M, const void* packed, int64_t N,
                            int64_t K, int64_t r, void* y, int64_t ldy, int32_t* dbg_acc_hi,
-                           int32_t* dbg_acc_lo, void* stream) {
-    if (!shape_ok(N, K, r) || M < 1 || M > 0x7FFFFFFF || ldy < N) return RESQ_ERR_SHAPE;
+                           int32_t* dbg_acc_lo, void* stream, bool swiglu = false) {
+    if (!shape_ok(N, K, r) || M < 1 || M > 0x7FFFFFFF) return RESQ_ERR_SHAPE;
+    if (swiglu ? (N % 2 != 0 || ldy < N / 2) : (ldy < N)) return RESQ_ERR_SHAPE;
     if (K - r > kMaxLoWidth || r > kMaxHiWidth) return RESQ_ERR_SHAPE;
     if (!packed || !y) return RESQ_ERR_NULL;
     if (r > 0 && (!q_hi || !s_hi || (asym && !c_hi))) return RESQ_ERR_NULL;
@@ -270,6 +271,7 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         d.ldy = ldy;
         d.dbg_hi = dbg_acc_hi;
         d.dbg_lo = dbg_acc_lo;
+        d.swiglu = swiglu ? 1 : 0;
         d.groups = (int)((N + 15) / 16);
         d.lds_row = (int)lds_row;
         const int lds_bytes = (int)(M * lds_row);
@@ -301,6 +303,7 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
     a.ldy = ldy;
     a.dbg_hi = dbg_acc_hi;
     a.dbg_lo = dbg_acc_lo;
+    a.swiglu = swiglu ? 1 : 0;
     a.stages_hi = (int)a.L.hi_blocks;  // one stage = one 64-byte block per row
     a.stages_lo = (int)a.L.lo_blocks;
     a.tiles_m = (int)((M + kBM - 1) / kBM);
@@ -322,6 +325,13 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
                     void* stream) {
     return gemm_mixed_impl(q_hi, q_lo, s_hi, s_lo, false, nullptr, nullptr, lo_sum, M, packed, N, K,
                            r, y, ldy, dbg_acc_hi, dbg_acc_lo, stream);
+}
+
+int resq_gemm_mixed_swiglu(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
+                           const float* s_lo, const int32_t* lo_sum, int64_t M, const void* packed,
+                           int64_t N2, int64_t K, int64_t r, void* y, int64_t ldy, void* stream) {
+    return gemm_mixed_impl(q_hi, q_lo, s_hi, s_lo, false, nullptr, nullptr, lo_sum, M, packed, N2, K,
+                           r, y, ldy, nullptr, nullptr, stream, true);
 }
 
 int resq_gemm_mixed_asym(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,

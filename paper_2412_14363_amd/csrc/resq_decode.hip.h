@@ -43,6 +43,7 @@ struct DecodeArgs {
     int64_t ldy;
     int32_t* dbg_hi;
     int32_t* dbg_lo;
+    int swiglu;       // 1: channels 2c, 2c+1 = gate and up row of feature c; y[m, c] = silu(gate) * up
     int groups;       // ceil(N / 16)
     int lds_row;      // bytes of one token row in LDS
 };
@@ -172,6 +173,19 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
                     if (a.dbg_lo) a.dbg_lo[(int64_t)tok * a.L.N + n + v] = a_lo;
                 }
             }
+        }
+        if (a.swiglu) {
+            // two (gate, up) pairs per lane -> two outputs
+            const int64_t c = n >> 1, c_end = a.L.N >> 1;
+            uint16_t* d2 = a.y + (int64_t)tok * a.ldy + c;
+            const uint32_t pair = pack_bf16(silu_f32(out[0]) * out[1], silu_f32(out[2]) * out[3]);
+            if (c + 1 < c_end && ((reinterpret_cast<uintptr_t>(a.y) & 3) == 0) && (a.ldy % 2 == 0)) {
+                *reinterpret_cast<uint32_t*>(d2) = pair;
+            } else {
+                if (c < c_end) d2[0] = (uint16_t)pair;
+                if (c + 1 < c_end) d2[1] = (uint16_t)(pair >> 16);
+            }
+            continue;
         }
         uint16_t* dst = a.y + (int64_t)tok * a.ldy + n;
         if (n + 3 < a.L.N && ((reinterpret_cast<uintptr_t>(a.y) & 7) == 0) && (a.ldy % 4 == 0)) {

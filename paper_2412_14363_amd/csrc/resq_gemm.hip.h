@@ -106,7 +106,14 @@ struct GemmArgs {
     int32_t* dbg_lo;
     int stages_hi, stages_lo;
     int tiles_m, tiles_n;
+    int swiglu;  // 1: channels 2c and 2c+1 are the gate and the up row of feature c; y[m, c] = silu(gate) * up
 };
+
+// x * sigmoid(x) with the hardware exponential and reciprocal (well inside the
+// output tolerance)
+__device__ __forceinline__ float silu_f32(float x) {
+    return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * x));
+}
 
 __device__ __forceinline__ float fp16_bits_to_f32(uint32_t h) {
     return __uint_as_float((((h >> 10) & 0x1Fu) + 112u) << 23 | (h & 0x3FFu) << 13);
@@ -406,9 +413,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     // ASYM (asymmetric activation codes, stored minus 2^(N-1)): each group gains the
     // zero-point term c[m] * wsum[n] * sw[n], c the real value of the stored code 0
     // and wsum the sum of the channel's weight codes (Eq. 1 inserted into Eq. 4).
-    auto fold = [&](auto has_hi, auto has_lo, auto is_asym) __attribute__((always_inline)) {
+    // GLU (gated pair epilogue): the lane's four consecutive channels are two (gate, up)
+    // pairs; silu(gate) * up of each goes out, so the staged row is half as wide.
+    auto fold = [&](auto has_hi, auto has_lo, auto is_asym, auto is_glu) __attribute__((always_inline)) {
         constexpr bool HI_ON = decltype(has_hi)::value, LO_ON = decltype(has_lo)::value;
-        constexpr bool ASYM = decltype(is_asym)::value;
+        constexpr bool ASYM = decltype(is_asym)::value, GLU = decltype(is_glu)::value;
         const uint8_t* meta = lds + kMetaOff;
         float st_hi[2] = {0.f, 0.f}, st_lo[2] = {0.f, 0.f}, ct_hi[2] = {0.f, 0.f}, ct_lo[2] = {0.f, 0.f};
         int ca[2] = {0, 0};
@@ -496,8 +505,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                     }
                     const int row = 32 * i + (lane & 31);
                     const int col = 32 * j + 8 * vq + 4 * (lane >> 5);
-                    *reinterpret_cast<uint2*>(out_stage + row * kOutRowBytes + col * 2) =
-                        make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
+                    if constexpr (GLU)
+                        *reinterpret_cast<uint32_t*>(out_stage + row * kOutRowBytes + col) =
+                            pack_bf16(silu_f32(val[0]) * val[1], silu_f32(val[2]) * val[3]);
+                    else
+                        *reinterpret_cast<uint2*>(out_stage + row * kOutRowBytes + col * 2) =
+                            make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -681,14 +694,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             lds_wait_all(py);  // reads past the last stage: let them land
         }
         wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
-        if (asym) {
-            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, YES{});
-            else if (S_hi > 0) fold(YES{}, NO{}, YES{});
-            else fold(NO{}, YES{}, YES{});
+        if (a.swiglu) {  // symmetric codes only (checked on the host)
+            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, NO{}, YES{});
+            else if (S_hi > 0) fold(YES{}, NO{}, NO{}, YES{});
+            else fold(NO{}, YES{}, NO{}, YES{});
+        } else if (asym) {
+            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, YES{}, NO{});
+            else if (S_hi > 0) fold(YES{}, NO{}, YES{}, NO{});
+            else fold(NO{}, YES{}, YES{}, NO{});
         } else {
-            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, NO{});
-            else if (S_hi > 0) fold(YES{}, NO{}, NO{});
-            else fold(NO{}, YES{}, NO{});
+            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, NO{}, NO{});
+            else if (S_hi > 0) fold(YES{}, NO{}, NO{}, NO{});
+            else fold(NO{}, YES{}, NO{}, NO{});
         }
     }
 
@@ -698,6 +715,27 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     __syncthreads();
     const bool fast = ((reinterpret_cast<uintptr_t>(a.y) & 15) == 0) && (a.ldy % 8 == 0) &&
                       (n0 + kBN <= a.L.N);
+    if (a.swiglu) {
+        // 64 x 64 outputs per wave: eight 128-byte row segments per store instruction
+        const int64_t n_out = a.L.N / 2;
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int row = it * 8 + (lane >> 3);
+            const int64_t m = m0 + wm * 64 + row;
+            const int64_t n = n0 / 2 + wn * 64 + (lane & 7) * 8;
+            const uint4 v = *reinterpret_cast<const uint4*>(out_stage + row * kOutRowBytes + (lane & 7) * 16);
+            if (m >= a.M) continue;
+            if (fast) {
+                *reinterpret_cast<uint4*>(a.y + m * a.ldy + n) = v;
+            } else {
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < n_out) a.y[m * a.ldy + n + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int it = 0; it < 16; ++it) {
         const int row = it * 4 + (lane >> 4);

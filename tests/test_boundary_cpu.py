@@ -132,6 +132,14 @@ def test_asym_entry_points_reject_bad_arguments():
     assert g(P, P, P, P, P, P, P, 16, P, 256, 256, 32, P, 255, None, None, None) == 2
 
 
+def test_swiglu_entry_point_rejects_bad_arguments():
+    g = binding.lib().resq_gemm_mixed_swiglu
+    assert g(P, P, P, P, P, 16, P, 255, 256, 32, P, 256, None) == 2          # odd channel count
+    assert g(P, P, P, P, P, 16, P, 256, 256, 32, P, 127, None) == 2          # ldy < N2 / 2
+    assert g(P, P, P, P, P, 16, None, 256, 256, 32, P, 128, None) == 1
+    assert g(P, P, P, P, None, 16, P, 256, 256, 32, P, 128, None) == 1
+
+
 def test_binding_fails_loudly_without_device_tensors():
     import torch
     x = torch.zeros(4, 256, dtype=torch.bfloat16)

@@ -589,3 +589,21 @@ def test_asym_layer_tracks_reference_and_beats_symmetric_on_one_sided_data(oracl
     ref = wl.bits_to_f64(xb) @ wl.bits_to_f64(wb).T
     a, s_ = oracle.snr_db(ref, oracle.linear_asym(xb, wb, 32).y), oracle.snr_db(ref, oracle.linear(xb, wb, 32).y)
     assert abs(a - s_) < 3.0
+
+
+def test_swiglu_definition(oracle):
+    # silu against torch in fp64, its reflection identity silu(x) - silu(-x) = x, the
+    # pairing of columns (2c, 2c+1), and limits; catches swapped gate/up, sigmoid of the
+    # wrong operand, a split into halves instead of interleaved pairs
+    rng = np.random.default_rng(2)
+    y = rng.normal(size=(7, 10)) * 3
+    out = oracle.swiglu(y)
+    g, u = torch.tensor(y[:, 0::2]), torch.tensor(y[:, 1::2])
+    assert np.allclose(out, (torch.nn.functional.silu(g) * u).numpy(), rtol=1e-13, atol=1e-15)
+    ones = np.ones_like(y)
+    ones[:, 0::2] = y[:, 0::2]
+    neg = ones.copy()
+    neg[:, 0::2] = -y[:, 0::2]
+    assert np.allclose(oracle.swiglu(ones) - oracle.swiglu(neg), y[:, 0::2], rtol=1e-12)
+    probe = np.array([[0.0, 5.0, 40.0, 2.0, -40.0, 3.0]])
+    assert np.allclose(oracle.swiglu(probe), [[0.0, 80.0, 0.0]], atol=1e-12)

@@ -445,3 +445,27 @@ def test_online_head_projection_as_uniform_int8_layer(oracle, rq):
     x = torch.randn(rows, d, generator=g).to(torch.bfloat16)
     u = torch.linalg.qr(torch.randn(d, d, generator=g))[0].contiguous().to(torch.bfloat16)   # an orthogonal U_C
     check_layer(oracle, rq, x, u, d)
+
+
+# ---- gate/up as one layer with the gated activation in the epilogue ----------------
+
+@pytest.mark.parametrize("M,K,F,r", [
+    (130, 640, 150, 128), (64, 512, 256, 64), (300, 1024, 384, 0), (40, 256, 130, 256),   # tiled kernel
+    (1, 512, 128, 64), (16, 1000, 257, 104), (5, 256, 64, 0),                             # weight-streaming kernel
+])
+def test_layer_swiglu(oracle, rq, M, K, F, r):
+    x, w = wl.random_small_case(M + K + F, M, K, 2 * F, r, act="student_t3")
+    w = (w.float() * 8).to(torch.bfloat16)     # outputs of order one, so that silu is exercised off its linear part
+    act = rq.resq_quantize_act(x.cuda(), r)
+    packed = rq.resq_pack_weights(w.cuda(), r)
+    ref = oracle.swiglu(oracle.linear(wl.bf16_bits(x), wl.bf16_bits(w), r).y)
+    ybuf = torch.zeros((M, F + 8), dtype=torch.bfloat16, device="cuda")
+    y = rq.resq_gemm_mixed_swiglu(act, packed, 2 * F, y=ybuf[:, :F])
+    torch.cuda.synchronize()
+    rel = y_within_tolerance(y, ref)
+    assert rel <= REL_TOL, f"gated output off by {rel}"
+    assert not ybuf[:, F:].any(), "wrote past F"
+    # and it is the two-step computation on the plain layer's fp32 result, up to bf16 rounding in between
+    z = rq.resq_gemm_mixed(act, packed, 2 * F).float()
+    two_step = torch.nn.functional.silu(z[:, 0::2]) * z[:, 1::2]
+    assert (y.float() - two_step).abs().max() <= 0.03 * two_step.abs().max()
