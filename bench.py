@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E peak, GB/s
 # rocprofv3 --pmc runs, each scaled by what the same counter reads for a 1 GiB device copy
 # (x2.000 and x1.000; the summaries are under profiles/).  Absent = not measured.
 MEASURED_TRAFFIC = {
-    "oproj_prefill": 38.40e6 + 16.78e6,
+    "oproj_prefill": 38.42e6 + 16.78e6,
     "decode_m16": 133.61e6 + 0.92e6,
 }
 
