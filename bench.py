@@ -50,6 +50,8 @@ def workload_shape(name: str):
         "decode_m1": wl.decode_shape(1),
         "decode_m4": wl.decode_shape(4),
         "decode_m16": wl.decode_shape(16),
+        "decode_m32": wl.decode_shape(32),
+        "decode_m64": wl.decode_shape(64),
         "qwen_r0": wl.qwen_mlp_shape(0),
         "qwen_r1024": wl.qwen_mlp_shape(1024),
         "qwen_r2048": wl.qwen_mlp_shape(2048),
@@ -307,7 +309,7 @@ def main() -> None:
     if s.N == 0:
         quant_only_bench(args, s)
         return
-    decode = s.M <= 16
+    decode = s.M <= 64
     x = wl.make_activations(s)
     w = wl.make_weights(s)
     xd = x.cuda()

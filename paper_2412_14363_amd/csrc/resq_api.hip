@@ -286,6 +286,47 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         return launch_status();
     }
 
+    // a few tens of tokens: the same single pass over the weights, activation codes
+    // chunked through LDS
+    if (M <= kStreamMaxM) {
+        DecodeArgs d;
+        d.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
+        d.q_lo = q_lo;
+        d.ld_hi = L.kh_pad;
+        d.ld_lo = L.kl_pad / 2;
+        d.s_hi = s_hi;
+        d.s_lo = s_lo;
+        d.lo_sum = lo_sum;
+        d.c_hi = c_hi;
+        d.c_lo = c_lo;
+        d.packed = static_cast<const uint8_t*>(packed);
+        d.L = L;
+        d.M = (int)M;
+        d.y = static_cast<uint16_t*>(y);
+        d.ldy = ldy;
+        d.dbg_hi = dbg_acc_hi;
+        d.dbg_lo = dbg_acc_lo;
+        d.swiglu = swiglu ? 1 : 0;
+        d.groups = (int)((N + 15) / 16);
+        d.lds_row = 0;
+#define RESQ_LAUNCH_STREAM(TG, THREADS)                                                            \
+    do {                                                                                           \
+        const int sets = (d.groups + THREADS / 64 - 1) / (THREADS / 64);                           \
+        const dim3 grid((unsigned)(sets < 256 ? sets : 256)), blk(THREADS);                        \
+        auto kernel = dbg ? gemm_stream_kernel<true, TG, THREADS> : gemm_stream_kernel<false, TG, THREADS>; \
+        const int lds_bytes = 2 * kChunkBlocks * TG * kBlockBytes;                                 \
+        if (lds_bytes > 64 * 1024 &&                                                               \
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),                             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) \
+            return RESQ_ERR_HIP;                                                                   \
+        launch(kernel, grid, blk, lds_bytes, st, d);                                               \
+    } while (0)
+        if (M <= 32) RESQ_LAUNCH_STREAM(2, 512);
+        else RESQ_LAUNCH_STREAM(4, 512);
+#undef RESQ_LAUNCH_STREAM
+        return launch_status();
+    }
+
     GemmArgs a;
     a.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
     a.q_lo = q_lo;

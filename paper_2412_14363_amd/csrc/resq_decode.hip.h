@@ -48,6 +48,71 @@ struct DecodeArgs {
     int lds_row;      // bytes of one token row in LDS
 };
 
+// Epilogue of the weight-streaming kernels for one lane: token `tok`, channels
+// n .. n + 3, the two integer sums of each.  Dequantizes (Eq. 4), adds the
+// zero-point term of asymmetric activation codes, applies the gated pair
+// epilogue when asked, writes bf16 (and the integer sums in the debug build).
+template <bool DBG>
+__device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, int64_t n, v4i acc_hi,
+                                                v4i acc_lo) {
+    const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
+    const uint16_t* sw_lo = sw_hi + a.L.n_pad;
+    const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
+    const int32_t* wsum_hi = even_sum + a.L.n_pad;
+    const int32_t* wsum_lo = even_sum + 2 * a.L.n_pad;
+    const bool has_hi = a.L.r > 0, has_lo = a.L.K - a.L.r > 0;
+    const bool asym = a.c_hi != nullptr || a.c_lo != nullptr;
+    const float sth = has_hi ? a.s_hi[tok] : 0.f;
+    const float stl = has_lo ? a.s_lo[tok] : 0.f;
+    const int ca = has_lo ? a.lo_sum[tok] : 0;
+    const float cth = (asym && has_hi) ? a.c_hi[tok] : 0.f;
+    const float ctl = (asym && has_lo) ? a.c_lo[tok] : 0.f;
+    const uint2 sch = *reinterpret_cast<const uint2*>(sw_hi + n);
+    const uint2 scl = *reinterpret_cast<const uint2*>(sw_lo + n);
+    const int4 es = *reinterpret_cast<const int4*>(even_sum + n);
+    const float snh[4] = {fp16_bits_to_f32(sch.x & 0xFFFFu), fp16_bits_to_f32(sch.x >> 16),
+                          fp16_bits_to_f32(sch.y & 0xFFFFu), fp16_bits_to_f32(sch.y >> 16)};
+    const float snl[4] = {fp16_bits_to_f32(scl.x & 0xFFFFu), fp16_bits_to_f32(scl.x >> 16),
+                          fp16_bits_to_f32(scl.y & 0xFFFFu), fp16_bits_to_f32(scl.y >> 16)};
+    const int ev[4] = {es.x, es.y, es.z, es.w};
+    float out[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int a_hi = acc_hi[v];
+        const int a_lo = (acc_lo[v] - 128 * (ev[v] + ca)) >> 4;  // exact
+        out[v] = (float)a_hi * (sth * snh[v]) + (float)a_lo * (stl * snl[v]);
+        if (asym)
+            out[v] += cth * ((float)wsum_hi[n + v] * snh[v]) + ctl * ((float)wsum_lo[n + v] * snl[v]);
+        if constexpr (DBG) {
+            if (n + v < a.L.N) {
+                if (a.dbg_hi) a.dbg_hi[(int64_t)tok * a.L.N + n + v] = a_hi;
+                if (a.dbg_lo) a.dbg_lo[(int64_t)tok * a.L.N + n + v] = a_lo;
+            }
+        }
+    }
+    if (a.swiglu) {
+        // two (gate, up) pairs per lane -> two outputs
+        const int64_t c = n >> 1, c_end = a.L.N >> 1;
+        uint16_t* d2 = a.y + (int64_t)tok * a.ldy + c;
+        const uint32_t pair = pack_bf16(silu_f32(out[0]) * out[1], silu_f32(out[2]) * out[3]);
+        if (c + 1 < c_end && ((reinterpret_cast<uintptr_t>(a.y) & 3) == 0) && (a.ldy % 2 == 0)) {
+            *reinterpret_cast<uint32_t*>(d2) = pair;
+        } else {
+            if (c < c_end) d2[0] = (uint16_t)pair;
+            if (c + 1 < c_end) d2[1] = (uint16_t)(pair >> 16);
+        }
+        return;
+    }
+    uint16_t* dst = a.y + (int64_t)tok * a.ldy + n;
+    if (n + 3 < a.L.N && ((reinterpret_cast<uintptr_t>(a.y) & 7) == 0) && (a.ldy % 4 == 0)) {
+        *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16(out[0], out[1]), pack_bf16(out[2], out[3]));
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (n + v < a.L.N) dst[v] = (uint16_t)pack_bf16(out[v], 0.f);
+    }
+}
+
 template <bool DBG>
 __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // [M][lds_row]
@@ -100,20 +165,6 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
     const bool tok_live = tok < a.M;
     const uint8_t* arow = act + (tok_live ? tok : 0) * a.lds_row + (lane >> 4) * 16;
     const v4i zero = {0, 0, 0, 0};
-    const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
-    const uint16_t* sw_lo = sw_hi + a.L.n_pad;
-    const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
-    const bool has_hi = a.L.r > 0, has_lo = a.L.K - a.L.r > 0;
-    const float sth = (has_hi && tok_live) ? a.s_hi[tok] : 0.f;
-    const float stl = (has_lo && tok_live) ? a.s_lo[tok] : 0.f;
-    const int ca = (has_lo && tok_live) ? a.lo_sum[tok] : 0;
-    // asymmetric activations: zero-point term c[m] * wsum[n] * sw[n] per group
-    const bool asym = a.c_hi != nullptr || a.c_lo != nullptr;
-    const float cth = (asym && has_hi && tok_live) ? a.c_hi[tok] : 0.f;
-    const float ctl = (asym && has_lo && tok_live) ? a.c_lo[tok] : 0.f;
-    const int32_t* wsum_hi = even_sum + a.L.n_pad;
-    const int32_t* wsum_lo = even_sum + 2 * a.L.n_pad;
-
     for (; group < a.groups; group += 8 * gridDim.x) {
         const uint4* wp = reinterpret_cast<const uint4*>(a.packed + (int64_t)group * a.L.group_bytes + lane_off);
         v4i acc_hi = {0, 0, 0, 0}, acc_lo = {0, 0, 0, 0};
@@ -150,50 +201,164 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
 
         // lane l now holds token l % 16, channels 16 group + 4 (l / 16) + {0..3}
         if (!tok_live) continue;
-        const int64_t n = (int64_t)group * 16 + (lane >> 4) * 4;
-        const uint2 sch = *reinterpret_cast<const uint2*>(sw_hi + n);
-        const uint2 scl = *reinterpret_cast<const uint2*>(sw_lo + n);
-        const int4 es = *reinterpret_cast<const int4*>(even_sum + n);
-        const float snh[4] = {fp16_bits_to_f32(sch.x & 0xFFFFu), fp16_bits_to_f32(sch.x >> 16),
-                              fp16_bits_to_f32(sch.y & 0xFFFFu), fp16_bits_to_f32(sch.y >> 16)};
-        const float snl[4] = {fp16_bits_to_f32(scl.x & 0xFFFFu), fp16_bits_to_f32(scl.x >> 16),
-                              fp16_bits_to_f32(scl.y & 0xFFFFu), fp16_bits_to_f32(scl.y >> 16)};
-        const int ev[4] = {es.x, es.y, es.z, es.w};
-        float out[4];
+        stream_epilogue<DBG>(a, tok, (int64_t)group * 16 + (lane >> 4) * 4, acc_hi, acc_lo);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The same for 17 .. 64 tokens (batched generation): still one pass over the
+// packed weights, each 1 KiB block going from HBM into operand registers once
+// and meeting every group of 16 tokens there (TG = 2 or 4 groups, one accumulator
+// pair each; eight groups do not fit the registers next to the weight ring, and a
+// spill in the loop would wait for the whole ring on the shared load counter).  The activation codes no longer fit LDS whole, so the eight wavefronts
+// of a workgroup walk the reduction axis together in chunks of kChunkBlocks
+// blocks; a chunk of all tokens' codes sits in LDS as the 16-row x 64-byte
+// blocks of the tiled kernel (piece kc of row r at unit 4 r + (kc ^ (r >> 2)),
+// so the 16 lanes that read one piece of 16 rows hit 16 bank groups), and the
+// next chunk is fetched into registers while this one is multiplied, then
+// written to the other buffer: one barrier per chunk.
+// ---------------------------------------------------------------------------
+constexpr int kChunkBlocks = 8;
+static_assert(kChunkBlocks == kDecodeDepth, "a chunk fills the weight ring exactly once");
+constexpr int kStreamMaxM = 64;
+
+template <bool DBG, int TG, int THREADS>
+__global__ __launch_bounds__(THREADS) void gemm_stream_kernel(const DecodeArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t act[];  // [2][kChunkBlocks][TG] blocks of 1 KiB
+    constexpr int kChunkBytes = kChunkBlocks * TG * kBlockBytes;
+    constexpr int kWaves = THREADS / 64;
+    constexpr int kUnitsPerThread = kChunkBlocks * TG * 64 / THREADS;  // 16-byte units
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // wave-uniform, and known to be
+    const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
+    const int chunks = (blocks + kChunkBlocks - 1) / kChunkBlocks;
+    const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
+    // operand read: lane l supplies token l % 16, piece l / 16 of a block
+    const int rr = lane & 15, rk = lane >> 4;
+    const int read_off = (4 * rr + (rk ^ (rr >> 2))) * 16;
+
+    // Chunk loader.  A wavefront always fetches the same token group (wave % TG), so a
+    // thread reads one token row throughout: piece t % 4 of row (t / 4) % 16 of that
+    // group, in blocks wave / TG, wave / TG + kWaves / TG, ... of the chunk.
+    static_assert(kWaves % TG == 0, "a wavefront fetches one token group");
+    static_assert(TG * 16 <= kStreamMaxM, "token groups beyond the dispatch limit");
+    constexpr int kBlockStep = kWaves / TG;
+    const int f_kc = t & 3, f_r = (t >> 2) & 15, f_tg = wave % TG, f_b0 = wave / TG;
+    int f_m = f_tg * 16 + f_r;
+    f_m = f_m < a.M ? f_m : a.M - 1;  // rows past M repeat the last token (never stored)
+    const uint8_t* src_hi = a.q_hi + (int64_t)f_m * a.ld_hi + f_kc * 16;
+    const uint8_t* src_lo = a.q_lo + (int64_t)f_m * a.ld_lo + f_kc * 16 - (int64_t)hi_blocks * kRowBytes;
+    const int f_lds = f_tg * kBlockBytes + (4 * f_r + (f_kc ^ (f_r >> 2))) * 16;
+    uint4 stage[kUnitsPerThread];
+    auto fetch_chunk = [&](int c) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int a_hi = acc_hi[v];
-            const int a_lo = (acc_lo[v] - 128 * (ev[v] + ca)) >> 4;  // exact
-            out[v] = (float)a_hi * (sth * snh[v]) + (float)a_lo * (stl * snl[v]);
-            if (asym)
-                out[v] += cth * ((float)wsum_hi[n + v] * snh[v]) + ctl * ((float)wsum_lo[n + v] * snl[v]);
-            if constexpr (DBG) {
-                if (n + v < a.L.N) {
-                    if (a.dbg_hi) a.dbg_hi[(int64_t)tok * a.L.N + n + v] = a_hi;
-                    if (a.dbg_lo) a.dbg_lo[(int64_t)tok * a.L.N + n + v] = a_lo;
+        for (int q = 0; q < kUnitsPerThread; ++q) {
+            const int b = c * kChunkBlocks + f_b0 + q * kBlockStep;
+            stage[q] = make_uint4(0u, 0u, 0u, 0u);
+            if (b < blocks)
+                stage[q] = *reinterpret_cast<const uint4*>((b < hi_blocks ? src_hi : src_lo) + b * kRowBytes);
+        }
+    };
+    auto store_chunk = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < kUnitsPerThread; ++q)
+            *reinterpret_cast<uint4*>(act + buf * kChunkBytes + (f_b0 + q * kBlockStep) * (TG * kBlockBytes) + f_lds) = stage[q];
+    };
+
+    const int sets = (a.groups + kWaves - 1) / kWaves;  // a set = one 16-channel group per wavefront
+    for (int set = blockIdx.x; set < sets; set += gridDim.x) {
+        const int group = set * kWaves + wave;
+        const bool live = group < a.groups;
+        const uint4* wp = reinterpret_cast<const uint4*>(
+            a.packed + (int64_t)(live ? group : 0) * a.L.group_bytes + lane_off);
+        uint4 ring[kDecodeDepth];
+#pragma unroll
+        for (int i = 0; i < kDecodeDepth; ++i)
+            if (live && i < blocks) ring[i] = wp[i * (kBlockBytes / 16)];
+        __syncthreads();  // every wavefront is done with the LDS buffers of the previous set
+        fetch_chunk(0);
+        store_chunk(0);
+        __syncthreads();
+
+        v4i acc_hi[TG], acc_lo[TG];
+#pragma unroll
+        for (int g = 0; g < TG; ++g) {
+            acc_hi[g] = (v4i){0, 0, 0, 0};
+            acc_lo[g] = (v4i){0, 0, 0, 0};
+        }
+        for (int c = 0; c < chunks; ++c) {
+            if (c + 1 < chunks) fetch_chunk(c + 1);
+            const uint8_t* cur = act + (c & 1) * kChunkBytes + read_off;
+            // A block meets the token groups PG at a time; the fragments of the next PG
+            // groups are read while these are multiplied, and no further ahead (a whole
+            // chunk's fragments would not fit the registers).  KIND 0: a full chunk of
+            // high blocks; 1: a full chunk of low blocks; 2: anything else (the chunk
+            // that holds the boundary between the groups, a partial last chunk).
+            constexpr int PG = TG < 4 ? TG : 4;         // groups per pass
+            constexpr int PASSES = TG / PG;             // passes per block
+            auto chunk_body = [&](auto kind) __attribute__((always_inline)) {
+                constexpr int KIND = decltype(kind)::value;
+                v4i p[PG], pn[PG];
+#pragma unroll
+                for (int g = 0; g < PG; ++g) p[g] = *reinterpret_cast<const v4i*>(cur + g * kBlockBytes);
+#pragma unroll
+                for (int i = 0; i < kChunkBlocks; ++i) {
+                    const int b = c * kChunkBlocks + i;  // kChunkBlocks == kDecodeDepth: ring slot i
+                    const uint4 wq = ring[i];
+                    if (b + kDecodeDepth < blocks) ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
+                    const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
+                    const bool hi_block = KIND == 0 || (KIND == 2 && b < hi_blocks);
+                    const bool lo_block = KIND == 1 || (KIND == 2 && b >= hi_blocks && b < blocks);
+#pragma unroll
+                    for (int h = 0; h < PASSES; ++h) {
+                        constexpr int kLast = kChunkBlocks * PASSES - 1;
+                        const int step = i * PASSES + h;
+                        if (step < kLast) {
+                            const int ni = (step + 1) / PASSES, nh = (step + 1) % PASSES;
+#pragma unroll
+                            for (int g = 0; g < PG; ++g)
+                                pn[g] = *reinterpret_cast<const v4i*>(cur + (ni * TG + nh * PG + g) * kBlockBytes);
+                        }
+                        if (hi_block) {
+#pragma unroll
+                            for (int g = 0; g < PG; ++g)
+                                acc_hi[h * PG + g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, p[g], acc_hi[h * PG + g], 0, 0, 0);
+                        }
+                        if (lo_block) {
+                            // see resq_gemm.hip.h: one operand of each product carries an offset of 8
+                            const v4i we = w & (int)0xF0F0F0F0, wo = w & (int)0x0F0F0F0F;
+#pragma unroll
+                            for (int g = 0; g < PG; ++g) {
+                                acc_lo[h * PG + g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                    we, p[g] & (int)0x0F0F0F0F, acc_lo[h * PG + g], 0, 0, 0);
+                                acc_lo[h * PG + g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                    wo, p[g] & (int)0xF0F0F0F0, acc_lo[h * PG + g], 0, 0, 0);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (step < kLast) {
+#pragma unroll
+                            for (int g = 0; g < PG; ++g) p[g] = pn[g];
+                        }
+                    }
                 }
+            };
+            if (live) {
+                const int first = c * kChunkBlocks, last = first + kChunkBlocks;
+                if (last <= hi_blocks) chunk_body(std::integral_constant<int, 0>{});
+                else if (first >= hi_blocks && last <= blocks) chunk_body(std::integral_constant<int, 1>{});
+                else chunk_body(std::integral_constant<int, 2>{});
             }
+            if (c + 1 < chunks) store_chunk((c + 1) & 1);  // that buffer was last read in chunk c - 1
+            __syncthreads();
         }
-        if (a.swiglu) {
-            // two (gate, up) pairs per lane -> two outputs
-            const int64_t c = n >> 1, c_end = a.L.N >> 1;
-            uint16_t* d2 = a.y + (int64_t)tok * a.ldy + c;
-            const uint32_t pair = pack_bf16(silu_f32(out[0]) * out[1], silu_f32(out[2]) * out[3]);
-            if (c + 1 < c_end && ((reinterpret_cast<uintptr_t>(a.y) & 3) == 0) && (a.ldy % 2 == 0)) {
-                *reinterpret_cast<uint32_t*>(d2) = pair;
-            } else {
-                if (c < c_end) d2[0] = (uint16_t)pair;
-                if (c + 1 < c_end) d2[1] = (uint16_t)(pair >> 16);
-            }
-            continue;
-        }
-        uint16_t* dst = a.y + (int64_t)tok * a.ldy + n;
-        if (n + 3 < a.L.N && ((reinterpret_cast<uintptr_t>(a.y) & 7) == 0) && (a.ldy % 4 == 0)) {
-            *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16(out[0], out[1]), pack_bf16(out[2], out[3]));
-        } else {
+        if (!live) continue;
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (n + v < a.L.N) dst[v] = (uint16_t)pack_bf16(out[v], 0.f);
+        for (int g = 0; g < TG; ++g) {
+            const int tok = g * 16 + (lane & 15);
+            if (tok < a.M)
+                stream_epilogue<DBG>(a, tok, (int64_t)group * 16 + (lane >> 4) * 4, acc_hi[g], acc_lo[g]);
+            __builtin_amdgcn_sched_barrier(0);  // one token group at a time: keeps the registers few
         }
     }
 }

@@ -188,6 +188,27 @@ def test_layer_decode_shapes(oracle, rq, M, K, N, r):
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
+@pytest.mark.parametrize("M,K,N,r", [
+    (17, 8192, 528, 1024), (32, 4096, 272, 512),         # two token groups
+    (33, 1000, 515, 104), (64, 14336, 144, 1792),        # four; K, r off the block size; longest K
+    (65, 2048, 400, 256), (100, 4096, 130, 512), (128, 8192, 272, 1024),   # eight
+    (128, 3200, 256, 448),                               # high blocks end inside a chunk of eight
+    (90, 256, 256, 0), (128, 256, 64, 256),              # uniform INT4, uniform INT8
+    (40, 90, 40, 30),                                    # everything smaller than one chunk
+])
+def test_layer_batched_decode_shapes(oracle, rq, M, K, N, r):
+    # 16 < M <= 64 takes the weight-streaming kernel with the activation codes chunked through LDS;
+    # the larger M here sit on the other side of that dispatch boundary
+    x, w = wl.random_small_case(M * 13 + K, M, K, N, r, outliers="first4")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+def test_layer_batched_decode_full_size(oracle, rq):
+    # the decode workload's layer with 64 tokens in flight; every accumulator and output
+    s = wl.decode_shape(64)
+    check_layer(oracle, rq, wl.make_activations(s), wl.make_weights(s), s.r)
+
+
 def test_layer_decode_full_size(oracle, rq):
     # the decode workload at full size (Llama-3-70B up_proj, 16 tokens); the oracle
     # checks all codes and every accumulator and output
@@ -400,6 +421,7 @@ def test_quantize_act_asym_constant_rows_and_ties(oracle, rq):
     (130, 640, 300, 128), (257, 1000, 515, 104), (64, 4096, 512, 512), (200, 90, 40, 30),
     (48, 512, 256, 0), (48, 512, 256, 512),          # tiled kernel
     (1, 512, 256, 64), (16, 1000, 515, 104), (7, 2048, 272, 256), (3, 256, 256, 0),   # weight-streaming kernel
+    (24, 2048, 272, 256), (100, 4096, 130, 512), (128, 1000, 515, 104),               # 16 < M <= 64: streaming with chunked codes; above: tiled
 ])
 def test_layer_asym(oracle, rq, M, K, N, r):
     x, w = wl.random_small_case(M * 5 + K, M, K, N, r, act="student_t3")
@@ -452,6 +474,7 @@ def test_online_head_projection_as_uniform_int8_layer(oracle, rq):
 @pytest.mark.parametrize("M,K,F,r", [
     (130, 640, 150, 128), (64, 512, 256, 64), (300, 1024, 384, 0), (40, 256, 130, 256),   # tiled kernel
     (1, 512, 128, 64), (16, 1000, 257, 104), (5, 256, 64, 0),                             # weight-streaming kernel
+    (20, 1000, 257, 104), (128, 2048, 136, 256),                                          # 16 < M <= 64: streaming with chunked codes; above: tiled
 ])
 def test_layer_swiglu(oracle, rq, M, K, F, r):
     x, w = wl.random_small_case(M + K + F, M, K, 2 * F, r, act="student_t3")
