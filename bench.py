@@ -56,6 +56,7 @@ def workload_shape(name: str):
         "qwen_r1024": wl.qwen_mlp_shape(1024),
         "qwen_r2048": wl.qwen_mlp_shape(2048),
         "kv_quant": wl.KV_CACHE_QUANT,
+        "uc_proj": wl.UC_PROJ,
     }
     if name not in table:
         raise SystemExit(f"unknown workload {name!r}; choose from {sorted(table)}")
@@ -67,6 +68,21 @@ def algorithmic_bytes_gemm(s) -> int:
     packed weights with their scales, and the bf16 output."""
     per_tok = s.r + (s.K - s.r) // 2 + 12
     return s.M * per_tok + s.N * (s.r + (s.K - s.r) // 2 + 8) + 2 * s.M * s.N
+
+
+def output_snr_db(x, w, y, rows: int = 32, cols: int = 4096) -> float:
+    """10 log10(sum ref^2 / sum (ref - y)^2) of the layer's output against the unquantized
+    product X W^T in fp64, on a strided sample of token rows and output channels (the
+    accuracy-side figure of Section 5: what a given r buys on these inputs)."""
+    import numpy as np
+    M, N = y.shape
+    ri = np.unique(np.linspace(0, M - 1, min(rows, M)).astype(np.int64))
+    ci = np.unique(np.linspace(0, N - 1, min(cols, N)).astype(np.int64))
+    import torch
+    rt, ct = torch.from_numpy(ri), torch.from_numpy(ci)
+    ref = x[rt].double().numpy() @ w[ct].double().numpy().T
+    got = y[rt.to(y.device)].cpu()[:, ct].double().numpy()
+    return float(10.0 * np.log10((ref ** 2).sum() / ((ref - got) ** 2).sum()))
 
 
 def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 0,
@@ -171,6 +187,83 @@ def quant_only_bench(args, s) -> None:
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": abytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
                                "kind": "oracle", "sample": f"all {s.M} rows, {dt:.2f} s"}
+    print(json.dumps(out))
+
+
+def head_proj_bench(args, s) -> None:
+    """The online 8-bit projection of query and key heads onto the cache basis as one kernel
+    (row quantizer + INT8 product + dequantization): HBM-bound, GB/s of algorithmic bytes."""
+    import ctypes
+    import torch
+    from paper_2412_14363_amd import binding as rq
+    from paper_2412_14363_amd import workloads as wl
+
+    x = wl.make_activations(s)
+    u = wl.random_orthogonal(s.K, s.seed + 1).to(torch.bfloat16).contiguous()
+    xd = x.cuda()
+    packed = rq.resq_pack_weights(u.cuda(), s.K)
+    y = torch.empty((s.M, s.N), dtype=torch.bfloat16, device="cuda")
+    L = rq.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    pa = (xd.data_ptr(), s.K, s.M, s.K, packed.data_ptr(), y.data_ptr(), s.N, st)
+
+    def step(events=None):
+        if events is not None:
+            L.resq_time_next_kernel(*events)
+        rc = L.resq_project_heads(*pa)
+        assert rc == 0, rc
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    hip = ctypes.CDLL("libamdhip64.so")
+    evs = []
+    for _ in range(args.steps):
+        a, b = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+        evs.append((a, b))
+        step((a, b))
+    torch.cuda.synchronize()
+    tot = 0.0
+    for a, b in evs:
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        tot += ms.value
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(b)
+    kernel_ms = tot / args.steps
+    abytes = s.M * (2 * s.K + 2 * s.N) + s.N * (s.K + 4)   # rows in and out, U_C codes and scales
+    out = {
+        "metric": "online head projection GB/s (% HBM peak)",
+        "value": abytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"{s.name}: rows={s.M} d_head={s.K}", "tag": args.workload,
+                   "step": "project_heads (quantize rows + W8A8 product + dequantize, one kernel)",
+                   "activations": "symmetric per head"},
+        "tops": 2.0 * s.M * s.N * s.K / (ms_per_step * 1e-3) / 1e12,
+        "roofline": {"bound": "hbm", "achieved": abytes / (kernel_ms * 1e-3) / 1e9,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "resq project_heads", "kernel_ms": kernel_ms},
+        "snr_db": output_snr_db(x, u, y),
+    }
+    if not args.no_cpu_baseline:
+        from oracle import resq_oracle as oracle
+        rows = min(s.M, 8192)
+        xb, ub = wl.bf16_bits(x[:rows].contiguous()), wl.bf16_bits(u)
+        t0 = time.perf_counter()
+        oracle.linear(xb, ub, s.K)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": abytes * rows / s.M / dt / 1e9, "unit": "GB/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"first {rows} of {s.M} rows, {dt:.2f} s"}
     print(json.dumps(out))
 
 
@@ -306,6 +399,9 @@ def main() -> None:
         mlp_block_bench(args)
         return
     s = workload_shape(args.workload)
+    if args.workload == "uc_proj":
+        head_proj_bench(args, s)
+        return
     if s.N == 0:
         quant_only_bench(args, s)
         return
@@ -442,6 +538,8 @@ def main() -> None:
         "hadamard_ms": had_ms, "quantize_ms": quant_ms, "gemm_ms": gemm_ms,
         "roofline": roof,
     }
+    if not s.hadamard:
+        out["snr_db"] = output_snr_db(x, w, y)
     if not args.no_cpu_baseline:
         from oracle import resq_oracle as oracle
         wq_np = oracle.quantize_weights(wl.bf16_bits(w), s.r)

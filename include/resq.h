@@ -233,6 +233,27 @@ int resq_gemm_mixed_swiglu(const int8_t* q_hi, const uint8_t* q_lo, const float*
                            int64_t N2, int64_t K, int64_t r, void* y, int64_t ldy, void* stream);
 
 /*
+ * The online projection of queries and keys onto the basis of the K/V cache
+ * (Section 4.3: after the position embedding each head is multiplied by the
+ * d_head x d_head matrix U_C, with 8-bit weights and 8-bit activations), as one
+ * kernel: every row of x (one head of one token) is quantized to INT8 with its
+ * own symmetric scale (Section 3 Eq. 1), multiplied by the INT8 codes of U_C
+ * and dequantized (Section 4.1 Eq. 4 with every column in the high group).
+ * The result equals resq_quantize_act followed by resq_gemm_mixed with
+ * K = N = r = d_head; the activation codes never go to memory.
+ *   x        bf16 [rows, ldx], ldx >= d_head                 (read)
+ *   rows     tokens x heads; 0 is allowed and does nothing (no pointer is looked at)
+ *   d_head   64 or 128 (else RESQ_ERR_SHAPE: use the two calls above)
+ *   packed   resq_pack_weights of the [d_head, d_head] matrix whose row n is
+ *            column n of U_C (the weight of output channel n), r = d_head
+ *   y        bf16 [rows, ldy], ldy >= d_head                 (written)
+ * Alignment: x 16 bytes and ldx % 8 == 0 (else RESQ_ERR_ALIGN); packed 256
+ * bytes; y 2 bytes (rows aligned to d_head / 8 bytes are written with wider stores).
+ */
+int resq_project_heads(const void* x, int64_t ldx, int64_t rows, int64_t d_head, const void* packed,
+                       void* y, int64_t ldy, void* stream);
+
+/*
  * The layer for asymmetric activation codes (resq_quantize_act_asym): inserting
  * x ~ stored * s + c (Section 3 Eq. 1) and w ~ code * sw into Section 4.1 Eq. 4
  * gives, per group,

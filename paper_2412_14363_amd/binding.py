@@ -33,6 +33,7 @@ SYMBOLS = {
     "resq_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p]),
     "resq_gemm_mixed_asym": (C.c_int, [_p, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
     "resq_gemm_mixed_swiglu": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p]),
+    "resq_project_heads": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _i64, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
     "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
     "resq_gemm_mixed": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
@@ -274,6 +275,25 @@ def resq_gemm_mixed_swiglu(act: ActCodes, packed: torch.Tensor, N2: int,
         act.lo_sum.data_ptr() if lo else None, M, _dev(packed, torch.uint8, "packed"), N2, K, r,
         _dev(y, torch.bfloat16, "y"), y.stride(0), _stream(stream))
     _check(st, "resq_gemm_mixed_swiglu")
+    return y
+
+
+def resq_project_heads(x: torch.Tensor, packed: torch.Tensor, y: Optional[torch.Tensor] = None,
+                       stream=None) -> torch.Tensor:
+    """x: bf16 [rows, d_head] (one row per token and head); packed: resq_pack_weights of the
+    [d_head, d_head] matrix of output-channel rows with r = d_head; returns bf16 [rows, d_head]."""
+    rows, d = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    if y is None:
+        y = torch.empty((rows, d), dtype=torch.bfloat16, device=x.device)
+    if y.stride(1) != 1:
+        raise ValueError("y must be row-major")
+    st = lib().resq_project_heads(_dev(x, torch.bfloat16, "x"), x.stride(0), rows, d,
+                                  _dev(packed, torch.uint8, "packed"),
+                                  _dev(y, torch.bfloat16, "y"), y.stride(0),
+                                  _stream(stream))
+    _check(st, "resq_project_heads")
     return y
 
 

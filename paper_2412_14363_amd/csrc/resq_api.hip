@@ -8,6 +8,7 @@
 #include "resq_decode.hip.h"
 #include "resq_gemm.hip.h"
 #include "resq_hadamard.hip.h"
+#include "resq_headproj.hip.h"
 #include "resq_layout.h"
 #include "resq_quantize.hip.h"
 
@@ -426,6 +427,32 @@ int resq_online_hadamard(const void* x, void* y, int64_t ld, int64_t M, int64_t 
         case 8: launch(hadamard_kernel<8>, grid, blk, 0, st, a); break;
         default: launch(hadamard_kernel<16>, grid, blk, 0, st, a); break;
     }
+    return launch_status();
+}
+
+int resq_project_heads(const void* x, int64_t ldx, int64_t rows, int64_t d_head, const void* packed,
+                       void* y, int64_t ldy, void* stream) {
+    if (rows < 0 || rows > 0x7FFFFFFF || (d_head != 64 && d_head != 128) || ldx < d_head || ldy < d_head)
+        return RESQ_ERR_SHAPE;
+    if (rows == 0) return RESQ_OK;
+    if (!x || !packed || !y) return RESQ_ERR_NULL;
+    if (!aligned(x, 16) || ldx % 8 != 0 || !aligned(packed, 256) || !aligned(y, 2)) return RESQ_ERR_ALIGN;
+    HeadProjArgs a;
+    a.x = static_cast<const uint16_t*>(x);
+    a.ldx = ldx;
+    a.rows = rows;
+    a.packed = static_cast<const uint8_t*>(packed);
+    a.L = make_weight_layout(d_head, d_head, d_head);
+    a.y = static_cast<uint16_t*>(y);
+    a.ldy = ldy;
+    const int store_bytes = (int)d_head / 8;  // d_head / 16 consecutive channels per lane
+    a.vec_store = aligned(y, store_bytes) && (ldy * 2) % store_bytes == 0;
+    const int64_t tiles = (rows + 15) / 16;
+    const int64_t wgs = (tiles + kHeadProjThreads / 64 - 1) / (kHeadProjThreads / 64);
+    const dim3 grid((unsigned)(wgs < 768 ? wgs : 768)), blk(kHeadProjThreads);  // three per compute unit
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (d_head == 128) launch(head_project_kernel<128>, grid, blk, 0, st, a);
+    else launch(head_project_kernel<64>, grid, blk, 0, st, a);
     return launch_status();
 }
 

@@ -126,10 +126,11 @@ __device__ __forceinline__ float absmax8(const uint4& v) {
 // few ulp of the correctly rounded quotient, and rint(t) equals rint(x / scale)
 // whenever t is further than that from every half-integer.  Elements within
 // qmax * 2^-20 of a half-integer (|t| <= qmax, so at least 8 ulp of t) are
-// redone with the true division, in a branch that is taken only by the
-// wavefronts that hold such an element.  The codes are therefore exactly those
-// of the definition.  (bf16 inputs make exact ties common, about 2 in 10^4
-// elements, so the branch is not rare, but it is cheap on average.)
+// redone with the true division, in branches that are taken only by the
+// wavefronts that hold such an element, for the element slots that hold one.
+// The codes are therefore exactly those of the definition.  (bf16 inputs make
+// exact ties common: about 2 in 10^4 elements of a 4096-wide row, 1 in 10^3 of
+// a 128-wide one, so the branches are not rare, but cheap on average.)
 // ---------------------------------------------------------------------------
 // Eight elements at once.  On return the low bits of u[j] hold the two's
 // complement code of element j (plus 8 for even j when LOW, the offset-binary
@@ -143,7 +144,7 @@ __device__ __forceinline__ void quant8(const uint4& v, float scale, float inv, u
     constexpr int qmax = LOW ? kQmaxLo : kQmaxHi;
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
     float xs[8], rr[8];
-    bool near_tie = false;
+    bool near_tie[8], any_tie = false;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         xs[j] = __uint_as_float((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
@@ -151,15 +152,21 @@ __device__ __forceinline__ void quant8(const uint4& v, float scale, float inv, u
         const float t = xs[j] * inv;
         const float uf = t + magic;
         rr[j] = uf - kMagic;                    // rint(t) (+ 8), exact
-        near_tie |= fabsf(t - (uf - magic)) > 0.5f - (LOW ? 8.0f : 128.0f) * 9.5367431640625e-07f;
+        near_tie[j] = fabsf(t - (uf - magic)) > 0.5f - (LOW ? 8.0f : 128.0f) * 9.5367431640625e-07f;
+        any_tie |= near_tie[j];
         u[j] = __float_as_uint(uf);
     }
-    if (__builtin_amdgcn_ballot_w64(near_tie) != 0) {  // wave-uniform: rarely taken
+    // Wave-uniform branches.  With short rows (one attention head) a wavefront holds a
+    // near-tie more often than not, so the redo is per element slot: one division for
+    // the slots in which some lane has one, not eight.
+    if (__builtin_amdgcn_ballot_w64(any_tie) != 0) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int c = quant_code(xs[j], scale, qmax) + ((LOW && !(j & 1)) ? 8 : 0);
-            u[j] = (uint32_t)c;
-            rr[j] = (float)c;
+            if (__builtin_amdgcn_ballot_w64(near_tie[j]) != 0) {
+                const int c = quant_code(xs[j], scale, qmax) + ((LOW && !(j & 1)) ? 8 : 0);
+                u[j] = (uint32_t)c;
+                rr[j] = (float)c;
+            }
         }
     }
     if (LOW) odd_sum += (rr[1] + rr[3]) + (rr[5] + rr[7]);
@@ -177,7 +184,7 @@ __device__ __forceinline__ void quant8_asym(const uint4& v, float zero, float sc
     constexpr int levels = LOW ? 15 : 255;
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
     float ds[8], rr[8];
-    bool near_tie = false;
+    bool near_tie[8], any_tie = false;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const float x = __uint_as_float((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
@@ -186,17 +193,20 @@ __device__ __forceinline__ void quant8_asym(const uint4& v, float zero, float sc
         const float t = ds[j] * inv;
         const float uf = t + (kMagic - off);
         rr[j] = uf - kMagic;                    // rint(t) - off, exact
-        near_tie |= fabsf(t - (uf - (kMagic - off))) > 0.5f - (LOW ? 16.0f : 256.0f) * 9.5367431640625e-07f;
+        near_tie[j] = fabsf(t - (uf - (kMagic - off))) > 0.5f - (LOW ? 16.0f : 256.0f) * 9.5367431640625e-07f;
+        any_tie |= near_tie[j];
         u[j] = __float_as_uint(uf);
     }
-    if (__builtin_amdgcn_ballot_w64(near_tie) != 0) {  // wave-uniform
+    if (__builtin_amdgcn_ballot_w64(any_tie) != 0) {  // wave-uniform, then per element slot
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            float q = rintf(ds[j] / scale);
-            q = fminf(fmaxf(q, 0.0f), (float)levels);
-            const int c = (int)q - (LOW ? ((j & 1) ? 8 : 0) : 128);
-            u[j] = (uint32_t)c;
-            rr[j] = (float)c;
+            if (__builtin_amdgcn_ballot_w64(near_tie[j]) != 0) {
+                float q = rintf(ds[j] / scale);
+                q = fminf(fmaxf(q, 0.0f), (float)levels);
+                const int c = (int)q - (LOW ? ((j & 1) ? 8 : 0) : 128);
+                u[j] = (uint32_t)c;
+                rr[j] = (float)c;
+            }
         }
     }
     if (LOW) odd_sum += (rr[1] + rr[3]) + (rr[5] + rr[7]);

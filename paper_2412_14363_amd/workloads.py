@@ -57,6 +57,10 @@ MLP_DOWN = LayerShape("llama3_8b_down_prefill", M=4096, K=14336, N=4096, r=1792,
 KV_CACHE_QUANT = LayerShape("llama3_8b_kv_cache_quant", M=2048 * 8 * 2, K=128, N=0, r=16,
                             act="student_t3", seed=7)
 
+# The online projection of queries (32 heads) and keys (8 heads) after RoPE onto the cache
+# basis U_C, in 8 bits: one row per token and head, K = N = d_head, every column high.
+UC_PROJ = LayerShape("llama3_8b_uc_proj_prefill", M=2048 * (32 + 8), K=128, N=128, r=128, seed=8)
+
 
 def decode_shape(M: int) -> LayerShape:
     return LayerShape(f"llama3_70b_up_decode_m{M}", M=M, K=8192, N=28672, r=1024,

@@ -140,6 +140,19 @@ def test_swiglu_entry_point_rejects_bad_arguments():
     assert g(P, P, P, P, None, 16, P, 256, 256, 32, P, 128, None) == 1
 
 
+def test_project_heads_rejects_bad_arguments():
+    g = binding.lib().resq_project_heads
+    assert g(P, 128, 64, 96, P, P, 128, None) == 2                           # d_head not 64 / 128
+    assert g(P, 120, 64, 128, P, P, 128, None) == 2                          # ldx < d_head
+    assert g(P, 128, 64, 128, P, P, 100, None) == 2                          # ldy < d_head
+    assert g(P, 128, -1, 128, P, P, 128, None) == 2
+    assert g(None, 128, 64, 128, P, P, 128, None) == 1
+    assert g(P, 128, 64, 128, None, P, 128, None) == 1
+    assert g(P, 132, 64, 128, P, P, 128, None) == 3                          # rows not 16-byte aligned
+    assert g(P + 8, 128, 64, 128, P, P, 128, None) == 3
+    assert g(P, 128, 0, 128, P, P, 128, None) == 0                           # no rows: nothing to do
+
+
 def test_binding_fails_loudly_without_device_tensors():
     import torch
     x = torch.zeros(4, 256, dtype=torch.bfloat16)

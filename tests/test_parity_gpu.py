@@ -469,6 +469,36 @@ def test_online_head_projection_as_uniform_int8_layer(oracle, rq):
     check_layer(oracle, rq, x, u, d)
 
 
+@pytest.mark.parametrize("rows,d,ldx_extra,ldy_extra", [
+    (32 * 40, 128, 0, 0), (32 * 40 + 5, 128, 0, 0), (1, 128, 0, 0), (31, 128, 8, 4), (33, 128, 16, 3),
+    (700, 64, 0, 0), (45, 64, 8, 1), (4096 * 5 + 17, 128, 0, 0),      # the last: more tiles than wavefronts in flight
+])
+def test_project_heads_fused(oracle, rq, rows, d, ldx_extra, ldy_extra):
+    # the same projection as one kernel: row quantizer, INT8 product and dequantization,
+    # against the oracle's layer with every column high, and against the two-kernel path
+    g = torch.Generator().manual_seed(rows + d)
+    xbuf = torch.randn(rows, d + ldx_extra, generator=g).to(torch.bfloat16)
+    xbuf[rows // 2] = 0                                              # an all-zero head: scale 1, output 0
+    x = xbuf[:, :d]
+    u = torch.linalg.qr(torch.randn(d, d, generator=g))[0].contiguous().to(torch.bfloat16)
+    packed = rq.resq_pack_weights(u.cuda(), d)
+    ybuf = torch.zeros((rows, d + ldy_extra), dtype=torch.bfloat16, device="cuda")
+    y = rq.resq_project_heads(xbuf.cuda()[:, :d], packed, y=ybuf[:, :d])
+    torch.cuda.synchronize()
+    ref = oracle.linear(wl.bf16_bits(x.contiguous()), wl.bf16_bits(u), d)
+    rel = y_within_tolerance(y, ref.y)
+    assert rel <= REL_TOL, f"projected heads off by {rel}"
+    assert not ybuf[:, d:].any(), "wrote past d_head"
+    two = rq.resq_gemm_mixed(rq.resq_quantize_act(x.contiguous().cuda(), d), packed, d)
+    assert torch.equal(y, two)
+
+
+def test_project_heads_no_rows(rq):
+    packed = rq.resq_pack_weights(torch.eye(128, dtype=torch.bfloat16, device="cuda"), 128)
+    y = rq.resq_project_heads(torch.empty((0, 128), dtype=torch.bfloat16, device="cuda"), packed)
+    assert y.shape == (0, 128)
+
+
 # ---- gate/up as one layer with the gated activation in the epilogue ----------------
 
 @pytest.mark.parametrize("M,K,F,r", [
@@ -492,3 +522,25 @@ def test_layer_swiglu(oracle, rq, M, K, F, r):
     z = rq.resq_gemm_mixed(act, packed, 2 * F).float()
     two_step = torch.nn.functional.silu(z[:, 0::2]) * z[:, 1::2]
     assert (y.float() - two_step).abs().max() <= 0.03 * two_step.abs().max()
+
+
+# ---- SNR per rank: the accuracy-side figure of the rank ablation (Section 5.4) -----
+
+def test_snr_per_rank_matches_oracle(oracle, rq):
+    # Qwen2.5-72B MLP proportions at 1/16 scale, r in {0, K/8, K/4}: the output SNR of the
+    # HIP path equals the oracle's (same codes, bf16 rounding aside) and grows with r
+    import numpy as np
+    shape = wl.LayerShape("snr", M=96, K=512, N=1848, r=0, act="student_t3", outliers="one_percent_hi", seed=5)
+    x, w = wl.make_activations(shape), wl.make_weights(shape)
+    xb, wb = wl.bf16_bits(x), wl.bf16_bits(w)
+    ref = wl.bits_to_f64(xb) @ wl.bits_to_f64(wb).T
+    got = []
+    for r in (0, 64, 128):
+        act = rq.resq_quantize_act(x.cuda(), r)
+        y = rq.resq_gemm_mixed(act, rq.resq_pack_weights(w.cuda(), r), shape.N)
+        torch.cuda.synchronize()
+        snr_gpu = oracle.snr_db(ref, y.float().cpu().numpy())
+        snr_cpu = oracle.snr_db(ref, oracle.linear(xb, wb, r).y)
+        assert abs(snr_gpu - snr_cpu) < 0.05, (r, snr_gpu, snr_cpu)
+        got.append(snr_gpu)
+    assert got[0] < got[1] < got[2], got
