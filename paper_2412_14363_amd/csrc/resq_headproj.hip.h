@@ -17,10 +17,11 @@
 // for is free as long as both operands agree, so step s takes columns
 // (l / 16) d_head / 4 + 16 s of the activation row and of the weight row: no
 // exchange between lanes.  The whole of U_C (d_head^2 bytes) is copied to LDS
-// once per workgroup and from there into registers once per wavefront; column
+// once per workgroup (while the first rows are quantized) and from there into
+// registers once per wavefront; column
 // slot c of tile j stands for channel (d_head / 16) c + j, so that a lane ends
 // with d_head / 16 consecutive channels of a row and a store instruction writes
-// four whole rows.  The next 16 rows are loaded while these are worked on.
+// four whole rows.  The next 16 rows are loaded while these are multiplied and written.
 //
 // Roofline: HBM (2 d_head bytes read and 2 d_head written per row); the row
 // quantizer's vector-ALU work is of the same order.
@@ -72,17 +73,37 @@ __global__ __launch_bounds__(kHeadProjThreads) void head_project_kernel(const He
     uint4 v[UNITS];
     if (tile < tiles) load_tile(tile, v);
 
+    // quantize the 16 x D values a wavefront holds: row scale and the operand of each step
+    auto quantize_tile = [&](const uint4 (&rowv)[UNITS], v4i (&qa)[KS], float& st) {
+        float amax = 0.0f;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) amax = fmaxf(amax, absmax8(rowv[u]));
+        amax = fmaxf(amax, lane_xor<16>(amax));
+        amax = fmaxf(amax, lane_xor<32>(amax));
+        st = group_scale(amax, kQmaxHi);
+        const float inv = 1.0f / st;
+        float unused = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            uint32_t c0[8], c1[8];
+            quant8<false>(rowv[2 * s], st, inv, c0, unused);
+            quant8<false>(rowv[2 * s + 1], st, inv, c1, unused);
+            qa[s] = (v4i){(int)pack_low_bytes(c0[0], c0[1], c0[2], c0[3]), (int)pack_low_bytes(c0[4], c0[5], c0[6], c0[7]),
+                          (int)pack_low_bytes(c1[0], c1[1], c1[2], c1[3]), (int)pack_low_bytes(c1[4], c1[5], c1[6], c1[7])};
+        }
+    };
+
     // U_C: the D / 16 channel groups of the packed image, two high blocks each (the
-    // second one is padding when D = 64), are contiguous
-    {
-        constexpr int kBytes = (D / 16) * 2 * kBlockBytes;
-        const uint4* src = reinterpret_cast<const uint4*>(a.packed);
-        for (int i = t; i < kBytes / 16; i += kHeadProjThreads) reinterpret_cast<uint4*>(wlds)[i] = src[i];
+    // second one is padding when D = 64), are contiguous.  They go to LDS by direct
+    // loads (1 KiB per wavefront and instruction), and the first tile is quantized
+    // while those are in flight.
+    constexpr int kStageLoads = (D / 16) * 2 / kWaves;  // blocks per wavefront
+    static_assert(kStageLoads * kWaves == (D / 16) * 2, "whole blocks per wavefront");
+#pragma unroll
+    for (int i = 0; i < kStageLoads; ++i) {
+        const int blk = wave + i * kWaves;
+        load_to_lds_16B(a.packed + blk * kBlockBytes + lane * 16, wlds + blk * kBlockBytes);
     }
-    __syncthreads();
-    // fragment (j, s) = channel NT c + j, bytes D/4 q + 16 s .. + 16 of its row
-    v4i wfrag[NT][KS];
-    float sw[NT];
     uint32_t sw_bits[NT / 2];  // the lane's NT consecutive fp16 channel scales
     {
         const uint8_t* swp = a.packed + a.L.scale_off + 2 * NT * c;
@@ -94,6 +115,13 @@ __global__ __launch_bounds__(kHeadProjThreads) void head_project_kernel(const He
             sw_bits[0] = w2.x; sw_bits[1] = w2.y;
         }
     }
+    v4i qa[KS];
+    float st = 1.0f;
+    if (tile < tiles) quantize_tile(v, qa, st);
+    wait_loads_and_barrier<0>();
+    // fragment (j, s) = channel NT c + j, bytes D/4 q + 16 s .. + 16 of its row
+    v4i wfrag[NT][KS];
+    float sw[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const int n = NT * c + j;
@@ -106,29 +134,11 @@ __global__ __launch_bounds__(kHeadProjThreads) void head_project_kernel(const He
         sw[j] = fp16_bits_to_f32((sw_bits[j / 2] >> (16 * (j & 1))) & 0xFFFFu);
     }
 
+    // v is free once its codes exist: the next 16 rows load while these are multiplied and
+    // written, and are quantized at the end of the iteration
     for (; tile < tiles; tile += stride) {
-        uint4 vn[UNITS];
         const bool more = tile + stride < tiles;
-        if (more) load_tile(tile + stride, vn);
-
-        float amax = 0.0f;
-#pragma unroll
-        for (int u = 0; u < UNITS; ++u) amax = fmaxf(amax, absmax8(v[u]));
-        amax = fmaxf(amax, lane_xor<16>(amax));
-        amax = fmaxf(amax, lane_xor<32>(amax));
-        const float st = group_scale(amax, kQmaxHi);
-        const float inv = 1.0f / st;
-
-        v4i qa[KS];
-        float unused = 0.0f;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            uint32_t c0[8], c1[8];
-            quant8<false>(v[2 * s], st, inv, c0, unused);
-            quant8<false>(v[2 * s + 1], st, inv, c1, unused);
-            qa[s] = (v4i){(int)pack_low_bytes(c0[0], c0[1], c0[2], c0[3]), (int)pack_low_bytes(c0[4], c0[5], c0[6], c0[7]),
-                          (int)pack_low_bytes(c1[0], c1[1], c1[2], c1[3]), (int)pack_low_bytes(c1[4], c1[5], c1[6], c1[7])};
-        }
+        if (more) load_tile(tile + stride, v);
 
         v4i acc[NT];
 #pragma unroll
@@ -161,10 +171,7 @@ __global__ __launch_bounds__(kHeadProjThreads) void head_project_kernel(const He
                 }
             }
         }
-        if (more) {
-#pragma unroll
-            for (int u = 0; u < UNITS; ++u) v[u] = vn[u];
-        }
+        if (more) quantize_tile(v, qa, st);
     }
 }
 
