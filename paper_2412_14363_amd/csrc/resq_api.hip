@@ -254,7 +254,7 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
 
     // few tokens: stream the weights once (HBM-bound kernel), activations in LDS
     const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
-    if (M <= kDecodeMaxM && M * lds_row <= 150 * 1024) {
+    if (M <= kDecodeMaxM && M * lds_row <= 140 * 1024) {
         DecodeArgs d;
         d.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
         d.q_lo = q_lo;
@@ -275,7 +275,32 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         d.swiglu = swiglu ? 1 : 0;
         d.groups = (int)((N + 15) / 16);
         d.lds_row = (int)lds_row;
-        const int lds_bytes = (int)(M * lds_row);
+        int lds_bytes = (int)(M * lds_row);
+        // Few output channels (at most half of the chip's 2048 wavefronts would have a
+        // group): cut each group's reduction axis into SK runs, one per wavefront, until
+        // more than half have one or a run would get shorter than 4 blocks.
+        const int blocks = (int)(L.hi_blocks + L.lo_blocks);
+        int sk = 1;
+        while (sk < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 4) sk *= 2;
+        if (sk > 1) {
+            lds_bytes = ((lds_bytes + 15) & ~15) + (kDecodeThreads / 64) * 2 * 64 * 16;
+            const int sets = (d.groups * sk + 7) / 8;
+            const dim3 grid((unsigned)(sets < 256 ? sets : 256)), blk(kDecodeThreads);
+#define RESQ_LAUNCH_SPLITK(SK)                                                                     \
+    do {                                                                                           \
+        auto kernel = dbg ? gemm_decode_splitk_kernel<true, SK> : gemm_decode_splitk_kernel<false, SK>; \
+        if (lds_bytes > 64 * 1024 &&                                                               \
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),                             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) \
+            return RESQ_ERR_HIP;                                                                   \
+        launch(kernel, grid, blk, lds_bytes, st, d);                                               \
+    } while (0)
+            if (sk == 2) RESQ_LAUNCH_SPLITK(2);
+            else if (sk == 4) RESQ_LAUNCH_SPLITK(4);
+            else RESQ_LAUNCH_SPLITK(8);
+#undef RESQ_LAUNCH_SPLITK
+            return launch_status();
+        }
         auto kernel = dbg ? gemm_decode_kernel<true> : gemm_decode_kernel<false>;
         if (lds_bytes > 64 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),

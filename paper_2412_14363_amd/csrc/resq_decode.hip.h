@@ -206,6 +206,134 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
 }
 
 // ---------------------------------------------------------------------------
+// The same for layers with few output channels (o_proj, down_proj: N / 16 groups
+// are fewer than the wavefronts the chip needs in flight to keep HBM busy): the
+// reduction axis of a group is cut into SK contiguous runs of blocks, one per
+// wavefront of a workgroup, whose integer sums meet in LDS; the wavefront of the
+// first run adds them and runs the epilogue.  A workgroup owns 8 / SK groups at
+// a time ("a set"); sets are dealt round-robin over workgroups.  Exact: integer
+// addition in any order.
+// ---------------------------------------------------------------------------
+template <bool DBG, int SK>
+__global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(const DecodeArgs a) {
+    static_assert(SK == 2 || SK == 4 || SK == 8, "runs per group");
+    constexpr int kWaves = kDecodeThreads / 64;
+    constexpr int G = kWaves / SK;  // groups per set
+    extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // [M][lds_row], then the partial sums
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int gsel = wave / SK, part = wave % SK;
+    const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
+    const int b_begin = (int)((int64_t)blocks * part / SK), b_end = (int)((int64_t)blocks * (part + 1) / SK);
+    const int hi_units = (int)(a.L.kh_pad / 16), row_units = hi_units + (int)(a.L.kl_pad / 32);
+    const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
+    v4i* partial = reinterpret_cast<v4i*>(act + ((a.M * a.lds_row + 15) & ~15));  // [kWaves][2][64]
+    const int sets = (a.groups + G - 1) / G;
+
+    // start the weight stream of this wave's first run before anything else
+    int set = blockIdx.x;
+    uint4 ring[kDecodeDepth];
+    {
+        const int group = set * G + gsel;
+        const bool live = set < sets && group < a.groups;
+        const uint4* wp = reinterpret_cast<const uint4*>(
+            a.packed + (int64_t)(live ? group : 0) * a.L.group_bytes + lane_off);
+#pragma unroll
+        for (int i = 0; i < kDecodeDepth; ++i)
+            if (live && b_begin + i < b_end) ring[i] = wp[(b_begin + i) * (kBlockBytes / 16)];
+    }
+
+    // activation codes of every token -> LDS, as in the kernel above
+    constexpr int FILL = 12;
+    const int units = a.M * row_units;
+    for (int u0 = t; u0 < units; u0 += FILL * kDecodeThreads) {
+        uint4 v[FILL];
+#pragma unroll
+        for (int q = 0; q < FILL; ++q) {
+            const int u = u0 + q * kDecodeThreads;
+            v[q] = make_uint4(0u, 0u, 0u, 0u);
+            if (u < units) {
+                const int m = u / row_units, c = u - m * row_units;
+                v[q] = c < hi_units
+                           ? *reinterpret_cast<const uint4*>(a.q_hi + m * a.ld_hi + c * 16)
+                           : *reinterpret_cast<const uint4*>(a.q_lo + m * a.ld_lo + (c - hi_units) * 16);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < FILL; ++q) {
+            const int u = u0 + q * kDecodeThreads;
+            if (u < units) {
+                const int m = u / row_units, c = u - m * row_units;
+                *reinterpret_cast<uint4*>(act + m * a.lds_row + c * 16) = v[q];
+            }
+        }
+    }
+    __syncthreads();
+
+    const int tok = lane & 15;
+    const bool tok_live = tok < a.M;
+    const uint8_t* arow = act + (tok_live ? tok : 0) * a.lds_row + (lane >> 4) * 16;
+    const v4i zero = {0, 0, 0, 0};
+    for (; set < sets; set += gridDim.x) {  // the same trip count for every wavefront of a workgroup
+        const int group = set * G + gsel;
+        const bool live = group < a.groups;
+        const uint4* wp = reinterpret_cast<const uint4*>(
+            a.packed + (int64_t)(live ? group : 0) * a.L.group_bytes + lane_off);
+        v4i acc_hi = {0, 0, 0, 0}, acc_lo = {0, 0, 0, 0};
+        if (live) {
+            for (int b0 = b_begin; b0 < b_end; b0 += kDecodeDepth) {
+#pragma unroll
+                for (int i = 0; i < kDecodeDepth; ++i) {
+                    const int b = b0 + i;
+                    if (b < b_end) {
+                        const uint4 wq = ring[i];
+                        if (b + kDecodeDepth < b_end) ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
+                        const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
+                        v4i p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
+                        if (!tok_live) p = zero;
+                        if (b < hi_blocks) {
+                            acc_hi = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, p, acc_hi, 0, 0, 0);
+                        } else {
+                            // see resq_gemm.hip.h: one operand of each product carries an offset of 8
+                            acc_lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                w & (int)0xF0F0F0F0, tok_live ? (p & (int)0x0F0F0F0F) : zero, acc_lo, 0, 0, 0);
+                            acc_lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                w & (int)0x0F0F0F0F, p & (int)0xF0F0F0F0, acc_lo, 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+        // the next set's first loads go out before the sums are exchanged
+        {
+            const int nset = set + gridDim.x;
+            const int ngroup = nset * G + gsel;
+            if (nset < sets && ngroup < a.groups) {
+                const uint4* np = reinterpret_cast<const uint4*>(a.packed + (int64_t)ngroup * a.L.group_bytes + lane_off);
+#pragma unroll
+                for (int i = 0; i < kDecodeDepth; ++i)
+                    if (b_begin + i < b_end) ring[i] = np[(b_begin + i) * (kBlockBytes / 16)];
+            }
+        }
+        if (part != 0) {
+            partial[(wave * 2 + 0) * 64 + lane] = acc_hi;
+            partial[(wave * 2 + 1) * 64 + lane] = acc_lo;
+        }
+        __syncthreads();
+        if (part == 0 && live) {
+#pragma unroll
+            for (int k = 1; k < SK; ++k) {
+                acc_hi += partial[((wave + k) * 2 + 0) * 64 + lane];
+                acc_lo += partial[((wave + k) * 2 + 1) * 64 + lane];
+            }
+            // lane l now holds token l % 16, channels 16 group + 4 (l / 16) + {0..3}
+            if (tok_live) stream_epilogue<DBG>(a, tok, (int64_t)group * 16 + (lane >> 4) * 4, acc_hi, acc_lo);
+        }
+        __syncthreads();  // the partial sums are read before the next set overwrites them
+    }
+}
+
+// ---------------------------------------------------------------------------
 // The same for 17 .. 64 tokens (batched generation): still one pass over the
 // packed weights, each 1 KiB block going from HBM into operand registers once
 // and meeting every group of 16 tokens there (TG = 2 or 4 groups, one accumulator
