@@ -335,20 +335,35 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         d.swiglu = swiglu ? 1 : 0;
         d.groups = (int)((N + 15) / 16);
         d.lds_row = 0;
-#define RESQ_LAUNCH_STREAM(TG, THREADS)                                                            \
+        // token groups by M; runs per group as for the decode kernel, at most 8 / TG of
+        // them (LDS holds the chunks of every run) and at least two chunks long
+        const int blocks = (int)(L.hi_blocks + L.lo_blocks);
+        const int tg = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+        int sk = 1;
+        while (sk * tg < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 2 * kChunkBlocks) sk *= 2;
+        const int sets = (d.groups * sk + 7) / 8;
+        const dim3 grid((unsigned)(sets < 256 ? sets : 256)), blk(kDecodeThreads);
+        const int lds_bytes = 2 * sk * tg * kChunkBlocks * kBlockBytes;
+#define RESQ_LAUNCH_STREAM(TG, SK)                                                                 \
     do {                                                                                           \
-        const int sets = (d.groups + THREADS / 64 - 1) / (THREADS / 64);                           \
-        const dim3 grid((unsigned)(sets < 256 ? sets : 256)), blk(THREADS);                        \
-        auto kernel = dbg ? gemm_stream_kernel<true, TG, THREADS> : gemm_stream_kernel<false, TG, THREADS>; \
-        const int lds_bytes = 2 * kChunkBlocks * TG * kBlockBytes;                                 \
+        auto kernel = dbg ? gemm_stream_kernel<true, TG, SK> : gemm_stream_kernel<false, TG, SK>;  \
         if (lds_bytes > 64 * 1024 &&                                                               \
             hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),                             \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) \
             return RESQ_ERR_HIP;                                                                   \
         launch(kernel, grid, blk, lds_bytes, st, d);                                               \
     } while (0)
-        if (M <= 32) RESQ_LAUNCH_STREAM(2, 512);
-        else RESQ_LAUNCH_STREAM(4, 512);
+        switch (tg * 16 + sk) {
+            case 1 * 16 + 1: RESQ_LAUNCH_STREAM(1, 1); break;
+            case 1 * 16 + 2: RESQ_LAUNCH_STREAM(1, 2); break;
+            case 1 * 16 + 4: RESQ_LAUNCH_STREAM(1, 4); break;
+            case 1 * 16 + 8: RESQ_LAUNCH_STREAM(1, 8); break;
+            case 2 * 16 + 1: RESQ_LAUNCH_STREAM(2, 1); break;
+            case 2 * 16 + 2: RESQ_LAUNCH_STREAM(2, 2); break;
+            case 2 * 16 + 4: RESQ_LAUNCH_STREAM(2, 4); break;
+            case 4 * 16 + 1: RESQ_LAUNCH_STREAM(4, 1); break;
+            default: RESQ_LAUNCH_STREAM(4, 2); break;
+        }
 #undef RESQ_LAUNCH_STREAM
         return launch_status();
     }

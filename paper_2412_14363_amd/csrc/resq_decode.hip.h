@@ -334,79 +334,86 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
 }
 
 // ---------------------------------------------------------------------------
-// The same for 17 .. 64 tokens (batched generation): still one pass over the
-// packed weights, each 1 KiB block going from HBM into operand registers once
-// and meeting every group of 16 tokens there (TG = 2 or 4 groups, one accumulator
-// pair each; eight groups do not fit the registers next to the weight ring, and a
-// spill in the loop would wait for the whole ring on the shared load counter).  The activation codes no longer fit LDS whole, so the eight wavefronts
-// of a workgroup walk the reduction axis together in chunks of kChunkBlocks
-// blocks; a chunk of all tokens' codes sits in LDS as the 16-row x 64-byte
-// blocks of the tiled kernel (piece kc of row r at unit 4 r + (kc ^ (r >> 2)),
-// so the 16 lanes that read one piece of 16 rows hit 16 bank groups), and the
-// next chunk is fetched into registers while this one is multiplied, then
-// written to the other buffer: one barrier per chunk.
+// The same for 17 .. 64 tokens (batched generation), and for up to 16 tokens of
+// a reduction axis too long for LDS: still one pass over the packed weights,
+// each 1 KiB block going from HBM into operand registers once and meeting every
+// group of 16 tokens there (TG = 1, 2 or 4 groups, one accumulator pair each;
+// eight groups do not fit the registers next to the weight ring, and a spill in
+// the loop would wait for the whole ring on the shared load counter).  The
+// activation codes do not fit LDS whole, so the wavefronts walk the reduction
+// axis in chunks of kChunkBlocks blocks; a chunk of all tokens' codes sits in
+// LDS as the 16-row x 64-byte blocks of the tiled kernel (piece kc of row r at
+// unit 4 r + (kc ^ (r >> 2)), so the 16 lanes that read one piece of 16 rows
+// hit 16 bank groups), fetched by direct-to-LDS loads one chunk ahead: one
+// barrier per chunk.  As in the kernel above the reduction axis of a group can
+// be cut into SK runs, one per wavefront (SK * TG <= 8: LDS holds the chunks of
+// all runs); a workgroup owns 8 / SK groups at a time.
 // ---------------------------------------------------------------------------
 constexpr int kChunkBlocks = 8;
 static_assert(kChunkBlocks == kDecodeDepth, "a chunk fills the weight ring exactly once");
 constexpr int kStreamMaxM = 64;
 
-template <bool DBG, int TG, int THREADS>
-__global__ __launch_bounds__(THREADS) void gemm_stream_kernel(const DecodeArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) uint8_t act[];  // [2][kChunkBlocks][TG] blocks of 1 KiB
-    constexpr int kChunkBytes = kChunkBlocks * TG * kBlockBytes;
-    constexpr int kWaves = THREADS / 64;
-    constexpr int kUnitsPerThread = kChunkBlocks * TG * 64 / THREADS;  // 16-byte units
+template <bool DBG, int TG, int SK>
+__global__ __launch_bounds__(kDecodeThreads) void gemm_stream_kernel(const DecodeArgs a) {
+    static_assert(TG * 16 <= kStreamMaxM && SK * TG <= 8, "LDS holds two chunks of every run");
+    extern __shared__ __attribute__((aligned(1024))) uint8_t act[];  // [2][SK][kChunkBlocks][TG] blocks
+    constexpr int kWaves = kDecodeThreads / 64;
+    constexpr int G = kWaves / SK;  // groups per set
+    constexpr int kRunBytes = kChunkBlocks * TG * kBlockBytes;  // one run's chunk
+    constexpr int kBufBytes = SK * kRunBytes;
+    constexpr int kFetches = SK * TG;  // direct-to-LDS loads per wavefront and chunk
     const int t = threadIdx.x, lane = t & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);  // wave-uniform, and known to be
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int gsel = wave / SK, part = wave % SK;
     const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
-    const int chunks = (blocks + kChunkBlocks - 1) / kChunkBlocks;
+    // run `part` covers blocks [run_begin(part), run_begin(part + 1)); every run walks the
+    // same number of chunks (the longest run's)
+    auto run_begin = [&](int p) { return (int)((int64_t)blocks * p / SK); };
+    const int b_begin = run_begin(part), b_end = run_begin(part + 1);
+    const int chunks = ((blocks + SK - 1) / SK + kChunkBlocks - 1) / kChunkBlocks;
     const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
     // operand read: lane l supplies token l % 16, piece l / 16 of a block
     const int rr = lane & 15, rk = lane >> 4;
-    const int read_off = (4 * rr + (rk ^ (rr >> 2))) * 16;
+    const int read_off = part * kRunBytes + (4 * rr + (rk ^ (rr >> 2))) * 16;
+    // the partial sums of the runs meet in the chunk buffers once the last chunk is done with
+    v4i* partial = reinterpret_cast<v4i*>(act);  // [kWaves][TG][2][64]
+    static_assert(kWaves * TG * 2 * 64 * 16 <= 2 * kBufBytes, "partial sums fit the chunk buffers");
 
-    // Chunk loader.  A wavefront always fetches the same token group (wave % TG), so a
-    // thread reads one token row throughout: piece t % 4 of row (t / 4) % 16 of that
-    // group, in blocks wave / TG, wave / TG + kWaves / TG, ... of the chunk.
-    static_assert(kWaves % TG == 0, "a wavefront fetches one token group");
-    static_assert(TG * 16 <= kStreamMaxM, "token groups beyond the dispatch limit");
-    constexpr int kBlockStep = kWaves / TG;
-    const int f_kc = t & 3, f_r = (t >> 2) & 15, f_tg = wave % TG, f_b0 = wave / TG;
-    int f_m = f_tg * 16 + f_r;
-    f_m = f_m < a.M ? f_m : a.M - 1;  // rows past M repeat the last token (never stored)
-    const uint8_t* src_hi = a.q_hi + (int64_t)f_m * a.ld_hi + f_kc * 16;
-    const uint8_t* src_lo = a.q_lo + (int64_t)f_m * a.ld_lo + f_kc * 16 - (int64_t)hi_blocks * kRowBytes;
-    const int f_lds = f_tg * kBlockBytes + (4 * f_r + (f_kc ^ (f_r >> 2))) * 16;
-    uint4 stage[kUnitsPerThread];
-    auto fetch_chunk = [&](int c) {
+    // Chunk loader: fetch f = q * kWaves + wave of a chunk step is block i of run p for
+    // token group g, f = (p * kChunkBlocks + i) * TG + g.  Lane l brings row l / 4, piece
+    // (l % 4) ^ (l / 16) of that block, which lands at unit l: the layout read above.
+    const int f_r = lane >> 2, f_kc = (lane & 3) ^ (lane >> 4);
+    auto fetch_chunk = [&](int c, int buf) {
 #pragma unroll
-        for (int q = 0; q < kUnitsPerThread; ++q) {
-            const int b = c * kChunkBlocks + f_b0 + q * kBlockStep;
-            stage[q] = make_uint4(0u, 0u, 0u, 0u);
-            if (b < blocks)
-                stage[q] = *reinterpret_cast<const uint4*>((b < hi_blocks ? src_hi : src_lo) + b * kRowBytes);
+        for (int q = 0; q < kFetches; ++q) {
+            const int f = q * kWaves + wave;
+            const int g = f % TG, i = (f / TG) % kChunkBlocks, p = f / (TG * kChunkBlocks);
+            const int b = run_begin(p) + c * kChunkBlocks + i;
+            if (b < run_begin(p + 1)) {
+                int m = g * 16 + f_r;
+                m = m < a.M ? m : a.M - 1;  // rows past M repeat the last token (never stored)
+                const uint8_t* src = b < hi_blocks
+                                         ? a.q_hi + (int64_t)m * a.ld_hi + (int64_t)b * kRowBytes
+                                         : a.q_lo + (int64_t)m * a.ld_lo + (int64_t)(b - hi_blocks) * kRowBytes;
+                load_to_lds_16B(src + f_kc * 16, act + buf * kBufBytes + f * kBlockBytes);
+            }
         }
-    };
-    auto store_chunk = [&](int buf) {
-#pragma unroll
-        for (int q = 0; q < kUnitsPerThread; ++q)
-            *reinterpret_cast<uint4*>(act + buf * kChunkBytes + (f_b0 + q * kBlockStep) * (TG * kBlockBytes) + f_lds) = stage[q];
+        asm volatile("" ::: "memory");  // later loads stay behind these
     };
 
-    const int sets = (a.groups + kWaves - 1) / kWaves;  // a set = one 16-channel group per wavefront
+    const int sets = (a.groups + G - 1) / G;
     for (int set = blockIdx.x; set < sets; set += gridDim.x) {
-        const int group = set * kWaves + wave;
+        const int group = set * G + gsel;
         const bool live = group < a.groups;
         const uint4* wp = reinterpret_cast<const uint4*>(
             a.packed + (int64_t)(live ? group : 0) * a.L.group_bytes + lane_off);
         uint4 ring[kDecodeDepth];
 #pragma unroll
         for (int i = 0; i < kDecodeDepth; ++i)
-            if (live && i < blocks) ring[i] = wp[i * (kBlockBytes / 16)];
+            if (live && b_begin + i < b_end) ring[i] = wp[(b_begin + i) * (kBlockBytes / 16)];
         __syncthreads();  // every wavefront is done with the LDS buffers of the previous set
-        fetch_chunk(0);
-        store_chunk(0);
-        __syncthreads();
+        fetch_chunk(0, 0);
+        wait_loads_and_barrier<0>();
 
         v4i acc_hi[TG], acc_lo[TG];
 #pragma unroll
@@ -415,13 +422,14 @@ __global__ __launch_bounds__(THREADS) void gemm_stream_kernel(const DecodeArgs a
             acc_lo[g] = (v4i){0, 0, 0, 0};
         }
         for (int c = 0; c < chunks; ++c) {
-            if (c + 1 < chunks) fetch_chunk(c + 1);
-            const uint8_t* cur = act + (c & 1) * kChunkBytes + read_off;
+            // the other buffer was last read in chunk c - 1, before the barrier that ended it
+            if (c + 1 < chunks) fetch_chunk(c + 1, (c + 1) & 1);
+            const uint8_t* cur = act + (c & 1) * kBufBytes + read_off;
+            const int first = b_begin + c * kChunkBlocks, last = first + kChunkBlocks;
             // A block meets the token groups PG at a time; the fragments of the next PG
-            // groups are read while these are multiplied, and no further ahead (a whole
-            // chunk's fragments would not fit the registers).  KIND 0: a full chunk of
-            // high blocks; 1: a full chunk of low blocks; 2: anything else (the chunk
-            // that holds the boundary between the groups, a partial last chunk).
+            // groups are read while these are multiplied.  KIND 0: a full chunk of high
+            // blocks; 1: a full chunk of low blocks; 2: anything else (the chunk that holds
+            // the boundary between the groups, a partial last chunk).
             constexpr int PG = TG < 4 ? TG : 4;         // groups per pass
             constexpr int PASSES = TG / PG;             // passes per block
             auto chunk_body = [&](auto kind) __attribute__((always_inline)) {
@@ -431,12 +439,12 @@ __global__ __launch_bounds__(THREADS) void gemm_stream_kernel(const DecodeArgs a
                 for (int g = 0; g < PG; ++g) p[g] = *reinterpret_cast<const v4i*>(cur + g * kBlockBytes);
 #pragma unroll
                 for (int i = 0; i < kChunkBlocks; ++i) {
-                    const int b = c * kChunkBlocks + i;  // kChunkBlocks == kDecodeDepth: ring slot i
+                    const int b = first + i;  // kChunkBlocks == kDecodeDepth: ring slot i
                     const uint4 wq = ring[i];
-                    if (b + kDecodeDepth < blocks) ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
+                    if (b + kDecodeDepth < b_end) ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
                     const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
-                    const bool hi_block = KIND == 0 || (KIND == 2 && b < hi_blocks);
-                    const bool lo_block = KIND == 1 || (KIND == 2 && b >= hi_blocks && b < blocks);
+                    const bool hi_block = KIND == 0 || (KIND == 2 && b < hi_blocks && b < b_end);
+                    const bool lo_block = KIND == 1 || (KIND == 2 && b >= hi_blocks && b < b_end);
 #pragma unroll
                     for (int h = 0; h < PASSES; ++h) {
                         constexpr int kLast = kChunkBlocks * PASSES - 1;
@@ -471,16 +479,37 @@ __global__ __launch_bounds__(THREADS) void gemm_stream_kernel(const DecodeArgs a
                     }
                 }
             };
-            if (live) {
-                const int first = c * kChunkBlocks, last = first + kChunkBlocks;
-                if (last <= hi_blocks) chunk_body(std::integral_constant<int, 0>{});
-                else if (first >= hi_blocks && last <= blocks) chunk_body(std::integral_constant<int, 1>{});
+            if (live && first < b_end) {
+                if (last <= hi_blocks && last <= b_end) chunk_body(std::integral_constant<int, 0>{});
+                else if (first >= hi_blocks && last <= b_end) chunk_body(std::integral_constant<int, 1>{});
                 else chunk_body(std::integral_constant<int, 2>{});
             }
-            if (c + 1 < chunks) store_chunk((c + 1) & 1);  // that buffer was last read in chunk c - 1
-            __syncthreads();
+            // The next chunk's codes must have landed; the weight loads issued after them
+            // (eight, when the run goes on for two more chunks) may stay in flight.
+            if (live && last + kDecodeDepth <= b_end) wait_loads_and_barrier<kDecodeDepth>();
+            else wait_loads_and_barrier<0>();
         }
-        if (!live) continue;
+        if constexpr (SK > 1) {
+            if (part != 0) {
+#pragma unroll
+                for (int g = 0; g < TG; ++g) {
+                    partial[((wave * TG + g) * 2 + 0) * 64 + lane] = acc_hi[g];
+                    partial[((wave * TG + g) * 2 + 1) * 64 + lane] = acc_lo[g];
+                }
+            }
+            __syncthreads();
+            if (part == 0) {
+#pragma unroll
+                for (int k = 1; k < SK; ++k) {
+#pragma unroll
+                    for (int g = 0; g < TG; ++g) {
+                        acc_hi[g] += partial[(((wave + k) * TG + g) * 2 + 0) * 64 + lane];
+                        acc_lo[g] += partial[(((wave + k) * TG + g) * 2 + 1) * 64 + lane];
+                    }
+                }
+            }
+        }
+        if (!live || part != 0) continue;  // the barriers of the next set are reached all the same
 #pragma unroll
         for (int g = 0; g < TG; ++g) {
             const int tok = g * 16 + (lane & 15);

@@ -203,6 +203,18 @@ def test_layer_batched_decode_shapes(oracle, rq, M, K, N, r):
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
+@pytest.mark.parametrize("M,K,N,r", [
+    (16, 28672, 272, 3584),      # Llama-70B down_proj's K: 16 token rows do not fit LDS; eight runs per group
+    (9, 30000, 100, 3000),       # ragged everything
+    (16, 16384, 8208, 2048),     # two runs per group
+    (16, 16384, 16400, 2048),    # one run per group
+])
+def test_layer_decode_long_rows(oracle, rq, M, K, N, r):
+    # M <= 16 with rows too long for LDS: the chunked weight-streaming kernel with one token group
+    x, w = wl.random_small_case(M * 3 + N, M, K, N, r, outliers="first4")
+    check_layer(oracle, rq, x, w, r)
+
+
 def test_layer_batched_decode_full_size(oracle, rq):
     # the decode workload's layer with 64 tokens in flight; every accumulator and output
     s = wl.decode_shape(64)
