@@ -204,9 +204,10 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
  *   dbg_acc_hi, dbg_acc_lo   int32 [M, N] each, or null: when given, the two
  *                            integer accumulators are written as well
  * Shapes with M <= 64 take weight-streaming kernels bound by HBM bandwidth
- * (the packed weights cross HBM once; up to 16 tokens sit in LDS whole, up to
- * 64 are chunked through it), larger M the tiled matrix-core kernel; the
- * integer accumulators are identical.
+ * (the packed weights cross HBM once; up to 16 tokens sit in LDS whole when
+ * they fit, else and up to 64 tokens they are chunked through it; layers with
+ * few output channels split the reduction axis over wavefronts), larger M the
+ * tiled matrix-core kernel; the integer accumulators are identical.
  * Alignment: q_hi, q_lo 16 bytes; packed 256 bytes; y 2 bytes.
  */
 int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
