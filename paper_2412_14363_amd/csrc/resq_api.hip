@@ -314,7 +314,25 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
 
     // a few tens of tokens: the same single pass over the weights, activation codes
     // chunked through LDS
-    if (M <= kStreamMaxM) {
+    // Up to 256 tokens take the same kernel in slices of 64 tokens (each slice streams
+    // the weights for itself) when the tiled kernel would leave most of the chip idle:
+    // few tiles, each walking the whole reduction axis alone.  Estimated from the
+    // measured costs of both kernels, per round of 256 workgroups: 10 us + 0.5 us per
+    // 1 KiB block of a channel group for a tile, 8 us + 0.4 us per block of a run for
+    // a slice.
+    bool streaming = M <= kStreamMaxM;
+    if (!streaming && M <= 4 * kStreamMaxM) {
+        const int64_t blocks = L.hi_blocks + L.lo_blocks, groups = (N + 15) / 16;
+        int64_t sk = 1;
+        while (sk * 4 < 8 && groups * sk <= 1024 && blocks / (2 * sk) >= 2 * kChunkBlocks) sk *= 2;
+        const int64_t slices = (M + kStreamMaxM - 1) / kStreamMaxM;
+        const int64_t wgs = (groups * sk + 7) / 8 * slices;
+        const int64_t tiles = ((M + kBM - 1) / kBM) * ((N + kBN - 1) / kBN);
+        const double stream_us = (double)((wgs + 255) / 256) * (8.0 + 0.4 * (double)(blocks / sk));
+        const double tiled_us = (double)((tiles + 255) / 256) * (10.0 + 0.5 * (double)blocks);
+        streaming = stream_us < 0.9 * tiled_us;
+    }
+    if (streaming) {
         DecodeArgs d;
         d.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
         d.q_lo = q_lo;
@@ -339,10 +357,11 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         // them (LDS holds the chunks of every run) and at least two chunks long
         const int blocks = (int)(L.hi_blocks + L.lo_blocks);
         const int tg = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+        const int slices = (int)((M + tg * 16 - 1) / (tg * 16));  // of tg * 16 tokens
         int sk = 1;
         while (sk * tg < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 2 * kChunkBlocks) sk *= 2;
         const int sets = (d.groups * sk + 7) / 8;
-        const dim3 grid((unsigned)(sets < 256 ? sets : 256)), blk(kDecodeThreads);
+        const dim3 grid((unsigned)(sets < 256 ? sets : 256), (unsigned)slices), blk(kDecodeThreads);
         const int lds_bytes = 2 * sk * tg * kChunkBlocks * kBlockBytes;
 #define RESQ_LAUNCH_STREAM(TG, SK)                                                                 \
     do {                                                                                           \

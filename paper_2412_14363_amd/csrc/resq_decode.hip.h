@@ -354,8 +354,25 @@ static_assert(kChunkBlocks == kDecodeDepth, "a chunk fills the weight ring exact
 constexpr int kStreamMaxM = 64;
 
 template <bool DBG, int TG, int SK>
-__global__ __launch_bounds__(kDecodeThreads) void gemm_stream_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__(kDecodeThreads) void gemm_stream_kernel(const DecodeArgs a_in) {
     static_assert(TG * 16 <= kStreamMaxM && SK * TG <= 8, "LDS holds two chunks of every run");
+    // blockIdx.y selects a slice of TG * 16 tokens (more tokens than that: every slice
+    // streams the weights for itself, out of the last-level cache after the first)
+    DecodeArgs a = a_in;
+    {
+        const int tok0 = (int)blockIdx.y * (TG * 16);
+        a.M = a_in.M - tok0 < TG * 16 ? a_in.M - tok0 : TG * 16;
+        if (a.q_hi) a.q_hi += (int64_t)tok0 * a.ld_hi;
+        if (a.q_lo) a.q_lo += (int64_t)tok0 * a.ld_lo;
+        if (a.s_hi) a.s_hi += tok0;
+        if (a.s_lo) a.s_lo += tok0;
+        if (a.lo_sum) a.lo_sum += tok0;
+        if (a.c_hi) a.c_hi += tok0;
+        if (a.c_lo) a.c_lo += tok0;
+        a.y += (int64_t)tok0 * a.ldy;
+        if (a.dbg_hi) a.dbg_hi += (int64_t)tok0 * a.L.N;
+        if (a.dbg_lo) a.dbg_lo += (int64_t)tok0 * a.L.N;
+    }
     extern __shared__ __attribute__((aligned(1024))) uint8_t act[];  // [2][SK][kChunkBlocks][TG] blocks
     constexpr int kWaves = kDecodeThreads / 64;
     constexpr int G = kWaves / SK;  // groups per set

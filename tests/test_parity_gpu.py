@@ -170,8 +170,11 @@ def test_layer_tiny_config(oracle, rq):
     (200, 90, 40, 30),                           # everything smaller than one stage
     (1, 512, 256, 64), (4, 512, 256, 64),        # decode-sized M
     (300, 2048, 768, 256),
+    (260, 640, 300, 128), (385, 90, 40, 30), (290, 4096, 512, 512), (258, 256, 256, 0), (258, 256, 256, 256),
 ])
 def test_layer_shapes(oracle, rq, M, K, N, r):
+    # M > 256 always takes the tiled kernel; 64 < M <= 256 takes it or the weight-streaming
+    # kernel in slices of 64 tokens, whichever the dispatch estimates to be faster
     x, w = wl.random_small_case(M * 7 + K, M, K, N, r, act="student_t3")
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
@@ -193,12 +196,13 @@ def test_layer_decode_shapes(oracle, rq, M, K, N, r):
     (33, 1000, 515, 104), (64, 14336, 144, 1792),        # four; K, r off the block size; longest K
     (65, 2048, 400, 256), (100, 4096, 130, 512), (128, 8192, 272, 1024),   # eight
     (128, 3200, 256, 448),                               # high blocks end inside a chunk of eight
+    (200, 8192, 4100, 1024), (256, 1000, 515, 104), (129, 14336, 272, 1792),   # two to four slices
     (90, 256, 256, 0), (128, 256, 64, 256),              # uniform INT4, uniform INT8
     (40, 90, 40, 30),                                    # everything smaller than one chunk
 ])
 def test_layer_batched_decode_shapes(oracle, rq, M, K, N, r):
     # 16 < M <= 64 takes the weight-streaming kernel with the activation codes chunked through LDS;
-    # the larger M here sit on the other side of that dispatch boundary
+    # the larger M here take it in slices of 64 tokens (few tiles) or the tiled kernel
     x, w = wl.random_small_case(M * 13 + K, M, K, N, r, outliers="first4")
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
