@@ -236,6 +236,61 @@ int resq_gemm_mixed_swiglu(const int8_t* q_hi, const uint8_t* q_lo, const float*
                            int64_t N2, int64_t K, int64_t r, void* y, int64_t ldy, void* stream);
 
 /*
+ * Offline construction of the projection basis (Section 4.2), three steps.
+ *
+ * 1. The covariance (Gram) matrix of calibration activations, accumulated over
+ *    calls:  c[i][j] += sum_t x[t][i] x[t][j]   (fp32 accumulation of exact bf16
+ *    products on the fp32 matrix cores; the caller zeroes c before the first
+ *    call).  When the token axis is cut over workgroups their sums meet by
+ *    atomic adds, so the last bits depend on the order of arrival.
+ *      x   bf16 [T, ldx], ldx >= K        (read)    T = 0 does nothing
+ *      c   fp32 [K, ldc], ldc >= K        (read and written)
+ *    Alignment: x 16 bytes, ldx % 8 == 0, K % 8 == 0 (else RESQ_ERR_ALIGN).
+ */
+int resq_gram_accumulate(const void* x, int64_t ldx, int64_t T, int64_t K, float* c, int64_t ldc,
+                         void* stream);
+
+/*
+ * 2. PCA: eigenvalues and eigenvectors of the symmetric matrix c (its symmetric
+ *    part is taken), by cyclic Jacobi rotations in fp64.  eigvals[k] decrease
+ *    with k and column k of p is the unit eigenvector of eigvals[k], so that the
+ *    high-precision subspace P_h of Section 4.2 (largest eigenvalues) is the
+ *    first r columns, as this library's column convention wants it (the paper
+ *    orders them increasingly and keeps the last r).  Signs of the vectors, and
+ *    bases inside a repeated eigenvalue, are whatever the rotations give.
+ *      c        fp32 [K, ldc]                        (read)
+ *      K        even, 2 .. 32768 (else RESQ_ERR_SHAPE)
+ *      sweeps   Jacobi sweeps, 1 .. 64; convergence is quadratic and 10 suffice
+ *               for fp32 data at K = 4096 (the count is fixed so that the call
+ *               never has to wait for the device)
+ *      eigvals  fp32 [K]                             (written)
+ *      p        fp32 [K, ldp], ldp >= K              (written)
+ *      workspace  device memory, 256-byte aligned, resq_sym_eig_workspace_bytes(K)
+ *               bytes (else RESQ_ERR_BUFFER); contents meaningless afterwards
+ */
+size_t resq_sym_eig_workspace_bytes(int64_t K);
+int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p,
+                 int64_t ldp, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * 3. Rows expressed in a basis:  out[i][j] = sum_k a[i][k] u[k][j]  (fp32
+ *    accumulation on the fp32 matrix cores).  This one product serves every
+ *    remaining step: U_h = P_h R_h and U_l = P_l R_l (the definition of U in
+ *    Section 4.2: a = a column block of p, u = a random orthogonal matrix passed
+ *    in by the caller, out = a column block of U), the folding of U into the
+ *    weights W U (Section 4.3; W as [out_features, in_features]) and the
+ *    projection X U of activations.
+ *      a    bf16 or fp32 (a_is_bf16) [rows, lda], lda >= K      (read)
+ *      u    fp32 [K, ldu], ldu >= J                             (read)
+ *      out  bf16 (rounded to nearest even) or fp32 (out_is_bf16) [rows, ldo], ldo >= J
+ *    Alignment: a, u 16 bytes; lda % 8 == 0, ldu % 8 == 0, J % 8 == 0.  rows = 0
+ *    does nothing.
+ */
+int resq_project_rows(const void* a, int a_is_bf16, int64_t lda, int64_t rows, int64_t K,
+                      const float* u, int64_t ldu, int64_t J, void* out, int out_is_bf16,
+                      int64_t ldo, void* stream);
+
+/*
  * The online projection of queries and keys onto the basis of the K/V cache
  * (Section 4.3: after the position embedding each head is multiplied by the
  * d_head x d_head matrix U_C, with 8-bit weights and 8-bit activations), as one

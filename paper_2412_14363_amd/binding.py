@@ -33,6 +33,10 @@ SYMBOLS = {
     "resq_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p]),
     "resq_gemm_mixed_asym": (C.c_int, [_p, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
     "resq_gemm_mixed_swiglu": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p]),
+    "resq_gram_accumulate": (C.c_int, [_p, _i64, _i64, _i64, _p, _i64, _p]),
+    "resq_sym_eig_workspace_bytes": (_sz, [_i64]),
+    "resq_sym_eig": (C.c_int, [_p, _i64, _i64, C.c_int, _p, _p, _i64, _p, _sz, _p]),
+    "resq_project_rows": (C.c_int, [_p, C.c_int, _i64, _i64, _i64, _p, _i64, _i64, _p, C.c_int, _i64, _p]),
     "resq_project_heads": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _i64, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
     "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
@@ -276,6 +280,54 @@ def resq_gemm_mixed_swiglu(act: ActCodes, packed: torch.Tensor, N2: int,
         _dev(y, torch.bfloat16, "y"), y.stride(0), _stream(stream))
     _check(st, "resq_gemm_mixed_swiglu")
     return y
+
+
+def resq_gram_accumulate(x: torch.Tensor, c: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """c (fp32 [K, K], zeros when not given) += x^T x for x bf16 [T, K]."""
+    T, K = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    if c is None:
+        c = torch.zeros((K, K), dtype=torch.float32, device=x.device)
+    st = lib().resq_gram_accumulate(_dev(x, torch.bfloat16, "x"), x.stride(0), T, K,
+                                    _dev(c, torch.float32, "c"), c.stride(0), _stream(stream))
+    _check(st, "resq_gram_accumulate")
+    return c
+
+
+def resq_sym_eig(c: torch.Tensor, sweeps: int = 10, stream=None):
+    """Eigenvalues (decreasing, fp32 [K]) and eigenvectors (columns of fp32 [K, K]) of the symmetric c."""
+    K = c.shape[0]
+    nbytes = lib().resq_sym_eig_workspace_bytes(K)
+    work = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=c.device)
+    lam = torch.empty(K, dtype=torch.float32, device=c.device)
+    p = torch.empty((K, K), dtype=torch.float32, device=c.device)
+    st = lib().resq_sym_eig(_dev(c, torch.float32, "c"), c.stride(0), K, sweeps, lam.data_ptr(), p.data_ptr(),
+                            p.stride(0), work.data_ptr(), nbytes, _stream(stream))
+    _check(st, "resq_sym_eig")
+    return lam, p
+
+
+def resq_project_rows(a: torch.Tensor, u: torch.Tensor, out: Optional[torch.Tensor] = None,
+                      out_dtype=None, stream=None) -> torch.Tensor:
+    """out = a @ u; a bf16 or fp32 [rows, K] (a column block of a wider matrix is fine), u fp32
+    [K, J]; out bf16 or fp32 [rows, J] (a column block of a wider matrix is fine)."""
+    rows, K = a.shape
+    J = u.shape[1]
+    if a.stride(1) != 1 or u.stride(1) != 1 or u.shape[0] != K:
+        raise ValueError("a, u must be row-major with matching inner size")
+    if a.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("a must be bf16 or fp32")
+    if out is None:
+        out = torch.empty((rows, J), dtype=out_dtype or a.dtype, device=a.device)
+    if out.stride(1) != 1 or out.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("out must be row-major bf16 or fp32")
+    st = lib().resq_project_rows(_dev(a, a.dtype, "a"), int(a.dtype == torch.bfloat16), a.stride(0), rows, K,
+                                 _dev(u, torch.float32, "u"), u.stride(0), J,
+                                 _dev(out, out.dtype, "out"), int(out.dtype == torch.bfloat16), out.stride(0),
+                                 _stream(stream))
+    _check(st, "resq_project_rows")
+    return out
 
 
 def resq_project_heads(x: torch.Tensor, packed: torch.Tensor, y: Optional[torch.Tensor] = None,

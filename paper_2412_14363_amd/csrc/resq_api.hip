@@ -6,7 +6,9 @@
 
 #include "resq.h"
 #include "resq_decode.hip.h"
+#include "resq_eig.hip.h"
 #include "resq_gemm.hip.h"
+#include "resq_basis.hip.h"
 #include "resq_hadamard.hip.h"
 #include "resq_headproj.hip.h"
 #include "resq_layout.h"
@@ -512,6 +514,98 @@ int resq_project_heads(const void* x, int64_t ldx, int64_t rows, int64_t d_head,
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (d_head == 128) launch(head_project_kernel<128>, grid, blk, 0, st, a);
     else launch(head_project_kernel<64>, grid, blk, 0, st, a);
+    return launch_status();
+}
+
+int resq_gram_accumulate(const void* x, int64_t ldx, int64_t T, int64_t K, float* c, int64_t ldc,
+                         void* stream) {
+    if (T < 0 || K < 1 || K > kMaxK || ldx < K || ldc < K) return RESQ_ERR_SHAPE;
+    if (T == 0) return RESQ_OK;
+    if (!x || !c) return RESQ_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(c, 4) || ldx % 8 != 0 || K % 8 != 0) return RESQ_ERR_ALIGN;
+    BasisGemmArgs g;
+    g.a = x; g.b = x; g.c = c;
+    g.lda = ldx; g.ldb = ldx; g.ldc = ldc;
+    g.I = K; g.J = K; g.T = T;
+    g.accumulate = 1;
+    // slices of the token axis (their sums meet by atomic adds) until the chip is full
+    const int64_t tiles = ((K + kBasisTile - 1) / kBasisTile) * ((K + kBasisTile - 1) / kBasisTile);
+    int64_t slices = 1;
+    while (tiles * slices < 512 && T / (2 * slices) >= 512) slices *= 2;
+    g.t_per_slice = round_up((T + slices - 1) / slices, kBasisChunk);
+    slices = (T + g.t_per_slice - 1) / g.t_per_slice;
+    const dim3 grid((unsigned)((K + kBasisTile - 1) / kBasisTile), (unsigned)((K + kBasisTile - 1) / kBasisTile),
+                    (unsigned)slices);
+    launch(basis_gemm_kernel<true, true, true, false>, grid, dim3(kBasisThreads), 0,
+           static_cast<hipStream_t>(stream), g);
+    return launch_status();
+}
+
+int resq_project_rows(const void* a, int a_is_bf16, int64_t lda, int64_t rows, int64_t K, const float* u,
+                      int64_t ldu, int64_t J, void* out, int out_is_bf16, int64_t ldo, void* stream) {
+    if (rows < 0 || rows > 0x7FFFFFFF || K < 1 || K > kMaxK || J < 1 || J > kMaxK || lda < K || ldu < J || ldo < J)
+        return RESQ_ERR_SHAPE;
+    if (rows == 0) return RESQ_OK;
+    if (!a || !u || !out) return RESQ_ERR_NULL;
+    if (!aligned(a, 16) || !aligned(u, 16) || !aligned(out, out_is_bf16 ? 2 : 4) || lda % 8 != 0 ||
+        ldu % 8 != 0 || J % 8 != 0)
+        return RESQ_ERR_ALIGN;
+    BasisGemmArgs g;
+    g.a = a; g.b = u; g.c = out;
+    g.lda = lda; g.ldb = ldu; g.ldc = ldo;
+    g.I = rows; g.J = J; g.T = K;
+    g.accumulate = 0;
+    g.t_per_slice = round_up(K, kBasisChunk);
+    const dim3 grid((unsigned)((J + kBasisTile - 1) / kBasisTile), (unsigned)((rows + kBasisTile - 1) / kBasisTile), 1);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a_is_bf16) {
+        if (out_is_bf16) launch(basis_gemm_kernel<false, true, false, true>, grid, dim3(kBasisThreads), 0, st, g);
+        else launch(basis_gemm_kernel<false, true, false, false>, grid, dim3(kBasisThreads), 0, st, g);
+    } else {
+        if (out_is_bf16) launch(basis_gemm_kernel<false, false, false, true>, grid, dim3(kBasisThreads), 0, st, g);
+        else launch(basis_gemm_kernel<false, false, false, false>, grid, dim3(kBasisThreads), 0, st, g);
+    }
+    return launch_status();
+}
+
+size_t resq_sym_eig_workspace_bytes(int64_t K) {
+    if (K < 2 || K % 2 != 0 || K > 32768) return 0;
+    const size_t nn = (size_t)K * (size_t)K * sizeof(double);
+    return 3 * round_up((int64_t)nn, 256) + round_up(K * (int64_t)sizeof(double), 256) +
+           round_up(K * (int64_t)sizeof(int), 256);
+}
+
+int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p, int64_t ldp,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (K < 2 || K % 2 != 0 || K > 32768 || ldc < K || ldp < K || sweeps < 1 || sweeps > 64) return RESQ_ERR_SHAPE;
+    if (!c || !eigvals || !p || !workspace) return RESQ_ERR_NULL;
+    if (!aligned(c, 4) || !aligned(eigvals, 4) || !aligned(p, 4) || !aligned(workspace, 256)) return RESQ_ERR_ALIGN;
+    if (workspace_bytes < resq_sym_eig_workspace_bytes(K)) return RESQ_ERR_BUFFER;
+    const int n = (int)K;
+    const size_t nn = (size_t)round_up((int64_t)((size_t)n * n * sizeof(double)), 256);
+    uint8_t* w = static_cast<uint8_t*>(workspace);
+    EigPlan e;
+    e.n = n;
+    e.a[0] = reinterpret_cast<double*>(w);
+    e.a[1] = reinterpret_cast<double*>(w + nn);
+    e.vt = reinterpret_cast<double*>(w + 2 * nn);
+    e.cs = reinterpret_cast<double*>(w + 3 * nn);
+    e.pq = reinterpret_cast<int*>(w + 3 * nn + round_up(K * (int64_t)sizeof(double), 256));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t elems = (int64_t)n * n;
+    hipLaunchKernelGGL(eig_init_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, c, ldc, e);
+    const dim3 rot_grid((unsigned)((n / 2 + 255) / 256));
+    const dim3 tr_grid((unsigned)((n + kEigCols - 1) / kEigCols), (unsigned)((n / 2 + kEigPairs - 1) / kEigPairs));
+    const dim3 row_grid((unsigned)((n + kEigThreads - 1) / kEigThreads), (unsigned)(n / 2));
+    for (int sweep = 0; sweep < sweeps; ++sweep) {
+        for (int round = 0; round < n - 1; ++round) {
+            hipLaunchKernelGGL(eig_rotations_kernel, rot_grid, dim3(256), 0, st, e, round);
+            hipLaunchKernelGGL(eig_rotate_transpose_kernel, tr_grid, dim3(kEigThreads), 0, st, e, 0);
+            hipLaunchKernelGGL(eig_rotate_transpose_kernel, tr_grid, dim3(kEigThreads), 0, st, e, 1);
+            hipLaunchKernelGGL(eig_rotate_rows_kernel, row_grid, dim3(kEigThreads), 0, st, e);
+        }
+    }
+    launch(eig_finish_kernel, dim3((unsigned)n), dim3(kEigThreads), 0, st, e, eigvals, p, ldp);
     return launch_status();
 }
 

@@ -153,6 +153,26 @@ def test_project_heads_rejects_bad_arguments():
     assert g(P, 128, 0, 128, P, P, 128, None) == 0                           # no rows: nothing to do
 
 
+def test_basis_entry_points_reject_bad_arguments():
+    L = binding.lib()
+    g = L.resq_gram_accumulate
+    assert g(P, 128, 10, 128, P, 120, None) == 2                             # ldc < K
+    assert g(P, 128, 10, 124, P, 128, None) == 3                             # K % 8 != 0
+    assert g(None, 128, 10, 128, P, 128, None) == 1
+    assert g(None, 128, 0, 128, None, 128, None) == 0                        # no tokens: nothing to do
+    e = L.resq_sym_eig
+    assert L.resq_sym_eig_workspace_bytes(7) == 0 and L.resq_sym_eig_workspace_bytes(64) >= 3 * 64 * 64 * 8
+    assert e(P, 63, 63, 8, P, P, 63, P, 1 << 30, None) == 2                  # odd order
+    assert e(P, 64, 64, 0, P, P, 64, P, 1 << 30, None) == 2                  # no sweeps
+    assert e(P, 64, 64, 8, P, P, 64, P, 100, None) == 4                      # workspace too small
+    assert e(P, 64, 64, 8, P, P, 64, None, 1 << 30, None) == 1
+    r = L.resq_project_rows
+    assert r(P, 1, 64, 8, 64, P, 60, 64, P, 1, 64, None) == 2                # ldu < J
+    assert r(P, 1, 64, 8, 64, P, 64, 60, P, 1, 64, None) == 3                # J % 8 != 0
+    assert r(P, 1, 64, 8, 64, None, 64, 64, P, 1, 64, None) == 1
+    assert r(P, 1, 64, 0, 64, P, 64, 64, P, 1, 64, None) == 0
+
+
 def test_binding_fails_loudly_without_device_tensors():
     import torch
     x = torch.zeros(4, 256, dtype=torch.bfloat16)
