@@ -267,6 +267,96 @@ def head_proj_bench(args, s) -> None:
     print(json.dumps(out))
 
 
+def basis_bench(args) -> None:
+    """The offline basis construction for one hidden-size basis (U_A of Llama-3-8B, Section 4.2):
+    Gram matrix of 32768 calibration tokens, PCA by Jacobi sweeps, U = P blockdiag(R), and the
+    folding of U into one 4096 x 4096 weight.  A step is the whole construction; it takes
+    seconds, so at most two steps are timed whatever --steps says."""
+    import torch
+    from paper_2412_14363_amd import binding as rq
+    from paper_2412_14363_amd import workloads as wl
+
+    K, T, r, N, sweeps = 4096, 32768, 512, 4096, 12
+    steps, warmup = max(1, min(args.steps, 2)), min(args.warmup, 1)
+    s = wl.LayerShape("llama3_8b_basis_calibration", M=T, K=K, N=N, r=r, seed=3)
+    x = wl.make_activations(s).cuda()                  # N(0,1) with 20x outlier columns
+    w = wl.make_weights(s).cuda()
+    r_h = wl.random_orthogonal(r, 1).contiguous().cuda()
+    r_l = wl.random_orthogonal(K - r, 2).contiguous().cuda()
+    c = torch.zeros((K, K), dtype=torch.float32, device="cuda")
+    u = torch.empty((K, K), dtype=torch.float32, device="cuda")
+    wr = torch.empty_like(w)
+    out = {}
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(timed=None):
+        marks = [ev() for _ in range(5)]
+        c.zero_()
+        marks[0].record()
+        rq.resq_gram_accumulate(x, c)
+        marks[1].record()
+        lam, p = rq.resq_sym_eig(c, sweeps=sweeps)
+        marks[2].record()
+        rq.resq_project_rows(p[:, :r], r_h, out=u[:, :r])
+        rq.resq_project_rows(p[:, r:], r_l, out=u[:, r:])
+        marks[3].record()
+        rq.resq_project_rows(w, u, out=wr)
+        marks[4].record()
+        out["lam"], out["p"] = lam, p
+        if timed is not None:
+            torch.cuda.synchronize()
+            timed.append([marks[i].elapsed_time(marks[i + 1]) for i in range(4)])
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    parts = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(parts)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+    gram_ms, eig_ms, compose_ms, fold_ms = [sum(p[i] for p in parts) / steps for i in range(4)]
+    # quality of what came out: eigenpair residual and orthogonality, on the device in fp64
+    lam, p = out["lam"].double(), out["p"].double()
+    resid = float(((c.double() @ p) - p * lam).abs().max() / lam[0])
+    orth = float((u.double().T @ u.double() - torch.eye(K, device="cuda", dtype=torch.float64)).abs().max())
+    # Jacobi: per round the matrix is read and written twice and the vectors once, in fp64
+    eig_bytes = sweeps * (K - 1) * 6.0 * K * K * 8
+    gram_flops = 2.0 * T * K * K
+    res = {
+        "metric": "basis construction time (Gram + PCA + compose + fold)", "value": ms_per_step / 1e3,
+        "unit": "s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32/f64",
+        "data": "synthetic",
+        "config": {"workload": f"{s.name}: tokens={T} K={K} r={r} fold N={N} sweeps={sweeps}", "tag": "basis",
+                   "step": "gram_accumulate + sym_eig + 2 x project_rows (U) + project_rows (W U)"},
+        "gram_ms": gram_ms, "eig_ms": eig_ms, "compose_ms": compose_ms, "fold_ms": fold_ms,
+        "gram_tflops": gram_flops / (gram_ms * 1e-3) / 1e12,
+        "fold_tflops": 2.0 * N * K * K / (fold_ms * 1e-3) / 1e12,
+        "eig_residual_over_scale": resid, "u_orthogonality_error": orth,
+        "roofline": {"bound": "hbm", "achieved": eig_bytes / (eig_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": eig_bytes / (eig_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "resq sym_eig (all Jacobi rounds)", "kernel_ms": eig_ms},
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import resq_basis_oracle as bo
+        xs = x[:4096].double().cpu().numpy()
+        t0 = time.perf_counter()
+        cg = bo.gram(xs)
+        t1 = time.perf_counter()
+        bo.pca_basis(c.double().cpu().numpy())
+        t2 = time.perf_counter()
+        est = (t1 - t0) * T / 4096 + (t2 - t1)
+        res["cpu_baseline"] = {"value": est, "unit": "s", "cores": os.cpu_count(), "kind": "oracle",
+                               "sample": f"Gram matrix of 4096 of {T} tokens ({t1 - t0:.1f} s, scaled) + LAPACK eigh of the "
+                                         f"full {K} x {K} matrix ({t2 - t1:.1f} s); fold not timed"}
+    print(json.dumps(res))
+
+
 def mlp_block_bench(args) -> None:
     """The MLP block of Llama-3-8B on 4096 tokens as four kernels: quantize_act,
     gate/up as one layer with the gated activation in its epilogue (N2 = 28672), the
@@ -397,6 +487,9 @@ def main() -> None:
 
     if args.workload == "mlp_block":
         mlp_block_bench(args)
+        return
+    if args.workload == "basis":
+        basis_bench(args)
         return
     s = workload_shape(args.workload)
     if args.workload == "uc_proj":

@@ -260,9 +260,11 @@ int resq_gram_accumulate(const void* x, int64_t ldx, int64_t T, int64_t K, float
  *    bases inside a repeated eigenvalue, are whatever the rotations give.
  *      c        fp32 [K, ldc]                        (read)
  *      K        even, 2 .. 32768 (else RESQ_ERR_SHAPE)
- *      sweeps   Jacobi sweeps, 1 .. 64; convergence is quadratic and 10 suffice
- *               for fp32 data at K = 4096 (the count is fixed so that the call
- *               never has to wait for the device)
+ *      sweeps   Jacobi sweeps, 1 .. 64.  Convergence is quadratic at the end: 12
+ *               sweeps bring every off-diagonal element of a K = 4096 covariance
+ *               below 2^-40 of its diagonal neighbours.  The count is fixed so
+ *               that the call never has to wait for the device; sweeps after one
+ *               that found nothing to rotate cost only their empty launches
  *      eigvals  fp32 [K]                             (written)
  *      p        fp32 [K, ldp], ldp >= K              (written)
  *      workspace  device memory, 256-byte aligned, resq_sym_eig_workspace_bytes(K)

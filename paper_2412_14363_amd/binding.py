@@ -295,7 +295,7 @@ def resq_gram_accumulate(x: torch.Tensor, c: Optional[torch.Tensor] = None, stre
     return c
 
 
-def resq_sym_eig(c: torch.Tensor, sweeps: int = 10, stream=None):
+def resq_sym_eig(c: torch.Tensor, sweeps: int = 12, stream=None):
     """Eigenvalues (decreasing, fp32 [K]) and eigenvectors (columns of fp32 [K, K]) of the symmetric c."""
     K = c.shape[0]
     nbytes = lib().resq_sym_eig_workspace_bytes(K)

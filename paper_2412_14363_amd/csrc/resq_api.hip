@@ -572,12 +572,12 @@ size_t resq_sym_eig_workspace_bytes(int64_t K) {
     if (K < 2 || K % 2 != 0 || K > 32768) return 0;
     const size_t nn = (size_t)K * (size_t)K * sizeof(double);
     return 3 * round_up((int64_t)nn, 256) + round_up(K * (int64_t)sizeof(double), 256) +
-           round_up(K * (int64_t)sizeof(int), 256);
+           round_up(K * (int64_t)sizeof(int), 256) + round_up(kEigMaxSweeps * (int64_t)sizeof(int), 256);
 }
 
 int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p, int64_t ldp,
                  void* workspace, size_t workspace_bytes, void* stream) {
-    if (K < 2 || K % 2 != 0 || K > 32768 || ldc < K || ldp < K || sweeps < 1 || sweeps > 64) return RESQ_ERR_SHAPE;
+    if (K < 2 || K % 2 != 0 || K > 32768 || ldc < K || ldp < K || sweeps < 1 || sweeps > kEigMaxSweeps) return RESQ_ERR_SHAPE;
     if (!c || !eigvals || !p || !workspace) return RESQ_ERR_NULL;
     if (!aligned(c, 4) || !aligned(eigvals, 4) || !aligned(p, 4) || !aligned(workspace, 256)) return RESQ_ERR_ALIGN;
     if (workspace_bytes < resq_sym_eig_workspace_bytes(K)) return RESQ_ERR_BUFFER;
@@ -591,18 +591,20 @@ int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigv
     e.vt = reinterpret_cast<double*>(w + 2 * nn);
     e.cs = reinterpret_cast<double*>(w + 3 * nn);
     e.pq = reinterpret_cast<int*>(w + 3 * nn + round_up(K * (int64_t)sizeof(double), 256));
+    e.nrot = reinterpret_cast<int*>(w + 3 * nn + round_up(K * (int64_t)sizeof(double), 256) +
+                                    round_up(K * (int64_t)sizeof(int), 256));
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t elems = (int64_t)n * n;
-    hipLaunchKernelGGL(eig_init_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, c, ldc, e);
+    hipLaunchKernelGGL(eig_init_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, c, ldc, e);  // >= 256 threads
     const dim3 rot_grid((unsigned)((n / 2 + 255) / 256));
     const dim3 tr_grid((unsigned)((n + kEigCols - 1) / kEigCols), (unsigned)((n / 2 + kEigPairs - 1) / kEigPairs));
     const dim3 row_grid((unsigned)((n + kEigThreads - 1) / kEigThreads), (unsigned)(n / 2));
     for (int sweep = 0; sweep < sweeps; ++sweep) {
         for (int round = 0; round < n - 1; ++round) {
-            hipLaunchKernelGGL(eig_rotations_kernel, rot_grid, dim3(256), 0, st, e, round);
-            hipLaunchKernelGGL(eig_rotate_transpose_kernel, tr_grid, dim3(kEigThreads), 0, st, e, 0);
-            hipLaunchKernelGGL(eig_rotate_transpose_kernel, tr_grid, dim3(kEigThreads), 0, st, e, 1);
-            hipLaunchKernelGGL(eig_rotate_rows_kernel, row_grid, dim3(kEigThreads), 0, st, e);
+            hipLaunchKernelGGL(eig_rotations_kernel, rot_grid, dim3(256), 0, st, e, sweep, round);
+            hipLaunchKernelGGL(eig_rotate_transpose_kernel, tr_grid, dim3(kEigThreads), 0, st, e, sweep, 0);
+            hipLaunchKernelGGL(eig_rotate_transpose_kernel, tr_grid, dim3(kEigThreads), 0, st, e, sweep, 1);
+            hipLaunchKernelGGL(eig_rotate_rows_kernel, row_grid, dim3(kEigThreads), 0, st, e, sweep);
         }
     }
     launch(eig_finish_kernel, dim3((unsigned)n), dim3(kEigThreads), 0, st, e, eigvals, p, ldp);

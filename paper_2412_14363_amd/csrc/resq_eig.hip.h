@@ -11,8 +11,10 @@
 // other buffer) runs twice per round; the eigenvectors are kept transposed
 // (Vt <- J^T Vt, in place).  In the tournament ordering 16 consecutive pairs have
 // 16 consecutive p and 16 consecutive q (mod n - 1), so the transposed writes are
-// contiguous runs as well.  Offline step, bound by HBM: 5 n^2 fp64 words move per
-// round.
+// contiguous runs as well.  Offline step, bound by HBM: 6 n^2 fp64 words move per
+// round (the matrix read and written twice, the vectors once).  Rotations of
+// elements already negligible are skipped, and once a whole sweep has skipped
+// all of them the remaining kernels return at once.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -29,7 +31,19 @@ struct EigPlan {
     double* vt;       // eigenvectors as rows, [n][n]
     int* pq;          // [n / 2][2]: the round's pairs, p < q
     double* cs;       // [n / 2][2]: cosine and sine of each pair's rotation
+    int* nrot;        // [kEigMaxSweeps]: rotations that each sweep still had to make
 };
+
+constexpr int kEigMaxSweeps = 64;
+// an off-diagonal element below this fraction of sqrt(a_pp a_qq) is left alone: fp32
+// outputs cannot tell, and a sweep that finds nothing larger ends the iteration
+constexpr double kEigSkip = 1.0 / (1ull << 40);
+
+// a sweep after one that rotated nothing has nothing to do (the host enqueues a fixed
+// number of sweeps, so that the call never waits for the device)
+__device__ __forceinline__ bool eig_converged(const EigPlan& e, int sweep) {
+    return sweep > 0 && e.nrot[sweep - 1] == 0;
+}
 
 // pair k of round s: (n - 1, s) for k = 0, else ((s + k) mod (n - 1), (s - k) mod (n - 1))
 __device__ __forceinline__ void eig_pair(int n, int s, int k, int& p, int& q) {
@@ -43,6 +57,7 @@ __device__ __forceinline__ void eig_pair(int n, int s, int k, int& p, int& q) {
 __global__ void eig_init_kernel(const float* __restrict__ c, int64_t ldc, EigPlan e) {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t nn = (int64_t)e.n * e.n;
+    if (idx < kEigMaxSweeps) e.nrot[idx] = 0;   // the grid has at least that many threads
     if (idx >= nn) return;
     const int i = (int)(idx / e.n), j = (int)(idx % e.n);
     // the symmetric part, so that rounding differences between c[i][j] and c[j][i] do not matter
@@ -51,15 +66,16 @@ __global__ void eig_init_kernel(const float* __restrict__ c, int64_t ldc, EigPla
 }
 
 // rotation that annihilates a[p][q] (the smaller of the two angles)
-__global__ void eig_rotations_kernel(EigPlan e, int round) {
+__global__ void eig_rotations_kernel(EigPlan e, int sweep, int round) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= e.n / 2) return;
+    if (k >= e.n / 2 || eig_converged(e, sweep)) return;
     int p, q;
     eig_pair(e.n, round, k, p, q);
     const double* a = e.a[0];
     const double app = a[(int64_t)p * e.n + p], aqq = a[(int64_t)q * e.n + q], apq = a[(int64_t)p * e.n + q];
     double c = 1.0, s = 0.0;
-    if (apq != 0.0) {
+    if (fabs(apq) > kEigSkip * sqrt(fabs(app * aqq))) {
+        atomicAdd(&e.nrot[sweep], 1);
         const double tau = (aqq - app) / (2.0 * apq);
         const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
         c = 1.0 / sqrt(1.0 + t * t);
@@ -72,8 +88,9 @@ __global__ void eig_rotations_kernel(EigPlan e, int round) {
 }
 
 // dst = (J^T src)^T: row p' = c row p - s row q, row q' = s row p + c row q, written as columns
-__global__ __launch_bounds__(kEigThreads) void eig_rotate_transpose_kernel(EigPlan e, int from) {
+__global__ __launch_bounds__(kEigThreads) void eig_rotate_transpose_kernel(EigPlan e, int sweep, int from) {
     __shared__ double tile[kEigCols][2 * kEigPairs + 1];
+    if (eig_converged(e, sweep)) return;
     const double* __restrict__ src = e.a[from];
     double* __restrict__ dst = e.a[from ^ 1];
     const int n = e.n;
@@ -115,7 +132,8 @@ __global__ __launch_bounds__(kEigThreads) void eig_rotate_transpose_kernel(EigPl
 }
 
 // Vt <- J^T Vt, in place
-__global__ __launch_bounds__(kEigThreads) void eig_rotate_rows_kernel(EigPlan e) {
+__global__ __launch_bounds__(kEigThreads) void eig_rotate_rows_kernel(EigPlan e, int sweep) {
+    if (eig_converged(e, sweep)) return;
     const int k = blockIdx.y;
     const int j = blockIdx.x * kEigThreads + threadIdx.x;
     if (j >= e.n) return;
