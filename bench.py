@@ -323,8 +323,8 @@ def basis_bench(args) -> None:
     lam, p = out["lam"].double(), out["p"].double()
     resid = float(((c.double() @ p) - p * lam).abs().max() / lam[0])
     orth = float((u.double().T @ u.double() - torch.eye(K, device="cuda", dtype=torch.float64)).abs().max())
-    # Jacobi: per round the matrix is read and written twice and the vectors once, in fp64
-    eig_bytes = sweeps * (K - 1) * 6.0 * K * K * 8
+    # Jacobi: per round the matrix and the vectors are read and written once, in fp64
+    eig_bytes = sweeps * (K - 1) * 4.0 * K * K * 8
     gram_flops = 2.0 * T * K * K
     res = {
         "metric": "basis construction time (Gram + PCA + compose + fold)", "value": ms_per_step / 1e3,

@@ -259,7 +259,7 @@ int resq_gram_accumulate(const void* x, int64_t ldx, int64_t T, int64_t K, float
  *    orders them increasingly and keeps the last r).  Signs of the vectors, and
  *    bases inside a repeated eigenvalue, are whatever the rotations give.
  *      c        fp32 [K, ldc]                        (read)
- *      K        even, 2 .. 32768 (else RESQ_ERR_SHAPE)
+ *      K        even, 2 .. 8192 (else RESQ_ERR_SHAPE; two fp64 rows sit in LDS)
  *      sweeps   Jacobi sweeps, 1 .. 64.  Convergence is quadratic at the end: 12
  *               sweeps bring every off-diagonal element of a K = 4096 covariance
  *               below 2^-40 of its diagonal neighbours.  The count is fixed so

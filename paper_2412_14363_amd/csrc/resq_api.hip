@@ -569,15 +569,16 @@ int resq_project_rows(const void* a, int a_is_bf16, int64_t lda, int64_t rows, i
 }
 
 size_t resq_sym_eig_workspace_bytes(int64_t K) {
-    if (K < 2 || K % 2 != 0 || K > 32768) return 0;
+    if (K < 2 || K % 2 != 0 || K > kEigMaxOrder) return 0;
     const size_t nn = (size_t)K * (size_t)K * sizeof(double);
-    return 3 * round_up((int64_t)nn, 256) + round_up(K * (int64_t)sizeof(double), 256) +
+    return 2 * round_up((int64_t)nn, 256) + round_up(K * (int64_t)sizeof(double), 256) +
            round_up(K * (int64_t)sizeof(int), 256) + round_up(kEigMaxSweeps * (int64_t)sizeof(int), 256);
 }
 
 int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p, int64_t ldp,
                  void* workspace, size_t workspace_bytes, void* stream) {
-    if (K < 2 || K % 2 != 0 || K > 32768 || ldc < K || ldp < K || sweeps < 1 || sweeps > kEigMaxSweeps) return RESQ_ERR_SHAPE;
+    if (K < 2 || K % 2 != 0 || K > kEigMaxOrder || ldc < K || ldp < K || sweeps < 1 || sweeps > kEigMaxSweeps)
+        return RESQ_ERR_SHAPE;
     if (!c || !eigvals || !p || !workspace) return RESQ_ERR_NULL;
     if (!aligned(c, 4) || !aligned(eigvals, 4) || !aligned(p, 4) || !aligned(workspace, 256)) return RESQ_ERR_ALIGN;
     if (workspace_bytes < resq_sym_eig_workspace_bytes(K)) return RESQ_ERR_BUFFER;
@@ -586,25 +587,25 @@ int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigv
     uint8_t* w = static_cast<uint8_t*>(workspace);
     EigPlan e;
     e.n = n;
-    e.a[0] = reinterpret_cast<double*>(w);
-    e.a[1] = reinterpret_cast<double*>(w + nn);
-    e.vt = reinterpret_cast<double*>(w + 2 * nn);
-    e.cs = reinterpret_cast<double*>(w + 3 * nn);
-    e.pq = reinterpret_cast<int*>(w + 3 * nn + round_up(K * (int64_t)sizeof(double), 256));
-    e.nrot = reinterpret_cast<int*>(w + 3 * nn + round_up(K * (int64_t)sizeof(double), 256) +
+    e.a = reinterpret_cast<double*>(w);
+    e.vt = reinterpret_cast<double*>(w + nn);
+    e.cs = reinterpret_cast<double*>(w + 2 * nn);
+    e.pq = reinterpret_cast<int*>(w + 2 * nn + round_up(K * (int64_t)sizeof(double), 256));
+    e.nrot = reinterpret_cast<int*>(w + 2 * nn + round_up(K * (int64_t)sizeof(double), 256) +
                                     round_up(K * (int64_t)sizeof(int), 256));
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const int lds_bytes = 2 * n * (int)sizeof(double);
+    if (lds_bytes > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(eig_round_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+        return RESQ_ERR_HIP;
     const int64_t elems = (int64_t)n * n;
     hipLaunchKernelGGL(eig_init_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, c, ldc, e);  // >= 256 threads
     const dim3 rot_grid((unsigned)((n / 2 + 255) / 256));
-    const dim3 tr_grid((unsigned)((n + kEigCols - 1) / kEigCols), (unsigned)((n / 2 + kEigPairs - 1) / kEigPairs));
-    const dim3 row_grid((unsigned)((n + kEigThreads - 1) / kEigThreads), (unsigned)(n / 2));
     for (int sweep = 0; sweep < sweeps; ++sweep) {
         for (int round = 0; round < n - 1; ++round) {
             hipLaunchKernelGGL(eig_rotations_kernel, rot_grid, dim3(256), 0, st, e, sweep, round);
-            hipLaunchKernelGGL(eig_rotate_transpose_kernel, tr_grid, dim3(kEigThreads), 0, st, e, sweep, 0);
-            hipLaunchKernelGGL(eig_rotate_transpose_kernel, tr_grid, dim3(kEigThreads), 0, st, e, sweep, 1);
-            hipLaunchKernelGGL(eig_rotate_rows_kernel, row_grid, dim3(kEigThreads), 0, st, e, sweep);
+            hipLaunchKernelGGL(eig_round_kernel, dim3((unsigned)(n / 2)), dim3(kEigThreads), lds_bytes, st, e, sweep);
         }
     }
     launch(eig_finish_kernel, dim3((unsigned)n), dim3(kEigThreads), 0, st, e, eigvals, p, ldp);

@@ -4,17 +4,17 @@
 // fp64 with the round-robin ("tournament") ordering, n / 2 disjoint rotations
 // per round, n - 1 rounds per sweep.
 //
-// A round applies J = product of its plane rotations as A <- J^T A J, V <- V J.
-// Everything is done as ROW operations on contiguous rows: with A symmetric,
-//   A2 = (J^T A)^T = A J      and      A3 = (J^T A2)^T = J^T A J,
-// so the same kernel (rotate pairs of rows, write the result transposed into the
-// other buffer) runs twice per round; the eigenvectors are kept transposed
-// (Vt <- J^T Vt, in place).  In the tournament ordering 16 consecutive pairs have
-// 16 consecutive p and 16 consecutive q (mod n - 1), so the transposed writes are
-// contiguous runs as well.  Offline step, bound by HBM: 6 n^2 fp64 words move per
-// round (the matrix read and written twice, the vectors once).  Rotations of
-// elements already negligible are skipped, and once a whole sweep has skipped
-// all of them the remaining kernels return at once.
+// A round applies J = product of its plane rotations as A <- J^T A J, V <- V J,
+// in one pass over the matrix: the workgroup of pair (p, q) owns rows p and q.
+// J^T A mixes exactly those two rows, element by element; (J^T A) J then mixes,
+// inside each row, the elements of every pair of the round, so the two rotated
+// rows sit in LDS (16 n bytes) while all n / 2 column rotations are applied to
+// them, and go back in place.  The eigenvectors are kept transposed, so that
+// their update Vt <- J^T Vt is the same two-row operation.  Every access to
+// memory is a contiguous row.  Offline step, bound by HBM: 4 n^2 fp64 words move
+// per round (matrix and vectors, read and written once).  Rotations of elements
+// already negligible are skipped, and once a whole sweep has skipped all of them
+// the remaining kernels return at once.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -22,12 +22,11 @@
 namespace resq {
 
 constexpr int kEigThreads = 256;
-constexpr int kEigPairs = 16;   // pairs per workgroup of the transposing kernel
-constexpr int kEigCols = 64;    // columns per workgroup of the transposing kernel
+constexpr int kEigMaxOrder = 8192;  // two fp64 rows in LDS: 128 KiB
 
 struct EigPlan {
     int n;            // matrix order, even
-    double* a[2];     // ping-pong copies of the matrix, [n][n]
+    double* a;        // the matrix, [n][n], symmetric between rounds
     double* vt;       // eigenvectors as rows, [n][n]
     int* pq;          // [n / 2][2]: the round's pairs, p < q
     double* cs;       // [n / 2][2]: cosine and sine of each pair's rotation
@@ -61,7 +60,7 @@ __global__ void eig_init_kernel(const float* __restrict__ c, int64_t ldc, EigPla
     if (idx >= nn) return;
     const int i = (int)(idx / e.n), j = (int)(idx % e.n);
     // the symmetric part, so that rounding differences between c[i][j] and c[j][i] do not matter
-    e.a[0][idx] = 0.5 * ((double)c[(int64_t)i * ldc + j] + (double)c[(int64_t)j * ldc + i]);
+    e.a[idx] = 0.5 * ((double)c[(int64_t)i * ldc + j] + (double)c[(int64_t)j * ldc + i]);
     e.vt[idx] = i == j ? 1.0 : 0.0;
 }
 
@@ -71,7 +70,7 @@ __global__ void eig_rotations_kernel(EigPlan e, int sweep, int round) {
     if (k >= e.n / 2 || eig_converged(e, sweep)) return;
     int p, q;
     eig_pair(e.n, round, k, p, q);
-    const double* a = e.a[0];
+    const double* a = e.a;
     const double app = a[(int64_t)p * e.n + p], aqq = a[(int64_t)q * e.n + q], apq = a[(int64_t)p * e.n + q];
     double c = 1.0, s = 0.0;
     if (fabs(apq) > kEigSkip * sqrt(fabs(app * aqq))) {
@@ -87,63 +86,47 @@ __global__ void eig_rotations_kernel(EigPlan e, int sweep, int round) {
     e.cs[2 * k + 1] = s;
 }
 
-// dst = (J^T src)^T: row p' = c row p - s row q, row q' = s row p + c row q, written as columns
-__global__ __launch_bounds__(kEigThreads) void eig_rotate_transpose_kernel(EigPlan e, int sweep, int from) {
-    __shared__ double tile[kEigCols][2 * kEigPairs + 1];
+// one round for pair blockIdx.x: rows p, q of A <- J^T A J, rows p, q of Vt <- J^T Vt
+__global__ __launch_bounds__(kEigThreads) void eig_round_kernel(EigPlan e, int sweep) {
+    extern __shared__ __attribute__((aligned(16))) double rows[];  // [2][n]
     if (eig_converged(e, sweep)) return;
-    const double* __restrict__ src = e.a[from];
-    double* __restrict__ dst = e.a[from ^ 1];
-    const int n = e.n;
-    const int t = threadIdx.x;
-    const int k0 = blockIdx.y * kEigPairs, j0 = blockIdx.x * kEigCols;
+    const int n = e.n, t = threadIdx.x, k = blockIdx.x;
+    const int p = e.pq[2 * k], q = e.pq[2 * k + 1];
+    const double c = e.cs[2 * k], s = e.cs[2 * k + 1];
+    double* ap = e.a + (int64_t)p * n;
+    double* aq = e.a + (int64_t)q * n;
+    double* rp = rows;
+    double* rq = rows + n;
+    for (int j = t; j < n; j += kEigThreads) {
+        const double x = ap[j], y = aq[j];
+        rp[j] = c * x - s * y;
+        rq[j] = s * x + c * y;
+    }
     {
-        const int kl = t >> 4, cg = (t & 15) * 4;   // pair of the workgroup, first of 4 columns
-        const int k = k0 + kl;
-        if (k < n / 2) {
-            const int p = e.pq[2 * k], q = e.pq[2 * k + 1];
-            const double c = e.cs[2 * k], s = e.cs[2 * k + 1];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int j = j0 + cg + u;
-                if (j < n) {
-                    const double ap = src[(int64_t)p * n + j], aq = src[(int64_t)q * n + j];
-                    tile[cg + u][2 * kl] = c * ap - s * aq;
-                    tile[cg + u][2 * kl + 1] = s * ap + c * aq;
-                }
-            }
+        double* vp = e.vt + (int64_t)p * n;
+        double* vq = e.vt + (int64_t)q * n;
+        for (int j = t; j < n; j += kEigThreads) {
+            const double x = vp[j], y = vq[j];
+            vp[j] = c * x - s * y;
+            vq[j] = s * x + c * y;
         }
     }
     __syncthreads();
-    {
-        // thread -> column j0 + t / 4, pairs (t % 4) * 4 .. + 4: consecutive threads write
-        // consecutive p (and consecutive q) of one destination row
-        const int col = t >> 2, j = j0 + col;
-        if (j < n) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int kl = (t & 3) * 4 + u, k = k0 + kl;
-                if (k < n / 2) {
-                    dst[(int64_t)j * n + e.pq[2 * k]] = tile[col][2 * kl];
-                    dst[(int64_t)j * n + e.pq[2 * k + 1]] = tile[col][2 * kl + 1];
-                }
-            }
-        }
+    // the column rotations of every pair of the round, on both rows (the pairs are disjoint)
+    for (int kk = t; kk < n / 2; kk += kEigThreads) {
+        const int p2 = e.pq[2 * kk], q2 = e.pq[2 * kk + 1];
+        const double c2 = e.cs[2 * kk], s2 = e.cs[2 * kk + 1];
+        const double x0 = rp[p2], y0 = rp[q2], x1 = rq[p2], y1 = rq[q2];
+        rp[p2] = c2 * x0 - s2 * y0;
+        rp[q2] = s2 * x0 + c2 * y0;
+        rq[p2] = c2 * x1 - s2 * y1;
+        rq[q2] = s2 * x1 + c2 * y1;
     }
-}
-
-// Vt <- J^T Vt, in place
-__global__ __launch_bounds__(kEigThreads) void eig_rotate_rows_kernel(EigPlan e, int sweep) {
-    if (eig_converged(e, sweep)) return;
-    const int k = blockIdx.y;
-    const int j = blockIdx.x * kEigThreads + threadIdx.x;
-    if (j >= e.n) return;
-    const int p = e.pq[2 * k], q = e.pq[2 * k + 1];
-    const double c = e.cs[2 * k], s = e.cs[2 * k + 1];
-    double* rp = e.vt + (int64_t)p * e.n;
-    double* rq = e.vt + (int64_t)q * e.n;
-    const double vp = rp[j], vq = rq[j];
-    rp[j] = c * vp - s * vq;
-    rq[j] = s * vp + c * vq;
+    __syncthreads();
+    for (int j = t; j < n; j += kEigThreads) {
+        ap[j] = rp[j];
+        aq[j] = rq[j];
+    }
 }
 
 // eigenvalue i = a[i][i]; its position in decreasing order (ties by index); column
@@ -152,7 +135,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_finish_kernel(EigPlan e, floa
                                                                  float* __restrict__ p, int64_t ldp) {
     const int i = blockIdx.x;
     const int n = e.n;
-    const double* a = e.a[0];
+    const double* a = e.a;
     const double li = a[(int64_t)i * n + i];
     __shared__ int count[kEigThreads];
     int c = 0;
