@@ -242,22 +242,29 @@ def test_layer_saturated_codes(oracle, rq):
     check_layer(oracle, rq, x.to(torch.bfloat16), w.to(torch.bfloat16), r)
 
 
-def test_layer_oproj_prefill_sampled(oracle, rq):
-    # the benchmark's configuration at full size; the oracle checks all codes and
-    # a seeded sample of 48 token rows of the accumulators and outputs
-    s = wl.OPROJ_PREFILL
+@pytest.mark.parametrize("which", ["oproj_prefill", "gate_up_prefill", "qwen_r1024"])
+def test_layer_prefill_full_size_sampled(oracle, rq, which):
+    # the benchmark's prefill configurations at full size, in the launch configuration the
+    # benchmark times; the oracle checks all activation codes, all packed weights, and a
+    # seeded sample of token rows of the accumulators and outputs
+    s = {"oproj_prefill": wl.OPROJ_PREFILL, "gate_up_prefill": wl.MLP_GATE_UP,
+         "qwen_r1024": wl.qwen_mlp_shape(1024)}[which]
+    nrows = 48 if which == "oproj_prefill" else 24
     x, w = wl.make_activations(s), wl.make_weights(s)
     act = check_act_codes(oracle, rq, x, s.r)
     packed, wq = check_weights(oracle, rq, w, s.r)
+    del w
     dbg_hi = torch.empty((s.M, s.N), dtype=torch.int32, device="cuda")
     dbg_lo = torch.empty((s.M, s.N), dtype=torch.int32, device="cuda")
     y = rq.resq_gemm_mixed(act, packed, s.N, dbg_acc_hi=dbg_hi, dbg_acc_lo=dbg_lo)
     torch.cuda.synchronize()
-    rows = np.sort(np.random.default_rng(0).choice(s.M, 48, replace=False))
+    rows = np.sort(np.random.default_rng(0).choice(s.M, nrows, replace=False))
+    rt = torch.from_numpy(rows).cuda()
     ref = oracle.linear(wl.bf16_bits(x[rows]), None, s.r, weights=wq)
-    assert np.array_equal(dbg_hi.cpu().numpy()[rows].astype(np.int64), ref.acc_hi)
-    assert np.array_equal(dbg_lo.cpu().numpy()[rows].astype(np.int64), ref.acc_lo)
-    assert y_within_tolerance(y[rows], ref.y) <= REL_TOL
+    assert np.array_equal(dbg_hi[rt].cpu().numpy().astype(np.int64), ref.acc_hi)
+    assert np.array_equal(dbg_lo[rt].cpu().numpy().astype(np.int64), ref.acc_lo)
+    assert y_within_tolerance(y[rt], ref.y) <= REL_TOL
+    del dbg_hi, dbg_lo
     y2 = rq.resq_gemm_mixed(act, packed, s.N)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
