@@ -310,6 +310,26 @@ def test_down_proj_path_hadamard_then_quantize(oracle, rq):
     check_layer(oracle, rq, xt.cpu(), w, s.r)
 
 
+@pytest.mark.parametrize("M,K,N,r", [(24, 1792 + 12544, 256, 1792), (130, 2048, 300, 512), (4096, 1792 + 12544, 4096, 1792)])
+def test_down_proj_chain_end_to_end(oracle, rq, M, K, N, r):
+    # the whole down_proj step against the oracle's own chain (its fp64 transform rounded to
+    # bf16, its quantizer, its GEMMs): nothing of the HIP path enters the oracle.  The fp32
+    # butterflies differ from the fp64 ones in the last bf16 bit of < 1 % of the elements, which
+    # moves a few codes by one step, so integers are not compared here, only the output, on a
+    # sample of rows at the full size (the last case is the benchmark's down_proj workload).
+    s = wl.LayerShape("down_chain", M=M, K=K, N=N, r=r, act="student_t3", hadamard=True, seed=M + N)
+    x, w = wl.make_activations(s), wl.make_weights(s)
+    b = rq.resq_hadamard_block(K - r)
+    act = rq.resq_hadamard_quantize_act(x.cuda(), r, 0)
+    packed = rq.resq_pack_weights(w.cuda(), r)
+    y = rq.resq_gemm_mixed(act, packed, N)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(1).choice(M, min(M, 24), replace=False))
+    xr = oracle.hadamard(wl.bf16_bits(x[rows]), r, K, b)
+    ref = oracle.linear(xr, wl.bf16_bits(w), r)
+    assert y_within_tolerance(y[torch.from_numpy(rows).cuda()], ref.y) <= REL_TOL
+
+
 @pytest.mark.parametrize("M,K,r,block", [
     (5, 1792 + 12544, 1792, 0),      # the down_proj input: 49 blocks of 256
     (3, 2048, 512, 512), (4, 1024, 256, 64), (3, 4096, 0, 512), (2, 528, 16, 16),
