@@ -232,6 +232,29 @@ def test_layer_decode_full_size(oracle, rq):
     check_layer(oracle, rq, wl.make_activations(s), wl.make_weights(s), s.r)
 
 
+def _random_layer_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M = int(rng.choice([1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100, 128, 129, 200, 255, 256, 257, 300]))
+        K = int(rng.choice([64, 90, 256, 520, 1000, 2048, 3200, 4096, 8192]))
+        K += int(rng.integers(0, 3)) * 2 if K not in (2048, 4096, 8192) else 0
+        N = int(rng.choice([16, 40, 130, 256, 272, 515, 1024, 2100]))
+        r = int(rng.choice([0, K // 8, K // 4, K])) // 2 * 2
+        if (K - r) % 2:
+            r += 1
+        out.append((M, K, N, min(r, K)))
+    return out
+
+
+@pytest.mark.parametrize("M,K,N,r", _random_layer_shapes(40, 2024))
+def test_layer_random_shapes_across_dispatch_boundaries(oracle, rq, M, K, N, r):
+    # seeded draw over the sizes at which resq_gemm_mixed changes kernel (16/17, 64/65, 256/257
+    # tokens; few or many channel groups; reduction axes short, ragged and long)
+    x, w = wl.random_small_case(M * 31 + K * 7 + N, M, K, N, r, act="student_t3")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
 def test_layer_saturated_codes(oracle, rq):
     # every code at +-qmax: the largest accumulators the shapes allow
     M, K, N, r = 32, 2048, 256, 256
