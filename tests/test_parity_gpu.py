@@ -610,3 +610,27 @@ def test_snr_per_rank_matches_oracle(oracle, rq):
         assert abs(snr_gpu - snr_cpu) < 0.05, (r, snr_gpu, snr_cpu)
         got.append(snr_gpu)
     assert got[0] < got[1] < got[2], got
+
+
+# ---- the variants over the same dispatch boundaries --------------------------------
+
+@pytest.mark.parametrize("M,K,N,r", _random_layer_shapes(16, 77))
+def test_layer_asym_random_shapes(oracle, rq, M, K, N, r):
+    x, w = wl.random_small_case(M * 3 + K + N, M, K, N, r, act="student_t3")
+    x = (x.float() + 1.5).to(torch.bfloat16)
+    check_layer_asym(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+@pytest.mark.parametrize("M,K,N,r", _random_layer_shapes(16, 99))
+def test_layer_swiglu_random_shapes(oracle, rq, M, K, N, r):
+    F = max(N // 2, 1)
+    x, w = wl.random_small_case(M + K + F, M, K, 2 * F, r, act="student_t3")
+    w = (w.float() * 8).to(torch.bfloat16)
+    act = rq.resq_quantize_act(x.cuda(), r)
+    packed = rq.resq_pack_weights(w.cuda(), r)
+    ref = oracle.swiglu(oracle.linear(wl.bf16_bits(x), wl.bf16_bits(w), r).y)
+    ybuf = torch.zeros((M, F + 8), dtype=torch.bfloat16, device="cuda")
+    y = rq.resq_gemm_mixed_swiglu(act, packed, 2 * F, y=ybuf[:, :F])
+    torch.cuda.synchronize()
+    assert y_within_tolerance(y, ref) <= REL_TOL
+    assert not ybuf[:, F:].any(), "wrote past F"
