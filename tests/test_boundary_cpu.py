@@ -161,7 +161,9 @@ def test_basis_entry_points_reject_bad_arguments():
     assert g(None, 128, 10, 128, P, 128, None) == 1
     assert g(None, 128, 0, 128, None, 128, None) == 0                        # no tokens: nothing to do
     e = L.resq_sym_eig
-    assert L.resq_sym_eig_workspace_bytes(7) == 0 and L.resq_sym_eig_workspace_bytes(64) >= 3 * 64 * 64 * 8
+    assert L.resq_sym_eig_workspace_bytes(7) == 0 and L.resq_sym_eig_workspace_bytes(64) >= 2 * 64 * 64 * 8
+    assert L.resq_sym_eig_workspace_bytes(8194) == 0                         # two rows must fit LDS
+    assert e(P, 8194, 8194, 8, P, P, 8194, P, 1 << 40, None) == 2
     assert e(P, 63, 63, 8, P, P, 63, P, 1 << 30, None) == 2                  # odd order
     assert e(P, 64, 64, 0, P, P, 64, P, 1 << 30, None) == 2                  # no sweeps
     assert e(P, 64, 64, 8, P, P, 64, P, 100, None) == 4                      # workspace too small
