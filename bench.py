@@ -357,6 +357,64 @@ def basis_bench(args) -> None:
     print(json.dumps(res))
 
 
+def mfma_ceiling_bench(args) -> None:
+    """Not a workload of the method: what this chip sustains on v_mfma_i32_32x32x32_i8 alone,
+    for operand bytes like the GEMM's (all zero; INT4 codes widened to the high nibble and the
+    offset low nibble; random INT8 codes) and launches about as long as the GEMM's.  The matrix
+    pipes are power-limited, so this, not the nominal 5 POPS, is what the GEMM can approach."""
+    import ctypes
+    import numpy as np
+    import torch
+    from paper_2412_14363_amd import binding as rq
+
+    L = rq.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(0)
+    kinds = {
+        "zeros": np.zeros(2048 * 16, np.uint8),
+        "int4_widened": np.where(np.arange(2048 * 16) % 32 < 16,
+                                 (rng.integers(-7, 8, 2048 * 16) * 16) & 0xFF,          # weight-like: code << 4
+                                 rng.integers(1, 16, 2048 * 16)).astype(np.uint8),      # activation-like: code + 8
+        "random_int8": (rng.integers(-127, 128, 2048 * 16) & 0xFF).astype(np.uint8),
+    }
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hip = ctypes.CDLL("libamdhip64.so")
+    wgs = 256                                  # one workgroup of four wavefronts per compute unit, as the GEMM
+    out_rows = {}
+    for name, host in kinds.items():
+        dev = torch.from_numpy(host).cuda()
+        for label, iters in (("35us", 290), ("200us", 1650), ("1500us", 12400)):
+            for _ in range(2):
+                assert L.resq_probe_mfma_int8(dev.data_ptr(), iters, wgs, sink.data_ptr(), st) == 0
+            torch.cuda.synchronize()
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+            tot, reps = 0.0, 5
+            for _ in range(reps):
+                L.resq_time_next_kernel(a, b)
+                assert L.resq_probe_mfma_int8(dev.data_ptr(), iters, wgs, sink.data_ptr(), st) == 0
+                torch.cuda.synchronize()
+                ms = ctypes.c_float()
+                assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+                tot += ms.value
+            hip.hipEventDestroy(a)
+            hip.hipEventDestroy(b)
+            ms_avg = tot / reps
+            ops = 2.0 * 32 ** 3 * 8 * 4 * iters * wgs
+            out_rows[f"{name}_{label}"] = {"kernel_ms": ms_avg, "tops": ops / (ms_avg * 1e-3) / 1e12}
+    best = out_rows["int4_widened_200us"]["tops"]
+    print(json.dumps({
+        "metric": "sustained int8 MFMA rate, matrix instructions only (TOPS)", "value": best, "unit": "TOPS",
+        "n_gpus": 1, "steps": 5, "warmup": 2, "ms_per_step": out_rows["int4_widened_200us"]["kernel_ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "mfma_ceiling: 256 workgroups x 4 wavefronts, 8 accumulator tiles each", "tag": "mfma_ceiling"},
+        "rates": out_rows,
+        "roofline": {"bound": "mfma", "achieved": best, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                     "frac": best / PEAK_INT8_TOPS, "traffic": None, "kernel": "resq probe_mfma_int8 (int4_widened, 200 us)",
+                     "kernel_ms": out_rows["int4_widened_200us"]["kernel_ms"]},
+    }))
+
+
 def mlp_block_bench(args) -> None:
     """The MLP block of Llama-3-8B on 4096 tokens as four kernels: quantize_act,
     gate/up as one layer with the gated activation in its epilogue (N2 = 28672), the
@@ -490,6 +548,9 @@ def main() -> None:
         return
     if args.workload == "basis":
         basis_bench(args)
+        return
+    if args.workload == "mfma_ceiling":
+        mfma_ceiling_bench(args)
         return
     s = workload_shape(args.workload)
     if args.workload == "uc_proj":

@@ -62,6 +62,19 @@ const char* resq_status_string(int status);
  */
 int resq_time_next_kernel(void* start_event, void* stop_event);
 
+/*
+ * Measurement aid, not part of the method (for callers that want to know what the
+ * GEMM's fraction of the nominal matrix peak is worth on the chip at hand): runs
+ * `iters` times eight independent v_mfma_i32_32x32x32_i8 per wavefront, four
+ * wavefronts per workgroup, with operand fragments taken from operand_bytes (device,
+ * 32 KiB, 16-byte aligned, read once) and nothing else in the loop:
+ * 2 * 32^3 * 8 * 4 * iters * workgroups operations.  The caller times it (with
+ * resq_time_next_kernel or its own events) and chooses the bytes: the matrix pipes
+ * are power-limited, so all-zero, INT4-like and random INT8 operands run at
+ * different rates.  sink: one int, device, never written in practice.
+ */
+int resq_probe_mfma_int8(const void* operand_bytes, int iters, int workgroups, int* sink, void* stream);
+
 /* ---- layout queries (pure host functions) ------------------------------- */
 
 /*

@@ -12,6 +12,7 @@
 #include "resq_hadamard.hip.h"
 #include "resq_headproj.hip.h"
 #include "resq_layout.h"
+#include "resq_probe.hip.h"
 #include "resq_quantize.hip.h"
 
 using namespace resq;
@@ -609,6 +610,15 @@ int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigv
         }
     }
     launch(eig_finish_kernel, dim3((unsigned)n), dim3(kEigThreads), 0, st, e, eigvals, p, ldp);
+    return launch_status();
+}
+
+int resq_probe_mfma_int8(const void* operand_bytes, int iters, int workgroups, int* sink, void* stream) {
+    if (iters < 1 || iters > (1 << 24) || workgroups < 1 || workgroups > 65536) return RESQ_ERR_SHAPE;
+    if (!operand_bytes || !sink) return RESQ_ERR_NULL;
+    if (!aligned(operand_bytes, 16) || !aligned(sink, 4)) return RESQ_ERR_ALIGN;
+    launch(probe_mfma_int8_kernel, dim3((unsigned)workgroups), dim3(kProbeThreads), 0,
+           static_cast<hipStream_t>(stream), iters, static_cast<const v4i*>(operand_bytes), sink);
     return launch_status();
 }
 
