@@ -415,6 +415,57 @@ def mfma_ceiling_bench(args) -> None:
     }))
 
 
+def hbm_ceiling_bench(args) -> None:
+    """Not a workload of the method: the rate of a plain streaming read, for a launch that reads
+    as many bytes as the decode GEMM does (the 132 MB of packed weights of the Llama-3-70B up_proj,
+    rotated over regions that the last-level cache cannot hold) and for one long read of 3 GiB."""
+    import ctypes
+    import torch
+    from paper_2412_14363_amd import binding as rq
+
+    L = rq.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    hip = ctypes.CDLL("libamdhip64.so")
+    region = 132_600_000 // 256 * 256
+    buf = torch.ones(3 << 30, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    rows = {}
+
+    def timed(offset, nbytes, wgs, reps):
+        a, b = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+        tot = 0.0
+        for i in range(reps + 2):
+            off = (offset + i * (region + 4096)) % (buf.numel() - nbytes) // 256 * 256 if nbytes == region else 0
+            L.resq_time_next_kernel(a, b)
+            assert L.resq_probe_hbm_read(buf.data_ptr() + off, nbytes, wgs, sink.data_ptr(), st) == 0
+            torch.cuda.synchronize()
+            ms = ctypes.c_float()
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+            if i >= 2:
+                tot += ms.value
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(b)
+        return tot / reps
+
+    for wgs in (1024, 2048, 4096, 8192):
+        ms = timed(0, region, wgs, 12)
+        rows[f"read_132MB_{wgs}wg"] = {"kernel_ms": ms, "gbs": region / (ms * 1e-3) / 1e9}
+    for wgs in (4096, 16384):
+        ms = timed(0, buf.numel(), wgs, 3)
+        rows[f"read_3GiB_{wgs}wg"] = {"kernel_ms": ms, "gbs": buf.numel() / (ms * 1e-3) / 1e9}
+    best = max(v["gbs"] for k, v in rows.items() if k.startswith("read_132MB"))
+    print(json.dumps({
+        "metric": "plain streaming read GB/s", "value": best, "unit": "GB/s", "n_gpus": 1, "steps": 12, "warmup": 2,
+        "ms_per_step": region / best / 1e6, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "hbm_ceiling: one launch reads 132.6 MB (regions rotated through 3 GiB), or all 3 GiB", "tag": "hbm_ceiling"},
+        "rates": rows,
+        "roofline": {"bound": "hbm", "achieved": best, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": best / PEAK_HBM_GBS,
+                     "traffic": None, "kernel": "resq probe_hbm_read (132.6 MB per launch)", "kernel_ms": region / best / 1e6},
+    }))
+
+
 def mlp_block_bench(args) -> None:
     """The MLP block of Llama-3-8B on 4096 tokens as four kernels: quantize_act,
     gate/up as one layer with the gated activation in its epilogue (N2 = 28672), the
@@ -551,6 +602,9 @@ def main() -> None:
         return
     if args.workload == "mfma_ceiling":
         mfma_ceiling_bench(args)
+        return
+    if args.workload == "hbm_ceiling":
+        hbm_ceiling_bench(args)
         return
     s = workload_shape(args.workload)
     if args.workload == "uc_proj":

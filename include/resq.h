@@ -75,6 +75,15 @@ int resq_time_next_kernel(void* start_event, void* stop_event);
  */
 int resq_probe_mfma_int8(const void* operand_bytes, int iters, int workgroups, int* sink, void* stream);
 
+/*
+ * Measurement aid, not part of the method: a plain streaming read of the first
+ * bytes / 16 * 16 bytes of buf (device, 16-byte aligned) by `workgroups` workgroups of
+ * 256 threads with four 16-byte loads in flight per lane; what a kernel that must
+ * read that many bytes once can reach on the chip at hand (the generation-stage GEMM
+ * reads its packed weights once).  sink: one int, device, never written in practice.
+ */
+int resq_probe_hbm_read(const void* buf, size_t bytes, int workgroups, int* sink, void* stream);
+
 /* ---- layout queries (pure host functions) ------------------------------- */
 
 /*

@@ -622,4 +622,14 @@ int resq_probe_mfma_int8(const void* operand_bytes, int iters, int workgroups, i
     return launch_status();
 }
 
+int resq_probe_hbm_read(const void* buf, size_t bytes, int workgroups, int* sink, void* stream) {
+    if (bytes < 16 || workgroups < 1 || workgroups > (1 << 20)) return RESQ_ERR_SHAPE;
+    if (!buf || !sink) return RESQ_ERR_NULL;
+    if (!aligned(buf, 16) || !aligned(sink, 4)) return RESQ_ERR_ALIGN;
+    launch(probe_hbm_read_kernel, dim3((unsigned)workgroups), dim3(kProbeThreads), 0,
+           static_cast<hipStream_t>(stream), static_cast<const uint4*>(buf), bytes / 16,
+           reinterpret_cast<uint32_t*>(sink));
+    return launch_status();
+}
+
 }  // extern "C"

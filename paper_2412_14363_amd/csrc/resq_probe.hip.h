@@ -44,4 +44,22 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mfma_int8_kernel(int iter
     if (s == 0x7fffffff) sink[0] = s;  // keeps the loop alive; practically never true
 }
 
+// The same for HBM: a plain streaming read of `n16` 16-byte words, four loads in flight per
+// lane, results folded into a value that is practically never stored: what a kernel that
+// must read this many bytes once (the generation-stage GEMM: its packed weights) can reach.
+__global__ __launch_bounds__(kProbeThreads) void probe_hbm_read_kernel(const uint4* __restrict__ p, size_t n16,
+                                                                      uint32_t* __restrict__ sink) {
+    size_t i = (size_t)blockIdx.x * kProbeThreads * 4 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kProbeThreads * 4;
+    uint32_t acc = 0;
+    for (; i < n16; i += stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = i + kProbeThreads * u < n16 ? p[i + kProbeThreads * u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x12345678u) sink[0] = acc;
+}
+
 }  // namespace resq
