@@ -317,22 +317,29 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
 
     // a few tens of tokens: the same single pass over the weights, activation codes
     // chunked through LDS
-    // Up to 256 tokens take the same kernel in slices of 64 tokens (each slice streams
+    // Up to 1024 tokens take the same kernel in slices of 64 tokens (each slice streams
     // the weights for itself) when the tiled kernel would leave most of the chip idle:
     // few tiles, each walking the whole reduction axis alone.  Estimated from the
     // measured costs of both kernels, per round of 256 workgroups: 10 us + 0.5 us per
     // 1 KiB block of a channel group for a tile, 8 us + 0.4 us per block of a run for
-    // a slice.
+    // a slice; the number of runs per group is the one with the lower estimate.
     bool streaming = M <= kStreamMaxM;
-    if (!streaming && M <= 4 * kStreamMaxM) {
+    int stream_sk = 0;  // 0: as many runs as the shape allows (a single slice)
+    if (!streaming && M <= 16 * kStreamMaxM) {
         const int64_t blocks = L.hi_blocks + L.lo_blocks, groups = (N + 15) / 16;
-        int64_t sk = 1;
-        while (sk * 4 < 8 && groups * sk <= 1024 && blocks / (2 * sk) >= 2 * kChunkBlocks) sk *= 2;
         const int64_t slices = (M + kStreamMaxM - 1) / kStreamMaxM;
-        const int64_t wgs = (groups * sk + 7) / 8 * slices;
         const int64_t tiles = ((M + kBM - 1) / kBM) * ((N + kBN - 1) / kBN);
-        const double stream_us = (double)((wgs + 255) / 256) * (8.0 + 0.4 * (double)(blocks / sk));
         const double tiled_us = (double)((tiles + 255) / 256) * (10.0 + 0.5 * (double)blocks);
+        double stream_us = 0.0;
+        for (int sk = 1; sk * 4 <= 8; sk *= 2) {
+            if (sk > 1 && (groups * sk > 2048 || blocks / sk < 2 * kChunkBlocks)) break;
+            const int64_t wgs = (groups * sk + 7) / 8 * slices;
+            const double us = (double)((wgs + 255) / 256) * (8.0 + 0.4 * (double)(blocks / sk));
+            if (stream_sk == 0 || us < stream_us) {
+                stream_us = us;
+                stream_sk = sk;
+            }
+        }
         streaming = stream_us < 0.9 * tiled_us;
     }
     if (streaming) {
@@ -362,7 +369,9 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         const int tg = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
         const int slices = (int)((M + tg * 16 - 1) / (tg * 16));  // of tg * 16 tokens
         int sk = 1;
-        while (sk * tg < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 2 * kChunkBlocks) sk *= 2;
+        if (stream_sk > 0) sk = stream_sk;
+        else
+            while (sk * tg < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 2 * kChunkBlocks) sk *= 2;
         const int sets = (d.groups * sk + 7) / 8;
         const dim3 grid((unsigned)(sets < 256 ? sets : 256), (unsigned)slices), blk(kDecodeThreads);
         const int lds_bytes = 2 * sk * tg * kChunkBlocks * kBlockBytes;

@@ -173,8 +173,8 @@ def test_layer_tiny_config(oracle, rq):
     (260, 640, 300, 128), (385, 90, 40, 30), (290, 4096, 512, 512), (258, 256, 256, 0), (258, 256, 256, 256),
 ])
 def test_layer_shapes(oracle, rq, M, K, N, r):
-    # M > 256 always takes the tiled kernel; 64 < M <= 256 takes it or the weight-streaming
-    # kernel in slices of 64 tokens, whichever the dispatch estimates to be faster
+    # 64 < M <= 1024 takes the tiled kernel or the weight-streaming kernel in slices of 64
+    # tokens, whichever the dispatch estimates to be faster (few channels: the latter)
     x, w = wl.random_small_case(M * 7 + K, M, K, N, r, act="student_t3")
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
@@ -217,6 +217,29 @@ def test_layer_decode_long_rows(oracle, rq, M, K, N, r):
     # M <= 16 with rows too long for LDS: the chunked weight-streaming kernel with one token group
     x, w = wl.random_small_case(M * 3 + N, M, K, N, r, outliers="first4")
     check_layer(oracle, rq, x, w, r)
+
+
+# more than 1024 tokens: always the tiled kernel, here on small ragged layers
+TILED_SHAPES = [
+    (1030, 640, 300, 128), (1100, 1000, 515, 104), (1025, 90, 40, 30),
+    (1153, 256, 256, 0), (1153, 256, 256, 256), (1200, 2048, 768, 256),
+]
+
+
+@pytest.mark.parametrize("M,K,N,r", TILED_SHAPES)
+def test_layer_tiled_kernel_small_layers(oracle, rq, M, K, N, r):
+    x, w = wl.random_small_case(M * 17 + K, M, K, N, r, act="student_t3")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+@pytest.mark.parametrize("M,K,N,r", [
+    (385, 2048, 400, 256), (512, 4096, 272, 512), (1000, 1000, 515, 104), (1024, 3200, 256, 448),
+    (700, 256, 256, 0), (640, 256, 64, 256), (1024, 14336, 144, 1792),
+])
+def test_layer_sliced_streaming_up_to_1024_tokens(oracle, rq, M, K, N, r):
+    # few channels, up to 16 slices of 64 tokens through the weight-streaming kernel
+    x, w = wl.random_small_case(M * 19 + K, M, K, N, r, outliers="first4")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
 def test_layer_batched_decode_full_size(oracle, rq):
@@ -485,13 +508,20 @@ def test_quantize_act_asym_constant_rows_and_ties(oracle, rq):
 
 @pytest.mark.parametrize("M,K,N,r", [
     (130, 640, 300, 128), (257, 1000, 515, 104), (64, 4096, 512, 512), (200, 90, 40, 30),
-    (48, 512, 256, 0), (48, 512, 256, 512),          # tiled kernel
-    (1, 512, 256, 64), (16, 1000, 515, 104), (7, 2048, 272, 256), (3, 256, 256, 0),   # weight-streaming kernel
-    (24, 2048, 272, 256), (100, 4096, 130, 512), (128, 1000, 515, 104),               # 16 < M <= 64: streaming with chunked codes; above: tiled
+    (48, 512, 256, 0), (48, 512, 256, 512),
+    (1, 512, 256, 64), (16, 1000, 515, 104), (7, 2048, 272, 256), (3, 256, 256, 0),   # activation codes resident in LDS
+    (24, 2048, 272, 256), (100, 4096, 130, 512), (128, 1000, 515, 104),               # chunked codes, one or several slices
 ])
 def test_layer_asym(oracle, rq, M, K, N, r):
     x, w = wl.random_small_case(M * 5 + K, M, K, N, r, act="student_t3")
     x = (x.float() + 1.5).to(torch.bfloat16)          # off-centre activations: a real zero-point
+    check_layer_asym(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+@pytest.mark.parametrize("M,K,N,r", TILED_SHAPES[:4] + [(900, 1000, 272, 104)])
+def test_layer_asym_tiled_kernel_and_many_slices(oracle, rq, M, K, N, r):
+    x, w = wl.random_small_case(M * 5 + K + 1, M, K, N, r, act="student_t3")
+    x = (x.float() + 1.5).to(torch.bfloat16)
     check_layer_asym(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
@@ -568,9 +598,10 @@ def test_project_heads_no_rows(rq):
 # ---- gate/up as one layer with the gated activation in the epilogue ----------------
 
 @pytest.mark.parametrize("M,K,F,r", [
-    (130, 640, 150, 128), (64, 512, 256, 64), (300, 1024, 384, 0), (40, 256, 130, 256),   # tiled kernel
-    (1, 512, 128, 64), (16, 1000, 257, 104), (5, 256, 64, 0),                             # weight-streaming kernel
-    (20, 1000, 257, 104), (128, 2048, 136, 256),                                          # 16 < M <= 64: streaming with chunked codes; above: tiled
+    (130, 640, 150, 128), (64, 512, 256, 64), (300, 1024, 384, 0), (40, 256, 130, 256),
+    (1, 512, 128, 64), (16, 1000, 257, 104), (5, 256, 64, 0),                             # activation codes resident in LDS
+    (20, 1000, 257, 104), (128, 2048, 136, 256), (900, 1000, 136, 104),                   # chunked codes, one or several slices
+    (1030, 640, 150, 128), (1100, 1000, 257, 104), (1153, 256, 128, 0), (1153, 256, 128, 256),   # above 1024 tokens: tiled kernel
 ])
 def test_layer_swiglu(oracle, rq, M, K, F, r):
     x, w = wl.random_small_case(M + K + F, M, K, 2 * F, r, act="student_t3")
