@@ -94,12 +94,15 @@ def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 
     from paper_2412_14363_amd import workloads as wl
 
     xb = wl.bf16_bits(x)
-    probe = min(shape.M, 2)
-    t0 = time.perf_counter()
     layer = oracle.linear_asym if asym else oracle.linear
-    layer(xb[:probe], None, shape.r, weights=wq_np)
-    t_probe = max(time.perf_counter() - t0, 1e-4)
-    rows = int(max(1, min(shape.M, probe * budget_s / t_probe)))
+    # two probes: the first pays the start-up of the oracle's threads, the second (as many
+    # rows as the first says fit into a tenth of the budget) gives the cost per row
+    rows = min(shape.M, 2)
+    for share in (0.1, 1.0):
+        t0 = time.perf_counter()
+        layer(xb[:rows], None, shape.r, weights=wq_np)
+        t_probe = max(time.perf_counter() - t0, 1e-4)
+        rows = int(max(1, min(shape.M, rows * share * budget_s / t_probe)))
     idx = np.sort(np.random.default_rng(0).choice(shape.M, rows, replace=False))
     sample = np.ascontiguousarray(xb[idx])
     t0 = time.perf_counter()
