@@ -55,6 +55,8 @@ def workload_shape(name: str):
         "qwen_r0": wl.qwen_mlp_shape(0),
         "qwen_r1024": wl.qwen_mlp_shape(1024),
         "qwen_r2048": wl.qwen_mlp_shape(2048),
+        "oproj_m512": wl.chunk_shape("o_proj", 512),
+        "down_m512": wl.chunk_shape("down", 512),
         "kv_quant": wl.KV_CACHE_QUANT,
         "uc_proj": wl.UC_PROJ,
     }

@@ -150,7 +150,11 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
  *   resq_quantize_act(t, ...)
  * (same butterflies in the same order, same rounding of the rotated values to
  * bf16 before they are quantized), but the rotated row is not written to memory
- * and read back: one read of x in all.
+ * and read back: one read of x in all.  Blocks of 256 (the Llama down_proj
+ * inputs) take most of their sums on the bf16 matrix cores, in another order:
+ * there a rotated value may be the neighbouring bf16 of the stand-alone
+ * transform's (both within rounding of the exact transform), and the codes are
+ * exactly those of resq_quantize_act on the rotated row that x_rot receives.
  *   block   power of two in [8, 512] dividing both r and K - r (a block is held
  *           by one wavefront); 0 selects resq_hadamard_block(K - r).  Other
  *           sizes: RESQ_ERR_SHAPE, use the two calls above.
@@ -158,7 +162,8 @@ int resq_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t 
  *           multiple of 8): receives columns [r, K) of the rotated rows, for
  *           inspection and parity checks; columns [0, r) are not touched.
  * Needs the vectorized path: x 16-byte aligned, ldx, K, r multiples of 8,
- * K <= 16384 (else RESQ_ERR_ALIGN).  Other arguments as resq_quantize_act.
+ * K <= 16384, or with blocks of 256 r <= 4096 and K - r <= 26624 (else
+ * RESQ_ERR_ALIGN).  Other arguments as resq_quantize_act.
  */
 int resq_hadamard_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
                                int64_t block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
@@ -189,6 +194,17 @@ int resq_hadamard_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K,
 int resq_quantize_act_asym(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
                            int64_t hadamard_block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
                            float* s_lo, float* c_hi, float* c_lo, int32_t* lo_sum, void* stream);
+
+/*
+ * resq_quantize_act_asym with the block Walsh-Hadamard transform of the low
+ * group in front (the down_proj input with asymmetric codes, Sections 4.3 and
+ * 5.1) and the optional inspection output of resq_hadamard_quantize_act:
+ * block, x_rot, ld_rot as there, everything else as resq_quantize_act_asym.
+ */
+int resq_hadamard_quantize_act_asym(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                                    int64_t block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
+                                    float* s_lo, float* c_hi, float* c_lo, int32_t* lo_sum,
+                                    void* x_rot, int64_t ld_rot, void* stream);
 
 /*
  * Offline weight quantization and packing (Section 4.1 Eq. 3; per output

@@ -31,6 +31,7 @@ SYMBOLS = {
     "resq_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p]),
     "resq_hadamard_quantize_act": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _i64, _p]),
     "resq_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p]),
+    "resq_hadamard_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _i64, _p]),
     "resq_gemm_mixed_asym": (C.c_int, [_p, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
     "resq_gemm_mixed_swiglu": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_gram_accumulate": (C.c_int, [_p, _i64, _i64, _i64, _p, _i64, _p]),
@@ -191,6 +192,29 @@ def resq_quantize_act_asym(x: torch.Tensor, r: int, hadamard_block: int = 0,
         out.c_hi.data_ptr() if hi else None, out.c_lo.data_ptr() if lo else None,
         out.lo_sum.data_ptr() if lo else None, _stream(stream))
     _check(st, "resq_quantize_act_asym")
+    out.asym = True
+    return out
+
+
+def resq_hadamard_quantize_act_asym(x: torch.Tensor, r: int, block: int = 0,
+                                    out: Optional[ActCodes] = None,
+                                    x_rot: Optional[torch.Tensor] = None, stream=None) -> ActCodes:
+    M, K = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    if x_rot is not None and x_rot.stride(1) != 1:
+        raise ValueError("x_rot must be row-major")
+    if out is None:
+        out = ActCodes(M, K, r, x.device)
+    hi = r > 0
+    st = lib().resq_hadamard_quantize_act_asym(
+        _dev(x, torch.bfloat16, "x"), x.stride(0), M, K, r, block,
+        out.q_hi.data_ptr() if hi else None, out.q_lo.data_ptr(),
+        out.s_hi.data_ptr() if hi else None, out.s_lo.data_ptr(),
+        out.c_hi.data_ptr() if hi else None, out.c_lo.data_ptr(), out.lo_sum.data_ptr(),
+        _dev(x_rot, torch.bfloat16, "x_rot"), x_rot.stride(0) if x_rot is not None else 0,
+        _stream(stream))
+    _check(st, "resq_hadamard_quantize_act_asym")
     out.asym = True
     return out
 

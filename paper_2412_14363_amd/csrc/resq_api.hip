@@ -108,8 +108,23 @@ static int quantize_act_impl(const void* x, int64_t ldx, int64_t M, int64_t K, i
     const dim3 block(kQuantThreads), grid((unsigned)M);
     const bool vec = aligned(x, 16) && ldx % 8 == 0 && K % 8 == 0 && r % 8 == 0 && K <= 16384;
     const bool rotate = rot.log2b > 0;
-    if (rotate && !vec) return RESQ_ERR_ALIGN;
 #define RESQ_QA_ARGS xp, ldx, (int)K, (int)r, q_hi, ld_hi, q_lo, ld_lo, s_hi, s_lo, lo_sum
+    // blocks of 256: the first five butterfly stages on the matrix cores
+    if (rot.log2b == 8 && aligned(x, 16) && ldx % 8 == 0 && r <= 4096 && K - r <= 13 * 2048) {
+#define RESQ_LAUNCH_H256(HI, LO)                                                                    \
+    do {                                                                                            \
+        if (asym)                                                                                   \
+            launch(hadamard256_quantize_kernel<HI, LO, true>, grid, block, 0, st, RESQ_QA_ARGS, rot, c_hi, c_lo);  \
+        else                                                                                        \
+            launch(hadamard256_quantize_kernel<HI, LO, false>, grid, block, 0, st, RESQ_QA_ARGS, rot, c_hi, c_lo); \
+    } while (0)
+        if (r <= 2048 && K - r <= 2 * 2048) RESQ_LAUNCH_H256(1, 2);
+        else if (r <= 2048 && K - r <= 7 * 2048) RESQ_LAUNCH_H256(1, 7);
+        else RESQ_LAUNCH_H256(2, 13);
+#undef RESQ_LAUNCH_H256
+        return launch_status();
+    }
+    if (rotate && !vec) return RESQ_ERR_ALIGN;
 #define RESQ_LAUNCH_QA(ITERS)                                                                       \
     do {                                                                                            \
         if (rotate && asym)                                                                         \
@@ -187,6 +202,18 @@ int resq_hadamard_quantize_act(const void* x, int64_t ldx, int64_t M, int64_t K,
     if (rc != RESQ_OK) return rc;
     return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, false, nullptr,
                              nullptr, stream);
+}
+
+int resq_hadamard_quantize_act_asym(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,
+                                    int64_t block, int8_t* q_hi, uint8_t* q_lo, float* s_hi,
+                                    float* s_lo, float* c_hi, float* c_lo, int32_t* lo_sum,
+                                    void* x_rot, int64_t ld_rot, void* stream) {
+    if (!shape_ok(M, K, r)) return RESQ_ERR_SHAPE;
+    RotateArgs rot;
+    const int rc = make_rotate_args(K, r, block, x_rot, ld_rot, rot);
+    if (rc != RESQ_OK) return rc;
+    return quantize_act_impl(x, ldx, M, K, r, q_hi, q_lo, s_hi, s_lo, lo_sum, rot, true, c_hi, c_lo,
+                             stream);
 }
 
 int resq_quantize_act_asym(const void* x, int64_t ldx, int64_t M, int64_t K, int64_t r,

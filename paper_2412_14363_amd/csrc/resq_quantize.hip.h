@@ -358,6 +358,214 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// The fused transform + quantizer for blocks of 256 (the down_proj input of the
+// Llama models: 12544 = 49 * 256 low columns), with the first five butterfly
+// stages on the bf16 matrix cores.  The vector-ALU butterflies of the kernel
+// above cost about 30 instructions per element, which makes that kernel
+// ALU-bound at twice the time its memory traffic takes.
+//
+// H_256 = H_8 (x) H_32: column e = 32 a + c of a block, a = 0..7, c = 0..31.  A
+// wavefront takes a span of 512 low columns (two blocks, 16 rows rho = 8 g + a of
+// 32 columns).  Lane l loads the 8 consecutive columns c = 8 q .. 8 q + 7 of row
+// rho = l % 16, q = l / 16: exactly the B operand of v_mfma_f32_16x16x32_bf16
+// (B[k = c][j = rho]), with A[i = c'][k = c] = H_32[c'][c] / 16 made in registers
+// (+-2^-4 is exact in bf16, the inputs are bf16, the sums accumulate in fp32).  Two
+// instructions (c' = 0..15 and 16..31) leave lane l with D[c' = 16 d + 4 q + v][rho],
+// d = 0, 1, v = 0..3: four consecutive output columns 32 rho + 16 d + 4 q + v per d.
+// The remaining H_8 over a runs across lanes: the row that lane l loads is chosen so
+// that a sits in lane bits 0, 1 and 3 (g in bit 2), whose exchanges (lane ^ 1, ^ 2,
+// ^ 8) are data-parallel-primitive modifiers of the arithmetic instruction itself.
+// A butterfly stage is new = partner + s own, s = -1 in the upper lane of a pair
+// = s (own + s partner): the stage computes own + s partner in ONE multiply-add and
+// leaves the factor s pending; partners of later stages share it, so the pending
+// factors multiply up to one sign per lane, which goes into the quantizer's scale
+// (symmetric codes) or is applied once at the end.
+// The eight values are then rounded to bf16 and go through the same
+// quantizer arithmetic as everywhere else (column parity = v parity, as in a unit
+// of eight consecutive columns), so the codes are exactly those of quantizing
+// the rotated row, which the caller can have written out (x_rot) to check.  The
+// fp32 sums are taken in another order than the stand-alone transform kernel takes
+// them, so a rotated value may round to the neighbouring bf16 there.
+//
+// HI: units of 8 high columns per thread; LO: spans per wavefront.
+// Requires r <= 2048 HI, K - r <= 2048 LO, r and K - r multiples of 256.
+// ---------------------------------------------------------------------------
+// partner + own * 0 form of the exchange whose move the compiler can fold into the
+// consuming multiply-add (no "old" value to preserve: every lane has a partner)
+template <int CTRL>
+__device__ __forceinline__ float dpp_partner(float x) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+typedef __bf16 v8bf_q __attribute__((ext_vector_type(8)));
+typedef float v4f_q __attribute__((ext_vector_type(4)));
+
+template <int HI, int LO, bool ASYM>
+__global__ __launch_bounds__(kQuantThreads) void hadamard256_quantize_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int K, int r, int8_t* __restrict__ q_hi,
+    int64_t ld_hi, uint8_t* __restrict__ q_lo, int64_t ld_lo, float* __restrict__ s_hi,
+    float* __restrict__ s_lo, int32_t* __restrict__ lo_sum, const RotateArgs rot,
+    float* __restrict__ c_hi, float* __restrict__ c_lo) {
+    constexpr int RT = kQuantThreads;
+    __shared__ float red[16];
+    __shared__ int red_sum[4];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int64_t m = blockIdx.x;
+    const int hi_units = r >> 3;
+    const int lo_cols = K - r;
+    const uint16_t* row = x + m * ldx;
+    const int q = lane >> 4;
+    // the lane's row of the span: a = lane bits 0, 1, 3; g = lane bit 2
+    const int rho = (lane & 3) | ((lane & 8) >> 1) | ((lane & 4) << 1);
+    const int cp = lane & 15;   // row c' (and 16 + c') of H_32 that this lane supplies
+    // pending sign of the lane after the three exchange stages
+    const bool neg = (__builtin_popcount(lane & 11) & 1) != 0;
+    const uint32_t flip = neg ? 0x80008000u : 0u;
+    const float m1 = (lane & 1) ? -1.0f : 1.0f, m2 = (lane & 2) ? -1.0f : 1.0f, m8 = (lane & 8) ? -1.0f : 1.0f;
+
+    uint4 vh[HI], vl[LO];
+#pragma unroll
+    for (int i = 0; i < HI; ++i) {
+        const int u = t + i * RT;
+        vh[i] = u < hi_units ? *reinterpret_cast<const uint4*>(row + (int64_t)u * 8) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    // rows c' = rho and 16 + rho of H_32 / 16, columns c = 8 q .. 8 q + 7
+    uint32_t h0[4], h1[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int c = 8 * q + 2 * k + e;
+            const uint32_t s0 = (uint32_t)__builtin_popcount(cp & c) & 1u;
+            const uint32_t s1 = (uint32_t)__builtin_popcount((16 + cp) & c) & 1u;
+            w0 |= (0x3D80u | (s0 << 15)) << (16 * e);
+            w1 |= (0x3D80u | (s1 << 15)) << (16 * e);
+        }
+        h0[k] = w0;
+        h1[k] = w1;
+    }
+    const v8bf_q ha0 = __builtin_bit_cast(v8bf_q, make_uint4(h0[0], h0[1], h0[2], h0[3]));
+    const v8bf_q ha1 = __builtin_bit_cast(v8bf_q, make_uint4(h1[0], h1[1], h1[2], h1[3]));
+    // column of the lane's first output of span s, relative to r: + 16 d + v
+    const int out_col = 32 * rho + 4 * q;
+    // every load of the row is issued before the first product (addresses past the row are
+    // clamped into it and the loaded value replaced by zero)
+#pragma unroll
+    for (int i = 0; i < LO; ++i) {
+        const int col = (wave + 4 * i) * 512 + 32 * rho + 8 * q;
+        vl[i] = *reinterpret_cast<const uint4*>(row + r + (col < lo_cols ? col : lo_cols - 8));
+    }
+#pragma unroll
+    for (int i = 0; i < LO; ++i) {
+        const int s = wave + 4 * i;
+        const int col = s * 512 + 32 * rho + 8 * q;
+        const uint4 raw = col < lo_cols ? vl[i] : make_uint4(0u, 0u, 0u, 0u);
+        const v4f_q zero = {0.0f, 0.0f, 0.0f, 0.0f};
+        const v4f_q d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ha0, __builtin_bit_cast(v8bf_q, raw), zero, 0, 0, 0);
+        const v4f_q d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ha1, __builtin_bit_cast(v8bf_q, raw), zero, 0, 0, 0);
+        float f[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = __builtin_fmaf(dpp_partner<0xB1>(f[e]), m1, f[e]);    // quad_perm [1,0,3,2]
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = __builtin_fmaf(dpp_partner<0x4E>(f[e]), m2, f[e]);    // quad_perm [2,3,0,1]
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = __builtin_fmaf(dpp_partner<0x128>(f[e]), m8, f[e]);   // row_ror:8
+        vl[i] = pack8_bf16(f, 1.0f);   // the rotated values times the pending sign
+        if constexpr (ASYM) vl[i] = make_uint4(vl[i].x ^ flip, vl[i].y ^ flip, vl[i].z ^ flip, vl[i].w ^ flip);
+        const int oc = s * 512 + out_col;
+        if (rot.x_rot && oc < lo_cols) {
+            const uint32_t fx = ASYM ? 0u : flip;
+            uint16_t* dst = rot.x_rot + m * rot.ld_rot + r + oc;
+            *reinterpret_cast<uint2*>(dst) = make_uint2(vl[i].x ^ fx, vl[i].y ^ fx);
+            *reinterpret_cast<uint2*>(dst + 16) = make_uint2(vl[i].z ^ fx, vl[i].w ^ fx);
+        }
+    }
+
+    float sh, sl, zh = 0.0f, zl = 0.0f;
+    if constexpr (ASYM) {
+        const float inf = __builtin_huge_valf();
+        float ext[4] = {-inf, -inf, -inf, -inf};  // max_h, -min_h, max_l, -min_l
+        auto take = [&](const uint4& v, int g) __attribute__((always_inline)) {
+            float f[8];
+            unpack8_bf16(v, f);
+            const float mx = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])),
+                                   fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+            const float mn = fminf(fminf(fminf(f[0], f[1]), fminf(f[2], f[3])),
+                                   fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+            ext[g] = fmaxf(ext[g], mx);
+            ext[g + 1] = fmaxf(ext[g + 1], -mn);
+        };
+#pragma unroll
+        for (int i = 0; i < HI; ++i)
+            if (t + i * RT < hi_units) take(vh[i], 0);
+#pragma unroll
+        for (int i = 0; i < LO; ++i)
+            if ((wave + 4 * i) * 512 + out_col < lo_cols) take(vl[i], 2);
+        block_max4(ext, red);
+        zh = -ext[1];
+        zl = -ext[3];
+        sh = r > 0 ? asym_scale(zh, ext[0], 255) : 1.0f;
+        sl = asym_scale(zl, ext[2], 15);
+        if (t == 0) {
+            if (r > 0) c_hi[m] = zh + 128.0f * sh;
+            c_lo[m] = zl + 8.0f * sl;
+        }
+    } else {
+        float amax_h = 0.0f, amax_l = 0.0f;
+#pragma unroll
+        for (int i = 0; i < HI; ++i) amax_h = fmaxf(amax_h, absmax8(vh[i]));   // zeros past the group
+#pragma unroll
+        for (int i = 0; i < LO; ++i) amax_l = fmaxf(amax_l, absmax8(vl[i]));   // zeros past the row
+        block_max2(amax_h, amax_l, red);
+        sh = group_scale(amax_h, kQmaxHi);
+        sl = group_scale(amax_l, kQmaxLo);
+    }
+    const float inv_h = 1.0f / sh, inv_l = 1.0f / sl;
+    if (t == 0) {
+        if (r > 0) s_hi[m] = sh;
+        s_lo[m] = sl;
+    }
+
+    int8_t* qh = q_hi + m * ld_hi;
+    uint8_t* ql = q_lo + m * ld_lo;
+    float odd_f = 0.0f, unused = 0.0f;
+#pragma unroll
+    for (int i = 0; i < HI; ++i) {
+        const int u = t + i * RT;
+        if (u < hi_units) {
+            uint32_t c[8];
+            if constexpr (ASYM) quant8_asym<false>(vh[i], zh, sh, inv_h, c, unused);
+            else quant8<false>(vh[i], sh, inv_h, c, unused);
+            *reinterpret_cast<uint2*>(qh + (int64_t)u * 8) =
+                make_uint2(pack_low_bytes(c[0], c[1], c[2], c[3]), pack_low_bytes(c[4], c[5], c[6], c[7]));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < LO; ++i) {
+        const int oc = (wave + 4 * i) * 512 + out_col;
+        if (oc < lo_cols) {   // the last span may hold one block only: its upper 8 rows are idle
+            uint32_t c[8];
+            if constexpr (ASYM) quant8_asym<true>(vl[i], zl, sl, inv_l, c, odd_f);
+            else quant8<true>(vl[i], neg ? -sl : sl, neg ? -inv_l : inv_l, c, odd_f);   // x / s = (-x) / (-s)
+            uint32_t by[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) by[k] = (c[2 * k + 1] << 4) | c[2 * k];
+            const uint32_t w = pack_low_bytes(by[0], by[1], by[2], by[3]);
+            uint8_t* dst = ql + (oc >> 1);
+            *reinterpret_cast<uint16_t*>(dst) = (uint16_t)w;          // columns oc .. oc + 3
+            *reinterpret_cast<uint16_t*>(dst + 8) = (uint16_t)(w >> 16);  // columns oc + 16 .. oc + 19
+        }
+    }
+    int odd_sum = (int)odd_f;
+    for (int64_t b = (int64_t)r + 8 * t; b < ld_hi; b += 8 * RT)
+        *reinterpret_cast<uint2*>(qh + b) = make_uint2(0u, 0u);
+    for (int64_t b = (int64_t)lo_cols / 2 + 4 * t; b < ld_lo; b += 4 * RT)
+        *reinterpret_cast<uint32_t*>(ql + b) = 0x08080808u;
+    odd_sum = block_sum(odd_sum, red_sum);
+    if (t == 0) lo_sum[m] = odd_sum;
+}
+
+// ---------------------------------------------------------------------------
 // Activations, short rows (K <= 512, e.g. one attention head of a K/V cache
 // entry, Section 4.3): a group of G = 16, 32 or 64 lanes per row (G * 8 >= K),
 // so 256 / G rows per workgroup, one 8-element unit per lane, reductions inside

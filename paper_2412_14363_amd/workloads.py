@@ -62,6 +62,18 @@ KV_CACHE_QUANT = LayerShape("llama3_8b_kv_cache_quant", M=2048 * 8 * 2, K=128, N
 UC_PROJ = LayerShape("llama3_8b_uc_proj_prefill", M=2048 * (32 + 8), K=128, N=128, r=128, seed=8)
 
 
+def chunk_shape(which: str, M: int) -> LayerShape:
+    """A prefill chunk (or a large generation batch) of M tokens on a Llama-3-8B layer: few
+    128 x 256 output tiles, the regime between the generation stage and a full prefill."""
+    if which == "o_proj":
+        return LayerShape(f"llama3_8b_o_proj_m{M}", M=M, K=4096, N=4096, r=512,
+                          outliers="one_percent_hi", rotate=True)
+    if which == "down":
+        return LayerShape(f"llama3_8b_down_m{M}", M=M, K=14336, N=4096, r=1792,
+                          act="student_t3", hadamard=True)
+    raise ValueError(which)
+
+
 def decode_shape(M: int) -> LayerShape:
     return LayerShape(f"llama3_70b_up_decode_m{M}", M=M, K=8192, N=28672, r=1024,
                       outliers="one_percent_hi")

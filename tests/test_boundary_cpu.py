@@ -126,6 +126,13 @@ def test_asym_entry_points_reject_bad_arguments():
     assert q(P, 256, 4, 256, 32, 64, P, P, P, P, P, P, P, None) == 2       # block does not divide r
     assert q(P, 256, 4, 256, 33, 0, P, P, P, P, P, P, P, None) == 2        # K - r odd
     assert q(P, 256, 4, 256, 32, 0, P, P, P, P, P + 2, P, P, None) == 3
+    h = binding.lib().resq_hadamard_quantize_act_asym
+    ok = (P, 1024, 4, 1024, 256)
+    assert h(*ok, 3, P, P, P, P, P, P, P, None, 0, None) == 2              # block not a power of two
+    assert h(*ok, 256, P, P, P, P, None, P, P, None, 0, None) == 1         # c_hi missing
+    assert h(*ok, 256, P, P, P, P, P, P, P, P, 1000, None) == 2            # ld_rot < K
+    assert h(*ok, 256, P, P, P, P, P, P, P, P + 8, 1024, None) == 3        # x_rot not 16-byte aligned
+    assert h(P + 2, 1024, 4, 1024, 256, 256, P, P, P, P, P, P, P, None, 0, None) == 3   # needs the vector path
     g = binding.lib().resq_gemm_mixed_asym
     assert g(P, P, P, P, None, P, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 1
     assert g(P, P, P, P, P, None, P, 16, P, 256, 256, 32, P, 256, None, None, None) == 1

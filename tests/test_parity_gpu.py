@@ -380,13 +380,19 @@ def test_down_proj_chain_end_to_end(oracle, rq, M, K, N, r):
     (5, 1792 + 12544, 1792, 0),      # the down_proj input: 49 blocks of 256
     (3, 2048, 512, 512), (4, 1024, 256, 64), (3, 4096, 0, 512), (2, 528, 16, 16),
     (130, 4096, 512, 256), (3, 1024, 512, 8),
+    (3, 3584 + 25088, 3584, 256),    # Llama-70B down_proj input: 98 blocks, two high units per thread
+    (4, 1024, 256, 256), (3, 1280, 0, 256), (2, 512 + 4096, 512, 256), (2, 2048 + 4352, 2048, 256),
+    (9, 256, 0, 256), (2, 4096 + 26624, 4096, 256),
 ])
 def test_hadamard_quantize_fused(oracle, rq, M, K, r, block):
     # one kernel: rotate the low group, round to bf16, quantize.  (1) the rotated
-    # values against the oracle's transform (fp32 butterflies vs the fp64
-    # definition); (2) codes, scales and lo_sum bit-exact against the oracle's
-    # quantizer fed the kernel's own rotated row; (3) everything identical to the
-    # two separate kernels.
+    # values against the oracle's transform (fp32 sums vs the fp64 definition);
+    # (2) codes, scales and lo_sum bit-exact against the oracle's quantizer fed the
+    # kernel's own rotated row; (3) everything identical to the separate kernels:
+    # for blocks of 256 the fused kernel takes its sums on the matrix cores, in
+    # another order than the stand-alone transform, so there the rotated rows agree
+    # to the neighbouring bf16 value and the stand-alone quantizer is given the
+    # fused kernel's rotated row.
     s = wl.LayerShape("hq", M=M, K=K, N=1, r=r, act="student_t3", seed=K + r + M)
     x = wl.make_activations(s)
     xd = x.cuda()
@@ -405,9 +411,17 @@ def test_hadamard_quantize_fused(oracle, rq, M, K, r, block):
     rotated[:, r:] = got[:, r:]
     compare_act_codes(oracle, act, rotated, r)
     y = rq.resq_online_hadamard(xd, r, K, block)
+    torch.cuda.synchronize()
+    if b == 256:
+        y64 = wl.bits_to_f64(wl.bf16_bits(y.cpu())[:, r:])
+        assert np.all(np.abs(g64 - y64) <= np.maximum(np.abs(y64), 2.0 ** -8 * scale) * 2.0 ** -7)
+        assert np.mean(g64 == y64) > 0.99
+        y = xd.clone()
+        y[:, r:] = x_rot[:, r:]
+    else:
+        assert torch.equal(y[:, r:], x_rot[:, r:])
     act2 = rq.resq_quantize_act(y, r)
     torch.cuda.synchronize()
-    assert torch.equal(y[:, r:], x_rot[:, r:])
     for name in ("q_hi", "q_lo", "s_hi", "s_lo", "lo_sum"):
         if name in ("q_hi", "s_hi") and r == 0:
             continue
@@ -416,6 +430,8 @@ def test_hadamard_quantize_fused(oracle, rq, M, K, r, block):
     act3 = rq.resq_hadamard_quantize_act(xd, r, block)
     torch.cuda.synchronize()
     assert torch.equal(act3.q_lo, act.q_lo) and torch.equal(act3.s_lo, act.s_lo)
+    if r > 0:
+        assert torch.equal(act3.q_hi, act.q_hi) and torch.equal(act3.s_hi, act.s_hi)
 
 
 # ---- asymmetric activations (the other branch of Eq. 1, the setting of Section 5.1) ----
@@ -525,18 +541,43 @@ def test_layer_asym_tiled_kernel_and_many_slices(oracle, rq, M, K, N, r):
     check_layer_asym(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
-def test_hadamard_then_asym_quantize_fused(oracle, rq):
-    # rotation fused in front of the asymmetric quantizer = the two kernels in sequence
-    s = wl.LayerShape("hqa", M=6, K=2048, N=1, r=512, act="student_t3", seed=11)
+@pytest.mark.parametrize("M,K,r,block", [
+    (6, 2048, 512, 256), (4, 1792 + 12544, 1792, 0), (3, 1280, 0, 256), (3, 3584 + 25088, 3584, 256),
+    (5, 2048, 512, 64), (3, 1024, 0, 512),
+])
+def test_hadamard_then_asym_quantize_fused(oracle, rq, M, K, r, block):
+    # rotation fused in front of the asymmetric quantizer: codes, scales and offsets bit-exact
+    # against the oracle's quantizer fed the kernel's own rotated row, which agrees with the
+    # stand-alone transform (exactly, or to the neighbouring bf16 for blocks of 256: the
+    # matrix-core path), and identical to the stand-alone quantizer on that row
+    s = wl.LayerShape("hqa", M=M, K=K, N=1, r=r, act="student_t3", seed=11 + K)
     x = (wl.make_activations(s).float().abs()).to(torch.bfloat16)
     xd = x.cuda()
-    fused = rq.resq_quantize_act_asym(xd, s.r, hadamard_block=256)
-    y = rq.resq_online_hadamard(xd, s.r, s.K, 256)
-    two = rq.resq_quantize_act_asym(y, s.r)
+    b = block or rq.resq_hadamard_block(K - r)
+    x_rot = torch.zeros_like(xd)
+    fused = rq.resq_hadamard_quantize_act_asym(xd, r, block, x_rot=x_rot)
+    y = rq.resq_online_hadamard(xd, r, K, block)
+    torch.cuda.synchronize()
+    assert not x_rot[:, :r].any()
+    if b == 256:
+        g64 = wl.bits_to_f64(wl.bf16_bits(x_rot.cpu())[:, r:])
+        y64 = wl.bits_to_f64(wl.bf16_bits(y.cpu())[:, r:])
+        scale = np.abs(y64).max()
+        assert np.all(np.abs(g64 - y64) <= np.maximum(np.abs(y64), 2.0 ** -8 * scale) * 2.0 ** -7)
+        assert np.mean(g64 == y64) > 0.99
+    else:
+        assert torch.equal(y[:, r:], x_rot[:, r:])
+    rotated = xd.clone()
+    rotated[:, r:] = x_rot[:, r:]
+    compare_asym_codes(oracle, fused, wl.bf16_bits(rotated.cpu()), r)
+    two = rq.resq_quantize_act_asym(rotated, r)
+    plain = rq.resq_quantize_act_asym(xd, r, hadamard_block=block or -1)   # the entry without the inspection output
     torch.cuda.synchronize()
     for name in ("q_hi", "q_lo", "s_hi", "s_lo", "c_hi", "c_lo", "lo_sum"):
+        if name in ("q_hi", "s_hi", "c_hi") and r == 0:
+            continue
         assert torch.equal(getattr(fused, name), getattr(two, name)), name
-    compare_asym_codes(oracle, fused, wl.bf16_bits(y.cpu()), s.r)
+        assert torch.equal(getattr(fused, name), getattr(plain, name)), name
 
 
 # ---- short rows: per-head quantization of a K/V cache entry (Section 4.3) ----------
