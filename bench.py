@@ -573,6 +573,9 @@ def main() -> None:
     ap.add_argument("--asym", action="store_true",
                     help="asymmetric per-token activations (the paper's experimental setting) "
                          "instead of the symmetric ones the headline metric is defined on")
+    ap.add_argument("--one-call", action="store_true",
+                    help="generation-stage workloads with at most 16 tokens: quantizer and GEMM as ONE "
+                         "kernel (resq_quantize_gemm_mixed) instead of the two calls")
     ap.add_argument("--unfused-hadamard", action="store_true",
                     help="down_proj input: transform and quantize in two kernels instead of one")
     args = ap.parse_args()
@@ -660,9 +663,20 @@ def main() -> None:
                        s.N, s.K, s.r, y.data_ptr(), s.N, None, None, st)
                       for p in packed]
 
+    one_call = args.one_call
+    if one_call and (s.M > 16 or args.asym or s.hadamard):
+        raise SystemExit("--one-call: symmetric codes, at most 16 tokens, no transform")
+    one_args = [(xd.data_ptr(), s.K, s.M, p.data_ptr(), s.N, s.K, s.r, y.data_ptr(), s.N, st) for p in packed]
+
     def step(i: int, events=None):
         # events: three (start, stop) pairs of hipEvent_t, recorded by the library at
         # the start and end of the kernel each call launches
+        if one_call:
+            if events is not None:
+                L.resq_time_next_kernel(*events[2])
+            rc = L.resq_quantize_gemm_mixed(*one_args[i % n_copies])
+            assert rc == 0, rc
+            return
         if s.hadamard and not fused:
             if events is not None:
                 L.resq_time_next_kernel(*events[0])
@@ -712,7 +726,7 @@ def main() -> None:
         step(i, evs[i])
     torch.cuda.synchronize()
     had_ms = sum(elapsed_ms(e[0]) for e in evs) / args.steps if s.hadamard and not fused else 0.0
-    quant_ms = sum(elapsed_ms(e[1]) for e in evs) / args.steps
+    quant_ms = 0.0 if one_call else sum(elapsed_ms(e[1]) for e in evs) / args.steps
     gemm_all = sorted(elapsed_ms(e[2]) for e in evs)
     gemm_ms = sum(gemm_all) / args.steps
     for e in evs:
@@ -735,7 +749,7 @@ def main() -> None:
         achieved = ops / (gemm_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                 "frac": achieved / PEAK_INT8_TOPS, "traffic": traffic}
-    roof["kernel"] = "resq gemm_mixed"
+    roof["kernel"] = "resq quantize_gemm_mixed" if one_call else "resq gemm_mixed"
     roof["kernel_ms"] = gemm_ms        # the mean: what `achieved` is priced with
     roof["kernel_ms_median"] = gemm_all[len(gemm_all) // 2]
     roof["kernel_ms_min"] = gemm_all[0]
@@ -745,7 +759,8 @@ def main() -> None:
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{s.name}: M={s.M} K={s.K} N={s.N} r={s.r}", "tag": args.workload,
-                   "step": ("hadamard_quantize_act (one kernel) + " if fused else
+                   "step": "quantize_gemm_mixed (one kernel)" if one_call else
+                           ("hadamard_quantize_act (one kernel) + " if fused else
                             "online_hadamard + quantize_act + " if s.hadamard else
                             "quantize_act + ") + "gemm_mixed",
                    "activations": "asymmetric per token" if args.asym else "symmetric per token",

@@ -257,6 +257,26 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
                     void* stream);
 
 /*
+ * The layer in ONE call for the generation stage (a handful of tokens, Section 1:
+ * memory-bound): resq_quantize_act (Section 4.1 Eq. 2) and resq_gemm_mixed
+ * (Eq. 4) in one kernel.  Every workgroup of the weight-streaming kernel
+ * quantizes the M token rows itself, straight into the LDS rows that the kernel
+ * reads its activation codes from, while its first weight blocks are on their
+ * way: the codes never go to memory and the launch of the quantizer is saved.
+ * y is bit-identical to the two calls (same quantizer arithmetic, same integer
+ * sums, same epilogue).
+ *   x        bf16 [M, ldx], ldx >= K                          (read)
+ *   M        1..16 tokens whose code rows fit LDS (M * (padded row bytes) <=
+ *            140 KiB; K = 8192 with r = 1024 takes 16), else RESQ_ERR_SHAPE: use
+ *            the two calls
+ *   packed, N, K, r, y, ldy   as in resq_gemm_mixed
+ * Alignment: x 16 bytes and ldx, K, r multiples of 8 (else RESQ_ERR_ALIGN); packed
+ * 256 bytes; y 2 bytes.  Symmetric codes, no gated epilogue, no debug outputs.
+ */
+int resq_quantize_gemm_mixed(const void* x, int64_t ldx, int64_t M, const void* packed, int64_t N,
+                             int64_t K, int64_t r, void* y, int64_t ldy, void* stream);
+
+/*
  * The gate and up projections of an MLP block as ONE layer with the gated
  * activation in its epilogue, so that the down_proj input (which Section 4.3
  * transforms and quantizes next) is written directly instead of two [M, F]

@@ -33,6 +33,7 @@ SYMBOLS = {
     "resq_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p]),
     "resq_hadamard_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _i64, _p]),
     "resq_gemm_mixed_asym": (C.c_int, [_p, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
+    "resq_quantize_gemm_mixed": (C.c_int, [_p, _i64, _i64, _p, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_gemm_mixed_swiglu": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_gram_accumulate": (C.c_int, [_p, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_sym_eig_workspace_bytes": (_sz, [_i64]),
@@ -194,6 +195,22 @@ def resq_quantize_act_asym(x: torch.Tensor, r: int, hadamard_block: int = 0,
     _check(st, "resq_quantize_act_asym")
     out.asym = True
     return out
+
+
+def resq_quantize_gemm_mixed(x: torch.Tensor, packed: torch.Tensor, N: int, r: int,
+                             y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    if y.stride(1) != 1:
+        raise ValueError("y must be row-major")
+    st = lib().resq_quantize_gemm_mixed(
+        _dev(x, torch.bfloat16, "x"), x.stride(0), M, _dev(packed, torch.uint8, "packed"), N, K, r,
+        _dev(y, torch.bfloat16, "y"), y.stride(0), _stream(stream))
+    _check(st, "resq_quantize_gemm_mixed")
+    return y
 
 
 def resq_hadamard_quantize_act_asym(x: torch.Tensor, r: int, block: int = 0,

@@ -257,6 +257,54 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
     return launch_status();
 }
 
+// The weight-streaming kernels for at most 16 tokens whose code rows fit LDS.  fused: the
+// kernels quantize d.x themselves instead of reading codes.
+static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t st) {
+    const WeightLayout& L = d.L;
+    int lds_bytes = d.M * d.lds_row;
+    const int extra = fused ? kFusedScratchFloats * 4 : 0;
+    // Few output channels (at most half of the chip's 2048 wavefronts would have a
+    // group): cut each group's reduction axis into SK runs, one per wavefront, until
+    // more than half have one or a run would get shorter than 4 blocks.
+    const int blocks = (int)(L.hi_blocks + L.lo_blocks);
+    int sk = 1;
+    while (sk < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 4) sk *= 2;
+    const dim3 blk(kDecodeThreads);
+#define RESQ_LAUNCH_DECODE(KERNEL, GRID)                                                           \
+    do {                                                                                           \
+        auto kernel = KERNEL;                                                                      \
+        if (lds_bytes > 64 * 1024 &&                                                               \
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),                             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) \
+            return RESQ_ERR_HIP;                                                                   \
+        launch(kernel, GRID, blk, lds_bytes, st, d);                                               \
+    } while (0)
+    if (sk > 1) {
+        lds_bytes = ((lds_bytes + 15) & ~15) + (kDecodeThreads / 64) * 2 * 64 * 16 + extra;
+        const int sets = (d.groups * sk + 7) / 8;
+        const dim3 grid((unsigned)(sets < 256 ? sets : 256));
+#define RESQ_LAUNCH_SPLITK(SK)                                                                     \
+    do {                                                                                           \
+        if (fused) RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<false, SK, true>), grid);         \
+        else if (dbg) RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<true, SK, false>), grid);      \
+        else RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<false, SK, false>), grid);              \
+    } while (0)
+        if (sk == 2) RESQ_LAUNCH_SPLITK(2);
+        else if (sk == 4) RESQ_LAUNCH_SPLITK(4);
+        else RESQ_LAUNCH_SPLITK(8);
+#undef RESQ_LAUNCH_SPLITK
+        return launch_status();
+    }
+    lds_bytes = ((lds_bytes + 15) & ~15) + extra;
+    // one workgroup per compute unit (256 of them), fewer when there is less work
+    const dim3 grid((unsigned)(d.groups < 256 ? d.groups : 256));
+    if (fused) RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, true>), grid);
+    else if (dbg) RESQ_LAUNCH_DECODE((gemm_decode_kernel<true, false>), grid);
+    else RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, false>), grid);
+#undef RESQ_LAUNCH_DECODE
+    return launch_status();
+}
+
 // shared by resq_gemm_mixed (asym false, c_hi = c_lo = null) and resq_gemm_mixed_asym
 static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
                            const float* s_lo, bool asym, const float* c_hi, const float* c_lo,
@@ -305,41 +353,10 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         d.swiglu = swiglu ? 1 : 0;
         d.groups = (int)((N + 15) / 16);
         d.lds_row = (int)lds_row;
-        int lds_bytes = (int)(M * lds_row);
-        // Few output channels (at most half of the chip's 2048 wavefronts would have a
-        // group): cut each group's reduction axis into SK runs, one per wavefront, until
-        // more than half have one or a run would get shorter than 4 blocks.
-        const int blocks = (int)(L.hi_blocks + L.lo_blocks);
-        int sk = 1;
-        while (sk < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 4) sk *= 2;
-        if (sk > 1) {
-            lds_bytes = ((lds_bytes + 15) & ~15) + (kDecodeThreads / 64) * 2 * 64 * 16;
-            const int sets = (d.groups * sk + 7) / 8;
-            const dim3 grid((unsigned)(sets < 256 ? sets : 256)), blk(kDecodeThreads);
-#define RESQ_LAUNCH_SPLITK(SK)                                                                     \
-    do {                                                                                           \
-        auto kernel = dbg ? gemm_decode_splitk_kernel<true, SK> : gemm_decode_splitk_kernel<false, SK>; \
-        if (lds_bytes > 64 * 1024 &&                                                               \
-            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),                             \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) \
-            return RESQ_ERR_HIP;                                                                   \
-        launch(kernel, grid, blk, lds_bytes, st, d);                                               \
-    } while (0)
-            if (sk == 2) RESQ_LAUNCH_SPLITK(2);
-            else if (sk == 4) RESQ_LAUNCH_SPLITK(4);
-            else RESQ_LAUNCH_SPLITK(8);
-#undef RESQ_LAUNCH_SPLITK
-            return launch_status();
-        }
-        auto kernel = dbg ? gemm_decode_kernel<true> : gemm_decode_kernel<false>;
-        if (lds_bytes > 64 * 1024 &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
-            return RESQ_ERR_HIP;
-        // one workgroup per compute unit (256 of them), fewer when there is less work
-        const int wgs = d.groups < 256 ? d.groups : 256;
-        launch(kernel, dim3((unsigned)wgs), dim3(kDecodeThreads), lds_bytes, st, d);
-        return launch_status();
+        d.x = nullptr;
+        d.ldx = 0;
+        d.fuse_rows = 1;
+        return launch_decode(d, dbg, false, st);
     }
 
     // a few tens of tokens: the same single pass over the weights, activation codes
@@ -390,6 +407,9 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         d.swiglu = swiglu ? 1 : 0;
         d.groups = (int)((N + 15) / 16);
         d.lds_row = 0;
+        d.x = nullptr;
+        d.ldx = 0;
+        d.fuse_rows = 1;
         // token groups by M; runs per group as for the decode kernel, at most 8 / TG of
         // them (LDS holds the chunks of every run) and at least two chunks long
         const int blocks = (int)(L.hi_blocks + L.lo_blocks);
@@ -465,6 +485,47 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi, 
                     void* stream) {
     return gemm_mixed_impl(q_hi, q_lo, s_hi, s_lo, false, nullptr, nullptr, lo_sum, M, packed, N, K,
                            r, y, ldy, dbg_acc_hi, dbg_acc_lo, stream);
+}
+
+int resq_quantize_gemm_mixed(const void* x, int64_t ldx, int64_t M, const void* packed, int64_t N,
+                             int64_t K, int64_t r, void* y, int64_t ldy, void* stream) {
+    if (!shape_ok(N, K, r) || M < 1 || ldx < K || ldy < N) return RESQ_ERR_SHAPE;
+    if (K - r > kMaxLoWidth || r > kMaxHiWidth) return RESQ_ERR_SHAPE;
+    if (!x || !packed || !y) return RESQ_ERR_NULL;
+    if (!aligned(x, 16) || ldx % 8 != 0 || K % 8 != 0 || r % 8 != 0 || !aligned(packed, 256) || !aligned(y, 2))
+        return RESQ_ERR_ALIGN;
+    const WeightLayout L = make_weight_layout(N, K, r);
+    const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
+    if (M > kDecodeMaxM || M * lds_row > 140 * 1024) return RESQ_ERR_SHAPE;
+    DecodeArgs d;
+    d.q_hi = nullptr;
+    d.q_lo = nullptr;
+    d.ld_hi = L.kh_pad;
+    d.ld_lo = L.kl_pad / 2;
+    d.s_hi = nullptr;
+    d.s_lo = nullptr;
+    d.lo_sum = nullptr;
+    d.c_hi = nullptr;
+    d.c_lo = nullptr;
+    d.packed = static_cast<const uint8_t*>(packed);
+    d.L = L;
+    d.M = (int)M;
+    d.y = static_cast<uint16_t*>(y);
+    d.ldy = ldy;
+    d.dbg_hi = nullptr;
+    d.dbg_lo = nullptr;
+    d.swiglu = 0;
+    d.groups = (int)((N + 15) / 16);
+    d.lds_row = (int)lds_row;
+    d.x = static_cast<const uint16_t*>(x);
+    d.ldx = ldx;
+    // rows quantized at a time, each by 512 / R threads holding at most kFusedUnits 16-byte units
+    const int64_t nunits = K / 8;
+    if (nunits > (int64_t)kFusedUnits * kDecodeThreads) return RESQ_ERR_SHAPE;
+    int R = 1;
+    while (R < 8 && R < M && nunits * (2 * R) <= (int64_t)kFusedUnits * kDecodeThreads) R *= 2;
+    d.fuse_rows = R;
+    return launch_decode(d, false, true, static_cast<hipStream_t>(stream));
 }
 
 int resq_gemm_mixed_swiglu(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,

@@ -19,6 +19,7 @@
 
 #include "resq_gemm.hip.h"
 #include "resq_layout.h"
+#include "resq_quantize.hip.h"
 
 namespace resq {
 
@@ -46,7 +47,14 @@ struct DecodeArgs {
     int swiglu;       // 1: channels 2c, 2c+1 = gate and up row of feature c; y[m, c] = silu(gate) * up
     int groups;       // ceil(N / 16)
     int lds_row;      // bytes of one token row in LDS
+    // quantizer fused in front (kernels built with FUSED): the bf16 activations, [M][ldx];
+    // q_hi .. lo_sum above are not read then
+    const uint16_t* x;
+    int64_t ldx;
+    int fuse_rows;    // rows quantized at a time: 1, 2, 4 or 8
 };
+
+constexpr int kFusedScratchFloats = 3 * 16 + 8 * 3;  // LDS beside the token rows, see fill_act_quantize
 
 // Epilogue of the weight-streaming kernels for one lane: token `tok`, channels
 // n .. n + 3, the two integer sums of each.  Dequantizes (Eq. 4), adds the
@@ -113,27 +121,10 @@ __device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, in
     }
 }
 
-template <bool DBG>
-__global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const DecodeArgs a) {
-    extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // [M][lds_row]
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
+// activation codes of every token -> LDS (row = high codes, then packed low codes);
+// 16-byte unit u of token m, up to twelve loads in flight per thread
+__device__ __forceinline__ void fill_act_codes(const DecodeArgs& a, uint8_t* act, int t) {
     const int hi_units = (int)(a.L.kh_pad / 16), row_units = hi_units + (int)(a.L.kl_pad / 32);
-    const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
-
-    // start the weight stream of this wave's first group before anything else
-    int group = wave * gridDim.x + blockIdx.x;
-    uint4 ring[kDecodeDepth];
-    {
-        const uint4* wp = reinterpret_cast<const uint4*>(
-            a.packed + (int64_t)(group < a.groups ? group : 0) * a.L.group_bytes + lane_off);
-#pragma unroll
-        for (int i = 0; i < kDecodeDepth; ++i)
-            if (group < a.groups && i < blocks) ring[i] = wp[i * (kBlockBytes / 16)];
-    }
-
-    // activation codes of every token -> LDS (row = high codes, then packed low codes);
-    // 16-byte unit u of token m, up to twelve loads in flight per thread
     constexpr int FILL = 12;
     const int units = a.M * row_units;
     for (int u0 = t; u0 < units; u0 += FILL * kDecodeThreads) {
@@ -159,6 +150,144 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
         }
     }
     __syncthreads();
+}
+
+// The per-token quantizer (Section 4.1 Eq. 2, symmetric) run by the workgroup itself on
+// the M bf16 rows of a.x, codes straight into the LDS rows: with a handful of tokens
+// every workgroup can afford to redo it, which saves a kernel launch in front of the
+// weight stream.  The arithmetic is the quantizer kernel's (absmax8, group_scale,
+// quant8), so the codes, scales and sums are the ones resq_quantize_act would have
+// written.  R = a.fuse_rows (1, 2, 4 or 8) rows are in flight at a time, each with a team
+// of 512 / R threads that holds the whole row in registers (at most kFusedUnits 16-byte
+// loads per thread, all issued before the first is used: one memory latency per batch
+// of rows, not per row), reduces its maxima through LDS and quantizes from registers.
+// scal: [3][16] floats = s_hi, s_lo, lo_sum (as int) per token, then reduction scratch.
+// Requires K, r, ldx multiples of 8, 16-byte aligned rows, K / 8 <= kFusedUnits * 512 / R.
+constexpr int kFusedUnits = 16;
+__device__ __forceinline__ void fill_act_quantize(const DecodeArgs& a, uint8_t* act, float* scal, int t) {
+    constexpr int kWaves = kDecodeThreads / 64;
+    const int lane = t & 63, wave = t >> 6;
+    const int K = (int)a.L.K, r = (int)a.L.r;
+    const int nunits = K >> 3, hi_units = r >> 3;
+    const int R = a.fuse_rows, T = kDecodeThreads / R, WT = T / 64;
+    const int team = t / T, tt = t - team * T;
+    float* red = scal + 3 * 16;                                      // [8 waves][2]
+    int* red_sum = reinterpret_cast<int*>(scal + 3 * 16 + kWaves * 2);  // [8 waves]
+    for (int m0 = 0; m0 < a.M; m0 += R) {   // the same trip count for every thread
+        const int m = m0 + team;
+        const bool live = m < a.M;
+        const uint4* row = reinterpret_cast<const uint4*>(a.x + (int64_t)(live ? m : a.M - 1) * a.ldx);
+        uint4 v[kFusedUnits];
+#pragma unroll
+        for (int i = 0; i < kFusedUnits; ++i) {
+            const int u = tt + i * T;
+            v[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (i * T >= nunits) continue;   // the same for every thread
+            if (u < nunits) v[i] = row[u];
+        }
+        float ah = 0.0f, al = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kFusedUnits; ++i) {
+            if (i * T >= nunits) break;
+            const int u = tt + i * T;
+            const float x = absmax8(v[i]);   // zero past the row
+            if (u < hi_units) ah = fmaxf(ah, x);
+            else al = fmaxf(al, x);
+        }
+        ah = wave_max(ah);
+        al = wave_max(al);
+        if (lane == 0) {
+            red[wave * 2] = ah;
+            red[wave * 2 + 1] = al;
+        }
+        __syncthreads();
+        ah = 0.0f;
+        al = 0.0f;
+        for (int w = 0; w < WT; ++w) {
+            ah = fmaxf(ah, red[(team * WT + w) * 2]);
+            al = fmaxf(al, red[(team * WT + w) * 2 + 1]);
+        }
+        const float sh = group_scale(ah, kQmaxHi), sl = group_scale(al, kQmaxLo);
+        const float inv_h = 1.0f / sh, inv_l = 1.0f / sl;
+        if (tt == 0 && live) {
+            scal[m] = sh;
+            scal[16 + m] = sl;
+        }
+        uint8_t* arow = act + (live ? m : 0) * a.lds_row;
+        uint8_t* alow = arow + a.L.kh_pad;
+        float odd_f = 0.0f, unused = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kFusedUnits; ++i) {
+            if (i * T >= nunits) break;
+            const int u = tt + i * T;
+            if (u < nunits && live) {
+                uint32_t c[8];
+                if (u < hi_units) {
+                    quant8<false>(v[i], sh, inv_h, c, unused);
+                    *reinterpret_cast<uint2*>(arow + u * 8) =
+                        make_uint2(pack_low_bytes(c[0], c[1], c[2], c[3]), pack_low_bytes(c[4], c[5], c[6], c[7]));
+                } else {
+                    quant8<true>(v[i], sl, inv_l, c, odd_f);
+                    uint32_t by[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) by[k] = (c[2 * k + 1] << 4) | c[2 * k];
+                    *reinterpret_cast<uint32_t*>(alow + (u - hi_units) * 4) = pack_low_bytes(by[0], by[1], by[2], by[3]);
+                }
+            }
+        }
+        if (live) {   // zero codes in the padding of both parts of the row
+            for (int b = r + 8 * tt; b < (int)a.L.kh_pad; b += 8 * T)
+                *reinterpret_cast<uint2*>(arow + b) = make_uint2(0u, 0u);
+            for (int b = (K - r) / 2 + 4 * tt; b < (int)(a.L.kl_pad / 2); b += 4 * T)
+                *reinterpret_cast<uint32_t*>(alow + b) = 0x08080808u;
+        }
+        const int odd = wave_sum((int)odd_f);
+        if (lane == 0) red_sum[wave] = odd;
+        __syncthreads();
+        if (tt == 0 && live) {
+            int sum = 0;
+            for (int w = 0; w < WT; ++w) sum += red_sum[team * WT + w];
+            reinterpret_cast<int*>(scal)[32 + m] = sum;
+        }
+    }
+    __syncthreads();
+}
+
+// the arguments as the epilogue reads them: with the fused quantizer the per-token
+// constants sit in LDS
+template <bool FUSED>
+__device__ __forceinline__ DecodeArgs epilogue_args(const DecodeArgs& a, const float* scal) {
+    DecodeArgs e = a;
+    if constexpr (FUSED) {
+        e.s_hi = scal;
+        e.s_lo = scal + 16;
+        e.lo_sum = reinterpret_cast<const int32_t*>(scal + 32);
+    }
+    return e;
+}
+
+template <bool DBG, bool FUSED>
+__global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const DecodeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // [M][lds_row]
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
+    const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
+
+    // start the weight stream of this wave's first group before anything else
+    int group = wave * gridDim.x + blockIdx.x;
+    uint4 ring[kDecodeDepth];
+    {
+        const uint4* wp = reinterpret_cast<const uint4*>(
+            a.packed + (int64_t)(group < a.groups ? group : 0) * a.L.group_bytes + lane_off);
+#pragma unroll
+        for (int i = 0; i < kDecodeDepth; ++i)
+            if (group < a.groups && i < blocks) ring[i] = wp[i * (kBlockBytes / 16)];
+    }
+
+    float* scal = reinterpret_cast<float*>(act + ((a.M * a.lds_row + 15) & ~15));
+    if constexpr (FUSED) fill_act_quantize(a, act, scal, t);
+    else fill_act_codes(a, act, t);
+    const DecodeArgs ea = epilogue_args<FUSED>(a, scal);
 
     // lane l supplies token l % 16 (zero operand past M), piece l / 16 of each 64-byte chunk
     const int tok = lane & 15;
@@ -201,7 +330,7 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
 
         // lane l now holds token l % 16, channels 16 group + 4 (l / 16) + {0..3}
         if (!tok_live) continue;
-        stream_epilogue<DBG>(a, tok, (int64_t)group * 16 + (lane >> 4) * 4, acc_hi, acc_lo);
+        stream_epilogue<DBG>(ea, tok, (int64_t)group * 16 + (lane >> 4) * 4, acc_hi, acc_lo);
     }
 }
 
@@ -214,7 +343,7 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
 // a time ("a set"); sets are dealt round-robin over workgroups.  Exact: integer
 // addition in any order.
 // ---------------------------------------------------------------------------
-template <bool DBG, int SK>
+template <bool DBG, int SK, bool FUSED>
 __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(const DecodeArgs a) {
     static_assert(SK == 2 || SK == 4 || SK == 8, "runs per group");
     constexpr int kWaves = kDecodeThreads / 64;
@@ -225,7 +354,6 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
     const int gsel = wave / SK, part = wave % SK;
     const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
     const int b_begin = (int)((int64_t)blocks * part / SK), b_end = (int)((int64_t)blocks * (part + 1) / SK);
-    const int hi_units = (int)(a.L.kh_pad / 16), row_units = hi_units + (int)(a.L.kl_pad / 32);
     const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
     v4i* partial = reinterpret_cast<v4i*>(act + ((a.M * a.lds_row + 15) & ~15));  // [kWaves][2][64]
     const int sets = (a.groups + G - 1) / G;
@@ -243,32 +371,10 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
             if (live && b_begin + i < b_end) ring[i] = wp[(b_begin + i) * (kBlockBytes / 16)];
     }
 
-    // activation codes of every token -> LDS, as in the kernel above
-    constexpr int FILL = 12;
-    const int units = a.M * row_units;
-    for (int u0 = t; u0 < units; u0 += FILL * kDecodeThreads) {
-        uint4 v[FILL];
-#pragma unroll
-        for (int q = 0; q < FILL; ++q) {
-            const int u = u0 + q * kDecodeThreads;
-            v[q] = make_uint4(0u, 0u, 0u, 0u);
-            if (u < units) {
-                const int m = u / row_units, c = u - m * row_units;
-                v[q] = c < hi_units
-                           ? *reinterpret_cast<const uint4*>(a.q_hi + m * a.ld_hi + c * 16)
-                           : *reinterpret_cast<const uint4*>(a.q_lo + m * a.ld_lo + (c - hi_units) * 16);
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < FILL; ++q) {
-            const int u = u0 + q * kDecodeThreads;
-            if (u < units) {
-                const int m = u / row_units, c = u - m * row_units;
-                *reinterpret_cast<uint4*>(act + m * a.lds_row + c * 16) = v[q];
-            }
-        }
-    }
-    __syncthreads();
+    float* scal = reinterpret_cast<float*>(partial + kWaves * 2 * 64);
+    if constexpr (FUSED) fill_act_quantize(a, act, scal, t);
+    else fill_act_codes(a, act, t);
+    const DecodeArgs ea = epilogue_args<FUSED>(a, scal);
 
     const int tok = lane & 15;
     const bool tok_live = tok < a.M;
@@ -327,7 +433,7 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
                 acc_lo += partial[((wave + k) * 2 + 1) * 64 + lane];
             }
             // lane l now holds token l % 16, channels 16 group + 4 (l / 16) + {0..3}
-            if (tok_live) stream_epilogue<DBG>(a, tok, (int64_t)group * 16 + (lane >> 4) * 4, acc_hi, acc_lo);
+            if (tok_live) stream_epilogue<DBG>(ea, tok, (int64_t)group * 16 + (lane >> 4) * 4, acc_hi, acc_lo);
         }
         __syncthreads();  // the partial sums are read before the next set overwrites them
     }

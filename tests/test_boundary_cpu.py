@@ -197,3 +197,20 @@ def test_binding_fails_loudly_without_device_tensors():
     x = torch.zeros(4, 256, dtype=torch.bfloat16)
     with pytest.raises((ValueError, RuntimeError)):
         binding.resq_quantize_act(x, 32)
+
+
+def test_quantize_gemm_mixed_rejects_bad_arguments():
+    f = binding.lib().resq_quantize_gemm_mixed
+    P256 = P - P % 256 + 256
+    assert f(P, 512, 17, P256, 256, 512, 64, P, 256, None) == 2       # more than 16 tokens
+    assert f(P, 512, 0, P256, 256, 512, 64, P, 256, None) == 2        # no token
+    assert f(P, 500, 4, P256, 256, 512, 64, P, 256, None) == 2        # ldx < K
+    assert f(P, 512, 4, P256, 256, 512, 64, P, 200, None) == 2        # ldy < N
+    assert f(P, 65536, 16, P256, 256, 65536, 8192, P, 256, None) == 2  # 16 rows of that length do not fit LDS
+    assert f(None, 512, 4, P256, 256, 512, 64, P, 256, None) == 1
+    assert f(P, 512, 4, None, 256, 512, 64, P, 256, None) == 1
+    assert f(P, 512, 4, P256, 256, 512, 64, None, 256, None) == 1
+    assert f(P + 2, 512, 4, P256, 256, 512, 64, P, 256, None) == 3    # x not 16-byte aligned
+    assert f(P, 516, 4, P256, 256, 512, 64, P, 256, None) == 3        # ldx not a multiple of 8
+    assert f(P, 512, 4, P256, 256, 508, 64, P, 256, None) == 3        # K not a multiple of 8
+    assert f(P, 512, 4, P256 + 16, 256, 512, 64, P, 256, None) == 3   # packed not 256-byte aligned

@@ -242,6 +242,46 @@ def test_layer_sliced_streaming_up_to_1024_tokens(oracle, rq, M, K, N, r):
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
+@pytest.mark.parametrize("M,K,N,r", [
+    (1, 8192, 4096, 1024), (4, 8192, 4096, 1024), (16, 8192, 4112, 1024),   # one run per group
+    (1, 4096, 512, 512), (3, 4096, 272, 512), (16, 14336, 272, 1792),       # split reduction axis
+    (2, 256, 256, 0), (5, 256, 64, 256), (7, 1000, 515, 104), (16, 1000, 40, 104),
+    (9, 2048, 1024, 256),
+])
+def test_quantize_gemm_mixed_one_call(oracle, rq, M, K, N, r):
+    # the quantizer inside the weight-streaming kernel: bit-identical to the two calls, and
+    # against the oracle like every other layer test
+    x, w = wl.random_small_case(M * 23 + K, M, K, N, r, outliers="first4")
+    xd = x.cuda()
+    packed = rq.resq_pack_weights(w.cuda(), r)
+    ybuf = torch.zeros((M, N + 8), dtype=torch.bfloat16, device="cuda")
+    y = rq.resq_quantize_gemm_mixed(xd, packed, N, r, y=ybuf[:, :N])
+    two = rq.resq_gemm_mixed(rq.resq_quantize_act(xd, r), packed, N)
+    torch.cuda.synchronize()
+    assert torch.equal(y, two)
+    assert not ybuf[:, N:].any(), "wrote past N"
+    ref = oracle.linear(wl.bf16_bits(x), wl.bf16_bits(w), r)
+    assert y_within_tolerance(y, ref.y) <= REL_TOL
+    # strided rows of x
+    xs = torch.zeros((M, K + 24), dtype=torch.bfloat16, device="cuda")
+    xs[:, :K] = xd
+    y2 = rq.resq_quantize_gemm_mixed(xs[:, :K], packed, N, r)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, two)
+
+
+def test_quantize_gemm_mixed_one_call_full_size(oracle, rq):
+    s = wl.decode_shape(4)
+    x, w = wl.make_activations(s), wl.make_weights(s)
+    packed = rq.resq_pack_weights(w.cuda(), s.r)
+    y = rq.resq_quantize_gemm_mixed(x.cuda(), packed, s.N, s.r)
+    two = rq.resq_gemm_mixed(rq.resq_quantize_act(x.cuda(), s.r), packed, s.N)
+    torch.cuda.synchronize()
+    assert torch.equal(y, two)
+    ref = oracle.linear(wl.bf16_bits(x), wl.bf16_bits(w), s.r)
+    assert y_within_tolerance(y, ref.y) <= REL_TOL
+
+
 def test_layer_batched_decode_full_size(oracle, rq):
     # the decode workload's layer with 64 tokens in flight; every accumulator and output
     s = wl.decode_shape(64)
