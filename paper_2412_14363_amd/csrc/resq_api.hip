@@ -257,6 +257,39 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
     return launch_status();
 }
 
+// arguments of the weight-streaming kernels; the code pointers are null when the kernel
+// quantizes x itself
+static DecodeArgs make_decode_args(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
+                                   const float* s_lo, const float* c_hi, const float* c_lo,
+                                   const int32_t* lo_sum, int64_t M, const void* packed,
+                                   const WeightLayout& L, void* y, int64_t ldy, int32_t* dbg_acc_hi,
+                                   int32_t* dbg_acc_lo, bool swiglu, int64_t lds_row) {
+    DecodeArgs d;
+    d.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
+    d.q_lo = q_lo;
+    d.ld_hi = L.kh_pad;
+    d.ld_lo = L.kl_pad / 2;
+    d.s_hi = s_hi;
+    d.s_lo = s_lo;
+    d.lo_sum = lo_sum;
+    d.c_hi = c_hi;
+    d.c_lo = c_lo;
+    d.packed = static_cast<const uint8_t*>(packed);
+    d.L = L;
+    d.M = (int)M;
+    d.y = static_cast<uint16_t*>(y);
+    d.ldy = ldy;
+    d.dbg_hi = dbg_acc_hi;
+    d.dbg_lo = dbg_acc_lo;
+    d.swiglu = swiglu ? 1 : 0;
+    d.groups = (int)((L.N + 15) / 16);
+    d.lds_row = (int)lds_row;
+    d.x = nullptr;
+    d.ldx = 0;
+    d.fuse_rows = 1;
+    return d;
+}
+
 // The weight-streaming kernels for at most 16 tokens whose code rows fit LDS.  fused: the
 // kernels quantize d.x themselves instead of reading codes.
 static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t st) {
@@ -333,29 +366,8 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
     // few tokens: stream the weights once (HBM-bound kernel), activations in LDS
     const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
     if (M <= kDecodeMaxM && M * lds_row <= 140 * 1024) {
-        DecodeArgs d;
-        d.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
-        d.q_lo = q_lo;
-        d.ld_hi = L.kh_pad;
-        d.ld_lo = L.kl_pad / 2;
-        d.s_hi = s_hi;
-        d.s_lo = s_lo;
-        d.lo_sum = lo_sum;
-        d.c_hi = c_hi;
-        d.c_lo = c_lo;
-        d.packed = static_cast<const uint8_t*>(packed);
-        d.L = L;
-        d.M = (int)M;
-        d.y = static_cast<uint16_t*>(y);
-        d.ldy = ldy;
-        d.dbg_hi = dbg_acc_hi;
-        d.dbg_lo = dbg_acc_lo;
-        d.swiglu = swiglu ? 1 : 0;
-        d.groups = (int)((N + 15) / 16);
-        d.lds_row = (int)lds_row;
-        d.x = nullptr;
-        d.ldx = 0;
-        d.fuse_rows = 1;
+        const DecodeArgs d = make_decode_args(q_hi, q_lo, s_hi, s_lo, c_hi, c_lo, lo_sum, M, packed, L, y, ldy,
+                                              dbg_acc_hi, dbg_acc_lo, swiglu, lds_row);
         return launch_decode(d, dbg, false, st);
     }
 
@@ -387,29 +399,8 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         streaming = stream_us < 0.9 * tiled_us;
     }
     if (streaming) {
-        DecodeArgs d;
-        d.q_hi = reinterpret_cast<const uint8_t*>(q_hi);
-        d.q_lo = q_lo;
-        d.ld_hi = L.kh_pad;
-        d.ld_lo = L.kl_pad / 2;
-        d.s_hi = s_hi;
-        d.s_lo = s_lo;
-        d.lo_sum = lo_sum;
-        d.c_hi = c_hi;
-        d.c_lo = c_lo;
-        d.packed = static_cast<const uint8_t*>(packed);
-        d.L = L;
-        d.M = (int)M;
-        d.y = static_cast<uint16_t*>(y);
-        d.ldy = ldy;
-        d.dbg_hi = dbg_acc_hi;
-        d.dbg_lo = dbg_acc_lo;
-        d.swiglu = swiglu ? 1 : 0;
-        d.groups = (int)((N + 15) / 16);
-        d.lds_row = 0;
-        d.x = nullptr;
-        d.ldx = 0;
-        d.fuse_rows = 1;
+        const DecodeArgs d = make_decode_args(q_hi, q_lo, s_hi, s_lo, c_hi, c_lo, lo_sum, M, packed, L, y, ldy,
+                                              dbg_acc_hi, dbg_acc_lo, swiglu, 0);
         // token groups by M; runs per group as for the decode kernel, at most 8 / TG of
         // them (LDS holds the chunks of every run) and at least two chunks long
         const int blocks = (int)(L.hi_blocks + L.lo_blocks);
@@ -497,26 +488,8 @@ int resq_quantize_gemm_mixed(const void* x, int64_t ldx, int64_t M, const void* 
     const WeightLayout L = make_weight_layout(N, K, r);
     const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
     if (M > kDecodeMaxM || M * lds_row > 140 * 1024) return RESQ_ERR_SHAPE;
-    DecodeArgs d;
-    d.q_hi = nullptr;
-    d.q_lo = nullptr;
-    d.ld_hi = L.kh_pad;
-    d.ld_lo = L.kl_pad / 2;
-    d.s_hi = nullptr;
-    d.s_lo = nullptr;
-    d.lo_sum = nullptr;
-    d.c_hi = nullptr;
-    d.c_lo = nullptr;
-    d.packed = static_cast<const uint8_t*>(packed);
-    d.L = L;
-    d.M = (int)M;
-    d.y = static_cast<uint16_t*>(y);
-    d.ldy = ldy;
-    d.dbg_hi = nullptr;
-    d.dbg_lo = nullptr;
-    d.swiglu = 0;
-    d.groups = (int)((N + 15) / 16);
-    d.lds_row = (int)lds_row;
+    DecodeArgs d = make_decode_args(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, M, packed, L, y,
+                                    ldy, nullptr, nullptr, false, lds_row);
     d.x = static_cast<const uint16_t*>(x);
     d.ldx = ldx;
     // rows quantized at a time, each by 512 / R threads holding at most kFusedUnits 16-byte units
