@@ -36,7 +36,15 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E peak, GB/s
 # (x2.000 and x1.000; the summaries are under profiles/).  Absent = not measured.
 MEASURED_TRAFFIC = {
     "oproj_prefill": 38.42e6 + 16.78e6,
+    "gate_up_prefill": 265.88e6 + 117.44e6,
+    "down_prefill": 265.08e6 + 33.55e6,
+    "qwen_r1024": 2194.69e6 + 484.44e6,
+    "oproj_m512": 19.27e6 + 4.19e6,
+    "down_m512": 66.45e6 + 4.19e6,
     "decode_m16": 133.61e6 + 0.92e6,
+    "decode_m64": 134.98e6 + 3.67e6,
+    "kv_quant": 8.47e6 + 9.04e6,
+    "uc_proj": 21.35e6 + 20.97e6,
 }
 
 
@@ -181,7 +189,7 @@ def quant_only_bench(args, s) -> None:
         "quantize_ms": kernel_ms,
         "roofline": {"bound": "hbm", "achieved": abytes / (kernel_ms * 1e-3) / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get(args.workload),
                      "kernel": "resq quantize_act (short rows)", "kernel_ms": kernel_ms},
     }
     if not args.no_cpu_baseline:
@@ -255,7 +263,7 @@ def head_proj_bench(args, s) -> None:
         "tops": 2.0 * s.M * s.N * s.K / (ms_per_step * 1e-3) / 1e12,
         "roofline": {"bound": "hbm", "achieved": abytes / (kernel_ms * 1e-3) / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get(args.workload),
                      "kernel": "resq project_heads", "kernel_ms": kernel_ms},
         "snr_db": output_snr_db(x, u, y),
     }
