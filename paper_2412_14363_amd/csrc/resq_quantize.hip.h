@@ -376,7 +376,8 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 // that a sits in lane bits 0, 1 and 3 (g in bit 2), whose exchanges (lane ^ 1, ^ 2,
 // ^ 8) are data-parallel-primitive modifiers of the arithmetic instruction itself.
 // A butterfly stage is new = partner + s own, s = -1 in the upper lane of a pair
-// = s (own + s partner): the stage computes own + s partner in ONE multiply-add and
+// = s (own + s partner): the stage computes own + s partner in ONE multiply-add
+// (v_fmac_f32 with the exchange as its DPP modifier, written as inline assembly) and
 // leaves the factor s pending; partners of later stages share it, so the pending
 // factors multiply up to one sign per lane, which goes into the quantizer's scale
 // (symmetric codes) or is applied once at the end.
@@ -390,12 +391,6 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_vec_kernel(
 // HI: units of 8 high columns per thread; LO: spans per wavefront.
 // Requires r <= 2048 HI, K - r <= 2048 LO, r and K - r multiples of 256.
 // ---------------------------------------------------------------------------
-// partner + own * 0 form of the exchange whose move the compiler can fold into the
-// consuming multiply-add (no "old" value to preserve: every lane has a partner)
-template <int CTRL>
-__device__ __forceinline__ float dpp_partner(float x) {
-    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), CTRL, 0xF, 0xF, true));
-}
 typedef __bf16 v8bf_q __attribute__((ext_vector_type(8)));
 typedef float v4f_q __attribute__((ext_vector_type(4)));
 
@@ -464,12 +459,26 @@ __global__ __launch_bounds__(kQuantThreads) void hadamard256_quantize_kernel(
         const v4f_q d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ha0, __builtin_bit_cast(v8bf_q, raw), zero, 0, 0, 0);
         const v4f_q d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ha1, __builtin_bit_cast(v8bf_q, raw), zero, 0, 0, 0);
         float f[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = __builtin_fmaf(dpp_partner<0xB1>(f[e]), m1, f[e]);    // quad_perm [1,0,3,2]
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = __builtin_fmaf(dpp_partner<0x4E>(f[e]), m2, f[e]);    // quad_perm [2,3,0,1]
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = __builtin_fmaf(dpp_partner<0x128>(f[e]), m8, f[e]);   // row_ror:8
+        // own + s * partner for all eight values, the exchange as a modifier of the
+        // multiply-add (the compiler keeps a separate move in front of it).  The wait states in
+        // front cover a write of these registers or of the execution mask just before.
+#define RESQ_H8_STAGE(CTRL, MUL)                                                                         \
+        asm volatile("s_nop 4\n\t"                                                                        \
+                     "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                   \
+                     "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                   \
+                     "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                   \
+                     "v_fmac_f32_dpp %3, %3, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                   \
+                     "v_fmac_f32_dpp %4, %4, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                   \
+                     "v_fmac_f32_dpp %5, %5, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                   \
+                     "v_fmac_f32_dpp %6, %6, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                   \
+                     "v_fmac_f32_dpp %7, %7, %8 " CTRL " row_mask:0xf bank_mask:0xf"                        \
+                     : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]),  \
+                       "+v"(f[7])                                                                        \
+                     : "v"(MUL))
+        RESQ_H8_STAGE("quad_perm:[1,0,3,2]", m1);
+        RESQ_H8_STAGE("quad_perm:[2,3,0,1]", m2);
+        RESQ_H8_STAGE("row_ror:8", m8);
+#undef RESQ_H8_STAGE
         vl[i] = pack8_bf16(f, 1.0f);   // the rotated values times the pending sign
         if constexpr (ASYM) vl[i] = make_uint4(vl[i].x ^ flip, vl[i].y ^ flip, vl[i].z ^ flip, vl[i].w ^ flip);
         const int oc = s * 512 + out_col;
