@@ -146,7 +146,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_finish_kernel(EigPlan e, floa
     count[threadIdx.x] = c;
     __syncthreads();
     for (int w = kEigThreads / 2; w > 0; w >>= 1) {
-        if (threadIdx.x < w) count[threadIdx.x] += count[threadIdx.x + w];
+        if ((int)threadIdx.x < w) count[threadIdx.x] += count[threadIdx.x + w];
         __syncthreads();
     }
     const int rank = count[0];
