@@ -242,8 +242,9 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
  *   dbg_acc_hi, dbg_acc_lo   int32 [M, N] each, or null: when given, the two
  *                            integer accumulators are written as well
  * Shapes with M <= 64 take weight-streaming kernels bound by HBM bandwidth
- * (the packed weights cross HBM once; up to 16 tokens sit in LDS whole when
- * they fit, else and up to 64 tokens they are chunked through it; layers with
+ * (the packed weights cross HBM once; the code rows of up to 16 tokens are
+ * read as they are needed while they are short enough to stay in cache, else
+ * and up to 64 tokens they are chunked through LDS; layers with
  * few output channels split the reduction axis over wavefronts), larger M the
  * tiled matrix-core kernel, except that up to 1024 tokens go through the
  * streaming kernel in slices of 64 where the layer has too few 128 x 256

@@ -294,7 +294,8 @@ static DecodeArgs make_decode_args(const int8_t* q_hi, const uint8_t* q_lo, cons
 // kernels quantize d.x themselves instead of reading codes.
 static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t st) {
     const WeightLayout& L = d.L;
-    int lds_bytes = d.M * d.lds_row;
+    // the code rows go through LDS only when the kernel makes them itself
+    int lds_bytes = fused ? ((d.M * d.lds_row + 15) & ~15) : 0;
     const int extra = fused ? kFusedScratchFloats * 4 : 0;
     // Few output channels (at most half of the chip's 2048 wavefronts would have a
     // group): cut each group's reduction axis into SK runs, one per wavefront, until
@@ -313,14 +314,14 @@ static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t 
         launch(kernel, GRID, blk, lds_bytes, st, d);                                               \
     } while (0)
     if (sk > 1) {
-        lds_bytes = ((lds_bytes + 15) & ~15) + (kDecodeThreads / 64) * 2 * 64 * 16 + extra;
+        lds_bytes += (kDecodeThreads / 64) * 2 * 64 * 16 + extra;   // the partial sums
         const int sets = (d.groups * sk + 7) / 8;
         const dim3 grid((unsigned)(sets < 256 ? sets : 256));
 #define RESQ_LAUNCH_SPLITK(SK)                                                                     \
     do {                                                                                           \
-        if (fused) RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<false, SK, true>), grid);         \
-        else if (dbg) RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<true, SK, false>), grid);      \
-        else RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<false, SK, false>), grid);              \
+        if (fused) RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<false, SK, kActQuantize>), grid);  \
+        else if (dbg) RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<true, SK, kActDirect>), grid);  \
+        else RESQ_LAUNCH_DECODE((gemm_decode_splitk_kernel<false, SK, kActDirect>), grid);          \
     } while (0)
         if (sk == 2) RESQ_LAUNCH_SPLITK(2);
         else if (sk == 4) RESQ_LAUNCH_SPLITK(4);
@@ -328,12 +329,12 @@ static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t 
 #undef RESQ_LAUNCH_SPLITK
         return launch_status();
     }
-    lds_bytes = ((lds_bytes + 15) & ~15) + extra;
+    lds_bytes += extra;
     // one workgroup per compute unit (256 of them), fewer when there is less work
     const dim3 grid((unsigned)(d.groups < 256 ? d.groups : 256));
-    if (fused) RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, true>), grid);
-    else if (dbg) RESQ_LAUNCH_DECODE((gemm_decode_kernel<true, false>), grid);
-    else RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, false>), grid);
+    if (fused) RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, kActQuantize>), grid);
+    else if (dbg) RESQ_LAUNCH_DECODE((gemm_decode_kernel<true, kActDirect>), grid);
+    else RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, kActDirect>), grid);
 #undef RESQ_LAUNCH_DECODE
     return launch_status();
 }
@@ -363,7 +364,8 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool dbg = dbg_acc_hi || dbg_acc_lo;
 
-    // few tokens: stream the weights once (HBM-bound kernel), activations in LDS
+    // few tokens: stream the weights once (HBM-bound kernel); code rows beyond 140 KiB in all
+    // go to the chunked kernel below, which reads them once per workgroup instead of once per wavefront
     const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
     if (M <= kDecodeMaxM && M * lds_row <= 140 * 1024) {
         const DecodeArgs d = make_decode_args(q_hi, q_lo, s_hi, s_lo, c_hi, c_lo, lo_sum, M, packed, L, y, ldy,

@@ -9,7 +9,7 @@
 // workgroup of eight wavefronts runs per compute unit, and groups are dealt
 // round-robin over compute units first, so that every unit streams the same
 // number of bytes.  The activation codes of all tokens (at most a few tens of
-// KiB) sit in LDS for the whole kernel.  The matrix cores are nearly idle here; they are used because
+// KiB) are read from L2 as they are needed.  The matrix cores are nearly idle here; they are used because
 // the vector ALU could not keep up with 8 TB/s of nibbles at M = 16.
 //
 // Roofline: HBM.  Algorithmic bytes = the packed weight buffer.
@@ -119,37 +119,6 @@ __device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, in
         for (int v = 0; v < 4; ++v)
             if (n + v < a.L.N) dst[v] = (uint16_t)pack_bf16(out[v], 0.f);
     }
-}
-
-// activation codes of every token -> LDS (row = high codes, then packed low codes);
-// 16-byte unit u of token m, up to twelve loads in flight per thread
-__device__ __forceinline__ void fill_act_codes(const DecodeArgs& a, uint8_t* act, int t) {
-    const int hi_units = (int)(a.L.kh_pad / 16), row_units = hi_units + (int)(a.L.kl_pad / 32);
-    constexpr int FILL = 12;
-    const int units = a.M * row_units;
-    for (int u0 = t; u0 < units; u0 += FILL * kDecodeThreads) {
-        uint4 v[FILL];
-#pragma unroll
-        for (int q = 0; q < FILL; ++q) {
-            const int u = u0 + q * kDecodeThreads;
-            v[q] = make_uint4(0u, 0u, 0u, 0u);
-            if (u < units) {
-                const int m = u / row_units, c = u - m * row_units;
-                v[q] = c < hi_units
-                           ? *reinterpret_cast<const uint4*>(a.q_hi + m * a.ld_hi + c * 16)
-                           : *reinterpret_cast<const uint4*>(a.q_lo + m * a.ld_lo + (c - hi_units) * 16);
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < FILL; ++q) {
-            const int u = u0 + q * kDecodeThreads;
-            if (u < units) {
-                const int m = u / row_units, c = u - m * row_units;
-                *reinterpret_cast<uint4*>(act + m * a.lds_row + c * 16) = v[q];
-            }
-        }
-    }
-    __syncthreads();
 }
 
 // The per-token quantizer (Section 4.1 Eq. 2, symmetric) run by the workgroup itself on
@@ -266,32 +235,66 @@ __device__ __forceinline__ DecodeArgs epilogue_args(const DecodeArgs& a, const f
     return e;
 }
 
-template <bool DBG, bool FUSED>
+// Where a wavefront's activation operand comes from: straight from the code rows in memory
+// through a second ring beside the weight ring (no LDS, no barrier: the first matrix
+// instruction waits for nothing but its own two loads; the code rows are a few KiB per
+// token, stay in L2, and every wavefront reads its part of them once per group; measured
+// 1 to 15 % faster than staging them in LDS first), or from LDS rows into which the
+// workgroup itself has quantized the bf16 activations.
+enum : int { kActQuantize = 1, kActDirect = 2 };
+
+// lane's pointers to its 16-byte piece of block 0 of the high and of the low codes of its
+// token (the low pointer moved back by the high blocks, so that both take the block index)
+struct ActPieces {
+    const uint8_t* hi;
+    const uint8_t* lo;
+    int hi_blocks;
+    __device__ __forceinline__ uint4 operator()(int b) const {
+        return *reinterpret_cast<const uint4*>((b < hi_blocks ? hi : lo) + (int64_t)b * kRowBytes);
+    }
+};
+__device__ __forceinline__ ActPieces act_pieces(const DecodeArgs& a, int lane, bool tok_live) {
+    const int tok = tok_live ? (lane & 15) : 0;
+    ActPieces p;
+    p.hi_blocks = (int)a.L.hi_blocks;
+    p.hi = a.q_hi + (int64_t)tok * a.ld_hi + (lane >> 4) * 16;
+    p.lo = a.q_lo + (int64_t)tok * a.ld_lo + (lane >> 4) * 16 - (int64_t)p.hi_blocks * kRowBytes;
+    return p;
+}
+
+template <bool DBG, int ACT>
 __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const DecodeArgs a) {
-    extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // [M][lds_row]
+    extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // kActQuantize: [M][lds_row]
+    constexpr bool DIRECT = ACT == kActDirect;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
     const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
+    // lane l supplies token l % 16 (zero operand past M), piece l / 16 of each 64-byte chunk
+    const int tok = lane & 15;
+    const bool tok_live = tok < a.M;
+    const ActPieces piece = act_pieces(a, lane, tok_live);
 
     // start the weight stream of this wave's first group before anything else
     int group = wave * gridDim.x + blockIdx.x;
-    uint4 ring[kDecodeDepth];
+    uint4 ring[kDecodeDepth], aring[DIRECT ? kDecodeDepth : 1];
     {
         const uint4* wp = reinterpret_cast<const uint4*>(
             a.packed + (int64_t)(group < a.groups ? group : 0) * a.L.group_bytes + lane_off);
 #pragma unroll
-        for (int i = 0; i < kDecodeDepth; ++i)
-            if (group < a.groups && i < blocks) ring[i] = wp[i * (kBlockBytes / 16)];
+        for (int i = 0; i < kDecodeDepth; ++i) {
+            if constexpr (DIRECT) aring[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (group < a.groups && i < blocks) {
+                ring[i] = wp[i * (kBlockBytes / 16)];
+                if constexpr (DIRECT)
+                    if (tok_live) aring[i] = piece(i);
+            }
+        }
     }
 
     float* scal = reinterpret_cast<float*>(act + ((a.M * a.lds_row + 15) & ~15));
-    if constexpr (FUSED) fill_act_quantize(a, act, scal, t);
-    else fill_act_codes(a, act, t);
-    const DecodeArgs ea = epilogue_args<FUSED>(a, scal);
+    if constexpr (ACT == kActQuantize) fill_act_quantize(a, act, scal, t);
+    const DecodeArgs ea = epilogue_args<ACT == kActQuantize>(a, scal);
 
-    // lane l supplies token l % 16 (zero operand past M), piece l / 16 of each 64-byte chunk
-    const int tok = lane & 15;
-    const bool tok_live = tok < a.M;
     const uint8_t* arow = act + (tok_live ? tok : 0) * a.lds_row + (lane >> 4) * 16;
     const v4i zero = {0, 0, 0, 0};
     for (; group < a.groups; group += 8 * gridDim.x) {
@@ -303,10 +306,21 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
                 const int b = b0 + i;
                 if (b < blocks) {
                     const uint4 wq = ring[i];
-                    if (b + kDecodeDepth < blocks) ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
+                    v4i p;
+                    if constexpr (DIRECT) {
+                        const uint4 pq = aring[i];   // zero past M
+                        p = v4i{(int)pq.x, (int)pq.y, (int)pq.z, (int)pq.w};
+                    }
+                    if (b + kDecodeDepth < blocks) {
+                        ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
+                        if constexpr (DIRECT)
+                            if (tok_live) aring[i] = piece(b + kDecodeDepth);
+                    }
                     const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
-                    v4i p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
-                    if (!tok_live) p = zero;
+                    if constexpr (!DIRECT) {
+                        p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
+                        if (!tok_live) p = zero;
+                    }
                     if (b < hi_blocks) {
                         acc_hi = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, p, acc_hi, 0, 0, 0);
                     } else {
@@ -325,7 +339,11 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
             const uint4* np = reinterpret_cast<const uint4*>(a.packed + (int64_t)next * a.L.group_bytes + lane_off);
 #pragma unroll
             for (int i = 0; i < kDecodeDepth; ++i)
-                if (i < blocks) ring[i] = np[i * (kBlockBytes / 16)];
+                if (i < blocks) {
+                    ring[i] = np[i * (kBlockBytes / 16)];
+                    if constexpr (DIRECT)
+                        if (tok_live) aring[i] = piece(i);
+                }
         }
 
         // lane l now holds token l % 16, channels 16 group + 4 (l / 16) + {0..3}
@@ -343,41 +361,48 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
 // a time ("a set"); sets are dealt round-robin over workgroups.  Exact: integer
 // addition in any order.
 // ---------------------------------------------------------------------------
-template <bool DBG, int SK, bool FUSED>
+template <bool DBG, int SK, int ACT>
 __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(const DecodeArgs a) {
     static_assert(SK == 2 || SK == 4 || SK == 8, "runs per group");
     constexpr int kWaves = kDecodeThreads / 64;
     constexpr int G = kWaves / SK;  // groups per set
-    extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // [M][lds_row], then the partial sums
+    extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // kActQuantize: [M][lds_row]; then the partial sums
+    constexpr bool DIRECT = ACT == kActDirect;
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int gsel = wave / SK, part = wave % SK;
     const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
     const int b_begin = (int)((int64_t)blocks * part / SK), b_end = (int)((int64_t)blocks * (part + 1) / SK);
     const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
-    v4i* partial = reinterpret_cast<v4i*>(act + ((a.M * a.lds_row + 15) & ~15));  // [kWaves][2][64]
+    v4i* partial = reinterpret_cast<v4i*>(act + (DIRECT ? 0 : ((a.M * a.lds_row + 15) & ~15)));  // [kWaves][2][64]
     const int sets = (a.groups + G - 1) / G;
+    const int tok = lane & 15;
+    const bool tok_live = tok < a.M;
+    const ActPieces piece = act_pieces(a, lane, tok_live);
 
     // start the weight stream of this wave's first run before anything else
     int set = blockIdx.x;
-    uint4 ring[kDecodeDepth];
+    uint4 ring[kDecodeDepth], aring[DIRECT ? kDecodeDepth : 1];
     {
         const int group = set * G + gsel;
         const bool live = set < sets && group < a.groups;
         const uint4* wp = reinterpret_cast<const uint4*>(
             a.packed + (int64_t)(live ? group : 0) * a.L.group_bytes + lane_off);
 #pragma unroll
-        for (int i = 0; i < kDecodeDepth; ++i)
-            if (live && b_begin + i < b_end) ring[i] = wp[(b_begin + i) * (kBlockBytes / 16)];
+        for (int i = 0; i < kDecodeDepth; ++i) {
+            if constexpr (DIRECT) aring[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (live && b_begin + i < b_end) {
+                ring[i] = wp[(b_begin + i) * (kBlockBytes / 16)];
+                if constexpr (DIRECT)
+                    if (tok_live) aring[i] = piece(b_begin + i);
+            }
+        }
     }
 
     float* scal = reinterpret_cast<float*>(partial + kWaves * 2 * 64);
-    if constexpr (FUSED) fill_act_quantize(a, act, scal, t);
-    else fill_act_codes(a, act, t);
-    const DecodeArgs ea = epilogue_args<FUSED>(a, scal);
+    if constexpr (ACT == kActQuantize) fill_act_quantize(a, act, scal, t);
+    const DecodeArgs ea = epilogue_args<ACT == kActQuantize>(a, scal);
 
-    const int tok = lane & 15;
-    const bool tok_live = tok < a.M;
     const uint8_t* arow = act + (tok_live ? tok : 0) * a.lds_row + (lane >> 4) * 16;
     const v4i zero = {0, 0, 0, 0};
     for (; set < sets; set += gridDim.x) {  // the same trip count for every wavefront of a workgroup
@@ -393,10 +418,21 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
                     const int b = b0 + i;
                     if (b < b_end) {
                         const uint4 wq = ring[i];
-                        if (b + kDecodeDepth < b_end) ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
+                        v4i p;
+                        if constexpr (DIRECT) {
+                            const uint4 pq = aring[i];   // zero past M
+                            p = v4i{(int)pq.x, (int)pq.y, (int)pq.z, (int)pq.w};
+                        }
+                        if (b + kDecodeDepth < b_end) {
+                            ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
+                            if constexpr (DIRECT)
+                                if (tok_live) aring[i] = piece(b + kDecodeDepth);
+                        }
                         const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
-                        v4i p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
-                        if (!tok_live) p = zero;
+                        if constexpr (!DIRECT) {
+                            p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
+                            if (!tok_live) p = zero;
+                        }
                         if (b < hi_blocks) {
                             acc_hi = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, p, acc_hi, 0, 0, 0);
                         } else {
@@ -418,7 +454,11 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
                 const uint4* np = reinterpret_cast<const uint4*>(a.packed + (int64_t)ngroup * a.L.group_bytes + lane_off);
 #pragma unroll
                 for (int i = 0; i < kDecodeDepth; ++i)
-                    if (b_begin + i < b_end) ring[i] = np[(b_begin + i) * (kBlockBytes / 16)];
+                    if (b_begin + i < b_end) {
+                        ring[i] = np[(b_begin + i) * (kBlockBytes / 16)];
+                        if constexpr (DIRECT)
+                            if (tok_live) aring[i] = piece(b_begin + i);
+                    }
             }
         }
         if (part != 0) {
