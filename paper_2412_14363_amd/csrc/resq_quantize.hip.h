@@ -767,12 +767,36 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
     const bool live = n < L.N;
     const uint16_t* row = w + (live ? n : 0) * ldw;
 
+    // rows that can be read 16 bytes at a time (every vector then lies inside one group)
+    const bool vec = (reinterpret_cast<uintptr_t>(w) & 15) == 0 && ldw % 8 == 0 && K % 8 == 0 && r % 8 == 0;
+    const uint4* row4 = reinterpret_cast<const uint4*>(row);
+    // eight consecutive weights from column k on (zero where the row or the group has ended)
+    auto load8 = [&](int k, int end, uint16_t (&e)[8]) __attribute__((always_inline)) {
+        if (vec) {
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (k < end) v = row4[k >> 3];
+            const uint32_t ww[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = (uint16_t)(ww[j >> 1] >> (16 * (j & 1)));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = k + j < end ? row[k + j] : (uint16_t)0;
+        }
+    };
     float amax_h = 0.0f, amax_l = 0.0f;
     if (live) {
-        for (int k = t; k < K; k += kQuantThreads) {
-            const float a = bf16_bits_to_f32(row[k] & 0x7FFFu);
-            if (k < r) amax_h = fmaxf(amax_h, a);
-            else amax_l = fmaxf(amax_l, a);
+        if (vec) {
+            for (int u = t; u < (K >> 3); u += kQuantThreads) {
+                const float a = absmax8(row4[u]);
+                if (u < (r >> 3)) amax_h = fmaxf(amax_h, a);
+                else amax_l = fmaxf(amax_l, a);
+            }
+        } else {
+            for (int k = t; k < K; k += kQuantThreads) {
+                const float a = bf16_bits_to_f32(row[k] & 0x7FFFu);
+                if (k < r) amax_h = fmaxf(amax_h, a);
+                else amax_l = fmaxf(amax_l, a);
+            }
         }
     }
     block_max2(amax_h, amax_l, red);
@@ -789,12 +813,17 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
         uint32_t out[4] = {0u, 0u, 0u, 0u};
         if (live) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int k = u * 16 + j;
-                if (k < r) {
-                    const int c = quant_code(bf16_bits_to_f32(row[k]), sh, kQmaxHi);
-                    sum_hi += c;
-                    out[j >> 2] |= (uint32_t)(c & 0xFF) << (8 * (j & 3));
+            for (int q = 0; q < 2; ++q) {
+                uint16_t e[8];
+                load8(u * 16 + q * 8, r, e);
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int j = q * 8 + jj, k = u * 16 + j;
+                    if (k < r) {
+                        const int c = quant_code(bf16_bits_to_f32(e[jj]), sh, kQmaxHi);
+                        sum_hi += c;
+                        out[j >> 2] |= (uint32_t)(c & 0xFF) << (8 * (j & 3));
+                    }
                 }
             }
         }
@@ -807,17 +836,22 @@ __global__ __launch_bounds__(kQuantThreads) void pack_weights_kernel(
         uint32_t out[4] = {0x08080808u, 0x08080808u, 0x08080808u, 0x08080808u};
         if (live) {
 #pragma unroll
-            for (int j = 0; j < 32; ++j) {
-                const int k = r + u * 32 + j;
-                if (k < K) {
-                    const int c = quant_code(bf16_bits_to_f32(row[k]), sl, kQmaxLo);
-                    if (j & 1) {
-                        sum_lo_odd += c;
-                        out[j >> 3] = (out[j >> 3] & ~(0xFu << (4 * (j & 7) - 4))) |
-                                      ((uint32_t)((c + 8) & 0xF) << (4 * (j & 7) - 4));
-                    } else {
-                        even_sum += c;
-                        out[j >> 3] |= (uint32_t)(c & 0xF) << (4 * (j & 7) + 4);
+            for (int q = 0; q < 4; ++q) {
+                uint16_t e[8];
+                load8(r + u * 32 + q * 8, K, e);
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int j = q * 8 + jj, k = r + u * 32 + j;
+                    if (k < K) {
+                        const int c = quant_code(bf16_bits_to_f32(e[jj]), sl, kQmaxLo);
+                        if (j & 1) {
+                            sum_lo_odd += c;
+                            out[j >> 3] = (out[j >> 3] & ~(0xFu << (4 * (j & 7) - 4))) |
+                                          ((uint32_t)((c + 8) & 0xF) << (4 * (j & 7) - 4));
+                        } else {
+                            even_sum += c;
+                            out[j >> 3] |= (uint32_t)(c & 0xF) << (4 * (j & 7) + 4);
+                        }
                     }
                 }
             }
