@@ -474,6 +474,25 @@ def test_hadamard_quantize_fused(oracle, rq, M, K, r, block):
         assert torch.equal(act3.q_hi, act.q_hi) and torch.equal(act3.s_hi, act.s_hi)
 
 
+def test_hadamard_quantize_fused_strided_rows(oracle, rq):
+    # the matrix-core path on rows that are slices of wider buffers, input and inspection output
+    M, K, r = 7, 256 + 1280, 256
+    s = wl.LayerShape("hqs", M=M, K=K, N=1, r=r, act="student_t3", seed=5)
+    x = wl.make_activations(s)
+    xbuf = torch.zeros((M, K + 40), dtype=torch.bfloat16, device="cuda")
+    xbuf[:, :K] = x.cuda()
+    rbuf = torch.full((M, K + 16), 3.0, dtype=torch.bfloat16, device="cuda")
+    act = rq.resq_hadamard_quantize_act(xbuf[:, :K], r, 256, x_rot=rbuf[:, :K])
+    ref = rq.resq_hadamard_quantize_act(x.cuda(), r, 256)
+    torch.cuda.synchronize()
+    assert torch.all(rbuf[:, K:] == 3.0) and torch.all(rbuf[:, :r] == 3.0), "wrote outside the low columns"
+    for name in ("q_hi", "q_lo", "s_hi", "s_lo", "lo_sum"):
+        assert torch.equal(getattr(act, name), getattr(ref, name)), name
+    rotated = wl.bf16_bits(x).copy()
+    rotated[:, r:] = wl.bf16_bits(rbuf[:, r:K].cpu())
+    compare_act_codes(oracle, act, rotated, r)
+
+
 # ---- asymmetric activations (the other branch of Eq. 1, the setting of Section 5.1) ----
 
 def stored_to_codes(act, r, K):
