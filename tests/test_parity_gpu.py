@@ -270,6 +270,30 @@ def test_quantize_gemm_mixed_one_call(oracle, rq, M, K, N, r):
     assert torch.equal(y2, two)
 
 
+def _random_one_call_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M = int(rng.integers(1, 17))
+        K = int(rng.choice([64, 136, 520, 1000, 2048, 4096, 8192]))
+        r = int(rng.choice([0, K // 8, K // 4, K])) // 8 * 8
+        N = int(rng.choice([16, 40, 272, 515, 1024, 4100]))
+        out.append((M, K, N, r))
+    return out
+
+
+@pytest.mark.parametrize("M,K,N,r", _random_one_call_shapes(16, 4321))
+def test_quantize_gemm_mixed_one_call_random_shapes(oracle, rq, M, K, N, r):
+    x, w = wl.random_small_case(M * 29 + K + N, M, K, N, r, act="student_t3")
+    packed = rq.resq_pack_weights(w.cuda(), r)
+    y = rq.resq_quantize_gemm_mixed(x.cuda(), packed, N, r)
+    two = rq.resq_gemm_mixed(rq.resq_quantize_act(x.cuda(), r), packed, N)
+    torch.cuda.synchronize()
+    assert torch.equal(y, two)
+    ref = oracle.linear(wl.bf16_bits(x), wl.bf16_bits(w), r)
+    assert y_within_tolerance(y, ref.y) <= REL_TOL
+
+
 def test_quantize_gemm_mixed_one_call_full_size(oracle, rq):
     s = wl.decode_shape(4)
     x, w = wl.make_activations(s), wl.make_weights(s)
@@ -472,6 +496,32 @@ def test_hadamard_quantize_fused(oracle, rq, M, K, r, block):
     assert torch.equal(act3.q_lo, act.q_lo) and torch.equal(act3.s_lo, act.s_lo)
     if r > 0:
         assert torch.equal(act3.q_hi, act.q_hi) and torch.equal(act3.s_hi, act.s_hi)
+
+
+def _random_h256_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, 12)), 256 * int(rng.integers(0, 17)), 256 * int(rng.integers(1, 105)))
+            for _ in range(n)]
+
+
+@pytest.mark.parametrize("M,r,lo", _random_h256_shapes(12, 2468))
+def test_hadamard256_quantize_random_shapes(oracle, rq, M, r, lo):
+    # every instantiation of the matrix-core kernel: high widths 0 .. 4096, 1 .. 104 low blocks
+    K = r + lo
+    s = wl.LayerShape("h256", M=M, K=K, N=1, r=r, act="student_t3", seed=K + M)
+    x = wl.make_activations(s)
+    x_rot = torch.zeros((M, K), dtype=torch.bfloat16, device="cuda")
+    act = rq.resq_hadamard_quantize_act(x.cuda(), r, 256, x_rot=x_rot)
+    torch.cuda.synchronize()
+    got = wl.bf16_bits(x_rot.cpu())
+    want = oracle.hadamard(wl.bf16_bits(x), r, K, 256)
+    g64, w64 = wl.bits_to_f64(got[:, r:]), wl.bits_to_f64(want[:, r:])
+    scale = np.abs(w64).max()
+    assert np.all(np.abs(g64 - w64) <= np.maximum(np.abs(w64), 2.0 ** -8 * scale) * 2.0 ** -7)
+    assert np.mean(got[:, r:] == want[:, r:]) > 0.99
+    rotated = wl.bf16_bits(x).copy()
+    rotated[:, r:] = got[:, r:]
+    compare_act_codes(oracle, act, rotated, r)
 
 
 def test_hadamard_quantize_fused_strided_rows(oracle, rq):
