@@ -373,45 +373,49 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         return launch_decode(d, dbg, false, st);
     }
 
-    // a few tens of tokens: the same single pass over the weights, activation codes
-    // chunked through LDS
-    // Up to 1024 tokens take the same kernel in slices of 64 tokens (each slice streams
-    // the weights for itself) when the tiled kernel would leave most of the chip idle:
-    // few tiles, each walking the whole reduction axis alone.  Estimated from the
-    // measured costs of both kernels, per round of 256 workgroups: 10 us + 0.5 us per
-    // 1 KiB block of a channel group for a tile, 8 us + 0.4 us per block of a run for
-    // a slice; the number of runs per group is the one with the lower estimate.
-    bool streaming = M <= kStreamMaxM;
-    int stream_sk = 0;  // 0: as many runs as the shape allows (a single slice)
-    if (!streaming && M <= 16 * kStreamMaxM) {
-        const int64_t blocks = L.hi_blocks + L.lo_blocks, groups = (N + 15) / 16;
-        const int64_t slices = (M + kStreamMaxM - 1) / kStreamMaxM;
-        const int64_t tiles = ((M + kBM - 1) / kBM) * ((N + kBN - 1) / kBN);
-        const double tiled_us = (double)((tiles + 255) / 256) * (10.0 + 0.5 * (double)blocks);
-        double stream_us = 0.0;
-        for (int sk = 1; sk * 4 <= 8; sk *= 2) {
-            if (sk > 1 && (groups * sk > 2048 || blocks / sk < 2 * kChunkBlocks)) break;
-            const int64_t wgs = (groups * sk + 7) / 8 * slices;
-            const double us = (double)((wgs + 255) / 256) * (8.0 + 0.4 * (double)(blocks / sk));
-            if (stream_sk == 0 || us < stream_us) {
-                stream_us = us;
-                stream_sk = sk;
+    // A few tens of tokens, and up to 1024 of them where the tiled kernel would leave most
+    // of the chip idle (few tiles, each walking the whole reduction axis alone): the same
+    // single pass over the weights, activation codes chunked through LDS, in slices of
+    // 16 TG tokens (each slice streams the weights for itself, out of the last-level cache
+    // after the first) with SK runs per channel group.  TG and SK are the pair with the
+    // lowest estimate from the measured costs of the kernel: per round of 256 workgroups
+    // 7 us + (0.16, 0.27, 0.42) us per 1 KiB block of a run for TG = (1, 2, 4), and never
+    // less than one pass over the weights at 5 TB/s; a tile costs 10 us + 0.5 us per block.
+    const int blocks = (int)(L.hi_blocks + L.lo_blocks);
+    int tg = 0, sk = 0;
+    double stream_us = 0.0;
+    if (M <= 16 * kStreamMaxM) {
+        const int64_t groups = (N + 15) / 16;
+        const double pass_us = (double)L.total_bytes / 5.0e6;
+        for (int cand_tg = 1; cand_tg <= 4; cand_tg *= 2) {
+            const double per_block = cand_tg == 1 ? 0.16 : (cand_tg == 2 ? 0.27 : 0.42);
+            const int64_t slices = (M + cand_tg * 16 - 1) / (cand_tg * 16);
+            for (int cand_sk = 1; cand_sk * cand_tg <= 8; cand_sk *= 2) {
+                // runs of at least two chunks, at most 2048 of them
+                if (cand_sk > 1 && (groups * cand_sk > 2048 || blocks / cand_sk < 2 * kChunkBlocks)) break;
+                const int64_t sets = (groups * cand_sk + 7) / 8;
+                const int64_t wgs = (sets < 256 ? sets : 256) * slices;
+                const int64_t rounds = ((wgs + 255) / 256) * ((sets + 255) / 256);
+                double us = (double)rounds * (7.0 + per_block * (double)(blocks / cand_sk));
+                if (us < pass_us) us = pass_us;
+                if (tg == 0 || us < stream_us) {
+                    stream_us = us;
+                    tg = cand_tg;
+                    sk = cand_sk;
+                }
             }
         }
+    }
+    bool streaming = M <= kStreamMaxM;
+    if (!streaming && tg != 0) {
+        const int64_t tiles = ((M + kBM - 1) / kBM) * ((N + kBN - 1) / kBN);
+        const double tiled_us = (double)((tiles + 255) / 256) * (10.0 + 0.5 * (double)blocks);
         streaming = stream_us < 0.9 * tiled_us;
     }
     if (streaming) {
         const DecodeArgs d = make_decode_args(q_hi, q_lo, s_hi, s_lo, c_hi, c_lo, lo_sum, M, packed, L, y, ldy,
                                               dbg_acc_hi, dbg_acc_lo, swiglu, 0);
-        // token groups by M; runs per group as for the decode kernel, at most 8 / TG of
-        // them (LDS holds the chunks of every run) and at least two chunks long
-        const int blocks = (int)(L.hi_blocks + L.lo_blocks);
-        const int tg = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
         const int slices = (int)((M + tg * 16 - 1) / (tg * 16));  // of tg * 16 tokens
-        int sk = 1;
-        if (stream_sk > 0) sk = stream_sk;
-        else
-            while (sk * tg < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 2 * kChunkBlocks) sk *= 2;
         const int sets = (d.groups * sk + 7) / 8;
         const dim3 grid((unsigned)(sets < 256 ? sets : 256), (unsigned)slices), blk(kDecodeThreads);
         const int lds_bytes = 2 * sk * tg * kChunkBlocks * kBlockBytes;
