@@ -258,6 +258,21 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
                     void* stream);
 
 /*
+ * Which kernel resq_gemm_mixed (and its variants) runs for a shape: host only,
+ * no device call.  For callers that want to know, and for tests.
+ *   kernel        0: weight-streaming kernel for at most 16 tokens
+ *                 1: weight-streaming kernel with the activation codes chunked
+ *                    through LDS, in slices of 16 * token_groups tokens
+ *                 2: tiled matrix-core kernel                        (written)
+ *   token_groups  1, 2 or 4 for kernel 1 (1 for kernel 0, 0 for kernel 2) (written)
+ *   runs          parts into which the reduction axis of a channel group is cut
+ *                 across wavefronts, 1..8 (0 for kernel 2)           (written)
+ * Errors as resq_gemm_mixed for the shape; RESQ_ERR_NULL for a null output.
+ */
+int resq_gemm_mixed_plan(int64_t M, int64_t N, int64_t K, int64_t r, int* kernel, int* token_groups,
+                         int* runs);
+
+/*
  * The layer in ONE call for the generation stage (a handful of tokens, Section 1:
  * memory-bound): resq_quantize_act (Section 4.1 Eq. 2) and resq_gemm_mixed
  * (Eq. 4) in one kernel.  Every workgroup of the weight-streaming kernel

@@ -33,6 +33,7 @@ SYMBOLS = {
     "resq_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p]),
     "resq_hadamard_quantize_act_asym": (C.c_int, [_p, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _i64, _p]),
     "resq_gemm_mixed_asym": (C.c_int, [_p, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
+    "resq_gemm_mixed_plan": (C.c_int, [_i64, _i64, _i64, _i64, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]),
     "resq_quantize_gemm_mixed": (C.c_int, [_p, _i64, _i64, _p, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_gemm_mixed_swiglu": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_gram_accumulate": (C.c_int, [_p, _i64, _i64, _i64, _p, _i64, _p]),
@@ -195,6 +196,13 @@ def resq_quantize_act_asym(x: torch.Tensor, r: int, hadamard_block: int = 0,
     _check(st, "resq_quantize_act_asym")
     out.asym = True
     return out
+
+
+def resq_gemm_mixed_plan(M: int, N: int, K: int, r: int):
+    """(kernel, token_groups, runs) that resq_gemm_mixed uses for this shape; host only."""
+    k, tg, sk = C.c_int(), C.c_int(), C.c_int()
+    _check(lib().resq_gemm_mixed_plan(M, N, K, r, C.byref(k), C.byref(tg), C.byref(sk)), "resq_gemm_mixed_plan")
+    return k.value, tg.value, sk.value
 
 
 def resq_quantize_gemm_mixed(x: torch.Tensor, packed: torch.Tensor, N: int, r: int,

@@ -257,6 +257,67 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
     return launch_status();
 }
 
+// Which kernel resq_gemm_mixed runs for a shape, and with how many token groups per
+// workgroup (TG) and runs per channel group (SK).
+//   kernel 0: M <= 16 and code rows of at most 140 KiB in all: the weights stream once,
+//             activation operands straight from the code rows (beyond that size the chunked
+//             kernel reads them once per workgroup instead of once per wavefront); SK = runs
+//             per group (layers with at most 1024 groups are cut until more than half of the
+//             chip's 2048 wavefronts have a run, or a run would get shorter than 4 blocks).
+//   kernel 1: a few tens of tokens, and up to 1024 of them where the tiled kernel would
+//             leave most of the chip idle (few tiles, each walking the whole reduction axis
+//             alone): the same single pass over the weights, activation codes chunked
+//             through LDS, in slices of 16 TG tokens (each slice streams the weights for
+//             itself, out of the last-level cache after the first).  TG and SK are the pair
+//             with the lowest estimate from the measured costs of the kernel: per round of
+//             256 workgroups 7 us + (0.16, 0.27, 0.42) us per 1 KiB block of a run for
+//             TG = (1, 2, 4), and never less than one pass over the weights at 5 TB/s.
+//   kernel 2: the tiled kernel; a tile costs 10 us + 0.5 us per block by the same measure.
+struct GemmPlan {
+    int kernel, tg, sk;
+};
+static GemmPlan plan_gemm(int64_t M, const WeightLayout& L) {
+    const int blocks = (int)(L.hi_blocks + L.lo_blocks);
+    const int64_t groups = (L.N + 15) / 16;
+    const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
+    if (M <= kDecodeMaxM && M * lds_row <= 140 * 1024) {
+        int sk = 1;
+        while (sk < 8 && groups * sk <= 1024 && blocks / (2 * sk) >= 4) sk *= 2;
+        return {0, 1, sk};
+    }
+    int tg = 0, sk = 0;
+    double stream_us = 0.0;
+    if (M <= 16 * kStreamMaxM) {
+        const double pass_us = (double)L.total_bytes / 5.0e6;
+        for (int cand_tg = 1; cand_tg <= 4; cand_tg *= 2) {
+            const double per_block = cand_tg == 1 ? 0.16 : (cand_tg == 2 ? 0.27 : 0.42);
+            const int64_t slices = (M + cand_tg * 16 - 1) / (cand_tg * 16);
+            for (int cand_sk = 1; cand_sk * cand_tg <= 8; cand_sk *= 2) {
+                // runs of at least two chunks, at most 2048 of them
+                if (cand_sk > 1 && (groups * cand_sk > 2048 || blocks / cand_sk < 2 * kChunkBlocks)) break;
+                const int64_t sets = (groups * cand_sk + 7) / 8;
+                const int64_t wgs = (sets < 256 ? sets : 256) * slices;
+                const int64_t rounds = ((wgs + 255) / 256) * ((sets + 255) / 256);
+                double us = (double)rounds * (7.0 + per_block * (double)(blocks / cand_sk));
+                if (us < pass_us) us = pass_us;
+                if (tg == 0 || us < stream_us) {
+                    stream_us = us;
+                    tg = cand_tg;
+                    sk = cand_sk;
+                }
+            }
+        }
+    }
+    bool streaming = M <= kStreamMaxM;
+    if (!streaming && tg != 0) {
+        const int64_t tiles = ((M + kBM - 1) / kBM) * ((L.N + kBN - 1) / kBN);
+        const double tiled_us = (double)((tiles + 255) / 256) * (10.0 + 0.5 * (double)blocks);
+        streaming = stream_us < 0.9 * tiled_us;
+    }
+    if (streaming) return {1, tg, sk};
+    return {2, 0, 0};
+}
+
 // arguments of the weight-streaming kernels; the code pointers are null when the kernel
 // quantizes x itself
 static DecodeArgs make_decode_args(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
@@ -297,12 +358,7 @@ static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t 
     // the code rows go through LDS only when the kernel makes them itself
     int lds_bytes = fused ? ((d.M * d.lds_row + 15) & ~15) : 0;
     const int extra = fused ? kFusedScratchFloats * 4 : 0;
-    // Few output channels (at most half of the chip's 2048 wavefronts would have a
-    // group): cut each group's reduction axis into SK runs, one per wavefront, until
-    // more than half have one or a run would get shorter than 4 blocks.
-    const int blocks = (int)(L.hi_blocks + L.lo_blocks);
-    int sk = 1;
-    while (sk < 8 && (int64_t)d.groups * sk <= 1024 && blocks / (2 * sk) >= 4) sk *= 2;
+    const int sk = plan_gemm(d.M, L).sk;   // runs per channel group
     const dim3 blk(kDecodeThreads);
 #define RESQ_LAUNCH_DECODE(KERNEL, GRID)                                                           \
     do {                                                                                           \
@@ -364,55 +420,15 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool dbg = dbg_acc_hi || dbg_acc_lo;
 
-    // few tokens: stream the weights once (HBM-bound kernel); code rows beyond 140 KiB in all
-    // go to the chunked kernel below, which reads them once per workgroup instead of once per wavefront
-    const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
-    if (M <= kDecodeMaxM && M * lds_row <= 140 * 1024) {
+    const GemmPlan plan = plan_gemm(M, L);
+    if (plan.kernel == 0) {
+        const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
         const DecodeArgs d = make_decode_args(q_hi, q_lo, s_hi, s_lo, c_hi, c_lo, lo_sum, M, packed, L, y, ldy,
                                               dbg_acc_hi, dbg_acc_lo, swiglu, lds_row);
         return launch_decode(d, dbg, false, st);
     }
-
-    // A few tens of tokens, and up to 1024 of them where the tiled kernel would leave most
-    // of the chip idle (few tiles, each walking the whole reduction axis alone): the same
-    // single pass over the weights, activation codes chunked through LDS, in slices of
-    // 16 TG tokens (each slice streams the weights for itself, out of the last-level cache
-    // after the first) with SK runs per channel group.  TG and SK are the pair with the
-    // lowest estimate from the measured costs of the kernel: per round of 256 workgroups
-    // 7 us + (0.16, 0.27, 0.42) us per 1 KiB block of a run for TG = (1, 2, 4), and never
-    // less than one pass over the weights at 5 TB/s; a tile costs 10 us + 0.5 us per block.
-    const int blocks = (int)(L.hi_blocks + L.lo_blocks);
-    int tg = 0, sk = 0;
-    double stream_us = 0.0;
-    if (M <= 16 * kStreamMaxM) {
-        const int64_t groups = (N + 15) / 16;
-        const double pass_us = (double)L.total_bytes / 5.0e6;
-        for (int cand_tg = 1; cand_tg <= 4; cand_tg *= 2) {
-            const double per_block = cand_tg == 1 ? 0.16 : (cand_tg == 2 ? 0.27 : 0.42);
-            const int64_t slices = (M + cand_tg * 16 - 1) / (cand_tg * 16);
-            for (int cand_sk = 1; cand_sk * cand_tg <= 8; cand_sk *= 2) {
-                // runs of at least two chunks, at most 2048 of them
-                if (cand_sk > 1 && (groups * cand_sk > 2048 || blocks / cand_sk < 2 * kChunkBlocks)) break;
-                const int64_t sets = (groups * cand_sk + 7) / 8;
-                const int64_t wgs = (sets < 256 ? sets : 256) * slices;
-                const int64_t rounds = ((wgs + 255) / 256) * ((sets + 255) / 256);
-                double us = (double)rounds * (7.0 + per_block * (double)(blocks / cand_sk));
-                if (us < pass_us) us = pass_us;
-                if (tg == 0 || us < stream_us) {
-                    stream_us = us;
-                    tg = cand_tg;
-                    sk = cand_sk;
-                }
-            }
-        }
-    }
-    bool streaming = M <= kStreamMaxM;
-    if (!streaming && tg != 0) {
-        const int64_t tiles = ((M + kBM - 1) / kBM) * ((N + kBN - 1) / kBN);
-        const double tiled_us = (double)((tiles + 255) / 256) * (10.0 + 0.5 * (double)blocks);
-        streaming = stream_us < 0.9 * tiled_us;
-    }
-    if (streaming) {
+    if (plan.kernel == 1) {
+        const int tg = plan.tg, sk = plan.sk;
         const DecodeArgs d = make_decode_args(q_hi, q_lo, s_hi, s_lo, c_hi, c_lo, lo_sum, M, packed, L, y, ldy,
                                               dbg_acc_hi, dbg_acc_lo, swiglu, 0);
         const int slices = (int)((M + tg * 16 - 1) / (tg * 16));  // of tg * 16 tokens
@@ -505,6 +521,18 @@ int resq_quantize_gemm_mixed(const void* x, int64_t ldx, int64_t M, const void* 
     while (R < 8 && R < M && nunits * (2 * R) <= (int64_t)kFusedUnits * kDecodeThreads) R *= 2;
     d.fuse_rows = R;
     return launch_decode(d, false, true, static_cast<hipStream_t>(stream));
+}
+
+int resq_gemm_mixed_plan(int64_t M, int64_t N, int64_t K, int64_t r, int* kernel, int* token_groups,
+                         int* runs) {
+    if (!shape_ok(N, K, r) || M < 1 || M > 0x7FFFFFFF) return RESQ_ERR_SHAPE;
+    if (K - r > kMaxLoWidth || r > kMaxHiWidth) return RESQ_ERR_SHAPE;
+    if (!kernel || !token_groups || !runs) return RESQ_ERR_NULL;
+    const GemmPlan plan = plan_gemm(M, make_weight_layout(N, K, r));
+    *kernel = plan.kernel;
+    *token_groups = plan.tg;
+    *runs = plan.sk;
+    return RESQ_OK;
 }
 
 int resq_gemm_mixed_swiglu(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,

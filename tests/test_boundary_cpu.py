@@ -214,3 +214,35 @@ def test_quantize_gemm_mixed_rejects_bad_arguments():
     assert f(P, 516, 4, P256, 256, 512, 64, P, 256, None) == 3        # ldx not a multiple of 8
     assert f(P, 512, 4, P256, 256, 508, 64, P, 256, None) == 3        # K not a multiple of 8
     assert f(P, 512, 4, P256 + 16, 256, 512, 64, P, 256, None) == 3   # packed not 256-byte aligned
+
+
+# shapes that take every (token groups, runs) pair of the chunked weight-streaming kernel; the GPU
+# parity tests run the same list
+STREAM_PLAN_SHAPES = [
+    ((17, 256, 40, 32), (1, 1, 1)), ((17, 4096, 40, 512), (1, 1, 2)), ((17, 8192, 130, 1024), (1, 1, 4)),
+    ((20, 16384, 130, 2048), (1, 1, 8)), ((130, 520, 4100, 64), (1, 2, 1)), ((64, 4096, 4100, 512), (1, 2, 2)),
+    ((24, 8192, 4100, 1024), (1, 2, 4)), ((300, 256, 4100, 32), (1, 4, 1)), ((130, 4096, 4100, 512), (1, 4, 2)),
+]
+
+
+def test_gemm_mixed_plan():
+    plan = binding.resq_gemm_mixed_plan
+    # the benchmark's workloads
+    assert plan(2048, 4096, 4096, 512) == (2, 0, 0)            # o_proj prefill: tiled
+    assert plan(1, 28672, 8192, 1024) == (0, 1, 1)             # decode, wide layer: one run per group
+    assert plan(16, 28672, 8192, 1024) == (0, 1, 1)
+    assert plan(1, 4096, 4096, 512) == (0, 1, 8)               # narrow layer: reduction axis cut
+    assert plan(16, 8192, 28672, 3584) == (1, 1, 4)            # code rows too long to re-read per wavefront
+    assert plan(64, 28672, 8192, 1024) == (1, 4, 1)            # batched decode, wide layer: one slice
+    assert plan(64, 4096, 4096, 512) == (1, 1, 2)              # ... narrow layer: four slices of 16 tokens
+    assert plan(512, 4096, 4096, 512)[0] == 1 and plan(640, 4096, 4096, 512)[0] == 2
+    assert plan(1025, 1024, 4096, 512) == (2, 0, 0)            # above 1024 tokens always tiled
+    for shape, want in STREAM_PLAN_SHAPES:
+        M, K, N, r = shape
+        assert plan(M, N, K, r) == want, shape
+    f = binding.lib().resq_gemm_mixed_plan
+    import ctypes
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    assert f(0, 256, 256, 32, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 2
+    assert f(4, 256, 256, 33, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 2
+    assert f(4, 256, 256, 32, None, ctypes.byref(b), ctypes.byref(c)) == 1

@@ -306,6 +306,19 @@ def test_quantize_gemm_mixed_one_call_full_size(oracle, rq):
     assert y_within_tolerance(y, ref.y) <= REL_TOL
 
 
+def _stream_plan_shapes():
+    from test_boundary_cpu import STREAM_PLAN_SHAPES
+    return [shape for shape, _ in STREAM_PLAN_SHAPES]
+
+
+@pytest.mark.parametrize("M,K,N,r", _stream_plan_shapes())
+def test_layer_every_token_group_and_run_count(oracle, rq, M, K, N, r):
+    # one shape per (token groups, runs) pair of the chunked kernel (the CPU test pins which)
+    assert rq.resq_gemm_mixed_plan(M, N, K, r)[0] == 1
+    x, w = wl.random_small_case(M * 37 + K + N, M, K, N, r, outliers="first4")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
 def test_layer_batched_decode_full_size(oracle, rq):
     # the decode workload's layer with 64 tokens in flight; every accumulator and output
     s = wl.decode_shape(64)
