@@ -62,28 +62,6 @@ const char* resq_status_string(int status);
  */
 int resq_time_next_kernel(void* start_event, void* stop_event);
 
-/*
- * Measurement aid, not part of the method (for callers that want to know what the
- * GEMM's fraction of the nominal matrix peak is worth on the chip at hand): runs
- * `iters` times eight independent v_mfma_i32_32x32x32_i8 per wavefront, four
- * wavefronts per workgroup, with operand fragments taken from operand_bytes (device,
- * 32 KiB, 16-byte aligned, read once) and nothing else in the loop:
- * 2 * 32^3 * 8 * 4 * iters * workgroups operations.  The caller times it (with
- * resq_time_next_kernel or its own events) and chooses the bytes: the matrix pipes
- * are power-limited, so all-zero, INT4-like and random INT8 operands run at
- * different rates.  sink: one int, device, never written in practice.
- */
-int resq_probe_mfma_int8(const void* operand_bytes, int iters, int workgroups, int* sink, void* stream);
-
-/*
- * Measurement aid, not part of the method: a plain streaming read of the first
- * bytes / 16 * 16 bytes of buf (device, 16-byte aligned) by `workgroups` workgroups of
- * 256 threads with four 16-byte loads in flight per lane; what a kernel that must
- * read that many bytes once can reach on the chip at hand (the generation-stage GEMM
- * reads its packed weights once).  sink: one int, device, never written in practice.
- */
-int resq_probe_hbm_read(const void* buf, size_t bytes, int workgroups, int* sink, void* stream);
-
 /* ---- layout queries (pure host functions) ------------------------------- */
 
 /*
@@ -234,8 +212,9 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
  *   y[m, n]    = bf16( A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n] )
  * Both sums run on the int8 matrix cores (nibbles are widened in registers)
  * inside one kernel; y is written once.  The integer sums are exact: the call
- * accepts r <= 133143 and K - r <= 2^20, so neither 127^2 * r nor the widened
- * low sum 1680 * (K - r) can reach 2^31 (larger groups: RESQ_ERR_SHAPE).
+ * accepts r <= 132104 and K - r <= 2^20, so neither 128 * 127 * r (stored asymmetric
+ * codes reach -128) nor the widened low sum 1680 * (K - r) can reach 2^31 (larger
+ * groups: RESQ_ERR_SHAPE).
  *   q_hi, q_lo, s_hi, s_lo, lo_sum   as written by resq_quantize_act for the same K, r
  *   packed                   as written by resq_pack_weights for the same N, K, r
  *   y        bf16 [M, ldy], ldy >= N                         (written)
@@ -412,7 +391,8 @@ int resq_gemm_mixed_asym(const int8_t* q_hi, const uint8_t* q_lo, const float* s
  *   x, y   bf16 [M, ld], ld >= K
  *   block  power of two dividing col_end - col_begin, <= 8192;
  *          0 selects resq_hadamard_block(col_end - col_begin)
- * col_begin must be even.
+ * Errors: RESQ_ERR_ALIGN unless x and y are 16-byte aligned and ld, col_begin and
+ * col_end - col_begin are multiples of 8 (rows are moved 16 bytes per lane).
  */
 int resq_online_hadamard(const void* x, void* y, int64_t ld, int64_t M, int64_t K,
                          int64_t col_begin, int64_t col_end, int64_t block, void* stream);

@@ -40,8 +40,6 @@ SYMBOLS = {
     "resq_sym_eig_workspace_bytes": (_sz, [_i64]),
     "resq_sym_eig": (C.c_int, [_p, _i64, _i64, C.c_int, _p, _p, _i64, _p, _sz, _p]),
     "resq_project_rows": (C.c_int, [_p, C.c_int, _i64, _i64, _i64, _p, _i64, _i64, _p, C.c_int, _i64, _p]),
-    "resq_probe_mfma_int8": (C.c_int, [_p, C.c_int, C.c_int, _p, _p]),
-    "resq_probe_hbm_read": (C.c_int, [_p, _sz, C.c_int, _p, _p]),
     "resq_project_heads": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _i64, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
     "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),

@@ -12,7 +12,6 @@
 #include "resq_hadamard.hip.h"
 #include "resq_headproj.hip.h"
 #include "resq_layout.h"
-#include "resq_probe.hip.h"
 #include "resq_quantize.hip.h"
 
 using namespace resq;
@@ -21,7 +20,7 @@ namespace {
 
 constexpr int64_t kMaxK = 1 << 20;
 constexpr int64_t kMaxLoWidth = 1 << 20;  // 1680 * (K - r) < 2^31 (widened low sums)
-constexpr int64_t kMaxHiWidth = 133143;  // 127^2 * r < 2^31
+constexpr int64_t kMaxHiWidth = 132104;  // 128 * 127 * r < 2^31 (stored asymmetric codes reach -128)
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -714,25 +713,6 @@ int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigv
         }
     }
     launch(eig_finish_kernel, dim3((unsigned)n), dim3(kEigThreads), 0, st, e, eigvals, p, ldp);
-    return launch_status();
-}
-
-int resq_probe_mfma_int8(const void* operand_bytes, int iters, int workgroups, int* sink, void* stream) {
-    if (iters < 1 || iters > (1 << 24) || workgroups < 1 || workgroups > 65536) return RESQ_ERR_SHAPE;
-    if (!operand_bytes || !sink) return RESQ_ERR_NULL;
-    if (!aligned(operand_bytes, 16) || !aligned(sink, 4)) return RESQ_ERR_ALIGN;
-    launch(probe_mfma_int8_kernel, dim3((unsigned)workgroups), dim3(kProbeThreads), 0,
-           static_cast<hipStream_t>(stream), iters, static_cast<const v4i*>(operand_bytes), sink);
-    return launch_status();
-}
-
-int resq_probe_hbm_read(const void* buf, size_t bytes, int workgroups, int* sink, void* stream) {
-    if (bytes < 16 || workgroups < 1 || workgroups > (1 << 20)) return RESQ_ERR_SHAPE;
-    if (!buf || !sink) return RESQ_ERR_NULL;
-    if (!aligned(buf, 16) || !aligned(sink, 4)) return RESQ_ERR_ALIGN;
-    launch(probe_hbm_read_kernel, dim3((unsigned)workgroups), dim3(kProbeThreads), 0,
-           static_cast<hipStream_t>(stream), static_cast<const uint4*>(buf), bytes / 16,
-           reinterpret_cast<uint32_t*>(sink));
     return launch_status();
 }
 

@@ -2,10 +2,15 @@
 //   A_hi = q_hi * w_hi^T over the high group, A_lo = q_lo * w_lo^T over the low
 //   group, y = bf16(A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n]).
 //
-// Tiling.  One workgroup of 4 wavefronts owns a 128 (tokens) x 256 (channels)
-// output tile; each wavefront owns 64 x 128 of it as 2 x 4 tiles of the
+// Tiling.  One workgroup of 8 wavefronts owns a 128 (tokens) x 256 (channels)
+// output tile; each wavefront owns 64 x 64 of it as 2 x 2 tiles of the
 // 32x32x32 int8 matrix-core instruction, the weights as its first operand so
-// that a lane ends up with four consecutive channels of one token.
+// that a lane ends up with four consecutive channels of one token.  Two
+// wavefronts share a SIMD (256 registers each): while one waits for the matrix
+// pipe, the other issues its vector-ALU, LDS and memory instructions, which a
+// single wavefront per SIMD cannot hide behind its own matrix instructions
+// (measured: about five other instructions fit behind one matrix instruction
+// of a lone wavefront, and the low group needs more).
 //
 // Stages.  The reduction axis is walked in stages of 64 bytes per row: 64 int8
 // codes of the high group or 128 nibble codes of the low group, i.e. two
@@ -13,12 +18,16 @@
 // global->LDS copy is the same for both.  Six LDS buffers of 24 KiB hold the
 // stage being multiplied, the next one, and up to four in flight.
 //
-// Global -> LDS.  The direct-to-LDS load moves 16 bytes per lane to a
+// Global -> LDS.  Buffer loads with the LDS flag move 16 bytes per lane to a
 // wave-uniform LDS base plus 16 * lane, so the LDS image is fixed by which
-// global address each lane asks for.  A block (16 rows x 64 bytes) is stored
-// with piece kc (16 bytes) of row r at unit 4 r + (kc ^ (r >> 2)): four
-// consecutive lanes fetch one row's 64 contiguous bytes, and the 16 lanes that
-// later read the same piece of 16 different rows hit 16 different bank groups.
+// global address each lane asks for; the address is a buffer resource (scalar
+// registers, fixed per tile) plus a per-lane offset that never changes plus a
+// scalar offset that advances per stage, so a load costs no vector-ALU work
+// (and measurably less issue time than the same load with a 64-bit address).
+// A block (16 rows x 64 bytes) is stored with piece kc (16 bytes) of row r at
+// unit 4 r + (kc ^ (r >> 2)): four consecutive lanes fetch one row's 64
+// contiguous bytes, and the 16 lanes that later read the same piece of 16
+// different rows hit 16 different bank groups.
 //
 // LDS -> registers.  Operand reads are issued as untracked ds_read_b128 (inline
 // asm) and paired with an explicit wait: reads the compiler can see would each
@@ -26,16 +35,15 @@
 //
 // Software pipeline.  Low steps: read(k+2) | widen(k+1) | multiply(k), so that
 // the matrix instructions of step k never wait for the vector ALU work of
-// their own operands.  High steps need no widening: read(k+1) lands in the
-// operand registers themselves while step k is multiplied.  The epilogue's
-// per-channel and per-token constants (3.5 KiB) are fetched into LDS by the
-// first loads of the kernel.
+// their own operands.  High steps need no widening: the reads of a whole stage
+// land in operand registers while the stage before it is multiplied.  The
+// epilogue's per-channel and per-token constants (3.5 KiB) are fetched into
+// LDS by the first loads of the kernel.
 //
 // The low group.  A lane's 16 packed bytes hold 32 codes, and each nibble is
-// widened to an int8 operand with one AND (the vector ALU has room for about
-// four instructions per matrix instruction, so every one counts).  In an
-// activation byte the low nibble is c_even + 8 and the high nibble c_odd; in a
-// weight byte the high nibble is w_even and the low nibble w_odd + 8.  Then
+// widened to an int8 operand with one AND.  In an activation byte the low
+// nibble is c_even + 8 and the high nibble c_odd; in a weight byte the high
+// nibble is w_even and the low nibble w_odd + 8.  Then
 //   (pa & 0x0F) * (pw & 0xF0) = (c_even + 8) * 16 w_even
 //   (pa & 0xF0) * (pw & 0x0F) = 16 c_odd * (w_odd + 8)
 // feed two matrix-core instructions, and the accumulator ends as
@@ -44,9 +52,9 @@
 // (written by the quantizer), so A_lo is recovered exactly.
 //
 // Two scale pairs, one output write.  Each group has its own int32 tile in
-// accumulation registers (2 x 128 per lane); both are folded into the output
+// accumulation registers (2 x 64 per lane); both are folded into the output
 // at the end, and y is written once, through LDS so that every store
-// instruction writes whole 256-byte row segments.
+// instruction writes whole 512-byte row segments.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -62,7 +70,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kGemmThreads = 256;
+constexpr int kGemmThreads = 512;  // 8 wavefronts, two per SIMD
 constexpr int kBM = 128;
 constexpr int kBN = 256;
 constexpr int kStageABytes = kBM * kRowBytes;  // 8 KiB = 8 blocks
@@ -70,8 +78,8 @@ constexpr int kStageBBytes = kBN * kRowBytes;  // 16 KiB = 16 blocks
 constexpr int kStageBytes = kStageABytes + kStageBBytes;
 constexpr int kNumBuf = 6;
 constexpr int kPrefetch = kNumBuf - 1;  // stages requested ahead of the one being multiplied
-constexpr int kLoadsPerStage = (kBM + kBN) / kRowsPerBlock / 4;  // per lane: 6
-constexpr int kOutRowBytes = 128 * 2 + 16;  // one wave-tile row of bf16 in LDS, padded
+constexpr int kLoadsPerStage = (kBM + kBN) / kRowsPerBlock / 8;  // per wavefront: 3 (one activation block, two weight blocks)
+constexpr int kOutRowBytes = kBN * 2 + 16;  // one tile row of bf16 in LDS, padded
 // After the stage buffers: the tile's per-channel and per-token constants of the
 // epilogue, copied there by the first loads of the kernel.
 constexpr int kMetaOff = kNumBuf * kStageBytes;
@@ -174,33 +182,35 @@ __device__ __forceinline__ void lds_read4(int& dst, uint32_t addr) {
 }
 
 // packed fragments of one reduction step as read from LDS:
-// 2 activation tiles and 4 weight tiles of 32 rows x 32 bytes
+// 2 activation tiles and 2 weight tiles of 32 rows x 32 bytes
 struct Packed {
     v4i fa[2];
-    v4i fb[4];
+    v4i fb[2];
 };
-// matrix-core operands of one reduction step: for a low step the even-code and
-// odd-code halves of every fragment; for a high step only the e members are used
+// matrix-core operands of one low reduction step: the even-code and the odd-code half of
+// every fragment
 struct Operands {
-    v4i ae[2], ao[2];
-    v4i be[4], bo[4];
+    Packed e, o;
 };
 
-// Wait until every LDS read has returned.  The registers are tied to the wait
-// as in/out operands so that no use of them can be scheduled above it.
-__device__ __forceinline__ void lds_wait_all(Packed& f) {
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(f.fa[0]), "+v"(f.fa[1]), "+v"(f.fb[0]), "+v"(f.fb[1]), "+v"(f.fb[2]),
-                   "+v"(f.fb[3]));
+// Wait until at most N LDS reads of this wavefront are outstanding (they return in order).
+// The four fragments are tied to the wait as in/out operands so that no use of them can be
+// scheduled above it.
+template <int N>
+__device__ __forceinline__ void lds_wait(v4i& a0, v4i& a1, v4i& b0, v4i& b1) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a0), "+v"(a1), "+v"(b0), "+v"(b1) : "n"(N));
 }
 
-// Wait until at most N LDS reads are outstanding (they return in order); ties the
-// e members of an operand set, which high steps read into directly.
-template <int N>
-__device__ __forceinline__ void lds_wait_operands(Operands& u) {
-    asm volatile("s_waitcnt lgkmcnt(%6)"
-                 : "+v"(u.ae[0]), "+v"(u.ae[1]), "+v"(u.be[0]), "+v"(u.be[1]), "+v"(u.be[2]), "+v"(u.be[3])
-                 : "n"(N));
+// buffer resource over all of memory from `base` on (raw, no stride, no bounds): the loads
+// below address base + per-lane offset + scalar offset
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
+}
+// direct-to-LDS buffer load: lane l's 16 bytes at base + voff + soff land at lds_wave_base + 16 l
+__device__ __forceinline__ void buffer_load_to_lds_16B(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t soff,
+                                                       uint8_t* lds_wave_base) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds_wave_base, 16,
+                                             (int)voff, (int)soff, 0, 0);
 }
 
 // blockIdx -> (tile_m, tile_n).  Consecutive workgroup ids land on different
@@ -247,20 +257,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int wm = wave >> 1;  // 0..1: 64-token half of the tile
-    const int wn = wave & 1;   // 0..1: 128-channel half of the tile
+    const int wm = wave >> 2;  // 0..1: 64-token half of the tile
+    const int wn = wave & 3;   // 0..3: 64-channel quarter of the tile
     int tile_m, tile_n;
     tile_of_block(a, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * kBM;
     const int64_t n0 = (int64_t)tile_n * kBN;
-    const int S_hi = a.stages_hi, S_lo = a.stages_lo, S = S_hi + S_lo;
+    const int S_hi = a.stages_hi, S_lo = a.stages_lo, S = S_hi + S_lo;  // S_hi and S_lo are even
     const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
     const uint16_t* sw_lo = sw_hi + a.L.n_pad;
     const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
     const bool asym = a.c_hi != nullptr || a.c_lo != nullptr;
 
     // ---- epilogue constants -> LDS ---------------------------------------------
-    // These are the oldest loads of every wave, so the first wait for a stage
+    // These are the oldest loads of their waves, so the first wait for a stage
     // covers them.  Token rows past M repeat the last row (never stored).
     if (wave == 0) {
         load_to_lds_16B((lane < 32 ? sw_hi : sw_lo) + n0 + (lane & 31) * 8, lds + kMetaOff + kMetaSwHi);
@@ -268,7 +278,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     } else if (wave == 1) {
         load_to_lds_16B(even_sum + n0 + lane * 4, lds + kMetaOff + kMetaEven);
         if (asym) load_to_lds_16B(even_sum + 2 * a.L.n_pad + n0 + lane * 4, lds + kMetaOff + kMetaWsumLo);
-    } else {
+    } else if (wave < 4) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             int64_t m = m0 + h * 64 + lane;
@@ -286,53 +296,58 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
 
     // ---- global -> LDS copy --------------------------------------------------
     // One load instruction fills one block: lane l fetches row l / 4, piece
-    // (l % 4) ^ (l / 16).  Wave w copies A blocks 2w, 2w+1 and B blocks 4w..4w+3
-    // of each stage.  Token rows past M are clamped to the last row (their
-    // results are never stored).  The weight blocks of one 16-channel group are
-    // contiguous over all stages, high ones first.  Every address is a
-    // wave-uniform base (scalar registers, advanced per stage) plus a 32-bit
-    // per-lane offset that never changes.
-    uint32_t a_voff_hi[2], a_voff_lo[2], b_voff;
-    const uint8_t* a_base_hi = a.q_hi + m0 * a.ld_hi;
-    const uint8_t* a_base_lo = a.q_lo + m0 * a.ld_lo - (int64_t)S_hi * kRowBytes;
-    const uint8_t* b_base = a.packed + (n0 / 16 + wave * 4) * a.L.group_bytes;
+    // (l % 4) ^ (l / 16).  Wave w copies A block w and B blocks 2w, 2w+1 of each
+    // stage.  Token rows past M are clamped to the last row (their results are
+    // never stored).  The weight blocks of one 16-channel group are contiguous
+    // over all stages, high ones first.  Every address is a buffer resource
+    // (wave-uniform, fixed) plus a per-lane offset that never changes plus a
+    // scalar offset that depends on the stage alone.
+    uint32_t a_voff_hi, a_voff_lo, b_voff[2];
     {
         const int r = lane >> 2, kc = (lane & 3) ^ (lane >> 4);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int64_t row = (wave * 2 + i) * 16 + r;
-            row = m0 + row < a.M ? row : a.M - 1 - m0;
-            a_voff_hi[i] = (uint32_t)(row * a.ld_hi + kc * 16);
-            a_voff_lo[i] = (uint32_t)(row * a.ld_lo + kc * 16);
-        }
-        b_voff = r * kRowBytes + kc * 16;
+        int64_t row = wave * 16 + r;
+        row = m0 + row < a.M ? row : a.M - 1 - m0;
+        a_voff_hi = (uint32_t)(row * a.ld_hi + kc * 16);
+        a_voff_lo = (uint32_t)(row * a.ld_lo + kc * 16);
+        b_voff[0] = r * kRowBytes + kc * 16;
+        b_voff[1] = b_voff[0] + (uint32_t)a.L.group_bytes;
     }
-    // load K of stage sg (0 .. S-1, high stages first) into buffer buf; K = 0, 1: A blocks, 2..5: B blocks
+    // the low rows are addressed by the global stage index too: their resource starts S_hi stages early
+    const __amdgpu_buffer_rsrc_t rs_a_hi = make_rsrc(a.q_hi + m0 * a.ld_hi);
+    const __amdgpu_buffer_rsrc_t rs_a_lo = make_rsrc(a.q_lo + m0 * a.ld_lo - (int64_t)S_hi * kRowBytes);
+    const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(a.packed + (n0 / 16 + wave * 2) * a.L.group_bytes);
+    // load K of stage sg (0 .. S-1, high stages first) into buffer buf; K = 0: the A block, 1, 2: the B blocks
     auto issue_load = [&](auto k, int sg, int buf) __attribute__((always_inline)) {
         constexpr int K = decltype(k)::value;
         uint8_t* dst = lds + buf * kStageBytes;
-        if constexpr (K < 2) {
+        if constexpr (K == 0) {
             const bool lo = sg >= S_hi;
-            const uint8_t* base = (lo ? a_base_lo : a_base_hi) + (int64_t)sg * kRowBytes;
-            load_to_lds_16B(base + (lo ? a_voff_lo[K] : a_voff_hi[K]), dst + (wave * 2 + K) * kBlockBytes);
+            buffer_load_to_lds_16B(lo ? rs_a_lo : rs_a_hi, lo ? a_voff_lo : a_voff_hi, (uint32_t)sg * kRowBytes,
+                                   dst + wave * kBlockBytes);
         } else {
-            const uint8_t* base = b_base + (K - 2) * a.L.group_bytes + (int64_t)sg * kBlockBytes;
-            // the lane offset is made opaque here so that it is not folded into a per-lane
-            // 64-bit pointer outside the loop: the load takes a scalar base plus a 32-bit offset
-            uint32_t voff = b_voff;
-            asm volatile("" : "+v"(voff));
-            load_to_lds_16B(base + voff, dst + kStageABytes + (wave * 4 + K - 2) * kBlockBytes);
+            buffer_load_to_lds_16B(rs_b, b_voff[K - 1], (uint32_t)sg * kBlockBytes,
+                                   dst + kStageABytes + (wave * 2 + K - 1) * kBlockBytes);
         }
+    };
+    // the same for a stage known to be a low one (no selection of the activation rows)
+    auto issue_load_lo = [&](auto k, int sg, int buf) __attribute__((always_inline)) {
+        constexpr int K = decltype(k)::value;
+        uint8_t* dst = lds + buf * kStageBytes;
+        if constexpr (K == 0)
+            buffer_load_to_lds_16B(rs_a_lo, a_voff_lo, (uint32_t)sg * kRowBytes, dst + wave * kBlockBytes);
+        else
+            buffer_load_to_lds_16B(rs_b, b_voff[K - 1], (uint32_t)sg * kBlockBytes,
+                                   dst + kStageABytes + (wave * 2 + K - 1) * kBlockBytes);
     };
 
     // ---- accumulators ----------------------------------------------------------
     // One int32 tile per group, both in accumulation registers for the whole
-    // kernel (2 x 128), folded into the output together at the end.
+    // kernel (2 x 64), folded into the output together at the end.
     // acc[j][i]: channels 32 j.., tokens 32 i.. of the wave tile.  Lane l holds
     // token (l % 32) and, in element v, channel 8 (v / 4) + 4 (l / 32) + v % 4.
-    v16i acc_hi[4][2], acc_lo[4][2];
+    v16i acc_hi[2][2], acc_lo[2][2];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -343,10 +358,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
 
     // The tile that a loop does not touch stays where it is, in accumulation
     // registers: stating so in every stage keeps the register allocator from
-    // moving it to ordinary registers and back around the loops (128 moves a time).
-    auto park = [&](v16i (&acc)[4][2]) __attribute__((always_inline)) {
+    // moving it to ordinary registers and back around the loops.
+    auto park = [&](v16i (&acc)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(acc[j][i]));
     };
@@ -363,45 +378,44 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             const int kc = 2 * st + g;
             const uint32_t off = (R >> 4) * kBlockBytes + (4 * r + (kc ^ (r >> 2))) * 16;
             a_off[st] = lds0 + wm * (4 * kBlockBytes) + off;
-            b_off[st] = lds0 + kStageABytes + wn * (8 * kBlockBytes) + off;
+            b_off[st] = lds0 + kStageABytes + wn * (4 * kBlockBytes) + off;
         }
     }
-    // read K of a step: K = 0, 1: activation fragments, 2..5: weight fragments
+    // read K of a step: K = 0, 1: activation fragments, 2, 3: weight fragments
     auto read_frag = [&](auto k, Packed& f, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
         constexpr int K = decltype(k)::value;
         if constexpr (K < 2) lds_read16<K * 2 * kBlockBytes>(f.fa[K], aa);
         else lds_read16<(K - 2) * 2 * kBlockBytes>(f.fb[K - 2], bb);
     };
-    // the same read into the e members of an operand set (high steps need no widening)
-    auto read_operand = [&](auto k, Operands& u, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
-        constexpr int K = decltype(k)::value;
-        if constexpr (K < 2) lds_read16<K * 2 * kBlockBytes>(u.ae[K], aa);
-        else lds_read16<(K - 2) * 2 * kBlockBytes>(u.be[K - 2], bb);
-    };
-    // piece P (0..11) of the widening of one low step's fragments: one AND over a fragment
+    // piece P (0..7) of the widening of one low step's fragments: one AND over a fragment
     auto widen_piece = [&](auto p, const Packed& f, Operands& u) __attribute__((always_inline)) {
         constexpr int P = decltype(p)::value;
-        if constexpr (P < 2) u.ae[P] = f.fa[P] & (int)0x0F0F0F0F;           // even columns: code + 8
-        else if constexpr (P < 4) u.ao[P - 2] = f.fa[P - 2] & (int)0xF0F0F0F0;  // odd columns: 16 * code
-        else if constexpr (P < 8) u.be[P - 4] = f.fb[P - 4] & (int)0xF0F0F0F0;  // even columns: 16 * code
-        else u.bo[P - 8] = f.fb[P - 8] & (int)0x0F0F0F0F;                        // odd columns: code + 8
+        if constexpr (P < 2) u.e.fa[P] = f.fa[P] & (int)0x0F0F0F0F;               // even columns: code + 8
+        else if constexpr (P < 4) u.e.fb[P - 2] = f.fb[P - 2] & (int)0xF0F0F0F0;  // even columns: 16 * code
+        else if constexpr (P < 6) u.o.fa[P - 4] = f.fa[P - 4] & (int)0xF0F0F0F0;  // odd columns: 16 * code
+        else u.o.fb[P - 6] = f.fb[P - 6] & (int)0x0F0F0F0F;                        // odd columns: code + 8
     };
-    // matrix instruction Q of a step (8 per high step, 16 per low step), in an
-    // order that keeps two instructions on the same accumulator eight apart
-    auto mfma = [&](auto q, const Operands& u, v16i (&acc)[4][2]) __attribute__((always_inline)) {
+    // matrix instruction Q of a low step (8 of them): the four products of the even halves,
+    // then those of the odd halves, so that two instructions on one accumulator are four apart
+    auto mfma_lo = [&](auto q, const Operands& u) __attribute__((always_inline)) {
         constexpr int Q = decltype(q)::value;
-        constexpr int j = (Q & 7) >> 1, i = Q & 1;
-        if constexpr (Q < 8)
-            acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.be[j], u.ae[i], acc[j][i], 0, 0, 0);
+        constexpr int j = (Q >> 1) & 1, i = Q & 1;
+        if constexpr (Q < 4)
+            acc_lo[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.e.fb[j], u.e.fa[i], acc_lo[j][i], 0, 0, 0);
         else
-            acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.bo[j], u.ao[i], acc[j][i], 0, 0, 0);
+            acc_lo[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.o.fb[j], u.o.fa[i], acc_lo[j][i], 0, 0, 0);
+    };
+    // matrix instruction Q of a high step (4 of them), operands as they were read
+    auto mfma_hi = [&](auto q, const Packed& f) __attribute__((always_inline)) {
+        constexpr int Q = decltype(q)::value;
+        constexpr int j = (Q >> 1) & 1, i = Q & 1;
+        acc_hi[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.fb[j], f.fa[i], acc_hi[j][i], 0, 0, 0);
     };
 
     // ---- epilogue pieces -------------------------------------------------------------
     // Lane coordinates inside the tile: token tl + 32 i, channel cl + 32 j + 8 vq + vr.
     const int tl = wm * 64 + (lane & 31);
-    const int cl = wn * 128 + (lane >> 5) * 4;
-    uint8_t* const out_stage = lds + wave * (64 * kOutRowBytes);
+    const int cl = wn * 64 + (lane >> 5) * 4;
 
     // Fold both integer tiles into the output:
     //   y = A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n]
@@ -448,7 +462,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
             }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < 2; ++j) {
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
                 const int c = cl + 32 * j + 8 * vq;
@@ -503,13 +517,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                             }
                         }
                     }
-                    const int row = 32 * i + (lane & 31);
-                    const int col = 32 * j + 8 * vq + 4 * (lane >> 5);
+                    const int row = tl + 32 * i;
+                    const int col = cl + 32 * j + 8 * vq;
                     if constexpr (GLU)
-                        *reinterpret_cast<uint32_t*>(out_stage + row * kOutRowBytes + col) =
+                        *reinterpret_cast<uint32_t*>(lds + row * kOutRowBytes + col) =
                             pack_bf16(silu_f32(val[0]) * val[1], silu_f32(val[2]) * val[3]);
                     else
-                        *reinterpret_cast<uint2*>(out_stage + row * kOutRowBytes + col * 2) =
+                        *reinterpret_cast<uint2*>(lds + row * kOutRowBytes + col * 2) =
                             make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
                 }
             }
@@ -521,46 +535,45 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     {
         Packed px, py;
         Operands ux, uy;
+        // the four register sets of the high stages: two stages' worth of operands, used as read
+        Packed& h0 = px;
+        Packed& h1 = py;
+        Packed& h2 = ux.e;
+        Packed& h3 = uy.e;
         const int ahead = S < kPrefetch ? S : kPrefetch;
         for (int i = 0; i < ahead; ++i)
             static_for<kLoadsPerStage>([&](auto k) __attribute__((always_inline)) { issue_load(k, i, i); });
         wait_stage_and_barrier(ahead - 1);  // stage 0 (and the epilogue constants) have landed everywhere
-        if (S_hi > 0) {
-            // high stages read straight into the operand registers
-            static_for<6>([&](auto k) __attribute__((always_inline)) { read_operand(k, ux, a_off[0], b_off[0]); });
-        } else {
-            static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, px, a_off[0], b_off[0]); });
-            lds_wait_all(px);
-            static_for<6>([&](auto k) __attribute__((always_inline)) { read_frag(k, py, a_off[1], b_off[1]); });
-            static_for<12>([&](auto p) __attribute__((always_inline)) { widen_piece(p, px, ux); });
+        static_for<4>([&](auto k) __attribute__((always_inline)) { read_frag(k, px, a_off[0], b_off[0]); });
+        static_for<4>([&](auto k) __attribute__((always_inline)) { read_frag(k, py, a_off[1], b_off[1]); });
+        if (S_hi == 0) {
+            lds_wait<4>(px.fa[0], px.fa[1], px.fb[0], px.fb[1]);
+            static_for<8>([&](auto p) __attribute__((always_inline)) { widen_piece(p, px, ux); });
         }
 
         int buf = 0;
-        // A low stage = two pipeline slots (reduction steps) of 16 matrix
+        // A low stage = two pipeline slots (reduction steps) of 8 matrix
         // instructions.  ISSUE: this stage requests stage sg + kPrefetch (every
         // stage but the last kPrefetch ones).  A slot is a fixed sequence of groups,
         // one matrix instruction each, with the slot's other work dealt out among
-        // them so that it issues in the shadow of the matrix pipeline (about four
-        // vector ALU instructions, or a read and a load, fit behind one matrix
-        // instruction):
-        //   slot 0: multiply step 0 | wait + barrier after 4 groups | then per group one
-        //           LDS read of the next stage's step 0 and one piece of step 1's widening
-        //   slot 1: multiply step 1 | per group one LDS read of the next stage's step 1 and
-        //           one piece of the next step 0's widening
-        // and the stage's six global loads at even distances after the barrier.
+        // them so that it issues while the SIMD's matrix pipe is busy with this or
+        // the other wavefront's instructions:
+        //   slot 0: multiply step 0 | wait + barrier after 2 groups | then the four LDS reads
+        //           of the next stage's step 0 and the widening of step 1
+        //   slot 1: multiply step 1 | the four LDS reads of the next stage's step 1 and the
+        //           widening of the next step 0
+        // and the stage's three global loads after the barrier.
         // Invariant at entry: ux = operands of (sg, step 0); the reads of (sg, step 1)
         // into py are in flight.
         auto stage_lo = [&](auto issue, int sg) __attribute__((always_inline)) {
             constexpr bool ISSUE = decltype(issue)::value;
-            constexpr int NM = 16;               // matrix instructions per step
-            constexpr int PRE = 4;               // ... of which this many go before the barrier
-            constexpr int LD_EVERY = (NM - PRE) / 3;  // a global load every so many groups, three per slot
             const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
             const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
             const uint32_t shift = nxt * kStageBytes;
             park(acc_hi);
             __builtin_amdgcn_sched_barrier(0);
-            static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, ux, acc_lo); });
+            mfma_lo(IC<0>{}, ux);
+            mfma_lo(IC<1>{}, ux);
             __builtin_amdgcn_sched_barrier(0);
             // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
             // stages sg + 2 .. sg + 4 may stay in flight
@@ -570,95 +583,88 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                 const int rem = S - 2 - sg;
                 wait_stage_and_barrier(rem > 3 ? 3 : rem);
             }
-            lds_wait_all(py);
+            lds_wait<0>(py.fa[0], py.fa[1], py.fb[0], py.fb[1]);
             __builtin_amdgcn_sched_barrier(0);
-            static_for<NM - PRE>([&](auto g) __attribute__((always_inline)) {
+            static_for<6>([&](auto g) __attribute__((always_inline)) {
                 constexpr int G = decltype(g)::value;
-                mfma(IC<PRE + G>{}, ux, acc_lo);
+                mfma_lo(IC<2 + G>{}, ux);
                 // past the last stage the reads fetch stale LDS: harmless
-                if constexpr (G < 6) read_frag(g, px, a_off[0] + shift, b_off[0] + shift);
+                if constexpr (G < 4) read_frag(g, px, a_off[0] + shift, b_off[0] + shift);
                 widen_piece(g, py, uy);
-                if constexpr (ISSUE && G % LD_EVERY == LD_EVERY - 1)
-                    issue_load(IC<G / LD_EVERY>{}, sg + kPrefetch, prv);
+                if constexpr (G == 4) widen_piece(IC<6>{}, py, uy);
+                if constexpr (G == 5) widen_piece(IC<7>{}, py, uy);
+                if constexpr (ISSUE && G == 4) issue_load_lo(IC<0>{}, sg + kPrefetch, prv);
                 __builtin_amdgcn_sched_barrier(0);
             });
-            static_for<PRE>([&](auto q) __attribute__((always_inline)) { mfma(q, uy, acc_lo); });
+            mfma_lo(IC<0>{}, uy);
+            read_frag(IC<0>{}, py, a_off[1] + shift, b_off[1] + shift);
             __builtin_amdgcn_sched_barrier(0);
-            lds_wait_all(px);
+            mfma_lo(IC<1>{}, uy);
+            read_frag(IC<1>{}, py, a_off[1] + shift, b_off[1] + shift);
+            if constexpr (ISSUE) issue_load_lo(IC<1>{}, sg + kPrefetch, prv);
             __builtin_amdgcn_sched_barrier(0);
-            static_for<NM - PRE>([&](auto g) __attribute__((always_inline)) {
+            lds_wait<2>(px.fa[0], px.fa[1], px.fb[0], px.fb[1]);   // px is older than the two reads of py
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<6>([&](auto g) __attribute__((always_inline)) {
                 constexpr int G = decltype(g)::value;
-                mfma(IC<PRE + G>{}, uy, acc_lo);
-                if constexpr (G < 6) read_frag(g, py, a_off[1] + shift, b_off[1] + shift);
+                mfma_lo(IC<2 + G>{}, uy);
+                if constexpr (G < 2) read_frag(IC<2 + G>{}, py, a_off[1] + shift, b_off[1] + shift);
                 widen_piece(g, px, ux);
-                if constexpr (ISSUE && G % LD_EVERY == LD_EVERY - 1)
-                    issue_load(IC<3 + G / LD_EVERY>{}, sg + kPrefetch, prv);
+                if constexpr (G == 4) widen_piece(IC<6>{}, px, ux);
+                if constexpr (G == 5) widen_piece(IC<7>{}, px, ux);
+                if constexpr (ISSUE && G == 3) issue_load_lo(IC<2>{}, sg + kPrefetch, prv);
                 __builtin_amdgcn_sched_barrier(0);
             });
             buf = nxt;
         };
-        // A high stage needs no widening, so its reads go straight into the operand
-        // registers of the step after the one being multiplied (ux and uy take
-        // turns) and the Packed sets are not used.  Invariant at entry: the reads
-        // of (sg, step 0) into ux have been issued.  Per slot, 8 matrix
-        // instructions M0..M7 with the 6 reads of the next step behind M0..M5 and
-        // the waits placed so that each instruction only waits for its own
-        // operands (activations first, then the weight fragments in order):
-        //   before M0: <= 3 reads of this step outstanding; before M2: <= 2, and so
-        //   on, each plus the reads of the next step issued by then.
-        auto stage_hi = [&](auto issue, int sg) __attribute__((always_inline)) {
-            constexpr bool ISSUE = decltype(issue)::value;
+        // A high stage needs no widening: 2 x 4 matrix instructions on the fragments as they
+        // were read.  Its eight reads were issued during the stage before it (after that
+        // stage's barrier, which says that this stage has landed), into the register sets
+        // (u0, u1); this stage issues the next stage's reads into (f0, f1).  The last high
+        // stage thereby leaves the packed bytes of the first low stage in px and py.
+        // Invariant at entry: the reads of (sg, step 0) into u0 and of (sg, step 1) into u1
+        // have been issued, in this order.
+        auto stage_hi = [&](Packed& u0, Packed& u1, Packed& f0, Packed& f1, int sg) __attribute__((always_inline)) {
             const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
             const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
-            const uint32_t here = buf * kStageBytes, shift = nxt * kStageBytes;
+            const uint32_t shift = nxt * kStageBytes;
+            const bool issue = sg + kPrefetch < S;
             park(acc_lo);
-            auto slot = [&](auto second, Operands& use, Operands& fill, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
-                constexpr bool SECOND = decltype(second)::value;
-                __builtin_amdgcn_sched_barrier(0);
-                lds_wait_operands<3>(use);
-                mfma(IC<0>{}, use, acc_hi);
-                read_operand(IC<0>{}, fill, aa, bb);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma(IC<1>{}, use, acc_hi);
-                read_operand(IC<1>{}, fill, aa, bb);
-                __builtin_amdgcn_sched_barrier(0);
-                if constexpr (!SECOND) {
-                    // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
-                    // stages sg + 2 .. sg + 4 may stay in flight
-                    if constexpr (ISSUE) {
-                        wait_loads_and_barrier<3 * kLoadsPerStage>();
-                    } else {
-                        const int rem = S - 2 - sg;
-                        wait_stage_and_barrier(rem > 3 ? 3 : rem);
-                    }
-                }
-                lds_wait_operands<2 + 2>(use);
-                mfma(IC<2>{}, use, acc_hi);
-                read_operand(IC<2>{}, fill, aa, bb);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma(IC<3>{}, use, acc_hi);
-                read_operand(IC<3>{}, fill, aa, bb);
-                if constexpr (ISSUE) issue_load(IC<SECOND ? 3 : 0>{}, sg + kPrefetch, prv);
-                __builtin_amdgcn_sched_barrier(0);
-                lds_wait_operands<1 + 4>(use);
-                mfma(IC<4>{}, use, acc_hi);
-                read_operand(IC<4>{}, fill, aa, bb);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma(IC<5>{}, use, acc_hi);
-                read_operand(IC<5>{}, fill, aa, bb);
-                if constexpr (ISSUE) issue_load(IC<SECOND ? 4 : 1>{}, sg + kPrefetch, prv);
-                __builtin_amdgcn_sched_barrier(0);
-                lds_wait_operands<0 + 6>(use);
-                mfma(IC<6>{}, use, acc_hi);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma(IC<7>{}, use, acc_hi);
-                if constexpr (ISSUE) issue_load(IC<SECOND ? 5 : 2>{}, sg + kPrefetch, prv);
-                __builtin_amdgcn_sched_barrier(0);
-            };
-            // slot 0 multiplies (sg, step 0) and reads (sg, step 1); slot 1 multiplies that
-            // and reads (sg + 1, step 0) -- stale LDS past the last stage, harmless
-            slot(std::false_type{}, ux, uy, a_off[1] + here, b_off[1] + here);
-            slot(std::true_type{}, uy, ux, a_off[0] + shift, b_off[0] + shift);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_wait<4>(u0.fa[0], u0.fa[1], u0.fb[0], u0.fb[1]);
+            mfma_hi(IC<0>{}, u0);
+            mfma_hi(IC<1>{}, u0);
+            __builtin_amdgcn_sched_barrier(0);
+            // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1
+            {
+                const int rem = S - 2 - sg;
+                wait_stage_and_barrier(rem > 3 ? 3 : rem);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_hi(IC<2>{}, u0);
+            read_frag(IC<0>{}, f0, a_off[0] + shift, b_off[0] + shift);
+            read_frag(IC<1>{}, f0, a_off[0] + shift, b_off[0] + shift);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_hi(IC<3>{}, u0);
+            read_frag(IC<2>{}, f0, a_off[0] + shift, b_off[0] + shift);
+            read_frag(IC<3>{}, f0, a_off[0] + shift, b_off[0] + shift);
+            if (issue) issue_load(IC<0>{}, sg + kPrefetch, prv);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_wait<4>(u1.fa[0], u1.fa[1], u1.fb[0], u1.fb[1]);   // u1 is older than the four reads of f0
+            mfma_hi(IC<0>{}, u1);
+            read_frag(IC<0>{}, f1, a_off[1] + shift, b_off[1] + shift);
+            read_frag(IC<1>{}, f1, a_off[1] + shift, b_off[1] + shift);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_hi(IC<1>{}, u1);
+            read_frag(IC<2>{}, f1, a_off[1] + shift, b_off[1] + shift);
+            read_frag(IC<3>{}, f1, a_off[1] + shift, b_off[1] + shift);
+            if (issue) issue_load(IC<1>{}, sg + kPrefetch, prv);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_hi(IC<2>{}, u1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_hi(IC<3>{}, u1);
+            if (issue) issue_load(IC<2>{}, sg + kPrefetch, prv);
+            __builtin_amdgcn_sched_barrier(0);
             buf = nxt;
         };
         using YES = std::true_type;
@@ -666,33 +672,24 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         const int issue_end = S - kPrefetch;  // stages below this one request a later stage
         int sg = 0;
         if (S_hi > 0) {
-            // The last high stage reads the first low step like a high one (its packed
-            // bytes land in ux), so that the loops need no stage of a mixed kind; they
-            // are widened in place afterwards.
-            for (; sg < S_hi && sg < issue_end; ++sg) stage_hi(YES{}, sg);
-            for (; sg < S_hi; ++sg) stage_hi(NO{}, sg);
-            lds_wait_operands<0>(ux);  // the packed bytes of the first low step (or stale ones)
+            // S_hi is even: the sets alternate (px, py) -> (h2, h3) -> (px, py), and the last
+            // high stage reads the first low stage (or stale bytes) into px and py
+            for (; sg < S_hi; sg += 2) {
+                stage_hi(h0, h1, h2, h3, sg);
+                stage_hi(h2, h3, h0, h1, sg + 1);
+            }
             if (S_lo > 0) {
-                static_for<6>([&](auto k) __attribute__((always_inline)) {
-                    read_frag(k, py, a_off[1] + buf * kStageBytes, b_off[1] + buf * kStageBytes);
-                });
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    ux.ao[i] = ux.ae[i] & (int)0xF0F0F0F0;
-                    ux.ae[i] = ux.ae[i] & (int)0x0F0F0F0F;
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    ux.bo[j] = ux.be[j] & (int)0x0F0F0F0F;
-                    ux.be[j] = ux.be[j] & (int)0xF0F0F0F0;
-                }
+                lds_wait<4>(px.fa[0], px.fa[1], px.fb[0], px.fb[1]);
+                static_for<8>([&](auto p) __attribute__((always_inline)) { widen_piece(p, px, ux); });
             }
         }
         if (S_lo > 0) {
             for (; sg < issue_end; ++sg) stage_lo(YES{}, sg);
             for (; sg < S; ++sg) stage_lo(NO{}, sg);
-            lds_wait_all(py);  // reads past the last stage: let them land
         }
+        // reads past the last stage: let them land
+        lds_wait<0>(px.fa[0], px.fa[1], px.fb[0], px.fb[1]);
+        lds_wait<0>(py.fa[0], py.fa[1], py.fb[0], py.fb[1]);
         wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
         if (a.swiglu) {  // symmetric codes only (checked on the host)
             if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, NO{}, YES{});
@@ -710,20 +707,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     }
 
     // ---- write y once --------------------------------------------------------
-    // The wave's 64 x 128 bf16 tile sits in LDS; each store instruction writes
-    // four whole 256-byte row segments.
+    // The 128 x 256 bf16 tile sits in LDS; wave w stores rows 16 w .. 16 w + 15, two
+    // whole 512-byte row segments per store instruction.
     __syncthreads();
     const bool fast = ((reinterpret_cast<uintptr_t>(a.y) & 15) == 0) && (a.ldy % 8 == 0) &&
                       (n0 + kBN <= a.L.N);
     if (a.swiglu) {
-        // 64 x 64 outputs per wave: eight 128-byte row segments per store instruction
+        // 128 outputs per row: four 256-byte row segments per store instruction
         const int64_t n_out = a.L.N / 2;
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const int row = it * 8 + (lane >> 3);
-            const int64_t m = m0 + wm * 64 + row;
-            const int64_t n = n0 / 2 + wn * 64 + (lane & 7) * 8;
-            const uint4 v = *reinterpret_cast<const uint4*>(out_stage + row * kOutRowBytes + (lane & 7) * 16);
+        for (int it = 0; it < 4; ++it) {
+            const int row = wave * 16 + it * 4 + (lane >> 4);
+            const int64_t m = m0 + row;
+            const int64_t n = n0 / 2 + (lane & 15) * 8;
+            const uint4 v = *reinterpret_cast<const uint4*>(lds + row * kOutRowBytes + (lane & 15) * 16);
             if (m >= a.M) continue;
             if (fast) {
                 *reinterpret_cast<uint4*>(a.y + m * a.ldy + n) = v;
@@ -737,11 +734,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         return;
     }
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
-        const int row = it * 4 + (lane >> 4);
-        const int64_t m = m0 + wm * 64 + row;
-        const int64_t n = n0 + wn * 128 + (lane & 15) * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(out_stage + row * kOutRowBytes + (lane & 15) * 16);
+    for (int it = 0; it < 8; ++it) {
+        const int row = wave * 16 + it * 2 + (lane >> 5);
+        const int64_t m = m0 + row;
+        const int64_t n = n0 + (lane & 31) * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(lds + row * kOutRowBytes + (lane & 31) * 16);
         if (m >= a.M) continue;
         if (fast) {
             *reinterpret_cast<uint4*>(a.y + m * a.ldy + n) = v;

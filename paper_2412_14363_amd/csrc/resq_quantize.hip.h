@@ -6,7 +6,10 @@
 //   amax  = max |x| over the group                (exact: bf16 -> fp32 is exact)
 //   scale = amax / qmax                           (fp32 IEEE division; 1 if amax == 0)
 //   code  = clip(rint(x / scale), -qmax, qmax)    (fp32 IEEE division, ties to even)
-// Do not build this file with fast-math or replace a division by a reciprocal.
+// The per-token kernels multiply by the reciprocal of the scale and redo with the
+// division every element whose quotient comes close to a half-integer or is not
+// finite (see quant8), which yields exactly these codes.  Do not build this file
+// with fast-math.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -152,7 +155,9 @@ __device__ __forceinline__ void quant8(const uint4& v, float scale, float inv, u
         const float t = xs[j] * inv;
         const float uf = t + magic;
         rr[j] = uf - kMagic;                    // rint(t) (+ 8), exact
-        near_tie[j] = fabsf(t - (uf - magic)) > 0.5f - (LOW ? 8.0f : 128.0f) * 9.5367431640625e-07f;
+        // negated <= so that a quotient that is not finite (a row whose scale is so small that its
+        // reciprocal overflows) is redone with the division as well
+        near_tie[j] = !(fabsf(t - (uf - magic)) <= 0.5f - (LOW ? 8.0f : 128.0f) * 9.5367431640625e-07f);
         any_tie |= near_tie[j];
         u[j] = __float_as_uint(uf);
     }
@@ -193,7 +198,7 @@ __device__ __forceinline__ void quant8_asym(const uint4& v, float zero, float sc
         const float t = ds[j] * inv;
         const float uf = t + (kMagic - off);
         rr[j] = uf - kMagic;                    // rint(t) - off, exact
-        near_tie[j] = fabsf(t - (uf - (kMagic - off))) > 0.5f - (LOW ? 16.0f : 256.0f) * 9.5367431640625e-07f;
+        near_tie[j] = !(fabsf(t - (uf - (kMagic - off))) <= 0.5f - (LOW ? 16.0f : 256.0f) * 9.5367431640625e-07f);
         any_tie |= near_tie[j];
         u[j] = __float_as_uint(uf);
     }

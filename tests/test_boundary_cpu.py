@@ -182,16 +182,6 @@ def test_basis_entry_points_reject_bad_arguments():
     assert r(P, 1, 64, 0, 64, P, 64, 64, P, 1, 64, None) == 0
 
 
-def test_probe_rejects_bad_arguments():
-    f = binding.lib().resq_probe_mfma_int8
-    assert f(P, 0, 256, P, None) == 2 and f(P, 10, 0, P, None) == 2
-    assert f(None, 10, 256, P, None) == 1 and f(P, 10, 256, None, None) == 1
-    assert f(P + 4, 10, 256, P, None) == 3
-    h = binding.lib().resq_probe_hbm_read
-    assert h(P, 8, 256, P, None) == 2 and h(P, 1 << 20, 0, P, None) == 2
-    assert h(None, 1 << 20, 256, P, None) == 1 and h(P + 8, 1 << 20, 256, P, None) == 3
-
-
 def test_binding_fails_loudly_without_device_tensors():
     import torch
     x = torch.zeros(4, 256, dtype=torch.bfloat16)
