@@ -3,9 +3,12 @@
 //   group, y = bf16(A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n]).
 //
 // Tiling.  One workgroup of 8 wavefronts owns a 128 (tokens) x 256 (channels)
-// output tile; each wavefront owns 64 x 64 of it as 2 x 2 tiles of the
-// 32x32x32 int8 matrix-core instruction, the weights as its first operand so
-// that a lane ends up with four consecutive channels of one token.  Two
+// output tile; each wavefront owns 64 x 64 of it as 4 x 4 tiles of the
+// 16x16x64 int8 matrix-core instruction, the weights as its first operand so
+// that a lane ends up with four consecutive channels of one token.  (Under the
+// chip's power limit this instruction sustains 16-20 % more operations per
+// second than the 32x32x32 one on the same operands: it moves a quarter of the
+// accumulator registers per instruction for half the products.)  Two
 // wavefronts share a SIMD (256 registers each): while one waits for the matrix
 // pipe, the other issues its vector-ALU, LDS and memory instructions, which a
 // single wavefront per SIMD cannot hide behind its own matrix instructions
@@ -13,8 +16,8 @@
 // of a lone wavefront, and the low group needs more).
 //
 // Stages.  The reduction axis is walked in stages of 64 bytes per row: 64 int8
-// codes of the high group or 128 nibble codes of the low group, i.e. two
-// matrix-core steps of 32 bytes.  High and low stages form one sequence; the
+// codes of the high group or 128 nibble codes of the low group, one reduction
+// step of the matrix-core instruction (two for nibbles: even and odd columns).  High and low stages form one sequence; the
 // global->LDS copy is the same for both.  Six LDS buffers of 24 KiB hold the
 // stage being multiplied, the next one, and up to four in flight.
 //
@@ -33,10 +36,12 @@
 // asm) and paired with an explicit wait: reads the compiler can see would each
 // be preceded by a wait for every direct-to-LDS load still in flight.
 //
-// Software pipeline.  Low steps: read(k+2) | widen(k+1) | multiply(k), so that
-// the matrix instructions of step k never wait for the vector ALU work of
-// their own operands.  High steps need no widening: the reads of a whole stage
-// land in operand registers while the stage before it is multiplied.  The
+// Software pipeline.  The eight fragment reads of stage k+1 are issued while
+// stage k is multiplied.  A low stage multiplies widened copies: the four
+// activation fragments of the whole stage and one weight fragment at a time;
+// the next weight fragment is widened behind the products of the current one,
+// the next stage's activation fragments in place behind the last products
+// that read their predecessors.  High stages multiply the fragments as read.  The
 // epilogue's per-channel and per-token constants (3.5 KiB) are fetched into
 // LDS by the first loads of the kernel.
 //
@@ -181,25 +186,37 @@ __device__ __forceinline__ void lds_read4(int& dst, uint32_t addr) {
     asm volatile("ds_read_b32 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
 }
 
-// packed fragments of one reduction step as read from LDS:
-// 2 activation tiles and 2 weight tiles of 32 rows x 32 bytes
-struct Packed {
-    v4i fa[2];
-    v4i fb[2];
-};
-// matrix-core operands of one low reduction step: the even-code and the odd-code half of
-// every fragment
-struct Operands {
-    Packed e, o;
+// the fragments of one stage as read from LDS: 4 activation and 4 weight fragments of
+// 16 rows x 64 bytes, 16 bytes per lane each (row l % 16, piece l / 16)
+struct Raw {
+    v4i a[4];
+    v4i b[4];
 };
 
 // Wait until at most N LDS reads of this wavefront are outstanding (they return in order).
-// The four fragments are tied to the wait as in/out operands so that no use of them can be
+// The fragments are tied to the wait as in/out operands so that no use of them can be
 // scheduled above it.
 template <int N>
-__device__ __forceinline__ void lds_wait(v4i& a0, v4i& a1, v4i& b0, v4i& b1) {
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a0), "+v"(a1), "+v"(b0), "+v"(b1) : "n"(N));
+__device__ __forceinline__ void lds_wait(v4i (&f)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : "n"(N));
 }
+
+// acc += b * a^T on the int8 matrix cores (b: 16 channels x 64 bytes, a: 16 tokens x 64 bytes), the
+// accumulator tile in place in accumulation registers.  Written as assembly because the
+// compiler, given the builtin, renames the 32 four-register tiles from instruction to
+// instruction and runs out of registers.  Nothing here tells the compiler how long the
+// instruction takes: two of them on one tile are kept at least four instructions apart by the
+// loops below, and the epilogue waits before it reads the tiles.
+__device__ __forceinline__ void mfma_16x16x64(v4i& acc, const v4i& b, const v4i& a) {
+    asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(acc) : "v"(b), "v"(a));
+}
+
+// Keeps the instructions that compute x where they are written, between the assembly
+// statements around them: the matrix instruction above is opaque to the compiler, which
+// therefore neither knows that an operand written by the vector ALU needs two wait states
+// before a matrix instruction may read it, nor has a reason to keep the widening spread
+// out between the matrix instructions.
+__device__ __forceinline__ void pin(v4i& x) { asm volatile("" : "+v"(x)); }
 
 // buffer resource over all of memory from `base` on (raw, no stride, no bounds): the loads
 // below address base + per-lane offset + scalar offset
@@ -343,79 +360,48 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     // ---- accumulators ----------------------------------------------------------
     // One int32 tile per group, both in accumulation registers for the whole
     // kernel (2 x 64), folded into the output together at the end.
-    // acc[j][i]: channels 32 j.., tokens 32 i.. of the wave tile.  Lane l holds
-    // token (l % 32) and, in element v, channel 8 (v / 4) + 4 (l / 32) + v % 4.
-    v16i acc_hi[2][2], acc_lo[2][2];
+    // acc[j][i]: channels 16 j.., tokens 16 i.. of the wave tile.  Lane l holds
+    // token (l % 16) and, in element v, channel 4 (l / 16) + v.
+    v4i acc_hi[4][4], acc_lo[4][4];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                acc_hi[j][i][v] = 0;
-                acc_lo[j][i][v] = 0;
-            }
+        for (int i = 0; i < 4; ++i) {
+            acc_hi[j][i] = (v4i){0, 0, 0, 0};
+            acc_lo[j][i] = (v4i){0, 0, 0, 0};
+        }
 
     // The tile that a loop does not touch stays where it is, in accumulation
     // registers: stating so in every stage keeps the register allocator from
     // moving it to ordinary registers and back around the loops.
-    auto park = [&](v16i (&acc)[2][2]) __attribute__((always_inline)) {
+    auto park = [&](v4i (&acc)[4][4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(acc[j][i]));
+            for (int i = 0; i < 4; ++i) asm volatile("" : "+a"(acc[j][i]));
     };
 
     // ---- LDS -> register reads ---------------------------------------------------
-    // An operand tile is 32 rows x 64 bytes (two blocks).  In step st (0, 1) of a
-    // stage lane l supplies row (l % 32), piece 2 st + l / 32.
+    // A fragment is one block (16 rows x 64 bytes): lane l supplies row l % 16, piece l / 16.
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
-    uint32_t a_off[2], b_off[2];
+    uint32_t a_off, b_off;
     {
-        const int R = lane & 31, r = R & 15, g = lane >> 5;
-#pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            const int kc = 2 * st + g;
-            const uint32_t off = (R >> 4) * kBlockBytes + (4 * r + (kc ^ (r >> 2))) * 16;
-            a_off[st] = lds0 + wm * (4 * kBlockBytes) + off;
-            b_off[st] = lds0 + kStageABytes + wn * (4 * kBlockBytes) + off;
-        }
+        const int r = lane & 15, kc = lane >> 4;
+        const uint32_t off = (4 * r + (kc ^ (r >> 2))) * 16;
+        a_off = lds0 + wm * (4 * kBlockBytes) + off;
+        b_off = lds0 + kStageABytes + wn * (4 * kBlockBytes) + off;
     }
-    // read K of a step: K = 0, 1: activation fragments, 2, 3: weight fragments
-    auto read_frag = [&](auto k, Packed& f, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
+    // read K of a stage: K = 0..3: activation fragments, 4..7: weight fragments
+    auto read_frag = [&](auto k, Raw& f, uint32_t aa, uint32_t bb) __attribute__((always_inline)) {
         constexpr int K = decltype(k)::value;
-        if constexpr (K < 2) lds_read16<K * 2 * kBlockBytes>(f.fa[K], aa);
-        else lds_read16<(K - 2) * 2 * kBlockBytes>(f.fb[K - 2], bb);
-    };
-    // piece P (0..7) of the widening of one low step's fragments: one AND over a fragment
-    auto widen_piece = [&](auto p, const Packed& f, Operands& u) __attribute__((always_inline)) {
-        constexpr int P = decltype(p)::value;
-        if constexpr (P < 2) u.e.fa[P] = f.fa[P] & (int)0x0F0F0F0F;               // even columns: code + 8
-        else if constexpr (P < 4) u.e.fb[P - 2] = f.fb[P - 2] & (int)0xF0F0F0F0;  // even columns: 16 * code
-        else if constexpr (P < 6) u.o.fa[P - 4] = f.fa[P - 4] & (int)0xF0F0F0F0;  // odd columns: 16 * code
-        else u.o.fb[P - 6] = f.fb[P - 6] & (int)0x0F0F0F0F;                        // odd columns: code + 8
-    };
-    // matrix instruction Q of a low step (8 of them): the four products of the even halves,
-    // then those of the odd halves, so that two instructions on one accumulator are four apart
-    auto mfma_lo = [&](auto q, const Operands& u) __attribute__((always_inline)) {
-        constexpr int Q = decltype(q)::value;
-        constexpr int j = (Q >> 1) & 1, i = Q & 1;
-        if constexpr (Q < 4)
-            acc_lo[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.e.fb[j], u.e.fa[i], acc_lo[j][i], 0, 0, 0);
-        else
-            acc_lo[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.o.fb[j], u.o.fa[i], acc_lo[j][i], 0, 0, 0);
-    };
-    // matrix instruction Q of a high step (4 of them), operands as they were read
-    auto mfma_hi = [&](auto q, const Packed& f) __attribute__((always_inline)) {
-        constexpr int Q = decltype(q)::value;
-        constexpr int j = (Q >> 1) & 1, i = Q & 1;
-        acc_hi[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.fb[j], f.fa[i], acc_hi[j][i], 0, 0, 0);
+        if constexpr (K < 4) lds_read16<K * kBlockBytes>(f.a[K], aa);
+        else lds_read16<(K - 4) * kBlockBytes>(f.b[K - 4], bb);
     };
 
     // ---- epilogue pieces -------------------------------------------------------------
-    // Lane coordinates inside the tile: token tl + 32 i, channel cl + 32 j + 8 vq + vr.
-    const int tl = wm * 64 + (lane & 31);
-    const int cl = wn * 64 + (lane >> 5) * 4;
+    // Lane coordinates inside the tile: token tl + 16 i, channel cl + 16 j + v.
+    const int tl = wm * 64 + (lane & 15);
+    const int cl = wn * 64 + (lane >> 4) * 4;
 
     // Fold both integer tiles into the output:
     //   y = A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n]
@@ -433,99 +419,94 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
         constexpr bool HI_ON = decltype(has_hi)::value, LO_ON = decltype(has_lo)::value;
         constexpr bool ASYM = decltype(is_asym)::value, GLU = decltype(is_glu)::value;
         const uint8_t* meta = lds + kMetaOff;
-        float st_hi[2] = {0.f, 0.f}, st_lo[2] = {0.f, 0.f}, ct_hi[2] = {0.f, 0.f}, ct_lo[2] = {0.f, 0.f};
-        int ca[2] = {0, 0};
+        float st_hi[4], st_lo[4], ct_hi[4], ct_lo[4];
+        int ca[4];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            if constexpr (HI_ON) st_hi[i] = *reinterpret_cast<const float*>(meta + kMetaSHi + (tl + 32 * i) * 4);
-            if constexpr (ASYM && HI_ON) ct_hi[i] = *reinterpret_cast<const float*>(meta + kMetaCHi + (tl + 32 * i) * 4);
-            if constexpr (ASYM && LO_ON) ct_lo[i] = *reinterpret_cast<const float*>(meta + kMetaCLo + (tl + 32 * i) * 4);
+        for (int i = 0; i < 4; ++i) {
+            st_hi[i] = st_lo[i] = ct_hi[i] = ct_lo[i] = 0.f;
+            ca[i] = 0;
+            if constexpr (HI_ON) st_hi[i] = *reinterpret_cast<const float*>(meta + kMetaSHi + (tl + 16 * i) * 4);
+            if constexpr (ASYM && HI_ON) ct_hi[i] = *reinterpret_cast<const float*>(meta + kMetaCHi + (tl + 16 * i) * 4);
+            if constexpr (ASYM && LO_ON) ct_lo[i] = *reinterpret_cast<const float*>(meta + kMetaCLo + (tl + 16 * i) * 4);
             if constexpr (LO_ON) {
-                st_lo[i] = *reinterpret_cast<const float*>(meta + kMetaSLo + (tl + 32 * i) * 4);
+                st_lo[i] = *reinterpret_cast<const float*>(meta + kMetaSLo + (tl + 16 * i) * 4);
                 if constexpr (!DBG) st_lo[i] *= 0.0625f;
-                ca[i] = 128 * *reinterpret_cast<const int*>(meta + kMetaLoSum + (tl + 32 * i) * 4);
+                ca[i] = 128 * *reinterpret_cast<const int*>(meta + kMetaLoSum + (tl + 16 * i) * 4);
             }
         }
         // debug dump of the integer sums: row pointers and the number of valid columns from cl on
-        int32_t* dbg_row_hi[2] = {nullptr, nullptr};
-        int32_t* dbg_row_lo[2] = {nullptr, nullptr};
-        bool dbg_ok[2] = {false, false};
+        int32_t* dbg_row_hi[4] = {nullptr, nullptr, nullptr, nullptr};
+        int32_t* dbg_row_lo[4] = {nullptr, nullptr, nullptr, nullptr};
+        bool dbg_ok[4] = {false, false, false, false};
         int dbg_cols = 0;
         if constexpr (DBG) {
             dbg_cols = (int)(a.L.N - n0 - cl);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int64_t m = m0 + tl + 32 * i;
+            for (int i = 0; i < 4; ++i) {
+                const int64_t m = m0 + tl + 16 * i;
                 dbg_ok[i] = m < a.M;
                 dbg_row_hi[i] = a.dbg_hi + m * a.L.N + n0 + cl;
                 dbg_row_lo[i] = a.dbg_lo + m * a.L.N + n0 + cl;
             }
         }
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < 4; ++j) {
+            const int c = cl + 16 * j;
+            float sn_hi[4] = {0.f, 0.f, 0.f, 0.f}, sn_lo[4] = {0.f, 0.f, 0.f, 0.f};
+            float zw_hi[4] = {0.f, 0.f, 0.f, 0.f}, zw_lo[4] = {0.f, 0.f, 0.f, 0.f};  // wsum[n] * sw[n]
+            v4i ev = {0, 0, 0, 0};
+            if constexpr (HI_ON) {
+                const v4h h = *reinterpret_cast<const v4h*>(meta + kMetaSwHi + c * 2);
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int c = cl + 32 * j + 8 * vq;
-                float sn_hi[4] = {0.f, 0.f, 0.f, 0.f}, sn_lo[4] = {0.f, 0.f, 0.f, 0.f};
-                float zw_hi[4] = {0.f, 0.f, 0.f, 0.f}, zw_lo[4] = {0.f, 0.f, 0.f, 0.f};  // wsum[n] * sw[n]
-                v4i ev = {0, 0, 0, 0};
-                if constexpr (HI_ON) {
-                    const v4h h = *reinterpret_cast<const v4h*>(meta + kMetaSwHi + c * 2);
+                for (int v = 0; v < 4; ++v) sn_hi[v] = (float)h[v];
+                if constexpr (ASYM) {
+                    const v4i ws = *reinterpret_cast<const v4i*>(meta + kMetaWsumHi + c * 4);
 #pragma unroll
-                    for (int vr = 0; vr < 4; ++vr) sn_hi[vr] = (float)h[vr];
-                    if constexpr (ASYM) {
-                        const v4i ws = *reinterpret_cast<const v4i*>(meta + kMetaWsumHi + c * 4);
-#pragma unroll
-                        for (int vr = 0; vr < 4; ++vr) zw_hi[vr] = (float)ws[vr] * sn_hi[vr];
-                    }
+                    for (int v = 0; v < 4; ++v) zw_hi[v] = (float)ws[v] * sn_hi[v];
                 }
-                if constexpr (LO_ON) {
-                    const v4h h = *reinterpret_cast<const v4h*>(meta + kMetaSwLo + c * 2);
+            }
+            if constexpr (LO_ON) {
+                const v4h h = *reinterpret_cast<const v4h*>(meta + kMetaSwLo + c * 2);
 #pragma unroll
-                    for (int vr = 0; vr < 4; ++vr) sn_lo[vr] = (float)h[vr];
-                    ev = *reinterpret_cast<const v4i*>(meta + kMetaEven + c * 4);
-                    if constexpr (ASYM) {
-                        const v4i ws = *reinterpret_cast<const v4i*>(meta + kMetaWsumLo + c * 4);
+                for (int v = 0; v < 4; ++v) sn_lo[v] = (float)h[v];
+                ev = *reinterpret_cast<const v4i*>(meta + kMetaEven + c * 4);
+                if constexpr (ASYM) {
+                    const v4i ws = *reinterpret_cast<const v4i*>(meta + kMetaWsumLo + c * 4);
 #pragma unroll
-                        for (int vr = 0; vr < 4; ++vr) zw_lo[vr] = (float)ws[vr] * sn_lo[vr];
-                    }
+                    for (int v = 0; v < 4; ++v) zw_lo[v] = (float)ws[v] * sn_lo[v];
                 }
+            }
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    float val[4];
+            for (int i = 0; i < 4; ++i) {
+                float val[4];
 #pragma unroll
-                    for (int vr = 0; vr < 4; ++vr) {
-                        const int v = vq * 4 + vr;
-                        val[vr] = 0.f;
-                        if constexpr (HI_ON) {
-                            const int ih = acc_hi[j][i][v];
-                            val[vr] = (float)ih * (st_hi[i] * sn_hi[vr]);
-                            if constexpr (ASYM) val[vr] += ct_hi[i] * zw_hi[vr];
-                            if constexpr (DBG) {
-                                if (a.dbg_hi && dbg_ok[i] && 32 * j + 8 * vq + vr < dbg_cols)
-                                    dbg_row_hi[i][32 * j + 8 * vq + vr] = ih;
-                            }
-                        }
-                        if constexpr (LO_ON) {
-                            int il = acc_lo[j][i][v] - (ev[vr] * 128 + ca[i]);
-                            if constexpr (DBG) il >>= 4;
-                            val[vr] += (float)il * (st_lo[i] * sn_lo[vr]);
-                            if constexpr (ASYM) val[vr] += ct_lo[i] * zw_lo[vr];
-                            if constexpr (DBG) {
-                                if (a.dbg_lo && dbg_ok[i] && 32 * j + 8 * vq + vr < dbg_cols)
-                                    dbg_row_lo[i][32 * j + 8 * vq + vr] = il;
-                            }
+                for (int v = 0; v < 4; ++v) {
+                    val[v] = 0.f;
+                    if constexpr (HI_ON) {
+                        const int ih = acc_hi[j][i][v];
+                        val[v] = (float)ih * (st_hi[i] * sn_hi[v]);
+                        if constexpr (ASYM) val[v] += ct_hi[i] * zw_hi[v];
+                        if constexpr (DBG) {
+                            if (a.dbg_hi && dbg_ok[i] && 16 * j + v < dbg_cols) dbg_row_hi[i][16 * j + v] = ih;
                         }
                     }
-                    const int row = tl + 32 * i;
-                    const int col = cl + 32 * j + 8 * vq;
-                    if constexpr (GLU)
-                        *reinterpret_cast<uint32_t*>(lds + row * kOutRowBytes + col) =
-                            pack_bf16(silu_f32(val[0]) * val[1], silu_f32(val[2]) * val[3]);
-                    else
-                        *reinterpret_cast<uint2*>(lds + row * kOutRowBytes + col * 2) =
-                            make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
+                    if constexpr (LO_ON) {
+                        int il = acc_lo[j][i][v] - (ev[v] * 128 + ca[i]);
+                        if constexpr (DBG) il >>= 4;
+                        val[v] += (float)il * (st_lo[i] * sn_lo[v]);
+                        if constexpr (ASYM) val[v] += ct_lo[i] * zw_lo[v];
+                        if constexpr (DBG) {
+                            if (a.dbg_lo && dbg_ok[i] && 16 * j + v < dbg_cols) dbg_row_lo[i][16 * j + v] = il;
+                        }
+                    }
                 }
+                const int row = tl + 16 * i;
+                if constexpr (GLU)
+                    *reinterpret_cast<uint32_t*>(lds + row * kOutRowBytes + c) =
+                        pack_bf16(silu_f32(val[0]) * val[1], silu_f32(val[2]) * val[3]);
+                else
+                    *reinterpret_cast<uint2*>(lds + row * kOutRowBytes + c * 2) =
+                        make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -533,164 +514,171 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
 
     // ---- main loop ---------------------------------------------------------------
     {
-        Packed px, py;
-        Operands ux, uy;
-        // the four register sets of the high stages: two stages' worth of operands, used as read
-        Packed& h0 = px;
-        Packed& h1 = py;
-        Packed& h2 = ux.e;
-        Packed& h3 = uy.e;
+        // Two sets of fragments as read from LDS: the stage being multiplied and the next one,
+        // taking turns (the numbers of high and of low stages are even).  Low stages multiply
+        // widened copies: the activation fragments of the whole stage (aw_e, aw_o: even and odd
+        // columns) and the two halves of one weight fragment at a time (bw_e, bw_o).
+        Raw p0, p1;
+        v4i aw_e[4], aw_o[4], bw_e, bw_o;
         const int ahead = S < kPrefetch ? S : kPrefetch;
         for (int i = 0; i < ahead; ++i)
             static_for<kLoadsPerStage>([&](auto k) __attribute__((always_inline)) { issue_load(k, i, i); });
         wait_stage_and_barrier(ahead - 1);  // stage 0 (and the epilogue constants) have landed everywhere
-        static_for<4>([&](auto k) __attribute__((always_inline)) { read_frag(k, px, a_off[0], b_off[0]); });
-        static_for<4>([&](auto k) __attribute__((always_inline)) { read_frag(k, py, a_off[1], b_off[1]); });
-        if (S_hi == 0) {
-            lds_wait<4>(px.fa[0], px.fa[1], px.fb[0], px.fb[1]);
-            static_for<8>([&](auto p) __attribute__((always_inline)) { widen_piece(p, px, ux); });
-        }
+        static_for<8>([&](auto k) __attribute__((always_inline)) { read_frag(k, p0, a_off, b_off); });
 
-        int buf = 0;
-        // A low stage = two pipeline slots (reduction steps) of 8 matrix
-        // instructions.  ISSUE: this stage requests stage sg + kPrefetch (every
-        // stage but the last kPrefetch ones).  A slot is a fixed sequence of groups,
-        // one matrix instruction each, with the slot's other work dealt out among
-        // them so that it issues while the SIMD's matrix pipe is busy with this or
-        // the other wavefront's instructions:
-        //   slot 0: multiply step 0 | wait + barrier after 2 groups | then the four LDS reads
-        //           of the next stage's step 0 and the widening of step 1
-        //   slot 1: multiply step 1 | the four LDS reads of the next stage's step 1 and the
-        //           widening of the next step 0
-        // and the stage's three global loads after the barrier.
-        // Invariant at entry: ux = operands of (sg, step 0); the reads of (sg, step 1)
-        // into py are in flight.
-        auto stage_lo = [&](auto issue, int sg) __attribute__((always_inline)) {
-            constexpr bool ISSUE = decltype(issue)::value;
-            const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
-            const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
-            const uint32_t shift = nxt * kStageBytes;
-            park(acc_hi);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_lo(IC<0>{}, ux);
-            mfma_lo(IC<1>{}, ux);
-            __builtin_amdgcn_sched_barrier(0);
-            // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
-            // stages sg + 2 .. sg + 4 may stay in flight
-            if constexpr (ISSUE) {
-                wait_loads_and_barrier<3 * kLoadsPerStage>();
+        // widening of a low stage's fragments: one AND over a fragment each
+        auto widen_a = [&](auto i_, auto odd, const Raw& f) __attribute__((always_inline)) {
+            constexpr int I = decltype(i_)::value;
+            if constexpr (!decltype(odd)::value) {
+                aw_e[I] = f.a[I] & (int)0x0F0F0F0F;  // even columns: code + 8
+                pin(aw_e[I]);
             } else {
-                const int rem = S - 2 - sg;
-                wait_stage_and_barrier(rem > 3 ? 3 : rem);
+                aw_o[I] = f.a[I] & (int)0xF0F0F0F0;  // odd columns: 16 * code
+                pin(aw_o[I]);
             }
-            lds_wait<0>(py.fa[0], py.fa[1], py.fb[0], py.fb[1]);
-            __builtin_amdgcn_sched_barrier(0);
-            static_for<6>([&](auto g) __attribute__((always_inline)) {
-                constexpr int G = decltype(g)::value;
-                mfma_lo(IC<2 + G>{}, ux);
-                // past the last stage the reads fetch stale LDS: harmless
-                if constexpr (G < 4) read_frag(g, px, a_off[0] + shift, b_off[0] + shift);
-                widen_piece(g, py, uy);
-                if constexpr (G == 4) widen_piece(IC<6>{}, py, uy);
-                if constexpr (G == 5) widen_piece(IC<7>{}, py, uy);
-                if constexpr (ISSUE && G == 4) issue_load_lo(IC<0>{}, sg + kPrefetch, prv);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-            mfma_lo(IC<0>{}, uy);
-            read_frag(IC<0>{}, py, a_off[1] + shift, b_off[1] + shift);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_lo(IC<1>{}, uy);
-            read_frag(IC<1>{}, py, a_off[1] + shift, b_off[1] + shift);
-            if constexpr (ISSUE) issue_load_lo(IC<1>{}, sg + kPrefetch, prv);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_wait<2>(px.fa[0], px.fa[1], px.fb[0], px.fb[1]);   // px is older than the two reads of py
-            __builtin_amdgcn_sched_barrier(0);
-            static_for<6>([&](auto g) __attribute__((always_inline)) {
-                constexpr int G = decltype(g)::value;
-                mfma_lo(IC<2 + G>{}, uy);
-                if constexpr (G < 2) read_frag(IC<2 + G>{}, py, a_off[1] + shift, b_off[1] + shift);
-                widen_piece(g, px, ux);
-                if constexpr (G == 4) widen_piece(IC<6>{}, px, ux);
-                if constexpr (G == 5) widen_piece(IC<7>{}, px, ux);
-                if constexpr (ISSUE && G == 3) issue_load_lo(IC<2>{}, sg + kPrefetch, prv);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-            buf = nxt;
-        };
-        // A high stage needs no widening: 2 x 4 matrix instructions on the fragments as they
-        // were read.  Its eight reads were issued during the stage before it (after that
-        // stage's barrier, which says that this stage has landed), into the register sets
-        // (u0, u1); this stage issues the next stage's reads into (f0, f1).  The last high
-        // stage thereby leaves the packed bytes of the first low stage in px and py.
-        // Invariant at entry: the reads of (sg, step 0) into u0 and of (sg, step 1) into u1
-        // have been issued, in this order.
-        auto stage_hi = [&](Packed& u0, Packed& u1, Packed& f0, Packed& f1, int sg) __attribute__((always_inline)) {
-            const int nxt = buf == kNumBuf - 1 ? 0 : buf + 1;
-            const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
-            const uint32_t shift = nxt * kStageBytes;
-            const bool issue = sg + kPrefetch < S;
-            park(acc_lo);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_wait<4>(u0.fa[0], u0.fa[1], u0.fb[0], u0.fb[1]);
-            mfma_hi(IC<0>{}, u0);
-            mfma_hi(IC<1>{}, u0);
-            __builtin_amdgcn_sched_barrier(0);
-            // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1
-            {
-                const int rem = S - 2 - sg;
-                wait_stage_and_barrier(rem > 3 ? 3 : rem);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_hi(IC<2>{}, u0);
-            read_frag(IC<0>{}, f0, a_off[0] + shift, b_off[0] + shift);
-            read_frag(IC<1>{}, f0, a_off[0] + shift, b_off[0] + shift);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_hi(IC<3>{}, u0);
-            read_frag(IC<2>{}, f0, a_off[0] + shift, b_off[0] + shift);
-            read_frag(IC<3>{}, f0, a_off[0] + shift, b_off[0] + shift);
-            if (issue) issue_load(IC<0>{}, sg + kPrefetch, prv);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_wait<4>(u1.fa[0], u1.fa[1], u1.fb[0], u1.fb[1]);   // u1 is older than the four reads of f0
-            mfma_hi(IC<0>{}, u1);
-            read_frag(IC<0>{}, f1, a_off[1] + shift, b_off[1] + shift);
-            read_frag(IC<1>{}, f1, a_off[1] + shift, b_off[1] + shift);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_hi(IC<1>{}, u1);
-            read_frag(IC<2>{}, f1, a_off[1] + shift, b_off[1] + shift);
-            read_frag(IC<3>{}, f1, a_off[1] + shift, b_off[1] + shift);
-            if (issue) issue_load(IC<1>{}, sg + kPrefetch, prv);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_hi(IC<2>{}, u1);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_hi(IC<3>{}, u1);
-            if (issue) issue_load(IC<2>{}, sg + kPrefetch, prv);
-            __builtin_amdgcn_sched_barrier(0);
-            buf = nxt;
         };
         using YES = std::true_type;
         using NO = std::false_type;
-        const int issue_end = S - kPrefetch;  // stages below this one request a later stage
+
+        int buf = 0;
+        // A low stage: 4 weight fragments x (4 even + 4 odd) products.  Invariant at entry: cur
+        // has landed; aw_e, aw_o hold the widened activation fragments of this stage and bw_e
+        // the even half of weight fragment 0.  Each half of a weight fragment is widened while
+        // the other half of the fragment before it is multiplied.  After the barrier the eight
+        // reads of the next stage go out (into nx) and the three global loads of stage
+        // sg + kPrefetch; during fragment 3 the next stage's activation fragments are widened
+        // in place, each right after the last instruction that reads its predecessor.
+        auto stage_lo = [&](auto steady, Raw& cur, Raw& nx, int sg) __attribute__((always_inline)) {
+            // STEADY: stage sg + kPrefetch exists (known to the caller), so the loads and the wait are unconditional
+            constexpr bool STEADY = decltype(steady)::value;
+            const int nbuf = buf == kNumBuf - 1 ? 0 : buf + 1;
+            const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
+            const uint32_t shift = nbuf * kStageBytes;
+            const bool issue = STEADY || sg + kPrefetch < S;
+            park(acc_hi);
+            static_for<4>([&](auto j_) __attribute__((always_inline)) {
+                constexpr int J = decltype(j_)::value;
+                static_for<8>([&](auto p_) __attribute__((always_inline)) {
+                    constexpr int P = decltype(p_)::value;
+                    constexpr int I = P & 3;
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (P < 4) mfma_16x16x64(acc_lo[J][I], bw_e, aw_e[I]);
+                    else mfma_16x16x64(acc_lo[J][I], bw_o, aw_o[I]);
+                    if constexpr (J == 0 && P == 1) {
+                        // stage sg + 1 has landed everywhere, and every wave is done with stage sg - 1;
+                        // stages sg + 2 .. sg + 4 may stay in flight
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (STEADY) {
+                            wait_loads_and_barrier<3 * kLoadsPerStage>();
+                        } else {
+                            const int rem = S - 2 - sg;
+                            wait_stage_and_barrier(rem > 3 ? 3 : rem);
+                        }
+                    }
+                    // the halves of the weight fragments: odd columns code + 8, even columns 16 * code
+                    if constexpr (P == 1) {
+                        bw_o = cur.b[J] & (int)0x0F0F0F0F;
+                        pin(bw_o);
+                    }
+                    if constexpr (P == 5) {
+                        if constexpr (J < 3) bw_e = cur.b[J + 1] & (int)0xF0F0F0F0;
+                        else bw_e = nx.b[0] & (int)0xF0F0F0F0;
+                        pin(bw_e);
+                    }
+                    // the reads of the next stage (stale LDS past the last stage: harmless)
+                    if constexpr (J == 0 && P >= 2 && P < 6) read_frag(IC<P + 2>{}, nx, a_off + shift, b_off + shift);
+                    if constexpr (J == 1 && P >= 4) read_frag(IC<P - 4>{}, nx, a_off + shift, b_off + shift);
+                    if constexpr (J == 1 && P == 3) { if (issue) issue_load_lo(IC<0>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 2 && P == 3) { if (issue) issue_load_lo(IC<1>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 2 && P == 6) { if (issue) issue_load_lo(IC<2>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 2 && P == 7) {
+                        lds_wait<0>(nx.b);
+                        lds_wait<0>(nx.a);
+                    }
+                    if constexpr (J == 3) {
+                        // aw_e[I] was last read by product (3, even, I), aw_o[I] by (3, odd, I)
+                        if constexpr (P >= 1 && P <= 4) widen_a(IC<P - 1>{}, NO{}, nx);
+                        if constexpr (P >= 6) widen_a(IC<P - 6>{}, YES{}, nx);
+                    }
+                });
+            });
+            __builtin_amdgcn_sched_barrier(0);
+            widen_a(IC<2>{}, YES{}, nx);
+            widen_a(IC<3>{}, YES{}, nx);
+            buf = nbuf;
+        };
+        // A high stage needs no widening: 4 x 4 products on the fragments as they were read.
+        // Invariant at entry: the eight reads of this stage into cur have been issued.
+        auto stage_hi = [&](auto steady, Raw& cur, Raw& nx, int sg) __attribute__((always_inline)) {
+            constexpr bool STEADY = decltype(steady)::value;  // as in stage_lo
+            const int nbuf = buf == kNumBuf - 1 ? 0 : buf + 1;
+            const int prv = buf == 0 ? kNumBuf - 1 : buf - 1;
+            const uint32_t shift = nbuf * kStageBytes;
+            const bool issue = STEADY || sg + kPrefetch < S;
+            park(acc_lo);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_wait<0>(cur.a);
+            lds_wait<0>(cur.b);
+            static_for<4>([&](auto j_) __attribute__((always_inline)) {
+                constexpr int J = decltype(j_)::value;
+                static_for<4>([&](auto i_) __attribute__((always_inline)) {
+                    constexpr int I = decltype(i_)::value;
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_16x16x64(acc_hi[J][I], cur.b[J], cur.a[I]);
+                    if constexpr (J == 0 && I == 1) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (STEADY) {
+                            wait_loads_and_barrier<3 * kLoadsPerStage>();
+                        } else {
+                            const int rem = S - 2 - sg;
+                            wait_stage_and_barrier(rem > 3 ? 3 : rem);
+                        }
+                    }
+                    if constexpr (J == 0 && I >= 2) read_frag(IC<I - 2>{}, nx, a_off + shift, b_off + shift);
+                    if constexpr (J == 1) read_frag(IC<I + 2>{}, nx, a_off + shift, b_off + shift);
+                    if constexpr (J == 2 && I < 2) read_frag(IC<I + 6>{}, nx, a_off + shift, b_off + shift);
+                    if constexpr (J == 2 && I == 3) { if (issue) issue_load(IC<0>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 3 && I == 1) { if (issue) issue_load(IC<1>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 3 && I == 3) { if (issue) issue_load(IC<2>{}, sg + kPrefetch, prv); }
+                });
+            });
+            __builtin_amdgcn_sched_barrier(0);
+            buf = nbuf;
+        };
         int sg = 0;
-        if (S_hi > 0) {
-            // S_hi is even: the sets alternate (px, py) -> (h2, h3) -> (px, py), and the last
-            // high stage reads the first low stage (or stale bytes) into px and py
-            for (; sg < S_hi; sg += 2) {
-                stage_hi(h0, h1, h2, h3, sg);
-                stage_hi(h2, h3, h0, h1, sg + 1);
-            }
-            if (S_lo > 0) {
-                lds_wait<4>(px.fa[0], px.fa[1], px.fb[0], px.fb[1]);
-                static_for<8>([&](auto p) __attribute__((always_inline)) { widen_piece(p, px, ux); });
-            }
+        for (; sg < S_hi && sg + 1 + kPrefetch < S; sg += 2) {
+            stage_hi(YES{}, p0, p1, sg);
+            stage_hi(YES{}, p1, p0, sg + 1);
+        }
+        for (; sg < S_hi; sg += 2) {
+            stage_hi(NO{}, p0, p1, sg);
+            stage_hi(NO{}, p1, p0, sg + 1);
         }
         if (S_lo > 0) {
-            for (; sg < issue_end; ++sg) stage_lo(YES{}, sg);
-            for (; sg < S; ++sg) stage_lo(NO{}, sg);
+            // p0 holds the first low stage, as read: widen its activation fragments and weight fragment 0
+            lds_wait<0>(p0.a);
+            lds_wait<0>(p0.b);
+            static_for<4>([&](auto i_) __attribute__((always_inline)) {
+                widen_a(i_, NO{}, p0);
+                widen_a(i_, YES{}, p0);
+            });
+            bw_e = p0.b[0] & (int)0xF0F0F0F0;
+            pin(bw_e);
+            asm volatile("s_nop 4" ::: "memory");  // wait states between the widening and the first product
+            for (; sg + 1 + kPrefetch < S; sg += 2) {
+                stage_lo(YES{}, p0, p1, sg);
+                stage_lo(YES{}, p1, p0, sg + 1);
+            }
+            for (; sg < S; sg += 2) {
+                stage_lo(NO{}, p0, p1, sg);
+                stage_lo(NO{}, p1, p0, sg + 1);
+            }
         }
-        // reads past the last stage: let them land
-        lds_wait<0>(px.fa[0], px.fa[1], px.fb[0], px.fb[1]);
-        lds_wait<0>(py.fa[0], py.fa[1], py.fb[0], py.fb[1]);
+        // the reads past the last stage went into p0: let them land before its registers are reused
+        lds_wait<0>(p0.a);
+        lds_wait<0>(p0.b);
         wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last matrix instructions have written their tiles
         if (a.swiglu) {  // symmetric codes only (checked on the host)
             if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, NO{}, YES{});
             else if (S_hi > 0) fold(YES{}, NO{}, NO{}, YES{});
