@@ -7,13 +7,22 @@ kernel, then the mixed GEMM with its dequantizing epilogue (for the down_proj
 workload the online Hadamard runs first).  Weights are quantized and packed
 once, before the timed region, as they are offline in the method.
 
-Prints ONE JSON line.  ``value`` is 2*M*N*K operations per second of the whole
-step for prefill workloads (TOPS) and algorithmic bytes per second for decode
-workloads (GB/s).  ``roofline`` prices the GEMM kernel alone, its duration
-measured with HIP events that the library records at the kernel's own start and
-end (resq_time_next_kernel) in a second pass over the same steps;
-``cpu_baseline`` is the CPU oracle timed on a bounded sample of the same
-workload on this host's cores.
+Prints ONE JSON line.  With no --workload it is the headline line: the largest
+single-GPU configuration (Qwen2.5-72B-shaped MLP prefill, M = 8192, K = 8192,
+N = 29568, r = K/8) as ``value`` / ``roofline`` / ``cpu_baseline``, and in the
+same line a ``decode`` block (M = 1, 4, 16 on the Llama-3-70B up_proj shape: the
+memory-bound half of the metric), the output SNR and TOPS per rank r in
+{0, K/8, K/4} (``rank_sweep``, the rank ablation of Section 5.4 on synthetic
+inputs), and ``calibration``: what the chip sustains on the matrix instruction
+alone and on a plain read, measured in the same process.
+
+``value`` is 2*M*N*K operations per second of the whole step for prefill
+workloads (TOPS) and algorithmic bytes per second for decode workloads (GB/s).
+``roofline`` prices the GEMM kernel alone, its duration measured with HIP
+events that the library records at the kernel's own start and end
+(resq_time_next_kernel) in a second pass over the same steps; ``cpu_baseline``
+is the CPU oracle timed on a bounded sample of the same workload on this
+host's cores.
 """
 from __future__ import annotations
 
@@ -31,21 +40,30 @@ if str(ROOT) not in sys.path:
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 matrix-core peak, TOP/s
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E peak, GB/s
 
-# HBM traffic of the GEMM kernel per launch, in bytes: FETCH_SIZE + WRITE_SIZE of two
-# rocprofv3 --pmc runs, each scaled by what the same counter reads for a 1 GiB device copy
-# (x2.000 and x1.000; the summaries are under profiles/).  Absent = not measured.
+# HBM traffic of the dominant kernel per launch, in bytes: FETCH_SIZE + WRITE_SIZE of two
+# rocprofv3 --pmc runs of this script, each scaled by what the same counter reads for a 1 GiB
+# device copy (x2.000 and x1.000).  This run does not measure it: the figures are copied from
+# the summaries under profiles/ (named in `traffic_source`); absent = not measured.
 MEASURED_TRAFFIC = {
-    "oproj_prefill": 38.42e6 + 16.78e6,
-    "gate_up_prefill": 265.88e6 + 117.44e6,
-    "down_prefill": 265.08e6 + 33.55e6,
-    "qwen_r1024": 2194.69e6 + 484.44e6,
-    "oproj_m512": 19.27e6 + 4.19e6,
-    "down_m512": 66.45e6 + 4.19e6,
-    "decode_m16": 133.61e6 + 0.92e6,
-    "decode_m64": 134.98e6 + 3.67e6,
-    "kv_quant": 8.47e6 + 9.04e6,
-    "uc_proj": 21.35e6 + 20.97e6,
+    "qwen_r1024": (2194.69e6 + 484.44e6, "profiles/qwen_r1024.txt"),
+    "oproj_prefill": (38.42e6 + 16.78e6, "profiles/oproj_prefill.txt"),
+    "gate_up_prefill": (265.88e6 + 117.44e6, "profiles/gate_up_prefill.txt"),
+    "down_prefill": (265.08e6 + 33.55e6, "profiles/down_prefill.txt"),
+    "oproj_m512": (19.27e6 + 4.19e6, "profiles/oproj_m512.txt"),
+    "down_m512": (66.45e6 + 4.19e6, "profiles/down_m512.txt"),
+    "decode_m16": (133.61e6 + 0.92e6, "profiles/decode_m16.txt"),
+    "decode_m64": (134.98e6 + 3.67e6, "profiles/decode_m64.txt"),
+    "kv_quant": (8.47e6 + 9.04e6, "profiles/kv_quant.txt"),
+    "uc_proj": (21.35e6 + 20.97e6, "profiles/uc_proj.txt"),
 }
+
+
+def traffic_fields(tag: str) -> dict:
+    """`traffic` and where it comes from (never measured by this run itself)."""
+    t = MEASURED_TRAFFIC.get(tag)
+    if t is None:
+        return {"traffic": None}
+    return {"traffic": t[0], "traffic_source": f"{t[1]} (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; copied, not measured by this run)"}
 
 
 def workload_shape(name: str):
@@ -189,7 +207,7 @@ def quant_only_bench(args, s) -> None:
         "quantize_ms": kernel_ms,
         "roofline": {"bound": "hbm", "achieved": abytes / (kernel_ms * 1e-3) / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get(args.workload),
+                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, **traffic_fields(args.workload),
                      "kernel": "resq quantize_act (short rows)", "kernel_ms": kernel_ms},
     }
     if not args.no_cpu_baseline:
@@ -263,7 +281,7 @@ def head_proj_bench(args, s) -> None:
         "tops": 2.0 * s.M * s.N * s.K / (ms_per_step * 1e-3) / 1e12,
         "roofline": {"bound": "hbm", "achieved": abytes / (kernel_ms * 1e-3) / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get(args.workload),
+                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, **traffic_fields(args.workload),
                      "kernel": "resq project_heads", "kernel_ms": kernel_ms},
         "snr_db": output_snr_db(x, u, y),
     }
@@ -370,112 +388,101 @@ def basis_bench(args) -> None:
     print(json.dumps(res))
 
 
-def mfma_ceiling_bench(args) -> None:
-    """Not a workload of the method: what this chip sustains on v_mfma_i32_32x32x32_i8 alone,
-    for operand bytes like the GEMM's (all zero; INT4 codes widened to the high nibble and the
-    offset low nibble; random INT8 codes) and launches about as long as the GEMM's.  The matrix
-    pipes are power-limited, so this, not the nominal 5 POPS, is what the GEMM can approach."""
+def calib_lib():
+    """The calibration kernels beside this script (bench_calib.hip), built on first use."""
+    import ctypes
+    import subprocess
+    so, src = ROOT / "libbench_calib.so", ROOT / "bench_calib.hip"
+    if not so.exists() or so.stat().st_mtime < src.stat().st_mtime:
+        subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+                        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                        "-Wno-unused-command-line-argument", "-o", str(so), str(src)], check=True,
+                       capture_output=True)
+    lib = ctypes.CDLL(str(so))
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.calib_mfma_int8.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp]
+    lib.calib_hbm_read.argtypes = [vp, ctypes.c_size_t, ci, vp, vp, vp, vp]
+    return lib
+
+
+def calibration(mfma_ms: float = 1.5, quick: bool = True) -> dict:
+    """What this chip sustains with nothing else going on, measured here and now:
+    * v_mfma_i32_16x16x64_i8 alone (operands in registers, two wavefronts per SIMD, launches about
+      as long as the headline GEMM) on operand bytes like the low group's (one operand code + 8 in
+      the low nibble, the other 16 * code) and like the high group's (random INT8).  The matrix
+      pipes are power-limited, so the rate depends on the bytes; `mix_r_eighth` is the rate of a
+      kernel that spends 7/8 of its products on the first kind and 1/8 on the second.
+    * a plain streaming read of as many bytes as the decode GEMM's packed weights, regions
+      rotated through 1 GiB so that the last-level cache cannot serve them."""
     import ctypes
     import numpy as np
     import torch
-    from paper_2412_14363_amd import binding as rq
-
-    L = rq.lib()
+    L = calib_lib()
+    hip = ctypes.CDLL("libamdhip64.so")
     st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     rng = np.random.default_rng(0)
+    n = 4096 * 16
+    frag = np.arange(n) // 16 // 512             # blocks of 512 lanes: 0..3 even halves, 4..7 odd halves
+    c, w = rng.integers(-7, 8, n), rng.integers(-7, 8, n)
+    odd = frag >= 4
     kinds = {
-        "zeros": np.zeros(2048 * 16, np.uint8),
-        "int4_widened": np.where(np.arange(2048 * 16) % 32 < 16,
-                                 (rng.integers(-7, 8, 2048 * 16) * 16) & 0xFF,          # weight-like: code << 4
-                                 rng.integers(1, 16, 2048 * 16)).astype(np.uint8),      # activation-like: code + 8
-        "random_int8": (rng.integers(-127, 128, 2048 * 16) & 0xFF).astype(np.uint8),
+        "low_group_like": (np.where(odd, c * 16, c + 8).astype(np.int64) & 0xFF,
+                           np.where(odd, w + 8, w * 16).astype(np.int64) & 0xFF),
+        "high_group_like": (rng.integers(-127, 128, n) & 0xFF, rng.integers(-127, 128, n) & 0xFF),
     }
-    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-    hip = ctypes.CDLL("libamdhip64.so")
-    wgs = 256                                  # one workgroup of four wavefronts per compute unit, as the GEMM
-    out_rows = {}
-    for name, host in kinds.items():
-        dev = torch.from_numpy(host).cuda()
-        for label, iters in (("35us", 290), ("200us", 1650), ("1500us", 12400)):
-            for _ in range(2):
-                assert L.resq_probe_mfma_int8(dev.data_ptr(), iters, wgs, sink.data_ptr(), st) == 0
-            torch.cuda.synchronize()
-            a, b = ctypes.c_void_p(), ctypes.c_void_p()
-            assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
-            tot, reps = 0.0, 5
-            for _ in range(reps):
-                L.resq_time_next_kernel(a, b)
-                assert L.resq_probe_mfma_int8(dev.data_ptr(), iters, wgs, sink.data_ptr(), st) == 0
-                torch.cuda.synchronize()
-                ms = ctypes.c_float()
-                assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
-                tot += ms.value
-            hip.hipEventDestroy(a)
-            hip.hipEventDestroy(b)
-            ms_avg = tot / reps
-            ops = 2.0 * 32 ** 3 * 8 * 4 * iters * wgs
-            out_rows[f"{name}_{label}"] = {"kernel_ms": ms_avg, "tops": ops / (ms_avg * 1e-3) / 1e12}
-    best = out_rows["int4_widened_200us"]["tops"]
-    print(json.dumps({
-        "metric": "sustained int8 MFMA rate, matrix instructions only (TOPS)", "value": best, "unit": "TOPS",
-        "n_gpus": 1, "steps": 5, "warmup": 2, "ms_per_step": out_rows["int4_widened_200us"]["kernel_ms"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "mfma_ceiling: 256 workgroups x 4 wavefronts, 8 accumulator tiles each", "tag": "mfma_ceiling"},
-        "rates": out_rows,
-        "roofline": {"bound": "mfma", "achieved": best, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                     "frac": best / PEAK_INT8_TOPS, "traffic": None, "kernel": "resq probe_mfma_int8 (int4_widened, 200 us)",
-                     "kernel_ms": out_rows["int4_widened_200us"]["kernel_ms"]},
-    }))
 
-
-def hbm_ceiling_bench(args) -> None:
-    """Not a workload of the method: the rate of a plain streaming read, for a launch that reads
-    as many bytes as the decode GEMM does (the 132 MB of packed weights of the Llama-3-70B up_proj,
-    rotated over regions that the last-level cache cannot hold) and for one long read of 3 GiB."""
-    import ctypes
-    import torch
-    from paper_2412_14363_amd import binding as rq
-
-    L = rq.lib()
-    st = torch.cuda.current_stream().cuda_stream
-    hip = ctypes.CDLL("libamdhip64.so")
-    region = 132_600_000 // 256 * 256
-    buf = torch.ones(3 << 30, dtype=torch.uint8, device="cuda")
-    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-    rows = {}
-
-    def timed(offset, nbytes, wgs, reps):
+    def timed(fn, reps):
         a, b = ctypes.c_void_p(), ctypes.c_void_p()
         assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
-        tot = 0.0
-        for i in range(reps + 2):
-            off = (offset + i * (region + 4096)) % (buf.numel() - nbytes) // 256 * 256 if nbytes == region else 0
-            L.resq_time_next_kernel(a, b)
-            assert L.resq_probe_hbm_read(buf.data_ptr() + off, nbytes, wgs, sink.data_ptr(), st) == 0
+        best = []
+        for i in range(reps + 1):
+            assert fn(i, a, b) == 0
             torch.cuda.synchronize()
             ms = ctypes.c_float()
             assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
-            if i >= 2:
-                tot += ms.value
+            if i > 0:
+                best.append(ms.value)
         hip.hipEventDestroy(a)
         hip.hipEventDestroy(b)
-        return tot / reps
+        return sum(best) / len(best)
 
-    for wgs in (1024, 2048, 4096, 8192):
-        ms = timed(0, region, wgs, 12)
-        rows[f"read_132MB_{wgs}wg"] = {"kernel_ms": ms, "gbs": region / (ms * 1e-3) / 1e9}
-    for wgs in (4096, 16384):
-        ms = timed(0, buf.numel(), wgs, 3)
-        rows[f"read_3GiB_{wgs}wg"] = {"kernel_ms": ms, "gbs": buf.numel() / (ms * 1e-3) / 1e9}
-    best = max(v["gbs"] for k, v in rows.items() if k.startswith("read_132MB"))
+    out = {}
+    ops_per_iter = 2.0 * 16 * 16 * 64 * 32 * 8 * 256
+    iters = max(1, int(mfma_ms * 1e-3 * 4.0e15 / ops_per_iter))
+    for name, (ha, hb) in kinds.items():
+        da = torch.from_numpy(ha.astype(np.uint8)).cuda()
+        db = torch.from_numpy(hb.astype(np.uint8)).cuda()
+        ms = timed(lambda i, a, b: L.calib_mfma_int8(da.data_ptr(), db.data_ptr(), iters, 256, sink.data_ptr(), a, b, st),
+                   3 if quick else 6)
+        out[name] = {"kernel_ms": ms, "tops": ops_per_iter * iters / (ms * 1e-3) / 1e12}
+    lo, hi = out["low_group_like"]["tops"], out["high_group_like"]["tops"]
+    out["mix_r_eighth"] = {"tops": 1.0 / (0.875 / lo + 0.125 / hi)}
+    region = 132_600_000 // 256 * 256
+    buf = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+    span = buf.numel() - region
+    ms = timed(lambda i, a, b: L.calib_hbm_read(buf.data_ptr() + (i * (region + 4096)) % span // 256 * 256, region, 2048,
+                                                sink.data_ptr(), a, b, st), 6 if quick else 12)
+    out["read_132MB"] = {"kernel_ms": ms, "gbs": region / (ms * 1e-3) / 1e9}
+    del buf
+    return out
+
+
+def calib_bench(args) -> None:
+    """`--workload calib`: the calibration alone, as its own line."""
+    cal = calibration(quick=False)
+    best = cal["mix_r_eighth"]["tops"]
     print(json.dumps({
-        "metric": "plain streaming read GB/s", "value": best, "unit": "GB/s", "n_gpus": 1, "steps": 12, "warmup": 2,
-        "ms_per_step": region / best / 1e6, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "hbm_ceiling: one launch reads 132.6 MB (regions rotated through 3 GiB), or all 3 GiB", "tag": "hbm_ceiling"},
-        "rates": rows,
-        "roofline": {"bound": "hbm", "achieved": best, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": best / PEAK_HBM_GBS,
-                     "traffic": None, "kernel": "resq probe_hbm_read (132.6 MB per launch)", "kernel_ms": region / best / 1e6},
+        "metric": "sustained int8 MFMA rate, matrix instructions only (TOPS)", "value": best, "unit": "TOPS",
+        "n_gpus": 1, "steps": 6, "warmup": 1, "ms_per_step": cal["low_group_like"]["kernel_ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "calib: v_mfma_i32_16x16x64_i8 alone (256 workgroups x 8 wavefronts) and a plain read of 132.6 MB",
+                   "tag": "calib"},
+        "calibration": cal,
+        "roofline": {"bound": "mfma", "achieved": best, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                     "frac": best / PEAK_INT8_TOPS, "traffic": None,
+                     "kernel": "calib_mfma_kernel (7/8 low-group-like, 1/8 high-group-like operands)",
+                     "kernel_ms": cal["low_group_like"]["kernel_ms"]},
     }))
 
 
@@ -570,76 +577,35 @@ def mlp_block_bench(args) -> None:
     print(json.dumps(out))
 
 
-def main() -> None:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="oproj_prefill")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-budget", type=float, default=15.0)
-    ap.add_argument("--asym", action="store_true",
-                    help="asymmetric per-token activations (the paper's experimental setting) "
-                         "instead of the symmetric ones the headline metric is defined on")
-    ap.add_argument("--one-call", action="store_true",
-                    help="generation-stage workloads with at most 16 tokens: quantizer and GEMM as ONE "
-                         "kernel (resq_quantize_gemm_mixed) instead of the two calls")
-    ap.add_argument("--unfused-hadamard", action="store_true",
-                    help="down_proj input: transform and quantize in two kernels instead of one")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        raise SystemExit("bench.py: this build runs on ONE GPU and has no multi-GPU path; "
-                         "--gpus must be 1")
+_WEIGHTS: dict = {}   # the last layer's weights and packed copies (see layer_bench)
 
+
+def layer_bench(args, tag: str, steps: int, warmup: int, with_cpu_baseline: bool, cpu_budget: float,
+                keep: dict | None = None) -> dict:
+    """One workload that is a whole layer step (quantizer + GEMM, the transform in front where the
+    workload has one): times `steps` steps, then a second pass with events around each kernel.
+    Returns the JSON object; `keep`, when given, receives the inputs for follow-up measurements."""
+    import ctypes
     import torch
-    if not torch.cuda.is_available():
-        raise SystemExit("bench.py needs a GPU: the library has no CPU path")
-    torch.cuda.set_device(0)
-    if args.workload == "copy_calib":
-        # Calibration for the FETCH_SIZE / WRITE_SIZE counters: a plain device copy of
-        # known size (1 GiB read, 1 GiB written per launch), to be run under rocprofv3 --pmc.
-        n = 1 << 30
-        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(args.steps):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"workload": "copy_calib", "bytes_read_per_copy": n,
-                          "bytes_written_per_copy": n, "copies": args.steps}))
-        return
     from paper_2412_14363_amd import binding as rq
     from paper_2412_14363_amd import workloads as wl
 
-    if args.workload == "mlp_block":
-        mlp_block_bench(args)
-        return
-    if args.workload == "basis":
-        basis_bench(args)
-        return
-    if args.workload == "mfma_ceiling":
-        mfma_ceiling_bench(args)
-        return
-    if args.workload == "hbm_ceiling":
-        hbm_ceiling_bench(args)
-        return
-    s = workload_shape(args.workload)
-    if args.workload == "uc_proj":
-        head_proj_bench(args, s)
-        return
-    if s.N == 0:
-        quant_only_bench(args, s)
-        return
+    s = workload_shape(tag)
     decode = s.M <= 64
     x = wl.make_activations(s)
-    w = wl.make_weights(s)
     xd = x.cuda()
     # decode: rotate over enough weight copies that the 256 MB last-level cache
-    # cannot hold them, so that HBM is what is measured
-    n_copies = 1
-    packed0 = rq.resq_pack_weights(w.cuda(), s.r)
-    if decode:
-        n_copies = max(1, int(-(-768e6 // packed0.numel())))
-    packed = [packed0] + [packed0.clone() for _ in range(n_copies - 1)]
+    # cannot hold them, so that HBM is what is measured.  The weights depend on the layer,
+    # not on M: workloads of one layer (decode_m1/4/16 in the headline run) share them.
+    wkey = (s.N, s.K, s.r, s.seed)
+    if _WEIGHTS.get("key") != wkey:
+        _WEIGHTS.clear()
+        w = wl.make_weights(s)
+        packed0 = rq.resq_pack_weights(w.cuda(), s.r)
+        n_copies = max(1, int(-(-768e6 // packed0.numel()))) if decode else 1
+        _WEIGHTS.update(key=wkey, w=w, packed=[packed0] + [packed0.clone() for _ in range(n_copies - 1)])
+    w, packed = _WEIGHTS["w"], _WEIGHTS["packed"]
+    n_copies = len(packed)
     act = rq.ActCodes(s.M, s.K, s.r)
     y = torch.empty((s.M, s.N), dtype=torch.bfloat16, device="cuda")
     fused = s.hadamard and not args.unfused_hadamard
@@ -705,18 +671,17 @@ def main() -> None:
             rc = L.resq_gemm_mixed(*gemm_args[i % n_copies])
         assert rc == 0, rc
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step = dt / steps * 1e3
 
     # second pass over the same steps; HIP events at the start and end of each kernel
-    import ctypes
     hip = ctypes.CDLL("libamdhip64.so")
 
     def new_event():
@@ -729,14 +694,14 @@ def main() -> None:
         assert hip.hipEventElapsedTime(ctypes.byref(ms), pair[0], pair[1]) == 0
         return ms.value
 
-    evs = [[(new_event(), new_event()) for _ in range(3)] for _ in range(args.steps)]
-    for i in range(args.steps):
+    evs = [[(new_event(), new_event()) for _ in range(3)] for _ in range(steps)]
+    for i in range(steps):
         step(i, evs[i])
     torch.cuda.synchronize()
-    had_ms = sum(elapsed_ms(e[0]) for e in evs) / args.steps if s.hadamard and not fused else 0.0
-    quant_ms = 0.0 if one_call else sum(elapsed_ms(e[1]) for e in evs) / args.steps
+    had_ms = sum(elapsed_ms(e[0]) for e in evs) / steps if s.hadamard and not fused else 0.0
+    quant_ms = 0.0 if one_call else sum(elapsed_ms(e[1]) for e in evs) / steps
     gemm_all = sorted(elapsed_ms(e[2]) for e in evs)
-    gemm_ms = sum(gemm_all) / args.steps
+    gemm_ms = sum(gemm_all) / steps
     for e in evs:
         for pair in e:
             hip.hipEventDestroy(pair[0])
@@ -744,29 +709,28 @@ def main() -> None:
 
     ops = 2.0 * s.M * s.N * s.K
     abytes = algorithmic_bytes_gemm(s)
-    traffic = MEASURED_TRAFFIC.get(args.workload)
     if decode:
         metric, unit = "decode GB/s (% HBM peak)", "GB/s"
         value = (abytes + 2 * s.M * s.K) / (ms_per_step * 1e-3) / 1e9
         achieved = abytes / (gemm_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": achieved / PEAK_HBM_GBS, "traffic": traffic}
+                "frac": achieved / PEAK_HBM_GBS, **traffic_fields(tag)}
     else:
         metric, unit = "mixed INT8/INT4 linear TOPS (% int8 MFMA peak)", "TOPS"
         value = ops / (ms_per_step * 1e-3) / 1e12
         achieved = ops / (gemm_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": achieved / PEAK_INT8_TOPS, "traffic": traffic}
+                "frac": achieved / PEAK_INT8_TOPS, **traffic_fields(tag)}
     roof["kernel"] = "resq quantize_gemm_mixed" if one_call else "resq gemm_mixed"
     roof["kernel_ms"] = gemm_ms        # the mean: what `achieved` is priced with
     roof["kernel_ms_median"] = gemm_all[len(gemm_all) // 2]
     roof["kernel_ms_min"] = gemm_all[0]
 
     out = {
-        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"{s.name}: M={s.M} K={s.K} N={s.N} r={s.r}", "tag": args.workload,
+        "config": {"workload": f"{s.name}: M={s.M} K={s.K} N={s.N} r={s.r}", "tag": tag,
                    "step": "quantize_gemm_mixed (one kernel)" if one_call else
                            ("hadamard_quantize_act (one kernel) + " if fused else
                             "online_hadamard + quantize_act + " if s.hadamard else
@@ -775,14 +739,16 @@ def main() -> None:
                    "weight_copies_rotated": n_copies},
         "tokens_per_s": s.M / (ms_per_step * 1e-3),
         "hadamard_ms": had_ms, "quantize_ms": quant_ms, "gemm_ms": gemm_ms,
+        # ms_per_step is host time over back-to-back steps; the *_ms fields are device time of
+        # each kernel from the second pass (events between the kernels), so they need not add up to it
         "roofline": roof,
     }
     if not s.hadamard:
         out["snr_db"] = output_snr_db(x, w, y)
-    if not args.no_cpu_baseline:
+    if with_cpu_baseline:
         from oracle import resq_oracle as oracle
         wq_np = oracle.quantize_weights(wl.bf16_bits(w), s.r)
-        cb = cpu_baseline(s, x, wq_np, args.cpu_budget,
+        cb = cpu_baseline(s, x, wq_np, cpu_budget,
                           rq.resq_hadamard_block(s.K - s.r) if s.hadamard else 0, args.asym)
         if decode:
             # same unit as the metric: algorithmic bytes of the sampled rows per second
@@ -790,7 +756,144 @@ def main() -> None:
             cb["value"] = abytes * frac / cb["seconds"] / 1e9
             cb["unit"] = "GB/s"
         out["cpu_baseline"] = {k: cb[k] for k in ("value", "unit", "cores", "kind", "sample")}
+    if keep is not None:
+        keep.update(x=x, w=w, xd=xd, shape=s)
+    return out
+
+
+def rank_sweep(args, x, w, xd, base, ranks, steps: int = 10) -> dict:
+    """The rank ablation of Section 5.4 on the headline workload's inputs: for each r the GEMM's
+    device time (events at the kernel's start and end) and the SNR of the layer's output against
+    the unquantized product in fp64 on a strided sample of rows and channels."""
+    import ctypes
+    import torch
+    from paper_2412_14363_amd import binding as rq
+    hip = ctypes.CDLL("libamdhip64.so")
+    L = rq.lib()
+    wd = w.cuda()
+    out = {}
+    for r in ranks:
+        packed = rq.resq_pack_weights(wd, r)
+        act = rq.resq_quantize_act(xd, r)
+        y = rq.resq_gemm_mixed(act, packed, base.N)
+        a, b = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+        tot = 0.0
+        for _ in range(steps):
+            L.resq_time_next_kernel(a, b)
+            rq.resq_gemm_mixed(act, packed, base.N, y=y)
+            torch.cuda.synchronize()
+            ms = ctypes.c_float()
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+            tot += ms.value
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(b)
+        gemm_ms = tot / steps
+        tops = 2.0 * base.M * base.N * base.K / (gemm_ms * 1e-3) / 1e12
+        out[f"r={r}"] = {"snr_db": output_snr_db(x, w, y), "gemm_ms": gemm_ms, "gemm_tops": tops,
+                         "frac_of_int8_peak": tops / PEAK_INT8_TOPS}
+        del packed, act, y
+    return out
+
+
+def headline(args) -> None:
+    """The default line: config 5 at r = K/8 in full, plus the decode half of the metric, the
+    rank sweep and the calibration."""
+    import torch
+    keep: dict = {}
+    out = layer_bench(args, "qwen_r1024", args.steps, args.warmup, not args.no_cpu_baseline, args.cpu_budget, keep)
+    s = keep["shape"]
+    out["rank_sweep"] = rank_sweep(args, keep["x"], keep["w"], keep["xd"], s, (0, s.K // 8, s.K // 4))
+    keep.clear()
+    _WEIGHTS.clear()
+    torch.cuda.empty_cache()
+    dec = {}
+    for m in (1, 4, 16):
+        d = layer_bench(args, f"decode_m{m}", max(args.steps, 100), args.warmup, not args.no_cpu_baseline and m == 16,
+                        min(args.cpu_budget, 5.0))
+        dec[f"M={m}"] = {"value": d["value"], "unit": d["unit"], "ms_per_step": d["ms_per_step"],
+                         "quantize_ms": d["quantize_ms"], "gemm_ms": d["gemm_ms"],
+                         "tokens_per_s": d["tokens_per_s"], "workload": d["config"]["workload"],
+                         "weight_copies_rotated": d["config"]["weight_copies_rotated"],
+                         "roofline": d["roofline"]}
+        if "cpu_baseline" in d:
+            dec[f"M={m}"]["cpu_baseline"] = d["cpu_baseline"]
+        torch.cuda.empty_cache()
+    out["decode"] = dec
+    cal = calibration()
+    out["calibration"] = cal
+    out["roofline"]["measured_peak"] = cal["mix_r_eighth"]["tops"]
+    out["roofline"]["frac_of_measured"] = out["roofline"]["achieved"] / cal["mix_r_eighth"]["tops"]
+    out["roofline"]["measured_peak_source"] = ("calibration.mix_r_eighth: the matrix instruction alone on operand "
+                                               "bytes like this workload's, same process")
+    for v in dec.values():
+        v["roofline"]["measured_peak"] = cal["read_132MB"]["gbs"]
+        v["roofline"]["frac_of_measured"] = v["roofline"]["achieved"] / cal["read_132MB"]["gbs"]
     print(json.dumps(out), flush=True)
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="headline",
+                    help="headline (default: Qwen2.5-72B MLP prefill + decode block + rank sweep + calibration), "
+                         "or one workload alone: oproj_prefill, gate_up_prefill, down_prefill, qwen_r0/r1024/r2048, "
+                         "decode_m1/4/16/32/64, oproj_m512, down_m512, mlp_block, kv_quant, uc_proj, basis, calib, "
+                         "copy_calib")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--asym", action="store_true",
+                    help="asymmetric per-token activations (the paper's experimental setting) "
+                         "instead of the symmetric ones the headline metric is defined on")
+    ap.add_argument("--one-call", action="store_true",
+                    help="generation-stage workloads with at most 16 tokens: quantizer and GEMM as ONE "
+                         "kernel (resq_quantize_gemm_mixed) instead of the two calls")
+    ap.add_argument("--unfused-hadamard", action="store_true",
+                    help="down_proj input: transform and quantize in two kernels instead of one")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU and has no multi-GPU path; "
+                         "--gpus must be 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU: the library has no CPU path")
+    torch.cuda.set_device(0)
+    if args.workload == "copy_calib":
+        # Calibration for the FETCH_SIZE / WRITE_SIZE counters: a plain device copy of
+        # known size (1 GiB read, 1 GiB written per launch), to be run under rocprofv3 --pmc.
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": "copy_calib", "bytes_read_per_copy": n,
+                          "bytes_written_per_copy": n, "copies": args.steps}))
+        return
+    if args.workload == "headline":
+        headline(args)
+        return
+    if args.workload == "mlp_block":
+        mlp_block_bench(args)
+        return
+    if args.workload == "basis":
+        basis_bench(args)
+        return
+    if args.workload == "calib":
+        calib_bench(args)
+        return
+    s = workload_shape(args.workload)
+    if args.workload == "uc_proj":
+        head_proj_bench(args, s)
+        return
+    if s.N == 0:
+        quant_only_bench(args, s)
+        return
+    print(json.dumps(layer_bench(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline,
+                                 args.cpu_budget)), flush=True)
 
 
 if __name__ == "__main__":

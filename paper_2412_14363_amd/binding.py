@@ -86,6 +86,28 @@ def _dev(t: Optional[torch.Tensor], dtype, name: str):
     return t.data_ptr()
 
 
+def _check_layer_buffers(where: str, act: "ActCodes", packed: torch.Tensor, N: int, n_out: int,
+                         y: torch.Tensor, dbg=(), want_asym: bool = False) -> None:
+    """Sizes the kernels rely on: a mismatch would make them read or write past a buffer."""
+    M, K, r = act.M, act.K, act.r
+    need = resq_packed_weight_bytes(N, K, r)
+    if need == 0:
+        raise ValueError(f"{where}: invalid (N, K, r) = ({N}, {K}, {r})")
+    if packed.numel() < need:
+        raise ValueError(f"{where}: packed holds {packed.numel()} bytes, (N, K, r) = ({N}, {K}, {r}) needs {need}")
+    if act.asym != want_asym:
+        raise ValueError(f"{where}: the activation codes are {'asymmetric' if act.asym else 'symmetric'}; "
+                         f"use resq_gemm_mixed{'_asym' if act.asym else ''}")
+    if tuple(y.shape) != (M, n_out):
+        raise ValueError(f"{where}: y must be [{M}, {n_out}], got {tuple(y.shape)}")
+    for name, t in dbg:
+        if t is not None and (tuple(t.shape) != (M, N) or not t.is_contiguous()):
+            raise ValueError(f"{where}: {name} must be a contiguous [{M}, {N}] tensor")
+    if act.q_hi.shape != (M, act.ld_hi) or act.q_lo.shape != (M, act.ld_lo) or act.ld_hi != resq_act_hi_ld(K, r) \
+            or act.ld_lo != resq_act_lo_ld(K, r):
+        raise ValueError(f"{where}: activation code buffers do not match (M, K, r) = ({M}, {K}, {r})")
+
+
 def _stream(stream) -> int:
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
@@ -212,6 +234,10 @@ def resq_quantize_gemm_mixed(x: torch.Tensor, packed: torch.Tensor, N: int, r: i
         y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
     if y.stride(1) != 1:
         raise ValueError("y must be row-major")
+    need = resq_packed_weight_bytes(N, K, r)
+    if need == 0 or packed.numel() < need or tuple(y.shape) != (M, N):
+        raise ValueError(f"resq_quantize_gemm_mixed: packed ({packed.numel()} bytes, needs {need}) or y "
+                         f"{tuple(y.shape)} do not match (M, N, K, r) = ({M}, {N}, {K}, {r})")
     st = lib().resq_quantize_gemm_mixed(
         _dev(x, torch.bfloat16, "x"), x.stride(0), M, _dev(packed, torch.uint8, "packed"), N, K, r,
         _dev(y, torch.bfloat16, "y"), y.stride(0), _stream(stream))
@@ -251,6 +277,8 @@ def resq_gemm_mixed_asym(act: ActCodes, packed: torch.Tensor, N: int,
         y = torch.empty((M, N), dtype=torch.bfloat16, device=packed.device)
     if y.stride(1) != 1:
         raise ValueError("y must be row-major")
+    _check_layer_buffers("resq_gemm_mixed_asym", act, packed, N, N, y,
+                         (("dbg_acc_hi", dbg_acc_hi), ("dbg_acc_lo", dbg_acc_lo)), want_asym=True)
     hi, lo = r > 0, K - r > 0
     st = lib().resq_gemm_mixed_asym(
         act.q_hi.data_ptr() if hi else None, act.q_lo.data_ptr() if lo else None,
@@ -279,6 +307,9 @@ def resq_pack_weights(w: torch.Tensor, r: int, packed: Optional[torch.Tensor] = 
 
 def resq_unpack_weights(packed: torch.Tensor, N: int, K: int, r: int, stream=None):
     dev = packed.device
+    need = resq_packed_weight_bytes(N, K, r)
+    if need == 0 or packed.numel() < need:
+        raise ValueError(f"resq_unpack_weights: packed holds {packed.numel()} bytes, (N, K, r) = ({N}, {K}, {r}) needs {need}")
     w_hi = torch.empty((N, r), dtype=torch.int8, device=dev)
     w_lo = torch.empty((N, K - r), dtype=torch.int8, device=dev)
     sw_hi = torch.empty(N, dtype=torch.int16, device=dev)
@@ -300,6 +331,8 @@ def resq_gemm_mixed(act: ActCodes, packed: torch.Tensor, N: int, y: Optional[tor
         y = torch.empty((M, N), dtype=torch.bfloat16, device=packed.device)
     if y.stride(1) != 1:
         raise ValueError("y must be row-major")
+    _check_layer_buffers("resq_gemm_mixed", act, packed, N, N, y,
+                         (("dbg_acc_hi", dbg_acc_hi), ("dbg_acc_lo", dbg_acc_lo)))
     st = lib().resq_gemm_mixed(act.q_hi.data_ptr() if r > 0 else None,
                                act.q_lo.data_ptr() if K - r > 0 else None,
                                act.s_hi.data_ptr() if r > 0 else None,
@@ -321,6 +354,9 @@ def resq_gemm_mixed_swiglu(act: ActCodes, packed: torch.Tensor, N2: int,
         y = torch.empty((M, N2 // 2), dtype=torch.bfloat16, device=packed.device)
     if y.stride(1) != 1:
         raise ValueError("y must be row-major")
+    if N2 % 2:
+        raise ValueError("resq_gemm_mixed_swiglu: N2 must be even (interleaved gate and up rows)")
+    _check_layer_buffers("resq_gemm_mixed_swiglu", act, packed, N2, N2 // 2, y)
     hi, lo = r > 0, K - r > 0
     st = lib().resq_gemm_mixed_swiglu(
         act.q_hi.data_ptr() if hi else None, act.q_lo.data_ptr() if lo else None,
@@ -390,6 +426,10 @@ def resq_project_heads(x: torch.Tensor, packed: torch.Tensor, y: Optional[torch.
         y = torch.empty((rows, d), dtype=torch.bfloat16, device=x.device)
     if y.stride(1) != 1:
         raise ValueError("y must be row-major")
+    need = resq_packed_weight_bytes(d, d, d)
+    if need == 0 or packed.numel() < need or tuple(y.shape) != (rows, d):
+        raise ValueError(f"resq_project_heads: packed ({packed.numel()} bytes, needs {need}) or y {tuple(y.shape)} "
+                         f"do not match rows = {rows}, d_head = {d}")
     st = lib().resq_project_heads(_dev(x, torch.bfloat16, "x"), x.stride(0), rows, d,
                                   _dev(packed, torch.uint8, "packed"),
                                   _dev(y, torch.bfloat16, "y"), y.stride(0),

@@ -44,9 +44,15 @@ def build(verbose: bool = False, extra_flags: list[str] | None = None) -> Path:
 
 
 def ensure_built() -> Path:
-    """Return the library path, compiling only if no library is there."""
+    """Return the library path, compiling if no library is there or a source is newer than it
+    (where there is no compiler, e.g. a box that only runs what was built, a library that is
+    there is used as it is)."""
     if not LIB.exists():
         build()
+    else:
+        newest = max(p.stat().st_mtime for p in [*CSRC.iterdir(), ROOT / "include" / "resq.h"])
+        if newest > LIB.stat().st_mtime and shutil.which("hipcc"):
+            build()
     return LIB
 
 

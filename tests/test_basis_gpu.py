@@ -95,7 +95,9 @@ def test_project_rows_on_column_blocks(rq):
                        p[:, :r].double().cpu().numpy() @ r_h.double().cpu().numpy(), atol=1e-6)
 
 
-@pytest.mark.parametrize("K,r", [(8, 2), (64, 8), (128, 16), (256, 32)])
+@pytest.mark.parametrize("K,r", [(8, 2), (64, 8), (128, 16), (256, 32),
+                                 (1024, 128),      # a hidden-size basis of a small model
+                                 (4608, 576)])     # two rows of this order need more than 64 KiB of LDS
 def test_sym_eig_against_oracle(rq, K, r):
     # planted spectrum with an open gap after the r-th eigenvalue
     sig = np.concatenate([np.linspace(30.0, 20.0, r), np.linspace(4.0, 0.5, K - r)])
@@ -103,14 +105,15 @@ def test_sym_eig_against_oracle(rq, K, r):
     c = (q * sig ** 2) @ q.T
     c32 = torch.tensor(c, dtype=torch.float32)
     lam_ref, p_ref = bo.pca_basis(c32.double().numpy())
-    lam, p = rq.resq_sym_eig(c32.cuda(), sweeps=10)
+    lam, p = rq.resq_sym_eig(c32.cuda(), sweeps=10 if K <= 256 else 14)
     torch.cuda.synchronize()
     lam, p = lam.double().cpu().numpy(), p.double().cpu().numpy()
     scale = lam_ref[0]
     assert np.all(np.diff(lam) <= 0)
     assert np.allclose(lam, lam_ref, atol=1e-6 * scale)          # fp32 outputs of an fp64 iteration
     assert np.allclose(p.T @ p, np.eye(K), atol=1e-5)             # orthonormal columns
-    assert np.abs(c32.double().numpy() @ p - p * lam).max() <= 1e-5 * scale   # eigenpairs of the input
+    # eigenpairs of the input; the fp32 rounding of the K entries of a vector adds up in c @ p
+    assert np.abs(c32.double().numpy() @ p - p * lam).max() <= (1e-5 if K <= 256 else 4e-5) * scale
     # the high-precision subspace is the oracle's
     assert np.allclose(p[:, :r] @ p[:, :r].T, p_ref[:, :r] @ p_ref[:, :r].T, atol=1e-4)
 

@@ -189,6 +189,36 @@ def test_binding_fails_loudly_without_device_tensors():
         binding.resq_quantize_act(x, 32)
 
 
+def test_binding_rejects_buffers_that_do_not_fit_the_shape():
+    # the kernels trust (M, N, K, r): the binding checks the buffers against them before any call
+    import torch
+    M, K, N, r = 4, 256, 64, 32
+    act = binding.ActCodes(M, K, r, device="cpu")
+    packed = torch.zeros(binding.resq_packed_weight_bytes(N, K, r), dtype=torch.uint8)
+    with pytest.raises(ValueError, match="packed holds"):
+        binding.resq_gemm_mixed(act, packed[:-16], N)
+    with pytest.raises(ValueError, match="packed holds"):
+        binding.resq_gemm_mixed(act, packed, 8 * N)                      # more channels than were packed
+    with pytest.raises(ValueError, match="y must be"):
+        binding.resq_gemm_mixed(act, packed, N, y=torch.zeros(M, N - 8, dtype=torch.bfloat16))
+    with pytest.raises(ValueError, match="dbg_acc_hi"):
+        binding.resq_gemm_mixed(act, packed, N, dbg_acc_hi=torch.zeros(M, N - 1, dtype=torch.int32))
+    with pytest.raises(ValueError, match="symmetric"):
+        binding.resq_gemm_mixed_asym(act, packed, N)                     # symmetric codes into the asymmetric entry
+    act.asym = True
+    with pytest.raises(ValueError, match="asymmetric"):
+        binding.resq_gemm_mixed(act, packed, N)
+    act.asym = False
+    with pytest.raises(ValueError, match="even"):
+        binding.resq_gemm_mixed_swiglu(act, packed, N + 1)
+    with pytest.raises(ValueError, match="packed holds"):
+        binding.resq_unpack_weights(packed[:100], N, K, r)
+    other = binding.ActCodes(M, 2 * K, r, device="cpu")
+    other.K = K                                                          # buffers of another row length
+    with pytest.raises(ValueError, match="activation code buffers"):
+        binding.resq_gemm_mixed(other, packed, N)
+
+
 def test_quantize_gemm_mixed_rejects_bad_arguments():
     f = binding.lib().resq_quantize_gemm_mixed
     P256 = P - P % 256 + 256

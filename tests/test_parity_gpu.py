@@ -144,6 +144,27 @@ def test_quantize_act_strided_rows_zero_rows_and_ties(oracle, rq):
     assert s_hi[1] == 1 and s_lo[1] == 1 and s_hi[2] == 1 and s_lo[3] == 1
 
 
+@pytest.mark.parametrize("K,r", [(512, 64), (4096, 512), (250, 30), (128, 16)])
+def test_quantize_act_rows_with_tiny_scales(oracle, rq, K, r):
+    # rows whose absmax is so small that the reciprocal of the scale overflows (scale below
+    # 2^-128): the kernels multiply by that reciprocal and must fall back to the division of
+    # the definition for every element of such a row
+    g = torch.Generator().manual_seed(K)
+    x = torch.randn(6, K, generator=g)
+    x[1] *= 2.0 ** -125
+    x[2] *= 2.0 ** -121          # scales around 2^-126: reciprocal finite, quotients fine
+    x[3] = 0
+    x[3, 5] = 2.0 ** -126
+    x[3, K - 3] = -(2.0 ** -126)
+    x[4, :r] *= 2.0 ** -124      # only the high group tiny
+    x[5, r:] *= 2.0 ** -124      # only the low group tiny
+    x = x.to(torch.bfloat16)
+    check_act_codes(oracle, rq, x, r)
+    act = rq.resq_quantize_act_asym(x.cuda(), r)
+    torch.cuda.synchronize()
+    compare_asym_codes(oracle, act, wl.bf16_bits(x), r)
+
+
 # ---- weights ---------------------------------------------------------------
 
 @pytest.mark.parametrize("N,K,r", [(256, 256, 32), (300, 520, 72), (17, 90, 30), (64, 512, 0),
@@ -223,6 +244,9 @@ def test_layer_decode_long_rows(oracle, rq, M, K, N, r):
 TILED_SHAPES = [
     (1030, 640, 300, 128), (1100, 1000, 515, 104), (1025, 90, 40, 30),
     (1153, 256, 256, 0), (1153, 256, 256, 256), (1200, 2048, 768, 256),
+    # 16 x 4 = 64 tiles: a multiple of 8 that is not a multiple of 256, the tile order that deals
+    # contiguous runs of tiles to the eight XCDs (e.g. a grouped-query key/value projection); ragged M too
+    (2048, 256, 1024, 32), (1925, 256, 1024, 32),
 ]
 
 
@@ -325,10 +349,11 @@ def test_layer_batched_decode_full_size(oracle, rq):
     check_layer(oracle, rq, wl.make_activations(s), wl.make_weights(s), s.r)
 
 
-def test_layer_decode_full_size(oracle, rq):
-    # the decode workload at full size (Llama-3-70B up_proj, 16 tokens); the oracle
-    # checks all codes and every accumulator and output
-    s = wl.decode_shape(16)
+@pytest.mark.parametrize("M", [16, 1])
+def test_layer_decode_full_size(oracle, rq, M):
+    # the decode workload at full size (Llama-3-70B up_proj, 16 tokens and a single token); the
+    # oracle checks all codes and every accumulator and output
+    s = wl.decode_shape(M)
     check_layer(oracle, rq, wl.make_activations(s), wl.make_weights(s), s.r)
 
 
@@ -365,18 +390,22 @@ def test_layer_saturated_codes(oracle, rq):
     check_layer(oracle, rq, x.to(torch.bfloat16), w.to(torch.bfloat16), r)
 
 
-@pytest.mark.parametrize("which", ["oproj_prefill", "gate_up_prefill", "qwen_r1024"])
+QWEN_SNR = {}   # r -> (SNR of the HIP path, SNR of the oracle) on the sampled rows, filled by the test below
+
+
+@pytest.mark.parametrize("which", ["oproj_prefill", "gate_up_prefill", "qwen_r0", "qwen_r1024", "qwen_r2048"])
 def test_layer_prefill_full_size_sampled(oracle, rq, which):
     # the benchmark's prefill configurations at full size, in the launch configuration the
     # benchmark times; the oracle checks all activation codes, all packed weights, and a
-    # seeded sample of token rows of the accumulators and outputs
+    # seeded sample of token rows of the accumulators and outputs.  For the Qwen-72B shape
+    # (r = 0, K/8, K/4: the rank sweep) the output SNR on those rows is taken too.
     s = {"oproj_prefill": wl.OPROJ_PREFILL, "gate_up_prefill": wl.MLP_GATE_UP,
-         "qwen_r1024": wl.qwen_mlp_shape(1024)}[which]
+         "qwen_r0": wl.qwen_mlp_shape(0), "qwen_r1024": wl.qwen_mlp_shape(1024),
+         "qwen_r2048": wl.qwen_mlp_shape(2048)}[which]
     nrows = 48 if which == "oproj_prefill" else 24
     x, w = wl.make_activations(s), wl.make_weights(s)
     act = check_act_codes(oracle, rq, x, s.r)
     packed, wq = check_weights(oracle, rq, w, s.r)
-    del w
     dbg_hi = torch.empty((s.M, s.N), dtype=torch.int32, device="cuda")
     dbg_lo = torch.empty((s.M, s.N), dtype=torch.int32, device="cuda")
     y = rq.resq_gemm_mixed(act, packed, s.N, dbg_acc_hi=dbg_hi, dbg_acc_lo=dbg_lo)
@@ -384,13 +413,29 @@ def test_layer_prefill_full_size_sampled(oracle, rq, which):
     rows = np.sort(np.random.default_rng(0).choice(s.M, nrows, replace=False))
     rt = torch.from_numpy(rows).cuda()
     ref = oracle.linear(wl.bf16_bits(x[rows]), None, s.r, weights=wq)
-    assert np.array_equal(dbg_hi[rt].cpu().numpy().astype(np.int64), ref.acc_hi)
+    if s.r > 0:
+        assert np.array_equal(dbg_hi[rt].cpu().numpy().astype(np.int64), ref.acc_hi)
     assert np.array_equal(dbg_lo[rt].cpu().numpy().astype(np.int64), ref.acc_lo)
     assert y_within_tolerance(y[rt], ref.y) <= REL_TOL
     del dbg_hi, dbg_lo
     y2 = rq.resq_gemm_mixed(act, packed, s.N)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
+    if which.startswith("qwen"):
+        exact = x[rows].double().numpy() @ w.double().numpy().T      # the unquantized layer, fp64
+        snr_gpu = oracle.snr_db(exact, y[rt].float().cpu().numpy())
+        snr_cpu = oracle.snr_db(exact, ref.y)
+        assert abs(snr_gpu - snr_cpu) < 0.05, (s.r, snr_gpu, snr_cpu)
+        QWEN_SNR[s.r] = (snr_gpu, snr_cpu)
+
+
+def test_qwen_snr_grows_with_rank_at_full_size():
+    # Section 5.4's rank ablation on the synthetic Qwen-72B-shaped layer, at full size: more
+    # columns in 8 bits, higher output SNR (needs the three sampled cases above to have run)
+    if sorted(QWEN_SNR) != [0, 1024, 2048]:
+        pytest.skip("the three Qwen-72B cases of test_layer_prefill_full_size_sampled did not all run")
+    assert QWEN_SNR[0][0] < QWEN_SNR[1024][0] < QWEN_SNR[2048][0], QWEN_SNR
+    print("SNR dB per r (HIP path, oracle):", QWEN_SNR)
 
 
 # ---- Hadamard --------------------------------------------------------------
@@ -451,6 +496,50 @@ def test_down_proj_chain_end_to_end(oracle, rq, M, K, N, r):
     xr = oracle.hadamard(wl.bf16_bits(x[rows]), r, K, b)
     ref = oracle.linear(xr, wl.bf16_bits(w), r)
     assert y_within_tolerance(y[torch.from_numpy(rows).cuda()], ref.y) <= REL_TOL
+
+
+def test_down_proj_full_size_sampled_integers(oracle, rq):
+    # the benchmark's down_proj workload (M = 4096, K = 14336, N = 4096, r = 1792) in the launch
+    # configuration the benchmark times, integers included: the fused transform + quantizer
+    # hands out its rotated rows, which are checked against the oracle's transform like the
+    # stand-alone kernel's; codes, scales and sums of a sample of token rows bit-exact against
+    # the oracle's quantizer on those rotated rows; all packed weights; both accumulators and
+    # the outputs of the sampled rows against the oracle's GEMMs on the oracle's codes
+    s = wl.MLP_DOWN
+    x, w = wl.make_activations(s), wl.make_weights(s)
+    xd = x.cuda()
+    x_rot = torch.zeros_like(xd)
+    act = rq.resq_hadamard_quantize_act(xd, s.r, 0, x_rot=x_rot)
+    packed, wq = check_weights(oracle, rq, w, s.r)
+    dbg_hi = torch.empty((s.M, s.N), dtype=torch.int32, device="cuda")
+    dbg_lo = torch.empty((s.M, s.N), dtype=torch.int32, device="cuda")
+    y = rq.resq_gemm_mixed(act, packed, s.N, dbg_acc_hi=dbg_hi, dbg_acc_lo=dbg_lo)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(2).choice(s.M, 24, replace=False))
+    rt = torch.from_numpy(rows).cuda()
+    b = rq.resq_hadamard_block(s.K - s.r)
+    got = wl.bf16_bits(x_rot[rt].cpu())
+    want = oracle.hadamard(wl.bf16_bits(x[rows]), s.r, s.K, b)
+    g64, w64 = wl.bits_to_f64(got[:, s.r:]), wl.bits_to_f64(want[:, s.r:])
+    scale = np.abs(w64).max()
+    assert np.all(np.abs(g64 - w64) <= np.maximum(np.abs(w64), 2.0 ** -8 * scale) * 2.0 ** -7)
+    assert np.mean(got[:, s.r:] == want[:, s.r:]) > 0.99
+    rotated = wl.bf16_bits(x[rows]).copy()
+    rotated[:, s.r:] = got[:, s.r:]
+    q_hi, q_lo, s_hi, s_lo = oracle.quantize_act(rotated, s.r)
+    assert np.array_equal(act.q_hi[rt].cpu().numpy()[:, :s.r], q_hi), "INT8 codes differ"
+    assert np.array_equal(act.q_lo[rt].cpu().numpy(), oracle.pack_nibbles(q_lo, act.ld_lo)), "INT4 codes differ"
+    assert np.array_equal(act.s_hi[rt].cpu().numpy().view(np.uint32), s_hi.view(np.uint32))
+    assert np.array_equal(act.s_lo[rt].cpu().numpy().view(np.uint32), s_lo.view(np.uint32))
+    assert np.array_equal(act.lo_sum[rt].cpu().numpy(), oracle.odd_code_sums(q_lo)), "lo_sum differs"
+    ref = oracle.linear(rotated, None, s.r, weights=wq)
+    assert np.array_equal(dbg_hi[rt].cpu().numpy().astype(np.int64), ref.acc_hi), "A_hi differs"
+    assert np.array_equal(dbg_lo[rt].cpu().numpy().astype(np.int64), ref.acc_lo), "A_lo differs"
+    assert y_within_tolerance(y[rt], ref.y) <= REL_TOL
+    del dbg_hi, dbg_lo
+    y2 = rq.resq_gemm_mixed(act, packed, s.N)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
 
 
 @pytest.mark.parametrize("M,K,r,block", [
