@@ -328,6 +328,22 @@ int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigv
                  int64_t ldp, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * resq_sym_eig for callers that cannot allocate device memory and have no workspace to pass
+ * (code under HIP graph capture, serving loops and harnesses that forbid hipMalloc, a basis
+ * refreshed between requests): the same kernels on the same arguments, with the workspace in
+ * a device array that is part of the library (4.2 MB on every GPU the library has run this
+ * call on, held until the process ends).  The call allocates and frees nothing.
+ *   K   even, 2 .. 512 (head-size and small hidden-size bases); larger: RESQ_ERR_BUFFER,
+ *       nothing is launched
+ * Results are those of resq_sym_eig bit for bit.  All calls on one GPU share the one array:
+ * calls that overlap on a GPU (different streams or host threads) race, and its contents
+ * after a call are meaningless (every call initializes what it reads).  RESQ_ERR_HIP if the
+ * array's address cannot be obtained on the current device.
+ */
+int resq_sym_eig_static(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p,
+                        int64_t ldp, void* stream);
+
+/*
  * 3. Rows expressed in a basis:  out[i][j] = sum_k a[i][k] u[k][j]  (fp32
  *    accumulation on the fp32 matrix cores).  This one product serves every
  *    remaining step: U_h = P_h R_h and U_l = P_l R_l (the definition of U in

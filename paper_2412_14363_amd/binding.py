@@ -39,6 +39,7 @@ SYMBOLS = {
     "resq_gram_accumulate": (C.c_int, [_p, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_sym_eig_workspace_bytes": (_sz, [_i64]),
     "resq_sym_eig": (C.c_int, [_p, _i64, _i64, C.c_int, _p, _p, _i64, _p, _sz, _p]),
+    "resq_sym_eig_static": (C.c_int, [_p, _i64, _i64, C.c_int, _p, _p, _i64, _p]),
     "resq_project_rows": (C.c_int, [_p, C.c_int, _i64, _i64, _i64, _p, _i64, _i64, _p, C.c_int, _i64, _p]),
     "resq_project_heads": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _i64, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
@@ -390,6 +391,18 @@ def resq_sym_eig(c: torch.Tensor, sweeps: int = 12, stream=None):
     st = lib().resq_sym_eig(_dev(c, torch.float32, "c"), c.stride(0), K, sweeps, lam.data_ptr(), p.data_ptr(),
                             p.stride(0), work.data_ptr(), nbytes, _stream(stream))
     _check(st, "resq_sym_eig")
+    return lam, p
+
+
+def resq_sym_eig_static(c: torch.Tensor, lam: torch.Tensor, p: torch.Tensor, sweeps: int = 12, stream=None):
+    """resq_sym_eig into caller-provided outputs (lam fp32 [K], p fp32 [K, K]) on the library's
+    built-in scratch area (K <= 512): the call itself allocates nothing."""
+    K = c.shape[0]
+    if tuple(lam.shape) != (K,) or tuple(p.shape) != (K, K) or p.stride(1) != 1:
+        raise ValueError("lam must be [K] and p a row-major [K, K]")
+    st = lib().resq_sym_eig_static(_dev(c, torch.float32, "c"), c.stride(0), K, sweeps, _dev(lam, torch.float32, "lam"),
+                                   _dev(p, torch.float32, "p"), p.stride(0), _stream(stream))
+    _check(st, "resq_sym_eig_static")
     return lam, p
 
 

@@ -4,6 +4,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "resq.h"
 #include "resq_decode.hip.h"
 #include "resq_eig.hip.h"
@@ -44,6 +46,31 @@ inline void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, 
     hipExtLaunchKernelGGL(kernel, grid, block, lds, st, e0, e1, 0, args...);
 }
 
+// ---- built-in scratch area of resq_sym_eig_static -------------------------------------------
+// Largest order it serves, and the bytes that order needs (the layout of
+// resq_sym_eig_workspace_bytes: matrix and transposed vectors in fp64, the round's rotations
+// and pairs, the per-sweep counters).
+constexpr int64_t kEigStaticMaxOrder = 512;
+constexpr size_t kEigStaticBytes = 2 * (size_t)kEigStaticMaxOrder * kEigStaticMaxOrder * sizeof(double) +
+                                   (size_t)kEigStaticMaxOrder * sizeof(double) + 256 +
+                                   (size_t)kEigStaticMaxOrder * sizeof(int) + 256 + kEigMaxSweeps * sizeof(int) + 256;
+static __device__ __align__(256) unsigned char g_eig_scratch[kEigStaticBytes];
+
+// The array's name is a host-side stand-in; its device address differs per GPU and is looked
+// up once per device, with that device current, and kept.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_eig_scratch_addr[kMaxDevices];
+
+void* eig_scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* ptr = g_eig_scratch_addr[dev].load(std::memory_order_acquire);
+    if (ptr) return ptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_eig_scratch)) != hipSuccess || !ptr) return nullptr;
+    g_eig_scratch_addr[dev].store(ptr, std::memory_order_release);   // every thread finds the same address
+    return ptr;
+}
+
 }  // namespace
 
 extern "C" {
@@ -54,7 +81,7 @@ const char* resq_status_string(int status) {
         case RESQ_ERR_NULL: return "RESQ_ERR_NULL: a required pointer is null";
         case RESQ_ERR_SHAPE: return "RESQ_ERR_SHAPE: invalid sizes, group width or leading dimension";
         case RESQ_ERR_ALIGN: return "RESQ_ERR_ALIGN: pointer or leading dimension misaligned";
-        case RESQ_ERR_BUFFER: return "RESQ_ERR_BUFFER: packed weight buffer too small";
+        case RESQ_ERR_BUFFER: return "RESQ_ERR_BUFFER: packed weight buffer, workspace or built-in scratch area too small";
         case RESQ_ERR_HIP: return "RESQ_ERR_HIP: the HIP runtime refused the launch";
         default: return "unknown resq status";
     }
@@ -679,13 +706,9 @@ size_t resq_sym_eig_workspace_bytes(int64_t K) {
            round_up(K * (int64_t)sizeof(int), 256) + round_up(kEigMaxSweeps * (int64_t)sizeof(int), 256);
 }
 
-int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p, int64_t ldp,
-                 void* workspace, size_t workspace_bytes, void* stream) {
-    if (K < 2 || K % 2 != 0 || K > kEigMaxOrder || ldc < K || ldp < K || sweeps < 1 || sweeps > kEigMaxSweeps)
-        return RESQ_ERR_SHAPE;
-    if (!c || !eigvals || !p || !workspace) return RESQ_ERR_NULL;
-    if (!aligned(c, 4) || !aligned(eigvals, 4) || !aligned(p, 4) || !aligned(workspace, 256)) return RESQ_ERR_ALIGN;
-    if (workspace_bytes < resq_sym_eig_workspace_bytes(K)) return RESQ_ERR_BUFFER;
+// the Jacobi iteration on a workspace that holds resq_sym_eig_workspace_bytes(K) bytes
+static int sym_eig_on_workspace(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p,
+                                int64_t ldp, void* workspace, void* stream) {
     const int n = (int)K;
     const size_t nn = (size_t)round_up((int64_t)((size_t)n * n * sizeof(double)), 256);
     uint8_t* w = static_cast<uint8_t*>(workspace);
@@ -714,6 +737,29 @@ int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigv
     }
     launch(eig_finish_kernel, dim3((unsigned)n), dim3(kEigThreads), 0, st, e, eigvals, p, ldp);
     return launch_status();
+}
+
+int resq_sym_eig(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p, int64_t ldp,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (K < 2 || K % 2 != 0 || K > kEigMaxOrder || ldc < K || ldp < K || sweeps < 1 || sweeps > kEigMaxSweeps)
+        return RESQ_ERR_SHAPE;
+    if (!c || !eigvals || !p || !workspace) return RESQ_ERR_NULL;
+    if (!aligned(c, 4) || !aligned(eigvals, 4) || !aligned(p, 4) || !aligned(workspace, 256)) return RESQ_ERR_ALIGN;
+    if (workspace_bytes < resq_sym_eig_workspace_bytes(K)) return RESQ_ERR_BUFFER;
+    return sym_eig_on_workspace(c, ldc, K, sweeps, eigvals, p, ldp, workspace, stream);
+}
+
+int resq_sym_eig_static(const float* c, int64_t ldc, int64_t K, int sweeps, float* eigvals, float* p,
+                        int64_t ldp, void* stream) {
+    if (K < 2 || K % 2 != 0 || K > kEigMaxOrder || ldc < K || ldp < K || sweeps < 1 || sweeps > kEigMaxSweeps)
+        return RESQ_ERR_SHAPE;
+    if (K > kEigStaticMaxOrder || resq_sym_eig_workspace_bytes(K) > kEigStaticBytes)
+        return RESQ_ERR_BUFFER;   // beyond the built-in scratch area
+    if (!c || !eigvals || !p) return RESQ_ERR_NULL;
+    if (!aligned(c, 4) || !aligned(eigvals, 4) || !aligned(p, 4)) return RESQ_ERR_ALIGN;
+    void* scratch = eig_scratch_on_current_device();
+    if (!scratch) return RESQ_ERR_HIP;
+    return sym_eig_on_workspace(c, ldc, K, sweeps, eigvals, p, ldp, scratch, stream);
 }
 
 }  // extern "C"

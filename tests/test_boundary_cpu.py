@@ -175,6 +175,10 @@ def test_basis_entry_points_reject_bad_arguments():
     assert e(P, 64, 64, 0, P, P, 64, P, 1 << 30, None) == 2                  # no sweeps
     assert e(P, 64, 64, 8, P, P, 64, P, 100, None) == 4                      # workspace too small
     assert e(P, 64, 64, 8, P, P, 64, None, 1 << 30, None) == 1
+    es = L.resq_sym_eig_static                                              # the variant on the built-in scratch area
+    assert es(P, 514, 514, 8, P, P, 514, None) == 4                          # beyond its 512: nothing is launched
+    assert es(P, 64, 63, 8, P, P, 64, None) == 2 and es(None, 64, 64, 8, P, P, 64, None) == 1
+    assert es(P, 64, 64, 8, P + 2, P, 64, None) == 3
     r = L.resq_project_rows
     assert r(P, 1, 64, 8, 64, P, 60, 64, P, 1, 64, None) == 2                # ldu < J
     assert r(P, 1, 64, 8, 64, P, 64, 60, P, 1, 64, None) == 3                # J % 8 != 0
