@@ -607,3 +607,30 @@ def test_swiglu_definition(oracle):
     assert np.allclose(oracle.swiglu(ones) - oracle.swiglu(neg), y[:, 0::2], rtol=1e-12)
     probe = np.array([[0.0, 5.0, 40.0, 2.0, -40.0, 3.0]])
     assert np.allclose(oracle.swiglu(probe), [[0.0, 80.0, 0.0]], atol=1e-12)
+
+
+# ---- the oracle under sanitizers ---------------------------------------------------
+
+def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    # every entry point of resq_oracle.c on small ragged shapes with exactly sized heap
+    # buffers, built with -fsanitize=address,undefined (CPU only; a stand-alone program, so
+    # that nothing has to be preloaded into the interpreter)
+    import shutil
+    import subprocess
+    from pathlib import Path
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = Path(__file__).resolve().parent.parent / "oracle" / "resq_oracle_sancheck.c"
+    exe = tmp_path / "sancheck"
+    build = subprocess.run(["gcc", "-std=c11", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined",
+                            "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-ffp-contract=off",
+                            "-o", str(exe), str(src), "-lm"], capture_output=True, text=True)
+    if build.returncode != 0 and "asan" in build.stderr.lower():
+        pytest.skip("this gcc has no sanitizer runtime")
+    assert build.returncode == 0, build.stderr
+    import os
+    run = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120,
+                         env={**os.environ, "ASAN_OPTIONS": "detect_leaks=1:verify_asan_link_order=0",
+                              "OMP_NUM_THREADS": "4"})
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert "clean" in run.stdout and "runtime error" not in run.stderr
