@@ -216,6 +216,47 @@ def quantize_act_asym(x_bits: np.ndarray, r: int):
     return q_hi, q_lo, s_hi, s_lo, z_hi, z_lo
 
 
+def kv_cache_row_bytes(d_head: int, r: int) -> int:
+    """Bytes of one cache row (one head of one token): r codes of 8 bits, d_head - r codes of 4
+    bits, and scale and zero-point of both groups in fp32."""
+    return r + (d_head - r) // 2 + 16
+
+
+def pack_kv_cache(q_hi: np.ndarray, q_lo: np.ndarray, s_hi, z_hi, s_lo, z_lo) -> np.ndarray:
+    """Compact storage of mixed-precision K/V cache entries (Section 5.1 and Appendix C: the
+    cache is quantized per head, asymmetrically, an eighth of the channels in 8 bits).  One row
+    per head of a token, no padding:
+        bytes [0, r)                 the 8-bit codes of Eq. 1's asymmetric branch, 0..255
+        bytes [r, r + (d - r)/2)     the 4-bit codes, 0..15, channel r + 2j in bits 0..3 of byte j,
+                                     channel r + 2j + 1 in bits 4..7
+        then four little-endian fp32: s_hi, z_hi, s_lo, z_lo   (x ~ code * s + z per group)
+    The codes and parameters are those of quantize_act_asym on rows of d_head columns."""
+    q_hi, q_lo = _c(q_hi, np.uint8), _c(q_lo, np.uint8)
+    rows, r = q_hi.shape
+    kl = q_lo.shape[1]
+    assert kl % 2 == 0 and q_lo.shape[0] == rows
+    out = np.zeros((rows, r + kl // 2 + 16), np.uint8)
+    out[:, :r] = q_hi
+    out[:, r:r + kl // 2] = q_lo[:, 0::2] | (q_lo[:, 1::2] << 4)
+    params = np.stack([np.asarray(v, np.float32) for v in (s_hi, z_hi, s_lo, z_lo)], axis=1)
+    out[:, r + kl // 2:] = params.astype("<f4").view(np.uint8).reshape(rows, 16)
+    return out
+
+
+def dequantize_kv_cache(cache: np.ndarray, d_head: int, r: int) -> np.ndarray:
+    """What a reader of the cache reconstructs (Eq. 1): code * s + z per group, in fp64."""
+    cache = _c(cache, np.uint8)
+    rows = cache.shape[0]
+    kl = d_head - r
+    par = cache[:, r + kl // 2:r + kl // 2 + 16].copy().view("<f4").astype(np.float64)
+    x = np.zeros((rows, d_head), np.float64)
+    x[:, :r] = cache[:, :r].astype(np.float64) * par[:, 0:1] + par[:, 1:2]
+    lo = cache[:, r:r + kl // 2]
+    x[:, r + 0::2] = (lo & 15).astype(np.float64) * par[:, 2:3] + par[:, 3:4]
+    x[:, r + 1::2] = (lo >> 4).astype(np.float64) * par[:, 2:3] + par[:, 3:4]
+    return x
+
+
 def gemm_u8i8_i64(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     """acc[m,n] = sum_k a[m,k] b[n,k] for unsigned a and signed b, exact in int64."""
     a = _c(a, np.uint8)

@@ -609,6 +609,46 @@ def test_swiglu_definition(oracle):
     assert np.allclose(oracle.swiglu(probe), [[0.0, 80.0, 0.0]], atol=1e-12)
 
 
+# ---- compact K/V cache rows (Section 5.1, Appendix C) -------------------------------
+
+def test_kv_cache_row_matches_the_hand_derived_bytes(oracle):
+    path = GOLDEN / "kv_cache_row.txt"
+    rows = [ln for ln in path.read_text().splitlines() if ln.strip() and not ln.startswith("#")]
+    assert rows
+    for ln in rows:
+        head, xs, hx = [f.strip() for f in ln.split("|")]
+        d, r = (int(v) for v in head.split())
+        x = np.array([[float(v) for v in xs.split()]])
+        want = np.array([int(b, 16) for b in hx.split()], np.uint8)
+        q_hi, q_lo, s_hi, s_lo, z_hi, z_lo = oracle.quantize_act_asym(bits_of(x), r)
+        row = oracle.pack_kv_cache(q_hi, q_lo, s_hi, z_hi, s_lo, z_lo)
+        assert row.shape == (1, oracle.kv_cache_row_bytes(d, r)) == (1, len(want))
+        assert np.array_equal(row[0], want)
+        # and a reader gets every channel back to within half a step of its group (Eq. 1)
+        back = oracle.dequantize_kv_cache(row, d, r)
+        assert np.all(np.abs(back[0, :r] - x[0, :r]) <= 0.5 * s_hi[0] + 1e-12)
+        assert np.all(np.abs(back[0, r:] - x[0, r:]) <= 0.5 * s_lo[0] + 1e-12)
+
+
+def test_kv_cache_pack_is_a_bijection_on_codes_and_keeps_group_order(oracle):
+    # brute force on random codes: every code can be read back from its place, low nibble first
+    rng = np.random.default_rng(3)
+    rows, d, r = 5, 32, 8
+    q_hi = rng.integers(0, 256, (rows, r)).astype(np.uint8)
+    q_lo = rng.integers(0, 16, (rows, d - r)).astype(np.uint8)
+    s_hi, z_hi, s_lo, z_lo = (rng.standard_normal(rows).astype(np.float32) for _ in range(4))
+    c = oracle.pack_kv_cache(q_hi, q_lo, s_hi, z_hi, s_lo, z_lo)
+    assert c.shape == (rows, r + (d - r) // 2 + 16)
+    for i in range(rows):
+        for k in range(r):
+            assert c[i, k] == q_hi[i, k]
+        for k in range(d - r):
+            byte = c[i, r + k // 2]
+            assert ((byte >> 4) if k % 2 else (byte & 15)) == q_lo[i, k]
+        par = np.frombuffer(c[i, r + (d - r) // 2:].tobytes(), "<f4")
+        assert np.array_equal(par, np.array([s_hi[i], z_hi[i], s_lo[i], z_lo[i]], np.float32))
+
+
 # ---- the oracle under sanitizers ---------------------------------------------------
 
 def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
