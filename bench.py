@@ -53,7 +53,6 @@ MEASURED_TRAFFIC = {
     "down_m512": (66.45e6 + 4.19e6, "profiles/down_m512.txt"),
     "decode_m16": (133.61e6 + 0.92e6, "profiles/decode_m16.txt"),
     "decode_m64": (134.98e6 + 3.67e6, "profiles/decode_m64.txt"),
-    "kv_quant": (8.47e6 + 9.04e6, "profiles/kv_quant.txt"),
     "uc_proj": (21.35e6 + 20.97e6, "profiles/uc_proj.txt"),
 }
 
@@ -147,8 +146,9 @@ def cpu_baseline(shape, x, wq_np, budget_s: float = 15.0, hadamard_block: int = 
 
 
 def quant_only_bench(args, s) -> None:
-    """A workload that is the quantizer alone (per-head quantization of K/V cache entries,
-    asymmetric as in the paper): HBM-bound, reported in GB/s of algorithmic bytes."""
+    """A workload that is the quantizer alone: per-head quantization of K/V cache entries into
+    compact cache rows (asymmetric, as in the paper): HBM-bound, reported in GB/s of
+    algorithmic bytes (the bf16 rows in, the cache rows out)."""
     import ctypes
     import numpy as np
     import torch
@@ -157,17 +157,16 @@ def quant_only_bench(args, s) -> None:
 
     x = wl.make_activations(s)
     xd = x.cuda()
-    act = rq.ActCodes(s.M, s.K, s.r)
+    row_bytes = rq.resq_kv_cache_row_bytes(s.K, s.r)
+    cache = torch.empty((s.M, row_bytes), dtype=torch.uint8, device="cuda")
     L = rq.lib()
     st = torch.cuda.current_stream().cuda_stream
-    qa = (xd.data_ptr(), s.K, s.M, s.K, s.r, 0, act.q_hi.data_ptr(), act.q_lo.data_ptr(),
-          act.s_hi.data_ptr(), act.s_lo.data_ptr(), act.c_hi.data_ptr(), act.c_lo.data_ptr(),
-          act.lo_sum.data_ptr(), st)
+    qa = (xd.data_ptr(), s.K, s.M, s.K, s.r, cache.data_ptr(), row_bytes, st)
 
     def step(events=None):
         if events is not None:
             L.resq_time_next_kernel(*events)
-        rc = L.resq_quantize_act_asym(*qa)
+        rc = L.resq_quantize_kv_cache(*qa)
         assert rc == 0, rc
 
     for _ in range(args.warmup):
@@ -194,8 +193,7 @@ def quant_only_bench(args, s) -> None:
         hip.hipEventDestroy(a)
         hip.hipEventDestroy(b)
     kernel_ms = tot / args.steps
-    # per row: the bf16 row in; padded codes, two scales, two offsets and one sum out
-    abytes = s.M * (2 * s.K + act.ld_hi + act.ld_lo + 20)
+    abytes = s.M * (2 * s.K + row_bytes)     # per head row: the bf16 row in, the compact cache row out
     out = {
         "metric": "per-head K/V cache quantization GB/s (% HBM peak)",
         "value": abytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
@@ -203,18 +201,20 @@ def quant_only_bench(args, s) -> None:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": f"{s.name}: rows={s.M} d_head={s.K} r={s.r}", "tag": args.workload,
-                   "step": "quantize_act_asym", "activations": "asymmetric per head"},
+                   "step": "quantize_kv_cache", "activations": "asymmetric per head",
+                   "cache_row_bytes": row_bytes, "compression_vs_bf16": 2 * s.K / row_bytes},
         "quantize_ms": kernel_ms,
         "roofline": {"bound": "hbm", "achieved": abytes / (kernel_ms * 1e-3) / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, **traffic_fields(args.workload),
-                     "kernel": "resq quantize_act (short rows)", "kernel_ms": kernel_ms},
+                     "frac": abytes / (kernel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "resq quantize_kv_cache", "kernel_ms": kernel_ms},
     }
     if not args.no_cpu_baseline:
         from oracle import resq_oracle as oracle
         xb = wl.bf16_bits(x)
         t0 = time.perf_counter()
-        oracle.quantize_act_asym(xb, s.r)
+        q = oracle.quantize_act_asym(xb, s.r)
+        oracle.pack_kv_cache(q[0], q[1], q[2], q[4], q[3], q[5])
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": abytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
                                "kind": "oracle", "sample": f"all {s.M} rows, {dt:.2f} s"}

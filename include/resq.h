@@ -399,6 +399,34 @@ int resq_gemm_mixed_asym(const int8_t* q_hi, const uint8_t* q_lo, const float* s
                          void* stream);
 
 /*
+ * Mixed-precision K/V cache entries (Section 5.1 and Appendix C: keys and values are
+ * quantized per head with the asymmetric quantizer of Section 3, Eq. 1, an eighth of the
+ * channels of a head in 8 bits, the rest in 4), in a compact row per head of a token:
+ *   bytes [0, r)                      8-bit codes 0..255 of channels [0, r)
+ *   bytes [r, r + (d_head - r) / 2)   4-bit codes 0..15: channel r + 2j in bits 0..3 of
+ *                                     byte j, channel r + 2j + 1 in bits 4..7
+ *   then fp32 s_hi, z_hi, s_lo, z_lo  scale and zero-point of both groups: a reader
+ *                                     reconstructs x ~ code * s + z (a group without
+ *                                     channels has s = 1, z = 0)
+ * resq_kv_cache_row_bytes = r + (d_head - r) / 2 + 16 (88 bytes for d_head = 128, r = 16,
+ * against 256 bytes of bf16), or 0 for an invalid pair.  Codes, scales and zero-points are
+ * those of resq_quantize_act_asym on rows of d_head columns (z = min, s = (max - min) /
+ * (2^N - 1), round half to even), stored here as Eq. 1 defines them.
+ *   x       bf16 [rows, ldx], ldx >= d_head; one row per token and head       (read / written)
+ *   cache   [rows, row_bytes] bytes, row_bytes >= resq_kv_cache_row_bytes     (written / read)
+ *   d_head  multiple of 8, 8 .. 512; r multiple of 8, 0 .. d_head (else RESQ_ERR_SHAPE);
+ *           rows = 0 does nothing
+ * resq_dequantize_kv_cache is the reader: x[m, k] = bf16(code * s + z), the multiply-add in
+ * fp32.  Errors: RESQ_ERR_BUFFER for a row_bytes too small; RESQ_ERR_ALIGN unless x is
+ * 16-byte aligned, ldx % 8 == 0, cache 4-byte aligned and row_bytes % 4 == 0.
+ */
+size_t resq_kv_cache_row_bytes(int64_t d_head, int64_t r);
+int resq_quantize_kv_cache(const void* x, int64_t ldx, int64_t rows, int64_t d_head, int64_t r, void* cache,
+                           int64_t row_bytes, void* stream);
+int resq_dequantize_kv_cache(const void* cache, int64_t row_bytes, int64_t rows, int64_t d_head, int64_t r,
+                             void* x, int64_t ldx, void* stream);
+
+/*
  * Online Hadamard projection of the down_proj input (Section 4.3, U_D):
  *   y[m, c0 + g*b + j] = (1/sqrt(b)) * sum_i x[m, c0 + g*b + i] * H_b[i, j]
  * for each block g of b columns in [col_begin, col_end), H_b the Sylvester

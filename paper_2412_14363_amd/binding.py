@@ -42,6 +42,9 @@ SYMBOLS = {
     "resq_sym_eig_static": (C.c_int, [_p, _i64, _i64, C.c_int, _p, _p, _i64, _p]),
     "resq_project_rows": (C.c_int, [_p, C.c_int, _i64, _i64, _i64, _p, _i64, _i64, _p, C.c_int, _i64, _p]),
     "resq_project_heads": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _i64, _p]),
+    "resq_kv_cache_row_bytes": (_sz, [_i64, _i64]),
+    "resq_quantize_kv_cache": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _i64, _p]),
+    "resq_dequantize_kv_cache": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _i64, _p]),
     "resq_pack_weights": (C.c_int, [_p, _i64, _i64, _i64, _i64, _p, _sz, _p]),
     "resq_unpack_weights": (C.c_int, [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p]),
     "resq_gemm_mixed": (C.c_int, [_p, _p, _p, _p, _p, _i64, _p, _i64, _i64, _i64, _p, _i64, _p, _p, _p]),
@@ -449,6 +452,45 @@ def resq_project_heads(x: torch.Tensor, packed: torch.Tensor, y: Optional[torch.
                                   _stream(stream))
     _check(st, "resq_project_heads")
     return y
+
+
+def resq_kv_cache_row_bytes(d_head: int, r: int) -> int:
+    return int(lib().resq_kv_cache_row_bytes(d_head, r))
+
+
+def resq_quantize_kv_cache(x: torch.Tensor, r: int, cache: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """x: bf16 [rows, d_head] (one row per token and head) -> uint8 [rows, row_bytes] compact cache rows."""
+    rows, d = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must be row-major")
+    need = resq_kv_cache_row_bytes(d, r)
+    if need == 0:
+        raise ValueError(f"invalid (d_head, r) = ({d}, {r})")
+    if cache is None:
+        cache = torch.empty((rows, need), dtype=torch.uint8, device=x.device)
+    if cache.dim() != 2 or cache.shape[0] != rows or cache.stride(1) != 1 or cache.shape[1] < need:
+        raise ValueError(f"cache must be a row-major [{rows}, >= {need}] byte tensor")
+    st = lib().resq_quantize_kv_cache(_dev(x, torch.bfloat16, "x"), x.stride(0), rows, d, r,
+                                      _dev(cache, torch.uint8, "cache"), cache.stride(0), _stream(stream))
+    _check(st, "resq_quantize_kv_cache")
+    return cache
+
+
+def resq_dequantize_kv_cache(cache: torch.Tensor, d_head: int, r: int, out: Optional[torch.Tensor] = None,
+                             stream=None) -> torch.Tensor:
+    """The reader: bf16 [rows, d_head] = code * s + z of every channel."""
+    rows = cache.shape[0]
+    need = resq_kv_cache_row_bytes(d_head, r)
+    if need == 0 or cache.dim() != 2 or cache.stride(1) != 1 or cache.shape[1] < need:
+        raise ValueError(f"cache must be a row-major [rows, >= {need}] byte tensor for (d_head, r) = ({d_head}, {r})")
+    if out is None:
+        out = torch.empty((rows, d_head), dtype=torch.bfloat16, device=cache.device)
+    if tuple(out.shape) != (rows, d_head) or out.stride(1) != 1:
+        raise ValueError(f"out must be a row-major [{rows}, {d_head}] tensor")
+    st = lib().resq_dequantize_kv_cache(_dev(cache, torch.uint8, "cache"), cache.stride(0), rows, d_head, r,
+                                        _dev(out, torch.bfloat16, "out"), out.stride(0), _stream(stream))
+    _check(st, "resq_dequantize_kv_cache")
+    return out
 
 
 def resq_online_hadamard(x: torch.Tensor, col_begin: int, col_end: int, block: int = 0,

@@ -255,6 +255,56 @@ int resq_quantize_act_asym(const void* x, int64_t ldx, int64_t M, int64_t K, int
                              stream);
 }
 
+static bool kv_cache_shape_ok(int64_t rows, int64_t d_head, int64_t r) {
+    return rows >= 0 && rows <= 0x7FFFFFFF && d_head >= 8 && d_head <= 512 && d_head % 8 == 0 && r >= 0 &&
+           r <= d_head && r % 8 == 0;
+}
+
+size_t resq_kv_cache_row_bytes(int64_t d_head, int64_t r) {
+    if (!kv_cache_shape_ok(0, d_head, r)) return 0;
+    return (size_t)(r + (d_head - r) / 2 + 16);
+}
+
+int resq_quantize_kv_cache(const void* x, int64_t ldx, int64_t rows, int64_t d_head, int64_t r, void* cache,
+                           int64_t row_bytes, void* stream) {
+    if (!kv_cache_shape_ok(rows, d_head, r) || ldx < d_head) return RESQ_ERR_SHAPE;
+    if (row_bytes < (int64_t)resq_kv_cache_row_bytes(d_head, r)) return RESQ_ERR_BUFFER;
+    if (rows == 0) return RESQ_OK;
+    if (!x || !cache) return RESQ_ERR_NULL;
+    if (!aligned(x, 16) || ldx % 8 != 0 || !aligned(cache, 4) || row_bytes % 4 != 0) return RESQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    uint8_t* cp = static_cast<uint8_t*>(cache);
+#define RESQ_LAUNCH_KV(G)                                                                          \
+    launch(quantize_kv_cache_kernel<G>, dim3((unsigned)((rows + kQuantThreads / G - 1) / (kQuantThreads / G))), \
+           dim3(kQuantThreads), 0, st, xp, ldx, rows, (int)d_head, (int)r, cp, row_bytes)
+    if (d_head <= 128) RESQ_LAUNCH_KV(16);
+    else if (d_head <= 256) RESQ_LAUNCH_KV(32);
+    else RESQ_LAUNCH_KV(64);
+#undef RESQ_LAUNCH_KV
+    return launch_status();
+}
+
+int resq_dequantize_kv_cache(const void* cache, int64_t row_bytes, int64_t rows, int64_t d_head, int64_t r,
+                             void* x, int64_t ldx, void* stream) {
+    if (!kv_cache_shape_ok(rows, d_head, r) || ldx < d_head) return RESQ_ERR_SHAPE;
+    if (row_bytes < (int64_t)resq_kv_cache_row_bytes(d_head, r)) return RESQ_ERR_BUFFER;
+    if (rows == 0) return RESQ_OK;
+    if (!x || !cache) return RESQ_ERR_NULL;
+    if (!aligned(x, 16) || ldx % 8 != 0 || !aligned(cache, 4) || row_bytes % 4 != 0) return RESQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t* cp = static_cast<const uint8_t*>(cache);
+    uint16_t* xp = static_cast<uint16_t*>(x);
+#define RESQ_LAUNCH_KV(G)                                                                          \
+    launch(dequantize_kv_cache_kernel<G>, dim3((unsigned)((rows + kQuantThreads / G - 1) / (kQuantThreads / G))), \
+           dim3(kQuantThreads), 0, st, cp, row_bytes, rows, (int)d_head, (int)r, xp, ldx)
+    if (d_head <= 128) RESQ_LAUNCH_KV(16);
+    else if (d_head <= 256) RESQ_LAUNCH_KV(32);
+    else RESQ_LAUNCH_KV(64);
+#undef RESQ_LAUNCH_KV
+    return launch_status();
+}
+
 int resq_pack_weights(const void* w, int64_t ldw, int64_t N, int64_t K, int64_t r, void* packed,
                       size_t packed_bytes, void* stream) {
     if (!shape_ok(N, K, r) || ldw < K) return RESQ_ERR_SHAPE;

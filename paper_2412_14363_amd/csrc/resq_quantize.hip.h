@@ -667,6 +667,112 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_short_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Compact K/V cache rows (Section 5.1 and Appendix C: the cache is quantized per
+// head with the asymmetric quantizer of Eq. 1, an eighth of the channels in 8
+// bits).  One row per head of a token, no padding:
+//   r bytes: the 8-bit codes, 0..255 | (d - r) / 2 bytes: the 4-bit codes, 0..15,
+//   channel r + 2j in bits 0..3, r + 2j + 1 in bits 4..7 | fp32 s_hi, z_hi, s_lo, z_lo
+// with x ~ code * s + z per group: r + (d - r) / 2 + 16 bytes for 2 d bytes of bf16.
+// The quantizer is the short-row kernel above (G lanes per row, no LDS, no
+// barrier); its stored codes (code - 2^(N-1), the GEMM's operand form) become the
+// codes of Eq. 1 with one XOR per four bytes.
+// ---------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(kQuantThreads) void quantize_kv_cache_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int64_t rows, int d, int r, uint8_t* __restrict__ cache,
+    int64_t row_bytes) {
+    const int gl = threadIdx.x & (G - 1);  // lane inside the group
+    const int64_t m_raw = (int64_t)blockIdx.x * (kQuantThreads / G) + threadIdx.x / G;
+    // every lane of a wavefront runs the exchanges and the votes below; groups past
+    // the last row work on the last row and store nothing
+    const bool row_live = m_raw < rows;
+    const int64_t m = row_live ? m_raw : rows - 1;
+    const int nunits = d >> 3, hi_units = r >> 3;
+    const bool live = gl < nunits, high = gl < hi_units;
+    const uint4 v = live ? reinterpret_cast<const uint4*>(x + m * ldx)[gl] : make_uint4(0u, 0u, 0u, 0u);
+
+    const float inf = __builtin_huge_valf();
+    float mx = -inf, nmn = -inf;
+    if (live) {
+        float f[8];
+        unpack8_bf16(v, f);
+        mx = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])), fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+        nmn = -fminf(fminf(fminf(f[0], f[1]), fminf(f[2], f[3])), fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+    }
+    const float mx_h = wave_max<G>(high ? mx : -inf), nmn_h = wave_max<G>(high ? nmn : -inf);
+    const float mx_l = wave_max<G>(live && !high ? mx : -inf);
+    const float nmn_l = wave_max<G>(live && !high ? nmn : -inf);
+    // an absent group: scale 1, zero-point 0
+    const float zh = r > 0 ? -nmn_h : 0.0f, zl = d - r > 0 ? -nmn_l : 0.0f;
+    const float sh = r > 0 ? asym_scale(zh, mx_h, 255) : 1.0f;
+    const float sl = d - r > 0 ? asym_scale(zl, mx_l, 15) : 1.0f;
+    // the branch on `high` is not wave-uniform, and the quantizer votes across the
+    // wavefront: run both kinds for every lane's vote, keep the own kind's result
+    uint32_t ch[8], cl8[8];
+    float odd_dummy = 0.0f;
+    if (hi_units > 0) quant8_asym<false>(v, zh, sh, 1.0f / sh, ch, odd_dummy);
+    if (nunits > hi_units) quant8_asym<true>(v, zl, sl, 1.0f / sl, cl8, odd_dummy);
+    if (!row_live) return;
+    uint8_t* row = cache + m * row_bytes;
+    if (live && high) {
+        // stored = code - 128 in the low byte: flipping bit 7 gives the code
+        uint32_t* dst = reinterpret_cast<uint32_t*>(row + gl * 8);   // rows are 4-byte aligned
+        dst[0] = pack_low_bytes(ch[0], ch[1], ch[2], ch[3]) ^ 0x80808080u;
+        dst[1] = pack_low_bytes(ch[4], ch[5], ch[6], ch[7]) ^ 0x80808080u;
+    } else if (live) {
+        // even channels are stored as the code already, odd ones as code - 8 in two's complement
+        uint32_t by[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) by[k] = ((cl8[2 * k + 1] << 4) | (cl8[2 * k] & 0xFu)) ^ 0x80u;
+        *reinterpret_cast<uint32_t*>(row + r + (gl - hi_units) * 4) = pack_low_bytes(by[0], by[1], by[2], by[3]);
+    }
+    if (gl == 0) {
+        float* par = reinterpret_cast<float*>(row + r + (d - r) / 2);
+        par[0] = sh;
+        par[1] = zh;
+        par[2] = sl;
+        par[3] = zl;
+    }
+}
+
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
+    const v2bf_had r = __builtin_convertvector((v2f_had){lo, hi}, v2bf_had);   // round to nearest even
+    return *reinterpret_cast<const uint32_t*>(&r);
+}
+
+// The reader of such rows: x[m, k] = bf16(code * s + z) (Eq. 1), one lane per eight channels.
+template <int G>
+__global__ __launch_bounds__(kQuantThreads) void dequantize_kv_cache_kernel(
+    const uint8_t* __restrict__ cache, int64_t row_bytes, int64_t rows, int d, int r, uint16_t* __restrict__ x,
+    int64_t ldx) {
+    const int gl = threadIdx.x & (G - 1);
+    const int64_t m = (int64_t)blockIdx.x * (kQuantThreads / G) + threadIdx.x / G;
+    const int nunits = d >> 3, hi_units = r >> 3;
+    if (m >= rows || gl >= nunits) return;
+    const uint8_t* row = cache + m * row_bytes;
+    const float* par = reinterpret_cast<const float*>(row + r + (d - r) / 2);
+    float f[8];
+    if (gl < hi_units) {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(row + gl * 8);
+        const uint32_t c0 = src[0], c1 = src[1];
+        const float s = par[0], z = par[1];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) f[k] = fmaf((float)(((k < 4 ? c0 : c1) >> (8 * (k & 3))) & 0xFFu), s, z);
+    } else {
+        const uint32_t c = *reinterpret_cast<const uint32_t*>(row + r + (gl - hi_units) * 4);
+        const float s = par[2], z = par[3];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) f[k] = fmaf((float)((c >> (4 * k)) & 0xFu), s, z);
+    }
+    uint4 o;
+    o.x = pack_bf16_pair(f[0], f[1]);
+    o.y = pack_bf16_pair(f[2], f[3]);
+    o.z = pack_bf16_pair(f[4], f[5]);
+    o.w = pack_bf16_pair(f[6], f[7]);
+    reinterpret_cast<uint4*>(x + m * ldx)[gl] = o;
+}
+
+// ---------------------------------------------------------------------------
 // Activations, any K, r (K - r even) and alignment: two passes over the row
 // with 2-byte loads.  Correct everywhere, fast nowhere.
 // ---------------------------------------------------------------------------

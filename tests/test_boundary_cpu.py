@@ -193,6 +193,23 @@ def test_binding_fails_loudly_without_device_tensors():
         binding.resq_quantize_act(x, 32)
 
 
+def test_kv_cache_entry_points_reject_bad_arguments():
+    L = binding.lib()
+    assert L.resq_kv_cache_row_bytes(128, 16) == 16 + 56 + 16 == 88
+    assert L.resq_kv_cache_row_bytes(64, 0) == 32 + 16 and L.resq_kv_cache_row_bytes(64, 64) == 64 + 16
+    assert L.resq_kv_cache_row_bytes(100, 16) == 0 and L.resq_kv_cache_row_bytes(128, 12) == 0
+    assert L.resq_kv_cache_row_bytes(1024, 128) == 0 and L.resq_kv_cache_row_bytes(128, 136) == 0
+    q, dq = L.resq_quantize_kv_cache, L.resq_dequantize_kv_cache
+    assert q(P, 128, 10, 100, 16, P, 88, None) == 2 and q(P, 120, 10, 128, 16, P, 88, None) == 2
+    assert q(P, 128, 10, 128, 16, P, 80, None) == 4                        # row_bytes too small
+    assert q(None, 128, 10, 128, 16, P, 88, None) == 1 and q(P, 128, 10, 128, 16, None, 88, None) == 1
+    assert q(P + 2, 128, 10, 128, 16, P, 88, None) == 3 and q(P, 128, 10, 128, 16, P + 1, 88, None) == 3
+    assert q(P, 128, 10, 128, 16, P, 90, None) == 3                        # row_bytes % 4
+    assert q(P, 128, 0, 128, 16, P, 88, None) == 0                         # no rows: nothing to do
+    assert dq(P, 80, 10, 128, 16, P, 128, None) == 4 and dq(P, 88, 10, 128, 16, None, 128, None) == 1
+    assert dq(P, 88, 10, 128, 16, P, 120, None) == 2 and dq(P, 88, 0, 128, 16, P, 128, None) == 0
+
+
 def test_binding_rejects_buffers_that_do_not_fit_the_shape():
     # the kernels trust (M, N, K, r): the binding checks the buffers against them before any call
     import torch

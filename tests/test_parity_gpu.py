@@ -807,6 +807,48 @@ def test_kv_cache_head_quantization(oracle, rq, rows, d_head, r):
     compare_asym_codes(oracle, act, wl.bf16_bits(x), r)
 
 
+@pytest.mark.parametrize("rows,d_head,r,pad", [(8 * 37, 128, 16, 0), (8 * 37 + 3, 128, 16, 8), (50, 64, 8, 0),
+                                               (21, 512, 64, 4), (33, 128, 0, 0), (33, 128, 128, 0), (5, 8, 8, 0),
+                                               (4099, 256, 32, 0), (7, 16, 8, 0)])
+def test_kv_cache_compact_rows(oracle, rq, rows, d_head, r, pad):
+    # the compact cache format (Section 5.1, Appendix C): every byte of every row against the
+    # oracle's layout of the oracle's own codes, scales and zero-points; rows wider than needed
+    # keep their padding; the reader against the oracle's reconstruction in fp64
+    s = wl.LayerShape("kvc", M=rows, K=d_head, N=1, r=r, act="student_t3", seed=rows + d_head + r)
+    x = wl.make_activations(s)
+    x[0] = 0                                   # a constant head: scale 1, codes 0
+    if rows > 2:
+        x[2] = x[2].abs()                      # a one-sided head: a real zero-point
+    need = rq.resq_kv_cache_row_bytes(d_head, r)
+    assert need == oracle.kv_cache_row_bytes(d_head, r)
+    buf = torch.full((rows, need + pad), 0xEE, dtype=torch.uint8, device="cuda")
+    xbuf = torch.zeros((rows, d_head + 8), dtype=torch.bfloat16, device="cuda")
+    xbuf[:, :d_head] = x.cuda()
+    cache = rq.resq_quantize_kv_cache(xbuf[:, :d_head], r, cache=buf)
+    torch.cuda.synchronize()
+    q_hi, q_lo, s_hi, s_lo, z_hi, z_lo = oracle.quantize_act_asym(wl.bf16_bits(x), r)
+    want = oracle.pack_kv_cache(q_hi, q_lo, s_hi, z_hi, s_lo, z_lo)
+    got = cache.cpu().numpy()
+    assert np.array_equal(got[:, :need], want), "cache rows differ"
+    assert np.all(got[:, need:] == 0xEE), "wrote past the row"
+    # the reader: fp32 multiply-add rounded to bf16 against the fp64 reconstruction
+    back = rq.resq_dequantize_kv_cache(cache, d_head, r)
+    torch.cuda.synchronize()
+    ref = oracle.dequantize_kv_cache(want, d_head, r)
+    b64 = wl.bits_to_f64(wl.bf16_bits(back.cpu()))
+    assert np.all(np.abs(b64 - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-30)
+    # and what comes back is within half a quantization step (plus the bf16 rounding of the
+    # reconstructed value, which is at most half a step away from the input) of what went in
+    x64 = wl.bits_to_f64(wl.bf16_bits(x))
+    step = np.concatenate([np.repeat(s_hi[:, None], r, 1), np.repeat(s_lo[:, None], d_head - r, 1)], axis=1).astype(np.float64)
+    assert np.all(np.abs(b64 - x64) <= 0.5 * step * (1 + 2.0 ** -7) + 2.0 ** -8 * np.abs(x64))
+
+
+def test_kv_cache_no_rows(rq):
+    c = rq.resq_quantize_kv_cache(torch.empty((0, 128), dtype=torch.bfloat16, device="cuda"), 16)
+    assert c.shape == (0, 88)
+
+
 def test_online_head_projection_as_uniform_int8_layer(oracle, rq):
     # the 8-bit online projection of queries and keys (U_C, d_head x d_head, Section 4.3):
     # rows = tokens x heads, K = N = d_head, every column in the high group
