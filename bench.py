@@ -678,11 +678,17 @@ def layer_bench(args, tag: str, steps: int, warmup: int, with_cpu_baseline: bool
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
+    # a generation-stage step is tens of microseconds, close to what the host needs to launch
+    # it: keep the interpreter's garbage collector out of the timed region
+    import gc
+    gc.collect()
+    gc.disable()
     t0 = time.perf_counter()
     for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    gc.enable()
     ms_per_step = dt / steps * 1e3
 
     # second pass over the same steps; HIP events at the start and end of each kernel
@@ -818,7 +824,7 @@ def headline(args) -> None:
     torch.cuda.empty_cache()
     dec = {}
     for m in (1, 4, 16):
-        d = layer_bench(args, f"decode_m{m}", max(args.steps, 100), args.warmup, not args.no_cpu_baseline and m == 16,
+        d = layer_bench(args, f"decode_m{m}", max(args.steps, 500), args.warmup, not args.no_cpu_baseline and m == 16,
                         min(args.cpu_budget, 5.0))
         dec[f"M={m}"] = {"value": d["value"], "unit": d["unit"], "ms_per_step": d["ms_per_step"],
                          "quantize_ms": d["quantize_ms"], "gemm_ms": d["gemm_ms"],

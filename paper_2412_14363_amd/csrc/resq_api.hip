@@ -432,9 +432,14 @@ static DecodeArgs make_decode_args(const int8_t* q_hi, const uint8_t* q_lo, cons
 static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t st) {
     const WeightLayout& L = d.L;
     // the code rows go through LDS only when the kernel makes them itself
-    int lds_bytes = fused ? ((d.M * d.lds_row + 15) & ~15) : 0;
-    const int extra = fused ? kFusedScratchFloats * 4 : 0;
     const int sk = plan_gemm(d.M, L).sk;   // runs per channel group
+    // From 14 tokens on, a load of one block's codes touches so many cache lines (one per
+    // token) that copying all code rows into LDS first is cheaper, on the long runs of wide
+    // layers (measured at M = 16, 132 MB of weights: 26.0 -> 24.4 us; at M = 12, and on the
+    // short runs of narrow layers at any M, the copy up front costs more than it saves).
+    const bool copy = !fused && !dbg && d.M >= 14 && sk == 1;
+    int lds_bytes = (fused || copy) ? ((d.M * d.lds_row + 15) & ~15) : 0;
+    const int extra = fused ? kFusedScratchFloats * 4 : 0;
     const dim3 blk(kDecodeThreads);
 #define RESQ_LAUNCH_DECODE(KERNEL, GRID)                                                           \
     do {                                                                                           \
@@ -465,6 +470,7 @@ static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t 
     // one workgroup per compute unit (256 of them), fewer when there is less work
     const dim3 grid((unsigned)(d.groups < 256 ? d.groups : 256));
     if (fused) RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, kActQuantize>), grid);
+    else if (copy) RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, kActCopy>), grid);
     else if (dbg) RESQ_LAUNCH_DECODE((gemm_decode_kernel<true, kActDirect>), grid);
     else RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, kActDirect>), grid);
 #undef RESQ_LAUNCH_DECODE

@@ -60,9 +60,19 @@ constexpr int kFusedScratchFloats = 3 * 16 + 8 * 3;  // LDS beside the token row
 // n .. n + 3, the two integer sums of each.  Dequantizes (Eq. 4), adds the
 // zero-point term of asymmetric activation codes, applies the gated pair
 // epilogue when asked, writes bf16 (and the integer sums in the debug build).
-template <bool DBG>
-__device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, int64_t n, v4i acc_hi,
-                                                v4i acc_lo) {
+// The per-token and per-channel constants it needs are a separate step, so that
+// a kernel can ask for them before it starts on the weights: they then arrive
+// under the stream instead of as two dependent memory round trips after it
+// (measured: 2 to 6 % on the short runs of the kernel that cuts the reduction
+// axis, nothing on the long runs of the plain one, which therefore asks late).
+struct EpilogueConsts {
+    float sth, stl, cth, ctl;
+    int ca;
+    float snh[4], snl[4];
+    int ev[4];
+    int wsh[4], wsl[4];  // asymmetric activation codes only
+};
+__device__ __forceinline__ EpilogueConsts load_epilogue_consts(const DecodeArgs& a, int tok, int64_t n) {
     const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
     const uint16_t* sw_lo = sw_hi + a.L.n_pad;
     const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
@@ -70,27 +80,46 @@ __device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, in
     const int32_t* wsum_lo = even_sum + 2 * a.L.n_pad;
     const bool has_hi = a.L.r > 0, has_lo = a.L.K - a.L.r > 0;
     const bool asym = a.c_hi != nullptr || a.c_lo != nullptr;
-    const float sth = has_hi ? a.s_hi[tok] : 0.f;
-    const float stl = has_lo ? a.s_lo[tok] : 0.f;
-    const int ca = has_lo ? a.lo_sum[tok] : 0;
-    const float cth = (asym && has_hi) ? a.c_hi[tok] : 0.f;
-    const float ctl = (asym && has_lo) ? a.c_lo[tok] : 0.f;
+    EpilogueConsts c;
+    c.sth = has_hi ? a.s_hi[tok] : 0.f;
+    c.stl = has_lo ? a.s_lo[tok] : 0.f;
+    c.ca = has_lo ? a.lo_sum[tok] : 0;
+    c.cth = (asym && has_hi) ? a.c_hi[tok] : 0.f;
+    c.ctl = (asym && has_lo) ? a.c_lo[tok] : 0.f;
     const uint2 sch = *reinterpret_cast<const uint2*>(sw_hi + n);
     const uint2 scl = *reinterpret_cast<const uint2*>(sw_lo + n);
     const int4 es = *reinterpret_cast<const int4*>(even_sum + n);
-    const float snh[4] = {fp16_bits_to_f32(sch.x & 0xFFFFu), fp16_bits_to_f32(sch.x >> 16),
-                          fp16_bits_to_f32(sch.y & 0xFFFFu), fp16_bits_to_f32(sch.y >> 16)};
-    const float snl[4] = {fp16_bits_to_f32(scl.x & 0xFFFFu), fp16_bits_to_f32(scl.x >> 16),
-                          fp16_bits_to_f32(scl.y & 0xFFFFu), fp16_bits_to_f32(scl.y >> 16)};
-    const int ev[4] = {es.x, es.y, es.z, es.w};
+    c.snh[0] = fp16_bits_to_f32(sch.x & 0xFFFFu);
+    c.snh[1] = fp16_bits_to_f32(sch.x >> 16);
+    c.snh[2] = fp16_bits_to_f32(sch.y & 0xFFFFu);
+    c.snh[3] = fp16_bits_to_f32(sch.y >> 16);
+    c.snl[0] = fp16_bits_to_f32(scl.x & 0xFFFFu);
+    c.snl[1] = fp16_bits_to_f32(scl.x >> 16);
+    c.snl[2] = fp16_bits_to_f32(scl.y & 0xFFFFu);
+    c.snl[3] = fp16_bits_to_f32(scl.y >> 16);
+    c.ev[0] = es.x;
+    c.ev[1] = es.y;
+    c.ev[2] = es.z;
+    c.ev[3] = es.w;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        c.wsh[v] = asym ? wsum_hi[n + v] : 0;
+        c.wsl[v] = asym ? wsum_lo[n + v] : 0;
+    }
+    return c;
+}
+
+template <bool DBG>
+__device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, int64_t n, const EpilogueConsts& c,
+                                                v4i acc_hi, v4i acc_lo) {
+    const bool asym = a.c_hi != nullptr || a.c_lo != nullptr;
     float out[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int a_hi = acc_hi[v];
-        const int a_lo = (acc_lo[v] - 128 * (ev[v] + ca)) >> 4;  // exact
-        out[v] = (float)a_hi * (sth * snh[v]) + (float)a_lo * (stl * snl[v]);
-        if (asym)
-            out[v] += cth * ((float)wsum_hi[n + v] * snh[v]) + ctl * ((float)wsum_lo[n + v] * snl[v]);
+        const int a_lo = (acc_lo[v] - 128 * (c.ev[v] + c.ca)) >> 4;  // exact
+        out[v] = (float)a_hi * (c.sth * c.snh[v]) + (float)a_lo * (c.stl * c.snl[v]);
+        if (asym) out[v] += c.cth * ((float)c.wsh[v] * c.snh[v]) + c.ctl * ((float)c.wsl[v] * c.snl[v]);
         if constexpr (DBG) {
             if (n + v < a.L.N) {
                 if (a.dbg_hi) a.dbg_hi[(int64_t)tok * a.L.N + n + v] = a_hi;
@@ -100,14 +129,14 @@ __device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, in
     }
     if (a.swiglu) {
         // two (gate, up) pairs per lane -> two outputs
-        const int64_t c = n >> 1, c_end = a.L.N >> 1;
-        uint16_t* d2 = a.y + (int64_t)tok * a.ldy + c;
+        const int64_t ch = n >> 1, ch_end = a.L.N >> 1;
+        uint16_t* d2 = a.y + (int64_t)tok * a.ldy + ch;
         const uint32_t pair = pack_bf16(silu_f32(out[0]) * out[1], silu_f32(out[2]) * out[3]);
-        if (c + 1 < c_end && ((reinterpret_cast<uintptr_t>(a.y) & 3) == 0) && (a.ldy % 2 == 0)) {
+        if (ch + 1 < ch_end && ((reinterpret_cast<uintptr_t>(a.y) & 3) == 0) && (a.ldy % 2 == 0)) {
             *reinterpret_cast<uint32_t*>(d2) = pair;
         } else {
-            if (c < c_end) d2[0] = (uint16_t)pair;
-            if (c + 1 < c_end) d2[1] = (uint16_t)(pair >> 16);
+            if (ch < ch_end) d2[0] = (uint16_t)pair;
+            if (ch + 1 < ch_end) d2[1] = (uint16_t)(pair >> 16);
         }
         return;
     }
@@ -119,6 +148,11 @@ __device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, in
         for (int v = 0; v < 4; ++v)
             if (n + v < a.L.N) dst[v] = (uint16_t)pack_bf16(out[v], 0.f);
     }
+}
+template <bool DBG>
+__device__ __forceinline__ void stream_epilogue(const DecodeArgs& a, int tok, int64_t n, v4i acc_hi,
+                                                v4i acc_lo) {
+    stream_epilogue<DBG>(a, tok, n, load_epilogue_consts(a, tok, n), acc_hi, acc_lo);
 }
 
 // The per-token quantizer (Section 4.1 Eq. 2, symmetric) run by the workgroup itself on
@@ -222,6 +256,48 @@ __device__ __forceinline__ void fill_act_quantize(const DecodeArgs& a, uint8_t* 
     __syncthreads();
 }
 
+// The code rows of all tokens copied from memory into the LDS rows (the layout that
+// fill_act_quantize writes: high part, low part, padding), 16 bytes at a time.  The loads of
+// the first kCopyBatch units per thread are issued by copy_issue, which a kernel calls
+// before it starts its weight stream, so that they are not queued behind it; copy_finish
+// stores them, moves whatever is left (rows longer than kCopyBatch * 8 KiB in total) and
+// ends with a barrier.
+constexpr int kCopyBatch = 10;
+struct ActCopy {
+    uint4 v[kCopyBatch];
+};
+__device__ __forceinline__ const uint4* copy_source(const DecodeArgs& a, int u, int per, int hi16, int& dst_off) {
+    const int m = u / per, k = u - m * per;
+    dst_off = m * a.lds_row + k * 16;
+    return reinterpret_cast<const uint4*>(k < hi16 ? a.q_hi + (int64_t)m * a.ld_hi + k * 16
+                                                   : a.q_lo + (int64_t)m * a.ld_lo + (k - hi16) * 16);
+}
+__device__ __forceinline__ void copy_issue(const DecodeArgs& a, int t, ActCopy& c) {
+    const int hi16 = (int)(a.L.kh_pad / 16), per = hi16 + (int)(a.L.kl_pad / 32), units = a.M * per;
+#pragma unroll
+    for (int j = 0; j < kCopyBatch; ++j) {
+        const int u = j * kDecodeThreads + t;
+        int off;
+        c.v[j] = *copy_source(a, u < units ? u : 0, per, hi16, off);
+    }
+}
+__device__ __forceinline__ void copy_finish(const DecodeArgs& a, uint8_t* act, int t, const ActCopy& c) {
+    const int hi16 = (int)(a.L.kh_pad / 16), per = hi16 + (int)(a.L.kl_pad / 32), units = a.M * per;
+#pragma unroll
+    for (int j = 0; j < kCopyBatch; ++j) {
+        const int u = j * kDecodeThreads + t;
+        int off;
+        copy_source(a, u < units ? u : 0, per, hi16, off);
+        if (u < units) *reinterpret_cast<uint4*>(act + off) = c.v[j];
+    }
+    for (int u = kCopyBatch * kDecodeThreads + t; u < units; u += kDecodeThreads) {
+        int off;
+        const uint4* src = copy_source(a, u, per, hi16, off);
+        *reinterpret_cast<uint4*>(act + off) = *src;
+    }
+    __syncthreads();
+}
+
 // the arguments as the epilogue reads them: with the fused quantizer the per-token
 // constants sit in LDS
 template <bool FUSED>
@@ -238,10 +314,10 @@ __device__ __forceinline__ DecodeArgs epilogue_args(const DecodeArgs& a, const f
 // Where a wavefront's activation operand comes from: straight from the code rows in memory
 // through a second ring beside the weight ring (no LDS, no barrier: the first matrix
 // instruction waits for nothing but its own two loads; the code rows are a few KiB per
-// token, stay in L2, and every wavefront reads its part of them once per group; measured
-// 1 to 15 % faster than staging them in LDS first), or from LDS rows into which the
-// workgroup itself has quantized the bf16 activations.
-enum : int { kActQuantize = 1, kActDirect = 2 };
+// token, stay in L2, and every wavefront reads its part of them once per group), from LDS
+// rows into which the workgroup has copied the code rows (the plain kernel from 14 tokens
+// on), or from LDS rows into which the workgroup itself has quantized the bf16 activations.
+enum : int { kActQuantize = 1, kActDirect = 2, kActCopy = 3 };
 
 // lane's pointers to its 16-byte piece of block 0 of the high and of the low codes of its
 // token (the low pointer moved back by the high blocks, so that both take the block index)
@@ -262,6 +338,102 @@ __device__ __forceinline__ ActPieces act_pieces(const DecodeArgs& a, int lane, b
     return p;
 }
 
+// A 16-byte piece of the packed weights, read with the non-temporal hint: the weights pass
+// through once per call, and without the hint they push the tokens' code rows, which every
+// wavefront reads again and again, out of the caches (measured on the 132 MB up projection
+// at M = 1: 5.5 -> 6.2 TB/s).
+typedef unsigned int v4u_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_weights_16B(const uint4* p) {
+    const v4u_t v = __builtin_nontemporal_load(reinterpret_cast<const v4u_t*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// One run of a wavefront: blocks [b_begin, b_end) of a channel group meet the tokens'
+// codes; the sums go to acc_hi / acc_lo.  On entry ring[i] (and aring[i], when the codes
+// come straight from memory) holds block b_begin + i for every i < min(kDecodeDepth,
+// b_end - b_begin); wp points at the lane's piece of the group's block 0.  While a turn of
+// kDecodeDepth blocks is multiplied, the loads of the turn after it go out, slot by slot.
+// Turns whose blocks are all of one kind and whose refills all exist are straight-line
+// code without a branch, in loops of their own: only then does the compiler count the
+// outstanding loads exactly and wait for just the oldest one, instead of draining the
+// ring at every turn (it gives up at the joins of conditional loads).  Nothing here
+// depends on the lane: lanes of tokens past M carry token 0's codes and produce sums in
+// output columns that are never stored.
+template <bool DIRECT>
+__device__ __forceinline__ void stream_run(uint4 (&ring)[kDecodeDepth], uint4 (&aring)[DIRECT ? kDecodeDepth : 1],
+                                           const uint4* wp, const ActPieces& piece, const uint8_t* arow,
+                                           int b_begin, int b_end, int hi_blocks, v4i& acc_hi, v4i& acc_lo) {
+    constexpr int D = kDecodeDepth;
+    auto product = [&](bool hi, const uint4& wq, const v4i& p) __attribute__((always_inline)) {
+        const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
+        if (hi) {
+            acc_hi = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, p, acc_hi, 0, 0, 0);
+        } else {
+            // see resq_gemm.hip.h: one operand of each product carries an offset of 8
+            acc_lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(w & (int)0xF0F0F0F0, p & (int)0x0F0F0F0F, acc_lo, 0, 0, 0);
+            acc_lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(w & (int)0x0F0F0F0F, p & (int)0xF0F0F0F0, acc_lo, 0, 0, 0);
+        }
+    };
+    // KIND 0: all high, 1: all low, 2: the turn that holds the boundary
+    auto full_turn = [&](auto kind, int b0) __attribute__((always_inline)) {
+        constexpr int KIND = decltype(kind)::value;
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            const int b = b0 + i;
+            v4i p;
+            if constexpr (DIRECT) p = v4i{(int)aring[i].x, (int)aring[i].y, (int)aring[i].z, (int)aring[i].w};
+            else p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
+            product(KIND == 0 || (KIND == 2 && b < hi_blocks), ring[i], p);
+            // the slot is refilled only after its product has been issued: old and new value
+            // never live side by side, so the ring stays in the same registers from turn to
+            // turn (a copy of a register just loaded would wait for that load)
+            __builtin_amdgcn_sched_barrier(0);
+            ring[i] = load_weights_16B(&wp[(b + D) * (kBlockBytes / 16)]);
+            if constexpr (DIRECT) aring[i] = piece(b + D);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // The ring was filled a moment ago under conditions; waiting for all of it here costs
+    // next to nothing (its loads went out back to back) and hands the loops below a state
+    // the compiler can count from.  vmcnt(0), other counters untouched.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    int b0 = b_begin;
+    while (b0 + D <= hi_blocks && b0 + 2 * D <= b_end) {
+        full_turn(std::integral_constant<int, 0>{}, b0);
+        b0 += D;
+    }
+    if (b0 < hi_blocks && b0 + 2 * D <= b_end) {
+        full_turn(std::integral_constant<int, 2>{}, b0);
+        b0 += D;
+    }
+    while (b0 >= hi_blocks && b0 + 2 * D <= b_end) {
+        full_turn(std::integral_constant<int, 1>{}, b0);
+        b0 += D;
+    }
+    // the last turns: some refills, then none
+    for (; b0 < b_end; b0 += D) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            const int b = b0 + i;
+            if (b < b_end) {
+                const uint4 wq = ring[i];
+                v4i p;
+                if constexpr (DIRECT) {
+                    const uint4 pq = aring[i];
+                    p = v4i{(int)pq.x, (int)pq.y, (int)pq.z, (int)pq.w};
+                } else {
+                    p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
+                }
+                if (b + D < b_end) {
+                    ring[i] = load_weights_16B(&wp[(b + D) * (kBlockBytes / 16)]);
+                    if constexpr (DIRECT) aring[i] = piece(b + D);
+                }
+                product(b < hi_blocks, wq, p);
+            }
+        }
+    }
+}
+
 template <bool DBG, int ACT>
 __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t act[];  // kActQuantize: [M][lds_row]
@@ -274,6 +446,8 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
     const bool tok_live = tok < a.M;
     const ActPieces piece = act_pieces(a, lane, tok_live);
 
+    ActCopy staged;
+    if constexpr (ACT == kActCopy) copy_issue(a, t, staged);
     // start the weight stream of this wave's first group before anything else
     int group = wave * gridDim.x + blockIdx.x;
     uint4 ring[kDecodeDepth], aring[DIRECT ? kDecodeDepth : 1];
@@ -282,57 +456,23 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
             a.packed + (int64_t)(group < a.groups ? group : 0) * a.L.group_bytes + lane_off);
 #pragma unroll
         for (int i = 0; i < kDecodeDepth; ++i) {
-            if constexpr (DIRECT) aring[i] = make_uint4(0u, 0u, 0u, 0u);
             if (group < a.groups && i < blocks) {
-                ring[i] = wp[i * (kBlockBytes / 16)];
-                if constexpr (DIRECT)
-                    if (tok_live) aring[i] = piece(i);
+                ring[i] = load_weights_16B(&wp[i * (kBlockBytes / 16)]);
+                if constexpr (DIRECT) aring[i] = piece(i);
             }
         }
     }
 
     float* scal = reinterpret_cast<float*>(act + ((a.M * a.lds_row + 15) & ~15));
     if constexpr (ACT == kActQuantize) fill_act_quantize(a, act, scal, t);
+    if constexpr (ACT == kActCopy) copy_finish(a, act, t, staged);
     const DecodeArgs ea = epilogue_args<ACT == kActQuantize>(a, scal);
 
     const uint8_t* arow = act + (tok_live ? tok : 0) * a.lds_row + (lane >> 4) * 16;
-    const v4i zero = {0, 0, 0, 0};
     for (; group < a.groups; group += 8 * gridDim.x) {
         const uint4* wp = reinterpret_cast<const uint4*>(a.packed + (int64_t)group * a.L.group_bytes + lane_off);
         v4i acc_hi = {0, 0, 0, 0}, acc_lo = {0, 0, 0, 0};
-        for (int b0 = 0; b0 < blocks; b0 += kDecodeDepth) {
-#pragma unroll
-            for (int i = 0; i < kDecodeDepth; ++i) {
-                const int b = b0 + i;
-                if (b < blocks) {
-                    const uint4 wq = ring[i];
-                    v4i p;
-                    if constexpr (DIRECT) {
-                        const uint4 pq = aring[i];   // zero past M
-                        p = v4i{(int)pq.x, (int)pq.y, (int)pq.z, (int)pq.w};
-                    }
-                    if (b + kDecodeDepth < blocks) {
-                        ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
-                        if constexpr (DIRECT)
-                            if (tok_live) aring[i] = piece(b + kDecodeDepth);
-                    }
-                    const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
-                    if constexpr (!DIRECT) {
-                        p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
-                        if (!tok_live) p = zero;
-                    }
-                    if (b < hi_blocks) {
-                        acc_hi = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, p, acc_hi, 0, 0, 0);
-                    } else {
-                        // see resq_gemm.hip.h: one operand of each product carries an offset of 8
-                        acc_lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                            w & (int)0xF0F0F0F0, tok_live ? (p & (int)0x0F0F0F0F) : zero, acc_lo, 0, 0, 0);
-                        acc_lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                            w & (int)0x0F0F0F0F, p & (int)0xF0F0F0F0, acc_lo, 0, 0, 0);
-                    }
-                }
-            }
-        }
+        stream_run<DIRECT>(ring, aring, wp, piece, arow, 0, blocks, hi_blocks, acc_hi, acc_lo);
         // the next group's first loads go out before this group's epilogue
         const int next = group + 8 * gridDim.x;
         if (next < a.groups) {
@@ -340,9 +480,8 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
 #pragma unroll
             for (int i = 0; i < kDecodeDepth; ++i)
                 if (i < blocks) {
-                    ring[i] = np[i * (kBlockBytes / 16)];
-                    if constexpr (DIRECT)
-                        if (tok_live) aring[i] = piece(i);
+                    ring[i] = load_weights_16B(&np[i * (kBlockBytes / 16)]);
+                    if constexpr (DIRECT) aring[i] = piece(i);
                 }
         }
 
@@ -390,11 +529,9 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
             a.packed + (int64_t)(live ? group : 0) * a.L.group_bytes + lane_off);
 #pragma unroll
         for (int i = 0; i < kDecodeDepth; ++i) {
-            if constexpr (DIRECT) aring[i] = make_uint4(0u, 0u, 0u, 0u);
             if (live && b_begin + i < b_end) {
-                ring[i] = wp[(b_begin + i) * (kBlockBytes / 16)];
-                if constexpr (DIRECT)
-                    if (tok_live) aring[i] = piece(b_begin + i);
+                ring[i] = load_weights_16B(&wp[(b_begin + i) * (kBlockBytes / 16)]);
+                if constexpr (DIRECT) aring[i] = piece(b_begin + i);
             }
         }
     }
@@ -404,48 +541,17 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
     const DecodeArgs ea = epilogue_args<ACT == kActQuantize>(a, scal);
 
     const uint8_t* arow = act + (tok_live ? tok : 0) * a.lds_row + (lane >> 4) * 16;
-    const v4i zero = {0, 0, 0, 0};
     for (; set < sets; set += gridDim.x) {  // the same trip count for every wavefront of a workgroup
         const int group = set * G + gsel;
         const bool live = group < a.groups;
         const uint4* wp = reinterpret_cast<const uint4*>(
             a.packed + (int64_t)(live ? group : 0) * a.L.group_bytes + lane_off);
         v4i acc_hi = {0, 0, 0, 0}, acc_lo = {0, 0, 0, 0};
-        if (live) {
-            for (int b0 = b_begin; b0 < b_end; b0 += kDecodeDepth) {
-#pragma unroll
-                for (int i = 0; i < kDecodeDepth; ++i) {
-                    const int b = b0 + i;
-                    if (b < b_end) {
-                        const uint4 wq = ring[i];
-                        v4i p;
-                        if constexpr (DIRECT) {
-                            const uint4 pq = aring[i];   // zero past M
-                            p = v4i{(int)pq.x, (int)pq.y, (int)pq.z, (int)pq.w};
-                        }
-                        if (b + kDecodeDepth < b_end) {
-                            ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
-                            if constexpr (DIRECT)
-                                if (tok_live) aring[i] = piece(b + kDecodeDepth);
-                        }
-                        const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
-                        if constexpr (!DIRECT) {
-                            p = *reinterpret_cast<const v4i*>(arow + b * kRowBytes);
-                            if (!tok_live) p = zero;
-                        }
-                        if (b < hi_blocks) {
-                            acc_hi = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, p, acc_hi, 0, 0, 0);
-                        } else {
-                            // see resq_gemm.hip.h: one operand of each product carries an offset of 8
-                            acc_lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                                w & (int)0xF0F0F0F0, tok_live ? (p & (int)0x0F0F0F0F) : zero, acc_lo, 0, 0, 0);
-                            acc_lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                                w & (int)0x0F0F0F0F, p & (int)0xF0F0F0F0, acc_lo, 0, 0, 0);
-                        }
-                    }
-                }
-            }
-        }
+        // the wavefront that will run the epilogue asks for its constants behind the first weight loads
+        const int64_t n0 = (int64_t)(live ? group : 0) * 16 + (lane >> 4) * 4;
+        EpilogueConsts ec;
+        if (part == 0) ec = load_epilogue_consts(ea, tok_live ? tok : 0, n0);
+        if (live) stream_run<DIRECT>(ring, aring, wp, piece, arow, b_begin, b_end, hi_blocks, acc_hi, acc_lo);
         // the next set's first loads go out before the sums are exchanged
         {
             const int nset = set + gridDim.x;
@@ -455,9 +561,8 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
 #pragma unroll
                 for (int i = 0; i < kDecodeDepth; ++i)
                     if (b_begin + i < b_end) {
-                        ring[i] = np[(b_begin + i) * (kBlockBytes / 16)];
-                        if constexpr (DIRECT)
-                            if (tok_live) aring[i] = piece(b_begin + i);
+                        ring[i] = load_weights_16B(&np[(b_begin + i) * (kBlockBytes / 16)]);
+                        if constexpr (DIRECT) aring[i] = piece(b_begin + i);
                     }
             }
         }
@@ -473,7 +578,7 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_splitk_kernel(cons
                 acc_lo += partial[((wave + k) * 2 + 1) * 64 + lane];
             }
             // lane l now holds token l % 16, channels 16 group + 4 (l / 16) + {0..3}
-            if (tok_live) stream_epilogue<DBG>(ea, tok, (int64_t)group * 16 + (lane >> 4) * 4, acc_hi, acc_lo);
+            if (tok_live) stream_epilogue<DBG>(ea, tok, n0, ec, acc_hi, acc_lo);
         }
         __syncthreads();  // the partial sums are read before the next set overwrites them
     }

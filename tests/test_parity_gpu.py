@@ -205,6 +205,8 @@ def test_layer_shapes(oracle, rq, M, K, N, r):
     (16, 1000, 515, 104),                        # K, r off the block size; N % 4 != 0
     (3, 256, 256, 0), (16, 256, 256, 256),       # uniform INT4, uniform INT8
     (7, 14336, 272, 1792),                       # longest K of the workloads
+    (14, 640, 300, 128), (15, 1024, 8720, 128),  # 14 tokens and more, one run per group: code rows copied to LDS
+    (13, 1024, 8720, 128),                       # the same layer just below that
 ])
 def test_layer_decode_shapes(oracle, rq, M, K, N, r):
     # M <= 16 takes the weight-streaming kernel
