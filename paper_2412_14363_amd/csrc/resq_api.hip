@@ -352,14 +352,27 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
 struct GemmPlan {
     int kernel, tg, sk;
 };
+// runs per channel group of the weight-streaming kernel for at most 16 tokens
+static int decode_runs(const WeightLayout& L) {
+    const int blocks = (int)(L.hi_blocks + L.lo_blocks);
+    const int64_t groups = (L.N + 15) / 16;
+    int sk = 1;
+    while (sk < 8 && groups * sk <= 1024 && blocks / (2 * sk) >= 4) sk *= 2;
+    return sk;
+}
 static GemmPlan plan_gemm(int64_t M, const WeightLayout& L) {
     const int blocks = (int)(L.hi_blocks + L.lo_blocks);
     const int64_t groups = (L.N + 15) / 16;
     const int64_t lds_row = L.kh_pad + L.kl_pad / 2 + kDecodeRowPad;
     if (M <= kDecodeMaxM && M * lds_row <= 140 * 1024) {
-        int sk = 1;
-        while (sk < 8 && groups * sk <= 1024 && blocks / (2 * sk) >= 4) sk *= 2;
-        return {0, 1, sk};
+        const int sk = decode_runs(L);
+        // From ten tokens on, a load of one block's codes straight from their rows touches so
+        // many cache lines (one per token) that the chunked kernel, which brings the codes
+        // through LDS, is faster on a wide layer too large for the caches (measured on 132 MB
+        // of weights: 24.1 / 24.9 -> 22.6 us at M = 12 / 16, equal at M = 9; on a 38 MB layer
+        // the plain kernel stays ahead at every M)
+        const bool chunked = M >= 10 && sk == 1 && L.total_bytes >= (int64_t)64 << 20;
+        if (!chunked) return {0, 1, sk};
     }
     int tg = 0, sk = 0;
     double stream_us = 0.0;
@@ -432,13 +445,9 @@ static DecodeArgs make_decode_args(const int8_t* q_hi, const uint8_t* q_lo, cons
 static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t st) {
     const WeightLayout& L = d.L;
     // the code rows go through LDS only when the kernel makes them itself
-    const int sk = plan_gemm(d.M, L).sk;   // runs per channel group
-    // From 14 tokens on, a load of one block's codes touches so many cache lines (one per
-    // token) that copying all code rows into LDS first is cheaper, on the long runs of wide
-    // layers (measured at M = 16, 132 MB of weights: 26.0 -> 24.4 us; at M = 12, and on the
-    // short runs of narrow layers at any M, the copy up front costs more than it saves).
-    const bool copy = !fused && !dbg && d.M >= 14 && sk == 1;
-    int lds_bytes = (fused || copy) ? ((d.M * d.lds_row + 15) & ~15) : 0;
+    const int sk = decode_runs(L);
+    // the code rows go through LDS only when the kernel makes them itself
+    int lds_bytes = fused ? ((d.M * d.lds_row + 15) & ~15) : 0;
     const int extra = fused ? kFusedScratchFloats * 4 : 0;
     const dim3 blk(kDecodeThreads);
 #define RESQ_LAUNCH_DECODE(KERNEL, GRID)                                                           \
@@ -470,7 +479,6 @@ static int launch_decode(const DecodeArgs& d, bool dbg, bool fused, hipStream_t 
     // one workgroup per compute unit (256 of them), fewer when there is less work
     const dim3 grid((unsigned)(d.groups < 256 ? d.groups : 256));
     if (fused) RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, kActQuantize>), grid);
-    else if (copy) RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, kActCopy>), grid);
     else if (dbg) RESQ_LAUNCH_DECODE((gemm_decode_kernel<true, kActDirect>), grid);
     else RESQ_LAUNCH_DECODE((gemm_decode_kernel<false, kActDirect>), grid);
 #undef RESQ_LAUNCH_DECODE
@@ -517,9 +525,13 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
         const int sets = (d.groups * sk + 7) / 8;
         const dim3 grid((unsigned)(sets < 256 ? sets : 256), (unsigned)slices), blk(kDecodeThreads);
         const int lds_bytes = 2 * sk * tg * kChunkBlocks * kBlockBytes;
+        // one slice over a layer that no cache holds: nobody reads the weights again (measured:
+        // 132 MB layers 4 to 10 % faster with the hint, a 38 MB layer 3 to 9 % slower)
+        const bool nt = !dbg && slices == 1 && L.total_bytes >= (int64_t)64 << 20;
 #define RESQ_LAUNCH_STREAM(TG, SK)                                                                 \
     do {                                                                                           \
-        auto kernel = dbg ? gemm_stream_kernel<true, TG, SK> : gemm_stream_kernel<false, TG, SK>;  \
+        auto kernel = dbg ? gemm_stream_kernel<true, TG, SK>                                       \
+                          : (nt ? gemm_stream_kernel<false, TG, SK, true> : gemm_stream_kernel<false, TG, SK>); \
         if (lds_bytes > 64 * 1024 &&                                                               \
             hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),                             \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) \

@@ -256,48 +256,6 @@ __device__ __forceinline__ void fill_act_quantize(const DecodeArgs& a, uint8_t* 
     __syncthreads();
 }
 
-// The code rows of all tokens copied from memory into the LDS rows (the layout that
-// fill_act_quantize writes: high part, low part, padding), 16 bytes at a time.  The loads of
-// the first kCopyBatch units per thread are issued by copy_issue, which a kernel calls
-// before it starts its weight stream, so that they are not queued behind it; copy_finish
-// stores them, moves whatever is left (rows longer than kCopyBatch * 8 KiB in total) and
-// ends with a barrier.
-constexpr int kCopyBatch = 10;
-struct ActCopy {
-    uint4 v[kCopyBatch];
-};
-__device__ __forceinline__ const uint4* copy_source(const DecodeArgs& a, int u, int per, int hi16, int& dst_off) {
-    const int m = u / per, k = u - m * per;
-    dst_off = m * a.lds_row + k * 16;
-    return reinterpret_cast<const uint4*>(k < hi16 ? a.q_hi + (int64_t)m * a.ld_hi + k * 16
-                                                   : a.q_lo + (int64_t)m * a.ld_lo + (k - hi16) * 16);
-}
-__device__ __forceinline__ void copy_issue(const DecodeArgs& a, int t, ActCopy& c) {
-    const int hi16 = (int)(a.L.kh_pad / 16), per = hi16 + (int)(a.L.kl_pad / 32), units = a.M * per;
-#pragma unroll
-    for (int j = 0; j < kCopyBatch; ++j) {
-        const int u = j * kDecodeThreads + t;
-        int off;
-        c.v[j] = *copy_source(a, u < units ? u : 0, per, hi16, off);
-    }
-}
-__device__ __forceinline__ void copy_finish(const DecodeArgs& a, uint8_t* act, int t, const ActCopy& c) {
-    const int hi16 = (int)(a.L.kh_pad / 16), per = hi16 + (int)(a.L.kl_pad / 32), units = a.M * per;
-#pragma unroll
-    for (int j = 0; j < kCopyBatch; ++j) {
-        const int u = j * kDecodeThreads + t;
-        int off;
-        copy_source(a, u < units ? u : 0, per, hi16, off);
-        if (u < units) *reinterpret_cast<uint4*>(act + off) = c.v[j];
-    }
-    for (int u = kCopyBatch * kDecodeThreads + t; u < units; u += kDecodeThreads) {
-        int off;
-        const uint4* src = copy_source(a, u, per, hi16, off);
-        *reinterpret_cast<uint4*>(act + off) = *src;
-    }
-    __syncthreads();
-}
-
 // the arguments as the epilogue reads them: with the fused quantizer the per-token
 // constants sit in LDS
 template <bool FUSED>
@@ -314,10 +272,9 @@ __device__ __forceinline__ DecodeArgs epilogue_args(const DecodeArgs& a, const f
 // Where a wavefront's activation operand comes from: straight from the code rows in memory
 // through a second ring beside the weight ring (no LDS, no barrier: the first matrix
 // instruction waits for nothing but its own two loads; the code rows are a few KiB per
-// token, stay in L2, and every wavefront reads its part of them once per group), from LDS
-// rows into which the workgroup has copied the code rows (the plain kernel from 14 tokens
-// on), or from LDS rows into which the workgroup itself has quantized the bf16 activations.
-enum : int { kActQuantize = 1, kActDirect = 2, kActCopy = 3 };
+// token, stay in L2, and every wavefront reads its part of them once per group), or from
+// LDS rows into which the workgroup itself has quantized the bf16 activations.
+enum : int { kActQuantize = 1, kActDirect = 2 };
 
 // lane's pointers to its 16-byte piece of block 0 of the high and of the low codes of its
 // token (the low pointer moved back by the high blocks, so that both take the block index)
@@ -446,8 +403,6 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
     const bool tok_live = tok < a.M;
     const ActPieces piece = act_pieces(a, lane, tok_live);
 
-    ActCopy staged;
-    if constexpr (ACT == kActCopy) copy_issue(a, t, staged);
     // start the weight stream of this wave's first group before anything else
     int group = wave * gridDim.x + blockIdx.x;
     uint4 ring[kDecodeDepth], aring[DIRECT ? kDecodeDepth : 1];
@@ -465,7 +420,6 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
 
     float* scal = reinterpret_cast<float*>(act + ((a.M * a.lds_row + 15) & ~15));
     if constexpr (ACT == kActQuantize) fill_act_quantize(a, act, scal, t);
-    if constexpr (ACT == kActCopy) copy_finish(a, act, t, staged);
     const DecodeArgs ea = epilogue_args<ACT == kActQuantize>(a, scal);
 
     const uint8_t* arow = act + (tok_live ? tok : 0) * a.lds_row + (lane >> 4) * 16;
@@ -604,7 +558,9 @@ constexpr int kChunkBlocks = 8;
 static_assert(kChunkBlocks == kDecodeDepth, "a chunk fills the weight ring exactly once");
 constexpr int kStreamMaxM = 64;
 
-template <bool DBG, int TG, int SK>
+// NT: the weights are read with the non-temporal hint (one token slice on a layer too large
+// for the caches: nobody reads them again)
+template <bool DBG, int TG, int SK, bool NT = false>
 __global__ __launch_bounds__(kDecodeThreads) void gemm_stream_kernel(const DecodeArgs a_in) {
     static_assert(TG * 16 <= kStreamMaxM && SK * TG <= 8, "LDS holds two chunks of every run");
     // blockIdx.y selects a slice of TG * 16 tokens (more tokens than that: every slice
@@ -651,24 +607,40 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_stream_kernel(const Decod
     // token group g, f = (p * kChunkBlocks + i) * TG + g.  Lane l brings row l / 4, piece
     // (l % 4) ^ (l / 16) of that block, which lands at unit l: the layout read above.
     const int f_r = lane >> 2, f_kc = (lane & 3) ^ (lane >> 4);
+    // (Buffer loads, not global ones: a global load to LDS counts for the compiler as an access
+    // through a flat address, after which it waits for every load in flight before any
+    // use of a loaded register.)
+    const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.q_hi), rs_lo = make_rsrc(a.q_lo);
+    auto fetch_one = [&](int q, int c, int buf, bool all) __attribute__((always_inline)) {
+        const int f = q * kWaves + wave;
+        const int g = f % TG, i = (f / TG) % kChunkBlocks, p = f / (TG * kChunkBlocks);
+        int b = run_begin(p) + c * kChunkBlocks + i;
+        if (!all && b >= run_begin(p + 1)) return;
+        b = b < blocks ? b : blocks - 1;  // a block past the end of its run: valid memory, never read from LDS
+        int m = g * 16 + f_r;
+        m = m < a.M ? m : a.M - 1;  // rows past M repeat the last token (never stored)
+        const bool hi = b < hi_blocks;
+        const uint32_t voff = hi ? (uint32_t)(m * (int)a.ld_hi + b * kRowBytes + f_kc * 16)
+                                 : (uint32_t)(m * (int)a.ld_lo + (b - hi_blocks) * kRowBytes + f_kc * 16);
+        buffer_load_to_lds_16B(hi ? rs_hi : rs_lo, voff, 0, act + buf * kBufBytes + f * kBlockBytes);
+    };
     auto fetch_chunk = [&](int c, int buf) {
 #pragma unroll
-        for (int q = 0; q < kFetches; ++q) {
-            const int f = q * kWaves + wave;
-            const int g = f % TG, i = (f / TG) % kChunkBlocks, p = f / (TG * kChunkBlocks);
-            const int b = run_begin(p) + c * kChunkBlocks + i;
-            if (b < run_begin(p + 1)) {
-                int m = g * 16 + f_r;
-                m = m < a.M ? m : a.M - 1;  // rows past M repeat the last token (never stored)
-                const uint8_t* src = b < hi_blocks
-                                         ? a.q_hi + (int64_t)m * a.ld_hi + (int64_t)b * kRowBytes
-                                         : a.q_lo + (int64_t)m * a.ld_lo + (int64_t)(b - hi_blocks) * kRowBytes;
-                load_to_lds_16B(src + f_kc * 16, act + buf * kBufBytes + f * kBlockBytes);
-            }
-        }
+        for (int q = 0; q < kFetches; ++q) fetch_one(q, c, buf, false);
         asm volatile("" ::: "memory");  // later loads stay behind these
     };
+    // the same without conditions, for chunk steps that are straight-line code
+    auto fetch_chunk_all = [&](int c, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < kFetches; ++q) fetch_one(q, c, buf, true);
+        asm volatile("" ::: "memory");
+    };
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)act;
 
+    auto load_w = [](const uint4* ptr) __attribute__((always_inline)) {
+        if constexpr (NT) return load_weights_16B(ptr);
+        else return *ptr;
+    };
     const int sets = (a.groups + G - 1) / G;
     for (int set = blockIdx.x; set < sets; set += gridDim.x) {
         const int group = set * G + gsel;
@@ -678,7 +650,7 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_stream_kernel(const Decod
         uint4 ring[kDecodeDepth];
 #pragma unroll
         for (int i = 0; i < kDecodeDepth; ++i)
-            if (live && b_begin + i < b_end) ring[i] = wp[(b_begin + i) * (kBlockBytes / 16)];
+            if (live && b_begin + i < b_end) ring[i] = load_w(&wp[(b_begin + i) * (kBlockBytes / 16)]);
         __syncthreads();  // every wavefront is done with the LDS buffers of the previous set
         fetch_chunk(0, 0);
         wait_loads_and_barrier<0>();
@@ -689,7 +661,86 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_stream_kernel(const Decod
             acc_hi[g] = (v4i){0, 0, 0, 0};
             acc_lo[g] = (v4i){0, 0, 0, 0};
         }
-        for (int c = 0; c < chunks; ++c) {
+        // Chunk steps of a run that has all eight blocks of this chunk and of the next, all of
+        // one kind: straight-line code in loops of their own (see stream_run for why), the
+        // activation fragments read by instructions the compiler does not track, so that it
+        // does not make every LDS read wait for the chunk loads in flight.
+        constexpr int PGs = TG < 4 ? TG : 4;            // groups per pass
+        constexpr int PASSESs = TG / PGs;               // passes per block
+        auto wait_frags = [&](v4i (&f)[PGs]) __attribute__((always_inline)) {
+            if constexpr (PGs == 1) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]));
+            else if constexpr (PGs == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]));
+            else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
+        };
+        auto steady_step = [&](auto kind, int c) __attribute__((always_inline)) {
+            constexpr int KIND = decltype(kind)::value;  // 0: high blocks, 1: low blocks, 2: both
+            fetch_chunk_all(c + 1, (c + 1) & 1);
+            const uint32_t cur = lds0 + (c & 1) * kBufBytes + read_off;
+            const int first = b_begin + c * kChunkBlocks;
+            v4i p[PGs], pn[PGs];
+            static_for<PGs>([&](auto g_) __attribute__((always_inline)) {
+                constexpr int g = decltype(g_)::value;
+                lds_read16<g * kBlockBytes>(p[g], cur);
+            });
+            wait_frags(p);
+            static_for<kChunkBlocks>([&](auto i_) __attribute__((always_inline)) {
+                constexpr int i = decltype(i_)::value;
+                static_for<PASSESs>([&](auto h_) __attribute__((always_inline)) {
+                    constexpr int h = decltype(h_)::value;
+                    constexpr int kLast = kChunkBlocks * PASSESs - 1, step = i * PASSESs + h;
+                    if constexpr (step < kLast) {
+                        constexpr int ni = (step + 1) / PASSESs, nh = (step + 1) % PASSESs;
+                        static_for<PGs>([&](auto g_) __attribute__((always_inline)) {
+                            constexpr int g = decltype(g_)::value;
+                            lds_read16<(ni * TG + nh * PGs + g) * kBlockBytes>(pn[g], cur);
+                        });
+                    }
+                    const v4i w = {(int)ring[i].x, (int)ring[i].y, (int)ring[i].z, (int)ring[i].w};
+                    if (KIND == 0 || (KIND == 2 && first + i < hi_blocks)) {
+#pragma unroll
+                        for (int g = 0; g < PGs; ++g)
+                            acc_hi[h * PGs + g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, p[g], acc_hi[h * PGs + g], 0, 0, 0);
+                    } else {
+                        // see resq_gemm.hip.h: one operand of each product carries an offset of 8
+                        const v4i we = w & (int)0xF0F0F0F0, wo = w & (int)0x0F0F0F0F;
+#pragma unroll
+                        for (int g = 0; g < PGs; ++g) {
+                            acc_lo[h * PGs + g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                we, p[g] & (int)0x0F0F0F0F, acc_lo[h * PGs + g], 0, 0, 0);
+                            acc_lo[h * PGs + g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                wo, p[g] & (int)0xF0F0F0F0, acc_lo[h * PGs + g], 0, 0, 0);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (step < kLast) {
+                        wait_frags(pn);
+#pragma unroll
+                        for (int g = 0; g < PGs; ++g) p[g] = pn[g];
+                    }
+                });
+                // the slot is refilled once its last product has been issued
+                ring[i] = load_w(&wp[(first + i + kDecodeDepth) * (kBlockBytes / 16)]);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            // the next chunk's codes have landed; the eight weight loads behind them stay in flight
+            wait_loads_and_barrier<kDecodeDepth>();
+        };
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // nothing in flight here (the wait above): tells the compiler so
+        int c = 0;
+        auto steady = [&](int cc) { return live && b_begin + (cc + 2) * kChunkBlocks <= b_end; };
+        while (steady(c) && b_begin + (c + 1) * kChunkBlocks <= hi_blocks) {
+            steady_step(std::integral_constant<int, 0>{}, c);
+            ++c;
+        }
+        if (steady(c) && b_begin + c * kChunkBlocks < hi_blocks) {
+            steady_step(std::integral_constant<int, 2>{}, c);
+            ++c;
+        }
+        while (steady(c) && b_begin + c * kChunkBlocks >= hi_blocks) {
+            steady_step(std::integral_constant<int, 1>{}, c);
+            ++c;
+        }
+        for (; c < chunks; ++c) {
             // the other buffer was last read in chunk c - 1, before the barrier that ended it
             if (c + 1 < chunks) fetch_chunk(c + 1, (c + 1) & 1);
             const uint8_t* cur = act + (c & 1) * kBufBytes + read_off;
@@ -709,7 +760,7 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_stream_kernel(const Decod
                 for (int i = 0; i < kChunkBlocks; ++i) {
                     const int b = first + i;  // kChunkBlocks == kDecodeDepth: ring slot i
                     const uint4 wq = ring[i];
-                    if (b + kDecodeDepth < b_end) ring[i] = wp[(b + kDecodeDepth) * (kBlockBytes / 16)];
+                    if (b + kDecodeDepth < b_end) ring[i] = load_w(&wp[(b + kDecodeDepth) * (kBlockBytes / 16)]);
                     const v4i w = {(int)wq.x, (int)wq.y, (int)wq.z, (int)wq.w};
                     const bool hi_block = KIND == 0 || (KIND == 2 && b < hi_blocks && b < b_end);
                     const bool lo_block = KIND == 1 || (KIND == 2 && b >= hi_blocks && b < b_end);

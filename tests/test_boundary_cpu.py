@@ -271,7 +271,9 @@ def test_gemm_mixed_plan():
     # the benchmark's workloads
     assert plan(2048, 4096, 4096, 512) == (2, 0, 0)            # o_proj prefill: tiled
     assert plan(1, 28672, 8192, 1024) == (0, 1, 1)             # decode, wide layer: one run per group
-    assert plan(16, 28672, 8192, 1024) == (0, 1, 1)
+    assert plan(9, 28672, 8192, 1024) == (0, 1, 1)
+    assert plan(16, 28672, 8192, 1024) == (1, 1, 1)            # ... ten tokens and more: codes chunked through LDS
+    assert plan(16, 8192, 8192, 1024)[0] == 0                  # not on a layer the caches hold
     assert plan(1, 4096, 4096, 512) == (0, 1, 8)               # narrow layer: reduction axis cut
     assert plan(16, 8192, 28672, 3584) == (1, 1, 4)            # code rows too long to re-read per wavefront
     assert plan(64, 28672, 8192, 1024) == (1, 4, 1)            # batched decode, wide layer: one slice

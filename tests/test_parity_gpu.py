@@ -205,8 +205,7 @@ def test_layer_shapes(oracle, rq, M, K, N, r):
     (16, 1000, 515, 104),                        # K, r off the block size; N % 4 != 0
     (3, 256, 256, 0), (16, 256, 256, 256),       # uniform INT4, uniform INT8
     (7, 14336, 272, 1792),                       # longest K of the workloads
-    (14, 640, 300, 128), (15, 1024, 8720, 128),  # 14 tokens and more, one run per group: code rows copied to LDS
-    (13, 1024, 8720, 128),                       # the same layer just below that
+    (14, 640, 300, 128), (15, 1024, 8720, 128), (9, 1024, 8720, 128),
 ])
 def test_layer_decode_shapes(oracle, rq, M, K, N, r):
     # M <= 16 takes the weight-streaming kernel
@@ -351,9 +350,9 @@ def test_layer_batched_decode_full_size(oracle, rq):
     check_layer(oracle, rq, wl.make_activations(s), wl.make_weights(s), s.r)
 
 
-@pytest.mark.parametrize("M", [16, 1])
+@pytest.mark.parametrize("M", [16, 9, 1])
 def test_layer_decode_full_size(oracle, rq, M):
-    # the decode workload at full size (Llama-3-70B up_proj, 16 tokens and a single token); the
+    # the decode workload at full size (Llama-3-70B up_proj; 16 tokens: the chunked kernel, 9 and 1: the plain one); the
     # oracle checks all codes and every accumulator and output
     s = wl.decode_shape(M)
     check_layer(oracle, rq, wl.make_activations(s), wl.make_weights(s), s.r)
