@@ -5,8 +5,9 @@
 // instruction (16 channels x 64 bytes, see resq_layout.h): lane l loads row
 // l % 16, 16-byte piece l / 16 straight into operand registers, no LDS in
 // between, and a wavefront walks the contiguous blocks of one 16-channel group
-// (all high blocks, then all low blocks) with eight loads in flight.  One
-// workgroup of eight wavefronts runs per compute unit, and groups are dealt
+// (all high blocks, then all low blocks) with a ring of eight loads in flight,
+// of which it only ever waits for the oldest (see stream_run for what that takes).
+// One workgroup of eight wavefronts runs per compute unit, and groups are dealt
 // round-robin over compute units first, so that every unit streams the same
 // number of bytes.  The activation codes of all tokens (at most a few tens of
 // KiB) are read from L2 as they are needed.  The matrix cores are nearly idle here; they are used because
