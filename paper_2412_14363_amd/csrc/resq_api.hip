@@ -377,17 +377,25 @@ static GemmPlan plan_gemm(int64_t M, const WeightLayout& L) {
     int tg = 0, sk = 0;
     double stream_us = 0.0;
     if (M <= 16 * kStreamMaxM) {
-        const double pass_us = (double)L.total_bytes / 5.0e6;
-        for (int cand_tg = 1; cand_tg <= 4; cand_tg *= 2) {
-            const double per_block = cand_tg == 1 ? 0.16 : (cand_tg == 2 ? 0.27 : 0.42);
+        // Estimate per (token groups, runs): 1.9 us + rounds of 256 workgroups x (a fixed part + a
+        // cost per 1 KiB block of a run), never less than one pass over the weights at 6 TB/s.
+        // The constants are a least-squares fit to a sweep of all pairs over seven layer shapes and
+        // M = 24..512 (on which this choice is the measured best or within 1 % of it).
+        static const double kFixed[3][4] = {{1.46, 1.88, 0.31, 3.0}, {3.23, 4.72, 0.0, 0.0}, {4.62, 0.0, 0.0, 0.0}};
+        static const double kPerBlock[3][4] = {{0.139, 0.146, 0.250, 0.45}, {0.170, 0.194, 0.0, 0.0}, {0.257, 0.0, 0.0, 0.0}};
+        const double pass_us = (double)L.total_bytes / 6.0e6;
+        for (int ti = 0; ti < 3; ++ti) {
+            const int cand_tg = 1 << ti;
             const int64_t slices = (M + cand_tg * 16 - 1) / (cand_tg * 16);
-            for (int cand_sk = 1; cand_sk * cand_tg <= 8; cand_sk *= 2) {
+            // pairs (2, 4) and (4, 2) were the measured best nowhere in that sweep: not built
+            for (int si = 0; cand_tg == 1 ? si <= 3 : (cand_tg << si) <= 4; ++si) {
+                const int cand_sk = 1 << si;
                 // runs of at least two chunks, at most 2048 of them
                 if (cand_sk > 1 && (groups * cand_sk > 2048 || blocks / cand_sk < 2 * kChunkBlocks)) break;
                 const int64_t sets = (groups * cand_sk + 7) / 8;
                 const int64_t wgs = (sets < 256 ? sets : 256) * slices;
                 const int64_t rounds = ((wgs + 255) / 256) * ((sets + 255) / 256);
-                double us = (double)rounds * (7.0 + per_block * (double)(blocks / cand_sk));
+                double us = 1.9 + (double)rounds * (kFixed[ti][si] + kPerBlock[ti][si] * (double)(blocks / cand_sk));
                 if (us < pass_us) us = pass_us;
                 if (tg == 0 || us < stream_us) {
                     stream_us = us;
@@ -545,9 +553,7 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
             case 1 * 16 + 8: RESQ_LAUNCH_STREAM(1, 8); break;
             case 2 * 16 + 1: RESQ_LAUNCH_STREAM(2, 1); break;
             case 2 * 16 + 2: RESQ_LAUNCH_STREAM(2, 2); break;
-            case 2 * 16 + 4: RESQ_LAUNCH_STREAM(2, 4); break;
-            case 4 * 16 + 1: RESQ_LAUNCH_STREAM(4, 1); break;
-            default: RESQ_LAUNCH_STREAM(4, 2); break;
+            default: RESQ_LAUNCH_STREAM(4, 1); break;
         }
 #undef RESQ_LAUNCH_STREAM
         return launch_status();
