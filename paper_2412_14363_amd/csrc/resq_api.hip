@@ -345,10 +345,10 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
 //             alone): the same single pass over the weights, activation codes chunked
 //             through LDS, in slices of 16 TG tokens (each slice streams the weights for
 //             itself, out of the last-level cache after the first).  TG and SK are the pair
-//             with the lowest estimate from the measured costs of the kernel: per round of
-//             256 workgroups 7 us + (0.16, 0.27, 0.42) us per 1 KiB block of a run for
-//             TG = (1, 2, 4), and never less than one pass over the weights at 5 TB/s.
-//   kernel 2: the tiled kernel; a tile costs 10 us + 0.5 us per block by the same measure.
+//             with the lowest estimate from the measured costs of the kernel (constants
+//             below), never less than one pass over the weights at 6 TB/s.
+//   kernel 2: the tiled kernel; a round of 512 tiles (two per compute unit) costs
+//             10 us + 0.5 us per block by the same measure.
 struct GemmPlan {
     int kernel, tg, sk;
 };
@@ -407,8 +407,9 @@ static GemmPlan plan_gemm(int64_t M, const WeightLayout& L) {
     }
     bool streaming = M <= kStreamMaxM;
     if (!streaming && tg != 0) {
+        // 512 tiles run at a time, two per compute unit
         const int64_t tiles = ((M + kBM - 1) / kBM) * ((L.N + kBN - 1) / kBN);
-        const double tiled_us = (double)((tiles + 255) / 256) * (10.0 + 0.5 * (double)blocks);
+        const double tiled_us = (double)((tiles + 511) / 512) * (10.0 + 0.5 * (double)blocks);
         streaming = stream_us < 0.9 * tiled_us;
     }
     if (streaming) return {1, tg, sk};

@@ -2,24 +2,30 @@
 //   A_hi = q_hi * w_hi^T over the high group, A_lo = q_lo * w_lo^T over the low
 //   group, y = bf16(A_hi * s_hi[m] * sw_hi[n] + A_lo * s_lo[m] * sw_lo[n]).
 //
-// Tiling.  One workgroup of 8 wavefronts owns a 128 (tokens) x 256 (channels)
+// Tiling.  One workgroup of 4 wavefronts owns a 128 (tokens) x 128 (channels)
 // output tile; each wavefront owns 64 x 64 of it as 4 x 4 tiles of the
 // 16x16x64 int8 matrix-core instruction, the weights as its first operand so
 // that a lane ends up with four consecutive channels of one token.  (Under the
 // chip's power limit this instruction sustains 16-20 % more operations per
 // second than the 32x32x32 one on the same operands: it moves a quarter of the
-// accumulator registers per instruction for half the products.)  Two
-// wavefronts share a SIMD (256 registers each): while one waits for the matrix
-// pipe, the other issues its vector-ALU, LDS and memory instructions, which a
-// single wavefront per SIMD cannot hide behind its own matrix instructions
-// (measured: about five other instructions fit behind one matrix instruction
-// of a lone wavefront, and the low group needs more).
+// accumulator registers per instruction for half the products.)  TWO workgroups
+// share a compute unit (half of its LDS and registers each), so two wavefronts
+// share a SIMD (256 registers each): while one waits for the matrix pipe, the
+// other issues its vector-ALU, LDS and memory instructions, which a single
+// wavefront per SIMD cannot hide behind its own matrix instructions (measured:
+// about five other instructions fit behind one matrix instruction of a lone
+// wavefront, and the low group needs more); and since the two are independent
+// workgroups, one's prologue, epilogue and barrier waits are the other's
+// matrix time.  (One workgroup of 8 wavefronts on a 128 x 256 tile, the same
+// wavefront tiles and registers, moves a quarter less through L2 per product
+// but leaves the compute unit idle at both ends of every tile: measured 10-17 %
+// slower on the Llama-3-8B MLP shapes, 0-3 % on the Qwen2.5-72B one.)
 //
 // Stages.  The reduction axis is walked in stages of 64 bytes per row: 64 int8
 // codes of the high group or 128 nibble codes of the low group, one reduction
 // step of the matrix-core instruction (two for nibbles: even and odd columns).  High and low stages form one sequence; the
-// global->LDS copy is the same for both.  Six LDS buffers of 24 KiB hold the
-// stage being multiplied, the next one, and up to four in flight.
+// global->LDS copy is the same for both.  Four LDS buffers of 16 KiB hold the
+// stage being multiplied, the next one, and two in flight.
 //
 // Global -> LDS.  Buffer loads with the LDS flag move 16 bytes per lane to a
 // wave-uniform LDS base plus 16 * lane, so the LDS image is fixed by which
@@ -42,8 +48,8 @@
 // the next weight fragment is widened behind the products of the current one,
 // the next stage's activation fragments in place behind the last products
 // that read their predecessors.  High stages multiply the fragments as read.  The
-// epilogue's per-channel and per-token constants (3.5 KiB) are fetched into
-// LDS by the first loads of the kernel.
+// epilogue's per-channel and per-token constants (2.5 KiB, 4.5 KiB with
+// asymmetric codes) are fetched into LDS by the first loads of the kernel.
 //
 // The low group.  A lane's 16 packed bytes hold 32 codes, and each nibble is
 // widened to an int8 operand with one AND.  In an activation byte the low
@@ -59,7 +65,7 @@
 // Two scale pairs, one output write.  Each group has its own int32 tile in
 // accumulation registers (2 x 64 per lane); both are folded into the output
 // at the end, and y is written once, through LDS so that every store
-// instruction writes whole 512-byte row segments.
+// instruction writes whole 256-byte row segments.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -75,31 +81,33 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kGemmThreads = 512;  // 8 wavefronts, two per SIMD
+constexpr int kGemmThreads = 256;  // 4 wavefronts, one per SIMD; two workgroups share a compute unit
 constexpr int kBM = 128;
-constexpr int kBN = 256;
+constexpr int kBN = 128;
 constexpr int kStageABytes = kBM * kRowBytes;  // 8 KiB = 8 blocks
-constexpr int kStageBBytes = kBN * kRowBytes;  // 16 KiB = 16 blocks
+constexpr int kStageBBytes = kBN * kRowBytes;  // 8 KiB = 8 blocks
 constexpr int kStageBytes = kStageABytes + kStageBBytes;
-constexpr int kNumBuf = 6;
+constexpr int kNumBuf = 4;
 constexpr int kPrefetch = kNumBuf - 1;  // stages requested ahead of the one being multiplied
-constexpr int kLoadsPerStage = (kBM + kBN) / kRowsPerBlock / 8;  // per wavefront: 3 (one activation block, two weight blocks)
+constexpr int kLoadsPerStage = (kBM + kBN) / kRowsPerBlock / 4;  // per wavefront: 4 (two activation blocks, two weight blocks)
 constexpr int kOutRowBytes = kBN * 2 + 16;  // one tile row of bf16 in LDS, padded
 // After the stage buffers: the tile's per-channel and per-token constants of the
 // epilogue, copied there by the first loads of the kernel.
 constexpr int kMetaOff = kNumBuf * kStageBytes;
-constexpr int kMetaSwHi = 0;       // fp16 [256] high-group weight scales
-constexpr int kMetaSwLo = 512;     // fp16 [256] low-group weight scales
-constexpr int kMetaEven = 1024;    // int32 [256] even-column code sums of the low group
-constexpr int kMetaSHi = 2048;     // fp32 [128] high-group token scales
-constexpr int kMetaSLo = 2560;     // fp32 [128] low-group token scales
-constexpr int kMetaLoSum = 3072;   // int32 [128] odd-column code sums of the low group
+constexpr int kMetaSwHi = 0;       // fp16 [128] high-group weight scales
+constexpr int kMetaSwLo = 256;     // fp16 [128] low-group weight scales
+constexpr int kMetaEven = 512;     // int32 [128] even-column code sums of the low group
+constexpr int kMetaSHi = 1024;     // fp32 [128] high-group token scales
+constexpr int kMetaSLo = 1536;     // fp32 [128] low-group token scales
+constexpr int kMetaLoSum = 2048;   // int32 [128] odd-column code sums of the low group
 // only for asymmetric activation codes:
-constexpr int kMetaWsumHi = 3584;  // int32 [256] sums of the high weight codes
-constexpr int kMetaWsumLo = 4608;  // int32 [256] sums of the low weight codes
-constexpr int kMetaCHi = 5632;     // fp32 [128] real value of the stored high code 0, per token
-constexpr int kMetaCLo = 6144;     // fp32 [128] the same for the low group
-constexpr int kMetaBytes = 6656;
+constexpr int kMetaWsumHi = 2560;  // int32 [128] sums of the high weight codes
+constexpr int kMetaWsumLo = 3072;  // int32 [128] sums of the low weight codes
+constexpr int kMetaCHi = 3584;     // fp32 [128] real value of the stored high code 0, per token
+constexpr int kMetaCLo = 4096;     // fp32 [128] the same for the low group
+constexpr int kMetaBytes = 4608;
+// two workgroups fit the 160 KiB of a compute unit
+static_assert(2 * (kMetaOff + kMetaBytes) <= 160 * 1024, "LDS of two resident workgroups");
 
 struct GemmArgs {
     const uint8_t* q_hi;
@@ -232,19 +240,19 @@ __device__ __forceinline__ void buffer_load_to_lds_16B(__amdgpu_buffer_rsrc_t rs
 
 // blockIdx -> (tile_m, tile_n).  Consecutive workgroup ids land on different
 // XCDs (8 of them, 32 compute units and one L2 each), and an XCD runs its
-// workgroups in id order, 32 at a time.  When the grid allows it, the 32 tiles
-// an XCD works on together form an 8 x 4 patch (1024 tokens x 1024 channels),
-// so that each activation stage is fetched into that L2 once per 4 tiles and
-// each weight stage once per 8; the 8 XCDs take neighbouring patches.
+// workgroups in id order, 64 at a time (two per compute unit).  When the grid
+// allows it, the 64 tiles an XCD works on together form an 8 x 8 patch (1024
+// tokens x 1024 channels), so that each activation stage and each weight stage
+// is fetched into that L2 once per 8 tiles; the 8 XCDs take neighbouring patches.
 __device__ __forceinline__ void tile_of_block(const GemmArgs& a, int& tm, int& tn) {
     const int total = a.tiles_m * a.tiles_n;
     const int id = blockIdx.x;
-    if (total % 256 == 0 && a.tiles_m % 8 == 0 && a.tiles_n % 4 == 0) {
+    if (total % 512 == 0 && a.tiles_m % 8 == 0 && a.tiles_n % 8 == 0) {
         const int xcd = id & 7, k = id >> 3;
-        const int patch = (k >> 5) * 8 + xcd, within = k & 31;
+        const int patch = (k >> 6) * 8 + xcd, within = k & 63;
         const int patches_m = a.tiles_m >> 3;
         tm = (patch % patches_m) * 8 + (within & 7);
-        tn = (patch / patches_m) * 4 + (within >> 3);
+        tn = (patch / patches_m) * 8 + (within >> 3);
     } else if (total % 8 == 0) {
         const int lin = (id & 7) * (total >> 3) + (id >> 3);
         tn = lin / a.tiles_m;
@@ -267,15 +275,17 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
+// Second launch bound: two workgroups per compute unit, i.e. two wavefronts per SIMD with
+// 256 registers each (128 vector + 128 accumulation).
 template <bool DBG>
-__global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_kernel(const GemmArgs a) {
     __shared__ __attribute__((aligned(1024))) uint8_t lds[kMetaOff + kMetaBytes];
 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int wm = wave >> 2;  // 0..1: 64-token half of the tile
-    const int wn = wave & 3;   // 0..3: 64-channel quarter of the tile
+    const int wm = wave >> 1;  // 0..1: 64-token half of the tile
+    const int wn = wave & 1;   // 0..1: 64-channel half of the tile
     int tile_m, tile_n;
     tile_of_block(a, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * kBM;
@@ -289,13 +299,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     // ---- epilogue constants -> LDS ---------------------------------------------
     // These are the oldest loads of their waves, so the first wait for a stage
     // covers them.  Token rows past M repeat the last row (never stored).
+    // (a load to LDS places an active lane's bytes at the base plus 16 x its lane number)
     if (wave == 0) {
-        load_to_lds_16B((lane < 32 ? sw_hi : sw_lo) + n0 + (lane & 31) * 8, lds + kMetaOff + kMetaSwHi);
-        if (asym) load_to_lds_16B(even_sum + a.L.n_pad + n0 + lane * 4, lds + kMetaOff + kMetaWsumHi);
+        if (lane < 32) {
+            load_to_lds_16B((lane < 16 ? sw_hi : sw_lo) + n0 + (lane & 15) * 8, lds + kMetaOff + kMetaSwHi);
+            if (asym) load_to_lds_16B(even_sum + a.L.n_pad + n0 + lane * 4, lds + kMetaOff + kMetaWsumHi);
+        }
     } else if (wave == 1) {
-        load_to_lds_16B(even_sum + n0 + lane * 4, lds + kMetaOff + kMetaEven);
-        if (asym) load_to_lds_16B(even_sum + 2 * a.L.n_pad + n0 + lane * 4, lds + kMetaOff + kMetaWsumLo);
-    } else if (wave < 4) {
+        if (lane < 32) {
+            load_to_lds_16B(even_sum + n0 + lane * 4, lds + kMetaOff + kMetaEven);
+            if (asym) load_to_lds_16B(even_sum + 2 * a.L.n_pad + n0 + lane * 4, lds + kMetaOff + kMetaWsumLo);
+        }
+    } else {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             int64_t m = m0 + h * 64 + lane;
@@ -313,19 +328,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
 
     // ---- global -> LDS copy --------------------------------------------------
     // One load instruction fills one block: lane l fetches row l / 4, piece
-    // (l % 4) ^ (l / 16).  Wave w copies A block w and B blocks 2w, 2w+1 of each
-    // stage.  Token rows past M are clamped to the last row (their results are
+    // (l % 4) ^ (l / 16).  Wave w copies A blocks 2w, 2w+1 and B blocks 2w, 2w+1 of
+    // each stage.  Token rows past M are clamped to the last row (their results are
     // never stored).  The weight blocks of one 16-channel group are contiguous
     // over all stages, high ones first.  Every address is a buffer resource
     // (wave-uniform, fixed) plus a per-lane offset that never changes plus a
     // scalar offset that depends on the stage alone.
-    uint32_t a_voff_hi, a_voff_lo, b_voff[2];
+    uint32_t a_voff_hi[2], a_voff_lo[2], b_voff[2];
     {
         const int r = lane >> 2, kc = (lane & 3) ^ (lane >> 4);
-        int64_t row = wave * 16 + r;
-        row = m0 + row < a.M ? row : a.M - 1 - m0;
-        a_voff_hi = (uint32_t)(row * a.ld_hi + kc * 16);
-        a_voff_lo = (uint32_t)(row * a.ld_lo + kc * 16);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int64_t row = (wave * 2 + h) * 16 + r;
+            row = m0 + row < a.M ? row : a.M - 1 - m0;
+            a_voff_hi[h] = (uint32_t)(row * a.ld_hi + kc * 16);
+            a_voff_lo[h] = (uint32_t)(row * a.ld_lo + kc * 16);
+        }
         b_voff[0] = r * kRowBytes + kc * 16;
         b_voff[1] = b_voff[0] + (uint32_t)a.L.group_bytes;
     }
@@ -333,28 +351,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     const __amdgpu_buffer_rsrc_t rs_a_hi = make_rsrc(a.q_hi + m0 * a.ld_hi);
     const __amdgpu_buffer_rsrc_t rs_a_lo = make_rsrc(a.q_lo + m0 * a.ld_lo - (int64_t)S_hi * kRowBytes);
     const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(a.packed + (n0 / 16 + wave * 2) * a.L.group_bytes);
-    // load K of stage sg (0 .. S-1, high stages first) into buffer buf; K = 0: the A block, 1, 2: the B blocks
+    // load K of stage sg (0 .. S-1, high stages first) into buffer buf; K = 0, 1: the A blocks, 2, 3: the B blocks
     auto issue_load = [&](auto k, int sg, int buf) __attribute__((always_inline)) {
         constexpr int K = decltype(k)::value;
         uint8_t* dst = lds + buf * kStageBytes;
-        if constexpr (K == 0) {
+        if constexpr (K < 2) {
             const bool lo = sg >= S_hi;
-            buffer_load_to_lds_16B(lo ? rs_a_lo : rs_a_hi, lo ? a_voff_lo : a_voff_hi, (uint32_t)sg * kRowBytes,
-                                   dst + wave * kBlockBytes);
+            buffer_load_to_lds_16B(lo ? rs_a_lo : rs_a_hi, lo ? a_voff_lo[K] : a_voff_hi[K], (uint32_t)sg * kRowBytes,
+                                   dst + (wave * 2 + K) * kBlockBytes);
         } else {
-            buffer_load_to_lds_16B(rs_b, b_voff[K - 1], (uint32_t)sg * kBlockBytes,
-                                   dst + kStageABytes + (wave * 2 + K - 1) * kBlockBytes);
+            buffer_load_to_lds_16B(rs_b, b_voff[K - 2], (uint32_t)sg * kBlockBytes,
+                                   dst + kStageABytes + (wave * 2 + K - 2) * kBlockBytes);
         }
     };
     // the same for a stage known to be a low one (no selection of the activation rows)
     auto issue_load_lo = [&](auto k, int sg, int buf) __attribute__((always_inline)) {
         constexpr int K = decltype(k)::value;
         uint8_t* dst = lds + buf * kStageBytes;
-        if constexpr (K == 0)
-            buffer_load_to_lds_16B(rs_a_lo, a_voff_lo, (uint32_t)sg * kRowBytes, dst + wave * kBlockBytes);
+        if constexpr (K < 2)
+            buffer_load_to_lds_16B(rs_a_lo, a_voff_lo[K], (uint32_t)sg * kRowBytes, dst + (wave * 2 + K) * kBlockBytes);
         else
-            buffer_load_to_lds_16B(rs_b, b_voff[K - 1], (uint32_t)sg * kBlockBytes,
-                                   dst + kStageABytes + (wave * 2 + K - 1) * kBlockBytes);
+            buffer_load_to_lds_16B(rs_b, b_voff[K - 2], (uint32_t)sg * kBlockBytes,
+                                   dst + kStageABytes + (wave * 2 + K - 2) * kBlockBytes);
     };
 
     // ---- accumulators ----------------------------------------------------------
@@ -571,10 +589,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                         // an all-low layer than a barrier after the second product)
                         __builtin_amdgcn_sched_barrier(0);
                         if constexpr (STEADY) {
-                            wait_loads_and_barrier<3 * kLoadsPerStage>();
+                            wait_loads_and_barrier<(kPrefetch - 2) * kLoadsPerStage>();
                         } else {
                             const int rem = S - 2 - sg;
-                            wait_stage_and_barrier(rem > 3 ? 3 : rem);
+                            wait_stage_and_barrier(rem > kPrefetch - 2 ? kPrefetch - 2 : rem);
                         }
                     }
                     // the halves of the weight fragments: odd columns code + 8, even columns 16 * code
@@ -597,8 +615,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                         }
                     }
                     if constexpr (J == 1 && P == 3) { if (issue) issue_load_lo(IC<0>{}, sg + kPrefetch, prv); }
-                    if constexpr (J == 2 && P == 3) { if (issue) issue_load_lo(IC<1>{}, sg + kPrefetch, prv); }
-                    if constexpr (J == 2 && P == 6) { if (issue) issue_load_lo(IC<2>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 1 && P == 7) { if (issue) issue_load_lo(IC<1>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 2 && P == 3) { if (issue) issue_load_lo(IC<2>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 2 && P == 6) { if (issue) issue_load_lo(IC<3>{}, sg + kPrefetch, prv); }
                     if constexpr (J == 2 && P == 7) {
                         lds_wait<0>(nx.b);
                         lds_wait<0>(nx.a);
@@ -636,17 +655,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
                     if constexpr (J == 0 && I == 3) {
                         __builtin_amdgcn_sched_barrier(0);
                         if constexpr (STEADY) {
-                            wait_loads_and_barrier<3 * kLoadsPerStage>();
+                            wait_loads_and_barrier<(kPrefetch - 2) * kLoadsPerStage>();
                         } else {
                             const int rem = S - 2 - sg;
-                            wait_stage_and_barrier(rem > 3 ? 3 : rem);
+                            wait_stage_and_barrier(rem > kPrefetch - 2 ? kPrefetch - 2 : rem);
                         }
                     }
                     if constexpr (J == 1) read_frag(IC<I>{}, nx, a_off + shift, b_off + shift);
                     if constexpr (J == 2) read_frag(IC<I + 4>{}, nx, a_off + shift, b_off + shift);
                     if constexpr (J == 3 && I == 0) { if (issue) issue_load(IC<0>{}, sg + kPrefetch, prv); }
-                    if constexpr (J == 3 && I == 2) { if (issue) issue_load(IC<1>{}, sg + kPrefetch, prv); }
-                    if constexpr (J == 3 && I == 3) { if (issue) issue_load(IC<2>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 3 && I == 1) { if (issue) issue_load(IC<1>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 3 && I == 2) { if (issue) issue_load(IC<2>{}, sg + kPrefetch, prv); }
+                    if constexpr (J == 3 && I == 3) { if (issue) issue_load(IC<3>{}, sg + kPrefetch, prv); }
                 });
             });
             __builtin_amdgcn_sched_barrier(0);
@@ -702,20 +722,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     }
 
     // ---- write y once --------------------------------------------------------
-    // The 128 x 256 bf16 tile sits in LDS; wave w stores rows 16 w .. 16 w + 15, two
-    // whole 512-byte row segments per store instruction.
+    // The 128 x 128 bf16 tile sits in LDS; wave w stores rows 32 w .. 32 w + 31, four
+    // whole 256-byte row segments per store instruction.
     __syncthreads();
     const bool fast = ((reinterpret_cast<uintptr_t>(a.y) & 15) == 0) && (a.ldy % 8 == 0) &&
                       (n0 + kBN <= a.L.N);
     if (a.swiglu) {
-        // 128 outputs per row: four 256-byte row segments per store instruction
+        // 64 outputs per row: eight 128-byte row segments per store instruction
         const int64_t n_out = a.L.N / 2;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            const int row = wave * 16 + it * 4 + (lane >> 4);
+            const int row = wave * 32 + it * 8 + (lane >> 3);
             const int64_t m = m0 + row;
-            const int64_t n = n0 / 2 + (lane & 15) * 8;
-            const uint4 v = *reinterpret_cast<const uint4*>(lds + row * kOutRowBytes + (lane & 15) * 16);
+            const int64_t n = n0 / 2 + (lane & 7) * 8;
+            const uint4 v = *reinterpret_cast<const uint4*>(lds + row * kOutRowBytes + (lane & 7) * 16);
             if (m >= a.M) continue;
             if (fast) {
                 *reinterpret_cast<uint4*>(a.y + m * a.ldy + n) = v;
@@ -730,10 +750,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mixed_kernel(const GemmArgs
     }
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
-        const int row = wave * 16 + it * 2 + (lane >> 5);
+        const int row = wave * 32 + it * 4 + (lane >> 4);
         const int64_t m = m0 + row;
-        const int64_t n = n0 + (lane & 31) * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(lds + row * kOutRowBytes + (lane & 31) * 16);
+        const int64_t n = n0 + (lane & 15) * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(lds + row * kOutRowBytes + (lane & 15) * 16);
         if (m >= a.M) continue;
         if (fast) {
             *reinterpret_cast<uint4*>(a.y + m * a.ldy + n) = v;
