@@ -290,6 +290,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_kernel(const GemmA
     tile_of_block(a, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * kBM;
     const int64_t n0 = (int64_t)tile_n * kBN;
+    // the grid covers the padded channel count (a multiple of 256, which keeps the patches of
+    // tile_of_block whole): a tile that holds padding channels only has nothing to do
+    if (n0 >= a.L.N) return;
     const int S_hi = a.stages_hi, S_lo = a.stages_lo, S = S_hi + S_lo;  // S_hi and S_lo are even
     const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
     const uint16_t* sw_lo = sw_hi + a.L.n_pad;
