@@ -227,7 +227,7 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
  * few output channels split the reduction axis over wavefronts), larger M the
  * tiled matrix-core kernel, except that up to 1024 tokens go through the
  * streaming kernel in slices of 16 to 64 tokens where the layer has too few
- * 128 x 256 tiles to occupy the chip; the integer accumulators are identical.
+ * 128 x 128 tiles to occupy the chip; the integer accumulators are identical.
  * Alignment: q_hi, q_lo 16 bytes; packed 256 bytes; y 2 bytes.
  */
 int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,

@@ -64,7 +64,7 @@ UC_PROJ = LayerShape("llama3_8b_uc_proj_prefill", M=2048 * (32 + 8), K=128, N=12
 
 def chunk_shape(which: str, M: int) -> LayerShape:
     """A prefill chunk (or a large generation batch) of M tokens on a Llama-3-8B layer: few
-    128 x 256 output tiles, the regime between the generation stage and a full prefill."""
+    128 x 128 output tiles, the regime between the generation stage and a full prefill."""
     if which == "o_proj":
         return LayerShape(f"llama3_8b_o_proj_m{M}", M=M, K=4096, N=4096, r=512,
                           outliers="one_percent_hi", rotate=True)
