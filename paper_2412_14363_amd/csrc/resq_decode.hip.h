@@ -399,7 +399,7 @@ __global__ __launch_bounds__(kDecodeThreads) void gemm_decode_kernel(const Decod
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int hi_blocks = (int)a.L.hi_blocks, blocks = (int)(a.L.hi_blocks + a.L.lo_blocks);
     const int lane_off = (lane & 15) * kRowBytes + (lane >> 4) * 16;
-    // lane l supplies token l % 16 (zero operand past M), piece l / 16 of each 64-byte chunk
+    // lane l supplies token l % 16 (token 0 again past M: those output columns are never stored), piece l / 16 of each 64-byte chunk
     const int tok = lane & 15;
     const bool tok_live = tok < a.M;
     const ActPieces piece = act_pieces(a, lane, tok_live);
