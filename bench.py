@@ -471,6 +471,22 @@ def calibration(mfma_ms: float = 1.5, quick: bool = True) -> dict:
         if best is None or ms < best[0]:
             best = (ms, wgs)
     out["read_132MB"] = {"kernel_ms": best[0], "gbs": region / (best[0] * 1e-3) / 1e9, "workgroups": best[1]}
+    # a plain device-to-device copy (the runtime's own copy kernel) of 134 MB, sources and
+    # destinations rotated through the same 1 GiB: the rate at which this chip moves memory
+    # when it reads and writes at once, which is what the quantizer has to do
+    n = 134_217_728
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    for i in range(12):
+        src = buf[(i % 3) * n:(i % 3 + 1) * n]
+        dst = buf[((i + 1) % 3 + 4) * n:((i + 1) % 3 + 5) * n]
+        if i >= 2:
+            ev[i - 2][0].record()
+        dst.copy_(src)
+        if i >= 2:
+            ev[i - 2][1].record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+    out["copy_134MB"] = {"ms": ms, "gbs_read_plus_write": 2 * n / (ms * 1e-3) / 1e9}
     del buf
     return out
 
@@ -844,6 +860,15 @@ def headline(args) -> None:
     out["roofline"]["frac_of_measured"] = out["roofline"]["achieved"] / cal["mix_r_eighth"]["tops"]
     out["roofline"]["measured_peak_source"] = ("calibration.mix_r_eighth: the matrix instruction alone on operand "
                                                "bytes like this workload's, same process")
+    # the quantizer of the headline step against HBM and against the measured copy rate
+    qbytes = s.M * (2 * s.K + s.r + (s.K - s.r) // 2 + 12)
+    qgbs = qbytes / (out["quantize_ms"] * 1e-3) / 1e9
+    out["quantize_roofline"] = {"bound": "hbm", "achieved": qgbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                "frac": qgbs / PEAK_HBM_GBS, "kernel": "resq quantize_act",
+                                "kernel_ms": out["quantize_ms"],
+                                "measured_peak": cal["copy_134MB"]["gbs_read_plus_write"],
+                                "frac_of_measured": qgbs / cal["copy_134MB"]["gbs_read_plus_write"],
+                                "measured_peak_source": "calibration.copy_134MB: a plain device copy, same process"}
     for v in dec.values():
         v["roofline"]["measured_peak"] = cal["read_132MB"]["gbs"]
         v["roofline"]["frac_of_measured"] = v["roofline"]["achieved"] / cal["read_132MB"]["gbs"]
