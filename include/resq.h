@@ -241,7 +241,8 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
  * no device call.  For callers that want to know, and for tests.
  *   kernel        0: weight-streaming kernel for at most 16 tokens
  *                 1: weight-streaming kernel with the activation codes chunked
- *                    through LDS, in slices of 16 * token_groups tokens
+ *                    through LDS, in slices of 16 * token_groups tokens (also
+ *                    for 10 to 16 tokens on wide layers of 64 MB and more)
  *                 2: tiled matrix-core kernel                        (written)
  *   token_groups  1, 2 or 4 for kernel 1 (1 for kernel 0, 0 for kernel 2) (written)
  *   runs          parts into which the reduction axis of a channel group is cut
