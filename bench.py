@@ -836,6 +836,8 @@ def headline(args) -> None:
     import torch
     keep: dict = {}
     out = layer_bench(args, "qwen_r1024", args.steps, args.warmup, not args.no_cpu_baseline, args.cpu_budget, keep)
+    # both halves of the metric are in this line: `value` is the prefill half (TOPS), `decode` the other
+    out["metric"] = "mixed INT8/INT4 linear TOPS (% int8 MFMA peak); decode GB/s (% HBM peak)"
     s = keep["shape"]
     out["rank_sweep"] = rank_sweep(args, keep["x"], keep["w"], keep["xd"], s, (0, s.K // 8, s.K // 4))
     keep.clear()
