@@ -225,9 +225,11 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
  * read as they are needed while they are short enough to stay in cache, else
  * and up to 64 tokens they are chunked through LDS; layers with
  * few output channels split the reduction axis over wavefronts), larger M the
- * tiled matrix-core kernel, except that up to 1024 tokens go through the
- * streaming kernel in slices of 16 to 64 tokens where the layer has too few
- * 128 x 128 tiles to occupy the chip; the integer accumulators are identical.
+ * tiled matrix-core kernel (128 x 128 tiles, or 64 x 128 where those are at
+ * most 512), except that up to 1024 tokens go through the streaming kernel in
+ * slices of 16 to 64 tokens where that is estimated faster (few tiles, each
+ * walking the whole reduction axis alone); the integer accumulators are
+ * identical.
  * Alignment: q_hi, q_lo 16 bytes; packed 256 bytes; y 2 bytes.
  */
 int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
@@ -243,10 +245,12 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
  *                 1: weight-streaming kernel with the activation codes chunked
  *                    through LDS, in slices of 16 * token_groups tokens (also
  *                    for 10 to 16 tokens on wide layers of 64 MB and more)
- *                 2: tiled matrix-core kernel                        (written)
- *   token_groups  1, 2 or 4 for kernel 1 (1 for kernel 0, 0 for kernel 2) (written)
+ *                 2: tiled matrix-core kernel, 128 x 128 tiles
+ *                 3: tiled matrix-core kernel, 64 (tokens) x 128 tiles, where
+ *                    those are at most 512                           (written)
+ *   token_groups  1, 2 or 4 for kernel 1 (1 for kernel 0, 0 for kernels 2, 3) (written)
  *   runs          parts into which the reduction axis of a channel group is cut
- *                 across wavefronts, 1..8 (0 for kernel 2)           (written)
+ *                 across wavefronts, 1..8 (0 for kernels 2, 3)       (written)
  * Errors as resq_gemm_mixed for the shape; RESQ_ERR_NULL for a null output.
  */
 int resq_gemm_mixed_plan(int64_t M, int64_t N, int64_t K, int64_t r, int* kernel, int* token_groups,

@@ -10,6 +10,7 @@
 #include "resq_decode.hip.h"
 #include "resq_eig.hip.h"
 #include "resq_gemm.hip.h"
+#include "resq_gemm_m64.hip.h"
 #include "resq_basis.hip.h"
 #include "resq_hadamard.hip.h"
 #include "resq_headproj.hip.h"
@@ -347,8 +348,9 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
 //             itself, out of the last-level cache after the first).  TG and SK are the pair
 //             with the lowest estimate from the measured costs of the kernel (constants
 //             below), never less than one pass over the weights at 6 TB/s.
-//   kernel 2: the tiled kernel; a round of 512 tiles (two per compute unit) costs
-//             10 us + 0.5 us per block by the same measure.
+//   kernel 2: the tiled kernel on 128 x 128 tiles; a round of 512 tiles (two per compute
+//             unit) costs 10 us + 0.5 us per block by the same measure.
+//   kernel 3: the tiled kernel on 64 x 128 tiles, where those are at most 512 (one round).
 struct GemmPlan {
     int kernel, tg, sk;
 };
@@ -405,15 +407,29 @@ static GemmPlan plan_gemm(int64_t M, const WeightLayout& L) {
             }
         }
     }
-    bool streaming = M <= kStreamMaxM;
+    // The tiled kernels: 64-token tiles where they fill at most one round of two workgroups per
+    // compute unit (measured against 128-token tiles on the seven shapes of that sweep: 8 to 30 %
+    // faster up to 384 such tiles, equal within 2 % up to 512, 10 to 25 % slower above)
+    const int64_t tiles64 = ((M + kBM64 - 1) / kBM64) * ((L.N + kBN - 1) / kBN);
+    const bool narrow = tiles64 <= 512;
+    bool streaming = M <= kStreamMaxM;  // (measured: the streaming kernel is ahead or equal there on every shape)
     if (!streaming && tg != 0) {
-        // 512 tiles run at a time, two per compute unit
-        const int64_t tiles = ((M + kBM - 1) / kBM) * ((L.N + kBN - 1) / kBN);
-        const double tiled_us = (double)((tiles + 511) / 512) * (10.0 + 0.5 * (double)blocks);
+        double tiled_us;
+        if (narrow) {
+            // fit to the sweep: a workgroup alone on its compute unit walks a stage in 0.21 us and
+            // slows down as more compute units stream; past 256 tiles two workgroups share one
+            const double lone = (double)(tiles64 < 256 ? tiles64 : 256), shared = (double)tiles64 - lone;
+            tiled_us = 4.9 + 0.21 * blocks + (2.0 + 0.048 * blocks) * lone / 256.0 + 0.18 * blocks * shared / 256.0;
+        } else {
+            // 512 tiles run at a time, two per compute unit
+            const int64_t tiles = ((M + kBM - 1) / kBM) * ((L.N + kBN - 1) / kBN);
+            tiled_us = (double)((tiles + 511) / 512) * (10.0 + 0.5 * (double)blocks);
+        }
+        // (the streaming estimate is up to 14 % low at four token groups)
         streaming = stream_us < 0.9 * tiled_us;
     }
     if (streaming) return {1, tg, sk};
-    return {2, 0, 0};
+    return {narrow ? 3 : 2, 0, 0};
 }
 
 // arguments of the weight-streaming kernels; the code pointers are null when the kernel
@@ -580,16 +596,20 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
     a.swiglu = swiglu ? 1 : 0;
     a.stages_hi = (int)a.L.hi_blocks;  // one stage = one 64-byte block per row
     a.stages_lo = (int)a.L.lo_blocks;
-    a.tiles_m = (int)((M + kBM - 1) / kBM);
+    const bool narrow = plan.kernel == 3;  // 64-token tiles
+    a.tiles_m = narrow ? (int)((M + kBM64 - 1) / kBM64) : (int)((M + kBM - 1) / kBM);
     a.tiles_n = (int)(a.L.n_pad / kBN);
     const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
     if (tiles > 0x7FFFFFFF) return RESQ_ERR_SHAPE;
 
-    // static LDS (six stage buffers, 144 KiB): one workgroup per compute unit
-    if (dbg)
-        launch(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
-    else
-        launch(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+    // static LDS (68.5 or 76.5 KiB): two workgroups per compute unit
+    if (narrow) {
+        if (dbg) launch(gemm_mixed_m64_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+        else launch(gemm_mixed_m64_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+    } else {
+        if (dbg) launch(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+        else launch(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+    }
     return launch_status();
 }
 

@@ -262,7 +262,7 @@ def test_quantize_gemm_mixed_rejects_bad_arguments():
 STREAM_PLAN_SHAPES = [
     ((17, 256, 40, 32), (1, 1, 1)), ((17, 4096, 40, 512), (1, 1, 2)), ((17, 8192, 130, 1024), (1, 1, 4)),
     ((17, 53248, 16, 6656), (1, 1, 8)), ((130, 520, 4100, 64), (1, 2, 1)), ((17, 14336, 8208, 1792), (1, 2, 2)),
-    ((300, 256, 4100, 32), (1, 4, 1)),
+    ((60, 520, 16400, 64), (1, 4, 1)),
 ]
 
 
@@ -278,8 +278,12 @@ def test_gemm_mixed_plan():
     assert plan(16, 8192, 28672, 3584) == (1, 1, 4)            # code rows too long to re-read per wavefront
     assert plan(64, 28672, 8192, 1024) == (1, 4, 1)            # batched decode, wide layer: one slice
     assert plan(64, 4096, 4096, 512) == (1, 1, 2)              # ... narrow layer: four slices of 16 tokens
-    assert plan(512, 4096, 4096, 512)[0] == 1 and plan(640, 4096, 4096, 512)[0] == 2
-    assert plan(1025, 1024, 4096, 512) == (2, 0, 0)            # above 1024 tokens always tiled
+    assert plan(256, 4096, 4096, 512)[0] == 1                  # few tiles: the streaming kernel in slices ...
+    assert plan(384, 4096, 4096, 512) == (3, 0, 0)             # ... until tiles of 64 tokens are estimated faster
+    assert plan(1024, 4096, 4096, 512) == (3, 0, 0)            # 512 of them: still those
+    assert plan(1025, 1024, 4096, 512) == (3, 0, 0)            # above 1024 tokens always tiled
+    assert plan(1025, 4096, 4096, 512) == (2, 0, 0)            # more than 512 tiles of 64 tokens: 128 x 128 tiles
+    assert plan(65, 14336, 4096, 512) == (3, 0, 0)             # a wide layer: tiles from 65 tokens on
     for shape, want in STREAM_PLAN_SHAPES:
         M, K, N, r = shape
         assert plan(M, N, K, r) == want, shape

@@ -241,19 +241,37 @@ def test_layer_decode_long_rows(oracle, rq, M, K, N, r):
     check_layer(oracle, rq, x, w, r)
 
 
-# more than 1024 tokens: always the tiled kernel, here on small ragged layers
+# more than 1024 tokens: always a tiled kernel; on these small ragged layers the one with 64 x 128 tiles
 TILED_SHAPES = [
     (1030, 640, 300, 128), (1100, 1000, 515, 104), (1025, 90, 40, 30),
     (1153, 256, 256, 0), (1153, 256, 256, 256), (1200, 2048, 768, 256),
-    # 16 x 4 = 64 tiles: a multiple of 8 that is not a multiple of 256, the tile order that deals
-    # contiguous runs of tiles to the eight XCDs (e.g. a grouped-query key/value projection); ragged M too
+    # 32 x 8 = 256 tiles: the tile order in 8 x 8 patches per XCD needs a multiple of 512, so this is
+    # the order that deals contiguous runs of tiles to the eight XCDs (e.g. a grouped-query
+    # key/value projection); ragged M too
     (2048, 256, 1024, 32), (1925, 256, 1024, 32),
+    # up to 1024 tokens on layers wide enough that the tiles beat the sliced streaming kernel
+    (300, 256, 4100, 32), (130, 520, 8200, 64), (65, 256, 28672, 0), (200, 640, 6000, 640), (513, 90, 4100, 30),
+    (1024, 128, 4096, 128),  # 16 x 32 = 512 tiles: the 8 x 8 patches
+]
+# more than 512 tiles of 64 x 128: the kernel with 128 x 128 tiles
+TILED128_SHAPES = [
+    (2100, 256, 2200, 32), (4100, 256, 1100, 0), (4100, 256, 1100, 256), (1100, 1000, 4200, 104),
+    (1925, 256, 4096, 32),   # 16 x 32 = 512 tiles, ragged M: the 8 x 8 patches
+    (4200, 90, 1040, 30),
 ]
 
 
 @pytest.mark.parametrize("M,K,N,r", TILED_SHAPES)
 def test_layer_tiled_kernel_small_layers(oracle, rq, M, K, N, r):
+    assert rq.resq_gemm_mixed_plan(M, N, K, r)[0] == 3
     x, w = wl.random_small_case(M * 17 + K, M, K, N, r, act="student_t3")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+@pytest.mark.parametrize("M,K,N,r", TILED128_SHAPES)
+def test_layer_tiled_kernel_wide_tiles(oracle, rq, M, K, N, r):
+    assert rq.resq_gemm_mixed_plan(M, N, K, r)[0] == 2
+    x, w = wl.random_small_case(M * 17 + K + 1, M, K, N, r, act="student_t3")
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
@@ -746,8 +764,8 @@ def test_layer_asym(oracle, rq, M, K, N, r):
     check_layer_asym(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
-@pytest.mark.parametrize("M,K,N,r", TILED_SHAPES[:4] + [(900, 1000, 272, 104)])
-def test_layer_asym_tiled_kernel_and_many_slices(oracle, rq, M, K, N, r):
+@pytest.mark.parametrize("M,K,N,r", TILED_SHAPES[:4] + TILED_SHAPES[8:10] + TILED128_SHAPES[:4] + [(900, 1000, 272, 104)])
+def test_layer_asym_tiled_kernels_and_many_slices(oracle, rq, M, K, N, r):
     x, w = wl.random_small_case(M * 5 + K + 1, M, K, N, r, act="student_t3")
     x = (x.float() + 1.5).to(torch.bfloat16)
     check_layer_asym(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
@@ -896,7 +914,9 @@ def test_project_heads_no_rows(rq):
     (130, 640, 150, 128), (64, 512, 256, 64), (300, 1024, 384, 0), (40, 256, 130, 256),
     (1, 512, 128, 64), (16, 1000, 257, 104), (5, 256, 64, 0),                             # activation codes resident in LDS
     (20, 1000, 257, 104), (128, 2048, 136, 256), (900, 1000, 136, 104),                   # chunked codes, one or several slices
-    (1030, 640, 150, 128), (1100, 1000, 257, 104), (1153, 256, 128, 0), (1153, 256, 128, 256),   # above 1024 tokens: tiled kernel
+    (1030, 640, 150, 128), (1100, 1000, 257, 104), (1153, 256, 128, 0), (1153, 256, 128, 256),   # above 1024 tokens: tiled kernel, 64 x 128 tiles
+    (300, 256, 2050, 32), (130, 520, 4100, 64),                                           # ... and below, on wide layers
+    (2100, 256, 1100, 32), (4100, 256, 550, 0), (4100, 256, 550, 256), (1100, 1000, 2100, 104),  # 128 x 128 tiles
 ])
 def test_layer_swiglu(oracle, rq, M, K, F, r):
     x, w = wl.random_small_case(M + K + F, M, K, 2 * F, r, act="student_t3")
