@@ -45,15 +45,15 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E peak, GB/s
 # device copy (x2.000 and x1.000).  This run does not measure it: the figures are copied from
 # the summaries under profiles/ (named in `traffic_source`); absent = not measured.
 MEASURED_TRAFFIC = {
-    "qwen_r1024": (3246.46e6 + 484.44e6, "profiles/qwen_r1024.txt"),
-    "oproj_prefill": (38.28e6 + 16.78e6, "profiles/oproj_prefill.txt"),
-    "gate_up_prefill": (284.06e6 + 117.44e6, "profiles/gate_up_prefill.txt"),
-    "down_prefill": (366.65e6 + 33.55e6, "profiles/down_prefill.txt"),
-    "oproj_m512": (19.40e6 + 4.19e6, "profiles/oproj_m512.txt"),
-    "down_m512": (66.62e6 + 4.19e6, "profiles/down_m512.txt"),
+    "qwen_r1024": (3241.78e6 + 484.44e6, "profiles/qwen_r1024.txt"),
+    "oproj_prefill": (38.29e6 + 16.78e6, "profiles/oproj_prefill.txt"),
+    "gate_up_prefill": (284.52e6 + 117.44e6, "profiles/gate_up_prefill.txt"),
+    "down_prefill": (366.70e6 + 33.55e6, "profiles/down_prefill.txt"),
+    "oproj_m512": (19.22e6 + 4.19e6, "profiles/oproj_m512.txt"),
+    "down_m512": (66.41e6 + 4.19e6, "profiles/down_m512.txt"),
     "decode_m1": (133.04e6 + 0.06e6, "profiles/decode_m1.txt"),
-    "decode_m16": (133.13e6 + 0.92e6, "profiles/decode_m16.txt"),
-    "decode_m64": (135.10e6 + 3.67e6, "profiles/decode_m64.txt"),
+    "decode_m16": (133.12e6 + 0.92e6, "profiles/decode_m16.txt"),
+    "decode_m64": (135.09e6 + 3.67e6, "profiles/decode_m64.txt"),
     "uc_proj": (21.35e6 + 20.97e6, "profiles/uc_proj.txt"),
     "kv_quant": (8.47e6 + 2.88e6, "profiles/kv_quant.txt"),
 }

@@ -412,7 +412,8 @@ def test_layer_saturated_codes(oracle, rq):
 QWEN_SNR = {}   # r -> (SNR of the HIP path, SNR of the oracle) on the sampled rows, filled by the test below
 
 
-@pytest.mark.parametrize("which", ["oproj_prefill", "gate_up_prefill", "qwen_r0", "qwen_r1024", "qwen_r2048"])
+@pytest.mark.parametrize("which", ["oproj_prefill", "gate_up_prefill", "qwen_r0", "qwen_r1024", "qwen_r2048",
+                                   "oproj_m512", "oproj_m1024"])
 def test_layer_prefill_full_size_sampled(oracle, rq, which):
     # the benchmark's prefill configurations at full size, in the launch configuration the
     # benchmark times; the oracle checks all activation codes, all packed weights, and a
@@ -420,8 +421,10 @@ def test_layer_prefill_full_size_sampled(oracle, rq, which):
     # (r = 0, K/8, K/4: the rank sweep) the output SNR on those rows is taken too.
     s = {"oproj_prefill": wl.OPROJ_PREFILL, "gate_up_prefill": wl.MLP_GATE_UP,
          "qwen_r0": wl.qwen_mlp_shape(0), "qwen_r1024": wl.qwen_mlp_shape(1024),
-         "qwen_r2048": wl.qwen_mlp_shape(2048)}[which]
-    nrows = 48 if which == "oproj_prefill" else 24
+         "qwen_r2048": wl.qwen_mlp_shape(2048),
+         # prefill chunks: 64 x 128 tiles, one per compute unit and two per compute unit
+         "oproj_m512": wl.chunk_shape("o_proj", 512), "oproj_m1024": wl.chunk_shape("o_proj", 1024)}[which]
+    nrows = 48 if which.startswith("oproj") else 24
     x, w = wl.make_activations(s), wl.make_weights(s)
     act = check_act_codes(oracle, rq, x, s.r)
     packed, wq = check_weights(oracle, rq, w, s.r)
