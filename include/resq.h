@@ -249,8 +249,9 @@ int resq_gemm_mixed(const int8_t* q_hi, const uint8_t* q_lo, const float* s_hi,
  *                 3: tiled matrix-core kernel, 64 (tokens) x 128 tiles, where
  *                    those are at most 512                           (written)
  *   token_groups  1, 2 or 4 for kernel 1 (1 for kernel 0, 0 for kernels 2, 3) (written)
- *   runs          parts into which the reduction axis of a channel group is cut
- *                 across wavefronts, 1..8 (0 for kernels 2, 3)       (written)
+ *   runs          parts into which the reduction axis of a channel group (kernels
+ *                 0, 1: 1..8) or of a tile (kernel 3: 2 where the tiles are at
+ *                 most 256, else 1) is cut across wavefronts; 0 for kernel 2 (written)
  * Errors as resq_gemm_mixed for the shape; RESQ_ERR_NULL for a null output.
  */
 int resq_gemm_mixed_plan(int64_t M, int64_t N, int64_t K, int64_t r, int* kernel, int* token_groups,

@@ -350,7 +350,8 @@ int resq_unpack_weights(const void* packed, int64_t N, int64_t K, int64_t r, int
 //             below), never less than one pass over the weights at 6 TB/s.
 //   kernel 2: the tiled kernel on 128 x 128 tiles; a round of 512 tiles (two per compute
 //             unit) costs 10 us + 0.5 us per block by the same measure.
-//   kernel 3: the tiled kernel on 64 x 128 tiles, where those are at most 512 (one round).
+//   kernel 3: the tiled kernel on 64 x 128 tiles, where those are at most 512 (one round);
+//             SK = 2: eight wavefronts per tile in two rings (at most 256 tiles), else 1.
 struct GemmPlan {
     int kernel, tg, sk;
 };
@@ -409,27 +410,33 @@ static GemmPlan plan_gemm(int64_t M, const WeightLayout& L) {
     }
     // The tiled kernels: 64-token tiles where they fill at most one round of two workgroups per
     // compute unit (measured against 128-token tiles on the seven shapes of that sweep: 8 to 30 %
-    // faster up to 384 such tiles, equal within 2 % up to 512, 10 to 25 % slower above)
+    // faster up to 384 such tiles, equal within 2 % up to 512, 10 to 25 % slower above); at most
+    // one per compute unit: with both rings (a further 5 to 14 %)
     const int64_t tiles64 = ((M + kBM64 - 1) / kBM64) * ((L.N + kBN - 1) / kBN);
     const bool narrow = tiles64 <= 512;
+    const int rings = narrow ? (tiles64 <= 256 ? 2 : 1) : 0;
     bool streaming = M <= kStreamMaxM;  // (measured: the streaming kernel is ahead or equal there on every shape)
     if (!streaming && tg != 0) {
-        double tiled_us;
         if (narrow) {
-            // fit to the sweep: a workgroup alone on its compute unit walks a stage in 0.21 us and
-            // slows down as more compute units stream; past 256 tiles two workgroups share one
-            const double lone = (double)(tiles64 < 256 ? tiles64 : 256), shared = (double)tiles64 - lone;
-            tiled_us = 4.9 + 0.21 * blocks + (2.0 + 0.048 * blocks) * lone / 256.0 + 0.18 * blocks * shared / 256.0;
+            // Fits to the sweep (within 10 %).  One ring: a workgroup alone on its compute unit
+            // walks a stage in 0.21 us and slows down as more compute units stream; past 256 tiles
+            // two workgroups share one.  Two rings: 0.14 us per stage.
+            double tiled_us;
+            if (rings == 2)
+                tiled_us = 5.8 + 0.1435 * blocks + (0.5 + 0.08 * blocks) * (double)tiles64 / 256.0;
+            else
+                tiled_us = 6.9 + 0.258 * blocks + 0.18 * blocks * (double)(tiles64 - 256) / 256.0;
+            // (the streaming estimate is up to 14 % low at four token groups)
+            streaming = stream_us * (tg == 4 ? 1.12 : 1.0) < tiled_us;
         } else {
             // 512 tiles run at a time, two per compute unit
             const int64_t tiles = ((M + kBM - 1) / kBM) * ((L.N + kBN - 1) / kBN);
-            tiled_us = (double)((tiles + 511) / 512) * (10.0 + 0.5 * (double)blocks);
+            const double tiled_us = (double)((tiles + 511) / 512) * (10.0 + 0.5 * (double)blocks);
+            streaming = stream_us < 0.9 * tiled_us;
         }
-        // (the streaming estimate is up to 14 % low at four token groups)
-        streaming = stream_us < 0.9 * tiled_us;
     }
     if (streaming) return {1, tg, sk};
-    return {narrow ? 3 : 2, 0, 0};
+    return {narrow ? 3 : 2, 0, rings};
 }
 
 // arguments of the weight-streaming kernels; the code pointers are null when the kernel
@@ -604,8 +611,13 @@ static int gemm_mixed_impl(const int8_t* q_hi, const uint8_t* q_lo, const float*
 
     // static LDS (68.5 or 76.5 KiB): two workgroups per compute unit
     if (narrow) {
-        if (dbg) launch(gemm_mixed_m64_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
-        else launch(gemm_mixed_m64_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+        if (plan.sk == 2) {  // both rings
+            if (dbg) launch(gemm_mixed_m64_kernel<true, 2>, dim3((unsigned)tiles), dim3(2 * kGemmThreads), 0, st, a);
+            else launch(gemm_mixed_m64_kernel<false, 2>, dim3((unsigned)tiles), dim3(2 * kGemmThreads), 0, st, a);
+        } else {
+            if (dbg) launch(gemm_mixed_m64_kernel<true, 1>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+            else launch(gemm_mixed_m64_kernel<false, 1>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
+        }
     } else {
         if (dbg) launch(gemm_mixed_kernel<true>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);
         else launch(gemm_mixed_kernel<false>, dim3((unsigned)tiles), dim3(kGemmThreads), 0, st, a);

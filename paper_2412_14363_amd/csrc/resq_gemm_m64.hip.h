@@ -19,6 +19,13 @@
 // fragment is widened behind the first product of the half before it, into
 // one of two registers taking turns.  The widened activation fragments exist
 // twice: the next stage's are written while this stage's are multiplied.
+//
+// Two rings (KS = 2), for layers with at most one such tile per compute unit: a
+// single wavefront per SIMD cannot keep the matrix pipe busy by itself, so a
+// second set of four wavefronts works on the same tile, taking every other
+// pair of stages through a ring of stage buffers of its own; at the end the
+// two sets exchange half of their integer tiles through LDS (integer sums:
+// exact in any order) and each folds and stores half of the channels.
 #pragma once
 #include "resq_gemm.hip.h"
 
@@ -27,12 +34,14 @@ namespace resq {
 constexpr int kBM64 = 64;
 constexpr int kStageABytes64 = kBM64 * kRowBytes;              // 4 KiB = 4 blocks
 constexpr int kStageBytes64 = kStageABytes64 + kStageBBytes;   // 12 KiB
-constexpr int kNumBuf64 = 6;
-constexpr int kPrefetch64 = kNumBuf64 - 1;
 constexpr int kLoadsPerStage64 = (kBM64 + kBN) / kRowsPerBlock / 4;  // per wavefront: 3 (one activation block, two weight blocks)
-constexpr int kMetaOff64 = kNumBuf64 * kStageBytes64;
-static_assert(2 * (kMetaOff64 + kMetaBytes) <= 160 * 1024, "LDS of two resident workgroups");
-static_assert(kBM64 * kOutRowBytes <= kMetaOff64, "the staged output tile fits the stage buffers");
+// stage buffers per ring: six for one ring (two workgroups per compute unit), five for each of two
+constexpr int num_buf64(int ks) { return ks == 1 ? 6 : 5; }
+constexpr int kXchgBytes64 = 8 * 8192;  // KS = 2: eight wavefronts hand over eight four-register tiles each
+static_assert(2 * (num_buf64(1) * kStageBytes64 + kMetaBytes) <= 160 * 1024, "LDS of two resident workgroups");
+static_assert(2 * num_buf64(2) * kStageBytes64 + kMetaBytes <= 160 * 1024, "LDS of one workgroup with two rings");
+static_assert(kBM64 * kOutRowBytes <= num_buf64(1) * kStageBytes64, "the staged output tile fits the stage buffers");
+static_assert(kXchgBytes64 + kBM64 * kOutRowBytes <= 2 * num_buf64(2) * kStageBytes64, "exchange area and staged tile fit the rings");
 
 // the fragments of one stage as read from LDS: 2 activation and 4 weight fragments
 struct Raw64 {
@@ -62,21 +71,41 @@ __device__ __forceinline__ void wait_stages_and_barrier(int later) {
     }
 }
 
-template <bool DBG>
-__global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const GemmArgs a) {
+// KS = 1: four wavefronts, the whole reduction axis.  KS = 2: eight wavefronts in two halves, each
+// half with a ring of its own walking every other PAIR of stages (pairs 0, 2, 4, ... and 1, 3, 5, ...;
+// a pair is all high or all low since both stage counts are even); at the end the halves swap
+// half of their integer tiles through LDS and each folds and stores half of the channels.
+template <bool DBG, int KS>
+__global__ __launch_bounds__(kGemmThreads * KS, KS == 1 ? 2 : 1) void gemm_mixed_m64_kernel(const GemmArgs a) {
+    constexpr int kNumBuf64 = num_buf64(KS);
+    constexpr int kPrefetch64 = kNumBuf64 - 1;  // stages requested ahead of the one being multiplied
+    constexpr int kRingBytes = kNumBuf64 * kStageBytes64;
+    constexpr int kMetaOff64 = KS * kRingBytes;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[kMetaOff64 + kMetaBytes];
 
     const int t = threadIdx.x;
     const int lane = t & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wave_wg = __builtin_amdgcn_readfirstlane(t >> 6);   // 0 .. 4 KS - 1
+    const int half = KS == 1 ? 0 : wave_wg >> 2;                   // which ring, which pairs of stages
+    const int wave = wave_wg & 3;
     const int wm = wave >> 1;  // 0..1: 32-token half of the tile
     const int wn = wave & 1;   // 0..1: 64-channel half of the tile
+    uint8_t* const ring = lds + half * kRingBytes;
     int tile_m, tile_n;
     tile_of_block(a, tile_m, tile_n);  // a.tiles_m counts 64-token tiles here
     const int64_t m0 = (int64_t)tile_m * kBM64;
     const int64_t n0 = (int64_t)tile_n * kBN;
     if (n0 >= a.L.N) return;  // a tile of padding channels only
-    const int S_hi = a.stages_hi, S_lo = a.stages_lo, S = S_hi + S_lo;  // S_hi and S_lo are even
+    // all stages of the layer (both counts even), and this half's share of them, in its own numbering
+    const int S_hi_all = a.stages_hi, S_all = S_hi_all + a.stages_lo;
+    const int S_hi = KS == 1 ? S_hi_all : 2 * ((S_hi_all / 2 - half + 1) / 2);
+    const int S = KS == 1 ? S_all : 2 * ((S_all / 2 - half + 1) / 2);
+    const int S_lo = S - S_hi;
+    const bool any_hi = S_hi_all > 0, any_lo = S_all > S_hi_all;  // the layer has a high (low) group
+    // this half's stage k is stage ... of the layer
+    auto layer_stage = [&](int k) __attribute__((always_inline)) {
+        return KS == 1 ? k : 4 * (k >> 1) + 2 * half + (k & 1);
+    };
     const uint16_t* sw_hi = reinterpret_cast<const uint16_t*>(a.packed + a.L.scale_off);
     const uint16_t* sw_lo = sw_hi + a.L.n_pad;
     const int32_t* even_sum = reinterpret_cast<const int32_t*>(a.packed + a.L.scale_off + 4 * a.L.n_pad);
@@ -84,7 +113,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
 
     // ---- epilogue constants -> LDS (the oldest loads of their waves) ------------
     // Token rows past M repeat the last row (never stored).
-    if (wave == 0) {
+    if (half != 0) {
+        // the first ring's wavefronts fetch them
+    } else if (wave == 0) {
         if (lane < 32) {
             load_to_lds_16B((lane < 16 ? sw_hi : sw_lo) + n0 + (lane & 15) * 8, lds + kMetaOff64 + kMetaSwHi);
             if (asym) load_to_lds_16B(even_sum + a.L.n_pad + n0 + lane * 4, lds + kMetaOff64 + kMetaWsumHi);
@@ -98,12 +129,12 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
         int64_t m = m0 + lane;
         m = m < a.M ? m : a.M - 1;
         if (wave == 2) {
-            if (S_hi > 0) load_to_lds_4B(a.s_hi + m, lds + kMetaOff64 + kMetaSHi);
-            if (S_lo > 0) load_to_lds_4B(a.s_lo + m, lds + kMetaOff64 + kMetaSLo);
+            if (any_hi) load_to_lds_4B(a.s_hi + m, lds + kMetaOff64 + kMetaSHi);
+            if (any_lo) load_to_lds_4B(a.s_lo + m, lds + kMetaOff64 + kMetaSLo);
         } else {
-            if (S_lo > 0) load_to_lds_4B(a.lo_sum + m, lds + kMetaOff64 + kMetaLoSum);
-            if (asym && S_hi > 0) load_to_lds_4B(a.c_hi + m, lds + kMetaOff64 + kMetaCHi);
-            if (asym && S_lo > 0) load_to_lds_4B(a.c_lo + m, lds + kMetaOff64 + kMetaCLo);
+            if (any_lo) load_to_lds_4B(a.lo_sum + m, lds + kMetaOff64 + kMetaLoSum);
+            if (asym && any_hi) load_to_lds_4B(a.c_hi + m, lds + kMetaOff64 + kMetaCHi);
+            if (asym && any_lo) load_to_lds_4B(a.c_lo + m, lds + kMetaOff64 + kMetaCLo);
         }
     }
 
@@ -120,29 +151,31 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
     }
     // the low rows are addressed by the global stage index too: their resource starts S_hi stages early
     const __amdgpu_buffer_rsrc_t rs_a_hi = make_rsrc(a.q_hi + m0 * a.ld_hi);
-    const __amdgpu_buffer_rsrc_t rs_a_lo = make_rsrc(a.q_lo + m0 * a.ld_lo - (int64_t)S_hi * kRowBytes);
+    const __amdgpu_buffer_rsrc_t rs_a_lo = make_rsrc(a.q_lo + m0 * a.ld_lo - (int64_t)S_hi_all * kRowBytes);
     const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(a.packed + (n0 / 16 + wave * 2) * a.L.group_bytes);
-    // load K of stage sg (high stages first) into buffer buf; K = 0: the A block, 1, 2: the B blocks
+    // load K of this half's stage sg (high stages first) into buffer buf of its ring; K = 0: the A block, 1, 2: the B blocks
     auto issue_load = [&](auto k, int sg, int buf) __attribute__((always_inline)) {
         constexpr int K = decltype(k)::value;
-        uint8_t* dst = lds + buf * kStageBytes64;
+        uint8_t* dst = ring + buf * kStageBytes64;
+        const uint32_t g = (uint32_t)layer_stage(sg);
         if constexpr (K == 0) {
             const bool lo = sg >= S_hi;
-            buffer_load_to_lds_16B(lo ? rs_a_lo : rs_a_hi, lo ? a_voff_lo : a_voff_hi, (uint32_t)sg * kRowBytes,
+            buffer_load_to_lds_16B(lo ? rs_a_lo : rs_a_hi, lo ? a_voff_lo : a_voff_hi, g * kRowBytes,
                                    dst + wave * kBlockBytes);
         } else {
-            buffer_load_to_lds_16B(rs_b, b_voff[K - 1], (uint32_t)sg * kBlockBytes,
+            buffer_load_to_lds_16B(rs_b, b_voff[K - 1], g * kBlockBytes,
                                    dst + kStageABytes64 + (wave * 2 + K - 1) * kBlockBytes);
         }
     };
     // the same for a stage known to be a low one
     auto issue_load_lo = [&](auto k, int sg, int buf) __attribute__((always_inline)) {
         constexpr int K = decltype(k)::value;
-        uint8_t* dst = lds + buf * kStageBytes64;
+        uint8_t* dst = ring + buf * kStageBytes64;
+        const uint32_t g = (uint32_t)layer_stage(sg);
         if constexpr (K == 0)
-            buffer_load_to_lds_16B(rs_a_lo, a_voff_lo, (uint32_t)sg * kRowBytes, dst + wave * kBlockBytes);
+            buffer_load_to_lds_16B(rs_a_lo, a_voff_lo, g * kRowBytes, dst + wave * kBlockBytes);
         else
-            buffer_load_to_lds_16B(rs_b, b_voff[K - 1], (uint32_t)sg * kBlockBytes,
+            buffer_load_to_lds_16B(rs_b, b_voff[K - 1], g * kBlockBytes,
                                    dst + kStageABytes64 + (wave * 2 + K - 1) * kBlockBytes);
     };
 
@@ -163,7 +196,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
     };
 
     // ---- LDS -> register reads: lane l supplies row l % 16, piece l / 16 of a block ----
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)ring;
     uint32_t a_off, b_off;
     {
         const int r = lane & 15, kc = lane >> 4;
@@ -181,9 +214,12 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
     // ---- epilogue: as in the wide kernel, on two token fragments ---------------------
     const int tl = wm * 32 + (lane & 15);
     const int cl = wn * 64 + (lane >> 4) * 4;
-    auto fold = [&](auto has_hi, auto has_lo, auto is_asym, auto is_glu) __attribute__((always_inline)) {
+    // KS = 2: this half folds the weight fragments J0, J0 + 1 only, and the tile is staged behind the exchange area
+    uint8_t* const staged = lds + (KS == 1 ? 0 : kXchgBytes64);
+    auto fold = [&](auto has_hi, auto has_lo, auto is_asym, auto is_glu, auto j0_) __attribute__((always_inline)) {
         constexpr bool HI_ON = decltype(has_hi)::value, LO_ON = decltype(has_lo)::value;
         constexpr bool ASYM = decltype(is_asym)::value, GLU = decltype(is_glu)::value;
+        constexpr int J0 = decltype(j0_)::value;
         const uint8_t* meta = lds + kMetaOff64;
         float st_hi[2], st_lo[2], ct_hi[2], ct_lo[2];
         int ca[2];
@@ -215,7 +251,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
             }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = J0; j < J0 + 4 / KS; ++j) {
             const int c = cl + 16 * j;
             float sn_hi[4] = {0.f, 0.f, 0.f, 0.f}, sn_lo[4] = {0.f, 0.f, 0.f, 0.f};
             float zw_hi[4] = {0.f, 0.f, 0.f, 0.f}, zw_lo[4] = {0.f, 0.f, 0.f, 0.f};  // wsum[n] * sw[n]
@@ -267,10 +303,10 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
                 }
                 const int row = tl + 16 * i;
                 if constexpr (GLU)
-                    *reinterpret_cast<uint32_t*>(lds + row * kOutRowBytes + c) =
+                    *reinterpret_cast<uint32_t*>(staged + row * kOutRowBytes + c) =
                         pack_bf16(silu_f32(val[0]) * val[1], silu_f32(val[2]) * val[3]);
                 else
-                    *reinterpret_cast<uint2*>(lds + row * kOutRowBytes + c * 2) =
+                    *reinterpret_cast<uint2*>(staged + row * kOutRowBytes + c * 2) =
                         make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -425,35 +461,81 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
         // the reads past the last stage went into p0: let them land before its registers are reused
         lds_wait<0>(p0.a);
         lds_wait<0>(p0.b);
+        if constexpr (KS == 2) {
+            // Every stage holds one workgroup barrier, and the first half may have one pair of
+            // stages more than this one: join its two barriers.
+            if (S < 2 * ((S_all / 2 + 1) / 2)) {
+                wait_loads_and_barrier<0>();
+                wait_loads_and_barrier<0>();
+            }
+        }
         wait_loads_and_barrier<0>();  // every wave is done reading the stage buffers
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last matrix instructions have written their tiles
-        if (a.swiglu) {  // symmetric codes only (checked on the host)
-            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, NO{}, YES{});
-            else if (S_hi > 0) fold(YES{}, NO{}, NO{}, YES{});
-            else fold(NO{}, YES{}, NO{}, YES{});
-        } else if (asym) {
-            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, YES{}, NO{});
-            else if (S_hi > 0) fold(YES{}, NO{}, YES{}, NO{});
-            else fold(NO{}, YES{}, YES{}, NO{});
-        } else {
-            if (S_hi > 0 && S_lo > 0) fold(YES{}, YES{}, NO{}, NO{});
-            else if (S_hi > 0) fold(YES{}, NO{}, NO{}, NO{});
-            else fold(NO{}, YES{}, NO{}, NO{});
+        if constexpr (KS == 2) {
+            // The first half folds weight fragments 0, 1 and the second 2, 3: wavefront (half, w)
+            // hands the other two of its own (both integer sets, 8 tiles of 1 KiB) to wavefront
+            // (1 - half, w) and adds what that one hands over.  Integer sums: exact in any order.
+            auto tile_at = [&](int slot, int idx) __attribute__((always_inline)) {
+                return reinterpret_cast<v4i*>(lds + slot * 8192 + idx * 1024 + lane * 16);
+            };
+            auto send = [&](auto j0_) __attribute__((always_inline)) {
+                constexpr int J0 = decltype(j0_)::value;
+                const int slot = (1 - half) * 4 + wave;
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        *tile_at(slot, jj * 2 + i) = acc_hi[J0 + jj][i];
+                        *tile_at(slot, 4 + jj * 2 + i) = acc_lo[J0 + jj][i];
+                    }
+            };
+            auto receive = [&](auto j0_) __attribute__((always_inline)) {
+                constexpr int J0 = decltype(j0_)::value;
+                const int slot = half * 4 + wave;
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        acc_hi[J0 + jj][i] += *tile_at(slot, jj * 2 + i);
+                        acc_lo[J0 + jj][i] += *tile_at(slot, 4 + jj * 2 + i);
+                    }
+            };
+            if (half == 0) send(IC<2>{}); else send(IC<0>{});
+            __syncthreads();
+            if (half == 0) receive(IC<0>{}); else receive(IC<2>{});
         }
+        auto fold_from = [&](auto j0_) __attribute__((always_inline)) {
+            if (a.swiglu) {  // symmetric codes only (checked on the host)
+                if (any_hi && any_lo) fold(YES{}, YES{}, NO{}, YES{}, j0_);
+                else if (any_hi) fold(YES{}, NO{}, NO{}, YES{}, j0_);
+                else fold(NO{}, YES{}, NO{}, YES{}, j0_);
+            } else if (asym) {
+                if (any_hi && any_lo) fold(YES{}, YES{}, YES{}, NO{}, j0_);
+                else if (any_hi) fold(YES{}, NO{}, YES{}, NO{}, j0_);
+                else fold(NO{}, YES{}, YES{}, NO{}, j0_);
+            } else {
+                if (any_hi && any_lo) fold(YES{}, YES{}, NO{}, NO{}, j0_);
+                else if (any_hi) fold(YES{}, NO{}, NO{}, NO{}, j0_);
+                else fold(NO{}, YES{}, NO{}, NO{}, j0_);
+            }
+        };
+        if (KS == 1 || half == 0) fold_from(IC<0>{});
+        else fold_from(IC<2>{});
     }
 
-    // ---- write y once: wave w stores rows 16 w .. 16 w + 15 of the staged tile ----------
+    // ---- write y once: each wavefront of the workgroup stores 16 / KS rows of the staged tile ----
+    constexpr int kRowsPerWave = 16 / KS;
     __syncthreads();
     const bool fast = ((reinterpret_cast<uintptr_t>(a.y) & 15) == 0) && (a.ldy % 8 == 0) &&
                       (n0 + kBN <= a.L.N);
     if (a.swiglu) {
         const int64_t n_out = a.L.N / 2;
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int row = wave * 16 + it * 8 + (lane >> 3);
+        for (int it = 0; it < kRowsPerWave / 8; ++it) {
+            const int row = wave_wg * kRowsPerWave + it * 8 + (lane >> 3);
             const int64_t m = m0 + row;
             const int64_t n = n0 / 2 + (lane & 7) * 8;
-            const uint4 v = *reinterpret_cast<const uint4*>(lds + row * kOutRowBytes + (lane & 7) * 16);
+            const uint4 v = *reinterpret_cast<const uint4*>(staged + row * kOutRowBytes + (lane & 7) * 16);
             if (m >= a.M) continue;
             if (fast) {
                 *reinterpret_cast<uint4*>(a.y + m * a.ldy + n) = v;
@@ -467,11 +549,11 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_mixed_m64_kernel(const G
         return;
     }
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int row = wave * 16 + it * 4 + (lane >> 4);
+    for (int it = 0; it < kRowsPerWave / 4; ++it) {
+        const int row = wave_wg * kRowsPerWave + it * 4 + (lane >> 4);
         const int64_t m = m0 + row;
         const int64_t n = n0 + (lane & 15) * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(lds + row * kOutRowBytes + (lane & 15) * 16);
+        const uint4 v = *reinterpret_cast<const uint4*>(staged + row * kOutRowBytes + (lane & 15) * 16);
         if (m >= a.M) continue;
         if (fast) {
             *reinterpret_cast<uint4*>(a.y + m * a.ldy + n) = v;

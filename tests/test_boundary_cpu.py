@@ -279,11 +279,11 @@ def test_gemm_mixed_plan():
     assert plan(64, 28672, 8192, 1024) == (1, 4, 1)            # batched decode, wide layer: one slice
     assert plan(64, 4096, 4096, 512) == (1, 1, 2)              # ... narrow layer: four slices of 16 tokens
     assert plan(256, 4096, 4096, 512)[0] == 1                  # few tiles: the streaming kernel in slices ...
-    assert plan(384, 4096, 4096, 512) == (3, 0, 0)             # ... until tiles of 64 tokens are estimated faster
-    assert plan(1024, 4096, 4096, 512) == (3, 0, 0)            # 512 of them: still those
-    assert plan(1025, 1024, 4096, 512) == (3, 0, 0)            # above 1024 tokens always tiled
+    assert plan(384, 4096, 4096, 512) == (3, 0, 2)             # ... until tiles of 64 tokens are estimated faster (192 tiles: two rings)
+    assert plan(1024, 4096, 4096, 512) == (3, 0, 1)            # 512 of them: still those, one ring
+    assert plan(1025, 1024, 4096, 512) == (3, 0, 2)            # above 1024 tokens always tiled
     assert plan(1025, 4096, 4096, 512) == (2, 0, 0)            # more than 512 tiles of 64 tokens: 128 x 128 tiles
-    assert plan(65, 14336, 4096, 512) == (3, 0, 0)             # a wide layer: tiles from 65 tokens on
+    assert plan(65, 14336, 4096, 512) == (3, 0, 2)             # a wide layer: tiles from 65 tokens on
     for shape, want in STREAM_PLAN_SHAPES:
         M, K, N, r = shape
         assert plan(M, N, K, r) == want, shape

@@ -241,7 +241,8 @@ def test_layer_decode_long_rows(oracle, rq, M, K, N, r):
     check_layer(oracle, rq, x, w, r)
 
 
-# more than 1024 tokens: always a tiled kernel; on these small ragged layers the one with 64 x 128 tiles
+# more than 1024 tokens: always a tiled kernel; on these small ragged layers the one with 64 x 128
+# tiles, and at most 256 of them: eight wavefronts per tile in two rings
 TILED_SHAPES = [
     (1030, 640, 300, 128), (1100, 1000, 515, 104), (1025, 90, 40, 30),
     (1153, 256, 256, 0), (1153, 256, 256, 256), (1200, 2048, 768, 256),
@@ -250,7 +251,15 @@ TILED_SHAPES = [
     # key/value projection); ragged M too
     (2048, 256, 1024, 32), (1925, 256, 1024, 32),
     # up to 1024 tokens on layers wide enough that the tiles beat the sliced streaming kernel
-    (300, 256, 4100, 32), (130, 520, 8200, 64), (65, 256, 28672, 0), (200, 640, 6000, 640), (513, 90, 4100, 30),
+    (300, 256, 4100, 32), (130, 520, 8200, 64), (200, 640, 6000, 640),
+    (1030, 128, 300, 128), (1030, 256, 300, 128), (1030, 640, 300, 128),   # 1, 2, 3 pairs of stages (the second ring gets none; the
+                                                                           # high pair and the low pair; one pair less than the first)
+    (1100, 896, 300, 128),                                                 # one high pair, three low pairs
+]
+# 257 to 512 such tiles: four wavefronts per tile, two workgroups per compute unit
+TILED64_ONE_RING_SHAPES = [
+    (65, 256, 28672, 0), (513, 90, 4100, 30), (1153, 256, 2100, 32), (1300, 640, 2300, 128),
+    (1100, 384, 3000, 384), (1500, 520, 2000, 0),
     (1024, 128, 4096, 128),  # 16 x 32 = 512 tiles: the 8 x 8 patches
 ]
 # more than 512 tiles of 64 x 128: the kernel with 128 x 128 tiles
@@ -263,14 +272,21 @@ TILED128_SHAPES = [
 
 @pytest.mark.parametrize("M,K,N,r", TILED_SHAPES)
 def test_layer_tiled_kernel_small_layers(oracle, rq, M, K, N, r):
-    assert rq.resq_gemm_mixed_plan(M, N, K, r)[0] == 3
+    assert rq.resq_gemm_mixed_plan(M, N, K, r) == (3, 0, 2)
     x, w = wl.random_small_case(M * 17 + K, M, K, N, r, act="student_t3")
+    check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
+
+
+@pytest.mark.parametrize("M,K,N,r", TILED64_ONE_RING_SHAPES)
+def test_layer_tiled_kernel_narrow_tiles_one_ring(oracle, rq, M, K, N, r):
+    assert rq.resq_gemm_mixed_plan(M, N, K, r) == (3, 0, 1)
+    x, w = wl.random_small_case(M * 17 + K + 2, M, K, N, r, act="student_t3")
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
 @pytest.mark.parametrize("M,K,N,r", TILED128_SHAPES)
 def test_layer_tiled_kernel_wide_tiles(oracle, rq, M, K, N, r):
-    assert rq.resq_gemm_mixed_plan(M, N, K, r)[0] == 2
+    assert rq.resq_gemm_mixed_plan(M, N, K, r) == (2, 0, 0)
     x, w = wl.random_small_case(M * 17 + K + 1, M, K, N, r, act="student_t3")
     check_layer(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
@@ -767,7 +783,8 @@ def test_layer_asym(oracle, rq, M, K, N, r):
     check_layer_asym(oracle, rq, x, w, r, ldy_extra=8 if N % 4 == 0 else 3)
 
 
-@pytest.mark.parametrize("M,K,N,r", TILED_SHAPES[:4] + TILED_SHAPES[8:10] + TILED128_SHAPES[:4] + [(900, 1000, 272, 104)])
+@pytest.mark.parametrize("M,K,N,r", TILED_SHAPES[:4] + TILED_SHAPES[8:10] + TILED_SHAPES[11:] + TILED64_ONE_RING_SHAPES[1:5] +
+                         TILED128_SHAPES[:4] + [(900, 1000, 272, 104)])
 def test_layer_asym_tiled_kernels_and_many_slices(oracle, rq, M, K, N, r):
     x, w = wl.random_small_case(M * 5 + K + 1, M, K, N, r, act="student_t3")
     x = (x.float() + 1.5).to(torch.bfloat16)
@@ -919,6 +936,7 @@ def test_project_heads_no_rows(rq):
     (20, 1000, 257, 104), (128, 2048, 136, 256), (900, 1000, 136, 104),                   # chunked codes, one or several slices
     (1030, 640, 150, 128), (1100, 1000, 257, 104), (1153, 256, 128, 0), (1153, 256, 128, 256),   # above 1024 tokens: tiled kernel, 64 x 128 tiles
     (300, 256, 2050, 32), (130, 520, 4100, 64),                                           # ... and below, on wide layers
+    (1153, 256, 1050, 32), (1300, 640, 1150, 128),                                        # ... 257 to 512 such tiles: one ring
     (2100, 256, 1100, 32), (4100, 256, 550, 0), (4100, 256, 550, 256), (1100, 1000, 2100, 104),  # 128 x 128 tiles
 ])
 def test_layer_swiglu(oracle, rq, M, K, F, r):
