@@ -49,8 +49,8 @@ MEASURED_TRAFFIC = {
     "oproj_prefill": (38.29e6 + 16.78e6, "profiles/oproj_prefill.txt"),
     "gate_up_prefill": (284.52e6 + 117.44e6, "profiles/gate_up_prefill.txt"),
     "down_prefill": (366.70e6 + 33.55e6, "profiles/down_prefill.txt"),
-    "oproj_m512": (19.22e6 + 4.19e6, "profiles/oproj_m512.txt"),
-    "down_m512": (66.41e6 + 4.19e6, "profiles/down_m512.txt"),
+    "oproj_m512": (19.28e6 + 4.19e6, "profiles/oproj_m512.txt"),
+    "down_m512": (66.47e6 + 4.19e6, "profiles/down_m512.txt"),
     "decode_m1": (133.04e6 + 0.06e6, "profiles/decode_m1.txt"),
     "decode_m16": (133.12e6 + 0.92e6, "profiles/decode_m16.txt"),
     "decode_m64": (135.09e6 + 3.67e6, "profiles/decode_m64.txt"),
