@@ -8,9 +8,9 @@
 // fragments of the 16x16x64 instruction, 2 x 32 accumulation registers.  A
 // stage is 12 KiB (4 activation blocks, 8 weight blocks), three loads per
 // wavefront.  Half the products per stage and wavefront means half the time
-// per stage, so six stage buffers (five stages ahead) keep the same distance
-// in time between a load and its use; two workgroups still share a compute
-// unit.
+// per stage: six stage buffers (five stages ahead) keep about the same
+// distance in time between a load and its use (more were measured to bring
+// nothing); two workgroups still share a compute unit.
 //
 // Low stages.  With two activation fragments the two products on one
 // accumulator tile (even and odd columns) would be two instructions apart in
